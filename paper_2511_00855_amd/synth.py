@@ -1,0 +1,211 @@
+"""Seeded synthetic inputs shaped like the paper's workloads (Table 1 and the
+experiment settings: a dense embedding, a learned-sparse vector and a bag of
+text tokens per document).
+
+This module holds NO arithmetic of the method: it only draws random corpora and
+queries.  Both the CPU oracle and the HIP path consume what it returns; BM25
+weighting, scoring, graph construction and search live elsewhere.
+
+Everything is a pure function of (config, seed), produced with
+``numpy.random.default_rng``.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, Optional, Tuple
+
+import numpy as np
+
+
+@dataclass
+class VecSet:
+    """A set of fused vectors: dense rows + learned-sparse CSR + text CSR.
+
+    ``tx_val`` holds raw term counts (tf) for both documents and queries.
+    ``dense_bf16`` (uint16 bit patterns) is present only when the config stores
+    the dense part in bf16; then ``dense`` holds exactly those bf16 values
+    widened back to fp32, so both sides of a parity test see the same numbers.
+    """
+    n: int
+    dim: int
+    dense: np.ndarray                 # float32 [n, dim]
+    sp_indptr: np.ndarray             # int64 [n+1]
+    sp_idx: np.ndarray                # int32 [nnz], strictly ascending per row
+    sp_val: np.ndarray                # float32 [nnz]
+    tx_indptr: np.ndarray             # int64 [n+1]
+    tx_idx: np.ndarray                # int32 [nnz], strictly ascending per row
+    tx_val: np.ndarray                # float32 [nnz] term counts
+    sp_vocab: int = 0
+    tx_vocab: int = 0
+    dense_bf16: Optional[np.ndarray] = None
+
+
+@dataclass
+class Workload:
+    name: str
+    docs: VecSet
+    queries: VecSet
+    weights: Tuple[float, float, float]
+    degree: int
+    beam: int
+    k: int
+    bm25_k1: float = 1.2
+    bm25_b: float = 0.75
+    extra: Dict[str, object] = field(default_factory=dict)
+
+
+def _zipf_cdf(vocab: int, s: float) -> np.ndarray:
+    p = np.arange(1, vocab + 1, dtype=np.float64) ** (-s)
+    c = np.cumsum(p)
+    return c / c[-1]
+
+
+def _draw_terms(rng: np.random.Generator, cdf: np.ndarray, perm: np.ndarray, n: int) -> np.ndarray:
+    """n i.i.d. term ids: Zipf rank by inverse CDF, rank -> id by a fixed permutation."""
+    r = np.searchsorted(cdf, rng.random(n), side="right")
+    np.minimum(r, len(cdf) - 1, out=r)
+    return perm[r]
+
+
+def _bags(rng, cdf, perm, counts: np.ndarray) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Token bags WITH repetition -> CSR of (term id ascending, count)."""
+    n = len(counts)
+    total = int(counts.sum())
+    rows = np.repeat(np.arange(n, dtype=np.int64), counts)
+    toks = _draw_terms(rng, cdf, perm, total).astype(np.int64)
+    vocab = len(cdf)
+    key = rows * vocab + toks
+    uk, cnt = np.unique(key, return_counts=True)
+    r = uk // vocab
+    t = (uk % vocab).astype(np.int32)
+    indptr = np.zeros(n + 1, dtype=np.int64)
+    np.add.at(indptr, r + 1, 1)
+    np.cumsum(indptr, out=indptr)
+    return indptr, t, cnt.astype(np.float32)
+
+
+def _distinct_sets(rng, cdf, perm, counts: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """Per row, `counts[i]` DISTINCT Zipf term ids (keep drawing until distinct), sorted."""
+    n = len(counts)
+    vocab = len(cdf)
+    counts = np.minimum(counts, vocab)
+    have = [np.empty(0, dtype=np.int64) for _ in range(n)]
+    need = counts.copy()
+    todo = np.nonzero(need > 0)[0]
+    # rounds of oversampled draws; a row keeps its first `need` new distinct ids
+    while len(todo):
+        over = (need[todo] * 2 + 8).astype(np.int64)
+        rows = np.repeat(todo, over)
+        toks = _draw_terms(rng, cdf, perm, int(over.sum())).astype(np.int64)
+        start = np.concatenate([[0], np.cumsum(over)])
+        for k, i in enumerate(todo):
+            seg = toks[start[k]:start[k + 1]]
+            # first occurrences, in draw order
+            _, first = np.unique(seg, return_index=True)
+            seg = seg[np.sort(first)]
+            if len(have[i]):
+                seg = seg[~np.isin(seg, have[i])]
+            take = seg[: need[i]]
+            have[i] = np.concatenate([have[i], take])
+            need[i] -= len(take)
+        todo = todo[need[todo] > 0]
+    indptr = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(counts, out=indptr[1:])
+    idx = np.concatenate([np.sort(h) for h in have]).astype(np.int32) if n else np.empty(0, np.int32)
+    return indptr, idx
+
+
+def f32_to_bf16_rne(x: np.ndarray) -> np.ndarray:
+    """fp32 -> bf16 bit patterns, round-to-nearest-even (storage format conversion only)."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    r = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+    return r
+
+
+def bf16_to_f32(b: np.ndarray) -> np.ndarray:
+    return (b.astype(np.uint32) << 16).view(np.float32)
+
+
+def _dense(rng, n: int, dim: int, bf16: bool):
+    x = rng.standard_normal((n, dim), dtype=np.float32)
+    x /= np.linalg.norm(x, axis=1, keepdims=True).astype(np.float32)
+    if bf16:
+        b = f32_to_bf16_rne(x)
+        return bf16_to_f32(b).reshape(n, dim), b.reshape(n, dim)
+    return x, None
+
+
+def make_vecset(rng, n: int, dim: int, *, bf16: bool, sp_vocab: int, sp_counts: np.ndarray,
+                tx_vocab: int, tx_counts: np.ndarray, sp_cdf, sp_perm, tx_cdf, tx_perm) -> VecSet:
+    dense, dense_b = _dense(rng, n, dim, bf16)
+    sp_indptr, sp_idx = _distinct_sets(rng, sp_cdf, sp_perm, sp_counts)
+    sp_val = np.abs(rng.standard_normal(len(sp_idx))).astype(np.float32)
+    # a weight that rounds to 0 would make "nnz" a lie; nudge (probability ~0)
+    sp_val[sp_val == 0] = np.float32(1e-3)
+    tx_indptr, tx_idx, tx_val = _bags(rng, tx_cdf, tx_perm, tx_counts)
+    return VecSet(n=n, dim=dim, dense=dense, sp_indptr=sp_indptr, sp_idx=sp_idx, sp_val=sp_val,
+                  tx_indptr=tx_indptr, tx_idx=tx_idx, tx_val=tx_val, sp_vocab=sp_vocab,
+                  tx_vocab=tx_vocab, dense_bf16=dense_b)
+
+
+def _lognormal_lengths(rng, n: int, mean: float, sigma: float = 0.5, lo: int = 5, hi: int = 512):
+    mu = np.log(mean) - 0.5 * sigma * sigma
+    return np.clip(np.rint(rng.lognormal(mu, sigma, n)), lo, hi).astype(np.int64)
+
+
+def _poisson_min1(rng, lam: float, n: int):
+    return np.maximum(rng.poisson(lam, n), 1).astype(np.int64)
+
+
+CONFIGS = {
+    # name: dict(N, nq, dim, bf16, vocab, doc sparse nnz ("fixed", v) or ("poisson", lam),
+    #            doc tokens ("fixed", v) or ("lognormal", mean), query nnz, query tokens,
+    #            weights, degree, beam, k)
+    "tiny": dict(n=2_000, nq=100, dim=128, bf16=False, vocab=10_000, sp=("fixed", 32), tx=("fixed", 40),
+                 qsp=("fixed", 8), qtx=("fixed", 6), weights=(0.5, 0.3, 0.2), degree=32, beam=64, k=10),
+    "cfg2": dict(n=100_000, nq=10_000, dim=768, bf16=False, vocab=30_522, sp=("poisson", 120),
+                 tx=("lognormal", 60), qsp=("poisson", 20), qtx=("poisson", 8), weights=(0.5, 0.3, 0.2),
+                 degree=64, beam=128, k=10),
+    "cfg3": dict(n=1_000_000, nq=10_000, dim=1024, bf16=True, vocab=250_002, sp=("poisson", 100),
+                 tx=("lognormal", 60), qsp=("poisson", 20), qtx=("poisson", 8), weights=(0.4, 0.4, 0.2),
+                 degree=64, beam=128, k=10),
+    "cfg5": dict(n=8_800_000, nq=10_000, dim=1024, bf16=True, vocab=250_002, sp=("poisson", 80),
+                 tx=("lognormal", 55), qsp=("poisson", 20), qtx=("poisson", 8), weights=(0.4, 0.4, 0.2),
+                 degree=64, beam=128, k=10),
+}
+
+
+def _counts(rng, spec, n):
+    kind, v = spec
+    if kind == "fixed":
+        return np.full(n, int(v), dtype=np.int64)
+    if kind == "poisson":
+        return _poisson_min1(rng, float(v), n)
+    if kind == "lognormal":
+        return _lognormal_lengths(rng, n, float(v))
+    raise ValueError(kind)
+
+
+def make_workload(name: str = "tiny", seed: int = 0, *, n: Optional[int] = None, nq: Optional[int] = None,
+                  **override) -> Workload:
+    """Build one of the named workloads.  `n`, `nq` and any config key can be
+    overridden to get a smaller case with the same distributions (used by tests
+    that need several tiles and a ragged tail but not the full size)."""
+    c = dict(CONFIGS[name])
+    c.update(override)
+    if n is not None:
+        c["n"] = n
+    if nq is not None:
+        c["nq"] = nq
+    rng = np.random.default_rng(seed)
+    vocab = c["vocab"]
+    cdf = _zipf_cdf(vocab, 1.1)
+    sp_perm = rng.permutation(vocab).astype(np.int64)
+    tx_perm = rng.permutation(vocab).astype(np.int64)
+    common = dict(sp_vocab=vocab, tx_vocab=vocab, sp_cdf=cdf, sp_perm=sp_perm, tx_cdf=cdf, tx_perm=tx_perm)
+    docs = make_vecset(rng, c["n"], c["dim"], bf16=c["bf16"], sp_counts=_counts(rng, c["sp"], c["n"]),
+                       tx_counts=_counts(rng, c["tx"], c["n"]), **common)
+    qs = make_vecset(rng, c["nq"], c["dim"], bf16=False, sp_counts=_counts(rng, c["qsp"], c["nq"]),
+                     tx_counts=np.maximum(_counts(rng, c["qtx"], c["nq"]), 1), **common)
+    return Workload(name=name, docs=docs, queries=qs, weights=tuple(c["weights"]), degree=c["degree"],
+                    beam=c["beam"], k=c["k"], extra=dict(seed=seed, config=c))

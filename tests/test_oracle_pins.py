@@ -1,0 +1,551 @@
+"""Pins of the CPU oracle against things other than itself: a hand-worked BM25
+example, dense expansion, numpy/scipy library routines on the single-path
+special cases, brute force written with Python sets on tiny inputs, and the
+invariants the paper states.  None of these need a GPU."""
+import os
+from types import SimpleNamespace
+
+import numpy as np
+import pytest
+import scipy.sparse as sps
+
+import oracle as O
+from paper_2511_00855_amd.synth import make_workload
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def vs_from_lists(dense, sp, tx, vocab=64):
+    """Hand-made vector set: sp/tx are lists of {term: value} dicts."""
+    n = len(dense)
+    def csr(rows):
+        indptr = [0]; idx = []; val = []
+        for r in rows:
+            for t in sorted(r):
+                idx.append(t); val.append(r[t])
+            indptr.append(len(idx))
+        return np.array(indptr, np.int64), np.array(idx, np.int32), np.array(val, np.float32)
+    si, sx, sv = csr(sp)
+    ti, tx_, tv = csr(tx)
+    d = np.asarray(dense, np.float32).reshape(n, -1)
+    return SimpleNamespace(n=n, dim=d.shape[1], dense=d, sp_indptr=si, sp_idx=sx, sp_val=sv,
+                           tx_indptr=ti, tx_idx=tx_, tx_val=tv, sp_vocab=vocab, tx_vocab=vocab)
+
+
+@pytest.fixture(scope="module")
+def small():
+    w = make_workload("tiny", seed=3, n=300, nq=20)
+    D = O.encode_docs(w.docs)
+    Q = O.VS(w.queries)
+    return w, D, Q
+
+
+def expand(vs, which, vocab):
+    """Dense expansion of a CSR part as float64 [n, vocab]."""
+    indptr, idx, val = ((vs.sp_indptr, vs.sp_idx, vs.sp_val) if which == "sp"
+                        else (vs.tx_indptr, vs.tx_idx, vs.tx_val))
+    out = np.zeros((vs.n, vocab), np.float64)
+    for i in range(vs.n):
+        out[i, idx[indptr[i]:indptr[i + 1]]] = val[indptr[i]:indptr[i + 1]]
+    return out
+
+
+# --------------------------------------------------------------- S0: BM25
+def _bm25_docs():
+    docs = [{1: 2, 2: 1}, {2: 1, 3: 1}, {3: 3, 4: 1}]
+    return vs_from_lists(np.zeros((3, 4)), [{}] * 3, docs, vocab=8)
+
+
+def test_bm25_hand_worked_example():
+    v = _bm25_docs()
+    w, df, avgdl = O.bm25_encode(3, 8, v.tx_indptr, v.tx_idx, v.tx_val)
+    assert avgdl == pytest.approx(3.0)
+    assert list(df[:5]) == [0, 1, 2, 2, 1]
+    D = O.VS(v, tx_val=w)
+    q = vs_from_lists(np.zeros((1, 4)), [{}], [{1: 1, 2: 1}], vocab=8)
+    Q = O.VS(q)
+    got_w = {}
+    for d in range(3):
+        for e in range(v.tx_indptr[d], v.tx_indptr[d + 1]):
+            got_w[(d, int(v.tx_idx[e]))] = float(w[e])
+    qs = O.hybrid_block(Q, [0], D, [[0, 1, 2]], (0, 0, 1))[0]
+    dd = O.hybrid_block(D, [0, 1, 2], D, [[0, 1, 2]] * 3, (0, 0, 1))
+    seen = 0
+    for line in open(os.path.join(GOLD, "bm25_worked_example.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        kind, a, b, val = line.split()
+        a, b, val = int(a), int(b), float(val)
+        if kind == "weight":
+            assert got_w[(a, b)] == pytest.approx(val, abs=2e-6)
+        elif kind == "query_score":
+            assert qs[b, 2] == pytest.approx(val, abs=2e-6)
+            assert qs[b, 3] == pytest.approx(val, abs=2e-6)
+        elif kind == "docdoc":
+            assert dd[a, b, 2] == pytest.approx(val, abs=2e-6)
+            assert dd[b, a, 2] == pytest.approx(val, abs=2e-6)
+        seen += 1
+    assert seen == 12
+
+
+def test_bm25_limits():
+    w0 = make_workload("tiny", seed=5, n=200, nq=1).docs
+    # k1 = 0: term frequency and length drop out, weight = IDF(df) alone
+    w, df, _ = O.bm25_encode(w0.n, w0.tx_vocab, w0.tx_indptr, w0.tx_idx, w0.tx_val, k1=0.0, b=0.75)
+    by_df = {}
+    for e, t in enumerate(w0.tx_idx):
+        by_df.setdefault(int(df[t]), set()).add(float(w[e]))
+    assert all(len(v) == 1 for v in by_df.values())
+    dfs = sorted(by_df)
+    vals = [next(iter(by_df[d])) for d in dfs]
+    assert all(a > b for a, b in zip(vals, vals[1:]))          # rarer term, larger weight
+    assert all(v > 0 for v in vals)                             # non-negative IDF variant
+    # a term in exactly one of N docs: IDF = ln(1 + (N-0.5)/1.5)
+    if 1 in by_df:
+        assert vals[0] == pytest.approx(np.log(1 + (w0.n - 0.5) / 1.5), rel=1e-6)
+    # b = 0: no length normalisation -> same (df, tf) gives same weight in docs of any length
+    w, df, _ = O.bm25_encode(w0.n, w0.tx_vocab, w0.tx_indptr, w0.tx_idx, w0.tx_val, k1=1.2, b=0.0)
+    grp = {}
+    for e, t in enumerate(w0.tx_idx):
+        grp.setdefault((int(df[t]), float(w0.tx_val[e])), set()).add(float(w[e]))
+    assert all(len(v) == 1 for v in grp.values())
+    # saturation in tf: weight rises with tf but stays below IDF*(k1+1)
+    one = {k: next(iter(v)) for k, v in grp.items()}
+    for (d, tf), val in one.items():
+        idf = np.log(1 + (w0.n - d + 0.5) / (d + 0.5))
+        assert val < idf * 2.2 * (1 + 1e-6)
+        if (d, tf + 1) in one:
+            assert one[(d, tf + 1)] > val
+
+
+# --------------------------------------------------------------- S1
+def test_sparse_ip_equals_dense_expansion():
+    rng = np.random.default_rng(0)
+    for _ in range(200):
+        vocab = 50
+        na, nb = rng.integers(0, 30, 2)
+        ia = np.sort(rng.choice(vocab, na, replace=False)); ib = np.sort(rng.choice(vocab, nb, replace=False))
+        va = rng.standard_normal(na).astype(np.float32); vb = rng.standard_normal(nb).astype(np.float32)
+        a = np.zeros(vocab); b = np.zeros(vocab)
+        a[ia] = va; b[ib] = vb
+        assert O.sparse_ip(ia, va, ib, vb) == pytest.approx(float(a @ b), abs=1e-12)
+
+
+def test_theorem1_identity(small):
+    """Fused score == plain dot product of the concatenated, densely expanded
+    vectors with the weights folded into the query (Theorem 1)."""
+    w, D, Q = small
+    V = w.docs.sp_vocab
+    dcat = np.concatenate([D.dense.astype(np.float64), expand(D, "sp", V), expand(D, "tx", V)], axis=1)
+    rng = np.random.default_rng(1)
+    wq = rng.uniform(-1, 2, (Q.n, 3)).astype(np.float32)
+    qcat = np.concatenate([Q.dense.astype(np.float64) * wq[:, :1].astype(np.float64),
+                           expand(Q, "sp", V) * wq[:, 1:2].astype(np.float64),
+                           expand(Q, "tx", V) * wq[:, 2:3].astype(np.float64)], axis=1)
+    ref = qcat @ dcat.T
+    cand = np.tile(np.arange(D.n, dtype=np.int32), (Q.n, 1))
+    got = O.hybrid_block(Q, np.arange(Q.n), D, cand, wq)
+    np.testing.assert_allclose(got[:, :, 3], ref, rtol=2e-6, atol=1e-6)
+    # components
+    np.testing.assert_allclose(got[:, :, 0], Q.dense.astype(np.float64) @ D.dense.astype(np.float64).T,
+                               rtol=2e-6, atol=1e-7)
+    np.testing.assert_allclose(got[:, :, 1], expand(Q, "sp", V) @ expand(D, "sp", V).T, rtol=2e-6, atol=1e-7)
+    np.testing.assert_allclose(got[:, :, 2], expand(Q, "tx", V) @ expand(D, "tx", V).T, rtol=2e-6, atol=1e-7)
+    # -1 candidate
+    o = O.hybrid_block(Q, [0], D, [[-1, 3]], (1, 1, 1))
+    assert np.all(np.isneginf(o[0, 0])) and np.isfinite(o[0, 1]).all()
+
+
+def _rank(scores64, k, skip=None):
+    """Reference ranking by numpy: score desc, id asc."""
+    ids = np.arange(len(scores64))
+    s = scores64.astype(np.float32)
+    order = np.lexsort((ids, -s.astype(np.float64)))
+    if skip is not None:
+        order = order[order != skip]
+    return order[:k], s[order[:k]]
+
+
+def test_single_path_special_cases(small):
+    """(1,0,0) is dense MIPS, (0,1,0) sparse MIPS, (0,0,1) BM25 ranking: each
+    reduces to a library matrix product (Section 4.2.1)."""
+    w, D, Q = small
+    V = w.docs.sp_vocab
+    qids = np.arange(Q.n)
+    dense = Q.dense.astype(np.float64) @ D.dense.astype(np.float64).T
+    Ssp = sps.csr_matrix((Q.sp_val.astype(np.float64), Q.sp_idx, Q.sp_indptr), shape=(Q.n, V)) @ \
+        sps.csr_matrix((D.sp_val.astype(np.float64), D.sp_idx, D.sp_indptr), shape=(D.n, V)).T
+    Stx = sps.csr_matrix((Q.tx_val.astype(np.float64), Q.tx_idx, Q.tx_indptr), shape=(Q.n, V)) @ \
+        sps.csr_matrix((D.tx_val.astype(np.float64), D.tx_idx, D.tx_indptr), shape=(D.n, V)).T
+    for wv, M in (((1, 0, 0), dense), ((0, 1, 0), Ssp.toarray()), ((0, 0, 1), Stx.toarray()),
+                  ((0, 2.5, 0), 2.5 * Ssp.toarray())):
+        ids, sc = O.bruteforce_topk(Q, qids, D, wv, 10)
+        for i in range(Q.n):
+            rid, rs = _rank(M[i], 10)
+            # same scores; ids equal wherever the reference scores are distinct
+            np.testing.assert_allclose(sc[i], rs, rtol=1e-6, atol=1e-7)
+            distinct = np.ones(10, bool)
+            distinct[1:] &= rs[1:] != rs[:-1]
+            distinct[:-1] &= rs[:-1] != rs[1:]
+            assert np.array_equal(ids[i][distinct], rid[distinct])
+
+
+def test_topk_tie_order_and_padding():
+    dense = np.array([[1, 0], [1, 0], [0, 1], [1, 0]], np.float32)
+    v = vs_from_lists(dense, [{}] * 4, [{}] * 4)
+    D = O.VS(v); Q = O.VS(vs_from_lists([[1, 0]], [{}], [{}]))
+    ids, sc = O.bruteforce_topk(Q, [0], D, (1, 0, 0), 6)
+    assert list(ids[0]) == [0, 1, 3, 2, -1, -1]
+    assert list(sc[0][:4]) == [1, 1, 1, 0] and np.isneginf(sc[0][4:]).all()
+    ids, _ = O.bruteforce_topk(D, [1], D, (1, 0, 0), 2, skip_same=True)
+    assert list(ids[0]) == [0, 3]
+
+
+# --------------------------------------------------------------- S2, S3
+def test_seed_knn_is_dense_topk(small):
+    w, D, _ = small
+    K = 16
+    ids, sc = O.seed_knn(D, np.arange(D.n), K)
+    G = D.dense.astype(np.float64) @ D.dense.astype(np.float64).T
+    for u in range(0, D.n, 7):
+        rid, rs = _rank(G[u], K, skip=u)
+        assert np.array_equal(ids[u], rid)
+        np.testing.assert_allclose(sc[u], rs, rtol=1e-6, atol=1e-7)
+
+
+def _fused_matrix(w, D, wv):
+    V = w.docs.sp_vocab
+    M = [D.dense.astype(np.float64) @ D.dense.astype(np.float64).T,
+         expand(D, "sp", V) @ expand(D, "sp", V).T, expand(D, "tx", V) @ expand(D, "tx", V).T]
+    return M, wv[0] * M[0] + wv[1] * M[1] + wv[2] * M[2]
+
+
+def test_refine_round_bruteforce(small):
+    """One refinement round against a set-based restatement: candidates = own
+    list plus the first S neighbours' first S neighbours (Algorithm 1, the
+    2-hop exploration), best K kept; per-path lists keep the best P by each
+    single similarity over everything scored so far."""
+    w, D, _ = small
+    N, K, S, P = D.n, 12, 5, 4
+    wv = np.array([1.0, 0.7, 1.3], np.float32)
+    comps, F = _fused_matrix(w, D, wv.astype(np.float64))
+    ids0, _ = O.seed_knn(D, np.arange(N), K)
+    ids0[5, 3] = -1                                      # a hole must be skipped
+    spi, spsc = O.empty_sp(N, P)
+    ids1, sc1, spi1, sps1 = O.refine_round(D, wv, K, S, P, ids0, spi, spsc)
+    ids2, sc2, spi2, sps2 = O.refine_round(D, wv, K, S, P, ids1, spi1, sps1)
+    seen = [set() for _ in range(N)]
+    for prev, cur, cur_sc, cur_spi in ((ids0, ids1, sc1, spi1), (ids1, ids2, sc2, spi2)):
+        for u in range(0, N, 3):
+            cand = set(int(x) for x in prev[u] if x >= 0)
+            for v in prev[u][:S]:
+                if v >= 0:
+                    cand |= set(int(x) for x in prev[v][:S] if x >= 0)
+            cand.discard(u)
+            seen[u] |= cand
+            c = np.array(sorted(cand))
+            rid, rs = _rank(F[u][c], K)
+            exp_ids = c[rid]
+            assert np.array_equal(cur[u][:len(exp_ids)], exp_ids), u
+            assert (cur[u][len(exp_ids):] == -1).all()
+            np.testing.assert_allclose(cur_sc[u][:len(exp_ids)], rs, rtol=2e-6, atol=1e-6)
+            pool = np.array(sorted(seen[u]))
+            for p in range(3):
+                rid, _ = _rank(comps[p][u][pool], P)
+                assert np.array_equal(cur_spi[p][u][:len(rid)], pool[rid]), (u, p)
+    # subset call returns the same rows
+    sub = np.array([7, 3, 250])
+    a, b, c, d = O.refine_round(D, wv, K, S, P, ids0, spi, spsc, node_ids=sub)
+    assert np.array_equal(a, ids1[sub]) and np.array_equal(c, spi1[:, sub])
+
+
+# --------------------------------------------------------------- S4
+def test_detour_recount_from_definition():
+    """Section 3.3: A->X->Y detours A->Y iff max(dis(A,X), dis(X,Y)) < dis(A,Y),
+    dis = -sim.  Recount with distances, no shared code."""
+    rng = np.random.default_rng(2)
+    for trial in range(50):
+        K = int(rng.integers(2, 20))
+        ids = rng.permutation(100)[:K].astype(np.int32)
+        if trial % 3 == 0:
+            ids[rng.integers(0, K)] = -1
+        sim = rng.standard_normal(K).astype(np.float32)
+        Pm = rng.standard_normal((K, K)).astype(np.float32)
+        Pm = ((Pm + Pm.T) / 2).astype(np.float32)
+        if trial % 5 == 0:                       # plant exact ties: strict inequality matters
+            Pm[0, 1] = Pm[1, 0] = sim[1] = sim[0]
+        cnt, order = O.detour_sort(ids, sim, Pm)
+        disA = -sim.astype(np.float64); disP = -Pm.astype(np.float64)
+        ref = np.zeros(K, int)
+        for y in range(K):
+            for x in range(K):
+                if x != y and ids[x] >= 0 and ids[y] >= 0 and max(disA[x], disP[x, y]) < disA[y]:
+                    ref[y] += 1
+        assert np.array_equal(cnt, ref)
+        valid = [r for r in range(K) if ids[r] >= 0]
+        exp = sorted(valid, key=lambda r: (ref[r], r)) + [r for r in range(K) if ids[r] < 0]
+        assert list(order) == exp
+
+
+def test_detour_asymmetric_matrix_uses_x_to_y():
+    # sim(A,X)=.9 sim(A,Y)=.1; only P[X][Y] large: Y is detoured via X, not X via Y
+    ids = np.array([10, 11], np.int32)
+    sim = np.array([0.9, 0.1], np.float32)
+    Pm = np.array([[9, 0.5], [-5, 9]], np.float32)
+    cnt, order = O.detour_sort(ids, sim, Pm)
+    assert list(cnt) == [0, 1] and list(order) == [0, 1]
+
+
+# --------------------------------------------------------------- S5
+def _py_flag(KA, KX, KYs):
+    shared = KA & KX
+    return int(bool(shared) and all(not shared <= KY for KY in KYs))
+
+
+def test_keyword_recycling_walkthrough():
+    """The walk-through of Step 3: A's current neighbours are B, C, D; E is due
+    for pruning; K(E) minus K(B) = {k1, k4}; k4 is in K(A) and in no current
+    neighbour, so E's flag is set and E becomes a keyword edge.  F shares only
+    k2 with A, which B covers, so F is dropped for good."""
+    k = lambda *a: {t: 1.0 for t in a}
+    #        A           B        C        D        E           F
+    tx = [k(2, 3, 4), k(2, 3), k(2, 5), k(3, 6), k(1, 2, 4), k(2, 7)]
+    v = vs_from_lists(np.eye(6, 4), [{}] * 6, tx, vocab=8)
+    D = O.VS(v)
+    ids = np.array([1, 2, 3, 4, 5], np.int32)
+    Pm = np.full((5, 5), 0.1, np.float32)
+    np.fill_diagonal(Pm, 1.0)
+    self_s = np.ones(5, np.float32)
+    se, ke, flag = O.ip_prune(D, 0, 3, 2, ids, np.arange(5), Pm, self_s)
+    assert list(ids[se]) == [1, 2, 3]
+    assert list(ids[ke]) == [4]
+    assert flag[3] == 1 and flag[4] == 0
+    # equality is a rejection: IP(B, C) == IP(C, C) keeps C out (strict "<" in Algorithm 1)
+    Pm2 = Pm.copy(); Pm2[0, 1] = Pm2[1, 0] = 1.0
+    se, ke, _ = O.ip_prune(D, 0, 5, 4, ids, np.arange(5), Pm2, self_s)
+    assert list(ids[se]) == [1, 3, 4, 5] and list(ids[ke]) == []   # K(A)&K(C)={k2} is covered by B
+    # with room in SE, E passes the IP test and nothing is recycled
+    se, ke, _ = O.ip_prune(D, 0, 5, 2, ids, np.arange(5), Pm, self_s)
+    assert list(ids[se]) == [1, 2, 3, 4, 5] and len(ke) == 0
+
+
+def test_ip_prune_invariants_and_flags(small):
+    w, D, _ = small
+    R, K, cap = 8, 24, 4
+    wv = np.array([1, 1, 1], np.float32)
+    allv = np.arange(D.n)
+    self_all = O.self_sim(D, allv, wv)
+    # shrink self-similarities so that the IP test rejects often
+    ids0, _ = O.bruteforce_topk(D, allv, D, wv, K, skip_same=True)
+    rng = np.random.default_rng(4)
+    sets = [set(D.tx_idx[D.tx_indptr[i]:D.tx_indptr[i + 1]].tolist()) for i in range(D.n)]
+    n_rej_ip = n_ke = 0
+    for u in range(0, D.n, 5):
+        ids = ids0[u].copy()
+        if u % 10 == 0:
+            ids[-2:] = -1
+        Pm = O.pairwise(D, wv, ids)
+        simA = O.hybrid_block(D, [u], D, [ids], wv)[0, :, 3]
+        cnt, order = O.detour_sort(ids, simA, Pm)
+        med = np.median(Pm[np.isfinite(Pm)])
+        self_s = np.where(ids >= 0, med * rng.uniform(0.8, 1.6, K), -np.inf).astype(np.float32)
+        se, ke, flag = O.ip_prune(D, u, R, cap, ids, order, Pm, self_s)
+        assert len(se) <= R and len(ke) <= cap
+        assert se[0] == order[0]
+        # kept list: every earlier member is less similar to v than v is to itself
+        for j in range(1, len(se)):
+            for i in range(j):
+                assert Pm[se[i], se[j]] < self_s[se[j]]
+        # replay: every v not kept has a witness or SE was full; flags by Python sets
+        now = [order[0]]
+        kept, recycled = [order[0]], []
+        for r in order[1:]:
+            if ids[r] < 0:
+                continue
+            f = _py_flag(sets[u], sets[ids[r]], [sets[ids[y]] for y in now])
+            assert flag[r] == f, (u, r)
+            ok = len(now) < R and all(Pm[y, r] < self_s[r] for y in now)
+            if ok:
+                now.append(r); kept.append(r)
+            else:
+                if len(now) < R:
+                    n_rej_ip += 1
+                    assert any(Pm[y, r] >= self_s[r] for y in now)
+                if f and len(recycled) < cap:
+                    recycled.append(r)
+        assert list(se) == kept and list(ke) == recycled
+        assert not set(se) & set(ke)
+        n_ke += len(ke)
+    assert n_rej_ip > 50 and n_ke > 50          # the test exercised both branches
+
+
+# --------------------------------------------------------------- S6
+def test_assemble_structure():
+    rng = np.random.default_rng(6)
+    N, R, K, P = 60, 8, 16, 2
+    q = R // 4
+    se = np.full((N, R), -1, np.int32)
+    srt = np.full((N, K), -1, np.int32)
+    for u in range(N):
+        others = np.array([x for x in rng.permutation(N) if x != u], np.int32)
+        srt[u] = others[:K]
+        m = int(rng.integers(1, R + 1))
+        se[u, :m] = others[:m]
+    spi = np.full((3, N, P), -1, np.int32)
+    for p in range(3):
+        for u in range(N):
+            c = np.array([x for x in rng.permutation(N) if x != u], np.int32)[:P]
+            spi[p, u] = c
+    spi[0, 3] = -1                                    # an empty per-path list
+    g = O.assemble(N, R, K, P, se, srt, spi)
+    for u in range(N):
+        row = list(g[u])
+        assert len(row) == R and u not in row
+        real = [x for x in row if x >= 0]
+        assert len(set(real)) == len(real) and all(0 <= x < N for x in real)
+        assert all(x == -1 for x in row[len(real):])           # padding only at the end
+        fwd = [x for x in se[u, :q] if x >= 0]
+        assert row[:len(fwd)] == fwd
+        # reverse segment, restated with sets
+        rev = sorted(((list(se[x, :q]).index(u), x) for x in range(N) if x != u and u in se[x, :q]))
+        rev = [x for _, x in rev if x not in fwd][:q]
+        assert row[len(fwd):len(fwd) + len(rev)] == rev
+        for x in rev:
+            assert u in se[x, :q]
+        # single-path segment: round robin d, s, f
+        have = fwd + rev
+        exp = []
+        ptr = [0, 0, 0]; turn = 0; idle = 0
+        while len(exp) < R // 2 and idle < 3:
+            took = False
+            while ptr[turn] < P:
+                v = int(spi[turn, u, ptr[turn]]); ptr[turn] += 1
+                if v < 0 or v == u or v in have or v in exp:
+                    continue
+                exp.append(v); took = True
+                break
+            idle = 0 if took else idle + 1
+            turn = (turn + 1) % 3
+        s0 = len(have)
+        assert row[s0:s0 + len(exp)] == exp
+        # padding comes from the rest of SE, then the sorted list, in order
+        pad_src = [int(x) for x in list(se[u, q:]) + list(srt[u]) if x >= 0]
+        exp_pad = []
+        for v in pad_src:
+            if len(have) + len(exp) + len(exp_pad) >= R:
+                break
+            if v not in have and v not in exp and v not in exp_pad:
+                exp_pad.append(v)
+        assert [x for x in row[s0 + len(exp):] if x >= 0] == exp_pad
+    sub = O.assemble(N, R, K, P, se, srt, spi, node_ids=[5, 2])
+    assert np.array_equal(sub, g[[5, 2]])
+
+
+def test_entry_points_are_largest_norms(small):
+    w, D, _ = small
+    wv = np.array([1, 1, 1], np.float32)
+    self_all = O.self_sim(D, np.arange(D.n), wv)
+    V = w.docs.sp_vocab
+    n2 = (D.dense.astype(np.float64) ** 2).sum(1) + (expand(D, "sp", V) ** 2).sum(1) + (expand(D, "tx", V) ** 2).sum(1)
+    np.testing.assert_allclose(self_all, n2, rtol=1e-6)
+    e = O.entry_points(self_all, 10)
+    assert list(e) == list(np.lexsort((np.arange(D.n), -self_all.astype(np.float64)))[:10])
+    assert list(O.entry_points(np.array([1, 3, 3], np.float32), 5)) == [1, 2, 0, -1, -1]
+
+
+# --------------------------------------------------------------- S7..S9
+def test_search_with_full_beam_is_bruteforce(small):
+    """With a pool as large as the corpus and a graph that reaches every node,
+    best-first search enumerates everything: result == exact top-k."""
+    w, D, Q = small
+    N = D.n
+    rng = np.random.default_rng(7)
+    R = 6
+    graph = np.stack([(np.arange(N) + s) % N for s in (1, 2, 5, 11, 17, 29)], axis=1).astype(np.int32)
+    graph[rng.integers(0, N, 40), rng.integers(1, R, 40)] = -1      # holes, ring edge +1 kept
+    entry = np.array([5, 100, -1, 5], np.int32)
+    wq = rng.uniform(0, 1, (Q.n, 3)).astype(np.float32)
+    gt, gs = O.bruteforce_topk(Q, np.arange(Q.n), D, wq, 10)
+    ids, sc, nv = O.search_batch(D, graph, entry, Q, np.arange(Q.n), wq, 10, N)
+    assert np.array_equal(ids, gt) and np.array_equal(sc, gs)
+    assert (nv == N).all()
+    ids, sc, nv = O.search_batch(D, graph, entry, Q, np.arange(Q.n), wq, 10, N, width=4)
+    assert np.array_equal(ids, gt)
+
+
+def test_search_semantics_small_beam(small):
+    """Pool smaller than the corpus: restate the loop with Python lists and the
+    dense-expansion score matrix; also the score-table replay and the log."""
+    w, D, Q = small
+    N = D.n
+    b = O.build_index(make_workload("tiny", seed=3, n=300, nq=20).docs, O.default_params(8, nd_rounds=1, n_entry=4))
+    wq = np.array([0.5, 0.3, 0.2], np.float32)
+    cand = np.tile(np.arange(N, dtype=np.int32), (Q.n, 1))
+    table = O.hybrid_block(Q, np.arange(Q.n), D, cand, wq)[:, :, 3]
+    for qi in range(Q.n):
+        for L, width, iters in ((12, 1, 0), (12, 2, 0), (16, 1, 3)):
+            ids, sc, log = O.search(D, b.graph, b.entry, Q, qi, wq, 5, L, iters, width, log=True)
+            ids2, sc2, _ = O.search(D, b.graph, b.entry, Q, qi, wq, 5, L, iters, width, score_table=table[qi])
+            assert np.array_equal(ids, ids2) and np.array_equal(sc, sc2)
+            top, order = _py_search(table[qi], b.graph, b.entry, L, width, iters)
+            assert top[:5] == [int(x) for x in ids if x >= 0]
+            assert order == list(log)
+
+
+def _py_search(scores, graph, entry, L, width, iters):
+    """Algorithm 2 (semantic edges only) restated with Python lists."""
+    visited = set(); pool = []; order = []
+    def offer(v):
+        if v < 0 or v in visited:
+            return
+        visited.add(v); order.append(v)
+        pool.append([-float(scores[v]), int(v), False])
+        pool.sort(key=lambda t: (t[0], t[1]))
+        del pool[L:]
+    for v in entry:
+        offer(int(v))
+    it = 0
+    while iters == 0 or it < iters:
+        par = [t for t in pool if not t[2]][:width]
+        if not par:
+            break
+        for t in par:
+            t[2] = True
+        for t in par:
+            for v in graph[t[1]]:
+                offer(int(v))
+        it += 1
+    return [t[1] for t in pool], order
+
+
+def test_search_ties_break_by_id():
+    """Equal scores everywhere: the pool must order and evict by ascending id."""
+    N = 12
+    dense = np.tile(np.array([[1.0, 0.0]], np.float32), (N, 1))
+    dense[4] = [0.5, 0]                       # one strictly worse document
+    v = vs_from_lists(dense, [{}] * N, [{}] * N)
+    D = O.VS(v); Q = O.VS(vs_from_lists([[1, 0]], [{}], [{}]))
+    graph = np.stack([(np.arange(N) + 5) % N, (np.arange(N) + 3) % N], axis=1).astype(np.int32)
+    table = (dense[:, 0]).astype(np.float32)
+    for entry in ([11], [4, 9], [7, 2]):
+        for L, width in ((3, 1), (4, 2), (2, 1)):
+            ids, sc, log = O.search(D, graph, np.array(entry, np.int32), Q, 0, (1, 0, 0), L, L, 0, width, log=True)
+            top, order = _py_search(table, graph, entry, L, width, 0)
+            assert [int(x) for x in ids if x >= 0] == top, (entry, L, width)
+            assert list(log) == order
+
+
+def test_whole_build_invariants():
+    w = make_workload("tiny", seed=11, n=400, nq=5)
+    p = O.default_params(16, nd_rounds=2, n_entry=8)
+    b = O.build_index(w.docs, p)
+    N, R = 400, 16
+    assert b.graph.shape == (N, R)
+    for u in range(N):
+        row = [x for x in b.graph[u] if x >= 0]
+        assert u not in row and len(set(row)) == len(row)
+        assert not set(b.se[u][b.se[u] >= 0]) & set(b.ke[u][:b.ke_count[u]])
+    # refinement never makes a list worse
+    for (a, sa), (c, sc) in zip(b.rounds, b.rounds[1:]):
+        assert (sc[:, -1] >= sa[:, -1]).all()
+    assert (b.graph >= 0).all()
