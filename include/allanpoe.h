@@ -1,0 +1,192 @@
+/*
+ * allanpoe.h -- C ABI of the MI355X (gfx950) hybrid graph index.
+ *
+ * The library computes, entirely in hand-written HIP kernels, the hot path of
+ * the all-in-one hybrid index: the hybrid similarity of Definition 1
+ *     M_w(q,d) = w_d <q_d,d_d> + w_s <q_s,d_s> + w_f <q_f,d_f>
+ * (dense inner product, learned-sparse inner product over ascending
+ * (term id, weight) lists, BM25 full-text score as a lexical sparse inner
+ * product, Section 3.2), the index construction it drives (Algorithm 1,
+ * Steps 1-3 of Section 4.1) and the batched best-first search on the semantic
+ * edges with per-query fusion weights (Algorithm 2, Section 4.2.1).
+ *
+ * General rules
+ *  - Every pointer is a DEVICE pointer owned by the caller unless the comment
+ *    says "host".  `stream` is a hipStream_t passed as void* (NULL = the null
+ *    stream).  Calls enqueue work on `stream`; outputs are valid once the
+ *    caller has synchronised it.  Calls that create an index (build, ingest,
+ *    import) synchronise the stream themselves before returning.
+ *  - An index BORROWS the corpus arrays (dense rows and both CSR structures):
+ *    they must stay alive and unchanged until ap_free_index.  Everything else
+ *    the index needs (BM25 weights, self-similarities, graph, workspaces) it
+ *    allocates with hipMalloc and releases in ap_free_index.
+ *  - Return value: 0 on success, a negative AP_E* code otherwise; the message
+ *    of the last failure on the calling thread is at ap_last_error().  Nothing
+ *    here throws or aborts.
+ *  - Scores are similarities: larger is better (the paper's dis is -score).
+ *    Every ranking is by (score descending, id ascending).  A missing result
+ *    has id -1 and score -inf.
+ *  - CSR rows must hold strictly ascending term ids in [0, vocab).  ids of
+ *    documents must fit 30 bits (n < 2^30).
+ *  - Calls on one index from several host threads at once are not supported
+ *    (the search workspace is per index).
+ */
+#ifndef ALLANPOE_H
+#define ALLANPOE_H
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define AP_OK 0
+#define AP_EINVAL (-1)   /* bad argument (null pointer, unsupported size, bad enum) */
+#define AP_ENOMEM (-2)   /* hipMalloc failed */
+#define AP_EHIP (-3)     /* a HIP runtime call or kernel launch failed */
+#define AP_ESTATE (-4)   /* the index lacks what the call needs (e.g. no graph yet) */
+
+#define AP_F32 0
+#define AP_BF16 1
+
+typedef struct ap_index ap_index; /* opaque */
+
+/* The corpus: n fused vectors (Section 3.2: dense part, learned sparse part,
+ * and the text as a bag of (term id, term count) from which the lexical
+ * sparse vector is derived at ingest). */
+typedef struct {
+    int64_t n;
+    int32_t dim;          /* dense dimension; multiple of 4 (f32) or 8 (bf16); <= 1024 (f32) / 2048 (bf16) */
+    int32_t dense_dtype;  /* AP_F32 or AP_BF16 (accumulation is always f32) */
+    const void *dense;    /* n x dim, row-major, 16-byte aligned */
+    const int64_t *sp_indptr; /* n+1 */
+    const int32_t *sp_idx;
+    const float *sp_val;
+    int32_t sp_vocab;
+    const int64_t *tx_indptr; /* n+1 */
+    const int32_t *tx_idx;
+    const float *tx_tf;   /* term counts */
+    int32_t tx_vocab;
+} ap_corpus;
+
+/* Construction parameters (Algorithm 1 names `it` and `d`; the rest are the
+ * quantities it leaves open). */
+typedef struct {
+    int32_t degree;     /* d: length of every semantic edge list; multiple of 4, <= 128 */
+    int32_t knn_k;      /* K: k-NN list length during construction; degree <= K <= 256 */
+    int32_t nd_rounds;  /* it: refinement rounds */
+    int32_t nd_sample;  /* S: neighbours (and neighbours of each) explored per round; <= 32 */
+    int32_t n_entry;    /* E: number of entry points; <= 256 */
+    int32_t sp_len;     /* P: length of each per-path list; <= 32; 0 = ceil(degree/6) */
+    float bm25_k1, bm25_b;
+    float build_w[3];   /* fusion weights used during construction */
+    uint64_t seed;      /* reserved (construction is deterministic) */
+} ap_build_params;
+
+/* A batch of queries.  tx_cnt holds term counts of the query text. */
+typedef struct {
+    int32_t nq;
+    const float *dense;   /* nq x dim f32 */
+    const int64_t *sp_indptr; const int32_t *sp_idx; const float *sp_val;
+    const int64_t *tx_indptr; const int32_t *tx_idx; const float *tx_cnt;
+} ap_queries;
+
+typedef struct {
+    int32_t k;            /* results per query; k <= beam */
+    int32_t beam;         /* L: candidate pool capacity; <= 1024 */
+    int32_t max_iters;    /* 0 = until the pool is fully expanded */
+    int32_t search_width; /* p: pool entries expanded per iteration; 1..8 */
+} ap_search_params;
+
+/* ---- the three calls of the problem statement -------------------------- */
+
+/* Algorithm 1 (Steps 1-3): S0 lexical encoding, seed lists, refinement rounds
+ * under the hybrid metric, detour sort, IP pruning with keyword recycling,
+ * edge-list assembly, entry points.  Synchronises `stream`. */
+int ap_build_index(const ap_corpus *corpus, const ap_build_params *params, void *stream, ap_index **out);
+
+/* Default fusion weights [w_d, w_s, w_f] (host pointer) used by searches that
+ * pass no per-query weights.  O(1): the index is never rebuilt for a change of
+ * weights (Theorem 1; Section 4.2.1). */
+int ap_set_weights(ap_index *index, const float w[3]);
+
+/* Algorithm 2 on the semantic edges for nq queries at once.  per_query_w is
+ * nq x 3 (device) or NULL for the index default.  out_ids / out_scores are
+ * nq x k. */
+int ap_search_batch(ap_index *index, const ap_queries *queries, const float *per_query_w,
+                    const ap_search_params *params, int32_t *out_ids, float *out_scores, void *stream);
+
+void ap_free_index(ap_index *index);
+const char *ap_last_error(void); /* host string, thread-local */
+
+/* ---- measurement / test surface: the same kernels, exposed stage by stage - */
+
+/* S0 only: an index with lexical weights and self-similarities but no graph. */
+int ap_ingest(const ap_corpus *corpus, const ap_build_params *params, void *stream, ap_index **out);
+
+/* Copies out what S0 computed.  Any pointer may be NULL.  tx_w: one f32 per
+ * lexical CSR entry; df: tx_vocab int32; avgdl: 1 f32; self_sim: n f32 (fused
+ * self-similarity under build_w). */
+int ap_export_ingest(const ap_index *index, float *tx_w, int32_t *df, float *avgdl, float *self_sim, void *stream);
+
+/* Definition 1 for explicit pairs: for query x and its c candidates
+ * cand_ids[x*c + y] (document ids, -1 = hole) writes
+ * out4[(x*c + y)*4 + {0,1,2,3}] = sim_d, sim_s, sim_f, M_w (holes: -inf). */
+int ap_hybrid_scores(const ap_index *index, const ap_queries *queries, const int32_t *cand_ids, int32_t c,
+                     const float *per_query_w, float *out4, void *stream);
+
+/* Same with documents on the query side (construction's document-document
+ * similarities): a_ids[na] document ids, w3 three host floats. */
+int ap_hybrid_scores_docs(const ap_index *index, const int32_t *a_ids, int32_t na, const int32_t *cand_ids,
+                          int32_t c, const float w3[3], float *out4, void *stream);
+
+/* Exact top-k by enumeration of all documents (Theorem 1's MIPS solved by
+ * brute force): ground truth for recall. */
+int ap_bruteforce_topk(const ap_index *index, const ap_queries *queries, const float *per_query_w, int32_t k,
+                       int32_t *out_ids, float *out_scores, void *stream);
+
+/* S2: exact top-K by dense inner product among the other documents for the
+ * nn listed nodes (NULL = all n, nn ignored).  out_*: nn x K. */
+int ap_stage_seed_knn(const ap_index *index, const int32_t *node_ids, int64_t nn, int32_t K, int32_t *out_ids,
+                      float *out_scores, void *stream);
+
+/* S3: one refinement round for the nn listed nodes (NULL = all).  knn_ids is
+ * n x K; sp_ids / sp_sc are 3 x n x P (per-path lists so far).  Outputs:
+ * out_ids/out_sc nn x K, out_sp_ids/out_sp_sc 3 x nn x P. */
+int ap_stage_refine(const ap_index *index, int32_t K, int32_t S, int32_t P, const int32_t *knn_ids,
+                    const int32_t *sp_ids, const float *sp_sc, const int32_t *node_ids, int64_t nn,
+                    int32_t *out_ids, float *out_sc, int32_t *out_sp_ids, float *out_sp_sc, void *stream);
+
+/* S4 + S5 for the nn listed nodes (NULL = all): neighbourhood similarities,
+ * detourable-route counts and sort, IP pruning with keyword flags.
+ * knn_ids / knn_sc: n x K lists ranked by fused score.  Outputs (any may be
+ * NULL): pm nn x K x K, count nn x K, sorted_ids nn x K, se nn x R (-1 padded),
+ * ke nn x R/2 (-1 padded), ke_count nn, flag nn x K (indexed by position in
+ * the input list). */
+int ap_stage_prune(const ap_index *index, int32_t K, int32_t R, const int32_t *knn_ids, const float *knn_sc,
+                   const int32_t *node_ids, int64_t nn, float *pm, int32_t *count, int32_t *sorted_ids,
+                   int32_t *se, int32_t *ke, int32_t *ke_count, int32_t *flag, void *stream);
+
+/* S6 for all nodes: se n x R, sorted_ids n x K, sp_ids 3 x n x P -> graph n x R. */
+int ap_stage_assemble(const ap_index *index, int32_t R, int32_t K, int32_t P, const int32_t *se,
+                      const int32_t *sorted_ids, const int32_t *sp_ids, int32_t *out_graph, void *stream);
+
+/* Entry points: the E documents of largest fused self-similarity. */
+int ap_stage_entry_points(const ap_index *index, int32_t E, int32_t *out_entry, void *stream);
+
+/* Graph exchange: lets the search run on a graph built elsewhere and a graph
+ * built here be checked elsewhere.  semantic n x degree, keyword n x degree/2,
+ * kw_count n, entry n_entry.  Export pointers may be NULL. */
+int ap_export_graph(const ap_index *index, int32_t *semantic, int32_t *keyword, int32_t *kw_count, int32_t *entry,
+                    void *stream);
+int ap_import_graph(const ap_corpus *corpus, const ap_build_params *params, const int32_t *semantic,
+                    const int32_t *keyword, const int32_t *kw_count, const int32_t *entry, void *stream,
+                    ap_index **out);
+
+/* Timings of the last ap_build_index on this index, host floats in seconds:
+ * [0] ingest, [1] seed, [2] refinement, [3] prune, [4] assemble+entry, [5] total. */
+int ap_build_timings(const ap_index *index, float out6[6]);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

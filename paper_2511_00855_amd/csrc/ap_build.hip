@@ -1,0 +1,761 @@
+// Index construction (Algorithm 1, Steps 1-3 of Section 4.1): seed lists by an
+// MFMA dense product with exact top-K selection, synchronous refinement rounds
+// under the hybrid metric, detourable-route sort, inner-product pruning with
+// keyword recycling, and assembly of the fixed-degree edge lists.
+// Every stage is a pure function of the previous stage's arrays; nothing that
+// decides an id depends on the order in which atomics arrive.
+#include <algorithm>
+#include "ap_tiles.hpp"
+
+int ap_fill_u32(void *p, size_t n, uint32_t v, hipStream_t st);
+int ap_alloc_graph(ap_index *ix);
+
+#define AP_A_CAP 512   // a-side list entries staged in LDS
+
+// =================================================================== S2: seed
+// scores[r][j] = <dense[node r], dense[j]> for a slab of rows and all columns.
+template <int DT>
+__global__ __launch_bounds__(256) void k_seed_scores(const void *dense, int32_t dim, int64_t n, const int32_t *node_ids,
+                                                     int64_t row0, int64_t nrows, float *__restrict__ scores) {
+    __shared__ float lA[AP_TILE * AP_LDS_STRIDE];
+    __shared__ float lB[AP_TILE * AP_LDS_STRIDE];
+    __shared__ int32_t a_rows[AP_TILE], b_rows[AP_TILE];
+    const int64_t i0 = (int64_t)blockIdx.y * AP_TILE, j0 = (int64_t)blockIdx.x * AP_TILE;
+    if (threadIdx.x < AP_TILE) {
+        const int64_t r = i0 + threadIdx.x;
+        a_rows[threadIdx.x] = r < nrows ? (node_ids ? node_ids[row0 + r] : (int32_t)(row0 + r)) : -1;
+        const int64_t j = j0 + threadIdx.x;
+        b_rows[threadIdx.x] = j < n ? (int32_t)j : -1;
+    }
+    ap_f32x16 acc[2][2];
+    ap_tile_gemm<DT>(dense, dim, a_rows, b_rows, lA, lB, acc);
+    ap_tile_foreach(acc, [&](int i, int j, float v) {
+        if (i0 + i < nrows && j0 + j < n) scores[(i0 + i) * n + (j0 + j)] = v;
+    });
+}
+
+// One block per row: exact top-K of the row (excluding the node itself), sorted.
+__global__ __launch_bounds__(256) void k_select_rows(const float *__restrict__ scores, int64_t n, int32_t K,
+                                                     const int32_t *node_ids, int64_t row0, int32_t exclude_self,
+                                                     int32_t *__restrict__ out_ids, float *__restrict__ out_sc) {
+    __shared__ uint32_t hist[256];
+    __shared__ uint64_t sel[256];
+    __shared__ int32_t misc[4];
+    __shared__ uint64_t pre;
+    const int64_t r = blockIdx.x;
+    const int32_t self = exclude_self ? (node_ids ? node_ids[row0 + r] : (int32_t)(row0 + r)) : -1;
+    for (int i = threadIdx.x; i < 256; i += blockDim.x) sel[i] = 0;
+    __syncthreads();
+    const int32_t got = ap_radix_select(scores + r * n, n, self, K, hist, sel, misc, &pre);
+    ap_bitonic_desc(sel, 256);
+    for (int32_t i = threadIdx.x; i < K; i += blockDim.x) {
+        out_ids[(row0 + r) * K + i] = i < got ? ap_key_id(sel[i]) : -1;
+        out_sc[(row0 + r) * K + i] = i < got ? ap_key_score(sel[i]) : -INFINITY;
+    }
+}
+
+static int seed_knn_impl(const ap_index *ix, const int32_t *node_ids, int64_t nn, int32_t K, int32_t *out_ids,
+                         float *out_sc, hipStream_t st) {
+    const int64_t n = ix->docs.n;
+    // slab of rows whose score matrix fits ~1 GiB
+    int64_t slab = ((int64_t)1 << 28) / n;
+    slab = std::max<int64_t>(AP_TILE, slab / AP_TILE * AP_TILE);
+    slab = std::min<int64_t>(slab, (nn + AP_TILE - 1) / AP_TILE * AP_TILE);
+    float *scratch = nullptr;
+    AP_TRY(ap_dev_alloc(&scratch, (size_t)slab * (size_t)n));
+    hipError_t e = hipSuccess;
+    for (int64_t row0 = 0; row0 < nn && e == hipSuccess; row0 += slab) {
+        const int64_t nrows = std::min(slab, nn - row0);
+        dim3 grid((unsigned)((n + AP_TILE - 1) / AP_TILE), (unsigned)((nrows + AP_TILE - 1) / AP_TILE));
+        if (ix->dtype == AP_F32)
+            hipLaunchKernelGGL(k_seed_scores<AP_F32>, grid, dim3(256), 0, st, ix->docs.dense, ix->docs.dim, n, node_ids, row0, nrows, scratch);
+        else
+            hipLaunchKernelGGL(k_seed_scores<AP_BF16>, grid, dim3(256), 0, st, ix->docs.dense, ix->docs.dim, n, node_ids, row0, nrows, scratch);
+        e = hipGetLastError();
+        if (e != hipSuccess) break;
+        hipLaunchKernelGGL(k_select_rows, dim3((unsigned)nrows), dim3(256), 0, st, scratch, n, K, node_ids, row0, 1, out_ids, out_sc);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    (void)hipFree(scratch);
+    if (e != hipSuccess) { ap_set_error("seed k-NN failed: %s", hipGetErrorString(e)); return AP_EHIP; }
+    return AP_OK;
+}
+
+extern "C" int ap_stage_seed_knn(const ap_index *ix, const int32_t *node_ids, int64_t nn, int32_t K, int32_t *out_ids,
+                                 float *out_scores, void *stream) {
+    AP_REQUIRE(ix && out_ids && out_scores, "NULL argument");
+    AP_REQUIRE(K >= 1 && K <= 256, "K = %d must be in [1, 256]", K);
+    if (!node_ids) nn = ix->docs.n;
+    AP_REQUIRE(nn >= 0, "nn is negative");
+    if (nn == 0) return AP_OK;
+    return seed_knn_impl(ix, node_ids, nn, K, out_ids, out_scores, (hipStream_t)stream);
+}
+
+extern "C" int ap_stage_entry_points(const ap_index *ix, int32_t E, int32_t *out_entry, void *stream) {
+    AP_REQUIRE(ix && out_entry, "NULL argument");
+    AP_REQUIRE(E >= 1 && E <= 256, "E = %d must be in [1, 256]", E);
+    hipStream_t st = (hipStream_t)stream;
+    float *sc = nullptr;
+    AP_TRY(ap_dev_alloc(&sc, (size_t)E));
+    hipLaunchKernelGGL(k_select_rows, dim3(1), dim3(256), 0, st, ix->self_sim, ix->docs.n, E, (const int32_t *)nullptr,
+                       (int64_t)0, 0, out_entry, sc);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    (void)hipFree(sc);
+    if (e != hipSuccess) { ap_set_error("entry point selection failed: %s", hipGetErrorString(e)); return AP_EHIP; }
+    return AP_OK;
+}
+
+// =================================================================== S3: refinement round
+#define AP_HT 4096
+#define AP_MAXC 1280   // K + S*S <= 256 + 32*32
+
+__device__ __forceinline__ bool ap_ht_insert(int32_t *ht, int32_t v) {
+    uint32_t h = ((uint32_t)v * 2654435761u) >> 20;  // 12 bits
+    for (;;) {
+        const int32_t old = atomicCAS(&ht[h], -1, v);
+        if (old == -1) return true;
+        if (old == v) return false;
+        h = (h + 1) & (AP_HT - 1);
+    }
+}
+__device__ __forceinline__ bool ap_ht_has(const int32_t *ht, int32_t v) {
+    uint32_t h = ((uint32_t)v * 2654435761u) >> 20;
+    for (;;) {
+        const int32_t cur = ht[h];
+        if (cur == -1) return false;
+        if (cur == v) return true;
+        h = (h + 1) & (AP_HT - 1);
+    }
+}
+
+// Block-wide maximum of a 64-bit key; every thread gets the result.
+__device__ __forceinline__ uint64_t ap_block_max(uint64_t v, uint64_t *red /* 8 */) {
+    for (int o = 32; o > 0; o >>= 1) {
+        const uint64_t other = __shfl_xor(v, o, 64);
+        v = other > v ? other : v;
+    }
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    uint64_t b = red[0];
+    for (int i = 1; i < (int)(blockDim.x >> 6); i++) b = red[i] > b ? red[i] : b;
+    return b;
+}
+
+template <int DT, int NV>
+__global__ __launch_bounds__(256) void k_refine(ApVecs D, float wd, float ws, float wf, int32_t K, int32_t S, int32_t P,
+                                                const int32_t *__restrict__ knn, const int32_t *__restrict__ sp_ids,
+                                                const float *__restrict__ sp_sc, const int32_t *__restrict__ node_ids,
+                                                int64_t nn, int32_t *__restrict__ out_ids, float *__restrict__ out_sc,
+                                                int32_t *__restrict__ out_sp_ids, float *__restrict__ out_sp_sc) {
+    __shared__ int32_t ht[AP_HT];
+    __shared__ int32_t cand[AP_MAXC];
+    __shared__ uint64_t keys[AP_MAXC];
+    __shared__ float comp[3][AP_MAXC];
+    __shared__ int32_t l_sp_idx[AP_A_CAP], l_tx_idx[AP_A_CAP];
+    __shared__ float l_sp_val[AP_A_CAP], l_tx_val[AP_A_CAP];
+    __shared__ uint64_t oldk[32];
+    __shared__ uint64_t red[8];
+    __shared__ int32_t s_cnt, s_nold;
+    const int64_t x = blockIdx.x;
+    const int64_t u = node_ids ? (int64_t)node_ids[x] : x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const ApLists a = ap_stage_lists(D, u, l_sp_idx, l_sp_val, l_tx_idx, l_tx_val, AP_A_CAP);
+    float qa[NV * ApDense<DT>::EPC];
+    ap_load_aside<DT, NV, DT>(D.dense, u, D.dim, qa);
+    for (int i = threadIdx.x; i < AP_HT; i += blockDim.x) ht[i] = -1;
+    if (threadIdx.x == 0) s_cnt = 0;
+    __syncthreads();
+    // candidates: own list, and the first S neighbours of the first S neighbours
+    const int32_t sl = S < K ? S : K;
+    const int32_t slots = K + sl * sl;
+    for (int32_t s = threadIdx.x; s < slots; s += blockDim.x) {
+        int32_t v;
+        if (s < K) v = knn[u * K + s];
+        else {
+            const int32_t i = (s - K) / sl, j = (s - K) % sl;
+            const int32_t p = knn[u * K + i];
+            v = p < 0 ? -1 : knn[(int64_t)p * K + j];
+        }
+        if (v >= 0 && v != (int32_t)u && ap_ht_insert(ht, v)) cand[atomicAdd(&s_cnt, 1)] = v;
+    }
+    __syncthreads();
+    const int32_t cnt = s_cnt;
+    for (int32_t i = wave; i < cnt; i += 4) {
+        const int32_t v = cand[i];
+        float sd, ss, sf;
+        ap_hybrid_wave<DT, NV>(D, qa, a, v, sd, ss, sf);
+        if (lane == 0) {
+            keys[i] = ap_make_key(ap_fuse(wd, ws, wf, sd, ss, sf), v, 1u);
+            comp[0][i] = sd; comp[1][i] = ss; comp[2][i] = sf;
+        }
+    }
+    __syncthreads();
+    // top-K under the fused score by ranking
+    for (int32_t t = threadIdx.x; t < cnt; t += blockDim.x) {
+        const uint64_t key = keys[t];
+        int32_t r = 0;
+        for (int32_t j = 0; j < cnt; j++) r += keys[j] > key;
+        if (r < K) { out_ids[x * K + r] = ap_key_id(key); out_sc[x * K + r] = ap_key_score(key); }
+    }
+    for (int32_t t = cnt + threadIdx.x; t < K; t += blockDim.x) { out_ids[x * K + t] = -1; out_sc[x * K + t] = -INFINITY; }
+    // per-path lists: the best P by each single similarity among this round's
+    // candidates and the previous list (entries scored again this round excepted)
+    for (int p = 0; p < 3; p++) {
+        __syncthreads();
+        if (threadIdx.x == 0) s_nold = 0;
+        __syncthreads();
+        if (threadIdx.x < P) {
+            const int32_t id = sp_ids[((int64_t)p * D.n + u) * P + threadIdx.x];
+            if (id >= 0 && !ap_ht_has(ht, id))
+                oldk[atomicAdd(&s_nold, 1)] = ap_make_key(sp_sc[((int64_t)p * D.n + u) * P + threadIdx.x], id, 1u);
+        }
+        __syncthreads();
+        const int32_t nold = s_nold;
+        uint64_t prev = ~0ull;
+        for (int32_t r = 0; r < P; r++) {
+            uint64_t best = 0;
+            for (int32_t t = threadIdx.x; t < cnt + nold; t += blockDim.x) {
+                const uint64_t key = t < cnt ? ap_make_key(comp[p][t], cand[t], 1u) : oldk[t - cnt];
+                if (key < prev && key > best) best = key;
+            }
+            best = ap_block_max(best, red);
+            if (threadIdx.x == 0) {
+                out_sp_ids[((int64_t)p * nn + x) * P + r] = best ? ap_key_id(best) : -1;
+                out_sp_sc[((int64_t)p * nn + x) * P + r] = best ? ap_key_score(best) : -INFINITY;
+            }
+            prev = best;   // 0 once exhausted: nothing ranks after it
+        }
+    }
+}
+
+extern "C" int ap_stage_refine(const ap_index *ix, int32_t K, int32_t S, int32_t P, const int32_t *knn_ids,
+                               const int32_t *sp_ids, const float *sp_sc, const int32_t *node_ids, int64_t nn,
+                               int32_t *out_ids, float *out_sc, int32_t *out_sp_ids, float *out_sp_sc, void *stream) {
+    AP_REQUIRE(ix && knn_ids && sp_ids && sp_sc && out_ids && out_sc && out_sp_ids && out_sp_sc, "NULL argument");
+    AP_REQUIRE(K >= 1 && K <= 256 && S >= 1 && S <= 32 && P >= 1 && P <= 32, "need 1<=K<=256, 1<=S<=32, 1<=P<=32");
+    if (!node_ids) nn = ix->docs.n;
+    if (nn <= 0) return AP_OK;
+    const float *w = ix->params.build_w;
+    AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim,
+                      hipLaunchKernelGGL((k_refine<DT, NV>), dim3((unsigned)nn), dim3(256), 0, (hipStream_t)stream, ix->docs,
+                                         w[0], w[1], w[2], K, S, P, knn_ids, sp_ids, sp_sc, node_ids, nn, out_ids, out_sc,
+                                         out_sp_ids, out_sp_sc));
+    AP_CHECK_HIP(hipGetLastError());
+    return AP_OK;
+}
+
+// =================================================================== S4: neighbourhood similarities
+// Dense part: G = X X^T for the K gathered rows of one neighbourhood (MFMA).
+template <int DT>
+__global__ __launch_bounds__(256) void k_gram_dense(const void *dense, int32_t dim, int32_t K, const int32_t *__restrict__ knn,
+                                                    const int32_t *__restrict__ node_ids, int64_t x0,
+                                                    float *__restrict__ pm /* chunk x K x K */) {
+    __shared__ float lA[AP_TILE * AP_LDS_STRIDE];
+    __shared__ float lB[AP_TILE * AP_LDS_STRIDE];
+    __shared__ int32_t a_rows[AP_TILE], b_rows[AP_TILE];
+    const int64_t x = blockIdx.y;
+    const int64_t u = node_ids ? (int64_t)node_ids[x0 + x] : x0 + x;
+    const int32_t tiles = (K + AP_TILE - 1) / AP_TILE;
+    const int32_t i0 = (blockIdx.x / tiles) * AP_TILE, j0 = (blockIdx.x % tiles) * AP_TILE;
+    if (threadIdx.x < AP_TILE) {
+        a_rows[threadIdx.x] = i0 + threadIdx.x < K ? knn[u * K + i0 + threadIdx.x] : -1;
+        b_rows[threadIdx.x] = j0 + threadIdx.x < K ? knn[u * K + j0 + threadIdx.x] : -1;
+    }
+    ap_f32x16 acc[2][2];
+    ap_tile_gemm<DT>(dense, dim, a_rows, b_rows, lA, lB, acc);
+    float *out = pm + x * (int64_t)K * K;
+    ap_tile_foreach(acc, [&](int i, int j, float v) {
+        if (i0 + i < K && j0 + j < K) out[(int64_t)(i0 + i) * K + (j0 + j)] = v;
+    });
+}
+
+// Sparse and lexical parts, and the fusion: one block per (neighbourhood,
+// block of CB columns).  The CB column documents' lists sit in LDS; each wave
+// walks the rows, staging the row document's lists in its own LDS slice.
+#define AP_CB 32
+#define AP_CB_ENTRIES 5632
+#define AP_W_CAP 256
+
+template <int DT>
+__global__ __launch_bounds__(256) void k_gram_sparse(ApVecs D, float wd, float ws, float wf, int32_t K,
+                                                     const int32_t *__restrict__ knn, const int32_t *__restrict__ node_ids,
+                                                     int64_t x0, float *__restrict__ pm) {
+    __shared__ int32_t b_idx[AP_CB_ENTRIES];
+    __shared__ float b_val[AP_CB_ENTRIES];
+    __shared__ int32_t b_off[2][AP_CB + 1];       // offsets into b_idx/b_val, or -1 when the list stayed in global memory
+    __shared__ int32_t b_len[2][AP_CB];
+    __shared__ int32_t b_id[AP_CB];
+    __shared__ int32_t w_idx[4][2][AP_W_CAP];
+    __shared__ float w_val[4][2][AP_W_CAP];
+    const int64_t x = blockIdx.y;
+    const int64_t u = node_ids ? (int64_t)node_ids[x0 + x] : x0 + x;
+    const int32_t j0 = blockIdx.x * AP_CB;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // plan the LDS layout of the column lists (thread 0), then copy cooperatively
+    if (threadIdx.x == 0) {
+        int32_t used = 0;
+        for (int c = 0; c < AP_CB; c++) {
+            const int32_t v = j0 + c < K ? knn[u * K + j0 + c] : -1;
+            b_id[c] = v;
+            for (int part = 0; part < 2; part++) {
+                int32_t len = 0;
+                if (v >= 0) len = (int32_t)(part == 0 ? D.sp_indptr[v + 1] - D.sp_indptr[v] : D.tx_indptr[v + 1] - D.tx_indptr[v]);
+                b_len[part][c] = len;
+                if (used + len <= AP_CB_ENTRIES) { b_off[part][c] = used; used += len; }
+                else b_off[part][c] = -1;
+            }
+        }
+    }
+    __syncthreads();
+    for (int c = 0; c < AP_CB; c++) {
+        const int32_t v = b_id[c];
+        if (v < 0) continue;
+        for (int part = 0; part < 2; part++) {
+            const int32_t off = b_off[part][c], len = b_len[part][c];
+            if (off < 0) continue;
+            const int64_t g0 = part == 0 ? D.sp_indptr[v] : D.tx_indptr[v];
+            const int32_t *gi = part == 0 ? D.sp_idx : D.tx_idx;
+            const float *gv = part == 0 ? D.sp_val : D.tx_val;
+            for (int32_t e = threadIdx.x; e < len; e += blockDim.x) { b_idx[off + e] = gi[g0 + e]; b_val[off + e] = gv[g0 + e]; }
+        }
+    }
+    __syncthreads();
+    float *out = pm + x * (int64_t)K * K;
+    for (int32_t i = wave; i < K; i += 4) {
+        const int32_t a = knn[u * K + i];
+        // this wave's row lists (LDS slice if short enough, else global)
+        const int32_t *ai[2]; const float *av[2]; int32_t an[2];
+        if (a >= 0) {
+            for (int part = 0; part < 2; part++) {
+                const int64_t g0 = part == 0 ? D.sp_indptr[a] : D.tx_indptr[a];
+                const int64_t g1 = part == 0 ? D.sp_indptr[a + 1] : D.tx_indptr[a + 1];
+                const int32_t *gi = part == 0 ? D.sp_idx : D.tx_idx;
+                const float *gv = part == 0 ? D.sp_val : D.tx_val;
+                an[part] = (int32_t)(g1 - g0);
+                if (an[part] <= AP_W_CAP) {
+                    for (int32_t e = lane; e < an[part]; e += 64) { w_idx[wave][part][e] = gi[g0 + e]; w_val[wave][part][e] = gv[g0 + e]; }
+                    ai[part] = w_idx[wave][part]; av[part] = w_val[wave][part];
+                } else { ai[part] = gi + g0; av[part] = gv + g0; }
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        for (int c = 0; c < AP_CB && j0 + c < K; c++) {
+            const int32_t b = b_id[c];
+            float val = -INFINITY;
+            if (a >= 0 && b >= 0) {
+                float part_sum[2];
+                for (int part = 0; part < 2; part++) {
+                    const int32_t off = b_off[part][c];
+                    float p;
+                    if (off >= 0) p = ap_sparse_partial(ai[part], av[part], an[part], b_idx, b_val, off, off + b_len[part][c], lane);
+                    else {
+                        const int64_t g0 = part == 0 ? D.sp_indptr[b] : D.tx_indptr[b];
+                        p = ap_sparse_partial(ai[part], av[part], an[part], part == 0 ? D.sp_idx : D.tx_idx,
+                                              part == 0 ? D.sp_val : D.tx_val, g0, g0 + b_len[part][c], lane);
+                    }
+                    part_sum[part] = ap_wave_sum(p);
+                }
+                val = ap_fuse(wd, ws, wf, out[(int64_t)i * K + j0 + c], part_sum[0], part_sum[1]);
+            }
+            if (lane == 0) out[(int64_t)i * K + j0 + c] = val;
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+// =================================================================== S4 + S5: detour sort, IP prune, keyword flags
+// Detourable routes (Section 3.3): A -> X -> Y detours A -> Y iff
+// min(sim(A,X), sim(X,Y)) > sim(A,Y).  Neighbours are stably sorted by their
+// number of such routes, then walked in that order (Algorithm 1): v joins SE
+// when |SE| < R and sim(w,v) < sim(v,v) for every w in SE; otherwise it is
+// recycled as a keyword edge if its keyword flag is set, i.e. if it shares a
+// keyword with A and no current member of SE covers all the shared keywords.
+#define AP_T_CAP 512
+
+__device__ __forceinline__ bool ap_list_has(const int32_t *idx, int64_t beg, int64_t end, int32_t t) {
+    int64_t lo = beg, hi = end;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (idx[mid] < t) lo = mid + 1; else hi = mid;
+    }
+    return lo < end && idx[lo] == t;
+}
+
+__global__ __launch_bounds__(256) void k_detour_prune(ApVecs D, const float *__restrict__ self_sim, int32_t K, int32_t R,
+                                                      int32_t ke_cap, const int32_t *__restrict__ knn,
+                                                      const float *__restrict__ knn_sc, const int32_t *__restrict__ node_ids,
+                                                      int64_t x0, int64_t xout0, const float *__restrict__ pm,
+                                                      int32_t *__restrict__ o_count, int32_t *__restrict__ o_sorted,
+                                                      int32_t *__restrict__ o_se, int32_t *__restrict__ o_ke,
+                                                      int32_t *__restrict__ o_ke_count, int32_t *__restrict__ o_flag) {
+    __shared__ int32_t ids[256], cnt[256], order[256], se_pos[128], flag[256];
+    __shared__ float simA[256];
+    __shared__ int32_t T[AP_T_CAP];
+    const int64_t x = blockIdx.x;               // index inside the chunk (pm)
+    const int64_t xo = xout0 + x;               // index in the output arrays
+    const int64_t u = node_ids ? (int64_t)node_ids[x0 + x] : x0 + x;
+    const float *P = pm + x * (int64_t)K * K;
+    const int t = threadIdx.x;
+    if (t < K) { ids[t] = knn[u * K + t]; simA[t] = knn_sc[u * K + t]; flag[t] = 0; }
+    __syncthreads();
+    if (t < K) {
+        int32_t c = 0;
+        if (ids[t] >= 0) {
+            const float sy = simA[t];
+            for (int32_t xx = 0; xx < K; xx++) {
+                if (xx == t || ids[xx] < 0) continue;
+                const float a = simA[xx], b = P[(int64_t)xx * K + t];
+                c += (a < b ? a : b) > sy;
+            }
+        }
+        cnt[t] = c;
+    }
+    __syncthreads();
+    if (t < K) {
+        int32_t r = 0;
+        if (ids[t] >= 0) {
+            for (int32_t z = 0; z < K; z++) r += ids[z] >= 0 && (cnt[z] < cnt[t] || (cnt[z] == cnt[t] && z < t));
+        } else {
+            for (int32_t z = 0; z < K; z++) r += ids[z] >= 0 || z < t;
+        }
+        order[r] = t;
+    }
+    __syncthreads();
+    if (t < K) {
+        if (o_count) o_count[xo * K + t] = cnt[t];
+        if (o_sorted) o_sorted[xo * K + t] = ids[order[t]];
+    }
+    if (t >= 64) return;   // the walk is sequential in v; one wave does it
+    const int lane = t;
+    const int64_t ab = D.tx_indptr[u], ae = D.tx_indptr[u + 1];
+    int32_t nse = 0, nke = 0;
+    for (int32_t r = 0; r < K; r++) {
+        const int32_t pv = order[r], v = ids[pv];
+        if (v < 0) break;   // holes are sorted last
+        if (nse == 0) { if (lane == 0) se_pos[0] = pv; nse = 1; __builtin_amdgcn_wave_barrier(); continue; }
+        // T = K(A) n K(v)
+        const int64_t vb = D.tx_indptr[v], ve = D.tx_indptr[v + 1];
+        int32_t nt_all = 0;
+        for (int64_t e0 = vb; e0 < ve; e0 += 64) {
+            const int64_t e = e0 + lane;
+            const int32_t term = e < ve ? D.tx_idx[e] : -1;
+            const bool in = term >= 0 && ap_list_has(D.tx_idx, ab, ae, term);
+            const uint64_t m = __ballot(in);
+            if (in) { const int32_t pos = nt_all + __popcll(m & ((1ull << lane) - 1ull)); if (pos < AP_T_CAP) T[pos] = term; }
+            nt_all += __popcll(m);
+        }
+        __builtin_amdgcn_wave_barrier();
+        const int32_t nt = nt_all < AP_T_CAP ? nt_all : AP_T_CAP;
+        int32_t fl = 0;
+        if (nt_all > 0) {
+            // does some member of SE hold every shared keyword?
+            bool covered = false;
+            for (int32_t i = lane; i < nse; i += 64) {
+                const int32_t y = ids[se_pos[i]];
+                const int64_t yb = D.tx_indptr[y], ye = D.tx_indptr[y + 1];
+                bool all_in = true;
+                for (int32_t k = 0; k < nt && all_in; k++) all_in = ap_list_has(D.tx_idx, yb, ye, T[k]);
+                if (all_in && nt_all > AP_T_CAP) {   // rare: the shared set overflowed T; test the rest directly
+                    for (int64_t e = vb; e < ve && all_in; e++) {
+                        const int32_t term = D.tx_idx[e];
+                        if (ap_list_has(D.tx_idx, ab, ae, term)) all_in = ap_list_has(D.tx_idx, yb, ye, term);
+                    }
+                }
+                covered = covered || all_in;
+            }
+            fl = __ballot(covered) ? 0 : 1;
+        }
+        // IP test against every member of SE
+        bool bad = false;
+        const float sv = self_sim[v];
+        for (int32_t i = lane; i < nse; i += 64) bad = bad || !(P[(int64_t)se_pos[i] * K + pv] < sv);
+        const bool ok = nse < R && !__ballot(bad);
+        if (lane == 0) {
+            flag[pv] = fl;
+            if (ok) se_pos[nse] = pv;
+            else if (fl && nke < ke_cap && o_ke) o_ke[xo * ke_cap + nke] = v;
+        }
+        if (ok) nse++;
+        else if (fl && nke < ke_cap) nke++;
+        __builtin_amdgcn_wave_barrier();
+    }
+    __builtin_amdgcn_wave_barrier();
+    for (int32_t i = lane; i < R; i += 64) if (o_se) o_se[xo * R + i] = i < nse ? ids[se_pos[i]] : -1;
+    for (int32_t i = nke + lane; i < ke_cap; i += 64) if (o_ke) o_ke[xo * ke_cap + i] = -1;
+    if (lane == 0 && o_ke_count) o_ke_count[xo] = nke;
+    for (int32_t i = lane; i < K; i += 64) if (o_flag) o_flag[xo * K + i] = flag[i];
+}
+
+static int prune_impl(const ap_index *ix, int32_t K, int32_t R, const int32_t *knn_ids, const float *knn_sc,
+                      const int32_t *node_ids, int64_t nn, float *pm_out, int32_t *count, int32_t *sorted_ids,
+                      int32_t *se, int32_t *ke, int32_t *ke_count, int32_t *flag, hipStream_t st) {
+    const int64_t per = (int64_t)K * K;
+    int64_t chunk = pm_out ? nn : std::min<int64_t>(nn, std::max<int64_t>(1, ((int64_t)1 << 28) / per));
+    float *scratch = nullptr;
+    if (!pm_out) AP_TRY(ap_dev_alloc(&scratch, (size_t)chunk * (size_t)per));
+    const float *w = ix->params.build_w;
+    const int32_t tiles = (K + AP_TILE - 1) / AP_TILE;
+    hipError_t e = hipSuccess;
+    for (int64_t x0 = 0; x0 < nn && e == hipSuccess; x0 += chunk) {
+        const int64_t cn = std::min(chunk, nn - x0);
+        float *pm = pm_out ? pm_out + x0 * per : scratch;
+        for (int64_t y0 = 0; y0 < cn && e == hipSuccess; y0 += 32768) {   // grid.y limit
+            const int64_t yn = std::min<int64_t>(32768, cn - y0);
+            dim3 g1((unsigned)(tiles * tiles), (unsigned)yn);
+            if (ix->dtype == AP_F32)
+                hipLaunchKernelGGL(k_gram_dense<AP_F32>, g1, dim3(256), 0, st, ix->docs.dense, ix->docs.dim, K, knn_ids, node_ids, x0 + y0, pm + y0 * per);
+            else
+                hipLaunchKernelGGL(k_gram_dense<AP_BF16>, g1, dim3(256), 0, st, ix->docs.dense, ix->docs.dim, K, knn_ids, node_ids, x0 + y0, pm + y0 * per);
+            e = hipGetLastError();
+            if (e != hipSuccess) break;
+            dim3 g2((unsigned)((K + AP_CB - 1) / AP_CB), (unsigned)yn);
+            if (ix->dtype == AP_F32)
+                hipLaunchKernelGGL(k_gram_sparse<AP_F32>, g2, dim3(256), 0, st, ix->docs, w[0], w[1], w[2], K, knn_ids, node_ids, x0 + y0, pm + y0 * per);
+            else
+                hipLaunchKernelGGL(k_gram_sparse<AP_BF16>, g2, dim3(256), 0, st, ix->docs, w[0], w[1], w[2], K, knn_ids, node_ids, x0 + y0, pm + y0 * per);
+            e = hipGetLastError();
+        }
+        if (e != hipSuccess) break;
+        hipLaunchKernelGGL(k_detour_prune, dim3((unsigned)cn), dim3(256), 0, st, ix->docs, ix->self_sim, K, R, R / 2, knn_ids,
+                           knn_sc, node_ids, x0, x0, pm, count, sorted_ids, se, ke, ke_count, flag);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (scratch) (void)hipFree(scratch);
+    if (e != hipSuccess) { ap_set_error("prune stage failed: %s", hipGetErrorString(e)); return AP_EHIP; }
+    return AP_OK;
+}
+
+extern "C" int ap_stage_prune(const ap_index *ix, int32_t K, int32_t R, const int32_t *knn_ids, const float *knn_sc,
+                              const int32_t *node_ids, int64_t nn, float *pm, int32_t *count, int32_t *sorted_ids,
+                              int32_t *se, int32_t *ke, int32_t *ke_count, int32_t *flag, void *stream) {
+    AP_REQUIRE(ix && knn_ids && knn_sc, "NULL argument");
+    AP_REQUIRE(K >= 1 && K <= 256 && R >= 2 && R <= 128, "need 1<=K<=256, 2<=R<=128");
+    if (!node_ids) nn = ix->docs.n;
+    if (nn <= 0) return AP_OK;
+    return prune_impl(ix, K, R, knn_ids, knn_sc, node_ids, nn, pm, count, sorted_ids, se, ke, ke_count, flag, (hipStream_t)stream);
+}
+
+// =================================================================== S6: assembly
+// Reverse neighbours of u: nodes x with u among the first q entries of SE(x),
+// ordered by (position of u in SE(x), x); the first q that are not already
+// forward neighbours of u.  Found in q rounds of an order-independent atomic
+// minimum over all (x, pos) edges: round r keeps, per target, the smallest key
+// above the one kept in round r-1.
+__global__ void k_rev_round(const int32_t *__restrict__ se, int64_t n, int32_t R, int32_t q, int32_t round,
+                            unsigned long long *__restrict__ rev /* n x q, ~0 = none */) {
+    const int64_t total = n * q;
+    for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t xnode = e / q;
+        const int32_t pos = (int32_t)(e % q);
+        const int32_t u = se[xnode * R + pos];
+        if (u < 0 || u == xnode) continue;
+        const unsigned long long key = (((unsigned long long)pos << 32) | (unsigned long long)xnode) + 1ull;
+        unsigned long long prev = 0;
+        if (round > 0) {
+            prev = rev[(int64_t)u * q + round - 1];
+            if (prev == ~0ull) continue;
+        }
+        if (key <= prev) continue;
+        bool fwd = false;                 // x already a forward neighbour of u?
+        for (int32_t i = 0; i < q; i++) fwd = fwd || se[(int64_t)u * R + i] == (int32_t)xnode;
+        if (!fwd) atomicMin(&rev[(int64_t)u * q + round], key);
+    }
+}
+
+// One wave per node, following the order: SE[0:q], reverse neighbours, the
+// per-path lists taken round-robin (dense, sparse, lexical) up to R/2, then
+// padding from the rest of SE and from the detour-sorted list.
+__global__ __launch_bounds__(256) void k_assemble(int64_t n, int32_t R, int32_t K, int32_t P, const int32_t *__restrict__ se,
+                                                  const int32_t *__restrict__ sorted_ids, const int32_t *__restrict__ sp_ids,
+                                                  const unsigned long long *__restrict__ rev, int32_t *__restrict__ out) {
+    __shared__ int32_t rows[4][128];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t u = blockIdx.x * 4 + wave;
+    if (u >= n) return;
+    int32_t *row = rows[wave];
+    int32_t len = 0;
+    const int32_t q = R / 4, h = R / 2;
+    auto present = [&](int32_t v) -> bool {
+        bool hit = false;
+        for (int32_t i = lane; i < len; i += 64) hit = hit || row[i] == v;
+        return __ballot(hit) != 0;
+    };
+    auto push = [&](int32_t v) -> bool {   // wave-uniform
+        if (v < 0 || v == (int32_t)u || present(v)) return false;
+        if (lane == 0) row[len] = v;
+        len++;
+        __builtin_amdgcn_wave_barrier();
+        return true;
+    };
+    for (int32_t i = 0; i < q; i++) push(se[u * R + i]);
+    for (int32_t i = 0, added = 0; i < q && added < q; i++) {
+        const unsigned long long key = rev[u * q + i];
+        if (key == ~0ull) break;
+        if (push((int32_t)((key - 1ull) & 0xffffffffull))) added++;
+    }
+    {
+        int32_t ptr[3] = {0, 0, 0}, added = 0, turn = 0, idle = 0;
+        while (added < h && idle < 3) {
+            bool took = false;
+            while (ptr[turn] < P) {
+                const int32_t v = sp_ids[((int64_t)turn * n + u) * P + ptr[turn]];
+                ptr[turn]++;
+                if (push(v)) { added++; took = true; break; }
+            }
+            idle = took ? 0 : idle + 1;
+            turn = (turn + 1) % 3;
+        }
+    }
+    for (int32_t i = q; i < R && len < R; i++) push(se[u * R + i]);
+    for (int32_t i = 0; i < K && len < R; i++) push(sorted_ids[u * K + i]);
+    __builtin_amdgcn_wave_barrier();
+    for (int32_t i = lane; i < R; i += 64) out[u * R + i] = i < len ? row[i] : -1;
+}
+
+static int assemble_impl(const ap_index *ix, int32_t R, int32_t K, int32_t P, const int32_t *se, const int32_t *sorted_ids,
+                         const int32_t *sp_ids, int32_t *out_graph, hipStream_t st) {
+    const int64_t n = ix->docs.n;
+    const int32_t q = R / 4;
+    unsigned long long *rev = nullptr;
+    AP_TRY(ap_dev_alloc(&rev, (size_t)n * (size_t)q));
+    int rc = ap_fill_u32(rev, (size_t)n * q * 2, 0xffffffffu, st);
+    hipError_t e = hipSuccess;
+    if (rc == AP_OK) {
+        const int64_t total = n * q;
+        const unsigned blocks = (unsigned)std::min<int64_t>((total + 255) / 256, 65536);
+        for (int32_t r = 0; r < q && e == hipSuccess; r++) {
+            hipLaunchKernelGGL(k_rev_round, dim3(blocks), dim3(256), 0, st, se, n, R, q, r, rev);
+            e = hipGetLastError();
+        }
+        if (e == hipSuccess) {
+            hipLaunchKernelGGL(k_assemble, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st, n, R, K, P, se, sorted_ids, sp_ids, rev, out_graph);
+            e = hipGetLastError();
+        }
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+    }
+    (void)hipFree(rev);
+    if (rc != AP_OK) return rc;
+    if (e != hipSuccess) { ap_set_error("assemble stage failed: %s", hipGetErrorString(e)); return AP_EHIP; }
+    return AP_OK;
+}
+
+extern "C" int ap_stage_assemble(const ap_index *ix, int32_t R, int32_t K, int32_t P, const int32_t *se,
+                                 const int32_t *sorted_ids, const int32_t *sp_ids, int32_t *out_graph, void *stream) {
+    AP_REQUIRE(ix && se && sorted_ids && sp_ids && out_graph, "NULL argument");
+    AP_REQUIRE(R >= 4 && R % 4 == 0 && R <= 128 && K >= 1 && K <= 256 && P >= 1 && P <= 32, "need R%%4==0, 4<=R<=128, 1<=K<=256, 1<=P<=32");
+    return assemble_impl(ix, R, K, P, se, sorted_ids, sp_ids, out_graph, (hipStream_t)stream);
+}
+
+// =================================================================== the whole build
+// Fused scores of existing lists (used when no refinement round runs).
+template <int DT, int NV>
+__global__ __launch_bounds__(256) void k_rescore_lists(ApVecs D, float wd, float ws, float wf, int32_t K,
+                                                       const int32_t *__restrict__ knn, float *__restrict__ sc) {
+    __shared__ int32_t l_sp_idx[AP_A_CAP], l_tx_idx[AP_A_CAP];
+    __shared__ float l_sp_val[AP_A_CAP], l_tx_val[AP_A_CAP];
+    const int64_t u = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const ApLists a = ap_stage_lists(D, u, l_sp_idx, l_sp_val, l_tx_idx, l_tx_val, AP_A_CAP);
+    float qa[NV * ApDense<DT>::EPC];
+    ap_load_aside<DT, NV, DT>(D.dense, u, D.dim, qa);
+    __syncthreads();
+    for (int32_t i = wave; i < K; i += 4) {
+        const int32_t v = knn[u * K + i];
+        float s = -INFINITY;
+        if (v >= 0) { float sd, ss, sf; ap_hybrid_wave<DT, NV>(D, qa, a, v, sd, ss, sf); s = ap_fuse(wd, ws, wf, sd, ss, sf); }
+        if (lane == 0) sc[u * K + i] = s;
+    }
+}
+
+struct BuildBufs {
+    int32_t *knn[2] = {nullptr, nullptr};
+    float *knn_sc[2] = {nullptr, nullptr};
+    int32_t *spi[2] = {nullptr, nullptr};
+    float *sps[2] = {nullptr, nullptr};
+    int32_t *se = nullptr, *sorted = nullptr;
+    void release() {
+        void *p[] = {knn[0], knn[1], knn_sc[0], knn_sc[1], spi[0], spi[1], sps[0], sps[1], se, sorted};
+        for (void *x : p) if (x) (void)hipFree(x);
+    }
+};
+
+static int build_impl(ap_index *ix, hipStream_t st, BuildBufs &b) {
+    const ap_build_params &p = ix->params;
+    const int64_t n = ix->corpus.n;   // ix->docs is only filled in by the ingest step below
+    const int32_t K = p.knn_k, R = p.degree, P = p.sp_len;
+    hipEvent_t ev[6];
+    for (auto &e : ev) AP_CHECK_HIP(hipEventCreate(&e));
+    auto mark = [&](int i) { return hipEventRecord(ev[i], st); };
+    AP_CHECK_HIP(mark(0));
+    AP_TRY(ap_ingest_impl(ix, st));
+    AP_CHECK_HIP(mark(1));
+    for (int i = 0; i < 2; i++) {
+        AP_TRY(ap_dev_alloc(&b.knn[i], (size_t)n * K));
+        AP_TRY(ap_dev_alloc(&b.knn_sc[i], (size_t)n * K));
+        AP_TRY(ap_dev_alloc(&b.spi[i], (size_t)3 * n * P));
+        AP_TRY(ap_dev_alloc(&b.sps[i], (size_t)3 * n * P));
+    }
+    AP_TRY(ap_dev_alloc(&b.se, (size_t)n * R));
+    AP_TRY(ap_dev_alloc(&b.sorted, (size_t)n * K));
+    AP_TRY(ap_alloc_graph(ix));
+    AP_TRY(seed_knn_impl(ix, nullptr, n, K, b.knn[0], b.knn_sc[0], st));
+    AP_CHECK_HIP(mark(2));
+    AP_TRY(ap_fill_u32(b.spi[0], (size_t)3 * n * P, 0xffffffffu, st));          // id -1
+    AP_TRY(ap_fill_u32(b.sps[0], (size_t)3 * n * P, 0xff800000u, st));          // -inf
+    int cur = 0;
+    for (int32_t t = 0; t < p.nd_rounds; t++) {
+        AP_TRY(ap_stage_refine(ix, K, p.nd_sample, P, b.knn[cur], b.spi[cur], b.sps[cur], nullptr, n, b.knn[1 - cur],
+                               b.knn_sc[1 - cur], b.spi[1 - cur], b.sps[1 - cur], st));
+        cur = 1 - cur;
+    }
+    if (p.nd_rounds == 0) {
+        AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim,
+                          hipLaunchKernelGGL((k_rescore_lists<DT, NV>), dim3((unsigned)n), dim3(256), 0, st, ix->docs,
+                                             p.build_w[0], p.build_w[1], p.build_w[2], K, b.knn[cur], b.knn_sc[cur]));
+        AP_CHECK_HIP(hipGetLastError());
+    }
+    AP_CHECK_HIP(mark(3));
+    AP_TRY(prune_impl(ix, K, R, b.knn[cur], b.knn_sc[cur], nullptr, n, nullptr, nullptr, b.sorted, b.se, ix->kw, ix->kw_count,
+                      nullptr, st));
+    AP_CHECK_HIP(mark(4));
+    AP_TRY(assemble_impl(ix, R, K, P, b.se, b.sorted, b.spi[cur], ix->graph, st));
+    AP_TRY(ap_stage_entry_points(ix, p.n_entry, ix->entry, st));
+    AP_CHECK_HIP(mark(5));
+    AP_CHECK_HIP(hipStreamSynchronize(st));
+    float total = 0.f;
+    for (int i = 0; i < 5; i++) {
+        float ms = 0.f;
+        AP_CHECK_HIP(hipEventElapsedTime(&ms, ev[i], ev[i + 1]));
+        ix->timings[i] = ms * 1e-3f;
+        total += ms * 1e-3f;
+    }
+    ix->timings[5] = total;
+    for (auto &e : ev) (void)hipEventDestroy(e);
+    ix->has_graph = true;
+    return AP_OK;
+}
+
+extern "C" int ap_build_index(const ap_corpus *corpus, const ap_build_params *params, void *stream, ap_index **out) {
+    AP_REQUIRE(out != nullptr, "out is NULL");
+    *out = nullptr;
+    AP_TRY(ap_validate_corpus(corpus));
+    AP_TRY(ap_validate_params(params));
+    AP_REQUIRE(corpus->n >= 2, "need at least two documents to build a graph");
+    ap_index *ix = new (std::nothrow) ap_index();
+    if (!ix) { ap_set_error("out of host memory"); return AP_ENOMEM; }
+    ix->corpus = *corpus;
+    ix->params = *params;
+    if (ix->params.sp_len == 0) ix->params.sp_len = (ix->params.degree + 5) / 6;
+    ix->dtype = corpus->dense_dtype;
+    BuildBufs b;
+    const int rc = build_impl(ix, (hipStream_t)stream, b);
+    (void)hipStreamSynchronize((hipStream_t)stream);
+    b.release();
+    if (rc != AP_OK) { ap_free_index(ix); return rc; }
+    *out = ix;
+    return AP_OK;
+}

@@ -1,0 +1,168 @@
+// Building blocks of the construction kernels: a 128x128 MFMA tile product of
+// gathered dense rows, an exact radix selection of the K best keys of a row,
+// and a bitonic sort of keys in LDS.
+#pragma once
+#include "ap_common.hpp"
+
+#ifdef __HIPCC__
+typedef float ap_f32x16 __attribute__((ext_vector_type(16)));
+
+#define AP_TILE 128
+#define AP_BK 32
+#define AP_LDS_STRIDE (AP_BK + 1)   // odd stride: the 32 rows read by one MFMA operand fall in distinct banks
+
+// Loads columns [k0, k0+32) of the 128 rows `rows[]` (row id -1 = zeros) into
+// lds[128][33] as f32.
+template <int DT>
+__device__ __forceinline__ void ap_tile_stage(const void *dense, int32_t dim, const int32_t *rows, int32_t k0, float *lds) {
+    const int t = threadIdx.x;
+#pragma unroll
+    for (int pass = 0; pass < 4; pass++) {
+        const int r = (t >> 3) + 32 * pass;
+        const int c = (t & 7) * 4;
+        const int32_t row = rows[r];
+        float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
+        if (row >= 0 && k0 + c < dim) {
+            if (DT == AP_F32) {
+                const float4 x = *reinterpret_cast<const float4 *>(static_cast<const float *>(dense) + (int64_t)row * dim + k0 + c);
+                v0 = x.x; v1 = x.y; v2 = x.z; v3 = x.w;
+            } else {
+                const uint2 x = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(dense) + (int64_t)row * dim + k0 + c);
+                v0 = __uint_as_float(x.x << 16); v1 = __uint_as_float(x.x & 0xffff0000u);
+                v2 = __uint_as_float(x.y << 16); v3 = __uint_as_float(x.y & 0xffff0000u);
+            }
+        }
+        float *d = lds + r * AP_LDS_STRIDE + c;
+        d[0] = v0; d[1] = v1; d[2] = v2; d[3] = v3;
+    }
+}
+
+// acc[a][b] (a, b in {0,1}) accumulate the 32x32 sub-tiles of this wave's
+// 64x64 quadrant: rows wm*64 + a*32 .., columns wn*64 + b*32 ..
+// C[i][j] = sum_k A[i][k] * B[j][k]   (both operands row-major: a Gram-type product).
+// v_mfma_f32_32x32x2_f32: lane l feeds A[l%32][l/32] and B[l/32][l%32]; the
+// result element (row, col) = (8*(r/4) + 4*(l/32) + r%4, l%32) sits in register r of lane l.
+template <int DT>
+__device__ __forceinline__ void ap_tile_gemm(const void *dense, int32_t dim, const int32_t *a_rows, const int32_t *b_rows,
+                                             float *lA, float *lB, ap_f32x16 acc[2][2]) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int li = lane & 31, lk = lane >> 5;
+#pragma unroll
+    for (int a = 0; a < 2; a++)
+#pragma unroll
+        for (int b = 0; b < 2; b++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) acc[a][b][r] = 0.f;
+    for (int32_t k0 = 0; k0 < dim; k0 += AP_BK) {
+        __syncthreads();
+        ap_tile_stage<DT>(dense, dim, a_rows, k0, lA);
+        ap_tile_stage<DT>(dense, dim, b_rows, k0, lB);
+        __syncthreads();
+        const float *pa0 = lA + (wm * 64 + li) * AP_LDS_STRIDE + lk;
+        const float *pa1 = pa0 + 32 * AP_LDS_STRIDE;
+        const float *pb0 = lB + (wn * 64 + li) * AP_LDS_STRIDE + lk;
+        const float *pb1 = pb0 + 32 * AP_LDS_STRIDE;
+#pragma unroll
+        for (int kk = 0; kk < AP_BK; kk += 2) {
+            const float a0 = pa0[kk], a1 = pa1[kk], b0 = pb0[kk], b1 = pb1[kk];
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+        }
+    }
+}
+
+// Calls f(i, j, value) for every element this lane holds of the 128x128 tile.
+template <typename F>
+__device__ __forceinline__ void ap_tile_foreach(const ap_f32x16 acc[2][2], F f) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+#pragma unroll
+    for (int a = 0; a < 2; a++)
+#pragma unroll
+        for (int b = 0; b < 2; b++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) {
+                const int i = wm * 64 + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                const int j = wn * 64 + b * 32 + (lane & 31);
+                f(i, j, acc[a][b][r]);
+            }
+}
+
+// Sorts keys[0..n) (n a power of two, <= 2*blockDim.x) in LDS, descending.
+__device__ __forceinline__ void ap_bitonic_desc(uint64_t *keys, int32_t n) {
+    for (int32_t size = 2; size <= n; size <<= 1)
+        for (int32_t stride = size >> 1; stride > 0; stride >>= 1) {
+            __syncthreads();
+            for (int32_t t = threadIdx.x; t < (n >> 1); t += blockDim.x) {
+                const int32_t lo = 2 * t - (t & (stride - 1));
+                const int32_t hi = lo + stride;
+                const bool desc = (lo & size) == 0;
+                const uint64_t x = keys[lo], y = keys[hi];
+                if ((x < y) == desc) { keys[lo] = y; keys[hi] = x; }
+            }
+        }
+    __syncthreads();
+}
+
+// Exact selection of the K largest keys among key(j) = ap_make_key(row[j], j)
+// for j in [0, n), j != exclude: radix selection on the 64-bit keys, eight
+// bits a pass from the top, stopping as soon as the digit bucket that holds
+// the K-th key is taken whole.  The selected keys land in sel[] (unordered);
+// returns their number (min(K, candidates)).  hist: 256 words of LDS.
+__device__ __forceinline__ int32_t ap_radix_select(const float *row, int64_t n, int32_t exclude, int32_t K,
+                                                   uint32_t *hist, uint64_t *sel, int32_t *s_misc /* 4 ints */,
+                                                   uint64_t *s_prefix /* 1 */) {
+    const int64_t valid = n - ((exclude >= 0 && exclude < n) ? 1 : 0);
+    int32_t krem = (int64_t)K < valid ? K : (int32_t)valid;
+    const int32_t ktotal = krem;
+    uint64_t prefix = 0, mask = 0;
+    if (ktotal > 0 && (int64_t)ktotal < valid) {
+        for (int pass = 0; pass < 8; pass++) {
+            const int shift = 56 - 8 * pass;
+            for (int i = threadIdx.x; i < 256; i += blockDim.x) hist[i] = 0;
+            __syncthreads();
+            for (int64_t j = threadIdx.x; j < n; j += blockDim.x) {
+                if (j == exclude) continue;
+                const uint64_t key = ap_make_key(row[j], (int32_t)j, 1u);
+                if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+            }
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                int32_t cum = 0, b = 255;
+                for (; b > 0; b--) {
+                    if (cum + (int32_t)hist[b] >= krem) break;
+                    cum += (int32_t)hist[b];
+                }
+                s_misc[0] = krem - cum;
+                s_misc[1] = ((int32_t)hist[b] == krem - cum) ? 1 : 0;
+                *s_prefix = prefix | ((uint64_t)b << shift);
+            }
+            __syncthreads();
+            krem = s_misc[0];
+            prefix = *s_prefix;
+            mask |= 0xffull << shift;
+            const int done = s_misc[1];
+            __syncthreads();
+            if (done) break;
+        }
+    }
+    if (threadIdx.x == 0) s_misc[2] = 0;
+    __syncthreads();
+    if (ktotal > 0) {
+        for (int64_t j = threadIdx.x; j < n; j += blockDim.x) {
+            if (j == exclude) continue;
+            const uint64_t key = ap_make_key(row[j], (int32_t)j, 1u);
+            if ((key & mask) >= prefix) {
+                const int32_t pos = atomicAdd(&s_misc[2], 1);
+                if (pos < ktotal) sel[pos] = key;
+            }
+        }
+    }
+    __syncthreads();
+    return ktotal;
+}
+
+#endif
