@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Benchmark of the hybrid-index hot path on one MI355X.
+
+One "step" = one batched search (S7-S9) of all queries of the workload on an
+index that this same run built on the GPU (S0-S6; build time reported beside
+it).  The headline value is queries per second at the smallest beam whose
+recall@10 against exact hybrid top-10 reaches 0.95.  Inputs are seeded
+synthetic data resident in HBM before the timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E data-sheet peak
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def recall_at_k(ids, gt):
+    import numpy as np
+    return float(np.mean([len(set(a.tolist()) & set(b.tolist())) / float(len(b)) for a, b in zip(ids, gt)]))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="cfg2", help="cfg2 (default), tiny, cfg3")
+    ap.add_argument("--n", type=int, default=None, help="override the number of documents (smaller rehearsal)")
+    ap.add_argument("--nq", type=int, default=None)
+    ap.add_argument("--rounds", type=int, default=3)
+    ap.add_argument("--beams", default="128,256,512,1024,1536,2048,3072,4096")
+    ap.add_argument("--beam", type=int, default=0, help="fix the beam (skips the sweep; for profiling runs)")
+    ap.add_argument("--target-recall", type=float, default=0.95)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a 1 GiB plain copy kernel (yardstick for profiler byte counters)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing leg")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2511_00855_amd import binding as B
+    from paper_2511_00855_amd.synth import make_workload
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    B.lib()   # fail loudly if the HIP library is not built
+
+    t0 = time.time()
+    w = make_workload(args.workload, seed=0, n=args.n, nq=args.nq)
+    cfg = w.extra["config"]
+    bf16 = bool(cfg["bf16"])
+    log(f"[bench] workload {args.workload}: n={w.docs.n} nq={w.queries.n} dim={w.docs.dim} bf16={bf16} "
+        f"generated in {time.time() - t0:.1f}s")
+    docs = B.DeviceVecs(w.docs, "cuda:0", bf16=bf16)
+    qs = B.DeviceVecs(w.queries, "cuda:0")
+    nq, k = qs.n, w.k
+    wq = torch.from_numpy(np.tile(np.float32(w.weights), (nq, 1))).to("cuda:0")
+    torch.cuda.synchronize()
+
+    if args.calibrate_copy:
+        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").normal_()
+        b = torch.empty_like(a)
+        for _ in range(3):
+            B.calibration_copy(b, a)
+        torch.cuda.synchronize()
+        del a, b
+
+    # ---- build on the GPU (S0-S6), timed to stream sync with data resident
+    bp = B.build_params(w.degree, nd_rounds=args.rounds)
+    t0 = time.time()
+    ix = B.Index.build(docs, bp)
+    torch.cuda.synchronize()
+    build_s = time.time() - t0
+    bt = ix.build_timings()
+    log(f"[bench] build {build_s:.2f}s stages {bt}")
+
+    # ---- ground truth: exact hybrid top-k under the same weights
+    t0 = time.time()
+    gt, _ = ix.bruteforce_topk(qs, k, wq)
+    torch.cuda.synchronize()
+    gt = gt.cpu().numpy()
+    log(f"[bench] exhaustive top-{k} of {nq} queries: {time.time() - t0:.2f}s")
+
+    # ---- beam sweep: nominal beam, then upward until the recall target
+    def run_once(beam):
+        ids, sc = ix.search_batch(qs, k, beam, wq)
+        return ids
+
+    sweep = []
+    chosen = None
+    beams = [args.beam] if args.beam else sorted(set(int(b) for b in args.beams.split(",")) | {w.beam})
+    for beam in beams:
+        ids = run_once(beam)
+        torch.cuda.synchronize()
+        t1 = time.time()
+        ids = run_once(beam)
+        torch.cuda.synchronize()
+        dt = time.time() - t1
+        rec = recall_at_k(ids.cpu().numpy(), gt)
+        counts, kms = ix.search_stats(nq)
+        nd = int(counts[:, 0].sum().item())
+        sweep.append(dict(beam=beam, recall=round(rec, 4), qps=round(nq / dt, 1), kernel_ms=round(kms, 3),
+                          dists_per_query=round(nd / nq, 1)))
+        log(f"[bench] beam {beam}: recall@{k} {rec:.4f}  {nq / dt:,.0f} qps  kernel {kms:.2f} ms  {nd / nq:.0f} dists/query")
+        if chosen is None and rec >= args.target_recall:
+            chosen = beam
+        if chosen is not None and beam >= w.beam:
+            break
+    reached = chosen is not None
+    if chosen is None:
+        chosen = beams[-1]
+
+    # ---- timed region: exactly `steps` searches at the chosen beam
+    out = (torch.empty((nq, k), dtype=torch.int32, device="cuda:0"), torch.empty((nq, k), dtype=torch.float32, device="cuda:0"))
+    for _ in range(args.warmup):
+        ix.search_batch(qs, k, chosen, wq, out=out)
+    torch.cuda.synchronize()
+    kernel_ms = []
+    t1 = time.time()
+    for _ in range(args.steps):
+        ix.search_batch(qs, k, chosen, wq, out=out)
+        kernel_ms.append(ix.search_kernel_ms())   # events recorded around the kernel on its own stream
+    torch.cuda.synchronize()
+    elapsed = time.time() - t1
+    ms_per_step = elapsed * 1e3 / args.steps
+    qps = nq * args.steps / elapsed
+    rec = recall_at_k(out[0].cpu().numpy(), gt)
+    counts, _ = ix.search_stats(nq)
+    counts = counts.cpu().numpy().astype(np.int64)
+    n_dist, n_iter = int(counts[:, 0].sum()), int(counts[:, 1].sum())
+
+    # ---- roofline of the search kernel: algorithmic bytes / measured kernel time
+    sp_nnz = float(w.docs.sp_indptr[-1]) / w.docs.n
+    tx_nnz = float(w.docs.tx_indptr[-1]) / w.docs.n
+    bytes_per_dist = w.docs.dim * (2 if bf16 else 4) + 8.0 * sp_nnz + 8.0 * tx_nnz + 32.0   # rows + 4 offsets
+    bytes_per_launch = n_dist * bytes_per_dist + n_iter * w.degree * 4.0
+    k_ms = float(np.mean(kernel_ms))
+    achieved = bytes_per_launch / (k_ms * 1e-3) / 1e9
+    roofline = dict(bound="hbm", kernel="k_search", achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None, kernel_ms=round(k_ms, 3),
+                    bytes_per_dist=round(bytes_per_dist, 1), dists_per_launch=n_dist,
+                    dists_per_s=round(n_dist / (k_ms * 1e-3), 1))
+
+    # ---- CPU baseline: the oracle as it stands, one thread, bounded sample of the same searches
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle as O
+        sem, _, _, ent = [t.cpu().numpy() for t in ix.export_graph()]
+        D = O.encode_docs(w.docs)
+        Q = O.VS(w.queries)
+        t2 = time.time()
+        O.search(D, sem, ent, Q, 0, w.weights, k, chosen)
+        per_q = max(time.time() - t2, 1e-4)
+        sample = int(max(4, min(nq, args.cpu_seconds / per_q)))
+        t2 = time.time()
+        oi, _, nv = O.search_batch(D, sem, ent, Q, range(sample), w.weights, k, chosen)
+        dt = time.time() - t2
+        agree = recall_at_k(out[0].cpu().numpy()[:sample], oi)
+        cpu = dict(value=round(sample / dt, 2), unit="queries/s", cores=1, kind="oracle",
+                   sample=f"first {sample} of {nq} queries, beam {chosen}, same GPU-built graph; "
+                          f"{int(nv.sum())} hybrid similarities in {dt:.1f}s; top-{k} overlap with GPU {agree:.3f}")
+        log(f"[bench] oracle: {sample} queries in {dt:.1f}s = {sample / dt:.1f} qps on 1 core ({os.cpu_count()} visible)")
+
+    line = {
+        "metric": "hybrid-search QPS at recall@10=0.95", "value": round(qps, 1), "unit": "queries/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16-storage/f32-accumulate" if bf16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: N={w.docs.n} docs, dense d={w.docs.dim} {'bf16' if bf16 else 'f32'}, "
+                               f"sparse ~{sp_nnz:.0f} nnz/doc, text ~{tx_nnz:.0f} distinct terms/doc, {nq} queries, "
+                               f"weights {tuple(w.weights)}, degree {w.degree}, k={k}",
+                   "beam": chosen, "recall_at_10": round(rec, 4), "recall_target_reached": reached,
+                   "nominal_beam": w.beam, "refine_rounds": args.rounds},
+        "build_s": round(build_s, 3), "build_stages_s": {a: round(b, 3) for a, b in bt.items()},
+        "hybrid_dists_per_s": roofline["dists_per_s"], "beam_sweep": sweep,
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+    ix.close()
+
+
+if __name__ == "__main__":
+    main()

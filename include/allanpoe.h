@@ -92,7 +92,7 @@ typedef struct {
 
 typedef struct {
     int32_t k;            /* results per query; k <= beam */
-    int32_t beam;         /* L: candidate pool capacity; <= 1024 */
+    int32_t beam;         /* L: candidate pool capacity; <= 4096 */
     int32_t max_iters;    /* 0 = until the pool is fully expanded */
     int32_t search_width; /* p: pool entries expanded per iteration; 1..8 */
 } ap_search_params;
@@ -181,6 +181,18 @@ int ap_export_graph(const ap_index *index, int32_t *semantic, int32_t *keyword, 
 int ap_import_graph(const ap_corpus *corpus, const ap_build_params *params, const int32_t *semantic,
                     const int32_t *keyword, const int32_t *kw_count, const int32_t *entry, void *stream,
                     ap_index **out);
+
+/* Counters of the last ap_search_batch on this index (synchronises on that
+ * search).  out_counts (device, may be NULL): nq x 2 int32 = per query the
+ * number of hybrid similarities evaluated and the number of iterations.
+ * kernel_ms (host, may be NULL): duration of the search kernel alone, measured
+ * with events on the stream it ran on. */
+int ap_search_stats(const ap_index *index, int32_t *out_counts, int32_t nq, float *kernel_ms, void *stream);
+
+/* Measurement aid: a plain streaming copy kernel (reads and writes `bytes`
+ * bytes once each; 16-byte aligned device buffers, bytes % 16 == 0).  Profiler
+ * byte counters are scaled by what they report for this copy of known size. */
+int ap_calibration_copy(void *dst, const void *src, size_t bytes, void *stream);
 
 /* Timings of the last ap_build_index on this index, host floats in seconds:
  * [0] ingest, [1] seed, [2] refinement, [3] prune, [4] assemble+entry, [5] total. */

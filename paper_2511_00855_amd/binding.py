@@ -86,6 +86,14 @@ def _ids(a, device):
     return _dev(np.asarray(a, dtype=np.int32) if not isinstance(a, torch.Tensor) else a, torch.int32, device)
 
 
+def calibration_copy(dst: torch.Tensor, src: torch.Tensor):
+    """Plain copy kernel of known size (see ap_calibration_copy)."""
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    with torch.cuda.device(src.device):
+        _check(lib().ap_calibration_copy(_ptr(dst), _ptr(src), C.c_size_t(nbytes), _stream()), "ap_calibration_copy")
+
+
 class DeviceVecs:
     """Device copies of a vector set (documents or queries)."""
 
@@ -315,6 +323,19 @@ class Index:
         with torch.cuda.device(dev):
             _check(lib().ap_export_graph(self._h, _ptr(sem), _ptr(kw), _ptr(kc), _ptr(ent), _stream()), "ap_export_graph")
         return sem, kw, kc, ent
+
+    def search_stats(self, nq: int):
+        """(counts[nq, 2] = similarities evaluated and iterations per query, search-kernel ms) of the last search."""
+        counts = torch.empty((nq, 2), dtype=torch.int32, device=self.device)
+        ms = C.c_float(0)
+        with torch.cuda.device(self.device):
+            _check(lib().ap_search_stats(self._h, _ptr(counts), C.c_int32(nq), C.byref(ms), _stream()), "ap_search_stats")
+        return counts, float(ms.value)
+
+    def search_kernel_ms(self) -> float:
+        ms = C.c_float(0)
+        _check(lib().ap_search_stats(self._h, None, C.c_int32(0), C.byref(ms), None), "ap_search_stats")
+        return float(ms.value)
 
     def build_timings(self):
         out = (C.c_float * 6)()

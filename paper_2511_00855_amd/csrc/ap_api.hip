@@ -183,8 +183,10 @@ extern "C" int ap_ingest(const ap_corpus *corpus, const ap_build_params *params,
 
 extern "C" void ap_free_index(ap_index *ix) {
     if (!ix) return;
-    void *ptrs[] = {ix->tx_w, ix->df, ix->stats, ix->self_sim, ix->graph, ix->kw, ix->kw_count, ix->entry, ix->visited, ix->w_dev};
+    void *ptrs[] = {ix->tx_w, ix->df, ix->stats, ix->self_sim, ix->graph, ix->kw, ix->kw_count, ix->entry, ix->visited, ix->w_dev,
+                    ix->search_counts};
     for (void *p : ptrs) if (p) (void)hipFree(p);
+    for (hipEvent_t e : ix->ev_search) if (e) (void)hipEventDestroy(e);
     delete ix;
 }
 
@@ -251,6 +253,19 @@ extern "C" int ap_export_graph(const ap_index *ix, int32_t *semantic, int32_t *k
     if (keyword) AP_CHECK_HIP(hipMemcpyAsync(keyword, ix->kw, n * (R / 2) * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
     if (kw_count) AP_CHECK_HIP(hipMemcpyAsync(kw_count, ix->kw_count, n * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
     if (entry) AP_CHECK_HIP(hipMemcpyAsync(entry, ix->entry, (size_t)ix->params.n_entry * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
+    return AP_OK;
+}
+
+// A plain streaming copy of known size: the yardstick the HBM byte counters are scaled by.
+__global__ void k_copy_u128(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n) {
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) dst[i] = src[i];
+}
+
+extern "C" int ap_calibration_copy(void *dst, const void *src, size_t bytes, void *stream) {
+    AP_REQUIRE(dst && src && bytes % 16 == 0 && (((uintptr_t)dst | (uintptr_t)src) & 15) == 0, "need 16-byte aligned buffers and size");
+    if (bytes == 0) return AP_OK;
+    hipLaunchKernelGGL(k_copy_u128, dim3(8192), dim3(256), 0, (hipStream_t)stream, (const uint4 *)src, (uint4 *)dst, bytes / 16);
+    AP_CHECK_HIP(hipGetLastError());
     return AP_OK;
 }
 

@@ -72,6 +72,10 @@ struct ap_index {
     uint32_t *visited = nullptr;
     size_t visited_words = 0;
     float *w_dev = nullptr;    // 3 floats: device copy of w_default
+    int32_t *search_counts = nullptr;  // nq x 2 of the last search: similarities evaluated, iterations
+    size_t search_counts_cap = 0;
+    int32_t last_nq = 0;
+    hipEvent_t ev_search[2] = {nullptr, nullptr};
     float timings[6] = {0, 0, 0, 0, 0, 0};
 };
 
@@ -168,51 +172,133 @@ __device__ __forceinline__ float ap_wave_sum(float v) {
     return v;
 }
 
+#define AP_LDS __attribute__((address_space(3)))
+
+// Largest power of two <= n (0 for n <= 0): first stride of the halving search below.
+__device__ __forceinline__ int32_t ap_pow2_floor(int32_t n) { return n > 0 ? (1 << (31 - __clz(n))) : 0; }
+
+// If term t occurs in the ascending list a (a_n entries), adds a_val * v to p.
+// The lower bound is found with a fixed, wave-uniform number of halving steps
+// (no divergence); t = -1 never matches.  IP / VP are pointer types so that a
+// list in LDS is read with ds_read and one in global memory with global loads.
+template <typename IP, typename VP>
+__device__ __forceinline__ float ap_match_fma(IP a_idx, VP a_val, int32_t a_n, int32_t step0, int32_t t, float v, float p) {
+    int32_t pos = 0;
+    for (int32_t st = step0; st > 0; st >>= 1) {
+        const int32_t p2 = pos + st;
+        if (p2 <= a_n && a_idx[p2 - 1] < t) pos = p2;
+    }
+    if (pos < a_n && a_idx[pos] == t) p = fmaf(a_val[pos], v, p);
+    return p;
+}
+
 // Partial inner product of an ascending list held by the a side with the
 // b side's list [beg, end) in global memory: lane l takes entries
-// beg+l, beg+l+64, ... of b and binary-searches a (Section 4.1, Step 1).
-__device__ __forceinline__ float ap_sparse_partial(const int32_t *a_idx, const float *a_val, int32_t a_n,
-                                                   const int32_t *b_idx, const float *b_val, int64_t beg,
-                                                   int64_t end, int lane) {
+// beg+l, beg+l+64, ... of b and searches a (Section 4.1, Step 1; on the search
+// side the document's entries are looked up in the short query list,
+// Section 4.2.1).
+template <typename IP, typename VP>
+__device__ __forceinline__ float ap_sparse_partial(IP a_idx, VP a_val, int32_t a_n, const int32_t *b_idx,
+                                                   const float *b_val, int64_t beg, int64_t end, int lane) {
     float p = 0.f;
-    for (int64_t e = beg + lane; e < end; e += 64) {
-        const int32_t t = b_idx[e];
-        const float v = b_val[e];
-        int32_t lo = 0, hi = a_n;
-        while (lo < hi) {
-            const int32_t mid = (lo + hi) >> 1;
-            if (a_idx[mid] < t) lo = mid + 1; else hi = mid;
-        }
-        if (lo < a_n && a_idx[lo] == t) p = fmaf(a_val[lo], v, p);
+    const int32_t step0 = ap_pow2_floor(a_n);
+    for (int64_t e0 = beg; e0 < end; e0 += 64) {
+        const int64_t e = e0 + lane;
+        const int32_t t = e < end ? b_idx[e] : -1;
+        const float v = e < end ? b_val[e] : 0.f;
+        p = ap_match_fma(a_idx, a_val, a_n, step0, t, v, p);
     }
     return p;
 }
 
-// Hybrid similarity of the a side with row j of B (Definition 1).  All 64
-// lanes of the wave take part and all return the same three sums.
+// Hybrid similarity (Definition 1) of the a side with up to G rows of B at
+// once.  All 64 lanes of the wave take part; the loads of all G rows are
+// issued before any of them is consumed, so that G rows are in flight per
+// wave.  Row g has its sparse list at [spb[g], spb[g]+spn[g]) and its lexical
+// list at [txb[g], txb[g]+txn[g]).  SS / TS are the numbers of 64-entry slots
+// of the sparse / lexical list that are prefetched into registers; longer
+// lists continue with a plain loop.  Every lane returns the same three sums
+// per row, and the sums are bit-identical for any G, SS, TS and pointer kind:
+// lane l always accumulates entries l, l+64, ... in that order.
+template <int DT, int NV, int G, int SS, int TS, typename IP, typename VP>
+__device__ __forceinline__ void ap_hybrid_batch(const ApVecs &B, const float *qa, IP a_sp_idx, VP a_sp_val, int32_t a_sp_n,
+                                                IP a_tx_idx, VP a_tx_val, int32_t a_tx_n, int32_t ng, const int32_t *v,
+                                                const int64_t *spb, const int32_t *spn, const int64_t *txb,
+                                                const int32_t *txn, float *sd, float *ss, float *sf) {
+    constexpr int EPC = ApDense<DT>::EPC;
+    const int lane = threadIdx.x & 63;
+    float d[G][NV * EPC];
+    int32_t si[G][SS], ti[G][TS];
+    float sv[G][SS], tv[G][TS];
+#pragma unroll
+    for (int g = 0; g < G; g++) {
+        if (g < ng) {
+#pragma unroll
+            for (int i = 0; i < NV; i++) {
+                const int col = (i * 64 + lane) * EPC;
+                if (col < B.dim) ApDense<DT>::load(B.dense, v[g], B.dim, col, d[g] + i * EPC);
+            }
+#pragma unroll
+            for (int k = 0; k < SS; k++) {
+                const int32_t e = k * 64 + lane;
+                si[g][k] = e < spn[g] ? B.sp_idx[spb[g] + e] : -1;
+                sv[g][k] = e < spn[g] ? B.sp_val[spb[g] + e] : 0.f;
+            }
+#pragma unroll
+            for (int k = 0; k < TS; k++) {
+                const int32_t e = k * 64 + lane;
+                ti[g][k] = e < txn[g] ? B.tx_idx[txb[g] + e] : -1;
+                tv[g][k] = e < txn[g] ? B.tx_val[txb[g] + e] : 0.f;
+            }
+        }
+    }
+    const int32_t sp_step = ap_pow2_floor(a_sp_n), tx_step = ap_pow2_floor(a_tx_n);
+#pragma unroll
+    for (int g = 0; g < G; g++) {
+        if (g < ng) {
+            float pd = 0.f, ps = 0.f, pf = 0.f;
+#pragma unroll
+            for (int i = 0; i < NV; i++) {
+                const int col = (i * 64 + lane) * EPC;
+                if (col < B.dim) {
+#pragma unroll
+                    for (int e = 0; e < EPC; e++) pd = fmaf(qa[i * EPC + e], d[g][i * EPC + e], pd);
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < SS; k++)
+                if (k * 64 < spn[g]) ps = ap_match_fma(a_sp_idx, a_sp_val, a_sp_n, sp_step, si[g][k], sv[g][k], ps);
+            for (int32_t e0 = SS * 64; e0 < spn[g]; e0 += 64) {
+                const int32_t e = e0 + lane;
+                const int32_t t = e < spn[g] ? B.sp_idx[spb[g] + e] : -1;
+                const float x = e < spn[g] ? B.sp_val[spb[g] + e] : 0.f;
+                ps = ap_match_fma(a_sp_idx, a_sp_val, a_sp_n, sp_step, t, x, ps);
+            }
+#pragma unroll
+            for (int k = 0; k < TS; k++)
+                if (k * 64 < txn[g]) pf = ap_match_fma(a_tx_idx, a_tx_val, a_tx_n, tx_step, ti[g][k], tv[g][k], pf);
+            for (int32_t e0 = TS * 64; e0 < txn[g]; e0 += 64) {
+                const int32_t e = e0 + lane;
+                const int32_t t = e < txn[g] ? B.tx_idx[txb[g] + e] : -1;
+                const float x = e < txn[g] ? B.tx_val[txb[g] + e] : 0.f;
+                pf = ap_match_fma(a_tx_idx, a_tx_val, a_tx_n, tx_step, t, x, pf);
+            }
+            sd[g] = ap_wave_sum(pd);
+            ss[g] = ap_wave_sum(ps);
+            sf[g] = ap_wave_sum(pf);
+        }
+    }
+}
+
+// One row: the same arithmetic as the batch form.
 template <int DT, int NV>
 __device__ __forceinline__ void ap_hybrid_wave(const ApVecs &B, const float *qa, const ApLists &a, int64_t j,
                                                float &sd, float &ss, float &sf) {
-    constexpr int EPC = ApDense<DT>::EPC;
-    const int lane = threadIdx.x & 63;
-    float pd = 0.f;
-#pragma unroll
-    for (int i = 0; i < NV; i++) {
-        const int col = (i * 64 + lane) * EPC;
-        if (col < B.dim) {
-            float d[EPC];
-            ApDense<DT>::load(B.dense, j, B.dim, col, d);
-#pragma unroll
-            for (int e = 0; e < EPC; e++) pd = fmaf(qa[i * EPC + e], d[e], pd);
-        }
-    }
-    const float ps = ap_sparse_partial(a.sp_idx, a.sp_val, a.sp_n, B.sp_idx, B.sp_val, B.sp_indptr[j],
-                                       B.sp_indptr[j + 1], lane);
-    const float pf = ap_sparse_partial(a.tx_idx, a.tx_val, a.tx_n, B.tx_idx, B.tx_val, B.tx_indptr[j],
-                                       B.tx_indptr[j + 1], lane);
-    sd = ap_wave_sum(pd);
-    ss = ap_wave_sum(ps);
-    sf = ap_wave_sum(pf);
+    const int32_t v = (int32_t)j;
+    const int64_t spb = B.sp_indptr[j], txb = B.tx_indptr[j];
+    const int32_t spn = (int32_t)(B.sp_indptr[j + 1] - spb), txn = (int32_t)(B.tx_indptr[j + 1] - txb);
+    ap_hybrid_batch<DT, NV, 1, 2, 1>(B, qa, a.sp_idx, a.sp_val, a.sp_n, a.tx_idx, a.tx_val, a.tx_n, 1, &v, &spb, &spn, &txb,
+                                     &txn, &sd, &ss, &sf);
 }
 
 __device__ __forceinline__ float ap_fuse(float wd, float ws, float wf, float sd, float ss, float sf) {
