@@ -145,7 +145,7 @@ __device__ __forceinline__ uint64_t ap_block_max(uint64_t v, uint64_t *red /* 8 
 }
 
 template <int DT, int NV>
-__global__ __launch_bounds__(256) void k_refine(ApVecs D, float wd, float ws, float wf, int32_t K, int32_t S, int32_t P,
+__global__ __launch_bounds__(512) void k_refine(ApVecs D, float wd, float ws, float wf, int32_t K, int32_t S, int32_t P,
                                                 const int32_t *__restrict__ knn, const int32_t *__restrict__ sp_ids,
                                                 const float *__restrict__ sp_sc, const int32_t *__restrict__ node_ids,
                                                 int64_t nn, int32_t *__restrict__ out_ids, float *__restrict__ out_sc,
@@ -183,7 +183,7 @@ __global__ __launch_bounds__(256) void k_refine(ApVecs D, float wd, float ws, fl
     }
     __syncthreads();
     const int32_t cnt = s_cnt;
-    for (int32_t i = wave; i < cnt; i += 4) {
+    for (int32_t i = wave; i < cnt; i += (int32_t)(blockDim.x >> 6)) {
         const int32_t v = cand[i];
         float sd, ss, sf;
         ap_hybrid_wave<DT, NV>(D, qa, a, v, sd, ss, sf);
@@ -240,7 +240,7 @@ extern "C" int ap_stage_refine(const ap_index *ix, int32_t K, int32_t S, int32_t
     if (nn <= 0) return AP_OK;
     const float *w = ix->params.build_w;
     AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim,
-                      hipLaunchKernelGGL((k_refine<DT, NV>), dim3((unsigned)nn), dim3(256), 0, (hipStream_t)stream, ix->docs,
+                      hipLaunchKernelGGL((k_refine<DT, NV>), dim3((unsigned)nn), dim3(512), 0, (hipStream_t)stream, ix->docs,
                                          w[0], w[1], w[2], K, S, P, knn_ids, sp_ids, sp_sc, node_ids, nn, out_ids, out_sc,
                                          out_sp_ids, out_sp_sc));
     AP_CHECK_HIP(hipGetLastError());
@@ -273,11 +273,89 @@ __global__ __launch_bounds__(256) void k_gram_dense(const void *dense, int32_t d
 }
 
 // Sparse and lexical parts, and the fusion: one block per (neighbourhood,
-// block of CB columns).  The CB column documents' lists sit in LDS; each wave
-// walks the rows, staging the row document's lists in its own LDS slice.
+// block of CB columns).  The CB column documents' lists sit in LDS.  Each wave
+// walks the rows at or below the block's first column (the matrix is
+// symmetric: P[i][j] is computed once, for i >= j, and mirrored), and for its
+// current row builds two small open-addressing tables (term -> weight) in its
+// own LDS slice, so that looking a column entry up costs about one LDS probe
+// instead of a binary search.  A lane's partial sum is w_s*ps + w_f*pf, so one
+// wave reduction per pair suffices.
 #define AP_CB 32
 #define AP_CB_ENTRIES 5632
-#define AP_W_CAP 256
+#define AP_SP_SLOTS 512     // sparse table slots per wave (row lists up to 256 entries)
+#define AP_TX_SLOTS 256     // lexical table slots per wave (row lists up to 128 entries)
+
+__device__ __forceinline__ uint32_t ap_term_hash(int32_t t, int bits) { return ((uint32_t)t * 2654435761u) >> (32 - bits); }
+
+// Fills an empty table (all terms -1) with the list [g0, g0+n) of global memory.
+__device__ __forceinline__ void ap_table_build(int2 *tab, int slots, int bits, const int32_t *gi, const float *gv, int64_t g0,
+                                               int32_t n, int lane) {
+    for (int i = lane; i < slots; i += 64) tab[i] = make_int2(-1, 0);
+    __builtin_amdgcn_wave_barrier();
+    for (int32_t e = lane; e < n; e += 64) {
+        const int32_t t = gi[g0 + e];
+        const int32_t vb = __float_as_int(gv[g0 + e]);
+        uint32_t h = ap_term_hash(t, bits);
+        for (;;) {
+            const int32_t old = atomicCAS(&tab[h].x, -1, t);
+            if (old == -1) { tab[h].y = vb; break; }
+            h = (h + 1) & (slots - 1);
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+}
+
+// Weight of term t in the table, 0 if absent (t = -1 is never present).  A
+// slot is read as one 64-bit word: term in the low half, weight bits in the high half.
+template <typename TP>
+__device__ __forceinline__ float ap_table_get(TP tab, int slots, int bits, int32_t t) {
+    uint32_t h = ap_term_hash(t, bits);
+    for (;;) {
+        const uint64_t e = tab[h];
+        const int32_t et = (int32_t)(uint32_t)e;
+        if (et == t) return __uint_as_float((uint32_t)(e >> 32));
+        if (et == -1) return 0.f;
+        h = (h + 1) & (slots - 1);
+    }
+}
+
+// NL look-ups at once: every round issues the LDS reads of all look-ups that
+// are still probing, so their latencies overlap; the number of rounds is the
+// longest probe sequence among them (linear probing, tables at most half full).
+// val[k] = weight of term[k] in its table (look-ups k < NSP use the sparse one).
+template <int NL, int NSP>
+__device__ __forceinline__ void ap_table_get_many(const AP_LDS uint64_t *tsp, const AP_LDS uint64_t *ttx, const int32_t *term,
+                                                  float *val) {
+    uint32_t h[NL];
+    bool pend[NL];
+    bool any = false;
+#pragma unroll
+    for (int k = 0; k < NL; k++) {
+        h[k] = ap_term_hash(term[k], k < NSP ? 9 : 8);
+        val[k] = 0.f;
+        pend[k] = term[k] >= 0;
+        any = any || pend[k];
+    }
+    while (__any(any)) {
+        uint64_t e[NL];
+#pragma unroll
+        for (int k = 0; k < NL; k++) {
+            e[k] = 0xffffffffull;
+            if (pend[k]) { if (k < NSP) e[k] = tsp[h[k]]; else e[k] = ttx[h[k]]; }
+        }
+        any = false;
+#pragma unroll
+        for (int k = 0; k < NL; k++) {
+            if (pend[k]) {
+                const int32_t et = (int32_t)(uint32_t)e[k];
+                if (et == term[k]) { val[k] = __uint_as_float((uint32_t)(e[k] >> 32)); pend[k] = false; }
+                else if (et == -1) pend[k] = false;
+                else h[k] = (h[k] + 1) & ((k < NSP ? AP_SP_SLOTS : AP_TX_SLOTS) - 1);
+            }
+            any = any || pend[k];
+        }
+    }
+}
 
 template <int DT>
 __global__ __launch_bounds__(256) void k_gram_sparse(ApVecs D, float wd, float ws, float wf, int32_t K,
@@ -288,26 +366,27 @@ __global__ __launch_bounds__(256) void k_gram_sparse(ApVecs D, float wd, float w
     __shared__ int32_t b_off[2][AP_CB + 1];       // offsets into b_idx/b_val, or -1 when the list stayed in global memory
     __shared__ int32_t b_len[2][AP_CB];
     __shared__ int32_t b_id[AP_CB];
-    __shared__ int32_t w_idx[4][2][AP_W_CAP];
-    __shared__ float w_val[4][2][AP_W_CAP];
+    __shared__ int2 t_sp[4][AP_SP_SLOTS];
+    __shared__ int2 t_tx[4][AP_TX_SLOTS];
     const int64_t x = blockIdx.y;
     const int64_t u = node_ids ? (int64_t)node_ids[x0 + x] : x0 + x;
     const int32_t j0 = blockIdx.x * AP_CB;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    // plan the LDS layout of the column lists (thread 0), then copy cooperatively
-    if (threadIdx.x == 0) {
-        int32_t used = 0;
-        for (int c = 0; c < AP_CB; c++) {
-            const int32_t v = j0 + c < K ? knn[u * K + j0 + c] : -1;
-            b_id[c] = v;
-            for (int part = 0; part < 2; part++) {
-                int32_t len = 0;
-                if (v >= 0) len = (int32_t)(part == 0 ? D.sp_indptr[v + 1] - D.sp_indptr[v] : D.tx_indptr[v + 1] - D.tx_indptr[v]);
-                b_len[part][c] = len;
-                if (used + len <= AP_CB_ENTRIES) { b_off[part][c] = used; used += len; }
-                else b_off[part][c] = -1;
-            }
+    // plan the LDS layout of the column lists: lane 2c+part of wave 0 owns list `part` of column c;
+    // offsets are an exclusive prefix sum of the lengths, lists past the capacity stay in global memory
+    if (wave == 0) {
+        const int c = lane >> 1, part = lane & 1;
+        const int32_t v = j0 + c < K ? knn[u * K + j0 + c] : -1;
+        int32_t len = 0;
+        if (v >= 0) len = (int32_t)(part == 0 ? D.sp_indptr[v + 1] - D.sp_indptr[v] : D.tx_indptr[v + 1] - D.tx_indptr[v]);
+        int32_t incl = len;
+        for (int o = 1; o < 64; o <<= 1) {
+            const int32_t up = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += up;
         }
+        if (part == 0) b_id[c] = v;
+        b_len[part][c] = len;
+        b_off[part][c] = incl <= AP_CB_ENTRIES ? incl - len : -1;
     }
     __syncthreads();
     for (int c = 0; c < AP_CB; c++) {
@@ -324,44 +403,108 @@ __global__ __launch_bounds__(256) void k_gram_sparse(ApVecs D, float wd, float w
     }
     __syncthreads();
     float *out = pm + x * (int64_t)K * K;
-    for (int32_t i = wave; i < K; i += 4) {
+    for (int32_t i = j0 + wave; i < K; i += 4) {
         const int32_t a = knn[u * K + i];
-        // this wave's row lists (LDS slice if short enough, else global)
-        const int32_t *ai[2]; const float *av[2]; int32_t an[2];
+        int32_t an_sp = 0, an_tx = 0;
+        int64_t a_sp0 = 0, a_tx0 = 0;
+        bool tab_sp = false, tab_tx = false;
         if (a >= 0) {
-            for (int part = 0; part < 2; part++) {
-                const int64_t g0 = part == 0 ? D.sp_indptr[a] : D.tx_indptr[a];
-                const int64_t g1 = part == 0 ? D.sp_indptr[a + 1] : D.tx_indptr[a + 1];
-                const int32_t *gi = part == 0 ? D.sp_idx : D.tx_idx;
-                const float *gv = part == 0 ? D.sp_val : D.tx_val;
-                an[part] = (int32_t)(g1 - g0);
-                if (an[part] <= AP_W_CAP) {
-                    for (int32_t e = lane; e < an[part]; e += 64) { w_idx[wave][part][e] = gi[g0 + e]; w_val[wave][part][e] = gv[g0 + e]; }
-                    ai[part] = w_idx[wave][part]; av[part] = w_val[wave][part];
-                } else { ai[part] = gi + g0; av[part] = gv + g0; }
-            }
+            a_sp0 = D.sp_indptr[a]; an_sp = (int32_t)(D.sp_indptr[a + 1] - a_sp0);
+            a_tx0 = D.tx_indptr[a]; an_tx = (int32_t)(D.tx_indptr[a + 1] - a_tx0);
+            tab_sp = an_sp <= AP_SP_SLOTS / 2;
+            tab_tx = an_tx <= AP_TX_SLOTS / 2;
+            if (tab_sp) ap_table_build(t_sp[wave], AP_SP_SLOTS, 9, D.sp_idx, D.sp_val, a_sp0, an_sp, lane);
+            if (tab_tx) ap_table_build(t_tx[wave], AP_TX_SLOTS, 8, D.tx_idx, D.tx_val, a_tx0, an_tx, lane);
         }
-        __builtin_amdgcn_wave_barrier();
-        for (int c = 0; c < AP_CB && j0 + c < K; c++) {
-            const int32_t b = b_id[c];
-            float val = -INFINITY;
-            if (a >= 0 && b >= 0) {
-                float part_sum[2];
-                for (int part = 0; part < 2; part++) {
-                    const int32_t off = b_off[part][c];
-                    float p;
-                    if (off >= 0) p = ap_sparse_partial(ai[part], av[part], an[part], b_idx, b_val, off, off + b_len[part][c], lane);
-                    else {
-                        const int64_t g0 = part == 0 ? D.sp_indptr[b] : D.tx_indptr[b];
-                        p = ap_sparse_partial(ai[part], av[part], an[part], part == 0 ? D.sp_idx : D.tx_idx,
-                                              part == 0 ? D.sp_val : D.tx_val, g0, g0 + b_len[part][c], lane);
-                    }
-                    part_sum[part] = ap_wave_sum(p);
+        const int32_t cmax = i - j0 < AP_CB - 1 ? i - j0 : AP_CB - 1;   // columns j <= i of this block
+        // the dense products of this row's pairs, one coalesced load (lane c holds column j0 + c)
+        const float g_row = (lane <= cmax && j0 + lane < K) ? out[(int64_t)i * K + j0 + lane] : 0.f;
+        float my_val = 0.f;
+        const int32_t clast = cmax < K - 1 - j0 ? cmax : K - 1 - j0;   // last column of this row in the block
+        constexpr int GC = 4;                                          // columns in flight per wave
+        for (int c0 = 0; c0 <= clast; c0 += GC) {
+            bool fast = a >= 0 && tab_sp && tab_tx;
+#pragma unroll
+            for (int g = 0; g < GC; g++)
+                if (c0 + g <= clast) fast = fast && b_id[c0 + g] >= 0 && b_off[0][c0 + g] >= 0 && b_off[1][c0 + g] >= 0;
+            float pr[GC];
+            if (fast) {
+                // column lists and row tables all in LDS: 2 sparse slots + 1 lexical slot per column, all in flight together
+                const AP_LDS int32_t *lb_idx = (const AP_LDS int32_t *)b_idx;
+                const AP_LDS float *lb_val = (const AP_LDS float *)b_val;
+                const AP_LDS uint64_t *tsp = (const AP_LDS uint64_t *)t_sp[wave];
+                const AP_LDS uint64_t *ttx = (const AP_LDS uint64_t *)t_tx[wave];
+                int32_t term[GC][3];
+                float bval[GC][3], aval[GC][3];
+#pragma unroll
+                for (int g = 0; g < GC; g++) {
+                    const int c = c0 + g <= clast ? c0 + g : clast;
+                    const int32_t so = b_off[0][c], sn = c0 + g <= clast ? b_len[0][c] : 0;
+                    const int32_t to = b_off[1][c], tn = c0 + g <= clast ? b_len[1][c] : 0;
+                    term[g][0] = lane < sn ? lb_idx[so + lane] : -1;        bval[g][0] = lane < sn ? lb_val[so + lane] : 0.f;
+                    term[g][1] = lane + 64 < sn ? lb_idx[so + 64 + lane] : -1; bval[g][1] = lane + 64 < sn ? lb_val[so + 64 + lane] : 0.f;
+                    term[g][2] = lane < tn ? lb_idx[to + lane] : -1;        bval[g][2] = lane < tn ? lb_val[to + lane] : 0.f;
                 }
-                val = ap_fuse(wd, ws, wf, out[(int64_t)i * K + j0 + c], part_sum[0], part_sum[1]);
+                {
+                    // look-ups ordered so that the first 2*GC use the sparse table, the last GC the lexical one
+                    int32_t tt[3 * GC]; float vv[3 * GC];
+#pragma unroll
+                    for (int g = 0; g < GC; g++) { tt[2 * g] = term[g][0]; tt[2 * g + 1] = term[g][1]; tt[2 * GC + g] = term[g][2]; }
+                    ap_table_get_many<3 * GC, 2 * GC>(tsp, ttx, tt, vv);
+#pragma unroll
+                    for (int g = 0; g < GC; g++) { aval[g][0] = vv[2 * g]; aval[g][1] = vv[2 * g + 1]; aval[g][2] = vv[2 * GC + g]; }
+                }
+#pragma unroll
+                for (int g = 0; g < GC; g++) {
+                    const int c = c0 + g <= clast ? c0 + g : clast;
+                    const int32_t so = b_off[0][c], sn = c0 + g <= clast ? b_len[0][c] : 0;
+                    const int32_t to = b_off[1][c], tn = c0 + g <= clast ? b_len[1][c] : 0;
+                    float qs = fmaf(aval[g][1], bval[g][1], aval[g][0] * bval[g][0]);
+                    for (int32_t e = 128 + lane; e < sn; e += 64) qs = fmaf(ap_table_get(tsp, AP_SP_SLOTS, 9, lb_idx[so + e]), lb_val[so + e], qs);
+                    float qt = aval[g][2] * bval[g][2];
+                    for (int32_t e = 64 + lane; e < tn; e += 64) qt = fmaf(ap_table_get(ttx, AP_TX_SLOTS, 8, lb_idx[to + e]), lb_val[to + e], qt);
+                    pr[g] = fmaf(wf, qt, ws * qs);
+                }
+            } else {
+#pragma unroll
+                for (int g = 0; g < GC; g++) {
+                    pr[g] = 0.f;
+                    const int c = c0 + g;
+                    if (c > clast || a < 0 || b_id[c] < 0) continue;
+                    const int32_t b = b_id[c];
+                    float q2[2];
+                    for (int part = 0; part < 2; part++) {
+                        const int32_t off = b_off[part][c], len = b_len[part][c];
+                        const bool tab = part == 0 ? tab_sp : tab_tx;
+                        const int32_t *bi; const float *bv; int64_t beg;
+                        if (off >= 0) { bi = b_idx; bv = b_val; beg = off; }
+                        else { bi = part == 0 ? D.sp_idx : D.tx_idx; bv = part == 0 ? D.sp_val : D.tx_val; beg = part == 0 ? D.sp_indptr[b] : D.tx_indptr[b]; }
+                        float q = 0.f;
+                        if (tab) {
+                            for (int32_t e = lane; e < len; e += 64) {
+                                const float av = part == 0 ? ap_table_get((const uint64_t *)t_sp[wave], AP_SP_SLOTS, 9, bi[beg + e])
+                                                           : ap_table_get((const uint64_t *)t_tx[wave], AP_TX_SLOTS, 8, bi[beg + e]);
+                                q = fmaf(av, bv[beg + e], q);
+                            }
+                        } else {   // a row list too long for the table: search it in global memory
+                            q = ap_sparse_partial(part == 0 ? D.sp_idx + a_sp0 : D.tx_idx + a_tx0, part == 0 ? D.sp_val + a_sp0 : D.tx_val + a_tx0,
+                                                  part == 0 ? an_sp : an_tx, bi, bv, beg, beg + len, lane);
+                        }
+                        q2[part] = q;
+                    }
+                    pr[g] = fmaf(wf, q2[1], ws * q2[0]);
+                }
             }
-            if (lane == 0) out[(int64_t)i * K + j0 + c] = val;
+#pragma unroll
+            for (int g = 0; g < GC; g++) {
+                const int c = c0 + g;
+                if (c > clast) continue;
+                float val = -INFINITY;
+                if (a >= 0 && b_id[c] >= 0) val = fmaf(wd, __shfl(g_row, c, 64), ap_wave_sum(pr[g]));
+                if (lane == c) my_val = val;
+            }
         }
+        if (lane <= cmax && j0 + lane < K) { out[(int64_t)i * K + j0 + lane] = my_val; out[(int64_t)(j0 + lane) * K + i] = my_val; }
         __builtin_amdgcn_wave_barrier();
     }
 }

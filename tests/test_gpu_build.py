@@ -151,7 +151,12 @@ def test_s5_rejections_by_ip_rule():
     _say("S5 IP-rule rejections")
     w = make_workload("tiny", seed=31, n=500, nq=4, dim=64, sp=("fixed", 2), tx=("fixed", 6))
     rng = np.random.default_rng(0)
-    w.docs.dense *= rng.uniform(0.2, 3.0, (500, 1)).astype(np.float32)
+    # clustered directions with very different norms: inside a cluster a long vector w has
+    # IP(w, v) >= IP(v, v) for every shorter v, which is exactly what the rule rejects
+    centers = rng.standard_normal((25, 64)).astype(np.float32)
+    centers /= np.linalg.norm(centers, axis=1, keepdims=True)
+    d = centers[rng.integers(0, 25, 500)] + 0.05 * rng.standard_normal((500, 64)).astype(np.float32)
+    w.docs.dense[:] = d * rng.uniform(0.2, 3.0, (500, 1)).astype(np.float32)
     docs = B.DeviceVecs(w.docs)
     R, K = 8, 32
     wv = np.array([1.0, 0.01, 0.01], np.float32)
