@@ -115,9 +115,11 @@ def main():
         rec = recall_at_k(ids.cpu().numpy(), gt)
         counts, kms = ix.search_stats(nq)
         nd = int(counts[:, 0].sum().item())
+        nsk = int(counts[:, 2].sum().item())
         sweep.append(dict(beam=beam, recall=round(rec, 4), qps=round(nq / dt, 1), kernel_ms=round(kms, 3),
-                          dists_per_query=round(nd / nq, 1)))
-        log(f"[bench] beam {beam}: recall@{k} {rec:.4f}  {nq / dt:,.0f} qps  kernel {kms:.2f} ms  {nd / nq:.0f} dists/query")
+                          dists_per_query=round(nd / nq, 1), dense_skipped_frac=round(nsk / max(nd, 1), 3)))
+        log(f"[bench] beam {beam}: recall@{k} {rec:.4f}  {nq / dt:,.0f} qps  kernel {kms:.2f} ms  {nd / nq:.0f} dists/query "
+            f"({100.0 * nsk / max(nd, 1):.1f}% without the dense row)")
         if chosen is None and rec >= args.target_recall:
             chosen = beam
         if chosen is not None and beam >= w.beam:
@@ -143,18 +145,24 @@ def main():
     rec = recall_at_k(out[0].cpu().numpy(), gt)
     counts, _ = ix.search_stats(nq)
     counts = counts.cpu().numpy().astype(np.int64)
-    n_dist, n_iter = int(counts[:, 0].sum()), int(counts[:, 1].sum())
+    n_dist, n_iter, n_skip = int(counts[:, 0].sum()), int(counts[:, 1].sum()), int(counts[:, 2].sum())
 
     # ---- roofline of the search kernel: algorithmic bytes / measured kernel time
     sp_nnz = float(w.docs.sp_indptr[-1]) / w.docs.n
     tx_nnz = float(w.docs.tx_indptr[-1]) / w.docs.n
-    bytes_per_dist = w.docs.dim * (2 if bf16 else 4) + 8.0 * sp_nnz + 8.0 * tx_nnz + 32.0   # rows + 4 offsets
+    dense_bytes = w.docs.dim * (2 if bf16 else 4)
+    bytes_per_dist = dense_bytes + 8.0 * sp_nnz + 8.0 * tx_nnz + 32.0   # rows + 4 offsets
+    # algorithmic bytes: the per-similarity figure times the similarities the launch evaluated
     bytes_per_launch = n_dist * bytes_per_dist + n_iter * w.degree * 4.0
+    # bytes the kernel actually had to move: a candidate that provably cannot enter the pool is
+    # evaluated without its dense row (its norm, 4 B, is read instead)
+    bytes_needed = bytes_per_launch - n_skip * (dense_bytes - 4.0)
     k_ms = float(np.mean(kernel_ms))
     achieved = bytes_per_launch / (k_ms * 1e-3) / 1e9
     roofline = dict(bound="hbm", kernel="k_search", achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None, kernel_ms=round(k_ms, 3),
-                    bytes_per_dist=round(bytes_per_dist, 1), dists_per_launch=n_dist,
+                    bytes_per_dist=round(bytes_per_dist, 1), dists_per_launch=n_dist, dense_rows_skipped=n_skip,
+                    needed_GBps_after_dense_skip=round(bytes_needed / (k_ms * 1e-3) / 1e9, 1),
                     dists_per_s=round(n_dist / (k_ms * 1e-3), 1))
 
     # ---- CPU baseline: the oracle as it stands, one thread, bounded sample of the same searches

@@ -183,8 +183,10 @@ int ap_import_graph(const ap_corpus *corpus, const ap_build_params *params, cons
                     ap_index **out);
 
 /* Counters of the last ap_search_batch on this index (synchronises on that
- * search).  out_counts (device, may be NULL): nq x 2 int32 = per query the
- * number of hybrid similarities evaluated and the number of iterations.
+ * search).  out_counts (device, may be NULL): nq x 3 int32 = per query the
+ * number of candidates scored, the number of iterations, and the number of
+ * scored candidates whose dense row was not read (their sparse + lexical parts
+ * plus the largest possible dense part could not reach the pool).
  * kernel_ms (host, may be NULL): duration of the search kernel alone, measured
  * with events on the stream it ran on. */
 int ap_search_stats(const ap_index *index, int32_t *out_counts, int32_t nq, float *kernel_ms, void *stream);

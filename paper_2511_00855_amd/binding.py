@@ -15,7 +15,7 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "liballanpoe.so")
+LIB_PATH = os.environ.get("ALLANPOE_LIB") or os.path.join(_HERE, "liballanpoe.so")
 
 AP_F32, AP_BF16 = 0, 1
 
@@ -325,8 +325,8 @@ class Index:
         return sem, kw, kc, ent
 
     def search_stats(self, nq: int):
-        """(counts[nq, 2] = similarities evaluated and iterations per query, search-kernel ms) of the last search."""
-        counts = torch.empty((nq, 2), dtype=torch.int32, device=self.device)
+        """(counts[nq, 3] = candidates scored, iterations, dense rows skipped per query; search-kernel ms) of the last search."""
+        counts = torch.empty((nq, 3), dtype=torch.int32, device=self.device)
         ms = C.c_float(0)
         with torch.cuda.device(self.device):
             _check(lib().ap_search_stats(self._h, _ptr(counts), C.c_int32(nq), C.byref(ms), _stream()), "ap_search_stats")

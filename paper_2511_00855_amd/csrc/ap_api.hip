@@ -84,7 +84,7 @@ __global__ void k_bm25_weights(const int64_t *__restrict__ indptr, const int32_t
 
 // Fused self-similarity M_w(v,v) = w_d |v_d|^2 + w_s |v_s|^2 + w_f |v_f|^2, one wave per document.
 template <int DT>
-__global__ void k_self_sim(ApVecs D, float wd, float ws, float wf, float *__restrict__ out) {
+__global__ void k_self_sim(ApVecs D, float wd, float ws, float wf, float *__restrict__ out, float *__restrict__ dnorm) {
     constexpr int EPC = ApDense<DT>::EPC;
     const int lane = threadIdx.x & 63;
     const int64_t wave = (blockIdx.x * (int64_t)blockDim.x + threadIdx.x) >> 6;
@@ -100,7 +100,7 @@ __global__ void k_self_sim(ApVecs D, float wd, float ws, float wf, float *__rest
         for (int64_t e = D.sp_indptr[v] + lane; e < D.sp_indptr[v + 1]; e += 64) ps = fmaf(D.sp_val[e], D.sp_val[e], ps);
         for (int64_t e = D.tx_indptr[v] + lane; e < D.tx_indptr[v + 1]; e += 64) pf = fmaf(D.tx_val[e], D.tx_val[e], pf);
         pd = ap_wave_sum(pd); ps = ap_wave_sum(ps); pf = ap_wave_sum(pf);
-        if (lane == 0) out[v] = ap_fuse(wd, ws, wf, pd, ps, pf);
+        if (lane == 0) { out[v] = ap_fuse(wd, ws, wf, pd, ps, pf); dnorm[v] = sqrtf(pd); }
     }
 }
 
@@ -128,6 +128,7 @@ int ap_ingest_impl(ap_index *ix, hipStream_t st) {
     AP_TRY(ap_dev_alloc(&ix->df, (size_t)c.tx_vocab));
     AP_TRY(ap_dev_alloc(&ix->stats, 4));
     AP_TRY(ap_dev_alloc(&ix->self_sim, (size_t)c.n));
+    AP_TRY(ap_dev_alloc(&ix->dense_norm, (size_t)c.n));
     AP_TRY(ap_dev_alloc(&ix->w_dev, 4));
     AP_TRY(ap_fill_u32(ix->df, (size_t)c.tx_vocab, 0, st));
     AP_TRY(ap_fill_u32(ix->stats, 4, 0, st));
@@ -149,9 +150,9 @@ int ap_ingest_impl(ap_index *ix, hipStream_t st) {
         int blocks = (int)((waves + 3) / 4);
         const float *w = ix->params.build_w;
         if (ix->dtype == AP_F32)
-            hipLaunchKernelGGL(k_self_sim<AP_F32>, dim3(blocks), dim3(256), 0, st, ix->docs, w[0], w[1], w[2], ix->self_sim);
+            hipLaunchKernelGGL(k_self_sim<AP_F32>, dim3(blocks), dim3(256), 0, st, ix->docs, w[0], w[1], w[2], ix->self_sim, ix->dense_norm);
         else
-            hipLaunchKernelGGL(k_self_sim<AP_BF16>, dim3(blocks), dim3(256), 0, st, ix->docs, w[0], w[1], w[2], ix->self_sim);
+            hipLaunchKernelGGL(k_self_sim<AP_BF16>, dim3(blocks), dim3(256), 0, st, ix->docs, w[0], w[1], w[2], ix->self_sim, ix->dense_norm);
         AP_CHECK_HIP(hipGetLastError());
     }
     AP_CHECK_HIP(hipMemcpyAsync(ix->w_dev, ix->w_default, 3 * sizeof(float), hipMemcpyHostToDevice, st));
@@ -184,7 +185,7 @@ extern "C" int ap_ingest(const ap_corpus *corpus, const ap_build_params *params,
 extern "C" void ap_free_index(ap_index *ix) {
     if (!ix) return;
     void *ptrs[] = {ix->tx_w, ix->df, ix->stats, ix->self_sim, ix->graph, ix->kw, ix->kw_count, ix->entry, ix->visited, ix->w_dev,
-                    ix->search_counts};
+                    ix->search_counts, ix->dense_norm};
     for (void *p : ptrs) if (p) (void)hipFree(p);
     for (hipEvent_t e : ix->ev_search) if (e) (void)hipEventDestroy(e);
     delete ix;

@@ -62,6 +62,7 @@ struct ap_index {
     int32_t *df = nullptr;     // owned: document frequency per term
     float *stats = nullptr;    // owned: [0] avgdl
     float *self_sim = nullptr; // owned: fused self-similarity under build_w
+    float *dense_norm = nullptr; // owned: |d_dense| per document (upper bound of the dense part in the search)
     int32_t *graph = nullptr;  // owned: n x degree
     int32_t *kw = nullptr;     // owned: n x degree/2
     int32_t *kw_count = nullptr;
@@ -166,9 +167,21 @@ __device__ __forceinline__ void ap_load_aside(const void *base, int64_t row, int
     }
 }
 
+// Sum over the 64 lanes of a wave, the same value returned in every lane.
+// Inside each row of 16 lanes the exchange is done with DPP (quad permutes,
+// then half-row and row mirrors), which costs a VALU cycle or two per step;
+// only the last two steps (lanes 16 and 32 apart) go through the LDS crossbar.
+template <int CTRL>
+__device__ __forceinline__ float ap_dpp(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
 __device__ __forceinline__ float ap_wave_sum(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    v += ap_dpp<0xB1>(v);    // quad_perm [1,0,3,2]: lane ^ 1
+    v += ap_dpp<0x4E>(v);    // quad_perm [2,3,0,1]: lane ^ 2
+    v += ap_dpp<0x141>(v);   // row_half_mirror: quads 0<->1, 2<->3 of a row
+    v += ap_dpp<0x140>(v);   // row_mirror: half rows 0<->1
+    v += __shfl_xor(v, 16, 64);
+    v += __shfl_xor(v, 32, 64);
     return v;
 }
 
@@ -211,94 +224,103 @@ __device__ __forceinline__ float ap_sparse_partial(IP a_idx, VP a_val, int32_t a
     return p;
 }
 
-// Hybrid similarity (Definition 1) of the a side with up to G rows of B at
-// once.  All 64 lanes of the wave take part; the loads of all G rows are
-// issued before any of them is consumed, so that G rows are in flight per
-// wave.  Row g has its sparse list at [spb[g], spb[g]+spn[g]) and its lexical
-// list at [txb[g], txb[g]+txn[g]).  SS / TS are the numbers of 64-entry slots
-// of the sparse / lexical list that are prefetched into registers; longer
-// lists continue with a plain loop.  Every lane returns the same three sums
-// per row, and the sums are bit-identical for any G, SS, TS and pointer kind:
-// lane l always accumulates entries l, l+64, ... in that order.
-template <int DT, int NV, int G, int SS, int TS, typename IP, typename VP>
-__device__ __forceinline__ void ap_hybrid_batch(const ApVecs &B, const float *qa, IP a_sp_idx, VP a_sp_val, int32_t a_sp_n,
-                                                IP a_tx_idx, VP a_tx_val, int32_t a_tx_n, int32_t ng, const int32_t *v,
-                                                const int64_t *spb, const int32_t *spn, const int64_t *txb,
-                                                const int32_t *txn, float *sd, float *ss, float *sf) {
+// Dense part of Definition 1: <a_d, B_d[row]>, lane l holding columns (64i+l)*EPC.. of the a side in qa.
+// All lanes return the same sum.
+template <int DT, int NV>
+__device__ __forceinline__ float ap_dense_dot(const ApVecs &B, const float *qa, int64_t row) {
     constexpr int EPC = ApDense<DT>::EPC;
     const int lane = threadIdx.x & 63;
-    float d[G][NV * EPC];
-    int32_t si[G][SS], ti[G][TS];
-    float sv[G][SS], tv[G][TS];
+    float d[NV * EPC];
 #pragma unroll
-    for (int g = 0; g < G; g++) {
-        if (g < ng) {
+    for (int i = 0; i < NV; i++) {
+        const int col = (i * 64 + lane) * EPC;
+        if (col < B.dim) ApDense<DT>::load(B.dense, row, B.dim, col, d + i * EPC);
+    }
+    float pd = 0.f;
 #pragma unroll
-            for (int i = 0; i < NV; i++) {
-                const int col = (i * 64 + lane) * EPC;
-                if (col < B.dim) ApDense<DT>::load(B.dense, v[g], B.dim, col, d[g] + i * EPC);
-            }
+    for (int i = 0; i < NV; i++) {
+        const int col = (i * 64 + lane) * EPC;
+        if (col < B.dim) {
 #pragma unroll
-            for (int k = 0; k < SS; k++) {
-                const int32_t e = k * 64 + lane;
-                si[g][k] = e < spn[g] ? B.sp_idx[spb[g] + e] : -1;
-                sv[g][k] = e < spn[g] ? B.sp_val[spb[g] + e] : 0.f;
-            }
-#pragma unroll
-            for (int k = 0; k < TS; k++) {
-                const int32_t e = k * 64 + lane;
-                ti[g][k] = e < txn[g] ? B.tx_idx[txb[g] + e] : -1;
-                tv[g][k] = e < txn[g] ? B.tx_val[txb[g] + e] : 0.f;
-            }
+            for (int e = 0; e < EPC; e++) pd = fmaf(qa[i * EPC + e], d[i * EPC + e], pd);
         }
     }
-    const int32_t sp_step = ap_pow2_floor(a_sp_n), tx_step = ap_pow2_floor(a_tx_n);
+    return ap_wave_sum(pd);
+}
+
+// Sparse and lexical parts of Definition 1 for one row of B whose lists are at
+// [spb, spb+spn) and [txb, txb+txn).  The first SS / TS 64-entry slots of the
+// two lists are loaded before any look-up starts (all loads in flight
+// together); longer lists continue with a plain loop.  Lane l always
+// accumulates entries l, l+64, ... in that order, so the sums do not depend
+// on SS, TS or on where the a side's lists live.
+template <int SS, int TS>
+__device__ __forceinline__ void ap_lists_load(const ApVecs &B, int64_t spb, int32_t spn, int64_t txb, int32_t txn,
+                                              int32_t *si, float *sv, int32_t *ti, float *tv) {
+    const int lane = threadIdx.x & 63;
 #pragma unroll
-    for (int g = 0; g < G; g++) {
-        if (g < ng) {
-            float pd = 0.f, ps = 0.f, pf = 0.f;
+    for (int k = 0; k < SS; k++) {
+        const int32_t e = k * 64 + lane;
+        si[k] = e < spn ? B.sp_idx[spb + e] : -1;
+        sv[k] = e < spn ? B.sp_val[spb + e] : 0.f;
+    }
 #pragma unroll
-            for (int i = 0; i < NV; i++) {
-                const int col = (i * 64 + lane) * EPC;
-                if (col < B.dim) {
-#pragma unroll
-                    for (int e = 0; e < EPC; e++) pd = fmaf(qa[i * EPC + e], d[g][i * EPC + e], pd);
-                }
-            }
-#pragma unroll
-            for (int k = 0; k < SS; k++)
-                if (k * 64 < spn[g]) ps = ap_match_fma(a_sp_idx, a_sp_val, a_sp_n, sp_step, si[g][k], sv[g][k], ps);
-            for (int32_t e0 = SS * 64; e0 < spn[g]; e0 += 64) {
-                const int32_t e = e0 + lane;
-                const int32_t t = e < spn[g] ? B.sp_idx[spb[g] + e] : -1;
-                const float x = e < spn[g] ? B.sp_val[spb[g] + e] : 0.f;
-                ps = ap_match_fma(a_sp_idx, a_sp_val, a_sp_n, sp_step, t, x, ps);
-            }
-#pragma unroll
-            for (int k = 0; k < TS; k++)
-                if (k * 64 < txn[g]) pf = ap_match_fma(a_tx_idx, a_tx_val, a_tx_n, tx_step, ti[g][k], tv[g][k], pf);
-            for (int32_t e0 = TS * 64; e0 < txn[g]; e0 += 64) {
-                const int32_t e = e0 + lane;
-                const int32_t t = e < txn[g] ? B.tx_idx[txb[g] + e] : -1;
-                const float x = e < txn[g] ? B.tx_val[txb[g] + e] : 0.f;
-                pf = ap_match_fma(a_tx_idx, a_tx_val, a_tx_n, tx_step, t, x, pf);
-            }
-            sd[g] = ap_wave_sum(pd);
-            ss[g] = ap_wave_sum(ps);
-            sf[g] = ap_wave_sum(pf);
-        }
+    for (int k = 0; k < TS; k++) {
+        const int32_t e = k * 64 + lane;
+        ti[k] = e < txn ? B.tx_idx[txb + e] : -1;
+        tv[k] = e < txn ? B.tx_val[txb + e] : 0.f;
     }
 }
 
-// One row: the same arithmetic as the batch form.
+template <int SS, int TS, typename IP, typename VP>
+__device__ __forceinline__ void ap_lists_reduce(const ApVecs &B, IP a_sp_idx, VP a_sp_val, int32_t a_sp_n, IP a_tx_idx,
+                                                VP a_tx_val, int32_t a_tx_n, int64_t spb, int32_t spn, int64_t txb,
+                                                int32_t txn, const int32_t *si, const float *sv, const int32_t *ti,
+                                                const float *tv, float &ss, float &sf) {
+    const int lane = threadIdx.x & 63;
+    const int32_t sp_step = ap_pow2_floor(a_sp_n), tx_step = ap_pow2_floor(a_tx_n);
+    float ps = 0.f, pf = 0.f;
+#pragma unroll
+    for (int k = 0; k < SS; k++)
+        if (k * 64 < spn) ps = ap_match_fma(a_sp_idx, a_sp_val, a_sp_n, sp_step, si[k], sv[k], ps);
+    for (int32_t e0 = SS * 64; e0 < spn; e0 += 64) {
+        const int32_t e = e0 + lane;
+        const int32_t t = e < spn ? B.sp_idx[spb + e] : -1;
+        const float x = e < spn ? B.sp_val[spb + e] : 0.f;
+        ps = ap_match_fma(a_sp_idx, a_sp_val, a_sp_n, sp_step, t, x, ps);
+    }
+#pragma unroll
+    for (int k = 0; k < TS; k++)
+        if (k * 64 < txn) pf = ap_match_fma(a_tx_idx, a_tx_val, a_tx_n, tx_step, ti[k], tv[k], pf);
+    for (int32_t e0 = TS * 64; e0 < txn; e0 += 64) {
+        const int32_t e = e0 + lane;
+        const int32_t t = e < txn ? B.tx_idx[txb + e] : -1;
+        const float x = e < txn ? B.tx_val[txb + e] : 0.f;
+        pf = ap_match_fma(a_tx_idx, a_tx_val, a_tx_n, tx_step, t, x, pf);
+    }
+    ss = ap_wave_sum(ps);
+    sf = ap_wave_sum(pf);
+}
+
+template <int SS, int TS, typename IP, typename VP>
+__device__ __forceinline__ void ap_lists_dot(const ApVecs &B, IP a_sp_idx, VP a_sp_val, int32_t a_sp_n, IP a_tx_idx,
+                                             VP a_tx_val, int32_t a_tx_n, int64_t spb, int32_t spn, int64_t txb, int32_t txn,
+                                             float &ss, float &sf) {
+    int32_t si[SS], ti[TS];
+    float sv[SS], tv[TS];
+    ap_lists_load<SS, TS>(B, spb, spn, txb, txn, si, sv, ti, tv);
+    ap_lists_reduce<SS, TS>(B, a_sp_idx, a_sp_val, a_sp_n, a_tx_idx, a_tx_val, a_tx_n, spb, spn, txb, txn, si, sv, ti, tv, ss, sf);
+}
+
+// Hybrid similarity (Definition 1) of the a side with row j of B.  All 64
+// lanes take part and all return the same three sums.
 template <int DT, int NV>
 __device__ __forceinline__ void ap_hybrid_wave(const ApVecs &B, const float *qa, const ApLists &a, int64_t j,
                                                float &sd, float &ss, float &sf) {
-    const int32_t v = (int32_t)j;
     const int64_t spb = B.sp_indptr[j], txb = B.tx_indptr[j];
     const int32_t spn = (int32_t)(B.sp_indptr[j + 1] - spb), txn = (int32_t)(B.tx_indptr[j + 1] - txb);
-    ap_hybrid_batch<DT, NV, 1, 2, 1>(B, qa, a.sp_idx, a.sp_val, a.sp_n, a.tx_idx, a.tx_val, a.tx_n, 1, &v, &spb, &spn, &txb,
-                                     &txn, &sd, &ss, &sf);
+    sd = ap_dense_dot<DT, NV>(B, qa, j);
+    ap_lists_dot<2, 1>(B, a.sp_idx, a.sp_val, a.sp_n, a.tx_idx, a.tx_val, a.tx_n, spb, spn, txb, txn, ss, sf);
 }
 
 __device__ __forceinline__ float ap_fuse(float wd, float ws, float wf, float sd, float ss, float sf) {

@@ -26,7 +26,8 @@ struct ApSearchArgs {
     size_t words;       // visited words per query
     int32_t *out_ids;
     float *out_scores;
-    int32_t *counts;    // nq x 2: similarities evaluated, iterations
+    int32_t *counts;    // nq x 3: candidates scored, iterations, candidates whose dense row was skipped
+    const float *dnorm; // |d_dense| per document
 };
 
 // Number of entries of the descending array keys[0..n) that rank before `key`.
@@ -39,50 +40,77 @@ __device__ __forceinline__ int32_t ap_rank_in(const uint64_t *keys, int32_t n, u
     return lo;
 }
 
-// Scores the c candidates of this iteration: wave w takes candidates
-// w, w+4, ... in groups of G whose loads are all in flight together.
-template <int DT, int NV, int G, typename IP, typename VP>
-__device__ __forceinline__ void ap_score_candidates(const ApVecs &D, const float *qa, IP sp_idx, VP sp_val, int32_t sp_n,
-                                                    IP tx_idx, VP tx_val, int32_t tx_n, float wd, float ws, float wf,
-                                                    const int32_t *cand, const int64_t *s_spb, const int32_t *s_spn,
-                                                    const int64_t *s_txb, const int32_t *s_txn, int32_t c, uint64_t *newk) {
+// Scores the c candidates of this iteration; wave w takes candidates w, w+4, ...
+// The sparse and lexical parts (the short segments) are evaluated first.  When
+// the pool is full and even the largest dense part the norms allow,
+// |w_d| |q_d| |d_d|, could not lift the candidate past the pool's last entry,
+// the dense row is not read at all: the candidate could not have entered the
+// pool, so the result of the search is unchanged (it still counts as visited).
+// Returns the number of candidates whose dense row was skipped (wave-uniform).
+template <int DT, int NV, typename IP, typename VP>
+__device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const float *qa, IP sp_idx, VP sp_val, int32_t sp_n,
+                                                       IP tx_idx, VP tx_val, int32_t tx_n, float wd, float ws, float wf,
+                                                       float qnorm, bool pool_full, float worst_score, const int32_t *cand,
+                                                       const int64_t *s_spb, const int32_t *s_spn, const int64_t *s_txb,
+                                                       const int32_t *s_txn, const float *s_dn, int32_t c, uint64_t *newk) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int32_t skipped = 0;
+    constexpr int G = 2;   // candidates whose list segments are in flight together
     for (int32_t i0 = wave; i0 < c; i0 += 4 * G) {
-        int32_t v[G], spn[G], txn[G];
-        int64_t spb[G], txb[G];
-        int32_t ng = 0;
+        int32_t si[G][2], ti[G][1];
+        float sv[G][2], tv[G][1];
 #pragma unroll
-        for (int g = 0; g < G; g++) {
-            const int32_t i = i0 + 4 * g;
-            if (i < c) { v[g] = cand[i]; spb[g] = s_spb[i]; spn[g] = s_spn[i]; txb[g] = s_txb[i]; txn[g] = s_txn[i]; ng = g + 1; }
+        for (int gi = 0; gi < G; gi++) {
+            const int32_t i = i0 + 4 * gi;
+            if (i < c) ap_lists_load<2, 1>(D, s_spb[i], s_spn[i], s_txb[i], s_txn[i], si[gi], sv[gi], ti[gi], tv[gi]);
         }
-        float sd[G], ss[G], sf[G];
-        ap_hybrid_batch<DT, NV, G, 2, 1>(D, qa, sp_idx, sp_val, sp_n, tx_idx, tx_val, tx_n, ng, v, spb, spn, txb, txn, sd, ss, sf);
-        if (lane == 0) {
 #pragma unroll
-            for (int g = 0; g < G; g++)
-                if (g < ng) newk[i0 + 4 * g] = ap_make_key(ap_fuse(wd, ws, wf, sd[g], ss[g], sf[g]), v[g], 1u);
+        for (int gi = 0; gi < G; gi++) {
+            const int32_t i = i0 + 4 * gi;
+            if (i >= c) continue;
+            const int32_t v = cand[i];
+            float ss, sf;
+            ap_lists_reduce<2, 1>(D, sp_idx, sp_val, sp_n, tx_idx, tx_val, tx_n, s_spb[i], s_spn[i], s_txb[i], s_txn[i], si[gi],
+                                  sv[gi], ti[gi], tv[gi], ss, sf);
+            // upper bound of the fused score, with slack far above fp32 rounding
+            const float dmax = fabsf(wd) * qnorm * s_dn[i] * 1.0001f;
+            const float part = fmaf(wf, sf, ws * ss);
+            const float ub = part + dmax + 1e-5f * (fabsf(ws * ss) + fabsf(wf * sf) + dmax);
+            uint64_t key;
+            if (pool_full && ub < worst_score) {
+                key = (uint64_t)(uint32_t)(i + 1);   // ranks after every real key (score bits 0), distinct per candidate
+                skipped++;
+            } else {
+                const float sd = ap_dense_dot<DT, NV>(D, qa, v);
+                key = ap_make_key(ap_fuse(wd, ws, wf, sd, ss, sf), v, 1u);
+            }
+            if (lane == 0) newk[i] = key;
         }
     }
+    return skipped;
 }
 
-template <int DT, int NV, int AP_SEARCH_G>
-__global__ __launch_bounds__(256) void k_search(ApSearchArgs g) {
+#ifndef AP_SEARCH_WAVES_PER_SIMD
+#define AP_SEARCH_WAVES_PER_SIMD 7
+#endif
+template <int DT, int NV>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_WAVES_PER_SIMD, 8))) void k_search(ApSearchArgs g) {
     extern __shared__ uint64_t smem64[];
-    uint64_t *poolA = smem64;
-    uint64_t *poolB = poolA + g.L;
-    uint64_t *newk = poolB + g.L;            // keys of this iteration's candidates, unordered
+    uint64_t *cur = smem64;                  // the pool: L keys, best first
+    uint64_t *newk = cur + g.L;              // keys of this iteration's candidates, unordered
     uint64_t *newS = newk + g.cmax;          // the same, sorted
-    int64_t *s_spb = reinterpret_cast<int64_t *>(newS + g.cmax);
+    uint64_t *nxt = newS + g.cmax;           // scratch of cmax words
+    int64_t *s_spb = reinterpret_cast<int64_t *>(nxt + g.cmax);
     int64_t *s_txb = s_spb + g.cmax;
     int32_t *s_spn = reinterpret_cast<int32_t *>(s_txb + g.cmax);
     int32_t *s_txn = s_spn + g.cmax;
-    int32_t *cand = s_txn + g.cmax;
+    float *s_dn = reinterpret_cast<float *>(s_txn + g.cmax);
+    int32_t *cand = reinterpret_cast<int32_t *>(s_dn + g.cmax);
     int32_t *l_sp_idx = cand + g.cmax;
     float *l_sp_val = reinterpret_cast<float *>(l_sp_idx + AP_Q_CAP);
     int32_t *l_tx_idx = reinterpret_cast<int32_t *>(l_sp_val + AP_Q_CAP);
     float *l_tx_val = reinterpret_cast<float *>(l_tx_idx + AP_Q_CAP);
-    __shared__ int32_t s_cnt, s_np;
+    __shared__ int32_t s_cnt, s_np, s_skip;
     __shared__ int32_t s_par[8];
 
     const int64_t q = blockIdx.x;
@@ -91,9 +119,16 @@ __global__ __launch_bounds__(256) void k_search(ApSearchArgs g) {
     const bool in_lds = a.sp_n <= AP_Q_CAP && a.tx_n <= AP_Q_CAP;   // uniform
     float qa[NV * ApDense<DT>::EPC];
     ap_load_aside<DT, NV, AP_F32>(g.Q.dense, q, g.D.dim, qa);
+    float qnorm;
+    {
+        float p = 0.f;
+#pragma unroll
+        for (int i = 0; i < NV * ApDense<DT>::EPC; i++) p = fmaf(qa[i], qa[i], p);
+        qnorm = sqrtf(ap_wave_sum(p));
+    }
     const float wd = g.w[q * g.w_stride + 0], ws = g.w[q * g.w_stride + 1], wf = g.w[q * g.w_stride + 2];
     uint32_t *vis = g.visited + (size_t)q * g.words;
-    if (threadIdx.x == 0) s_cnt = 0;
+    if (threadIdx.x == 0) { s_cnt = 0; s_skip = 0; }
     __syncthreads();
 
     // S7: entry points
@@ -106,8 +141,7 @@ __global__ __launch_bounds__(256) void k_search(ApSearchArgs g) {
         }
     }
     __syncthreads();
-    uint64_t *cur = poolA, *nxt = poolB;
-    int32_t len = 0, it = 0, nscored = 0;
+    int32_t len = 0, it = 0, nscored = 0, nskipped = 0;
     for (;;) {
         const int32_t c = s_cnt;
         nscored += c;
@@ -117,19 +151,22 @@ __global__ __launch_bounds__(256) void k_search(ApSearchArgs g) {
             const int64_t sb = g.D.sp_indptr[v], tb = g.D.tx_indptr[v];
             s_spb[i] = sb; s_spn[i] = (int32_t)(g.D.sp_indptr[v + 1] - sb);
             s_txb[i] = tb; s_txn[i] = (int32_t)(g.D.tx_indptr[v + 1] - tb);
+            s_dn[i] = g.dnorm[v];
         }
         __syncthreads();
+        const bool pool_full = len == g.L;
+        const uint64_t worst = pool_full ? cur[g.L - 1] : 0ull;
+        const float worst_score = ap_key_score(worst);
         if (in_lds)
-            ap_score_candidates<DT, NV, AP_SEARCH_G>(g.D, qa, (const AP_LDS int32_t *)l_sp_idx, (const AP_LDS float *)l_sp_val,
-                                                     a.sp_n, (const AP_LDS int32_t *)l_tx_idx, (const AP_LDS float *)l_tx_val,
-                                                     a.tx_n, wd, ws, wf, cand, s_spb, s_spn, s_txb, s_txn, c, newk);
+            nskipped += ap_score_candidates<DT, NV>(g.D, qa, (const AP_LDS int32_t *)l_sp_idx, (const AP_LDS float *)l_sp_val, a.sp_n,
+                                                    (const AP_LDS int32_t *)l_tx_idx, (const AP_LDS float *)l_tx_val, a.tx_n, wd, ws, wf,
+                                                    qnorm, pool_full, worst_score, cand, s_spb, s_spn, s_txb, s_txn, s_dn, c, newk);
         else
-            ap_score_candidates<DT, NV, AP_SEARCH_G>(g.D, qa, a.sp_idx, a.sp_val, a.sp_n, a.tx_idx, a.tx_val, a.tx_n, wd, ws, wf,
-                                                     cand, s_spb, s_spn, s_txb, s_txn, c, newk);
+            nskipped += ap_score_candidates<DT, NV>(g.D, qa, a.sp_idx, a.sp_val, a.sp_n, a.tx_idx, a.tx_val, a.tx_n, wd, ws, wf, qnorm,
+                                                    pool_full, worst_score, cand, s_spb, s_spn, s_txb, s_txn, s_dn, c, newk);
         __syncthreads();
         // sort the new keys by ranking them among themselves; only those that
         // rank before the pool's last entry (when the pool is full) can enter
-        const uint64_t worst = len == g.L ? cur[g.L - 1] : 0ull;
         for (int32_t t = threadIdx.x; t < c; t += blockDim.x) {
             const uint64_t key = newk[t];
             int32_t r = 0;
@@ -137,20 +174,39 @@ __global__ __launch_bounds__(256) void k_search(ApSearchArgs g) {
             newS[r] = key;
         }
         __syncthreads();
-        int32_t cin = ap_rank_in(newS, c, worst);   // new keys that rank before `worst` (all of them while the pool has room)
+        const int32_t cin = ap_rank_in(newS, c, worst);   // new keys that rank before `worst` (all of them while the pool has room)
         if (cin > 0) {
-            for (int32_t t = threadIdx.x; t < cin; t += blockDim.x) {
+            // In-place rank merge.  A pool entry at position t moves up by the number of entering keys that rank
+            // before it, so only entries from the first insertion point on move, and they only move towards the
+            // end: chunks of 512 entries are read, then written, from the back of the pool to the front.
+            const int32_t rmin = ap_rank_in(cur, len, newS[0]);
+            uint64_t nkey = 0; int32_t npos = g.L;
+            if ((int32_t)threadIdx.x < cin) { nkey = newS[threadIdx.x]; npos = (int32_t)threadIdx.x + ap_rank_in(cur, len, nkey); }
+            for (int32_t t = (int32_t)threadIdx.x + 256; t < cin; t += 256) {   // more than 256 entering keys (wide searches)
                 const uint64_t key = newS[t];
-                const int32_t r = t + ap_rank_in(cur, len, key);
-                if (r < g.L) nxt[r] = key;
+                nxt[t] = (uint64_t)(uint32_t)(t + ap_rank_in(cur, len, key));   // park the positions in the scratch array
             }
-            for (int32_t t = threadIdx.x; t < len; t += blockDim.x) {
-                const uint64_t key = cur[t];
-                const int32_t r = t + ap_rank_in(newS, cin, key);
-                if (r < g.L) nxt[r] = key;
+            __syncthreads();
+            for (int32_t hi = len; hi > rmin; hi -= 512) {
+                const int32_t lo = hi - 512 > rmin ? hi - 512 : rmin;
+                uint64_t held[2]; int32_t dest[2];
+#pragma unroll
+                for (int m = 0; m < 2; m++) {
+                    const int32_t t = lo + (int32_t)threadIdx.x + 256 * m;
+                    dest[m] = g.L;
+                    if (t < hi) { held[m] = cur[t]; dest[m] = t + ap_rank_in(newS, cin, held[m]); }
+                }
+                __syncthreads();
+#pragma unroll
+                for (int m = 0; m < 2; m++) if (dest[m] < g.L) cur[dest[m]] = held[m];
+                __syncthreads();
+            }
+            if (npos < g.L) cur[npos] = nkey;
+            for (int32_t t = (int32_t)threadIdx.x + 256; t < cin; t += 256) {
+                const int32_t r = (int32_t)(uint32_t)nxt[t];
+                if (r < g.L) cur[r] = newS[t];
             }
             len = len + cin < g.L ? len + cin : g.L;
-            { uint64_t *t = cur; cur = nxt; nxt = t; }
             __syncthreads();
         }
         if (g.max_iters > 0 && it >= g.max_iters) break;
@@ -185,7 +241,9 @@ __global__ __launch_bounds__(256) void k_search(ApSearchArgs g) {
         __syncthreads();
         it++;
     }
-    if (threadIdx.x == 0) { g.counts[q * 2] = nscored; g.counts[q * 2 + 1] = it; }
+    if (lane == 0) atomicAdd(&s_skip, nskipped);
+    __syncthreads();
+    if (threadIdx.x == 0) { g.counts[q * 3] = nscored; g.counts[q * 3 + 1] = it; g.counts[q * 3 + 2] = s_skip; }
     // S9
     for (int32_t i = threadIdx.x; i < g.k; i += blockDim.x) {
         g.out_ids[q * g.k + i] = i < len ? ap_key_id(cur[i]) : -1;
@@ -223,10 +281,10 @@ extern "C" int ap_search_batch(ap_index *ix, const ap_queries *q, const float *p
         AP_TRY(ap_dev_alloc(&ix->visited, need));
         ix->visited_words = need;
     }
-    if ((size_t)q->nq * 2 > ix->search_counts_cap) {
+    if ((size_t)q->nq * 3 > ix->search_counts_cap) {
         if (ix->search_counts) { AP_CHECK_HIP(hipStreamSynchronize(st)); (void)hipFree(ix->search_counts); ix->search_counts = nullptr; ix->search_counts_cap = 0; }
-        AP_TRY(ap_dev_alloc(&ix->search_counts, (size_t)q->nq * 2));
-        ix->search_counts_cap = (size_t)q->nq * 2;
+        AP_TRY(ap_dev_alloc(&ix->search_counts, (size_t)q->nq * 3));
+        ix->search_counts_cap = (size_t)q->nq * 3;
     }
     if (!ix->ev_search[0]) {
         AP_CHECK_HIP(hipEventCreate(&ix->ev_search[0]));
@@ -236,27 +294,19 @@ extern "C" int ap_search_batch(ap_index *ix, const ap_queries *q, const float *p
     g.out_ids = out_ids;
     g.out_scores = out_scores;
     g.counts = ix->search_counts;
+    g.dnorm = ix->dense_norm;
     ix->last_nq = q->nq;
     AP_TRY(ap_fill_u32(ix->visited, need, 0u, st));
-    const size_t smem = (size_t)(2 * g.L + 2 * g.cmax) * 8 + (size_t)g.cmax * (8 + 8 + 4 + 4 + 4) + 4 * AP_Q_CAP * 4;
+    const size_t smem = (size_t)(g.L + 3 * g.cmax) * 8 + (size_t)g.cmax * (8 + 8 + 4 + 4 + 4 + 4) + 4 * AP_Q_CAP * 4;
     AP_CHECK_HIP(hipEventRecord(ix->ev_search[0], st));
     AP_REQUIRE(smem <= 160 * 1024, "beam and search_width need %zu bytes of LDS (limit 160 KiB)", smem);
     hipError_t le = hipSuccess;
-    static const int rows_in_flight = [] { const char *e = getenv("AP_SEARCH_ROWS_IN_FLIGHT"); return e ? atoi(e) : 1; }();
-#define AP_LAUNCH_SEARCH(GG)                                                                                     \
-    do {                                                                                                         \
-        if (smem > 48 * 1024)                                                                                    \
-            le = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_search<DT, NV, GG>),                      \
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);                     \
-        if (le == hipSuccess) hipLaunchKernelGGL((k_search<DT, NV, GG>), dim3((unsigned)q->nq), dim3(256), smem, st, g); \
-    } while (0)
     AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim, {
-        if (rows_in_flight <= 1) AP_LAUNCH_SEARCH(1);
-        else if (rows_in_flight == 2) AP_LAUNCH_SEARCH(2);
-        else if (rows_in_flight == 3) AP_LAUNCH_SEARCH(3);
-        else AP_LAUNCH_SEARCH(4);
+        if (smem > 48 * 1024)
+            le = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_search<DT, NV>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)smem);
+        if (le == hipSuccess) hipLaunchKernelGGL((k_search<DT, NV>), dim3((unsigned)q->nq), dim3(256), smem, st, g);
     });
-#undef AP_LAUNCH_SEARCH
     AP_CHECK_HIP(le);
     AP_CHECK_HIP(hipGetLastError());
     AP_CHECK_HIP(hipEventRecord(ix->ev_search[1], st));
@@ -270,7 +320,7 @@ extern "C" int ap_search_stats(const ap_index *ix, int32_t *out_counts, int32_t 
     if (kernel_ms) AP_CHECK_HIP(hipEventElapsedTime(kernel_ms, ix->ev_search[0], ix->ev_search[1]));
     if (out_counts) {
         AP_REQUIRE(nq == ix->last_nq, "nq = %d does not match the last search (%d)", nq, ix->last_nq);
-        AP_CHECK_HIP(hipMemcpyAsync(out_counts, ix->search_counts, (size_t)nq * 2 * sizeof(int32_t), hipMemcpyDeviceToDevice,
+        AP_CHECK_HIP(hipMemcpyAsync(out_counts, ix->search_counts, (size_t)nq * 3 * sizeof(int32_t), hipMemcpyDeviceToDevice,
                                     (hipStream_t)stream));
     }
     return AP_OK;
