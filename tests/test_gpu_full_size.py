@@ -1,0 +1,190 @@
+"""Parity at the full size of the benchmark workload (config 2: 100,000
+documents, d = 768, 10,000 queries) in the launch configuration bench.py
+times, on sampled outputs the oracle can compute one by one; plus the
+dynamic-fusion sweep of config 4 (five weight settings on the same index, no
+rebuild)."""
+import time
+import types
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from paper_2511_00855_amd import binding as B
+from paper_2511_00855_amd.synth import make_workload
+from parity import RTOL_F32, assert_ranked_equiv, assert_scores_close, row_norms, score_tol
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+@pytest.fixture(scope="module")
+def full():
+    t0 = time.time()
+    w = make_workload("cfg2", seed=0)
+    _say(f"cfg2 generated in {time.time() - t0:.1f}s")
+    docs = B.DeviceVecs(w.docs)
+    qs = B.DeviceVecs(w.queries)
+    bp = B.build_params(w.degree)                      # what bench.py uses
+    t0 = time.time()
+    ix = B.Index.build(docs, bp)
+    torch.cuda.synchronize()
+    _say(f"built in {time.time() - t0:.2f}s {ix.build_timings()}")
+    D = O.encode_docs(w.docs)
+    Q = O.VS(w.queries)
+    yield w, docs, qs, bp, ix, D, Q
+    ix.close()
+
+
+def test_full_size_scores_sampled(full):
+    w, docs, qs, bp, ix, D, Q = full
+    _say("full size: sampled hybrid scores")
+    rng = np.random.default_rng(0)
+    nq, N = qs.n, docs.n
+    c = 64
+    cand = rng.integers(0, N, (nq, c)).astype(np.int32)
+    wq = rng.uniform(0, 1, (nq, 3)).astype(np.float32)
+    got = ix.hybrid_scores(qs, cand, wq).cpu().numpy()
+    rows = rng.choice(nq, 400, replace=False)
+    ref = O.hybrid_block(Q, rows, D, cand[rows], wq[rows])
+    qn = row_norms(w.queries)[rows][:, None]
+    dn = np.linalg.norm(w.docs.dense[cand[rows].ravel()].astype(np.float64), axis=1).reshape(len(rows), c)
+    assert_scores_close(got[rows], ref, score_tol(ref, wq[rows][:, None, :], qn, dn, RTOL_F32), "full-size scores")
+
+
+@pytest.mark.parametrize("beam", [128, 2304])
+def test_full_size_search_replay(full, beam):
+    """All 10,000 queries are searched exactly as bench.py does; for a sample the
+    oracle's search, replayed on the GPU's own scores, must return the same ids
+    and scores bit for bit."""
+    w, docs, qs, bp, ix, D, Q = full
+    _say(f"full size: search beam {beam}")
+    nq, N, k = qs.n, docs.n, w.k
+    wq = np.tile(np.float32(w.weights), (nq, 1))
+    ids, sc = [t.cpu().numpy() for t in ix.search_batch(qs, k, beam, wq)]
+    counts, ms = ix.search_stats(nq)
+    counts = counts.cpu().numpy()
+    sem, _, _, ent = [t.cpu().numpy() for t in ix.export_graph()]
+    sample = np.arange(0, nq, nq // 48)[:48]
+    # a query set holding only the sample, for the score table the replay runs on
+    sq = types.SimpleNamespace(n=len(sample), dim=w.queries.dim, dense=w.queries.dense[sample],
+                               sp_indptr=None, sp_idx=None, sp_val=None, tx_indptr=None, tx_idx=None, tx_val=None,
+                               sp_vocab=w.queries.sp_vocab, tx_vocab=w.queries.tx_vocab)
+    for pre in ("sp", "tx"):
+        ip = getattr(w.queries, pre + "_indptr")
+        lens = (ip[1:] - ip[:-1])[sample]
+        setattr(sq, pre + "_indptr", np.concatenate([[0], np.cumsum(lens)]).astype(np.int64))
+        setattr(sq, pre + "_idx", np.concatenate([getattr(w.queries, pre + "_idx")[ip[i]:ip[i + 1]] for i in sample]))
+        setattr(sq, pre + "_val", np.concatenate([getattr(w.queries, pre + "_val")[ip[i]:ip[i + 1]] for i in sample]))
+    dsq = B.DeviceVecs(sq)
+    allc = np.tile(np.arange(N, dtype=np.int32), (len(sample), 1))
+    table = ix.hybrid_scores(dsq, allc, wq[sample]).cpu().numpy()[:, :, 3]
+    for x, qi in enumerate(sample):
+        oi, os_, nv = O.search(D, sem, ent, Q, int(qi), wq[qi], k, beam, score_table=table[x])
+        assert np.array_equal(ids[qi], oi), (qi, beam)
+        assert np.array_equal(sc[qi], os_), (qi, beam)
+        assert counts[qi, 0] == nv, (qi, counts[qi], nv)     # the same documents were scored
+    # scores of the answers agree with the oracle's own arithmetic
+    ref = O.hybrid_block(Q, sample, D, ids[sample], wq[sample])
+    qn = row_norms(w.queries)[sample][:, None]
+    dn = np.linalg.norm(w.docs.dense[ids[sample].ravel()].astype(np.float64), axis=1).reshape(len(sample), k)
+    tol = score_tol(ref, wq[sample][:, None, :], qn, dn, RTOL_F32)[:, :, 3]
+    assert (np.abs(sc[sample] - ref[:, :, 3]) <= tol).all()
+    _say(f"  kernel {ms:.1f} ms, {counts[:, 0].mean():.0f} candidates/query, {counts[:, 2].sum() / counts[:, 0].sum():.2f} without dense row")
+
+
+def test_full_size_build_stages_sampled(full):
+    """Each construction stage re-run on the GPU for sampled nodes at full size
+    and compared with the oracle fed the same inputs."""
+    w, docs, qs, bp, ix, D, Q = full
+    N, R, K, S, P = docs.n, bp.degree, bp.knn_k, bp.nd_sample, (bp.degree + 5) // 6
+    wv = np.array([1, 1, 1], np.float32)
+    dn = row_norms(w.docs)
+    nodes = np.sort(np.random.default_rng(5).choice(N, 24, replace=False)).astype(np.int32)
+    _say("full size: seed")
+    ids, sc = [t.cpu().numpy() for t in ix.stage_seed_knn(K, nodes)]
+    oid, osc = O.seed_knn(D, nodes, K)
+    assert_ranked_equiv(ids, sc, oid, osc, lambda r, s: RTOL_F32 * dn[nodes[r]] * dn.max(),
+                        lambda r, j: float(np.dot(D.dense[nodes[r]].astype(np.float64), D.dense[j].astype(np.float64))), "seed")
+    _say("full size: refine")
+    seed_all, seed_sc = ix.stage_seed_knn(K)
+    spi = torch.full((3, N, P), -1, dtype=torch.int32, device=docs.device)
+    sps = torch.full((3, N, P), -np.inf, dtype=torch.float32, device=docs.device)
+    g = [t.cpu().numpy() for t in ix.stage_refine(K, S, P, seed_all, spi, sps, nodes)]
+    seed_np = seed_all.cpu().numpy()
+    o = O.refine_round(D, wv, K, S, P, seed_np, spi.cpu().numpy(), sps.cpu().numpy(), node_ids=nodes)
+
+    def oscore(r, j, col=3):
+        return float(O.hybrid_block(D, [nodes[r]], D, [[j]], wv)[0, 0, col])
+    assert_ranked_equiv(g[0], g[1], o[0], o[1], lambda r, s: RTOL_F32 * (dn[nodes[r]] * dn.max() + abs(s)), oscore, "refine")
+    for p in range(3):
+        tol = (lambda r, s: RTOL_F32 * dn[nodes[r]] * dn.max()) if p == 0 else (lambda r, s: RTOL_F32 * abs(s) + 1e-30)
+        assert_ranked_equiv(g[2][p], g[3][p], o[2][p], o[3][p], tol, lambda r, j, p=p: oscore(r, j, p), f"path list {p}")
+    _say("full size: prune")
+    # one full GPU round gives realistic lists for every node
+    ids1, sc1, spi1, sps1 = ix.stage_refine(K, S, P, seed_all, spi, sps)
+    pr = ix.stage_prune(K, R, ids1, sc1, nodes)
+    pm, count, sorted_ids, se, ke, ke_count, flag = [pr[n].cpu().numpy() for n in ("pm", "count", "sorted_ids", "se", "ke", "ke_count", "flag")]
+    ids1n, sc1n = ids1.cpu().numpy(), sc1.cpu().numpy()
+    self_gpu = ix.export_ingest()[3].cpu().numpy()
+    for x, u in enumerate(nodes):
+        idl = ids1n[u]
+        if x < 4:
+            opm = O.pairwise(D, wv, idl)
+            tol = RTOL_F32 * (np.outer(dn[idl], dn[idl]) + np.abs(opm))
+            assert (np.abs(pm[x] - opm) <= tol).all(), (u, np.max(np.abs(pm[x] - opm) / tol))
+        cnt, order = O.detour_sort(idl, sc1n[u], pm[x])
+        assert np.array_equal(count[x], cnt) and np.array_equal(sorted_ids[x], idl[order])
+        se_pos, ke_pos, fl = O.ip_prune(D, int(u), R, R // 2, idl, order, pm[x], self_gpu[idl])
+        assert np.array_equal(se[x][:len(se_pos)], idl[se_pos]) and (se[x][len(se_pos):] == -1).all()
+        assert ke_count[x] == len(ke_pos) and np.array_equal(ke[x][:len(ke_pos)], idl[ke_pos])
+        assert np.array_equal(flag[x], fl)
+    _say("full size: assemble")
+    allp = ix.stage_prune(K, R, ids1, sc1, want_pm=False)
+    graph = ix.stage_assemble(R, K, P, allp["se"], allp["sorted_ids"], spi1).cpu().numpy()
+    ref = O.assemble(N, R, K, P, allp["se"].cpu().numpy(), allp["sorted_ids"].cpu().numpy(), spi1.cpu().numpy(), node_ids=nodes)
+    assert np.array_equal(graph[nodes], ref)
+    assert np.array_equal(ix.stage_entry_points(64).cpu().numpy(), O.entry_points(self_gpu, 64))
+
+
+WEIGHT_SETTINGS = [(1, 0, 0), (0, 1, 0), (0, 0, 1), (0.5, 0.5, 0), (0.34, 0.33, 0.33)]
+
+
+@pytest.mark.parametrize("wset", WEIGHT_SETTINGS)
+def test_dynamic_fusion_sweep(full, wset):
+    """Config 4: the same index, no rebuild, searched under another weight
+    vector through set_weights; ground truth recomputed per setting."""
+    w, docs, qs, bp, ix, D, Q = full
+    nq, k = qs.n, w.k
+    graph_before = ix.export_graph()[0].clone()
+    ix.set_weights(wset)
+    t0 = time.time()
+    gt, gts = [t.cpu().numpy() for t in ix.bruteforce_topk(qs, k)]
+    # the exhaustive scorer itself against the oracle on a few queries
+    sample = np.arange(0, nq, nq // 6)[:6]
+    wrow = np.tile(np.float32(wset), (len(sample), 1))
+    oid, osc = O.bruteforce_topk(Q, sample, D, wrow, k)
+    qn = row_norms(w.queries); dmax = 1.0 + 1e-6
+
+    def oscore(r, j):
+        return float(O.hybrid_block(Q, [sample[r]], D, [[j]], wrow[r])[0, 0, 3])
+    assert_ranked_equiv(gt[sample], gts[sample], oid, osc, lambda r, s: RTOL_F32 * (abs(wset[0]) * qn[sample[r]] * dmax + abs(s)),
+                        oscore, f"ground truth {wset}")
+    res = []
+    for beam in (128, 1024):
+        ids, _ = ix.search_batch(qs, k, beam)            # default weights of the index
+        torch.cuda.synchronize()
+        t1 = time.time()
+        ids, _ = ix.search_batch(qs, k, beam)
+        torch.cuda.synchronize()
+        dt = time.time() - t1
+        rec = float(np.mean([len(set(a) & set(b)) / k for a, b in zip(ids.cpu().numpy(), gt)]))
+        res.append((beam, round(rec, 4), round(nq / dt)))
+    _say(f"weights {wset}: (beam, recall@10, qps) = {res}")
+    assert torch.equal(graph_before, ix.export_graph()[0])          # no rebuild happened
+    assert res[1][1] >= res[0][1] - 1e-9 and res[1][1] > 0.3
+    ix.set_weights(w.weights)
