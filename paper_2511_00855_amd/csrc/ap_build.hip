@@ -272,38 +272,20 @@ __global__ __launch_bounds__(256) void k_gram_dense(const void *dense, int32_t d
     });
 }
 
-// Sparse and lexical parts, and the fusion: one block per (neighbourhood,
-// block of CB columns).  The CB column documents' lists sit in LDS.  Each wave
-// walks the rows at or below the block's first column (the matrix is
-// symmetric: P[i][j] is computed once, for i >= j, and mirrored), and for its
-// current row builds two small open-addressing tables (term -> weight) in its
-// own LDS slice, so that looking a column entry up costs about one LDS probe
-// instead of a binary search.  A lane's partial sum is w_s*ps + w_f*pf, so one
-// wave reduction per pair suffices.
+// Sparse and lexical parts, and the fusion.  The 32 column documents' lists
+// of a block sit in LDS; the row document's lists are turned into two small
+// open-addressing tables (term -> weight), so that looking a column entry up
+// costs about one LDS probe instead of a binary search.  The matrix is
+// symmetric: P[i][j] is computed once, for i >= j, and mirrored.  A lane's
+// partial sum is w_s*ps + w_f*pf, so one wave reduction per pair suffices.
 #define AP_CB 32
 #define AP_CB_ENTRIES 5632
-#define AP_SP_SLOTS 512     // sparse table slots per wave (row lists up to 256 entries)
-#define AP_TX_SLOTS 256     // lexical table slots per wave (row lists up to 128 entries)
+#define AP_SP_SLOTS 1024    // sparse table slots (row lists up to 256 entries: at most a quarter full)
+#define AP_SP_BITS 10
+#define AP_TX_SLOTS 512     // lexical table slots (row lists up to 128 entries)
+#define AP_TX_BITS 9
 
 __device__ __forceinline__ uint32_t ap_term_hash(int32_t t, int bits) { return ((uint32_t)t * 2654435761u) >> (32 - bits); }
-
-// Fills an empty table (all terms -1) with the list [g0, g0+n) of global memory.
-__device__ __forceinline__ void ap_table_build(int2 *tab, int slots, int bits, const int32_t *gi, const float *gv, int64_t g0,
-                                               int32_t n, int lane) {
-    for (int i = lane; i < slots; i += 64) tab[i] = make_int2(-1, 0);
-    __builtin_amdgcn_wave_barrier();
-    for (int32_t e = lane; e < n; e += 64) {
-        const int32_t t = gi[g0 + e];
-        const int32_t vb = __float_as_int(gv[g0 + e]);
-        uint32_t h = ap_term_hash(t, bits);
-        for (;;) {
-            const int32_t old = atomicCAS(&tab[h].x, -1, t);
-            if (old == -1) { tab[h].y = vb; break; }
-            h = (h + 1) & (slots - 1);
-        }
-    }
-    __builtin_amdgcn_wave_barrier();
-}
 
 // Weight of term t in the table, 0 if absent (t = -1 is never present).  A
 // slot is read as one 64-bit word: term in the low half, weight bits in the high half.
@@ -331,49 +313,68 @@ __device__ __forceinline__ void ap_table_get_many(const AP_LDS uint64_t *tsp, co
     bool any = false;
 #pragma unroll
     for (int k = 0; k < NL; k++) {
-        h[k] = ap_term_hash(term[k], k < NSP ? 9 : 8);
+        h[k] = ap_term_hash(term[k], k < NSP ? AP_SP_BITS : AP_TX_BITS);
         val[k] = 0.f;
         pend[k] = term[k] >= 0;
         any = any || pend[k];
     }
     while (__any(any)) {
+        // straight-line code: every look-up reads its current slot (a finished one re-reads harmlessly)
         uint64_t e[NL];
 #pragma unroll
-        for (int k = 0; k < NL; k++) {
-            e[k] = 0xffffffffull;
-            if (pend[k]) { if (k < NSP) e[k] = tsp[h[k]]; else e[k] = ttx[h[k]]; }
-        }
+        for (int k = 0; k < NL; k++) e[k] = k < NSP ? tsp[h[k]] : ttx[h[k]];
         any = false;
 #pragma unroll
         for (int k = 0; k < NL; k++) {
-            if (pend[k]) {
-                const int32_t et = (int32_t)(uint32_t)e[k];
-                if (et == term[k]) { val[k] = __uint_as_float((uint32_t)(e[k] >> 32)); pend[k] = false; }
-                else if (et == -1) pend[k] = false;
-                else h[k] = (h[k] + 1) & ((k < NSP ? AP_SP_SLOTS : AP_TX_SLOTS) - 1);
-            }
-            any = any || pend[k];
+            const int32_t et = (int32_t)(uint32_t)e[k];
+            const bool hit = pend[k] & (et == term[k]);
+            val[k] = hit ? __uint_as_float((uint32_t)(e[k] >> 32)) : val[k];
+            pend[k] = pend[k] & (et != term[k]) & (et != -1);
+            h[k] = (h[k] + 1) & ((k < NSP ? AP_SP_SLOTS : AP_TX_SLOTS) - 1);
+            any = any | pend[k];
         }
     }
 }
 
+// Inserts (term, weight bits) into an open-addressing table that holds no such term yet.
+__device__ __forceinline__ void ap_table_put(uint64_t *tab, int slots, int bits, int32_t t, int32_t vb) {
+    int32_t *w32 = reinterpret_cast<int32_t *>(tab);
+    uint32_t h = ap_term_hash(t, bits);
+    for (;;) {
+        const int32_t old = atomicCAS(&w32[2 * h], -1, t);
+        if (old == -1) { w32[2 * h + 1] = vb; return; }
+        h = (h + 1) & (slots - 1);
+    }
+}
+
+#define AP_GRAM_THREADS 512
+#define AP_GRAM_WAVES 8
+#define AP_GC 4     // columns per wave per row: AP_GRAM_WAVES * AP_GC == AP_CB
+
+// One 512-thread block per (neighbourhood, block of 32 columns).  Rows i >= j0
+// are taken one after the other by the whole block: the row document's two
+// tables are shared (double buffered: while row i is being used, the entries
+// of row i+1 are already on their way from global memory), and wave w handles
+// columns j0+4w .. j0+4w+3 of the row, all twelve list slots in flight at once.
 template <int DT>
-__global__ __launch_bounds__(256) void k_gram_sparse(ApVecs D, float wd, float ws, float wf, int32_t K,
-                                                     const int32_t *__restrict__ knn, const int32_t *__restrict__ node_ids,
-                                                     int64_t x0, float *__restrict__ pm) {
+__global__ __launch_bounds__(AP_GRAM_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_gram_sparse(ApVecs D, float wd, float ws, float wf, int32_t K,
+                                                                const int32_t *__restrict__ knn,
+                                                                const int32_t *__restrict__ node_ids, int64_t x0,
+                                                                float *__restrict__ pm) {
     __shared__ int32_t b_idx[AP_CB_ENTRIES];
     __shared__ float b_val[AP_CB_ENTRIES];
-    __shared__ int32_t b_off[2][AP_CB + 1];       // offsets into b_idx/b_val, or -1 when the list stayed in global memory
+    __shared__ int32_t b_off[2][AP_CB];           // offsets into b_idx/b_val, or -1 when the list stayed in global memory
     __shared__ int32_t b_len[2][AP_CB];
     __shared__ int32_t b_id[AP_CB];
-    __shared__ int2 t_sp[4][AP_SP_SLOTS];
-    __shared__ int2 t_tx[4][AP_TX_SLOTS];
+    __shared__ uint64_t t_sp[2][AP_SP_SLOTS];
+    __shared__ uint64_t t_tx[2][AP_TX_SLOTS];
+    __shared__ int32_t r_id[256], r_spn[256], r_txn[256];
+    __shared__ int64_t r_spb[256], r_txb[256];
     const int64_t x = blockIdx.y;
     const int64_t u = node_ids ? (int64_t)node_ids[x0 + x] : x0 + x;
     const int32_t j0 = blockIdx.x * AP_CB;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    // plan the LDS layout of the column lists: lane 2c+part of wave 0 owns list `part` of column c;
-    // offsets are an exclusive prefix sum of the lengths, lists past the capacity stay in global memory
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // layout of the column lists: lane 2c+part of wave 0 owns list `part` of column c
     if (wave == 0) {
         const int c = lane >> 1, part = lane & 1;
         const int32_t v = j0 + c < K ? knn[u * K + j0 + c] : -1;
@@ -388,6 +389,16 @@ __global__ __launch_bounds__(256) void k_gram_sparse(ApVecs D, float wd, float w
         b_len[part][c] = len;
         b_off[part][c] = incl <= AP_CB_ENTRIES ? incl - len : -1;
     }
+    // where the row documents' lists are (rows j0 .. K-1)
+    for (int32_t i = j0 + tid; i < K; i += AP_GRAM_THREADS) {
+        const int32_t a = knn[u * K + i];
+        r_id[i] = a;
+        if (a >= 0) {
+            const int64_t sb = D.sp_indptr[a], tb = D.tx_indptr[a];
+            r_spb[i] = sb; r_spn[i] = (int32_t)(D.sp_indptr[a + 1] - sb);
+            r_txb[i] = tb; r_txn[i] = (int32_t)(D.tx_indptr[a + 1] - tb);
+        } else { r_spb[i] = 0; r_spn[i] = 0; r_txb[i] = 0; r_txn[i] = 0; }
+    }
     __syncthreads();
     for (int c = 0; c < AP_CB; c++) {
         const int32_t v = b_id[c];
@@ -398,114 +409,113 @@ __global__ __launch_bounds__(256) void k_gram_sparse(ApVecs D, float wd, float w
             const int64_t g0 = part == 0 ? D.sp_indptr[v] : D.tx_indptr[v];
             const int32_t *gi = part == 0 ? D.sp_idx : D.tx_idx;
             const float *gv = part == 0 ? D.sp_val : D.tx_val;
-            for (int32_t e = threadIdx.x; e < len; e += blockDim.x) { b_idx[off + e] = gi[g0 + e]; b_val[off + e] = gv[g0 + e]; }
+            for (int32_t e = tid; e < len; e += AP_GRAM_THREADS) { b_idx[off + e] = gi[g0 + e]; b_val[off + e] = gv[g0 + e]; }
         }
     }
+    // a row whose lists fit the tables is "tabled": thread t holds entry t of the row (sparse entries first)
+    auto row_tabled = [&](int32_t i) { return r_id[i] >= 0 && r_spn[i] <= AP_SP_SLOTS / 4 && r_txn[i] <= AP_TX_SLOTS / 4; };
+    auto fetch = [&](int32_t i, int32_t &t, int32_t &vb, int &which) {
+        which = -1;
+        if (i >= K || !row_tabled(i)) return;
+        const int32_t sn = r_spn[i], tn = r_txn[i];
+        if (tid < sn) { t = D.sp_idx[r_spb[i] + tid]; vb = __float_as_int(D.sp_val[r_spb[i] + tid]); which = 0; }
+        else if (tid < sn + tn) { t = D.tx_idx[r_txb[i] + tid - sn]; vb = __float_as_int(D.tx_val[r_txb[i] + tid - sn]); which = 1; }
+    };
+    auto clear = [&](int buf) {
+        for (int s2 = tid; s2 < AP_SP_SLOTS; s2 += AP_GRAM_THREADS) t_sp[buf][s2] = 0xffffffffull;
+        for (int s2 = tid; s2 < AP_TX_SLOTS; s2 += AP_GRAM_THREADS) t_tx[buf][s2] = 0xffffffffull;
+    };
+    int32_t pf_t = 0, pf_v = 0; int pf_which;
+    clear(0);
+    fetch(j0, pf_t, pf_v, pf_which);
+    __syncthreads();
+    if (pf_which == 0) ap_table_put(t_sp[0], AP_SP_SLOTS, AP_SP_BITS, pf_t, pf_v);
+    else if (pf_which == 1) ap_table_put(t_tx[0], AP_TX_SLOTS, AP_TX_BITS, pf_t, pf_v);
     __syncthreads();
     float *out = pm + x * (int64_t)K * K;
-    for (int32_t i = j0 + wave; i < K; i += 4) {
-        const int32_t a = knn[u * K + i];
-        int32_t an_sp = 0, an_tx = 0;
-        int64_t a_sp0 = 0, a_tx0 = 0;
-        bool tab_sp = false, tab_tx = false;
-        if (a >= 0) {
-            a_sp0 = D.sp_indptr[a]; an_sp = (int32_t)(D.sp_indptr[a + 1] - a_sp0);
-            a_tx0 = D.tx_indptr[a]; an_tx = (int32_t)(D.tx_indptr[a + 1] - a_tx0);
-            tab_sp = an_sp <= AP_SP_SLOTS / 2;
-            tab_tx = an_tx <= AP_TX_SLOTS / 2;
-            if (tab_sp) ap_table_build(t_sp[wave], AP_SP_SLOTS, 9, D.sp_idx, D.sp_val, a_sp0, an_sp, lane);
-            if (tab_tx) ap_table_build(t_tx[wave], AP_TX_SLOTS, 8, D.tx_idx, D.tx_val, a_tx0, an_tx, lane);
-        }
-        const int32_t cmax = i - j0 < AP_CB - 1 ? i - j0 : AP_CB - 1;   // columns j <= i of this block
-        // the dense products of this row's pairs, one coalesced load (lane c holds column j0 + c)
-        const float g_row = (lane <= cmax && j0 + lane < K) ? out[(int64_t)i * K + j0 + lane] : 0.f;
-        float my_val = 0.f;
-        const int32_t clast = cmax < K - 1 - j0 ? cmax : K - 1 - j0;   // last column of this row in the block
-        constexpr int GC = 4;                                          // columns in flight per wave
-        for (int c0 = 0; c0 <= clast; c0 += GC) {
-            bool fast = a >= 0 && tab_sp && tab_tx;
+    const AP_LDS int32_t *lb_idx = (const AP_LDS int32_t *)b_idx;
+    const AP_LDS float *lb_val = (const AP_LDS float *)b_val;
+    for (int32_t i = j0; i < K; i++) {
+        const int cur = (i - j0) & 1, nxt = cur ^ 1;
+        fetch(i + 1, pf_t, pf_v, pf_which);          // next row's entries: in flight during this row's work
+        clear(nxt);
+        const int32_t a = r_id[i];
+        const bool tabled = row_tabled(i);
+        const int32_t clast = (i - j0 < AP_CB - 1 ? i - j0 : AP_CB - 1) < K - 1 - j0 ? (i - j0 < AP_CB - 1 ? i - j0 : AP_CB - 1) : K - 1 - j0;
+        const int c0 = wave * AP_GC;
+        if (c0 <= clast) {
+            const float g_mine = (lane < AP_GC && c0 + lane <= clast) ? out[(int64_t)i * K + j0 + c0 + lane] : 0.f;
+            bool fast = tabled;
 #pragma unroll
-            for (int g = 0; g < GC; g++)
-                if (c0 + g <= clast) fast = fast && b_id[c0 + g] >= 0 && b_off[0][c0 + g] >= 0 && b_off[1][c0 + g] >= 0;
-            float pr[GC];
+            for (int gq = 0; gq < AP_GC; gq++)
+                if (c0 + gq <= clast) fast = fast && b_id[c0 + gq] >= 0 && b_off[0][c0 + gq] >= 0 && b_off[1][c0 + gq] >= 0;
+            float pr[AP_GC];
             if (fast) {
-                // column lists and row tables all in LDS: 2 sparse slots + 1 lexical slot per column, all in flight together
-                const AP_LDS int32_t *lb_idx = (const AP_LDS int32_t *)b_idx;
-                const AP_LDS float *lb_val = (const AP_LDS float *)b_val;
-                const AP_LDS uint64_t *tsp = (const AP_LDS uint64_t *)t_sp[wave];
-                const AP_LDS uint64_t *ttx = (const AP_LDS uint64_t *)t_tx[wave];
-                int32_t term[GC][3];
-                float bval[GC][3], aval[GC][3];
+                const AP_LDS uint64_t *tsp = (const AP_LDS uint64_t *)t_sp[cur];
+                const AP_LDS uint64_t *ttx = (const AP_LDS uint64_t *)t_tx[cur];
+                int32_t term[3 * AP_GC];
+                float bval[3 * AP_GC], aval[3 * AP_GC];
 #pragma unroll
-                for (int g = 0; g < GC; g++) {
-                    const int c = c0 + g <= clast ? c0 + g : clast;
-                    const int32_t so = b_off[0][c], sn = c0 + g <= clast ? b_len[0][c] : 0;
-                    const int32_t to = b_off[1][c], tn = c0 + g <= clast ? b_len[1][c] : 0;
-                    term[g][0] = lane < sn ? lb_idx[so + lane] : -1;        bval[g][0] = lane < sn ? lb_val[so + lane] : 0.f;
-                    term[g][1] = lane + 64 < sn ? lb_idx[so + 64 + lane] : -1; bval[g][1] = lane + 64 < sn ? lb_val[so + 64 + lane] : 0.f;
-                    term[g][2] = lane < tn ? lb_idx[to + lane] : -1;        bval[g][2] = lane < tn ? lb_val[to + lane] : 0.f;
+                for (int gq = 0; gq < AP_GC; gq++) {
+                    const int c = c0 + gq <= clast ? c0 + gq : clast;
+                    const int32_t so = b_off[0][c], sn = c0 + gq <= clast ? b_len[0][c] : 0;
+                    const int32_t to = b_off[1][c], tn = c0 + gq <= clast ? b_len[1][c] : 0;
+                    // look-ups 0..2GC-1 use the sparse table, 2GC..3GC-1 the lexical one
+                    term[2 * gq] = lane < sn ? lb_idx[so + lane] : -1;             bval[2 * gq] = lane < sn ? lb_val[so + lane] : 0.f;
+                    term[2 * gq + 1] = lane + 64 < sn ? lb_idx[so + 64 + lane] : -1; bval[2 * gq + 1] = lane + 64 < sn ? lb_val[so + 64 + lane] : 0.f;
+                    term[2 * AP_GC + gq] = lane < tn ? lb_idx[to + lane] : -1;      bval[2 * AP_GC + gq] = lane < tn ? lb_val[to + lane] : 0.f;
                 }
-                {
-                    // look-ups ordered so that the first 2*GC use the sparse table, the last GC the lexical one
-                    int32_t tt[3 * GC]; float vv[3 * GC];
+                ap_table_get_many<3 * AP_GC, 2 * AP_GC>(tsp, ttx, term, aval);
 #pragma unroll
-                    for (int g = 0; g < GC; g++) { tt[2 * g] = term[g][0]; tt[2 * g + 1] = term[g][1]; tt[2 * GC + g] = term[g][2]; }
-                    ap_table_get_many<3 * GC, 2 * GC>(tsp, ttx, tt, vv);
-#pragma unroll
-                    for (int g = 0; g < GC; g++) { aval[g][0] = vv[2 * g]; aval[g][1] = vv[2 * g + 1]; aval[g][2] = vv[2 * GC + g]; }
-                }
-#pragma unroll
-                for (int g = 0; g < GC; g++) {
-                    const int c = c0 + g <= clast ? c0 + g : clast;
-                    const int32_t so = b_off[0][c], sn = c0 + g <= clast ? b_len[0][c] : 0;
-                    const int32_t to = b_off[1][c], tn = c0 + g <= clast ? b_len[1][c] : 0;
-                    float qs = fmaf(aval[g][1], bval[g][1], aval[g][0] * bval[g][0]);
-                    for (int32_t e = 128 + lane; e < sn; e += 64) qs = fmaf(ap_table_get(tsp, AP_SP_SLOTS, 9, lb_idx[so + e]), lb_val[so + e], qs);
-                    float qt = aval[g][2] * bval[g][2];
-                    for (int32_t e = 64 + lane; e < tn; e += 64) qt = fmaf(ap_table_get(ttx, AP_TX_SLOTS, 8, lb_idx[to + e]), lb_val[to + e], qt);
-                    pr[g] = fmaf(wf, qt, ws * qs);
+                for (int gq = 0; gq < AP_GC; gq++) {
+                    const int c = c0 + gq <= clast ? c0 + gq : clast;
+                    const int32_t so = b_off[0][c], sn = c0 + gq <= clast ? b_len[0][c] : 0;
+                    const int32_t to = b_off[1][c], tn = c0 + gq <= clast ? b_len[1][c] : 0;
+                    float qs = fmaf(aval[2 * gq + 1], bval[2 * gq + 1], aval[2 * gq] * bval[2 * gq]);
+                    for (int32_t e = 128 + lane; e < sn; e += 64) qs = fmaf(ap_table_get(tsp, AP_SP_SLOTS, AP_SP_BITS, lb_idx[so + e]), lb_val[so + e], qs);
+                    float qt = aval[2 * AP_GC + gq] * bval[2 * AP_GC + gq];
+                    for (int32_t e = 64 + lane; e < tn; e += 64) qt = fmaf(ap_table_get(ttx, AP_TX_SLOTS, AP_TX_BITS, lb_idx[to + e]), lb_val[to + e], qt);
+                    pr[gq] = fmaf(wf, qt, ws * qs);
                 }
             } else {
+                // a list that did not fit (column list not in LDS, or row list too long for the tables): plain search
 #pragma unroll
-                for (int g = 0; g < GC; g++) {
-                    pr[g] = 0.f;
-                    const int c = c0 + g;
+                for (int gq = 0; gq < AP_GC; gq++) {
+                    pr[gq] = 0.f;
+                    const int c = c0 + gq;
                     if (c > clast || a < 0 || b_id[c] < 0) continue;
                     const int32_t b = b_id[c];
                     float q2[2];
                     for (int part = 0; part < 2; part++) {
                         const int32_t off = b_off[part][c], len = b_len[part][c];
-                        const bool tab = part == 0 ? tab_sp : tab_tx;
                         const int32_t *bi; const float *bv; int64_t beg;
                         if (off >= 0) { bi = b_idx; bv = b_val; beg = off; }
                         else { bi = part == 0 ? D.sp_idx : D.tx_idx; bv = part == 0 ? D.sp_val : D.tx_val; beg = part == 0 ? D.sp_indptr[b] : D.tx_indptr[b]; }
-                        float q = 0.f;
-                        if (tab) {
-                            for (int32_t e = lane; e < len; e += 64) {
-                                const float av = part == 0 ? ap_table_get((const uint64_t *)t_sp[wave], AP_SP_SLOTS, 9, bi[beg + e])
-                                                           : ap_table_get((const uint64_t *)t_tx[wave], AP_TX_SLOTS, 8, bi[beg + e]);
-                                q = fmaf(av, bv[beg + e], q);
-                            }
-                        } else {   // a row list too long for the table: search it in global memory
-                            q = ap_sparse_partial(part == 0 ? D.sp_idx + a_sp0 : D.tx_idx + a_tx0, part == 0 ? D.sp_val + a_sp0 : D.tx_val + a_tx0,
-                                                  part == 0 ? an_sp : an_tx, bi, bv, beg, beg + len, lane);
-                        }
-                        q2[part] = q;
+                        q2[part] = ap_sparse_partial(part == 0 ? D.sp_idx + r_spb[i] : D.tx_idx + r_txb[i],
+                                                     part == 0 ? D.sp_val + r_spb[i] : D.tx_val + r_txb[i],
+                                                     part == 0 ? r_spn[i] : r_txn[i], bi, bv, beg, beg + len, lane);
                     }
-                    pr[g] = fmaf(wf, q2[1], ws * q2[0]);
+                    pr[gq] = fmaf(wf, q2[1], ws * q2[0]);
                 }
             }
+            float my_val = 0.f;
 #pragma unroll
-            for (int g = 0; g < GC; g++) {
-                const int c = c0 + g;
+            for (int gq = 0; gq < AP_GC; gq++) {
+                const int c = c0 + gq;
                 if (c > clast) continue;
                 float val = -INFINITY;
-                if (a >= 0 && b_id[c] >= 0) val = fmaf(wd, __shfl(g_row, c, 64), ap_wave_sum(pr[g]));
-                if (lane == c) my_val = val;
+                if (a >= 0 && b_id[c] >= 0) val = fmaf(wd, __shfl(g_mine, gq, 64), ap_wave_sum(pr[gq]));
+                if (lane == gq) my_val = val;
+            }
+            if (lane < AP_GC && c0 + lane <= clast) {
+                out[(int64_t)i * K + j0 + c0 + lane] = my_val;
+                out[(int64_t)(j0 + c0 + lane) * K + i] = my_val;
             }
         }
-        if (lane <= cmax && j0 + lane < K) { out[(int64_t)i * K + j0 + lane] = my_val; out[(int64_t)(j0 + lane) * K + i] = my_val; }
-        __builtin_amdgcn_wave_barrier();
+        __syncthreads();     // table `nxt` is clear and nobody reads table `cur` any more
+        if (pf_which == 0) ap_table_put(t_sp[nxt], AP_SP_SLOTS, AP_SP_BITS, pf_t, pf_v);
+        else if (pf_which == 1) ap_table_put(t_tx[nxt], AP_TX_SLOTS, AP_TX_BITS, pf_t, pf_v);
+        __syncthreads();     // table `nxt` holds row i+1
     }
 }
 
@@ -656,9 +666,9 @@ static int prune_impl(const ap_index *ix, int32_t K, int32_t R, const int32_t *k
             if (e != hipSuccess) break;
             dim3 g2((unsigned)((K + AP_CB - 1) / AP_CB), (unsigned)yn);
             if (ix->dtype == AP_F32)
-                hipLaunchKernelGGL(k_gram_sparse<AP_F32>, g2, dim3(256), 0, st, ix->docs, w[0], w[1], w[2], K, knn_ids, node_ids, x0 + y0, pm + y0 * per);
+                hipLaunchKernelGGL(k_gram_sparse<AP_F32>, g2, dim3(AP_GRAM_THREADS), 0, st, ix->docs, w[0], w[1], w[2], K, knn_ids, node_ids, x0 + y0, pm + y0 * per);
             else
-                hipLaunchKernelGGL(k_gram_sparse<AP_BF16>, g2, dim3(256), 0, st, ix->docs, w[0], w[1], w[2], K, knn_ids, node_ids, x0 + y0, pm + y0 * per);
+                hipLaunchKernelGGL(k_gram_sparse<AP_BF16>, g2, dim3(AP_GRAM_THREADS), 0, st, ix->docs, w[0], w[1], w[2], K, knn_ids, node_ids, x0 + y0, pm + y0 * per);
             e = hipGetLastError();
         }
         if (e != hipSuccess) break;

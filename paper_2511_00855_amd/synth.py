@@ -84,42 +84,73 @@ def _bags(rng, cdf, perm, counts: np.ndarray) -> Tuple[np.ndarray, np.ndarray, n
     return indptr, t, cnt.astype(np.float32)
 
 
+def _first_distinct(draws: np.ndarray, need: np.ndarray) -> np.ndarray:
+    """Mask of the first need[r] distinct values of row r of `draws`, in draw order (negative = void)."""
+    order = np.argsort(draws, axis=1, kind="stable")
+    srt = np.take_along_axis(draws, order, axis=1)
+    first_sorted = np.ones_like(srt, dtype=bool)
+    first_sorted[:, 1:] = srt[:, 1:] != srt[:, :-1]
+    first_sorted &= srt >= 0
+    first = np.zeros_like(first_sorted)
+    np.put_along_axis(first, order, first_sorted, axis=1)
+    return first & (np.cumsum(first, axis=1) <= need[:, None])
+
+
 def _distinct_sets(rng, cdf, perm, counts: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
-    """Per row, `counts[i]` DISTINCT Zipf term ids (keep drawing until distinct), sorted."""
+    """Per row, `counts[i]` DISTINCT Zipf term ids (keep drawing until distinct), sorted.
+
+    Rows are handled in blocks: every row of a block draws the same number of
+    candidates (enough for almost all rows) and keeps its first `counts[i]`
+    distinct ones in draw order; the few rows that still lack ids keep drawing."""
     n = len(counts)
     vocab = len(cdf)
-    counts = np.minimum(counts, vocab)
-    have = [np.empty(0, dtype=np.int64) for _ in range(n)]
-    need = counts.copy()
-    todo = np.nonzero(need > 0)[0]
-    # rounds of oversampled draws; a row keeps its first `need` new distinct ids
-    while len(todo):
-        over = (need[todo] * 2 + 8).astype(np.int64)
-        rows = np.repeat(todo, over)
-        toks = _draw_terms(rng, cdf, perm, int(over.sum())).astype(np.int64)
-        start = np.concatenate([[0], np.cumsum(over)])
-        for k, i in enumerate(todo):
-            seg = toks[start[k]:start[k + 1]]
-            # first occurrences, in draw order
-            _, first = np.unique(seg, return_index=True)
-            seg = seg[np.sort(first)]
-            if len(have[i]):
-                seg = seg[~np.isin(seg, have[i])]
-            take = seg[: need[i]]
-            have[i] = np.concatenate([have[i], take])
-            need[i] -= len(take)
-        todo = todo[need[todo] > 0]
+    counts = np.minimum(counts, vocab).astype(np.int64)
     indptr = np.zeros(n + 1, dtype=np.int64)
     np.cumsum(counts, out=indptr[1:])
-    idx = np.concatenate([np.sort(h) for h in have]).astype(np.int32) if n else np.empty(0, np.int32)
-    return indptr, idx
+    out = np.empty(int(indptr[-1]), dtype=np.int32)
+    block = 65536
+    for b0 in range(0, n, block):
+        b1 = min(n, b0 + block)
+        need = counts[b0:b1]
+        rows = np.nonzero(need > 0)[0]
+        if not len(rows):
+            continue
+        m = int(need.max()) * 2 + 8
+        draws = _draw_terms(rng, cdf, perm, len(rows) * m).astype(np.int32).reshape(len(rows), m)
+        keep = _first_distinct(draws, need[rows])
+        nk = keep.sum(axis=1)
+        done = nk == need[rows]
+        # complete rows: sort each row's ids and store, all at once
+        kd = keep[done]
+        vals = draws[done][kd]
+        rid = np.repeat(np.arange(int(done.sum())), nk[done])
+        o = np.lexsort((vals, rid))
+        starts = indptr[b0 + rows[done]]
+        seg0 = np.concatenate([[0], np.cumsum(nk[done])])[:-1]
+        dest = starts[rid] + (np.arange(len(vals)) - seg0[rid])
+        out[dest] = vals[o]
+        # the rest keep drawing, one row at a time
+        for r in np.nonzero(~done)[0]:
+            i = rows[r]
+            have = draws[r][keep[r]]
+            while len(have) < need[i]:
+                extra = _draw_terms(rng, cdf, perm, int(need[i]) * 2 + 8).astype(np.int32)
+                extra = extra[~np.isin(extra, have)]
+                _, f = np.unique(extra, return_index=True)
+                have = np.concatenate([have, extra[np.sort(f)][: need[i] - len(have)]])
+            out[indptr[b0 + i]:indptr[b0 + i + 1]] = np.sort(have)
+    return indptr, out
 
 
 def f32_to_bf16_rne(x: np.ndarray) -> np.ndarray:
     """fp32 -> bf16 bit patterns, round-to-nearest-even (storage format conversion only)."""
-    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
-    r = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
-    return r
+    flat = np.ascontiguousarray(x, dtype=np.float32).reshape(-1)
+    out = np.empty(flat.shape, dtype=np.uint16)
+    step = 1 << 24
+    for a in range(0, len(flat), step):
+        u = flat[a:a + step].view(np.uint32).astype(np.uint64)
+        out[a:a + step] = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+    return out.reshape(np.shape(x))
 
 
 def bf16_to_f32(b: np.ndarray) -> np.ndarray:
