@@ -4,6 +4,7 @@
 // keyword recycling, and assembly of the fixed-degree edge lists.
 // Every stage is a pure function of the previous stage's arrays; nothing that
 // decides an id depends on the order in which atomics arrive.
+#include <stdlib.h>
 #include <algorithm>
 #include "ap_tiles.hpp"
 
@@ -16,27 +17,58 @@ int ap_alloc_graph(ap_index *ix);
 // scores[r][j] = <dense[node r], dense[j]> for a slab of rows and all columns.
 template <int DT>
 __global__ __launch_bounds__(256) void k_seed_scores(const void *dense, int32_t dim, int64_t n, const int32_t *node_ids,
-                                                     int64_t row0, int64_t nrows, float *__restrict__ scores) {
-    __shared__ float lA[AP_TILE * AP_LDS_STRIDE];
-    __shared__ float lB[AP_TILE * AP_LDS_STRIDE];
+                                                     int64_t row0, int64_t nrows, int64_t col0, int64_t ncols,
+                                                     float *__restrict__ scores /* nrows x ncols */) {
+    __shared__ __attribute__((aligned(16))) unsigned char lds[AP_TILE_LDS_BYTES];
     __shared__ int32_t a_rows[AP_TILE], b_rows[AP_TILE];
     const int64_t i0 = (int64_t)blockIdx.y * AP_TILE, j0 = (int64_t)blockIdx.x * AP_TILE;
     if (threadIdx.x < AP_TILE) {
         const int64_t r = i0 + threadIdx.x;
         a_rows[threadIdx.x] = r < nrows ? (node_ids ? node_ids[row0 + r] : (int32_t)(row0 + r)) : -1;
         const int64_t j = j0 + threadIdx.x;
+        b_rows[threadIdx.x] = j < ncols ? (int32_t)(col0 + j) : -1;
+    }
+    ap_f32x16 acc[2][2];
+    ap_tile_product<DT>(dense, dim, a_rows, b_rows, lds, acc);
+    ap_tile_foreach(acc, [&](int i, int j, float v) {
+        if (i0 + i < nrows && j0 + j < ncols) scores[(i0 + i) * ncols + (j0 + j)] = v;
+    });
+}
+
+// The same product over all columns, but instead of storing the scores, every
+// score that reaches its row's threshold tau (a lower bound of the row's K-th
+// best, found on a sample of the columns) is appended to the row's candidate
+// buffer as a ranking key.  cnt[r] counts the appends (also those beyond cap).
+template <int DT>
+__global__ __launch_bounds__(256) void k_seed_thresh(const void *dense, int32_t dim, int64_t n, const int32_t *node_ids,
+                                                     int64_t row0, int64_t nrows, const float *__restrict__ tau,
+                                                     unsigned long long *__restrict__ buf, int32_t cap,
+                                                     int32_t *__restrict__ cnt) {
+    __shared__ __attribute__((aligned(16))) unsigned char lds[AP_TILE_LDS_BYTES];
+    __shared__ int32_t a_rows[AP_TILE], b_rows[AP_TILE];
+    __shared__ float s_tau[AP_TILE];
+    const int64_t i0 = (int64_t)blockIdx.y * AP_TILE, j0 = (int64_t)blockIdx.x * AP_TILE;
+    if (threadIdx.x < AP_TILE) {
+        const int64_t r = i0 + threadIdx.x;
+        a_rows[threadIdx.x] = r < nrows ? (node_ids ? node_ids[row0 + r] : (int32_t)(row0 + r)) : -1;
+        s_tau[threadIdx.x] = r < nrows ? tau[r] : INFINITY;
+        const int64_t j = j0 + threadIdx.x;
         b_rows[threadIdx.x] = j < n ? (int32_t)j : -1;
     }
     ap_f32x16 acc[2][2];
-    ap_tile_gemm<DT>(dense, dim, a_rows, b_rows, lA, lB, acc);
+    ap_tile_product<DT>(dense, dim, a_rows, b_rows, lds, acc);
     ap_tile_foreach(acc, [&](int i, int j, float v) {
-        if (i0 + i < nrows && j0 + j < n) scores[(i0 + i) * n + (j0 + j)] = v;
+        if (i0 + i < nrows && j0 + j < n && v >= s_tau[i] && a_rows[i] != (int32_t)(j0 + j)) {
+            const int32_t pos = atomicAdd(&cnt[i0 + i], 1);
+            if (pos < cap) buf[(i0 + i) * (int64_t)cap + pos] = ap_make_key(v, (int32_t)(j0 + j), 1u);
+        }
     });
 }
 
 // One block per row: exact top-K of the row (excluding the node itself), sorted.
-__global__ __launch_bounds__(256) void k_select_rows(const float *__restrict__ scores, int64_t n, int32_t K,
-                                                     const int32_t *node_ids, int64_t row0, int32_t exclude_self,
+// Row r of `scores` has ncols entries; its result goes to row out_row0 + r.
+__global__ __launch_bounds__(256) void k_select_rows(const float *__restrict__ scores, int64_t ncols, int32_t K,
+                                                     const int32_t *node_ids, int64_t row0, int32_t exclude_self, int64_t out_row0,
                                                      int32_t *__restrict__ out_ids, float *__restrict__ out_sc) {
     __shared__ uint32_t hist[256];
     __shared__ uint64_t sel[256];
@@ -46,38 +78,143 @@ __global__ __launch_bounds__(256) void k_select_rows(const float *__restrict__ s
     const int32_t self = exclude_self ? (node_ids ? node_ids[row0 + r] : (int32_t)(row0 + r)) : -1;
     for (int i = threadIdx.x; i < 256; i += blockDim.x) sel[i] = 0;
     __syncthreads();
-    const int32_t got = ap_radix_select(scores + r * n, n, self, K, hist, sel, misc, &pre);
+    const int32_t got = ap_radix_select(scores + r * ncols, ncols, self, K, hist, sel, misc, &pre);
     ap_bitonic_desc(sel, 256);
     for (int32_t i = threadIdx.x; i < K; i += blockDim.x) {
-        out_ids[(row0 + r) * K + i] = i < got ? ap_key_id(sel[i]) : -1;
-        out_sc[(row0 + r) * K + i] = i < got ? ap_key_score(sel[i]) : -INFINITY;
+        if (out_ids) out_ids[(out_row0 + r) * K + i] = i < got ? ap_key_id(sel[i]) : -1;
+        out_sc[(out_row0 + r) * K + i] = i < got ? ap_key_score(sel[i]) : -INFINITY;
     }
 }
 
+// tau[r] = K-th best score of row r of a [nrows x K] sorted score table.
+__global__ void k_take_tau(const float *__restrict__ sc, int64_t nrows, int32_t K, float *__restrict__ tau) {
+    const int64_t r = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (r < nrows) tau[r] = sc[r * K + K - 1];
+}
+
+// One block per row: exact top-K among the row's buffered candidate keys.
+// Rows whose buffer overflowed are reported (flags[r] = 1) and left to the caller.
+__global__ __launch_bounds__(256) void k_select_buf(const unsigned long long *__restrict__ buf, int32_t cap,
+                                                    const int32_t *__restrict__ cnt, int32_t K, int64_t out_row0,
+                                                    int32_t *__restrict__ out_ids, float *__restrict__ out_sc,
+                                                    int32_t *__restrict__ n_overflow, int32_t *__restrict__ overflow_rows) {
+    __shared__ uint32_t hist[256];
+    __shared__ uint64_t sel[256];
+    __shared__ int32_t misc[4];
+    __shared__ uint64_t pre;
+    const int64_t r = blockIdx.x;
+    const int32_t c = cnt[r];
+    if (c > cap) {   // uniform for the block
+        if (threadIdx.x == 0) overflow_rows[atomicAdd(n_overflow, 1)] = (int32_t)r;
+        return;
+    }
+    for (int i = threadIdx.x; i < 256; i += blockDim.x) sel[i] = 0;
+    __syncthreads();
+    const unsigned long long *row = buf + r * (int64_t)cap;
+    const int32_t got = ap_radix_select_keys([&](int64_t j) -> uint64_t { return row[j]; }, c, c, K, hist, sel, misc, &pre);
+    ap_bitonic_desc(sel, 256);
+    for (int32_t i = threadIdx.x; i < K; i += blockDim.x) {
+        out_ids[(out_row0 + r) * K + i] = i < got ? ap_key_id(sel[i]) : -1;
+        out_sc[(out_row0 + r) * K + i] = i < got ? ap_key_score(sel[i]) : -INFINITY;
+    }
+}
+
+// Exact path: full score rows of a slab, then selection.  Rows [row0, row0+nrows) of the node list.
+static hipError_t seed_exact_rows(const ap_index *ix, const int32_t *node_ids, int64_t row0, int64_t nrows, int32_t K,
+                                  float *scratch, int64_t scratch_rows, int32_t *out_ids, float *out_sc, hipStream_t st) {
+    const int64_t n = ix->docs.n;
+    hipError_t e = hipSuccess;
+    for (int64_t r0 = row0; r0 < row0 + nrows && e == hipSuccess; r0 += scratch_rows) {
+        const int64_t nr = std::min(scratch_rows, row0 + nrows - r0);
+        dim3 grid((unsigned)((n + AP_TILE - 1) / AP_TILE), (unsigned)((nr + AP_TILE - 1) / AP_TILE));
+        if (ix->dtype == AP_F32)
+            hipLaunchKernelGGL(k_seed_scores<AP_F32>, grid, dim3(256), 0, st, ix->docs.dense, ix->docs.dim, n, node_ids, r0, nr, (int64_t)0, n, scratch);
+        else
+            hipLaunchKernelGGL(k_seed_scores<AP_BF16>, grid, dim3(256), 0, st, ix->docs.dense, ix->docs.dim, n, node_ids, r0, nr, (int64_t)0, n, scratch);
+        e = hipGetLastError();
+        if (e != hipSuccess) break;
+        hipLaunchKernelGGL(k_select_rows, dim3((unsigned)nr), dim3(256), 0, st, scratch, n, K, node_ids, r0, 1, r0, out_ids, out_sc);
+        e = hipGetLastError();
+    }
+    return e;
+}
+
+// S2.  Small corpora: every score row is materialised and the K best are
+// selected from it.  Large corpora: the N x N scores are never stored: a
+// sample of the columns gives each row a lower bound tau of its K-th best
+// score, then one sweep over all columns appends only the scores >= tau to a
+// per-row candidate buffer, from which the exact top-K is selected.  A row
+// whose buffer overflows (not observed; the buffer holds twice the expected
+// number of candidates) is redone by the exact path.
 static int seed_knn_impl(const ap_index *ix, const int32_t *node_ids, int64_t nn, int32_t K, int32_t *out_ids,
                          float *out_sc, hipStream_t st) {
     const int64_t n = ix->docs.n;
-    // slab of rows whose score matrix fits ~1 GiB
-    int64_t slab = ((int64_t)1 << 28) / n;
-    slab = std::max<int64_t>(AP_TILE, slab / AP_TILE * AP_TILE);
-    slab = std::min<int64_t>(slab, (nn + AP_TILE - 1) / AP_TILE * AP_TILE);
-    float *scratch = nullptr;
-    AP_TRY(ap_dev_alloc(&scratch, (size_t)slab * (size_t)n));
+    int64_t cs = std::max<int64_t>(16384, (n + 63) / 64);
+    if (const char *env = getenv("AP_SEED_SAMPLE_COLS")) cs = std::max<int64_t>(K + 1, atoll(env));
+    cs = (cs + AP_TILE - 1) / AP_TILE * AP_TILE;
+    // rows per launch of the exact path: a score slab of ~1 GiB
+    int64_t ex_rows = std::max<int64_t>(AP_TILE, (((int64_t)1 << 28) / n) / AP_TILE * AP_TILE);
+    ex_rows = std::min<int64_t>(ex_rows, (nn + AP_TILE - 1) / AP_TILE * AP_TILE);
     hipError_t e = hipSuccess;
-    for (int64_t row0 = 0; row0 < nn && e == hipSuccess; row0 += slab) {
-        const int64_t nrows = std::min(slab, nn - row0);
-        dim3 grid((unsigned)((n + AP_TILE - 1) / AP_TILE), (unsigned)((nrows + AP_TILE - 1) / AP_TILE));
+    int rc = AP_OK;
+    if (n < 2 * cs) {
+        float *scratch = nullptr;
+        AP_TRY(ap_dev_alloc(&scratch, (size_t)ex_rows * (size_t)n));
+        e = seed_exact_rows(ix, node_ids, 0, nn, K, scratch, ex_rows, out_ids, out_sc, st);
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+        (void)hipFree(scratch);
+        if (e != hipSuccess) { ap_set_error("seed k-NN failed: %s", hipGetErrorString(e)); return AP_EHIP; }
+        return AP_OK;
+    }
+    const int64_t RS = std::min<int64_t>(8192, (nn + AP_TILE - 1) / AP_TILE * AP_TILE);
+    // expected candidates per row = K * n / cs (tau is the K-th best of cs sampled columns)
+    int64_t cap = 1024;
+    while (cap < 2 * ((int64_t)K * n / cs + K)) cap <<= 1;
+    if (const char *env = getenv("AP_SEED_BUFFER_CAP")) cap = std::max<int64_t>(1, atoll(env));   // test knob: forces overflows
+    float *scratch = nullptr, *tau = nullptr, *tmp_sc = nullptr, *ex_scratch = nullptr;
+    unsigned long long *buf = nullptr;
+    int32_t *cnt = nullptr, *ovf = nullptr;   // ovf[0] = number of overflowed rows, ovf[1..] = their indices
+    rc = ap_dev_alloc(&scratch, (size_t)RS * (size_t)cs);
+    if (rc == AP_OK) rc = ap_dev_alloc(&tau, (size_t)RS);
+    if (rc == AP_OK) rc = ap_dev_alloc(&tmp_sc, (size_t)RS * K);
+    if (rc == AP_OK) rc = ap_dev_alloc(&buf, (size_t)RS * (size_t)cap);
+    if (rc == AP_OK) rc = ap_dev_alloc(&cnt, (size_t)RS);
+    if (rc == AP_OK) rc = ap_dev_alloc(&ovf, (size_t)RS + 1);
+    for (int64_t row0 = 0; rc == AP_OK && row0 < nn && e == hipSuccess; row0 += RS) {
+        const int64_t nrows = std::min(RS, nn - row0);
+        const unsigned ytiles = (unsigned)((nrows + AP_TILE - 1) / AP_TILE);
+        dim3 gs((unsigned)(cs / AP_TILE), ytiles), gf((unsigned)((n + AP_TILE - 1) / AP_TILE), ytiles);
         if (ix->dtype == AP_F32)
-            hipLaunchKernelGGL(k_seed_scores<AP_F32>, grid, dim3(256), 0, st, ix->docs.dense, ix->docs.dim, n, node_ids, row0, nrows, scratch);
+            hipLaunchKernelGGL(k_seed_scores<AP_F32>, gs, dim3(256), 0, st, ix->docs.dense, ix->docs.dim, n, node_ids, row0, nrows, (int64_t)0, cs, scratch);
         else
-            hipLaunchKernelGGL(k_seed_scores<AP_BF16>, grid, dim3(256), 0, st, ix->docs.dense, ix->docs.dim, n, node_ids, row0, nrows, scratch);
+            hipLaunchKernelGGL(k_seed_scores<AP_BF16>, gs, dim3(256), 0, st, ix->docs.dense, ix->docs.dim, n, node_ids, row0, nrows, (int64_t)0, cs, scratch);
+        hipLaunchKernelGGL(k_select_rows, dim3((unsigned)nrows), dim3(256), 0, st, scratch, cs, K, node_ids, row0, 1, (int64_t)0,
+                           (int32_t *)nullptr, tmp_sc);
+        hipLaunchKernelGGL(k_take_tau, dim3((unsigned)((nrows + 255) / 256)), dim3(256), 0, st, tmp_sc, nrows, K, tau);
+        rc = ap_fill_u32(cnt, (size_t)nrows, 0u, st);
+        if (rc == AP_OK) rc = ap_fill_u32(ovf, 1, 0u, st);
+        if (rc != AP_OK) break;
+        if (ix->dtype == AP_F32)
+            hipLaunchKernelGGL(k_seed_thresh<AP_F32>, gf, dim3(256), 0, st, ix->docs.dense, ix->docs.dim, n, node_ids, row0, nrows, tau, buf, (int32_t)cap, cnt);
+        else
+            hipLaunchKernelGGL(k_seed_thresh<AP_BF16>, gf, dim3(256), 0, st, ix->docs.dense, ix->docs.dim, n, node_ids, row0, nrows, tau, buf, (int32_t)cap, cnt);
+        hipLaunchKernelGGL(k_select_buf, dim3((unsigned)nrows), dim3(256), 0, st, buf, (int32_t)cap, cnt, K, row0, out_ids, out_sc, ovf, ovf + 1);
         e = hipGetLastError();
         if (e != hipSuccess) break;
-        hipLaunchKernelGGL(k_select_rows, dim3((unsigned)nrows), dim3(256), 0, st, scratch, n, K, node_ids, row0, 1, out_ids, out_sc);
-        e = hipGetLastError();
+        int32_t n_ovf = 0;
+        e = hipMemcpyAsync(&n_ovf, ovf, sizeof(int32_t), hipMemcpyDeviceToHost, st);
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+        if (e != hipSuccess) break;
+        if (n_ovf > 0) {   // redo the slab by the exact path
+            if (!ex_scratch) rc = ap_dev_alloc(&ex_scratch, (size_t)ex_rows * (size_t)n);
+            if (rc != AP_OK) break;
+            e = seed_exact_rows(ix, node_ids, row0, nrows, K, ex_scratch, ex_rows, out_ids, out_sc, st);
+        }
     }
     if (e == hipSuccess) e = hipStreamSynchronize(st);
-    (void)hipFree(scratch);
+    void *ptrs[] = {scratch, tau, tmp_sc, buf, cnt, ovf, ex_scratch};
+    for (void *p : ptrs) if (p) (void)hipFree(p);
+    if (rc != AP_OK) return rc;
     if (e != hipSuccess) { ap_set_error("seed k-NN failed: %s", hipGetErrorString(e)); return AP_EHIP; }
     return AP_OK;
 }
@@ -99,7 +236,7 @@ extern "C" int ap_stage_entry_points(const ap_index *ix, int32_t E, int32_t *out
     float *sc = nullptr;
     AP_TRY(ap_dev_alloc(&sc, (size_t)E));
     hipLaunchKernelGGL(k_select_rows, dim3(1), dim3(256), 0, st, ix->self_sim, ix->docs.n, E, (const int32_t *)nullptr,
-                       (int64_t)0, 0, out_entry, sc);
+                       (int64_t)0, 0, (int64_t)0, out_entry, sc);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     (void)hipFree(sc);
@@ -253,8 +390,7 @@ template <int DT>
 __global__ __launch_bounds__(256) void k_gram_dense(const void *dense, int32_t dim, int32_t K, const int32_t *__restrict__ knn,
                                                     const int32_t *__restrict__ node_ids, int64_t x0,
                                                     float *__restrict__ pm /* chunk x K x K */) {
-    __shared__ float lA[AP_TILE * AP_LDS_STRIDE];
-    __shared__ float lB[AP_TILE * AP_LDS_STRIDE];
+    __shared__ __attribute__((aligned(16))) unsigned char lds[AP_TILE_LDS_BYTES];
     __shared__ int32_t a_rows[AP_TILE], b_rows[AP_TILE];
     const int64_t x = blockIdx.y;
     const int64_t u = node_ids ? (int64_t)node_ids[x0 + x] : x0 + x;
@@ -265,7 +401,7 @@ __global__ __launch_bounds__(256) void k_gram_dense(const void *dense, int32_t d
         b_rows[threadIdx.x] = j0 + threadIdx.x < K ? knn[u * K + j0 + threadIdx.x] : -1;
     }
     ap_f32x16 acc[2][2];
-    ap_tile_gemm<DT>(dense, dim, a_rows, b_rows, lA, lB, acc);
+    ap_tile_product<DT>(dense, dim, a_rows, b_rows, lds, acc);
     float *out = pm + x * (int64_t)K * K;
     ap_tile_foreach(acc, [&](int i, int j, float v) {
         if (i0 + i < K && j0 + j < K) out[(int64_t)(i0 + i) * K + (j0 + j)] = v;

@@ -74,6 +74,78 @@ __device__ __forceinline__ void ap_tile_gemm(const void *dense, int32_t dim, con
     }
 }
 
+// bf16 rows: the same 128x128 tile product on v_mfma_f32_32x32x16_bf16 (8x the
+// rate of the f32 instruction).  Rows are staged as bf16, 64 columns a chunk;
+// lane l feeds A[l%32][8*(l/32) .. +8] and B[8*(l/32) .. +8][l%32] per 16-wide
+// step; the result layout is that of the f32 instruction.
+typedef __bf16 ap_bf16x8 __attribute__((ext_vector_type(8)));
+#define AP_BK16 64
+#define AP_LDS_STRIDE16 (AP_BK16 + 8)   // in bf16 elements: 144-byte rows keep the 16-byte operand reads spread over the banks
+
+__device__ __forceinline__ void ap_tile_stage_bf16(const void *dense, int32_t dim, const int32_t *rows, int32_t k0, uint16_t *lds) {
+    const int t = threadIdx.x;
+#pragma unroll
+    for (int pass = 0; pass < 4; pass++) {
+        const int r = (t >> 3) + 32 * pass;
+        const int c = (t & 7) * 8;
+        const int32_t row = rows[r];
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (row >= 0 && k0 + c < dim)   // dim is a multiple of 8: a 16-byte group is all inside or all outside
+            v = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(dense) + (int64_t)row * dim + k0 + c);
+        *reinterpret_cast<uint4 *>(lds + r * AP_LDS_STRIDE16 + c) = v;
+    }
+}
+
+__device__ __forceinline__ void ap_tile_gemm_bf16(const void *dense, int32_t dim, const int32_t *a_rows, const int32_t *b_rows,
+                                                  uint16_t *lA, uint16_t *lB, ap_f32x16 acc[2][2]) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int li = lane & 31, lk = (lane >> 5) * 8;
+#pragma unroll
+    for (int a = 0; a < 2; a++)
+#pragma unroll
+        for (int b = 0; b < 2; b++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) acc[a][b][r] = 0.f;
+    for (int32_t k0 = 0; k0 < dim; k0 += AP_BK16) {
+        __syncthreads();
+        ap_tile_stage_bf16(dense, dim, a_rows, k0, lA);
+        ap_tile_stage_bf16(dense, dim, b_rows, k0, lB);
+        __syncthreads();
+        const uint16_t *pa0 = lA + (wm * 64 + li) * AP_LDS_STRIDE16 + lk;
+        const uint16_t *pa1 = pa0 + 32 * AP_LDS_STRIDE16;
+        const uint16_t *pb0 = lB + (wn * 64 + li) * AP_LDS_STRIDE16 + lk;
+        const uint16_t *pb1 = pb0 + 32 * AP_LDS_STRIDE16;
+#pragma unroll
+        for (int kk = 0; kk < AP_BK16; kk += 16) {
+            const ap_bf16x8 a0 = __builtin_bit_cast(ap_bf16x8, *reinterpret_cast<const uint4 *>(pa0 + kk));
+            const ap_bf16x8 a1 = __builtin_bit_cast(ap_bf16x8, *reinterpret_cast<const uint4 *>(pa1 + kk));
+            const ap_bf16x8 b0 = __builtin_bit_cast(ap_bf16x8, *reinterpret_cast<const uint4 *>(pb0 + kk));
+            const ap_bf16x8 b1 = __builtin_bit_cast(ap_bf16x8, *reinterpret_cast<const uint4 *>(pb1 + kk));
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc[1][1], 0, 0, 0);
+        }
+    }
+}
+
+// LDS bytes the tile product needs (both operands), for either storage type.
+#define AP_TILE_LDS_BYTES (2 * AP_TILE * AP_LDS_STRIDE * 4 > 2 * AP_TILE * AP_LDS_STRIDE16 * 2 ? 2 * AP_TILE * AP_LDS_STRIDE * 4 : 2 * AP_TILE * AP_LDS_STRIDE16 * 2)
+
+// Tile product for storage type DT out of one raw LDS area of AP_TILE_LDS_BYTES bytes.
+template <int DT>
+__device__ __forceinline__ void ap_tile_product(const void *dense, int32_t dim, const int32_t *a_rows, const int32_t *b_rows,
+                                                void *lds, ap_f32x16 acc[2][2]) {
+    if (DT == AP_BF16) {
+        uint16_t *l = static_cast<uint16_t *>(lds);
+        ap_tile_gemm_bf16(dense, dim, a_rows, b_rows, l, l + AP_TILE * AP_LDS_STRIDE16, acc);
+    } else {
+        float *l = static_cast<float *>(lds);
+        ap_tile_gemm<AP_F32>(dense, dim, a_rows, b_rows, l, l + AP_TILE * AP_LDS_STRIDE, acc);
+    }
+}
+
 // Calls f(i, j, value) for every element this lane holds of the 128x128 tile.
 template <typename F>
 __device__ __forceinline__ void ap_tile_foreach(const ap_f32x16 acc[2][2], F f) {
@@ -107,15 +179,15 @@ __device__ __forceinline__ void ap_bitonic_desc(uint64_t *keys, int32_t n) {
     __syncthreads();
 }
 
-// Exact selection of the K largest keys among key(j) = ap_make_key(row[j], j)
-// for j in [0, n), j != exclude: radix selection on the 64-bit keys, eight
+// Exact selection of the K largest of the n keys key_of(j), j in [0, n) (a key
+// of 0 means "no candidate here"): radix selection on the 64-bit keys, eight
 // bits a pass from the top, stopping as soon as the digit bucket that holds
 // the K-th key is taken whole.  The selected keys land in sel[] (unordered);
-// returns their number (min(K, candidates)).  hist: 256 words of LDS.
-__device__ __forceinline__ int32_t ap_radix_select(const float *row, int64_t n, int32_t exclude, int32_t K,
-                                                   uint32_t *hist, uint64_t *sel, int32_t *s_misc /* 4 ints */,
-                                                   uint64_t *s_prefix /* 1 */) {
-    const int64_t valid = n - ((exclude >= 0 && exclude < n) ? 1 : 0);
+// returns their number (min(K, number of non-zero keys)).  `valid` = number of
+// non-zero keys, known to the caller.  hist: 256 words of LDS.
+template <typename KeyOf>
+__device__ __forceinline__ int32_t ap_radix_select_keys(KeyOf key_of, int64_t n, int64_t valid, int32_t K, uint32_t *hist,
+                                                        uint64_t *sel, int32_t *s_misc /* 4 ints */, uint64_t *s_prefix /* 1 */) {
     int32_t krem = (int64_t)K < valid ? K : (int32_t)valid;
     const int32_t ktotal = krem;
     uint64_t prefix = 0, mask = 0;
@@ -125,9 +197,8 @@ __device__ __forceinline__ int32_t ap_radix_select(const float *row, int64_t n, 
             for (int i = threadIdx.x; i < 256; i += blockDim.x) hist[i] = 0;
             __syncthreads();
             for (int64_t j = threadIdx.x; j < n; j += blockDim.x) {
-                if (j == exclude) continue;
-                const uint64_t key = ap_make_key(row[j], (int32_t)j, 1u);
-                if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+                const uint64_t key = key_of(j);
+                if (key != 0 && (key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
             }
             __syncthreads();
             if (threadIdx.x == 0) {
@@ -153,9 +224,8 @@ __device__ __forceinline__ int32_t ap_radix_select(const float *row, int64_t n, 
     __syncthreads();
     if (ktotal > 0) {
         for (int64_t j = threadIdx.x; j < n; j += blockDim.x) {
-            if (j == exclude) continue;
-            const uint64_t key = ap_make_key(row[j], (int32_t)j, 1u);
-            if ((key & mask) >= prefix) {
+            const uint64_t key = key_of(j);
+            if (key != 0 && (key & mask) >= prefix) {
                 const int32_t pos = atomicAdd(&s_misc[2], 1);
                 if (pos < ktotal) sel[pos] = key;
             }
@@ -163,6 +233,14 @@ __device__ __forceinline__ int32_t ap_radix_select(const float *row, int64_t n, 
     }
     __syncthreads();
     return ktotal;
+}
+
+// The K best of a row of scores: key(j) = ap_make_key(row[j], j), j != exclude.
+__device__ __forceinline__ int32_t ap_radix_select(const float *row, int64_t n, int32_t exclude, int32_t K,
+                                                   uint32_t *hist, uint64_t *sel, int32_t *s_misc, uint64_t *s_prefix) {
+    const int64_t valid = n - ((exclude >= 0 && exclude < n) ? 1 : 0);
+    return ap_radix_select_keys([&](int64_t j) -> uint64_t { return j == exclude ? 0ull : ap_make_key(row[j], (int32_t)j, 1u); },
+                                n, valid, K, hist, sel, s_misc, s_prefix);
 }
 
 #endif

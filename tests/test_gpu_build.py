@@ -70,6 +70,25 @@ def test_s2_seed_knn(case):
         assert u not in ids[r]
 
 
+def test_s2_seed_knn_threshold_path(case, monkeypatch):
+    """Large corpora never store the N x N scores: a column sample bounds each
+    row's K-th best, one sweep buffers the scores above the bound.  Forced here
+    on small corpora by shrinking the sample; also with a buffer so small that
+    rows overflow and are redone by the exact path.  All three must agree."""
+    name, w, docs, ix, D, wv, dn, (R, K, S, P) = case
+    if docs.n < 2 * 256:
+        pytest.skip("corpus smaller than two samples")
+    _say(f"S2 seed threshold path {name}")
+    sub, nodes = _nodes(docs.n, name)
+    exact = _np(*ix.stage_seed_knn(K, sub))
+    monkeypatch.setenv("AP_SEED_SAMPLE_COLS", "256")
+    thr = _np(*ix.stage_seed_knn(K, sub))
+    monkeypatch.setenv("AP_SEED_BUFFER_CAP", "64")
+    ovf = _np(*ix.stage_seed_knn(K, sub))
+    for got in (thr, ovf):
+        assert np.array_equal(got[0], exact[0]) and np.array_equal(got[1], exact[1])
+
+
 def test_s3_refine_round(case):
     name, w, docs, ix, D, wv, dn, (R, K, S, P) = case
     sub, nodes = _nodes(docs.n, name)
