@@ -122,7 +122,12 @@ int ap_ingest_impl(ap_index *ix, hipStream_t st) {
     int64_t last = 0;
     AP_CHECK_HIP(hipMemcpyAsync(&last, c.tx_indptr + c.n, sizeof(int64_t), hipMemcpyDeviceToHost, st));
     AP_CHECK_HIP(hipStreamSynchronize(st));
-    AP_REQUIRE(last >= 0, "tx_indptr[n] is negative");
+    int64_t sp_last = 0;
+    AP_CHECK_HIP(hipMemcpyAsync(&sp_last, c.sp_indptr + c.n, sizeof(int64_t), hipMemcpyDeviceToHost, st));
+    AP_CHECK_HIP(hipStreamSynchronize(st));
+    AP_REQUIRE(last >= 0 && sp_last >= 0, "indptr[n] is negative");
+    AP_REQUIRE(last < (1ll << 30) && sp_last < (1ll << 30),
+               "each CSR part must hold fewer than 2^30 entries (the search addresses list entries with 32-bit byte offsets)");
     ix->tx_nnz = last;
     AP_TRY(ap_dev_alloc(&ix->tx_w, (size_t)last));
     AP_TRY(ap_dev_alloc(&ix->df, (size_t)c.tx_vocab));

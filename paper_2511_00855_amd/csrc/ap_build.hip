@@ -421,68 +421,6 @@ __global__ __launch_bounds__(256) void k_gram_dense(const void *dense, int32_t d
 #define AP_TX_SLOTS 512     // lexical table slots (row lists up to 128 entries)
 #define AP_TX_BITS 9
 
-__device__ __forceinline__ uint32_t ap_term_hash(int32_t t, int bits) { return ((uint32_t)t * 2654435761u) >> (32 - bits); }
-
-// Weight of term t in the table, 0 if absent (t = -1 is never present).  A
-// slot is read as one 64-bit word: term in the low half, weight bits in the high half.
-template <typename TP>
-__device__ __forceinline__ float ap_table_get(TP tab, int slots, int bits, int32_t t) {
-    uint32_t h = ap_term_hash(t, bits);
-    for (;;) {
-        const uint64_t e = tab[h];
-        const int32_t et = (int32_t)(uint32_t)e;
-        if (et == t) return __uint_as_float((uint32_t)(e >> 32));
-        if (et == -1) return 0.f;
-        h = (h + 1) & (slots - 1);
-    }
-}
-
-// NL look-ups at once: every round issues the LDS reads of all look-ups that
-// are still probing, so their latencies overlap; the number of rounds is the
-// longest probe sequence among them (linear probing, tables at most half full).
-// val[k] = weight of term[k] in its table (look-ups k < NSP use the sparse one).
-template <int NL, int NSP>
-__device__ __forceinline__ void ap_table_get_many(const AP_LDS uint64_t *tsp, const AP_LDS uint64_t *ttx, const int32_t *term,
-                                                  float *val) {
-    uint32_t h[NL];
-    bool pend[NL];
-    bool any = false;
-#pragma unroll
-    for (int k = 0; k < NL; k++) {
-        h[k] = ap_term_hash(term[k], k < NSP ? AP_SP_BITS : AP_TX_BITS);
-        val[k] = 0.f;
-        pend[k] = term[k] >= 0;
-        any = any || pend[k];
-    }
-    while (__any(any)) {
-        // straight-line code: every look-up reads its current slot (a finished one re-reads harmlessly)
-        uint64_t e[NL];
-#pragma unroll
-        for (int k = 0; k < NL; k++) e[k] = k < NSP ? tsp[h[k]] : ttx[h[k]];
-        any = false;
-#pragma unroll
-        for (int k = 0; k < NL; k++) {
-            const int32_t et = (int32_t)(uint32_t)e[k];
-            const bool hit = pend[k] & (et == term[k]);
-            val[k] = hit ? __uint_as_float((uint32_t)(e[k] >> 32)) : val[k];
-            pend[k] = pend[k] & (et != term[k]) & (et != -1);
-            h[k] = (h[k] + 1) & ((k < NSP ? AP_SP_SLOTS : AP_TX_SLOTS) - 1);
-            any = any | pend[k];
-        }
-    }
-}
-
-// Inserts (term, weight bits) into an open-addressing table that holds no such term yet.
-__device__ __forceinline__ void ap_table_put(uint64_t *tab, int slots, int bits, int32_t t, int32_t vb) {
-    int32_t *w32 = reinterpret_cast<int32_t *>(tab);
-    uint32_t h = ap_term_hash(t, bits);
-    for (;;) {
-        const int32_t old = atomicCAS(&w32[2 * h], -1, t);
-        if (old == -1) { w32[2 * h + 1] = vb; return; }
-        h = (h + 1) & (slots - 1);
-    }
-}
-
 #define AP_GRAM_THREADS 512
 #define AP_GRAM_WAVES 8
 #define AP_GC 4     // columns per wave per row: AP_GRAM_WAVES * AP_GC == AP_CB
@@ -601,7 +539,7 @@ __global__ __launch_bounds__(AP_GRAM_THREADS) __attribute__((amdgpu_waves_per_eu
                     term[2 * gq + 1] = lane + 64 < sn ? lb_idx[so + 64 + lane] : -1; bval[2 * gq + 1] = lane + 64 < sn ? lb_val[so + 64 + lane] : 0.f;
                     term[2 * AP_GC + gq] = lane < tn ? lb_idx[to + lane] : -1;      bval[2 * AP_GC + gq] = lane < tn ? lb_val[to + lane] : 0.f;
                 }
-                ap_table_get_many<3 * AP_GC, 2 * AP_GC>(tsp, ttx, term, aval);
+                ap_table_get_many<3 * AP_GC, 2 * AP_GC, AP_SP_BITS, AP_TX_BITS>(tsp, ttx, term, aval);
 #pragma unroll
                 for (int gq = 0; gq < AP_GC; gq++) {
                     const int c = c0 + gq <= clast ? c0 + gq : clast;

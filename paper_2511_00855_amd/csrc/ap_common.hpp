@@ -196,13 +196,92 @@ __device__ __forceinline__ int32_t ap_pow2_floor(int32_t n) { return n > 0 ? (1 
 // list in LDS is read with ds_read and one in global memory with global loads.
 template <typename IP, typename VP>
 __device__ __forceinline__ float ap_match_fma(IP a_idx, VP a_val, int32_t a_n, int32_t step0, int32_t t, float v, float p) {
+    if (a_n <= 0) return p;            // wave-uniform
+    // straight-line code: every step reads a valid entry (index clamped) and selects
     int32_t pos = 0;
     for (int32_t st = step0; st > 0; st >>= 1) {
         const int32_t p2 = pos + st;
-        if (p2 <= a_n && a_idx[p2 - 1] < t) pos = p2;
+        const int32_t at = (p2 < a_n ? p2 : a_n) - 1;
+        const bool take = (p2 <= a_n) & (a_idx[at] < t);
+        pos = take ? p2 : pos;
     }
-    if (pos < a_n && a_idx[pos] == t) p = fmaf(a_val[pos], v, p);
-    return p;
+    const int32_t at = pos < a_n ? pos : a_n - 1;
+    const bool hit = (pos < a_n) & (a_idx[at] == t);
+    return fmaf(hit ? a_val[at] : 0.f, v, p);   // adds exactly 0 when the term is absent
+}
+
+// ---- small open-addressing tables (term -> weight) in LDS ----------------
+// A slot is one 64-bit word: term id in the low half (-1 = empty), weight
+// bits in the high half.  Linear probing; a table is never more than half
+// full, so every probe sequence ends at an empty slot.
+__device__ __forceinline__ uint32_t ap_term_hash(int32_t t, int bits) {
+    return (__umul24((uint32_t)t & 0xffffffu, 0x9E3779u) ^ ((uint32_t)t >> 24)) >> (32 - bits) ;
+}
+
+// Weight of term t in the table, 0 if absent (t = -1 is never present).
+template <typename TP>
+__device__ __forceinline__ float ap_table_get(TP tab, int slots, int bits, int32_t t) {
+    uint32_t h = ap_term_hash(t, bits);
+    for (;;) {
+        const uint64_t e = tab[h];
+        const int32_t et = (int32_t)(uint32_t)e;
+        if (et == t) return __uint_as_float((uint32_t)(e >> 32));
+        if (et == -1) return 0.f;
+        h = (h + 1) & (slots - 1);
+    }
+}
+
+// NL look-ups at once: every round issues the LDS reads of all look-ups that
+// are still probing, so their latencies overlap; the number of rounds is the
+// longest probe sequence among them.  Straight-line code: a finished look-up
+// re-reads harmlessly.  Look-ups k < NSP use the first table (2^SPB slots),
+// the others the second (2^TXB slots).  val[k] = weight of term[k], 0 if absent.
+template <int NL, int NSP, int SPB, int TXB>
+__device__ __forceinline__ void ap_table_get_many(const AP_LDS uint64_t *tsp, const AP_LDS uint64_t *ttx, const int32_t *term,
+                                                  float *val) {
+    uint32_t h[NL];
+    bool pend[NL];
+    bool any = false;
+#pragma unroll
+    for (int k = 0; k < NL; k++) {
+        h[k] = ap_term_hash(term[k], k < NSP ? SPB : TXB);
+        val[k] = 0.f;
+        pend[k] = term[k] >= 0;
+        any = any || pend[k];
+    }
+    while (__any(any)) {
+        uint64_t e[NL];
+#pragma unroll
+        for (int k = 0; k < NL; k++) e[k] = k < NSP ? tsp[h[k]] : ttx[h[k]];
+        any = false;
+#pragma unroll
+        for (int k = 0; k < NL; k++) {
+            const int32_t et = (int32_t)(uint32_t)e[k];
+            const bool hit = pend[k] & (et == term[k]);
+            val[k] = hit ? __uint_as_float((uint32_t)(e[k] >> 32)) : val[k];
+            pend[k] = pend[k] & (et != term[k]) & (et != -1);
+            h[k] = (h[k] + 1) & ((1u << (k < NSP ? SPB : TXB)) - 1u);
+            any = any | pend[k];
+        }
+    }
+}
+
+// Inserts (term, weight bits) into a table that holds no such term yet.
+__device__ __forceinline__ void ap_table_put(uint64_t *tab, int slots, int bits, int32_t t, int32_t vb) {
+    int32_t *w32 = reinterpret_cast<int32_t *>(tab);
+    uint32_t h = ap_term_hash(t, bits);
+    for (;;) {
+        const int32_t old = atomicCAS(&w32[2 * h], -1, t);
+        if (old == -1) { w32[2 * h + 1] = vb; return; }
+        h = (h + 1) & (slots - 1);
+    }
+}
+
+// 32-bit indexed global load: base + zero-extended 32-bit byte offset (the
+// index must stay below 2^30 elements of 4 bytes).
+template <typename T>
+__device__ __forceinline__ T ap_ld32(const T *base, uint32_t index) {
+    return *reinterpret_cast<const T *>(reinterpret_cast<const char *>(base) + (uint32_t)(index * (uint32_t)sizeof(T)));
 }
 
 // Partial inner product of an ascending list held by the a side with the
@@ -270,6 +349,61 @@ __device__ __forceinline__ void ap_lists_load(const ApVecs &B, int64_t spb, int3
         ti[k] = e < txn ? B.tx_idx[txb + e] : -1;
         tv[k] = e < txn ? B.tx_val[txb + e] : 0.f;
     }
+}
+
+// The same loads with 32-bit element offsets (lists stored below 2^30 entries).
+template <int SS, int TS>
+__device__ __forceinline__ void ap_lists_load32(const ApVecs &B, uint32_t spb, int32_t spn, uint32_t txb, int32_t txn,
+                                                int32_t *si, float *sv, int32_t *ti, float *tv) {
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int k = 0; k < SS; k++) {
+        const int32_t e = k * 64 + lane;
+        si[k] = e < spn ? ap_ld32(B.sp_idx, spb + (uint32_t)e) : -1;
+        sv[k] = e < spn ? ap_ld32(B.sp_val, spb + (uint32_t)e) : 0.f;
+    }
+#pragma unroll
+    for (int k = 0; k < TS; k++) {
+        const int32_t e = k * 64 + lane;
+        ti[k] = e < txn ? ap_ld32(B.tx_idx, txb + (uint32_t)e) : -1;
+        tv[k] = e < txn ? ap_ld32(B.tx_val, txb + (uint32_t)e) : 0.f;
+    }
+}
+
+// Sparse and lexical sums with the a side's lists held as look-up tables
+// (2^SPB and 2^TXB slots).  Same per-lane accumulation order as
+// ap_lists_reduce: an absent term adds exactly 0.
+template <int SS, int TS, int SPB, int TXB>
+__device__ __forceinline__ void ap_lists_reduce_tab(const ApVecs &B, const AP_LDS uint64_t *tsp, const AP_LDS uint64_t *ttx,
+                                                    uint32_t spb, int32_t spn, uint32_t txb, int32_t txn, const int32_t *si,
+                                                    const float *sv, const int32_t *ti, const float *tv, float &ss, float &sf) {
+    const int lane = threadIdx.x & 63;
+    int32_t term[SS + TS];
+    float av[SS + TS];
+#pragma unroll
+    for (int k = 0; k < SS; k++) term[k] = si[k];
+#pragma unroll
+    for (int k = 0; k < TS; k++) term[SS + k] = ti[k];
+    ap_table_get_many<SS + TS, SS, SPB, TXB>(tsp, ttx, term, av);
+    float ps = 0.f, pf = 0.f;
+#pragma unroll
+    for (int k = 0; k < SS; k++) ps = fmaf(av[k], sv[k], ps);
+    for (int32_t e0 = SS * 64; e0 < spn; e0 += 64) {
+        const int32_t e = e0 + lane;
+        const int32_t t = e < spn ? ap_ld32(B.sp_idx, spb + (uint32_t)e) : -1;
+        const float x = e < spn ? ap_ld32(B.sp_val, spb + (uint32_t)e) : 0.f;
+        ps = fmaf(t >= 0 ? ap_table_get(tsp, 1 << SPB, SPB, t) : 0.f, x, ps);
+    }
+#pragma unroll
+    for (int k = 0; k < TS; k++) pf = fmaf(av[SS + k], tv[k], pf);
+    for (int32_t e0 = TS * 64; e0 < txn; e0 += 64) {
+        const int32_t e = e0 + lane;
+        const int32_t t = e < txn ? ap_ld32(B.tx_idx, txb + (uint32_t)e) : -1;
+        const float x = e < txn ? ap_ld32(B.tx_val, txb + (uint32_t)e) : 0.f;
+        pf = fmaf(t >= 0 ? ap_table_get(ttx, 1 << TXB, TXB, t) : 0.f, x, pf);
+    }
+    ss = ap_wave_sum(ps);
+    sf = ap_wave_sum(pf);
 }
 
 template <int SS, int TS, typename IP, typename VP>

@@ -10,7 +10,6 @@
 #include <stdlib.h>
 #include "ap_common.hpp"
 
-#define AP_Q_CAP 128  // query list entries staged in LDS
 
 int ap_fill_u32(void *p, size_t n, uint32_t v, hipStream_t st);
 int ap_validate_queries(const ap_queries *q);
@@ -46,23 +45,31 @@ __device__ __forceinline__ int32_t ap_rank_in(const uint64_t *keys, int32_t n, u
 // |w_d| |q_d| |d_d|, could not lift the candidate past the pool's last entry,
 // the dense row is not read at all: the candidate could not have entered the
 // pool, so the result of the search is unchanged (it still counts as visited).
+// TAB: the query's lists are look-up tables in LDS (the usual case); otherwise
+// they are searched where they lie in global memory.
 // Returns the number of candidates whose dense row was skipped (wave-uniform).
-template <int DT, int NV, typename IP, typename VP>
-__device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const float *qa, IP sp_idx, VP sp_val, int32_t sp_n,
-                                                       IP tx_idx, VP tx_val, int32_t tx_n, float wd, float ws, float wf,
-                                                       float qnorm, bool pool_full, float worst_score, const int32_t *cand,
-                                                       const int64_t *s_spb, const int32_t *s_spn, const int64_t *s_txb,
-                                                       const int32_t *s_txn, const float *s_dn, int32_t c, uint64_t *newk) {
+#ifndef AP_SEARCH_G
+#define AP_SEARCH_G 2
+#endif
+#define AP_QSP_BITS 8    // query sparse table: 256 slots, lists up to 64 entries
+#define AP_QTX_BITS 7    // query lexical table: 128 slots, lists up to 32 entries
+
+template <int DT, int NV, bool TAB>
+__device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const float *qa, const uint64_t *qtab, const ApLists &a,
+                                                       float wd, float ws, float wf, float qnorm, bool pool_full,
+                                                       float worst_score, const int32_t *cand, const uint32_t *s_spb,
+                                                       const int32_t *s_spn, const uint32_t *s_txb, const int32_t *s_txn,
+                                                       const float *s_dn, int32_t c, uint64_t *newk) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int32_t skipped = 0;
-    constexpr int G = 2;   // candidates whose list segments are in flight together
+    constexpr int G = AP_SEARCH_G;   // candidates whose list segments are in flight together
     for (int32_t i0 = wave; i0 < c; i0 += 4 * G) {
         int32_t si[G][2], ti[G][1];
         float sv[G][2], tv[G][1];
 #pragma unroll
         for (int gi = 0; gi < G; gi++) {
             const int32_t i = i0 + 4 * gi;
-            if (i < c) ap_lists_load<2, 1>(D, s_spb[i], s_spn[i], s_txb[i], s_txn[i], si[gi], sv[gi], ti[gi], tv[gi]);
+            if (i < c) ap_lists_load32<2, 1>(D, s_spb[i], s_spn[i], s_txb[i], s_txn[i], si[gi], sv[gi], ti[gi], tv[gi]);
         }
 #pragma unroll
         for (int gi = 0; gi < G; gi++) {
@@ -70,8 +77,13 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const fl
             if (i >= c) continue;
             const int32_t v = cand[i];
             float ss, sf;
-            ap_lists_reduce<2, 1>(D, sp_idx, sp_val, sp_n, tx_idx, tx_val, tx_n, s_spb[i], s_spn[i], s_txb[i], s_txn[i], si[gi],
-                                  sv[gi], ti[gi], tv[gi], ss, sf);
+            if (TAB)
+                ap_lists_reduce_tab<2, 1, AP_QSP_BITS, AP_QTX_BITS>(D, (const AP_LDS uint64_t *)qtab,
+                                                                    (const AP_LDS uint64_t *)(qtab + (1 << AP_QSP_BITS)), s_spb[i],
+                                                                    s_spn[i], s_txb[i], s_txn[i], si[gi], sv[gi], ti[gi], tv[gi], ss, sf);
+            else
+                ap_lists_reduce<2, 1>(D, a.sp_idx, a.sp_val, a.sp_n, a.tx_idx, a.tx_val, a.tx_n, (int64_t)s_spb[i], s_spn[i],
+                                      (int64_t)s_txb[i], s_txn[i], si[gi], sv[gi], ti[gi], tv[gi], ss, sf);
             // upper bound of the fused score, with slack far above fp32 rounding
             const float dmax = fabsf(wd) * qnorm * s_dn[i] * 1.0001f;
             const float part = fmaf(wf, sf, ws * ss);
@@ -91,7 +103,7 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const fl
 }
 
 #ifndef AP_SEARCH_WAVES_PER_SIMD
-#define AP_SEARCH_WAVES_PER_SIMD 7
+#define AP_SEARCH_WAVES_PER_SIMD 6
 #endif
 template <int DT, int NV>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_WAVES_PER_SIMD, 8))) void k_search(ApSearchArgs g) {
@@ -100,23 +112,34 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
     uint64_t *newk = cur + g.L;              // keys of this iteration's candidates, unordered
     uint64_t *newS = newk + g.cmax;          // the same, sorted
     uint64_t *nxt = newS + g.cmax;           // scratch of cmax words
-    int64_t *s_spb = reinterpret_cast<int64_t *>(nxt + g.cmax);
-    int64_t *s_txb = s_spb + g.cmax;
+    uint64_t *qtab = nxt + g.cmax;           // the query's two look-up tables
+    uint32_t *s_spb = reinterpret_cast<uint32_t *>(qtab + (1 << AP_QSP_BITS) + (1 << AP_QTX_BITS));
+    uint32_t *s_txb = s_spb + g.cmax;
     int32_t *s_spn = reinterpret_cast<int32_t *>(s_txb + g.cmax);
     int32_t *s_txn = s_spn + g.cmax;
     float *s_dn = reinterpret_cast<float *>(s_txn + g.cmax);
     int32_t *cand = reinterpret_cast<int32_t *>(s_dn + g.cmax);
-    int32_t *l_sp_idx = cand + g.cmax;
-    float *l_sp_val = reinterpret_cast<float *>(l_sp_idx + AP_Q_CAP);
-    int32_t *l_tx_idx = reinterpret_cast<int32_t *>(l_sp_val + AP_Q_CAP);
-    float *l_tx_val = reinterpret_cast<float *>(l_tx_idx + AP_Q_CAP);
     __shared__ int32_t s_cnt, s_np, s_skip;
     __shared__ int32_t s_par[8];
 
     const int64_t q = blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const ApLists a = ap_stage_lists(g.Q, q, l_sp_idx, l_sp_val, l_tx_idx, l_tx_val, AP_Q_CAP);
-    const bool in_lds = a.sp_n <= AP_Q_CAP && a.tx_n <= AP_Q_CAP;   // uniform
+    // the query's lists: look-up tables in LDS when they are short (the usual case), else left in global memory
+    ApLists a;
+    {
+        const int64_t sb = g.Q.sp_indptr[q], tb = g.Q.tx_indptr[q];
+        a.sp_n = (int32_t)(g.Q.sp_indptr[q + 1] - sb); a.tx_n = (int32_t)(g.Q.tx_indptr[q + 1] - tb);
+        a.sp_idx = g.Q.sp_idx + sb; a.sp_val = g.Q.sp_val + sb; a.tx_idx = g.Q.tx_idx + tb; a.tx_val = g.Q.tx_val + tb;
+    }
+    const bool use_tab = a.sp_n <= (1 << AP_QSP_BITS) / 4 && a.tx_n <= (1 << AP_QTX_BITS) / 4;   // uniform
+    if (use_tab) {
+        for (int i = threadIdx.x; i < (1 << AP_QSP_BITS) + (1 << AP_QTX_BITS); i += blockDim.x) qtab[i] = 0xffffffffull;
+        __syncthreads();
+        const int t = threadIdx.x;
+        if (t < a.sp_n) ap_table_put(qtab, 1 << AP_QSP_BITS, AP_QSP_BITS, a.sp_idx[t], __float_as_int(a.sp_val[t]));
+        else if (t < a.sp_n + a.tx_n)
+            ap_table_put(qtab + (1 << AP_QSP_BITS), 1 << AP_QTX_BITS, AP_QTX_BITS, a.tx_idx[t - a.sp_n], __float_as_int(a.tx_val[t - a.sp_n]));
+    }
     float qa[NV * ApDense<DT>::EPC];
     ap_load_aside<DT, NV, AP_F32>(g.Q.dense, q, g.D.dim, qa);
     float qnorm;
@@ -149,21 +172,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
         for (int32_t i = threadIdx.x; i < c; i += blockDim.x) {
             const int32_t v = cand[i];
             const int64_t sb = g.D.sp_indptr[v], tb = g.D.tx_indptr[v];
-            s_spb[i] = sb; s_spn[i] = (int32_t)(g.D.sp_indptr[v + 1] - sb);
-            s_txb[i] = tb; s_txn[i] = (int32_t)(g.D.tx_indptr[v + 1] - tb);
+            s_spb[i] = (uint32_t)sb; s_spn[i] = (int32_t)(g.D.sp_indptr[v + 1] - sb);
+            s_txb[i] = (uint32_t)tb; s_txn[i] = (int32_t)(g.D.tx_indptr[v + 1] - tb);
             s_dn[i] = g.dnorm[v];
         }
         __syncthreads();
         const bool pool_full = len == g.L;
         const uint64_t worst = pool_full ? cur[g.L - 1] : 0ull;
         const float worst_score = ap_key_score(worst);
-        if (in_lds)
-            nskipped += ap_score_candidates<DT, NV>(g.D, qa, (const AP_LDS int32_t *)l_sp_idx, (const AP_LDS float *)l_sp_val, a.sp_n,
-                                                    (const AP_LDS int32_t *)l_tx_idx, (const AP_LDS float *)l_tx_val, a.tx_n, wd, ws, wf,
-                                                    qnorm, pool_full, worst_score, cand, s_spb, s_spn, s_txb, s_txn, s_dn, c, newk);
+        if (use_tab)
+            nskipped += ap_score_candidates<DT, NV, true>(g.D, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score, cand, s_spb, s_spn,
+                                                          s_txb, s_txn, s_dn, c, newk);
         else
-            nskipped += ap_score_candidates<DT, NV>(g.D, qa, a.sp_idx, a.sp_val, a.sp_n, a.tx_idx, a.tx_val, a.tx_n, wd, ws, wf, qnorm,
-                                                    pool_full, worst_score, cand, s_spb, s_spn, s_txb, s_txn, s_dn, c, newk);
+            nskipped += ap_score_candidates<DT, NV, false>(g.D, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score, cand, s_spb, s_spn,
+                                                           s_txb, s_txn, s_dn, c, newk);
         __syncthreads();
         // sort the new keys by ranking them among themselves; only those that
         // rank before the pool's last entry (when the pool is full) can enter
@@ -297,7 +319,7 @@ extern "C" int ap_search_batch(ap_index *ix, const ap_queries *q, const float *p
     g.dnorm = ix->dense_norm;
     ix->last_nq = q->nq;
     AP_TRY(ap_fill_u32(ix->visited, need, 0u, st));
-    const size_t smem = (size_t)(g.L + 3 * g.cmax) * 8 + (size_t)g.cmax * (8 + 8 + 4 + 4 + 4 + 4) + 4 * AP_Q_CAP * 4;
+    const size_t smem = (size_t)(g.L + 3 * g.cmax) * 8 + (size_t)g.cmax * (4 + 4 + 4 + 4 + 4 + 4) + ((1 << AP_QSP_BITS) + (1 << AP_QTX_BITS)) * 8;
     AP_CHECK_HIP(hipEventRecord(ix->ev_search[0], st));
     AP_REQUIRE(smem <= 160 * 1024, "beam and search_width need %zu bytes of LDS (limit 160 KiB)", smem);
     hipError_t le = hipSuccess;
