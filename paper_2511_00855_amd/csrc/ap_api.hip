@@ -104,6 +104,33 @@ __global__ void k_self_sim(ApVecs D, float wd, float ws, float wf, float *__rest
     }
 }
 
+// Search-side records: per document, its sparse entries then its lexical entries (term, weight bits),
+// plus a 16-byte descriptor.  One wave per document.
+__global__ void k_pack_records(ApVecs D, const float *__restrict__ dnorm, uint2 *__restrict__ rec, uint4 *__restrict__ meta) {
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (blockIdx.x * (int64_t)blockDim.x + threadIdx.x) >> 6;
+    const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    for (int64_t v = wave; v < D.n; v += nwaves) {
+        const int64_t sb = D.sp_indptr[v], tb = D.tx_indptr[v];
+        const int32_t sn = (int32_t)(D.sp_indptr[v + 1] - sb), tn = (int32_t)(D.tx_indptr[v + 1] - tb);
+        const int64_t off = sb + tb;
+        for (int32_t e = lane; e < sn; e += 64) rec[off + e] = make_uint2((uint32_t)D.sp_idx[sb + e], __float_as_uint(D.sp_val[sb + e]));
+        for (int32_t e = lane; e < tn; e += 64) rec[off + sn + e] = make_uint2((uint32_t)D.tx_idx[tb + e], __float_as_uint(D.tx_val[tb + e]));
+        if (lane == 0) meta[v] = make_uint4((uint32_t)off, (uint32_t)sn | ((uint32_t)tn << 16), __float_as_uint(dnorm[v]), 0u);
+    }
+}
+
+// largest list length of either part (documents whose lists do not fit the 16-bit counts of a descriptor are refused)
+__global__ void k_max_list_len(const int64_t *__restrict__ sp_indptr, const int64_t *__restrict__ tx_indptr, int64_t n, int32_t *out) {
+    int32_t m = 0;
+    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t a = sp_indptr[i + 1] - sp_indptr[i], b = tx_indptr[i + 1] - tx_indptr[i];
+        const int64_t x = a > b ? a : b;
+        m = x > m ? (x > 0x7fffffff ? 0x7fffffff : (int32_t)x) : m;
+    }
+    atomicMax(out, m);
+}
+
 __global__ void k_fill_u32(uint32_t *p, size_t n, uint32_t v) {
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
 }
@@ -126,8 +153,7 @@ int ap_ingest_impl(ap_index *ix, hipStream_t st) {
     AP_CHECK_HIP(hipMemcpyAsync(&sp_last, c.sp_indptr + c.n, sizeof(int64_t), hipMemcpyDeviceToHost, st));
     AP_CHECK_HIP(hipStreamSynchronize(st));
     AP_REQUIRE(last >= 0 && sp_last >= 0, "indptr[n] is negative");
-    AP_REQUIRE(last < (1ll << 30) && sp_last < (1ll << 30),
-               "each CSR part must hold fewer than 2^30 entries (the search addresses list entries with 32-bit byte offsets)");
+    AP_REQUIRE(last + sp_last < (1ll << 32), "the two CSR parts together must hold fewer than 2^32 entries");
     ix->tx_nnz = last;
     AP_TRY(ap_dev_alloc(&ix->tx_w, (size_t)last));
     AP_TRY(ap_dev_alloc(&ix->df, (size_t)c.tx_vocab));
@@ -160,6 +186,21 @@ int ap_ingest_impl(ap_index *ix, hipStream_t st) {
             hipLaunchKernelGGL(k_self_sim<AP_BF16>, dim3(blocks), dim3(256), 0, st, ix->docs, w[0], w[1], w[2], ix->self_sim, ix->dense_norm);
         AP_CHECK_HIP(hipGetLastError());
     }
+    {
+        AP_TRY(ap_dev_alloc(&ix->rec, (size_t)(last + sp_last)));
+        AP_TRY(ap_dev_alloc(&ix->meta, (size_t)c.n));
+        int32_t *mx = reinterpret_cast<int32_t *>(ix->stats + 1);
+        int blocks = (int)((c.n + 255) / 256 < 4096 ? (c.n + 255) / 256 : 4096);
+        hipLaunchKernelGGL(k_max_list_len, dim3(blocks), dim3(256), 0, st, c.sp_indptr, c.tx_indptr, c.n, mx);
+        AP_CHECK_HIP(hipGetLastError());
+        int32_t longest = 0;
+        AP_CHECK_HIP(hipMemcpyAsync(&longest, mx, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+        AP_CHECK_HIP(hipStreamSynchronize(st));
+        AP_REQUIRE(longest < 65536, "a document list has %d entries; at most 65535 per part are supported", longest);
+        int64_t waves = c.n < 16384 ? c.n : 16384;
+        hipLaunchKernelGGL(k_pack_records, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, ix->docs, ix->dense_norm, ix->rec, ix->meta);
+        AP_CHECK_HIP(hipGetLastError());
+    }
     AP_CHECK_HIP(hipMemcpyAsync(ix->w_dev, ix->w_default, 3 * sizeof(float), hipMemcpyHostToDevice, st));
     AP_CHECK_HIP(hipStreamSynchronize(st));
     return AP_OK;
@@ -190,7 +231,7 @@ extern "C" int ap_ingest(const ap_corpus *corpus, const ap_build_params *params,
 extern "C" void ap_free_index(ap_index *ix) {
     if (!ix) return;
     void *ptrs[] = {ix->tx_w, ix->df, ix->stats, ix->self_sim, ix->graph, ix->kw, ix->kw_count, ix->entry, ix->visited, ix->w_dev,
-                    ix->search_counts, ix->dense_norm};
+                    ix->search_counts, ix->dense_norm, ix->rec, ix->meta};
     for (void *p : ptrs) if (p) (void)hipFree(p);
     for (hipEvent_t e : ix->ev_search) if (e) (void)hipEventDestroy(e);
     delete ix;

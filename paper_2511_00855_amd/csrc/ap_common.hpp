@@ -63,6 +63,11 @@ struct ap_index {
     float *stats = nullptr;    // owned: [0] avgdl
     float *self_sim = nullptr; // owned: fused self-similarity under build_w
     float *dense_norm = nullptr; // owned: |d_dense| per document (upper bound of the dense part in the search)
+    // owned: the search-side copy of the two sparse parts, one contiguous record per document:
+    // rec[meta.x .. +sp_n) = (term, weight bits) of the learned-sparse list, then tx_n lexical entries;
+    // meta[v] = {first entry, sp_n | tx_n << 16, bits of |d_dense|, 0}
+    uint2 *rec = nullptr;
+    uint4 *meta = nullptr;
     int32_t *graph = nullptr;  // owned: n x degree
     int32_t *kw = nullptr;     // owned: n x degree/2
     int32_t *kw_count = nullptr;
@@ -401,6 +406,92 @@ __device__ __forceinline__ void ap_lists_reduce_tab(const ApVecs &B, const AP_LD
         const int32_t t = e < txn ? ap_ld32(B.tx_idx, txb + (uint32_t)e) : -1;
         const float x = e < txn ? ap_ld32(B.tx_val, txb + (uint32_t)e) : 0.f;
         pf = fmaf(t >= 0 ? ap_table_get(ttx, 1 << TXB, TXB, t) : 0.f, x, pf);
+    }
+    ss = ap_wave_sum(ps);
+    sf = ap_wave_sum(pf);
+}
+
+// ---- packed document records (search side) -------------------------------
+// One document's sparse entries followed by its lexical entries, 8 bytes each
+// (term id, weight bits), so that a candidate costs one contiguous segment
+// and one 16-byte descriptor instead of four segments and five scattered words.
+// `r` points at the document's first entry (wave-uniform).
+template <int SS, int TS>
+__device__ __forceinline__ void ap_rec_load(const uint2 *r, int32_t spn, int32_t txn, int32_t *si, float *sv, int32_t *ti, float *tv) {
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int k = 0; k < SS; k++) {
+        const int32_t e = k * 64 + lane;
+        uint2 x = make_uint2(0xffffffffu, 0u);
+        if (e < spn) x = r[e];
+        si[k] = (int32_t)x.x; sv[k] = __uint_as_float(x.y);
+    }
+#pragma unroll
+    for (int k = 0; k < TS; k++) {
+        const int32_t e = k * 64 + lane;
+        uint2 x = make_uint2(0xffffffffu, 0u);
+        if (e < txn) x = r[spn + e];
+        ti[k] = (int32_t)x.x; tv[k] = __uint_as_float(x.y);
+    }
+}
+
+// Sparse and lexical sums of a packed record against the a side's look-up
+// tables; same per-lane accumulation order as ap_lists_reduce.
+template <int SS, int TS, int SPB, int TXB>
+__device__ __forceinline__ void ap_rec_reduce_tab(const uint2 *r, const AP_LDS uint64_t *tsp, const AP_LDS uint64_t *ttx, int32_t spn,
+                                                  int32_t txn, const int32_t *si, const float *sv, const int32_t *ti,
+                                                  const float *tv, float &ss, float &sf) {
+    const int lane = threadIdx.x & 63;
+    int32_t term[SS + TS];
+    float av[SS + TS];
+#pragma unroll
+    for (int k = 0; k < SS; k++) term[k] = si[k];
+#pragma unroll
+    for (int k = 0; k < TS; k++) term[SS + k] = ti[k];
+    ap_table_get_many<SS + TS, SS, SPB, TXB>(tsp, ttx, term, av);
+    float ps = 0.f, pf = 0.f;
+#pragma unroll
+    for (int k = 0; k < SS; k++) ps = fmaf(av[k], sv[k], ps);
+    for (int32_t e0 = SS * 64; e0 < spn; e0 += 64) {
+        const int32_t e = e0 + lane;
+        uint2 x = make_uint2(0xffffffffu, 0u);
+        if (e < spn) x = r[e];
+        ps = fmaf((int32_t)x.x >= 0 ? ap_table_get(tsp, 1 << SPB, SPB, (int32_t)x.x) : 0.f, __uint_as_float(x.y), ps);
+    }
+#pragma unroll
+    for (int k = 0; k < TS; k++) pf = fmaf(av[SS + k], tv[k], pf);
+    for (int32_t e0 = TS * 64; e0 < txn; e0 += 64) {
+        const int32_t e = e0 + lane;
+        uint2 x = make_uint2(0xffffffffu, 0u);
+        if (e < txn) x = r[spn + e];
+        pf = fmaf((int32_t)x.x >= 0 ? ap_table_get(ttx, 1 << TXB, TXB, (int32_t)x.x) : 0.f, __uint_as_float(x.y), pf);
+    }
+    ss = ap_wave_sum(ps);
+    sf = ap_wave_sum(pf);
+}
+
+// The same sums with the a side's lists searched where they lie (lists too long for the tables).
+template <int SS, int TS>
+__device__ __forceinline__ void ap_rec_reduce_lists(const uint2 *r, const ApLists &a, int32_t spn, int32_t txn, const int32_t *si,
+                                                    const float *sv, const int32_t *ti, const float *tv, float &ss, float &sf) {
+    const int lane = threadIdx.x & 63;
+    const int32_t sp_step = ap_pow2_floor(a.sp_n), tx_step = ap_pow2_floor(a.tx_n);
+    float ps = 0.f, pf = 0.f;
+#pragma unroll
+    for (int k = 0; k < SS; k++) ps = ap_match_fma(a.sp_idx, a.sp_val, a.sp_n, sp_step, si[k], sv[k], ps);
+    for (int32_t e0 = SS * 64; e0 < spn; e0 += 64) {
+        const int32_t e = e0 + lane;
+        uint2 x = make_uint2(0xffffffffu, 0u);
+        if (e < spn) x = r[e];
+        ps = ap_match_fma(a.sp_idx, a.sp_val, a.sp_n, sp_step, (int32_t)x.x, __uint_as_float(x.y), ps);
+    }
+#pragma unroll
+    for (int k = 0; k < TS; k++) pf = ap_match_fma(a.tx_idx, a.tx_val, a.tx_n, tx_step, ti[k], tv[k], pf);
+    for (int32_t e0 = TS * 64; e0 < txn; e0 += 64) {
+        const int32_t e = e0 + lane;
+        uint2 x = make_uint2(0xffffffffu, 0u);
+        if (e < txn) x = r[spn + e];
+        pf = ap_match_fma(a.tx_idx, a.tx_val, a.tx_n, tx_step, (int32_t)x.x, __uint_as_float(x.y), pf);
     }
     ss = ap_wave_sum(ps);
     sf = ap_wave_sum(pf);

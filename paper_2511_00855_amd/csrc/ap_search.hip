@@ -26,7 +26,8 @@ struct ApSearchArgs {
     int32_t *out_ids;
     float *out_scores;
     int32_t *counts;    // nq x 3: candidates scored, iterations, candidates whose dense row was skipped
-    const float *dnorm; // |d_dense| per document
+    const uint2 *rec;   // packed (term, weight) records of the documents' two sparse parts
+    const uint4 *meta;  // per document: first entry, counts, |d_dense|
 };
 
 // Number of entries of the descending array keys[0..n) that rank before `key`.
@@ -49,43 +50,52 @@ __device__ __forceinline__ int32_t ap_rank_in(const uint64_t *keys, int32_t n, u
 // they are searched where they lie in global memory.
 // Returns the number of candidates whose dense row was skipped (wave-uniform).
 #ifndef AP_SEARCH_G
-#define AP_SEARCH_G 2
+#define AP_SEARCH_G 1
 #endif
 #define AP_QSP_BITS 8    // query sparse table: 256 slots, lists up to 64 entries
 #define AP_QTX_BITS 7    // query lexical table: 128 slots, lists up to 32 entries
 
 template <int DT, int NV, bool TAB>
-__device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const float *qa, const uint64_t *qtab, const ApLists &a,
-                                                       float wd, float ws, float wf, float qnorm, bool pool_full,
-                                                       float worst_score, const int32_t *cand, const uint32_t *s_spb,
-                                                       const int32_t *s_spn, const uint32_t *s_txb, const int32_t *s_txn,
-                                                       const float *s_dn, int32_t c, uint64_t *newk) {
+__device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const uint2 *rec, const float *qa, const uint64_t *qtab,
+                                                       const ApLists &a, float wd, float ws, float wf, float qnorm, bool pool_full,
+                                                       float worst_score, const int32_t *cand, const uint4 *s_meta, int32_t c,
+                                                       uint64_t *newk) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int32_t skipped = 0;
     constexpr int G = AP_SEARCH_G;   // candidates whose list segments are in flight together
     for (int32_t i0 = wave; i0 < c; i0 += 4 * G) {
         int32_t si[G][2], ti[G][1];
         float sv[G][2], tv[G][1];
+        const uint2 *r[G];
+        int32_t spn[G], txn[G];
+        float dn[G];
 #pragma unroll
         for (int gi = 0; gi < G; gi++) {
             const int32_t i = i0 + 4 * gi;
-            if (i < c) ap_lists_load32<2, 1>(D, s_spb[i], s_spn[i], s_txb[i], s_txn[i], si[gi], sv[gi], ti[gi], tv[gi]);
+            if (i < c) {
+                const uint4 m = s_meta[i];
+                // the descriptor is the same in every lane: keep the record's address in scalar registers
+                r[gi] = rec + __builtin_amdgcn_readfirstlane(m.x);
+                spn[gi] = __builtin_amdgcn_readfirstlane((int32_t)(m.y & 0xffffu));
+                txn[gi] = __builtin_amdgcn_readfirstlane((int32_t)(m.y >> 16));
+                dn[gi] = __uint_as_float(__builtin_amdgcn_readfirstlane(m.z));
+                ap_rec_load<2, 1>(r[gi], spn[gi], txn[gi], si[gi], sv[gi], ti[gi], tv[gi]);
+            }
         }
 #pragma unroll
         for (int gi = 0; gi < G; gi++) {
             const int32_t i = i0 + 4 * gi;
             if (i >= c) continue;
-            const int32_t v = cand[i];
+            const int32_t v = __builtin_amdgcn_readfirstlane(cand[i]);
             float ss, sf;
             if (TAB)
-                ap_lists_reduce_tab<2, 1, AP_QSP_BITS, AP_QTX_BITS>(D, (const AP_LDS uint64_t *)qtab,
-                                                                    (const AP_LDS uint64_t *)(qtab + (1 << AP_QSP_BITS)), s_spb[i],
-                                                                    s_spn[i], s_txb[i], s_txn[i], si[gi], sv[gi], ti[gi], tv[gi], ss, sf);
+                ap_rec_reduce_tab<2, 1, AP_QSP_BITS, AP_QTX_BITS>(r[gi], (const AP_LDS uint64_t *)qtab,
+                                                                  (const AP_LDS uint64_t *)(qtab + (1 << AP_QSP_BITS)), spn[gi], txn[gi],
+                                                                  si[gi], sv[gi], ti[gi], tv[gi], ss, sf);
             else
-                ap_lists_reduce<2, 1>(D, a.sp_idx, a.sp_val, a.sp_n, a.tx_idx, a.tx_val, a.tx_n, (int64_t)s_spb[i], s_spn[i],
-                                      (int64_t)s_txb[i], s_txn[i], si[gi], sv[gi], ti[gi], tv[gi], ss, sf);
+                ap_rec_reduce_lists<2, 1>(r[gi], a, spn[gi], txn[gi], si[gi], sv[gi], ti[gi], tv[gi], ss, sf);
             // upper bound of the fused score, with slack far above fp32 rounding
-            const float dmax = fabsf(wd) * qnorm * s_dn[i] * 1.0001f;
+            const float dmax = fabsf(wd) * qnorm * dn[gi] * 1.0001f;
             const float part = fmaf(wf, sf, ws * ss);
             const float ub = part + dmax + 1e-5f * (fabsf(ws * ss) + fabsf(wf * sf) + dmax);
             uint64_t key;
@@ -103,7 +113,7 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const fl
 }
 
 #ifndef AP_SEARCH_WAVES_PER_SIMD
-#define AP_SEARCH_WAVES_PER_SIMD 6
+#define AP_SEARCH_WAVES_PER_SIMD 7
 #endif
 template <int DT, int NV>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_WAVES_PER_SIMD, 8))) void k_search(ApSearchArgs g) {
@@ -113,12 +123,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
     uint64_t *newS = newk + g.cmax;          // the same, sorted
     uint64_t *nxt = newS + g.cmax;           // scratch of cmax words
     uint64_t *qtab = nxt + g.cmax;           // the query's two look-up tables
-    uint32_t *s_spb = reinterpret_cast<uint32_t *>(qtab + (1 << AP_QSP_BITS) + (1 << AP_QTX_BITS));
-    uint32_t *s_txb = s_spb + g.cmax;
-    int32_t *s_spn = reinterpret_cast<int32_t *>(s_txb + g.cmax);
-    int32_t *s_txn = s_spn + g.cmax;
-    float *s_dn = reinterpret_cast<float *>(s_txn + g.cmax);
-    int32_t *cand = reinterpret_cast<int32_t *>(s_dn + g.cmax);
+    // descriptors of this iteration's candidates (16-byte aligned: an odd pool size shifts them by one word)
+    uint4 *s_meta = reinterpret_cast<uint4 *>(qtab + (1 << AP_QSP_BITS) + (1 << AP_QTX_BITS) + ((g.L + 3 * g.cmax) & 1));
+    int32_t *cand = reinterpret_cast<int32_t *>(s_meta + g.cmax);
     __shared__ int32_t s_cnt, s_np, s_skip;
     __shared__ int32_t s_par[8];
 
@@ -168,24 +175,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
     for (;;) {
         const int32_t c = s_cnt;
         nscored += c;
-        // where each candidate's lists are: one round of loads for all of them
-        for (int32_t i = threadIdx.x; i < c; i += blockDim.x) {
-            const int32_t v = cand[i];
-            const int64_t sb = g.D.sp_indptr[v], tb = g.D.tx_indptr[v];
-            s_spb[i] = (uint32_t)sb; s_spn[i] = (int32_t)(g.D.sp_indptr[v + 1] - sb);
-            s_txb[i] = (uint32_t)tb; s_txn[i] = (int32_t)(g.D.tx_indptr[v + 1] - tb);
-            s_dn[i] = g.dnorm[v];
-        }
+        // each candidate's descriptor (where its record is, how long, its dense norm): one round of 16-byte loads
+        for (int32_t i = threadIdx.x; i < c; i += blockDim.x) s_meta[i] = g.meta[cand[i]];
         __syncthreads();
         const bool pool_full = len == g.L;
         const uint64_t worst = pool_full ? cur[g.L - 1] : 0ull;
         const float worst_score = ap_key_score(worst);
         if (use_tab)
-            nskipped += ap_score_candidates<DT, NV, true>(g.D, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score, cand, s_spb, s_spn,
-                                                          s_txb, s_txn, s_dn, c, newk);
+            nskipped += ap_score_candidates<DT, NV, true>(g.D, g.rec, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score, cand, s_meta, c, newk);
         else
-            nskipped += ap_score_candidates<DT, NV, false>(g.D, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score, cand, s_spb, s_spn,
-                                                           s_txb, s_txn, s_dn, c, newk);
+            nskipped += ap_score_candidates<DT, NV, false>(g.D, g.rec, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score, cand, s_meta, c, newk);
         __syncthreads();
         // sort the new keys by ranking them among themselves; only those that
         // rank before the pool's last entry (when the pool is full) can enter
@@ -316,10 +315,11 @@ extern "C" int ap_search_batch(ap_index *ix, const ap_queries *q, const float *p
     g.out_ids = out_ids;
     g.out_scores = out_scores;
     g.counts = ix->search_counts;
-    g.dnorm = ix->dense_norm;
+    g.rec = ix->rec;
+    g.meta = ix->meta;
     ix->last_nq = q->nq;
     AP_TRY(ap_fill_u32(ix->visited, need, 0u, st));
-    const size_t smem = (size_t)(g.L + 3 * g.cmax) * 8 + (size_t)g.cmax * (4 + 4 + 4 + 4 + 4 + 4) + ((1 << AP_QSP_BITS) + (1 << AP_QTX_BITS)) * 8;
+    const size_t smem = (size_t)(g.L + 3 * g.cmax) * 8 + (size_t)g.cmax * (16 + 4) + ((1 << AP_QSP_BITS) + (1 << AP_QTX_BITS)) * 8 + 8;
     AP_CHECK_HIP(hipEventRecord(ix->ev_search[0], st));
     AP_REQUIRE(smem <= 160 * 1024, "beam and search_width need %zu bytes of LDS (limit 160 KiB)", smem);
     hipError_t le = hipSuccess;
