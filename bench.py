@@ -152,17 +152,25 @@ def main():
     tx_nnz = float(w.docs.tx_indptr[-1]) / w.docs.n
     dense_bytes = w.docs.dim * (2 if bf16 else 4)
     bytes_per_dist = dense_bytes + 8.0 * sp_nnz + 8.0 * tx_nnz + 32.0   # rows + 4 offsets
-    # algorithmic bytes: the per-similarity figure times the similarities the launch evaluated
-    bytes_per_launch = n_dist * bytes_per_dist + n_iter * w.degree * 4.0
-    # bytes the kernel actually had to move: a candidate that provably cannot enter the pool is
-    # evaluated without its dense row (its norm, 4 B, is read instead)
-    bytes_needed = bytes_per_launch - n_skip * (dense_bytes - 4.0)
+    # algorithmic bytes per launch = units x per-unit figure, for the two kinds of unit the kernel counts:
+    #   a full similarity (descriptor + lists + dense row) and a partial one (the candidate provably cannot
+    #   enter the pool, so its dense row is not needed: descriptor + lists only), plus the edge rows.
+    partial_bytes = bytes_per_dist - dense_bytes
+    bytes_per_launch = (n_dist - n_skip) * bytes_per_dist + n_skip * partial_bytes + n_iter * w.degree * 4.0
+    bytes_if_all_full = n_dist * bytes_per_dist + n_iter * w.degree * 4.0
     k_ms = float(np.mean(kernel_ms))
     achieved = bytes_per_launch / (k_ms * 1e-3) / 1e9
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", f"k_search_{args.workload}_beam{chosen}_traffic.json")
+    if os.path.exists(tfile):      # HBM-side bytes per launch from the committed rocprofv3 --pmc summary of this same configuration
+        t = json.load(open(tfile))
+        traffic = round(t["fetch_bytes_per_launch"] + t["write_bytes_per_launch"])
     roofline = dict(bound="hbm", kernel="k_search", achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None, kernel_ms=round(k_ms, 3),
-                    bytes_per_dist=round(bytes_per_dist, 1), dists_per_launch=n_dist, dense_rows_skipped=n_skip,
-                    needed_GBps_after_dense_skip=round(bytes_needed / (k_ms * 1e-3) / 1e9, 1),
+                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=traffic, kernel_ms=round(k_ms, 3),
+                    bytes_per_full_similarity=round(bytes_per_dist, 1), bytes_per_partial_similarity=round(partial_bytes, 1),
+                    similarities_per_launch=n_dist, partial_similarities_per_launch=n_skip,
+                    algorithmic_bytes_per_launch=round(bytes_per_launch),
+                    GBps_if_every_similarity_were_full=round(bytes_if_all_full / (k_ms * 1e-3) / 1e9, 1),
                     dists_per_s=round(n_dist / (k_ms * 1e-3), 1))
 
     # ---- CPU baseline: the oracle as it stands, one thread, bounded sample of the same searches

@@ -27,7 +27,8 @@
  *    Every ranking is by (score descending, id ascending).  A missing result
  *    has id -1 and score -inf.
  *  - CSR rows must hold strictly ascending term ids in [0, vocab).  ids of
- *    documents must fit 30 bits (n < 2^30).
+ *    documents must fit 30 bits (n < 2^30); the two CSR parts together hold
+ *    fewer than 2^32 entries and no list more than 65,535 (else AP_EINVAL).
  *  - Calls on one index from several host threads at once are not supported
  *    (the search workspace is per index).
  */
