@@ -43,6 +43,7 @@ def lib():
         _lib = C.CDLL(build())
         _lib.orc_sparse_ip.restype = C.c_double
         _lib.orc_search.restype = C.c_int64
+        _lib.orc_search_kw.restype = C.c_int64
         _lib.orc_bm25_encode.restype = C.c_int
     return _lib
 
@@ -303,3 +304,25 @@ def search_batch(D: VS, graph, entry, Q: VS, q_ids: Sequence[int], w, k, L, max_
     for x, qi in enumerate(q_ids):
         ids[x], sc[x], nv[x] = search(D, graph, entry, Q, qi, w[x], k, L, max_iters, width)
     return ids, sc, nv
+
+
+def search_kw(D: VS, graph, kw_edges, kw_count, entry, Q: VS, qi, w, k, L, kw, kw_all=False, use_kw_edges=True,
+              max_iters=0, width=1, score_table=None, log=False):
+    """Keyword-constrained search (Section 4.2.2, Algorithm 2's keyword branches) for one query.
+    kw: the required term ids (empty = unconstrained)."""
+    graph = _c(graph, np.int32); kw_edges = _c(kw_edges, np.int32); kw_count = _c(kw_count, np.int32)
+    entry = _c(entry, np.int32)
+    kw = _c(np.asarray(kw, np.int32).reshape(-1), np.int32)
+    w = _c(w, np.float32)
+    ids = np.empty(k, np.int32); sc = np.empty(k, np.float32)
+    st = None if score_table is None else _c(score_table, np.float32)
+    cap = D.n if log else 0
+    vl = np.empty(max(cap, 1), np.int32)
+    n = lib().orc_search_kw(D.ref, _p(graph), C.c_int32(graph.shape[1]), _p(kw_edges), C.c_int32(kw_edges.shape[1]),
+                            _p(kw_count), _p(entry), C.c_int32(len(entry)), Q.ref, C.c_int64(qi), _p(w), C.c_int32(k),
+                            C.c_int32(L), C.c_int32(max_iters), C.c_int32(width), _p(kw), C.c_int32(len(kw)),
+                            C.c_int32(int(kw_all)), C.c_int32(int(use_kw_edges)), _p(st), _p(ids), _p(sc),
+                            _p(vl) if log else None, C.c_int64(cap))
+    if log:
+        return ids, sc, vl[:n].copy()
+    return ids, sc, int(n)

@@ -542,3 +542,126 @@ int64_t orc_search(const orc_vecset *D, const int32_t *graph, int32_t R, const i
     free(visited); free(pool); free(expanded); free(parents);
     return nscored;
 }
+
+/* ------------------------------------------------------------------ */
+/* Keyword-constrained search (Section 4.2.2 and the keyword branches of
+ * Algorithm 2).  KW = the required term ids; K(v) = the terms of document
+ * v's text.  A document "satisfies" the constraint when K(v) meets KW
+ * (kw_all = 0, the condition Algorithm 2 writes) or contains all of KW
+ * (kw_all = 1).  Differences from the base search:
+ *  - a parent that satisfies the constraint also expands its keyword edges
+ *    (after its semantic edges; off when use_kw_edges = 0);
+ *  - every satisfying document that is scored but not kept by the pool --
+ *    rejected on arrival or evicted later -- goes to a secondary pool that
+ *    keeps the k best of them;
+ *  - the result is the k best satisfying documents of pool and secondary
+ *    pool together.
+ * n_kw = 0 means "no constraint": the base search.                     */
+static int kw_satisfied(const orc_vecset *D, int64_t v, const int32_t *kw, int32_t n_kw, int32_t kw_all) {
+    int32_t hits = 0, j;
+    int64_t p;
+    for (j = 0; j < n_kw; j++) {
+        int found = 0;
+        for (p = D->tx_indptr[v]; p < D->tx_indptr[v + 1]; p++)
+            if (D->tx_idx[p] == kw[j]) found = 1;
+        hits += found;
+    }
+    return kw_all ? hits == n_kw : hits > 0;
+}
+
+int64_t orc_search_kw(const orc_vecset *D, const int32_t *graph, int32_t R, const int32_t *kw_edges, int32_t KR,
+                      const int32_t *kw_count, const int32_t *entry, int32_t E, const orc_vecset *Q, int64_t qi,
+                      const float w[3], int32_t k, int32_t L, int32_t max_iters, int32_t width, const int32_t *kw,
+                      int32_t n_kw, int32_t kw_all, int32_t use_kw_edges, const float *score_table, int32_t *out_ids,
+                      float *out_scores, int32_t *visit_log, int64_t log_cap) {
+    int64_t N = D->n, nscored = 0;
+    unsigned char *visited = (unsigned char *)calloc((size_t)(N > 0 ? N : 1), 1);
+    scored *pool = (scored *)malloc(sizeof(scored) * (size_t)(L + 1));
+    unsigned char *expanded = (unsigned char *)malloc((size_t)(L + 1));
+    unsigned char *sat = (unsigned char *)malloc((size_t)(L + 1));      /* pool entry satisfies the constraint */
+    scored *second = (scored *)malloc(sizeof(scored) * (size_t)(k + 1)); /* secondary pool, best first */
+    scored *all = (scored *)malloc(sizeof(scored) * (size_t)(L + k + 1));
+    int32_t *parents = (int32_t *)malloc(sizeof(int32_t) * (size_t)(width > 0 ? width : 1));
+    unsigned char *psat = (unsigned char *)malloc((size_t)(width > 0 ? width : 1));   /* parent satisfies the constraint */
+    int32_t len = 0, nsec = 0, it = 0, i, e, nall = 0;
+
+    if (n_kw <= 0) {
+        free(visited); free(pool); free(expanded); free(sat); free(second); free(all); free(parents); free(psat);
+        return orc_search(D, graph, R, entry, E, Q, qi, w, k, L, max_iters, width, score_table, out_ids, out_scores,
+                          visit_log, log_cap);
+    }
+    /* one newly seen document: score it, offer it to the pool, pass what the pool does not keep to the secondary pool */
+#define KW_VISIT(v)                                                                                   \
+    do {                                                                                              \
+        scored out_;                                                                                  \
+        int out_sat_ = 0, have_out_ = 0, p_;                                                          \
+        float s_ = score_table ? score_table[(v)] : hybrid_fused(Q, qi, D, (v), w);                   \
+        int sat_ = kw_satisfied(D, (v), kw, n_kw, kw_all);                                            \
+        if (visit_log && nscored < log_cap) visit_log[nscored] = (v);                                 \
+        nscored++;                                                                                    \
+        if (len == L && !ranks_before(s_, (v), pool[len - 1].s, pool[len - 1].id)) {                  \
+            out_.s = s_; out_.id = (v); out_sat_ = sat_; have_out_ = 1;                               \
+        } else {                                                                                      \
+            if (len == L) { out_ = pool[len - 1]; out_sat_ = sat[len - 1]; have_out_ = 1; len--; }    \
+            p_ = len;                                                                                 \
+            while (p_ > 0 && ranks_before(s_, (v), pool[p_ - 1].s, pool[p_ - 1].id)) {                \
+                pool[p_] = pool[p_ - 1]; expanded[p_] = expanded[p_ - 1]; sat[p_] = sat[p_ - 1]; p_--; \
+            }                                                                                         \
+            pool[p_].s = s_; pool[p_].id = (v); expanded[p_] = 0; sat[p_] = (unsigned char)sat_; len++; \
+        }                                                                                             \
+        if (have_out_ && out_sat_ &&                                                                  \
+            (nsec < k || ranks_before(out_.s, out_.id, second[nsec - 1].s, second[nsec - 1].id))) {   \
+            if (nsec == k) nsec--;                                                                    \
+            p_ = nsec;                                                                                \
+            while (p_ > 0 && ranks_before(out_.s, out_.id, second[p_ - 1].s, second[p_ - 1].id)) {    \
+                second[p_] = second[p_ - 1]; p_--;                                                    \
+            }                                                                                         \
+            second[p_] = out_; nsec++;                                                                \
+        }                                                                                             \
+    } while (0)
+
+    for (e = 0; e < E; e++) {
+        int32_t v = entry[e];
+        if (v < 0 || visited[v]) continue;
+        visited[v] = 1;
+        KW_VISIT(v);
+    }
+    while (max_iters <= 0 || it < max_iters) {
+        int32_t np = 0;
+        for (i = 0; i < len && np < width; i++)
+            if (!expanded[i]) { expanded[i] = 1; psat[np] = sat[i]; parents[np++] = pool[i].id; }
+        if (np == 0) break;
+        for (i = 0; i < np; i++) {
+            const int32_t u = parents[i];
+            const int32_t *nb = graph + (int64_t)u * R;
+            for (e = 0; e < R; e++) {
+                int32_t v = nb[e];
+                if (v < 0 || visited[v]) continue;
+                visited[v] = 1;
+                KW_VISIT(v);
+            }
+            /* the keyword edges of a parent that itself satisfies the constraint */
+            if (use_kw_edges && psat[i]) {
+                const int32_t *ke = kw_edges + (int64_t)u * KR;
+                for (e = 0; e < kw_count[u] && e < KR; e++) {
+                    int32_t v = ke[e];
+                    if (v < 0 || visited[v]) continue;
+                    visited[v] = 1;
+                    KW_VISIT(v);
+                }
+            }
+        }
+        it++;
+    }
+#undef KW_VISIT
+    /* merge both pools, keep the satisfying documents, best k */
+    for (i = 0; i < len; i++) if (sat[i]) all[nall++] = pool[i];
+    for (i = 0; i < nsec; i++) all[nall++] = second[i];
+    qsort(all, (size_t)nall, sizeof(scored), cmp_scored);
+    for (i = 0; i < k; i++) {
+        out_ids[i] = i < nall ? all[i].id : -1;
+        out_scores[i] = i < nall ? all[i].s : -INFINITY;
+    }
+    free(visited); free(pool); free(expanded); free(sat); free(second); free(all); free(parents); free(psat);
+    return nscored;
+}
