@@ -116,6 +116,26 @@ int ap_set_weights(ap_index *index, const float w[3]);
 int ap_search_batch(ap_index *index, const ap_queries *queries, const float *per_query_w,
                     const ap_search_params *params, int32_t *out_ids, float *out_scores, void *stream);
 
+/* Keyword-constrained search (Section 4.2.2; the keyword branches of
+ * Algorithm 2).  kw_terms (device): nq x kw_stride term ids of the lexical
+ * vocabulary that a result's text must contain, -1 = unused slot, kw_stride in
+ * [1, 16]; a query whose slots are all unused runs the plain search.  A
+ * document satisfies the constraint when its text holds at least one required
+ * term (the condition Algorithm 2 writes), or all of them with AP_KW_ALL.
+ * While searching, a parent that satisfies the constraint also expands its
+ * keyword edges (unless AP_KW_NO_EDGES), every scored satisfying document the
+ * pool does not keep -- rejected on arrival or evicted later -- goes to a
+ * secondary pool of the k best, and the result is the k best satisfying
+ * documents of both pools (-1 / -inf padded when fewer were met).  Satisfying
+ * candidates are always scored in full.  Needs n < 2^29 and an index with
+ * keyword edges (built here or imported).  Other arguments as ap_search_batch;
+ * ap_search_stats reports on this search as well. */
+#define AP_KW_ALL 1u
+#define AP_KW_NO_EDGES 2u
+int ap_search_batch_keywords(ap_index *index, const ap_queries *queries, const float *per_query_w,
+                             const ap_search_params *params, const int32_t *kw_terms, int32_t kw_stride,
+                             uint32_t kw_flags, int32_t *out_ids, float *out_scores, void *stream);
+
 void ap_free_index(ap_index *index);
 const char *ap_last_error(void); /* host string, thread-local */
 
@@ -183,7 +203,7 @@ int ap_import_graph(const ap_corpus *corpus, const ap_build_params *params, cons
                     const int32_t *keyword, const int32_t *kw_count, const int32_t *entry, void *stream,
                     ap_index **out);
 
-/* Counters of the last ap_search_batch on this index (synchronises on that
+/* Counters of the last search (plain or keyword-constrained) on this index (synchronises on that
  * search).  out_counts (device, may be NULL): nq x 3 int32 = per query the
  * number of candidates scored, the number of iterations, and the number of
  * scored candidates whose dense row was not read (their sparse + lexical parts

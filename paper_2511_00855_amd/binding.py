@@ -206,6 +206,27 @@ class Index:
         _check(rc, "ap_search_batch")
         return ids, sc
 
+    def search_batch_keywords(self, queries: DeviceVecs, k: int, beam: int, kw_terms, per_query_w=None,
+                              kw_all: bool = False, use_kw_edges: bool = True, max_iters: int = 0,
+                              search_width: int = 1):
+        """kw_terms: nq x stride int32 required term ids, -1 = unused slot (see ap_search_batch_keywords)."""
+        nq = queries.n
+        kw = _dev(kw_terms, torch.int32, self.device)
+        assert kw.dim() == 2 and kw.shape[0] == nq
+        ids = torch.empty((nq, k), dtype=torch.int32, device=self.device)
+        sc = torch.empty((nq, k), dtype=torch.float32, device=self.device)
+        w = None if per_query_w is None else _dev(per_query_w, torch.float32, self.device)
+        if w is not None:
+            assert w.shape == (nq, 3)
+        qs = queries.queries_struct()
+        sp = _SearchParams(k, beam, max_iters, search_width)
+        flags = (1 if kw_all else 0) | (0 if use_kw_edges else 2)
+        with torch.cuda.device(self.device):
+            rc = lib().ap_search_batch_keywords(self._h, C.byref(qs), _ptr(w), C.byref(sp), _ptr(kw), C.c_int32(kw.shape[1]),
+                                                C.c_uint32(flags), _ptr(ids), _ptr(sc), _stream())
+        _check(rc, "ap_search_batch_keywords")
+        return ids, sc
+
     # -- measurement / test surface -------------------------------------------
     def export_ingest(self):
         dev = self.device

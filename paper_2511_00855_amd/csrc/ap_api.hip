@@ -269,6 +269,7 @@ extern "C" int ap_import_graph(const ap_corpus *corpus, const ap_build_params *p
                                const int32_t *keyword, const int32_t *kw_count, const int32_t *entry, void *stream,
                                ap_index **out) {
     AP_REQUIRE(semantic && entry, "semantic and entry are required");
+    AP_REQUIRE((keyword == nullptr) == (kw_count == nullptr), "keyword and kw_count come together or not at all");
     AP_TRY(new_index(corpus, params, out));
     ap_index *ix = *out;
     hipStream_t st = (hipStream_t)stream;

@@ -1,5 +1,8 @@
-// S7-S9: batched best-first search on the semantic edges (Algorithm 2 without
-// its keyword and entity branches), one workgroup per query.
+// S7-S9: batched best-first search (Algorithm 2 without its entity branches),
+// one workgroup per query.  The KW instantiation adds the keyword branches of
+// Section 4.2.2: keyword edges of parents that satisfy the query's keyword
+// constraint, a secondary pool of satisfying documents the pool did not keep,
+// and the final filter.
 //
 // Per query, in LDS: the candidate pool (one sorted array of 64-bit keys that
 // plays both `cand` and `topk` of Algorithm 2; bit 0 of a key = "not yet
@@ -28,7 +31,25 @@ struct ApSearchArgs {
     int32_t *counts;    // nq x 3: candidates scored, iterations, candidates whose dense row was skipped
     const uint2 *rec;   // packed (term, weight) records of the documents' two sparse parts
     const uint4 *meta;  // per document: first entry, counts, |d_dense|
+    // keyword-constrained search only
+    const int32_t *kw_edges;   // n x KR keyword edges, kw_count[u] of them valid
+    const int32_t *kw_count;
+    const int32_t *kw_terms;   // nq x kw_stride required terms, -1 = unused slot
+    int32_t KR, kw_stride, kw_all, kw_use_edges;
 };
+
+// Pool keys.  Plain search: ap_make_key (30-bit id, bit 0 = "not yet expanded").
+// Keyword search: 29-bit id, bit 0 as before, bit 1 = "satisfies the keyword
+// constraint".  Ids are unique within a pool, so the flag bits never decide an order.
+#define AP_KW_MAX_TERMS 16
+template <bool KW> __device__ __forceinline__ uint64_t ap_pool_key(float s, int32_t id, uint32_t flags) {
+    if (KW) return ((uint64_t)ap_f2ord(s) << 32) | (uint64_t)(((0x1fffffffu - (uint32_t)id) << 2) | flags);
+    return ap_make_key(s, id, flags);
+}
+template <bool KW> __device__ __forceinline__ int32_t ap_pool_id(uint64_t k) {
+    if (KW) return (int32_t)(0x1fffffffu - (((uint32_t)k) >> 2));
+    return ap_key_id(k);
+}
 
 // Number of entries of the descending array keys[0..n) that rank before `key`.
 __device__ __forceinline__ int32_t ap_rank_in(const uint64_t *keys, int32_t n, uint64_t key) {
@@ -55,11 +76,14 @@ __device__ __forceinline__ int32_t ap_rank_in(const uint64_t *keys, int32_t n, u
 #define AP_QSP_BITS 8    // query sparse table: 256 slots, lists up to 64 entries
 #define AP_QTX_BITS 7    // query lexical table: 128 slots, lists up to 32 entries
 
-template <int DT, int NV, bool TAB>
+// KW: each candidate's lexical terms are also compared with the query's required
+// terms (s_kw[0..n_kw)); a candidate that satisfies the constraint is always
+// scored in full and its key carries the "satisfies" flag.
+template <int DT, int NV, bool TAB, bool KW>
 __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const uint2 *rec, const float *qa, const uint64_t *qtab,
                                                        const ApLists &a, float wd, float ws, float wf, float qnorm, bool pool_full,
                                                        float worst_score, const int32_t *cand, const uint4 *s_meta, int32_t c,
-                                                       uint64_t *newk) {
+                                                       uint64_t *newk, const int32_t *s_kw, int32_t n_kw, bool kw_all) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int32_t skipped = 0;
     constexpr int G = AP_SEARCH_G;   // candidates whose list segments are in flight together
@@ -98,13 +122,24 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const ui
             const float dmax = fabsf(wd) * qnorm * dn[gi] * 1.0001f;
             const float part = fmaf(wf, sf, ws * ss);
             const float ub = part + dmax + 1e-5f * (fabsf(ws * ss) + fabsf(wf * sf) + dmax);
+            uint32_t flags = 1u;
+            if (KW && n_kw > 0) {
+                uint32_t hit = 0;   // bit j: required term j occurs in the candidate's text
+                for (int32_t e0 = 0; e0 < txn[gi]; e0 += 64) {
+                    int32_t term = ti[gi][0];
+                    if (e0 > 0) term = e0 + lane < txn[gi] ? (int32_t)r[gi][spn[gi] + e0 + lane].x : -1;
+                    for (int32_t j = 0; j < n_kw; j++) hit |= __ballot(term == s_kw[j]) != 0ull ? 1u << j : 0u;
+                }
+                const bool sat = kw_all ? hit == (1u << n_kw) - 1u : hit != 0u;
+                flags |= sat ? 2u : 0u;
+            }
             uint64_t key;
-            if (pool_full && ub < worst_score) {
+            if (pool_full && ub < worst_score && !(flags & 2u)) {
                 key = (uint64_t)(uint32_t)(i + 1);   // ranks after every real key (score bits 0), distinct per candidate
                 skipped++;
             } else {
                 const float sd = ap_dense_dot<DT, NV>(D, qa, v);
-                key = ap_make_key(ap_fuse(wd, ws, wf, sd, ss, sf), v, 1u);
+                key = ap_pool_key<KW>(ap_fuse(wd, ws, wf, sd, ss, sf), v, flags);
             }
             if (lane == 0) newk[i] = key;
         }
@@ -115,19 +150,23 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const ui
 #ifndef AP_SEARCH_WAVES_PER_SIMD
 #define AP_SEARCH_WAVES_PER_SIMD 7
 #endif
-template <int DT, int NV>
+template <int DT, int NV, bool KW>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_WAVES_PER_SIMD, 8))) void k_search(ApSearchArgs g) {
     extern __shared__ uint64_t smem64[];
     uint64_t *cur = smem64;                  // the pool: L keys, best first
     uint64_t *newk = cur + g.L;              // keys of this iteration's candidates, unordered
     uint64_t *newS = newk + g.cmax;          // the same, sorted
     uint64_t *nxt = newS + g.cmax;           // scratch of cmax words
-    uint64_t *qtab = nxt + g.cmax;           // the query's two look-up tables
-    // descriptors of this iteration's candidates (16-byte aligned: an odd pool size shifts them by one word)
-    uint4 *s_meta = reinterpret_cast<uint4 *>(qtab + (1 << AP_QSP_BITS) + (1 << AP_QTX_BITS) + ((g.L + 3 * g.cmax) & 1));
+    uint64_t *xk = nxt + g.cmax;             // KW: satisfying keys the pool did not keep in this iteration (cmax words)
+    uint64_t *kwc = xk + (KW ? g.cmax : 0);  // KW: the secondary pool, k keys, best first
+    uint64_t *qtab = kwc + (KW ? g.k : 0);   // the query's two look-up tables
+    // descriptors of this iteration's candidates (16-byte aligned: an odd number of words before them shifts them by one)
+    uint4 *s_meta = reinterpret_cast<uint4 *>(qtab + (1 << AP_QSP_BITS) + (1 << AP_QTX_BITS) +
+                                              ((g.L + 3 * g.cmax + (KW ? g.cmax + g.k : 0)) & 1));
     int32_t *cand = reinterpret_cast<int32_t *>(s_meta + g.cmax);
-    __shared__ int32_t s_cnt, s_np, s_skip;
-    __shared__ int32_t s_par[8];
+    __shared__ int32_t s_cnt, s_np, s_skip, s_xn;
+    __shared__ int32_t s_par[8], s_psat[8];
+    __shared__ int32_t s_kw[AP_KW_MAX_TERMS];
 
     const int64_t q = blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -158,13 +197,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
     }
     const float wd = g.w[q * g.w_stride + 0], ws = g.w[q * g.w_stride + 1], wf = g.w[q * g.w_stride + 2];
     uint32_t *vis = g.visited + (size_t)q * g.words;
-    if (threadIdx.x == 0) { s_cnt = 0; s_skip = 0; }
+    if (threadIdx.x == 0) { s_cnt = 0; s_skip = 0; s_xn = 0; }
+    // the query's required terms, unused slots squeezed out (uniform)
+    int32_t n_kw = 0;
+    if (KW) {
+        for (int32_t j = 0; j < g.kw_stride; j++) {
+            const int32_t t = g.kw_terms[q * g.kw_stride + j];
+            if (t >= 0) { if (threadIdx.x == 0) s_kw[n_kw] = t; n_kw++; }
+        }
+    }
+    const bool kw_on = KW && n_kw > 0;
+    int32_t kc = 0;   // entries in the secondary pool (maintained by wave 0)
     __syncthreads();
 
     // S7: entry points
     for (int32_t i = threadIdx.x; i < g.E; i += blockDim.x) {
         const int32_t v = g.entry[i];
-        if (v >= 0) {
+        if (v >= 0 && v < (int32_t)g.D.n) {
             const uint32_t bit = 1u << (v & 31);
             const uint32_t old = atomicOr(&vis[v >> 5], bit);
             if (!(old & bit)) cand[atomicAdd(&s_cnt, 1)] = v;
@@ -182,9 +231,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
         const uint64_t worst = pool_full ? cur[g.L - 1] : 0ull;
         const float worst_score = ap_key_score(worst);
         if (use_tab)
-            nskipped += ap_score_candidates<DT, NV, true>(g.D, g.rec, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score, cand, s_meta, c, newk);
+            nskipped += ap_score_candidates<DT, NV, true, KW>(g.D, g.rec, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score, cand,
+                                                              s_meta, c, newk, s_kw, n_kw, g.kw_all != 0);
         else
-            nskipped += ap_score_candidates<DT, NV, false>(g.D, g.rec, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score, cand, s_meta, c, newk);
+            nskipped += ap_score_candidates<DT, NV, false, KW>(g.D, g.rec, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score, cand,
+                                                               s_meta, c, newk, s_kw, n_kw, g.kw_all != 0);
         __syncthreads();
         // sort the new keys by ranking them among themselves; only those that
         // rank before the pool's last entry (when the pool is full) can enter
@@ -196,6 +247,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
         }
         __syncthreads();
         const int32_t cin = ap_rank_in(newS, c, worst);   // new keys that rank before `worst` (all of them while the pool has room)
+        if (kw_on) {
+            // scored, satisfying, but ranked after the full pool's last entry: to the secondary pool
+            for (int32_t t = cin + (int32_t)threadIdx.x; t < c; t += blockDim.x) {
+                const uint64_t key = newS[t];
+                if ((key >> 32) != 0ull && (key & 2ull)) xk[atomicAdd(&s_xn, 1)] = key;
+            }
+        }
         if (cin > 0) {
             // In-place rank merge.  A pool entry at position t moves up by the number of entering keys that rank
             // before it, so only entries from the first insertion point on move, and they only move towards the
@@ -219,16 +277,54 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
                 }
                 __syncthreads();
 #pragma unroll
-                for (int m = 0; m < 2; m++) if (dest[m] < g.L) cur[dest[m]] = held[m];
+                for (int m = 0; m < 2; m++) {
+                    if (dest[m] < g.L) cur[dest[m]] = held[m];
+                    else if (kw_on && lo + (int32_t)threadIdx.x + 256 * m < hi && (held[m] & 2ull)) xk[atomicAdd(&s_xn, 1)] = held[m];   // evicted
+                }
                 __syncthreads();
             }
             if (npos < g.L) cur[npos] = nkey;
+            else if (kw_on && (int32_t)threadIdx.x < cin && (nkey & 2ull)) xk[atomicAdd(&s_xn, 1)] = nkey;
             for (int32_t t = (int32_t)threadIdx.x + 256; t < cin; t += 256) {
                 const int32_t r = (int32_t)(uint32_t)nxt[t];
                 if (r < g.L) cur[r] = newS[t];
+                else if (kw_on && (newS[t] & 2ull)) xk[atomicAdd(&s_xn, 1)] = newS[t];
             }
             len = len + cin < g.L ? len + cin : g.L;
             __syncthreads();
+        }
+        if (kw_on) {
+            // the secondary pool keeps the k best of everything handed over so far (any order of arrival gives the same k)
+            __syncthreads();
+            if (wave == 0) {
+                const int32_t m = s_xn;
+                for (int32_t j = 0; j < m; j++) {
+                    const uint64_t key = xk[j] & ~1ull;
+                    if (kc == g.k && key < kwc[kc - 1]) continue;
+                    int32_t pos = 0;
+                    for (int32_t base = 0; base < kc; base += 64) {
+                        const int32_t i = base + lane;
+                        pos += __popcll(__ballot(i < kc && kwc[i] > key));
+                    }
+                    const int32_t last = kc < g.k ? kc : g.k - 1;   // entries [pos, last) move one place towards the end
+                    for (int32_t hi = last; hi > pos; hi -= 64) {
+                        const int32_t lo = hi - 64 > pos ? hi - 64 : pos;
+                        const int32_t i = lo + lane;
+                        uint64_t h = 0;
+                        if (i < hi) h = kwc[i];
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                        if (i < hi) kwc[i + 1] = h;
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                    }
+                    if (lane == 0) kwc[pos] = key;
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    kc = kc < g.k ? kc + 1 : g.k;
+                }
+                if (lane == 0) s_xn = 0;
+            }
         }
         if (g.max_iters > 0 && it >= g.max_iters) break;
         // S8: pick the best `width` unexpanded entries (wave 0), mark them expanded
@@ -240,7 +336,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
                 const uint64_t mask = __ballot(un);
                 const int32_t rank = __popcll(mask & ((1ull << lane) - 1ull));
                 if (un && found + rank < g.width) {
-                    s_par[found + rank] = ap_key_id(cur[i]);
+                    s_par[found + rank] = ap_pool_id<KW>(cur[i]);
+                    if (KW) s_psat[found + rank] = (int32_t)((cur[i] >> 1) & 1ull);
                     cur[i] &= ~1ull;
                 }
                 found += __popcll(mask);
@@ -250,10 +347,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
         __syncthreads();
         const int32_t np = s_np;
         if (np == 0) break;
-        // neighbours of the parents that were never seen before
-        for (int32_t i = threadIdx.x; i < np * g.R; i += blockDim.x) {
-            const int32_t v = g.graph[(int64_t)s_par[i / g.R] * g.R + (i % g.R)];
-            if (v >= 0) {
+        // neighbours of the parents that were never seen before; a parent that satisfies the keyword
+        // constraint also brings its keyword edges
+        const int32_t per = g.R + (KW ? g.KR : 0);
+        for (int32_t i = threadIdx.x; i < np * per; i += blockDim.x) {
+            const int32_t pi = i / per, sl = i % per, u = s_par[pi];
+            int32_t v = -1;
+            if (sl < g.R) v = g.graph[(int64_t)u * g.R + sl];
+            else if (KW && g.kw_use_edges && s_psat[pi] && sl - g.R < g.kw_count[u]) v = g.kw_edges[(int64_t)u * g.KR + (sl - g.R)];
+            if (v >= 0 && v < (int32_t)g.D.n) {   // an imported graph is not trusted to hold valid ids
                 const uint32_t bit = 1u << (v & 31);
                 const uint32_t old = atomicOr(&vis[v >> 5], bit);
                 if (!(old & bit)) cand[atomicAdd(&s_cnt, 1)] = v;
@@ -266,14 +368,42 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
     __syncthreads();
     if (threadIdx.x == 0) { g.counts[q * 3] = nscored; g.counts[q * 3 + 1] = it; g.counts[q * 3 + 2] = s_skip; }
     // S9
+    if (kw_on) {
+        // Everything in the secondary pool ranked after the pool's last entry when it was handed over, and that
+        // entry only ever improves: the satisfying pool entries in order, then the secondary pool, is the merged order.
+        if (wave == 0) {
+            int32_t o = 0;
+            for (int32_t base = 0; base < len && o < g.k; base += 64) {
+                const int32_t i = base + lane;
+                const bool sat = i < len && (cur[i] & 2ull);
+                const uint64_t mask = __ballot(sat);
+                const int32_t at = o + __popcll(mask & ((1ull << lane) - 1ull));
+                if (sat && at < g.k) {
+                    g.out_ids[q * g.k + at] = ap_pool_id<KW>(cur[i]);
+                    g.out_scores[q * g.k + at] = ap_key_score(cur[i]);
+                }
+                o += __popcll(mask);
+            }
+            o = o < g.k ? o : g.k;
+            for (int32_t i = o + lane; i < g.k; i += 64) {
+                const bool have = i - o < kc;
+                g.out_ids[q * g.k + i] = have ? ap_pool_id<KW>(kwc[i - o]) : -1;
+                g.out_scores[q * g.k + i] = have ? ap_key_score(kwc[i - o]) : -INFINITY;
+            }
+        }
+        return;
+    }
     for (int32_t i = threadIdx.x; i < g.k; i += blockDim.x) {
-        g.out_ids[q * g.k + i] = i < len ? ap_key_id(cur[i]) : -1;
+        g.out_ids[q * g.k + i] = i < len ? ap_pool_id<KW>(cur[i]) : -1;
         g.out_scores[q * g.k + i] = i < len ? ap_key_score(cur[i]) : -INFINITY;
     }
 }
 
-extern "C" int ap_search_batch(ap_index *ix, const ap_queries *q, const float *per_query_w,
-                               const ap_search_params *p, int32_t *out_ids, float *out_scores, void *stream) {
+// kw_terms == NULL: the plain search; otherwise the keyword-constrained one.
+static int ap_search_impl(ap_index *ix, const ap_queries *q, const float *per_query_w, const ap_search_params *p,
+                          const int32_t *kw_terms, int32_t kw_stride, uint32_t kw_flags, int32_t *out_ids, float *out_scores,
+                          void *stream) {
+    const bool kw = kw_terms != nullptr;
     AP_REQUIRE(ix && p, "NULL argument");
     if (!ix->has_graph) { ap_set_error("index has no graph: build or import one first"); return AP_ESTATE; }
     AP_TRY(ap_validate_queries(q));
@@ -294,7 +424,11 @@ extern "C" int ap_search_batch(ap_index *ix, const ap_queries *q, const float *p
     g.R = ix->params.degree;
     g.E = ix->params.n_entry;
     g.k = p->k; g.L = p->beam; g.max_iters = p->max_iters; g.width = p->search_width;
-    g.cmax = g.E > g.width * g.R ? g.E : g.width * g.R;
+    g.KR = kw ? ix->params.degree / 2 : 0;
+    g.kw_edges = ix->kw; g.kw_count = ix->kw_count; g.kw_terms = kw_terms; g.kw_stride = kw_stride;
+    g.kw_all = (kw_flags & AP_KW_ALL) ? 1 : 0;
+    g.kw_use_edges = (kw_flags & AP_KW_NO_EDGES) ? 0 : 1;
+    g.cmax = g.E > g.width * (g.R + g.KR) ? g.E : g.width * (g.R + g.KR);
     g.words = ((size_t)ix->docs.n + 31) / 32;
     const size_t need = g.words * (size_t)q->nq;
     if (need > ix->visited_words) {
@@ -319,20 +453,49 @@ extern "C" int ap_search_batch(ap_index *ix, const ap_queries *q, const float *p
     g.meta = ix->meta;
     ix->last_nq = q->nq;
     AP_TRY(ap_fill_u32(ix->visited, need, 0u, st));
-    const size_t smem = (size_t)(g.L + 3 * g.cmax) * 8 + (size_t)g.cmax * (16 + 4) + ((1 << AP_QSP_BITS) + (1 << AP_QTX_BITS)) * 8 + 8;
+    const size_t smem = (size_t)(g.L + 3 * g.cmax + (kw ? g.cmax + g.k : 0)) * 8 + (size_t)g.cmax * (16 + 4) +
+                        ((1 << AP_QSP_BITS) + (1 << AP_QTX_BITS)) * 8 + 8;
     AP_CHECK_HIP(hipEventRecord(ix->ev_search[0], st));
     AP_REQUIRE(smem <= 160 * 1024, "beam and search_width need %zu bytes of LDS (limit 160 KiB)", smem);
     hipError_t le = hipSuccess;
-    AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim, {
-        if (smem > 48 * 1024)
-            le = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_search<DT, NV>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     (int)smem);
-        if (le == hipSuccess) hipLaunchKernelGGL((k_search<DT, NV>), dim3((unsigned)q->nq), dim3(256), smem, st, g);
-    });
+    if (kw) {
+        AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim, {
+            if (smem > 48 * 1024)
+                le = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_search<DT, NV, true>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+            if (le == hipSuccess) hipLaunchKernelGGL((k_search<DT, NV, true>), dim3((unsigned)q->nq), dim3(256), smem, st, g);
+        });
+    } else {
+        AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim, {
+            if (smem > 48 * 1024)
+                le = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_search<DT, NV, false>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+            if (le == hipSuccess) hipLaunchKernelGGL((k_search<DT, NV, false>), dim3((unsigned)q->nq), dim3(256), smem, st, g);
+        });
+    }
     AP_CHECK_HIP(le);
     AP_CHECK_HIP(hipGetLastError());
     AP_CHECK_HIP(hipEventRecord(ix->ev_search[1], st));
     return AP_OK;
+}
+
+extern "C" int ap_search_batch(ap_index *ix, const ap_queries *q, const float *per_query_w,
+                               const ap_search_params *p, int32_t *out_ids, float *out_scores, void *stream) {
+    return ap_search_impl(ix, q, per_query_w, p, nullptr, 0, 0u, out_ids, out_scores, stream);
+}
+
+extern "C" int ap_search_batch_keywords(ap_index *ix, const ap_queries *q, const float *per_query_w,
+                                        const ap_search_params *p, const int32_t *kw_terms, int32_t kw_stride,
+                                        uint32_t kw_flags, int32_t *out_ids, float *out_scores, void *stream) {
+    AP_REQUIRE(ix && q, "NULL argument");
+    AP_REQUIRE(kw_stride >= 1 && kw_stride <= AP_KW_MAX_TERMS, "kw_stride = %d must be in [1, %d]", kw_stride, AP_KW_MAX_TERMS);
+    AP_REQUIRE(kw_terms || q->nq == 0, "kw_terms is NULL");
+    AP_REQUIRE((kw_flags & ~(uint32_t)(AP_KW_ALL | AP_KW_NO_EDGES)) == 0, "unknown bits in kw_flags");
+    if (!ix->has_graph) { ap_set_error("index has no graph: build or import one first"); return AP_ESTATE; }
+    AP_REQUIRE(ix->kw && ix->kw_count, "index has no keyword edges");
+    AP_REQUIRE(ix->docs.n < (1ll << 29), "keyword search needs n < 2^29");
+    if (q->nq == 0) return ap_search_impl(ix, q, per_query_w, p, nullptr, 0, 0u, out_ids, out_scores, stream);
+    return ap_search_impl(ix, q, per_query_w, p, kw_terms, kw_stride, kw_flags, out_ids, out_scores, stream);
 }
 
 extern "C" int ap_search_stats(const ap_index *ix, int32_t *out_counts, int32_t nq, float *kernel_ms, void *stream) {

@@ -240,3 +240,19 @@ def make_workload(name: str = "tiny", seed: int = 0, *, n: Optional[int] = None,
                      tx_counts=np.maximum(_counts(rng, c["qtx"], c["nq"]), 1), **common)
     return Workload(name=name, docs=docs, queries=qs, weights=tuple(c["weights"]), degree=c["degree"],
                     beam=c["beam"], k=c["k"], extra=dict(seed=seed, config=c))
+
+
+def make_keywords(queries: VecSet, seed: int = 0, max_terms: int = 2, stride: int = 4, p_none: float = 0.0) -> np.ndarray:
+    """Required keywords for a keyword-constrained search: for each query 1..max_terms
+    of its own distinct text tokens, chosen uniformly, as an nq x stride int32 array
+    padded with -1.  With probability p_none a query gets no keyword at all."""
+    assert 1 <= max_terms <= stride
+    rng = np.random.default_rng(seed)
+    out = np.full((queries.n, stride), -1, np.int32)
+    for i in range(queries.n):
+        terms = queries.tx_idx[queries.tx_indptr[i]:queries.tx_indptr[i + 1]]
+        if len(terms) == 0 or rng.random() < p_none:
+            continue
+        m = min(int(rng.integers(1, max_terms + 1)), len(terms))
+        out[i, :m] = rng.choice(terms, m, replace=False)
+    return out
