@@ -31,6 +31,58 @@ def recall_at_k(ids, gt):
     return float(np.mean([len(set(a.tolist()) & set(b.tolist())) / float(len(b)) for a, b in zip(ids, gt)]))
 
 
+def keyword_leg(args, w, ix, qs, wq, k, chosen):
+    """Keyword-constrained search (Section 4.2.2): every query requires 1-2 of its own text tokens.  Ground truth
+    = exact top-k among the documents holding a required term, on up to 1000 sampled queries (exhaustive scores
+    from ap_hybrid_scores, filter and top-k in torch: measurement only)."""
+    import numpy as np
+    import scipy.sparse as sps
+    import torch
+    from paper_2511_00855_amd import binding as B
+    from paper_2511_00855_amd.synth import make_keywords, subset_vecset
+    nq, n = qs.n, w.docs.n
+    kw = make_keywords(w.queries, seed=1, max_terms=2, stride=2)
+    sample = np.arange(0, nq, max(1, nq // 1000))[:1000]
+    inv = sps.csr_matrix((np.ones(len(w.docs.tx_idx), np.int8), w.docs.tx_idx, w.docs.tx_indptr),
+                         shape=(n, w.docs.tx_vocab)).tocsc()
+    gt = []
+    for c0 in range(0, len(sample), 250):
+        rows = sample[c0:c0 + 250]
+        sub = B.DeviceVecs(subset_vecset(w.queries, rows), "cuda:0")
+        allc = torch.arange(n, dtype=torch.int32, device="cuda:0").repeat(len(rows), 1)
+        sc = ix.hybrid_scores(sub, allc, wq[torch.from_numpy(rows).to("cuda:0")])[:, :, 3]
+        rr, cc = [], []
+        for x, qi in enumerate(rows):
+            for t in kw[qi][kw[qi] >= 0]:
+                d = inv.indices[inv.indptr[t]:inv.indptr[t + 1]]
+                rr.append(np.full(len(d), x, np.int64)); cc.append(d.astype(np.int64))
+        mask = torch.zeros(sc.shape, dtype=torch.bool, device="cuda:0")
+        mask[torch.from_numpy(np.concatenate(rr)).to("cuda:0"), torch.from_numpy(np.concatenate(cc)).to("cuda:0")] = True
+        top = sc.masked_fill(~mask, float("-inf")).topk(k, dim=1)
+        ids = torch.where(torch.isinf(top.values), torch.full_like(top.indices, -1), top.indices)
+        gt.append(ids.cpu().numpy())
+        del sc, mask, allc
+    gt = np.concatenate(gt)
+    out = []
+    for beam in sorted({w.beam, 512, chosen}):
+        for edges in (True, False):
+            ix.search_batch_keywords(qs, k, beam, kw, wq, use_kw_edges=edges)
+            torch.cuda.synchronize()
+            t1 = time.time()
+            ids, _ = ix.search_batch_keywords(qs, k, beam, kw, wq, use_kw_edges=edges)
+            torch.cuda.synchronize()
+            dt = time.time() - t1
+            counts, kms = ix.search_stats(nq)
+            got = ids.cpu().numpy()[sample]
+            rec = float(np.mean([len(set(a[a >= 0].tolist()) & set(b[b >= 0].tolist())) / max(1, int((b >= 0).sum()))
+                                 for a, b in zip(got, gt)]))
+            out.append(dict(beam=beam, keyword_edges=edges, recall=round(rec, 4), qps=round(nq / dt, 1), kernel_ms=round(kms, 3),
+                            dists_per_query=round(float(counts[:, 0].float().mean().item()), 1)))
+            log(f"[bench] keywords beam {beam} edges {edges}: recall@{k} {rec:.4f} (on {len(sample)} sampled queries)  "
+                f"{nq / dt:,.0f} qps  kernel {kms:.2f} ms  {out[-1]['dists_per_query']:.0f} dists/query")
+    return dict(required_terms="1-2 of each query's own text tokens, any-match", sampled_queries=len(sample), sweep=out)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -44,7 +96,11 @@ def main():
     ap.add_argument("--beam", type=int, default=0, help="fix the beam (skips the sweep; for profiling runs)")
     ap.add_argument("--target-recall", type=float, default=0.95)
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run a 1 GiB plain copy kernel (yardstick for profiler byte counters)")
+                    help="kept for older command lines: the 1 GiB plain copy kernel (yardstick for profiler byte "
+                         "counters and for the streaming rate of this box) always runs three times")
+    ap.add_argument("--keywords", action="store_true",
+                    help="also measure the keyword-constrained search (1-2 required terms per query, with and "
+                         "without keyword edges) and add a keyword_search object to the line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing leg")
     args = ap.parse_args()
@@ -73,13 +129,19 @@ def main():
     wq = torch.from_numpy(np.tile(np.float32(w.weights), (nq, 1))).to("cuda:0")
     torch.cuda.synchronize()
 
-    if args.calibrate_copy:
-        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").normal_()
-        b = torch.empty_like(a)
-        for _ in range(3):
-            B.calibration_copy(b, a)
-        torch.cuda.synchronize()
-        del a, b
+    # ---- a plain 1 GiB copy: what this machine streams (read + write), and the yardstick of the profiler's byte counters
+    a = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").normal_()
+    b = torch.empty_like(a)
+    B.calibration_copy(b, a)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(2):
+        B.calibration_copy(b, a)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2 * 2.0 * a.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    log(f"[bench] streaming copy of 1 GiB: {copy_gbs:,.0f} GB/s (read + write)")
+    del a, b
 
     # ---- build on the GPU (S0-S6), timed to stream sync with data resident
     bp = B.build_params(w.degree, nd_rounds=args.rounds)
@@ -171,7 +233,11 @@ def main():
                     similarities_per_launch=n_dist, partial_similarities_per_launch=n_skip,
                     algorithmic_bytes_per_launch=round(bytes_per_launch),
                     GBps_if_every_similarity_were_full=round(bytes_if_all_full / (k_ms * 1e-3) / 1e9, 1),
-                    dists_per_s=round(n_dist / (k_ms * 1e-3), 1))
+                    dists_per_s=round(n_dist / (k_ms * 1e-3), 1),
+                    streaming_copy_GBps=round(copy_gbs, 1),
+                    traffic_GBps=None if traffic is None else round(traffic / (k_ms * 1e-3) / 1e9, 1))
+
+    kw_report = keyword_leg(args, w, ix, qs, wq, k, chosen) if args.keywords else None
 
     # ---- CPU baseline: the oracle as it stands, one thread, bounded sample of the same searches
     cpu = None
@@ -207,6 +273,8 @@ def main():
         "hybrid_dists_per_s": roofline["dists_per_s"], "beam_sweep": sweep,
         "roofline": roofline, "cpu_baseline": cpu,
     }
+    if kw_report is not None:
+        line["keyword_search"] = kw_report
     print(json.dumps(line), flush=True)
     ix.close()
 

@@ -77,13 +77,15 @@ __device__ __forceinline__ int32_t ap_rank_in(const uint64_t *keys, int32_t n, u
 #define AP_QTX_BITS 7    // query lexical table: 128 slots, lists up to 32 entries
 
 // KW: each candidate's lexical terms are also compared with the query's required
-// terms (s_kw[0..n_kw)); a candidate that satisfies the constraint is always
-// scored in full and its key carries the "satisfies" flag.
+// terms (s_kw[0..n_kw)); the key of a candidate that satisfies the constraint
+// carries the "satisfies" flag, and its dense row may only be skipped when the
+// bound also rules out the secondary pool (full, and its last score above the bound).
 template <int DT, int NV, bool TAB, bool KW>
 __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const uint2 *rec, const float *qa, const uint64_t *qtab,
                                                        const ApLists &a, float wd, float ws, float wf, float qnorm, bool pool_full,
                                                        float worst_score, const int32_t *cand, const uint4 *s_meta, int32_t c,
-                                                       uint64_t *newk, const int32_t *s_kw, int32_t n_kw, bool kw_all) {
+                                                       uint64_t *newk, const int32_t *s_kw, int32_t n_kw, bool kw_all,
+                                                       bool second_full, float second_worst) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int32_t skipped = 0;
     constexpr int G = AP_SEARCH_G;   // candidates whose list segments are in flight together
@@ -134,7 +136,7 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const ui
                 flags |= sat ? 2u : 0u;
             }
             uint64_t key;
-            if (pool_full && ub < worst_score && !(flags & 2u)) {
+            if (pool_full && ub < worst_score && (!(flags & 2u) || (second_full && ub < second_worst))) {
                 key = (uint64_t)(uint32_t)(i + 1);   // ranks after every real key (score bits 0), distinct per candidate
                 skipped++;
             } else {
@@ -164,7 +166,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
     uint4 *s_meta = reinterpret_cast<uint4 *>(qtab + (1 << AP_QSP_BITS) + (1 << AP_QTX_BITS) +
                                               ((g.L + 3 * g.cmax + (KW ? g.cmax + g.k : 0)) & 1));
     int32_t *cand = reinterpret_cast<int32_t *>(s_meta + g.cmax);
-    __shared__ int32_t s_cnt, s_np, s_skip, s_xn;
+    __shared__ int32_t s_cnt, s_np, s_skip, s_xn, s_kc;
     __shared__ int32_t s_par[8], s_psat[8];
     __shared__ int32_t s_kw[AP_KW_MAX_TERMS];
 
@@ -197,7 +199,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
     }
     const float wd = g.w[q * g.w_stride + 0], ws = g.w[q * g.w_stride + 1], wf = g.w[q * g.w_stride + 2];
     uint32_t *vis = g.visited + (size_t)q * g.words;
-    if (threadIdx.x == 0) { s_cnt = 0; s_skip = 0; s_xn = 0; }
+    if (threadIdx.x == 0) { s_cnt = 0; s_skip = 0; s_xn = 0; s_kc = 0; }
     // the query's required terms, unused slots squeezed out (uniform)
     int32_t n_kw = 0;
     if (KW) {
@@ -230,12 +232,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
         const bool pool_full = len == g.L;
         const uint64_t worst = pool_full ? cur[g.L - 1] : 0ull;
         const float worst_score = ap_key_score(worst);
+        const bool second_full = kw_on && s_kc == g.k;   // s_kc and kwc were last written before the previous barriers
+        const float second_worst = second_full ? ap_key_score(kwc[g.k - 1]) : 0.f;
         if (use_tab)
             nskipped += ap_score_candidates<DT, NV, true, KW>(g.D, g.rec, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score, cand,
-                                                              s_meta, c, newk, s_kw, n_kw, g.kw_all != 0);
+                                                              s_meta, c, newk, s_kw, n_kw, g.kw_all != 0, second_full, second_worst);
         else
             nskipped += ap_score_candidates<DT, NV, false, KW>(g.D, g.rec, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score, cand,
-                                                               s_meta, c, newk, s_kw, n_kw, g.kw_all != 0);
+                                                               s_meta, c, newk, s_kw, n_kw, g.kw_all != 0, second_full, second_worst);
         __syncthreads();
         // sort the new keys by ranking them among themselves; only those that
         // rank before the pool's last entry (when the pool is full) can enter
@@ -323,7 +327,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
                     __builtin_amdgcn_wave_barrier();
                     kc = kc < g.k ? kc + 1 : g.k;
                 }
-                if (lane == 0) s_xn = 0;
+                if (lane == 0) { s_xn = 0; s_kc = kc; }
             }
         }
         if (g.max_iters > 0 && it >= g.max_iters) break;

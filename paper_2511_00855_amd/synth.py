@@ -11,6 +11,7 @@ Everything is a pure function of (config, seed), produced with
 """
 from __future__ import annotations
 
+import dataclasses
 from dataclasses import dataclass, field
 from typing import Dict, Optional, Tuple
 
@@ -256,3 +257,18 @@ def make_keywords(queries: VecSet, seed: int = 0, max_terms: int = 2, stride: in
         m = min(int(rng.integers(1, max_terms + 1)), len(terms))
         out[i, :m] = rng.choice(terms, m, replace=False)
     return out
+
+
+def subset_vecset(v: VecSet, rows) -> VecSet:
+    """The listed rows of a vector set as a vector set of their own (CSR parts rebuilt)."""
+    rows = np.asarray(rows, np.int64)
+    parts = {}
+    for pre in ("sp", "tx"):
+        ip = getattr(v, pre + "_indptr")
+        lens = (ip[1:] - ip[:-1])[rows]
+        take = np.concatenate([np.arange(ip[r], ip[r + 1]) for r in rows]) if len(rows) else np.zeros(0, np.int64)
+        parts[pre + "_indptr"] = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+        parts[pre + "_idx"] = getattr(v, pre + "_idx")[take]
+        parts[pre + "_val"] = getattr(v, pre + "_val")[take]
+    bf = None if v.dense_bf16 is None else v.dense_bf16[rows]
+    return dataclasses.replace(v, n=len(rows), dense=v.dense[rows], dense_bf16=bf, **parts)

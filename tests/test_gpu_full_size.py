@@ -12,7 +12,7 @@ import torch
 
 import oracle as O
 from paper_2511_00855_amd import binding as B
-from paper_2511_00855_amd.synth import make_workload
+from paper_2511_00855_amd.synth import make_keywords, make_workload
 from parity import RTOL_F32, assert_ranked_equiv, assert_scores_close, row_norms, score_tol
 
 pytestmark = pytest.mark.gpu
@@ -38,6 +38,23 @@ def full():
     Q = O.VS(w.queries)
     yield w, docs, qs, bp, ix, D, Q
     ix.close()
+
+
+def _score_table(w, ix, sample, wq):
+    """Fused scores of every document for the sampled queries, from ap_hybrid_scores (what an oracle replay runs on)."""
+    N = w.docs.n
+    sq = types.SimpleNamespace(n=len(sample), dim=w.queries.dim, dense=w.queries.dense[sample],
+                               sp_indptr=None, sp_idx=None, sp_val=None, tx_indptr=None, tx_idx=None, tx_val=None,
+                               sp_vocab=w.queries.sp_vocab, tx_vocab=w.queries.tx_vocab)
+    for pre in ("sp", "tx"):
+        ip = getattr(w.queries, pre + "_indptr")
+        lens = (ip[1:] - ip[:-1])[sample]
+        setattr(sq, pre + "_indptr", np.concatenate([[0], np.cumsum(lens)]).astype(np.int64))
+        setattr(sq, pre + "_idx", np.concatenate([getattr(w.queries, pre + "_idx")[ip[i]:ip[i + 1]] for i in sample]))
+        setattr(sq, pre + "_val", np.concatenate([getattr(w.queries, pre + "_val")[ip[i]:ip[i + 1]] for i in sample]))
+    dsq = B.DeviceVecs(sq)
+    allc = np.tile(np.arange(N, dtype=np.int32), (len(sample), 1))
+    return ix.hybrid_scores(dsq, allc, wq[sample]).cpu().numpy()[:, :, 3]
 
 
 def test_full_size_scores_sampled(full):
@@ -70,19 +87,7 @@ def test_full_size_search_replay(full, beam):
     counts = counts.cpu().numpy()
     sem, _, _, ent = [t.cpu().numpy() for t in ix.export_graph()]
     sample = np.arange(0, nq, nq // 48)[:48]
-    # a query set holding only the sample, for the score table the replay runs on
-    sq = types.SimpleNamespace(n=len(sample), dim=w.queries.dim, dense=w.queries.dense[sample],
-                               sp_indptr=None, sp_idx=None, sp_val=None, tx_indptr=None, tx_idx=None, tx_val=None,
-                               sp_vocab=w.queries.sp_vocab, tx_vocab=w.queries.tx_vocab)
-    for pre in ("sp", "tx"):
-        ip = getattr(w.queries, pre + "_indptr")
-        lens = (ip[1:] - ip[:-1])[sample]
-        setattr(sq, pre + "_indptr", np.concatenate([[0], np.cumsum(lens)]).astype(np.int64))
-        setattr(sq, pre + "_idx", np.concatenate([getattr(w.queries, pre + "_idx")[ip[i]:ip[i + 1]] for i in sample]))
-        setattr(sq, pre + "_val", np.concatenate([getattr(w.queries, pre + "_val")[ip[i]:ip[i + 1]] for i in sample]))
-    dsq = B.DeviceVecs(sq)
-    allc = np.tile(np.arange(N, dtype=np.int32), (len(sample), 1))
-    table = ix.hybrid_scores(dsq, allc, wq[sample]).cpu().numpy()[:, :, 3]
+    table = _score_table(w, ix, sample, wq)
     for x, qi in enumerate(sample):
         oi, os_, nv = O.search(D, sem, ent, Q, int(qi), wq[qi], k, beam, score_table=table[x])
         assert np.array_equal(ids[qi], oi), (qi, beam)
@@ -95,6 +100,39 @@ def test_full_size_search_replay(full, beam):
     tol = score_tol(ref, wq[sample][:, None, :], qn, dn, RTOL_F32)[:, :, 3]
     assert (np.abs(sc[sample] - ref[:, :, 3]) <= tol).all()
     _say(f"  kernel {ms:.1f} ms, {counts[:, 0].mean():.0f} candidates/query, {counts[:, 2].sum() / counts[:, 0].sum():.2f} without dense row")
+
+
+@pytest.mark.parametrize("beam,kw_all", [(128, False), (1024, True)])
+def test_full_size_keyword_search_replay(full, beam, kw_all):
+    """Keyword-constrained search over all 10,000 queries (1-2 required terms drawn from each query's own text);
+    sampled queries are replayed by the oracle on the GPU's scores."""
+    w, docs, qs, bp, ix, D, Q = full
+    _say(f"full size: keyword search beam {beam} all={kw_all}")
+    nq, k = qs.n, w.k
+    wq = np.tile(np.float32(w.weights), (nq, 1))
+    kw = make_keywords(w.queries, seed=1, max_terms=2, stride=2, p_none=0.05)
+    ids, sc = [t.cpu().numpy() for t in ix.search_batch_keywords(qs, k, beam, kw, wq, kw_all)]
+    counts, ms = ix.search_stats(nq)
+    counts = counts.cpu().numpy()
+    sem, ke, kc, ent = [t.cpu().numpy() for t in ix.export_graph()]
+    sample = np.arange(7, nq, nq // 32)[:32]
+    table = _score_table(w, ix, sample, wq)
+    for x, qi in enumerate(sample):
+        kwl = [int(t) for t in kw[qi] if t >= 0]
+        oi, os_, nv = O.search_kw(D, sem, ke, kc, ent, Q, int(qi), wq[qi], k, beam, kwl, kw_all, score_table=table[x])
+        assert np.array_equal(ids[qi], oi), (qi, beam)
+        assert np.array_equal(sc[qi], os_), (qi, beam)
+        assert counts[qi, 0] == nv, (qi, counts[qi], nv)
+    # every answer of every query holds its required terms
+    ip, tx = w.docs.tx_indptr, w.docs.tx_idx
+    for qi in range(0, nq, 37):
+        kwl = set(int(t) for t in kw[qi] if t >= 0)
+        if not kwl:
+            continue
+        for v in ids[qi][ids[qi] >= 0]:
+            terms = set(tx[ip[v]:ip[v + 1]].tolist())
+            assert (kwl <= terms) if kw_all else bool(kwl & terms), (qi, v)
+    _say(f"  kernel {ms:.1f} ms, {counts[:, 0].mean():.0f} candidates/query, answers/query {np.mean((ids >= 0).sum(1)):.2f}")
 
 
 def test_full_size_build_stages_sampled(full):
