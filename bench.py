@@ -98,6 +98,8 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="kept for older command lines: the 1 GiB plain copy kernel (yardstick for profiler byte "
                          "counters and for the streaming rate of this box) always runs three times")
+    ap.add_argument("--prune-mode", type=int, default=0,
+                    help="0 = joint RNG-IP pruning (the method), 1 = RNG only, 2 = IP only (the paper's pruning ablation)")
     ap.add_argument("--keywords", action="store_true",
                     help="also measure the keyword-constrained search (1-2 required terms per query, with and "
                          "without keyword edges) and add a keyword_search object to the line")
@@ -144,7 +146,7 @@ def main():
     del a, b
 
     # ---- build on the GPU (S0-S6), timed to stream sync with data resident
-    bp = B.build_params(w.degree, nd_rounds=args.rounds)
+    bp = B.build_params(w.degree, nd_rounds=args.rounds, prune_mode=args.prune_mode)
     t0 = time.time()
     ix = B.Index.build(docs, bp)
     torch.cuda.synchronize()
@@ -268,7 +270,8 @@ def main():
                                f"sparse ~{sp_nnz:.0f} nnz/doc, text ~{tx_nnz:.0f} distinct terms/doc, {nq} queries, "
                                f"weights {tuple(w.weights)}, degree {w.degree}, k={k}",
                    "beam": chosen, "recall_at_10": round(rec, 4), "recall_target_reached": reached,
-                   "nominal_beam": w.beam, "refine_rounds": args.rounds},
+                   "nominal_beam": w.beam, "refine_rounds": args.rounds,
+                   "pruning": ("joint RNG-IP", "RNG only", "IP only")[args.prune_mode]},
         "build_s": round(build_s, 3), "build_stages_s": {a: round(b, 3) for a, b in bt.items()},
         "hybrid_dists_per_s": roofline["dists_per_s"], "beam_sweep": sweep,
         "roofline": roofline, "cpu_baseline": cpu,

@@ -80,8 +80,15 @@ typedef struct {
     int32_t sp_len;     /* P: length of each per-path list; <= 32; 0 = ceil(degree/6) */
     float bm25_k1, bm25_b;
     float build_w[3];   /* fusion weights used during construction */
+    int32_t prune_mode; /* AP_PRUNE_JOINT (0, Algorithm 1), or one of the two ablations of the joint strategy
+                           (Section 5, effectiveness of RNG-IP joint pruning): AP_PRUNE_RNG_ONLY keeps the first d
+                           neighbours of the detour order without the inner-product test, AP_PRUNE_IP_ONLY applies
+                           the test to the list in its similarity order without the detour sort */
     uint64_t seed;      /* reserved (construction is deterministic) */
 } ap_build_params;
+#define AP_PRUNE_JOINT 0
+#define AP_PRUNE_RNG_ONLY 1
+#define AP_PRUNE_IP_ONLY 2
 
 /* A batch of queries.  tx_cnt holds term counts of the query text. */
 typedef struct {

@@ -185,7 +185,16 @@ def detour_sort(ids, simA, Pm):
     return cnt, order
 
 
-def ip_prune(D: VS, A, R, ke_cap, ids, order, Pm, self_s):
+PRUNE_JOINT, PRUNE_RNG_ONLY, PRUNE_IP_ONLY = 0, 1, 2
+
+
+def similarity_order(ids):
+    """The walk order of the IP-only ablation: the list as it is ranked (holes last)."""
+    ids = np.asarray(ids)
+    return np.concatenate([np.nonzero(ids >= 0)[0], np.nonzero(ids < 0)[0]]).astype(np.int32)
+
+
+def ip_prune(D: VS, A, R, ke_cap, ids, order, Pm, self_s, use_ip=True):
     ids = _c(ids, np.int32); order = _c(order, np.int32); Pm = _c(Pm, np.float32)
     self_s = _c(self_s, np.float32)
     K = len(ids)
@@ -193,7 +202,8 @@ def ip_prune(D: VS, A, R, ke_cap, ids, order, Pm, self_s):
     nse = C.c_int32(0); nke = C.c_int32(0)
     flag = np.zeros(K, np.int32)
     lib().orc_ip_prune(D.ref, C.c_int64(A), C.c_int32(K), C.c_int32(R), C.c_int32(ke_cap), _p(ids),
-                       _p(order), _p(Pm), _p(self_s), _p(se), C.byref(nse), _p(ke), C.byref(nke), _p(flag))
+                       _p(order), _p(Pm), _p(self_s), C.c_int32(int(use_ip)), _p(se), C.byref(nse), _p(ke),
+                       C.byref(nke), _p(flag))
     return se[:nse.value].copy(), ke[:nke.value].copy(), flag
 
 
@@ -214,25 +224,28 @@ def entry_points(self_s, E):
     return out
 
 
-def prune_node(D: VS, u, w, R, ke_cap, ids, scores, self_all=None, Pm=None):
+def prune_node(D: VS, u, w, R, ke_cap, ids, scores, self_all=None, Pm=None, mode=PRUNE_JOINT):
     """S4 + S5 for one node from its K-list (ids, scores sorted by rank).
-    Returns a namespace with Pm, count, order, sorted ids, SE ids, KE ids, flags."""
+    Returns a namespace with Pm, count, order, sorted ids, SE ids, KE ids, flags.
+    mode: the joint strategy, or one of its two ablations."""
     ids = _c(ids, np.int32)
     if Pm is None:
         Pm = pairwise(D, w, ids)
     cnt, order = detour_sort(ids, scores, Pm)
+    if mode == PRUNE_IP_ONLY:
+        order = similarity_order(ids)
     if self_all is None:
         self_s = np.where(ids >= 0, np.diag(Pm), -np.inf).astype(np.float32)
     else:
         self_s = np.where(ids >= 0, np.asarray(self_all)[np.maximum(ids, 0)], -np.inf).astype(np.float32)
-    se_pos, ke_pos, flag = ip_prune(D, u, R, ke_cap, ids, order, Pm, self_s)
+    se_pos, ke_pos, flag = ip_prune(D, u, R, ke_cap, ids, order, Pm, self_s, use_ip=mode != PRUNE_RNG_ONLY)
     return SimpleNamespace(Pm=Pm, count=cnt, order=order, sorted=ids[order], se=ids[se_pos],
                            ke=ids[ke_pos], flag=flag, se_pos=se_pos, ke_pos=ke_pos)
 
 
 def default_params(R: int, **kw):
     p = dict(degree=R, knn_k=2 * R, nd_rounds=3, nd_sample=32, n_entry=64, sp_len=-(-R // 6),
-             build_w=(1.0, 1.0, 1.0), bm25_k1=1.2, bm25_b=0.75)
+             build_w=(1.0, 1.0, 1.0), bm25_k1=1.2, bm25_b=0.75, prune_mode=PRUNE_JOINT)
     p.update(kw)
     p["ke_cap"] = p["degree"] // 2
     return SimpleNamespace(**p)
@@ -263,7 +276,7 @@ def build_index(docs, params):
     sorted_ids = np.empty((N, K), np.int32)
     counts = np.empty((N, K), np.int32)
     for u in range(N):
-        r = prune_node(D, u, w, R, params.ke_cap, ids[u], sc[u], self_all=self_s)
+        r = prune_node(D, u, w, R, params.ke_cap, ids[u], sc[u], self_all=self_s, mode=params.prune_mode)
         se[u, :len(r.se)] = r.se
         ke[u, :len(r.ke)] = r.ke
         ke_cnt[u] = len(r.ke)

@@ -347,7 +347,11 @@ void orc_detour_sort(int32_t K, const int32_t *ids, const float *simA, const flo
  *   flag(X) = [ K(A) n K(X) != {} ]  and  for every Y in SE now:
  *             K(A) n K(X) is NOT a subset of K(Y).
  * K(.) is the set of term ids of the lexical vector.
- * Positions index the ORIGINAL neighbour array (ids, Pm, self).          */
+ * Positions index the ORIGINAL neighbour array (ids, Pm, self).
+ * Ablation of the joint strategy (Section 5, effectiveness of RNG-IP joint
+ * pruning): use_ip = 0 drops the IP test, so SE is simply the first R
+ * neighbours in detour order ("RNG alone"); "IP alone" is this routine with
+ * use_ip = 1 fed the neighbours in their original similarity order.      */
 static int contains(const int32_t *a, int64_t n, int32_t t) {
     int64_t i;
     for (i = 0; i < n; i++) if (a[i] == t) return 1;
@@ -355,7 +359,7 @@ static int contains(const int32_t *a, int64_t n, int32_t t) {
 }
 
 void orc_ip_prune(const orc_vecset *D, int64_t A, int32_t K, int32_t R, int32_t ke_cap,
-                  const int32_t *ids, const int32_t *order, const float *Pm, const float *self,
+                  const int32_t *ids, const int32_t *order, const float *Pm, const float *self, int32_t use_ip,
                   int32_t *se_pos, int32_t *n_se, int32_t *ke_pos, int32_t *n_ke, int32_t *flag) {
     int32_t r, nse = 0, nke = 0, i;
     const int32_t *KA = D->tx_idx + D->tx_indptr[A];
@@ -385,7 +389,7 @@ void orc_ip_prune(const orc_vecset *D, int64_t A, int32_t K, int32_t R, int32_t 
             }
         }
         ok = nse < R;
-        for (i = 0; i < nse && ok; i++)
+        for (i = 0; i < nse && ok && use_ip; i++)
             if (!(Pm[se_pos[i] * K + pv] < self[pv])) ok = 0;
         if (ok) se_pos[nse++] = pv;
         else if (flag[pv] && nke < ke_cap) ke_pos[nke++] = pv;

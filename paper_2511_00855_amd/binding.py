@@ -33,7 +33,7 @@ class _Corpus(C.Structure):
 class _BuildParams(C.Structure):
     _fields_ = [("degree", C.c_int32), ("knn_k", C.c_int32), ("nd_rounds", C.c_int32), ("nd_sample", C.c_int32),
                 ("n_entry", C.c_int32), ("sp_len", C.c_int32), ("bm25_k1", C.c_float), ("bm25_b", C.c_float),
-                ("build_w", C.c_float * 3), ("seed", C.c_uint64)]
+                ("build_w", C.c_float * 3), ("prune_mode", C.c_int32), ("seed", C.c_uint64)]
 
 
 class _Queries(C.Structure):
@@ -132,9 +132,10 @@ class DeviceVecs:
 
 def build_params(degree: int, knn_k: Optional[int] = None, nd_rounds: int = 3, nd_sample: int = 32,
                  n_entry: int = 64, sp_len: int = 0, bm25_k1: float = 1.2, bm25_b: float = 0.75,
-                 build_w: Sequence[float] = (1.0, 1.0, 1.0), seed: int = 0) -> _BuildParams:
+                 build_w: Sequence[float] = (1.0, 1.0, 1.0), seed: int = 0, prune_mode: int = 0) -> _BuildParams:
+    """prune_mode: 0 joint RNG-IP pruning, 1 RNG only, 2 IP only (see ap_build_params)."""
     return _BuildParams(degree, knn_k if knn_k is not None else 2 * degree, nd_rounds, nd_sample, n_entry, sp_len,
-                        bm25_k1, bm25_b, (C.c_float * 3)(*build_w), seed)
+                        bm25_k1, bm25_b, (C.c_float * 3)(*build_w), prune_mode, seed)
 
 
 class Index:

@@ -37,6 +37,7 @@ int ap_validate_params(const ap_build_params *p) {
                p->degree);
     AP_REQUIRE(p->knn_k >= p->degree && p->knn_k <= 256, "knn_k = %d must be in [degree, 256]", p->knn_k);
     AP_REQUIRE(p->nd_rounds >= 0, "nd_rounds = %d must be >= 0", p->nd_rounds);
+    AP_REQUIRE(p->prune_mode >= AP_PRUNE_JOINT && p->prune_mode <= AP_PRUNE_IP_ONLY, "prune_mode = %d must be 0, 1 or 2", p->prune_mode);
     AP_REQUIRE(p->nd_sample >= 1 && p->nd_sample <= 32, "nd_sample = %d must be in [1, 32]", p->nd_sample);
     AP_REQUIRE(p->n_entry >= 1 && p->n_entry <= 256, "n_entry = %d must be in [1, 256]", p->n_entry);
     AP_REQUIRE(p->sp_len >= 0 && p->sp_len <= 32, "sp_len = %d must be in [0, 32]", p->sp_len);

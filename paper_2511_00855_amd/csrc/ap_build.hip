@@ -617,7 +617,8 @@ __global__ __launch_bounds__(256) void k_detour_prune(ApVecs D, const float *__r
                                                       int64_t x0, int64_t xout0, const float *__restrict__ pm,
                                                       int32_t *__restrict__ o_count, int32_t *__restrict__ o_sorted,
                                                       int32_t *__restrict__ o_se, int32_t *__restrict__ o_ke,
-                                                      int32_t *__restrict__ o_ke_count, int32_t *__restrict__ o_flag) {
+                                                      int32_t *__restrict__ o_ke_count, int32_t *__restrict__ o_flag,
+                                                      int32_t mode) {
     __shared__ int32_t ids[256], cnt[256], order[256], se_pos[128], flag[256];
     __shared__ float simA[256];
     __shared__ int32_t T[AP_T_CAP];
@@ -644,7 +645,11 @@ __global__ __launch_bounds__(256) void k_detour_prune(ApVecs D, const float *__r
     if (t < K) {
         int32_t r = 0;
         if (ids[t] >= 0) {
-            for (int32_t z = 0; z < K; z++) r += ids[z] >= 0 && (cnt[z] < cnt[t] || (cnt[z] == cnt[t] && z < t));
+            if (mode == AP_PRUNE_IP_ONLY) {   // ablation: no detour sort, the list as ranked by similarity
+                for (int32_t z = 0; z < t; z++) r += ids[z] >= 0;
+            } else {
+                for (int32_t z = 0; z < K; z++) r += ids[z] >= 0 && (cnt[z] < cnt[t] || (cnt[z] == cnt[t] && z < t));
+            }
         } else {
             for (int32_t z = 0; z < K; z++) r += ids[z] >= 0 || z < t;
         }
@@ -698,7 +703,8 @@ __global__ __launch_bounds__(256) void k_detour_prune(ApVecs D, const float *__r
         // IP test against every member of SE
         bool bad = false;
         const float sv = self_sim[v];
-        for (int32_t i = lane; i < nse; i += 64) bad = bad || !(P[(int64_t)se_pos[i] * K + pv] < sv);
+        if (mode != AP_PRUNE_RNG_ONLY)   // ablation: without the test SE is the first R of the detour order
+            for (int32_t i = lane; i < nse; i += 64) bad = bad || !(P[(int64_t)se_pos[i] * K + pv] < sv);
         const bool ok = nse < R && !__ballot(bad);
         if (lane == 0) {
             flag[pv] = fl;
@@ -747,7 +753,7 @@ static int prune_impl(const ap_index *ix, int32_t K, int32_t R, const int32_t *k
         }
         if (e != hipSuccess) break;
         hipLaunchKernelGGL(k_detour_prune, dim3((unsigned)cn), dim3(256), 0, st, ix->docs, ix->self_sim, K, R, R / 2, knn_ids,
-                           knn_sc, node_ids, x0, x0, pm, count, sorted_ids, se, ke, ke_count, flag);
+                           knn_sc, node_ids, x0, x0, pm, count, sorted_ids, se, ke, ke_count, flag, ix->params.prune_mode);
         e = hipGetLastError();
     }
     if (e == hipSuccess) e = hipStreamSynchronize(st);

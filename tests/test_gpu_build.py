@@ -195,6 +195,35 @@ def test_s5_rejections_by_ip_rule():
         witness += int(rank_of[int(se_pos[-1])] + 1 > len(se_pos))     # someone before the last member was turned away
     assert witness > 100            # the IP rule, not only the degree cap, rejected candidates
     ix.close()
+    # the two ablations of the joint strategy on the same lists: the stage equals the oracle's replay, and a whole
+    # build in that mode equals the chain of its stages
+    for mode in (O.PRUNE_RNG_ONLY, O.PRUNE_IP_ONLY):
+        _say(f"S5 ablation mode {mode}")
+        bp = B.build_params(R, knn_k=K, build_w=tuple(wv), prune_mode=mode, nd_rounds=1, nd_sample=8, n_entry=8)
+        ix = B.Index.ingest(docs, bp)
+        g = ix.stage_prune(K, R, ids1, sc1)
+        pm, srt, se, ke, ke_count, flag = _np(g["pm"], g["sorted_ids"], g["se"], g["ke"], g["ke_count"], g["flag"])
+        changed = 0
+        for u in range(500):
+            r = O.prune_node(D, u, wv, R, R // 2, ids1[u], sc1[u], self_all=self_gpu, Pm=pm[u], mode=mode)
+            assert np.array_equal(srt[u], r.sorted), (mode, u)
+            assert np.array_equal(se[u][:len(r.se)], r.se) and (se[u][len(r.se):] == -1).all(), (mode, u)
+            assert ke_count[u] == len(r.ke) and np.array_equal(ke[u][:len(r.ke)], r.ke) and np.array_equal(flag[u], r.flag)
+            j = O.prune_node(D, u, wv, R, R // 2, ids1[u], sc1[u], self_all=self_gpu, Pm=pm[u])
+            changed += list(j.se) != list(r.se)
+        assert changed > 100, (mode, changed)
+        P = bp.sp_len or -(-R // 6)
+        kid, ksc = ix.stage_seed_knn(K)
+        spi = torch.full((3, 500, P), -1, dtype=torch.int32, device=docs.device)
+        sps = torch.full((3, 500, P), -np.inf, dtype=torch.float32, device=docs.device)
+        kid, ksc, spi, sps = ix.stage_refine(K, 8, P, kid, spi, sps)
+        g = ix.stage_prune(K, R, kid, ksc)
+        graph = ix.stage_assemble(R, K, P, g["se"], g["sorted_ids"], spi).cpu().numpy()
+        whole = B.Index.build(docs, bp)
+        assert np.array_equal(whole.export_graph()[0].cpu().numpy(), graph), mode
+        whole.close(); ix.close()
+    with pytest.raises(RuntimeError):
+        B.Index.ingest(docs, B.build_params(R, knn_k=K, prune_mode=3))
 
 
 def test_s6_assemble_and_entry(case):

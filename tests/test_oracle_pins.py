@@ -379,6 +379,48 @@ def test_ip_prune_invariants_and_flags(small):
     assert n_rej_ip > 50 and n_ke > 50          # the test exercised both branches
 
 
+def test_pruning_ablations(small):
+    """The two ablations of the joint strategy (Section 5, RNG-IP joint pruning): RNG alone keeps the first R of the
+    detour order whatever the inner products say; IP alone walks the list in its similarity order."""
+    w, D, _ = small
+    R, K, cap = 6, 20, 3
+    wv = np.array([1, 1, 1], np.float32)
+    allv = np.arange(D.n)
+    ids0, sc0 = O.bruteforce_topk(D, allv, D, wv, K, skip_same=True)
+    sets = [set(D.tx_idx[D.tx_indptr[i]:D.tx_indptr[i + 1]].tolist()) for i in range(D.n)]
+    rng = np.random.default_rng(8)
+    differ_rng = differ_ip = 0
+    for u in range(0, D.n, 7):
+        ids = ids0[u].copy()
+        if u % 14 == 0:
+            ids[3] = -1
+        Pm = O.pairwise(D, wv, ids)
+        med = np.median(Pm[np.isfinite(Pm)])
+        self_s = np.where(ids >= 0, med * rng.uniform(0.8, 1.6, K), -np.inf).astype(np.float32)
+        self_all = np.zeros(D.n, np.float32); self_all[ids[ids >= 0]] = self_s[ids >= 0]
+        joint = O.prune_node(D, u, wv, R, cap, ids, sc0[u], self_all=self_all, Pm=Pm)
+        rng_only = O.prune_node(D, u, wv, R, cap, ids, sc0[u], self_all=self_all, Pm=Pm, mode=O.PRUNE_RNG_ONLY)
+        ip_only = O.prune_node(D, u, wv, R, cap, ids, sc0[u], self_all=self_all, Pm=Pm, mode=O.PRUNE_IP_ONLY)
+        valid_sorted = [int(x) for x in joint.sorted if x >= 0]
+        assert list(rng_only.se) == valid_sorted[:R]
+        assert np.array_equal(rng_only.order, joint.order) and np.array_equal(rng_only.count, joint.count)
+        # RNG alone recycles only what arrives after SE is full, and only if flagged against the full SE
+        full = [sets[y] for y in valid_sorted[:R]]
+        want_ke = [v for v in valid_sorted[R:] if _py_flag(sets[u], sets[v], full)][:cap]
+        assert list(rng_only.ke) == want_ke
+        # IP alone: greedy over the list as ranked by similarity
+        pos = [i for i in range(K) if ids[i] >= 0]
+        kept = [pos[0]]
+        for r in pos[1:]:
+            if len(kept) < R and all(Pm[y, r] < self_s[r] for y in kept):
+                kept.append(r)
+        assert list(ip_only.se) == [int(ids[r]) for r in kept]
+        assert list(ip_only.sorted[:len(pos)]) == [int(ids[r]) for r in pos]
+        differ_rng += list(rng_only.se) != list(joint.se)
+        differ_ip += list(ip_only.se) != list(joint.se)
+    assert differ_rng > 10 and differ_ip > 10
+
+
 # --------------------------------------------------------------- S6
 def test_assemble_structure():
     rng = np.random.default_rng(6)
