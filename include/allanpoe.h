@@ -143,6 +143,15 @@ int ap_search_batch_keywords(ap_index *index, const ap_queries *queries, const f
                              const ap_search_params *params, const int32_t *kw_terms, int32_t kw_stride,
                              uint32_t kw_flags, int32_t *out_ids, float *out_scores, void *stream);
 
+/* Mark-deletion (Section 4.1, updates of the hybrid index): the count listed
+ * documents (device ids) are marked deleted, or restored when restore != 0.
+ * Deleted documents stay in the graph and are searched through like any
+ * other; ap_search_batch and ap_search_batch_keywords leave them out of their
+ * answers (and out of the secondary pool), so an answer holds the best k live
+ * documents the search met.  Synchronises `stream`; ids outside [0, n) are
+ * skipped and reported as AP_EINVAL after the others were applied. */
+int ap_mark_deleted(ap_index *index, const int32_t *ids, int64_t count, int restore, void *stream);
+
 void ap_free_index(ap_index *index);
 const char *ap_last_error(void); /* host string, thread-local */
 

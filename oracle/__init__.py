@@ -290,8 +290,18 @@ def build_index(docs, params):
 
 
 # ---------------------------------------------------------------- S7..S9
+def _deleted_bytes(deleted, n):
+    if deleted is None:
+        return None
+    d = np.zeros(n, np.uint8)
+    d[np.asarray(deleted, np.int64)] = 1
+    return d
+
+
 def search(D: VS, graph, entry, Q: VS, qi, w, k, L, max_iters=0, width=1, score_table=None,
-           log=False):
+           log=False, deleted=None):
+    """deleted: ids of mark-deleted documents (searched through, left out of the answer)."""
+    dl = _deleted_bytes(deleted, D.n)
     graph = _c(graph, np.int32)
     entry = _c(entry, np.int32)
     R = graph.shape[1]
@@ -302,7 +312,7 @@ def search(D: VS, graph, entry, Q: VS, qi, w, k, L, max_iters=0, width=1, score_
     vl = np.empty(max(cap, 1), np.int32)
     n = lib().orc_search(D.ref, _p(graph), C.c_int32(R), _p(entry), C.c_int32(len(entry)), Q.ref,
                          C.c_int64(qi), _p(w), C.c_int32(k), C.c_int32(L), C.c_int32(max_iters),
-                         C.c_int32(width), _p(st), _p(ids), _p(sc), _p(vl) if log else None,
+                         C.c_int32(width), _p(st), _p(dl), _p(ids), _p(sc), _p(vl) if log else None,
                          C.c_int64(cap))
     if log:
         return ids, sc, vl[:n].copy()
@@ -320,12 +330,13 @@ def search_batch(D: VS, graph, entry, Q: VS, q_ids: Sequence[int], w, k, L, max_
 
 
 def search_kw(D: VS, graph, kw_edges, kw_count, entry, Q: VS, qi, w, k, L, kw, kw_all=False, use_kw_edges=True,
-              max_iters=0, width=1, score_table=None, log=False):
+              max_iters=0, width=1, score_table=None, log=False, deleted=None):
     """Keyword-constrained search (Section 4.2.2, Algorithm 2's keyword branches) for one query.
     kw: the required term ids (empty = unconstrained)."""
     graph = _c(graph, np.int32); kw_edges = _c(kw_edges, np.int32); kw_count = _c(kw_count, np.int32)
     entry = _c(entry, np.int32)
     kw = _c(np.asarray(kw, np.int32).reshape(-1), np.int32)
+    dl = _deleted_bytes(deleted, D.n)     # kept alive across the call
     w = _c(w, np.float32)
     ids = np.empty(k, np.int32); sc = np.empty(k, np.float32)
     st = None if score_table is None else _c(score_table, np.float32)
@@ -334,8 +345,8 @@ def search_kw(D: VS, graph, kw_edges, kw_count, entry, Q: VS, qi, w, k, L, kw, k
     n = lib().orc_search_kw(D.ref, _p(graph), C.c_int32(graph.shape[1]), _p(kw_edges), C.c_int32(kw_edges.shape[1]),
                             _p(kw_count), _p(entry), C.c_int32(len(entry)), Q.ref, C.c_int64(qi), _p(w), C.c_int32(k),
                             C.c_int32(L), C.c_int32(max_iters), C.c_int32(width), _p(kw), C.c_int32(len(kw)),
-                            C.c_int32(int(kw_all)), C.c_int32(int(use_kw_edges)), _p(st), _p(ids), _p(sc),
-                            _p(vl) if log else None, C.c_int64(cap))
+                            C.c_int32(int(kw_all)), C.c_int32(int(use_kw_edges)), _p(st),
+                            _p(dl), _p(ids), _p(sc), _p(vl) if log else None, C.c_int64(cap))
     if log:
         return ids, sc, vl[:n].copy()
     return ids, sc, int(n)

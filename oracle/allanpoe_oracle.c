@@ -481,18 +481,20 @@ void orc_entry_points(int64_t N, const float *self, int32_t E, int32_t *out) {
  * iterations (0 = no limit).  score_table, if not NULL, supplies the fused
  * score of every document for this query (length N) instead of computing it:
  * used to replay the selection logic on another implementation's scores.
+ * deleted, if not NULL, marks documents (one byte each) that are removed from
+ * the answer but not from the search.
  * visit_log (optional, capacity log_cap) receives the ids in scoring order.
  * Returns the number of scored documents.                               */
 int64_t orc_search(const orc_vecset *D, const int32_t *graph, int32_t R, const int32_t *entry,
                    int32_t E, const orc_vecset *Q, int64_t qi, const float w[3], int32_t k, int32_t L,
-                   int32_t max_iters, int32_t width, const float *score_table, int32_t *out_ids,
-                   float *out_scores, int32_t *visit_log, int64_t log_cap) {
+                   int32_t max_iters, int32_t width, const float *score_table, const unsigned char *deleted,
+                   int32_t *out_ids, float *out_scores, int32_t *visit_log, int64_t log_cap) {
     int64_t N = D->n, nscored = 0;
     unsigned char *visited = (unsigned char *)calloc((size_t)(N > 0 ? N : 1), 1);
     scored *pool = (scored *)malloc(sizeof(scored) * (size_t)(L + 1));
     unsigned char *expanded = (unsigned char *)malloc((size_t)(L + 1));
     int32_t *parents = (int32_t *)malloc(sizeof(int32_t) * (size_t)(width > 0 ? width : 1));
-    int32_t len = 0, it = 0, i, e;
+    int32_t len = 0, it = 0, i, e, nout = 0;
 
 #define ORC_SCORE(v) (score_table ? score_table[(v)] : hybrid_fused(Q, qi, D, (v), w))
 #define ORC_INSERT(v, s)                                                                       \
@@ -537,10 +539,13 @@ int64_t orc_search(const orc_vecset *D, const int32_t *graph, int32_t R, const i
         }
         it++;
     }
-    for (i = 0; i < k; i++) {
-        out_ids[i] = i < len ? pool[i].id : -1;
-        out_scores[i] = i < len ? pool[i].s : -INFINITY;
+    /* mark-deletion (Section 4.1, updates): deleted documents take part in the search like any other and are
+     * left out of the answer */
+    for (i = 0; i < len && nout < k; i++) {
+        if (deleted && deleted[pool[i].id]) continue;
+        out_ids[nout] = pool[i].id; out_scores[nout] = pool[i].s; nout++;
     }
+    for (i = nout; i < k; i++) { out_ids[i] = -1; out_scores[i] = -INFINITY; }
 #undef ORC_SCORE
 #undef ORC_INSERT
     free(visited); free(pool); free(expanded); free(parents);
@@ -560,7 +565,9 @@ int64_t orc_search(const orc_vecset *D, const int32_t *graph, int32_t R, const i
  *    keeps the k best of them;
  *  - the result is the k best satisfying documents of pool and secondary
  *    pool together.
- * n_kw = 0 means "no constraint": the base search.                     */
+ * n_kw = 0 means "no constraint": the base search.  Deleted documents
+ * (see orc_search) still expand their keyword edges when they satisfy the
+ * constraint, but enter neither the secondary pool nor the answer.      */
 static int kw_satisfied(const orc_vecset *D, int64_t v, const int32_t *kw, int32_t n_kw, int32_t kw_all) {
     int32_t hits = 0, j;
     int64_t p;
@@ -576,8 +583,9 @@ static int kw_satisfied(const orc_vecset *D, int64_t v, const int32_t *kw, int32
 int64_t orc_search_kw(const orc_vecset *D, const int32_t *graph, int32_t R, const int32_t *kw_edges, int32_t KR,
                       const int32_t *kw_count, const int32_t *entry, int32_t E, const orc_vecset *Q, int64_t qi,
                       const float w[3], int32_t k, int32_t L, int32_t max_iters, int32_t width, const int32_t *kw,
-                      int32_t n_kw, int32_t kw_all, int32_t use_kw_edges, const float *score_table, int32_t *out_ids,
-                      float *out_scores, int32_t *visit_log, int64_t log_cap) {
+                      int32_t n_kw, int32_t kw_all, int32_t use_kw_edges, const float *score_table,
+                      const unsigned char *deleted, int32_t *out_ids, float *out_scores, int32_t *visit_log,
+                      int64_t log_cap) {
     int64_t N = D->n, nscored = 0;
     unsigned char *visited = (unsigned char *)calloc((size_t)(N > 0 ? N : 1), 1);
     scored *pool = (scored *)malloc(sizeof(scored) * (size_t)(L + 1));
@@ -591,8 +599,8 @@ int64_t orc_search_kw(const orc_vecset *D, const int32_t *graph, int32_t R, cons
 
     if (n_kw <= 0) {
         free(visited); free(pool); free(expanded); free(sat); free(second); free(all); free(parents); free(psat);
-        return orc_search(D, graph, R, entry, E, Q, qi, w, k, L, max_iters, width, score_table, out_ids, out_scores,
-                          visit_log, log_cap);
+        return orc_search(D, graph, R, entry, E, Q, qi, w, k, L, max_iters, width, score_table, deleted, out_ids,
+                          out_scores, visit_log, log_cap);
     }
     /* one newly seen document: score it, offer it to the pool, pass what the pool does not keep to the secondary pool */
 #define KW_VISIT(v)                                                                                   \
@@ -613,7 +621,7 @@ int64_t orc_search_kw(const orc_vecset *D, const int32_t *graph, int32_t R, cons
             }                                                                                         \
             pool[p_].s = s_; pool[p_].id = (v); expanded[p_] = 0; sat[p_] = (unsigned char)sat_; len++; \
         }                                                                                             \
-        if (have_out_ && out_sat_ &&                                                                  \
+        if (have_out_ && out_sat_ && !(deleted && deleted[out_.id]) &&                                \
             (nsec < k || ranks_before(out_.s, out_.id, second[nsec - 1].s, second[nsec - 1].id))) {   \
             if (nsec == k) nsec--;                                                                    \
             p_ = nsec;                                                                                \
@@ -659,7 +667,7 @@ int64_t orc_search_kw(const orc_vecset *D, const int32_t *graph, int32_t R, cons
     }
 #undef KW_VISIT
     /* merge both pools, keep the satisfying documents, best k */
-    for (i = 0; i < len; i++) if (sat[i]) all[nall++] = pool[i];
+    for (i = 0; i < len; i++) if (sat[i] && !(deleted && deleted[pool[i].id])) all[nall++] = pool[i];
     for (i = 0; i < nsec; i++) all[nall++] = second[i];
     qsort(all, (size_t)nall, sizeof(scored), cmp_scored);
     for (i = 0; i < k; i++) {

@@ -207,6 +207,13 @@ class Index:
         _check(rc, "ap_search_batch")
         return ids, sc
 
+    def mark_deleted(self, ids, restore: bool = False):
+        """Marks documents deleted (or restores them): searched through, left out of the answers."""
+        t = _dev(ids, torch.int32, self.device).reshape(-1)
+        with torch.cuda.device(self.device):
+            _check(lib().ap_mark_deleted(self._h, _ptr(t), C.c_int64(t.numel()), C.c_int(int(restore)), _stream()),
+                   "ap_mark_deleted")
+
     def search_batch_keywords(self, queries: DeviceVecs, k: int, beam: int, kw_terms, per_query_w=None,
                               kw_all: bool = False, use_kw_edges: bool = True, max_iters: int = 0,
                               search_width: int = 1):

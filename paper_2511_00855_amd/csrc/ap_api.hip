@@ -231,7 +231,7 @@ extern "C" int ap_ingest(const ap_corpus *corpus, const ap_build_params *params,
 
 extern "C" void ap_free_index(ap_index *ix) {
     if (!ix) return;
-    void *ptrs[] = {ix->tx_w, ix->df, ix->stats, ix->self_sim, ix->graph, ix->kw, ix->kw_count, ix->entry, ix->visited, ix->w_dev,
+    void *ptrs[] = {ix->deleted, ix->deleted_bad, ix->tx_w, ix->df, ix->stats, ix->self_sim, ix->graph, ix->kw, ix->kw_count, ix->entry, ix->visited, ix->w_dev,
                     ix->search_counts, ix->dense_norm, ix->rec, ix->meta};
     for (void *p : ptrs) if (p) (void)hipFree(p);
     for (hipEvent_t e : ix->ev_search) if (e) (void)hipEventDestroy(e);
@@ -302,6 +302,41 @@ extern "C" int ap_export_graph(const ap_index *ix, int32_t *semantic, int32_t *k
     if (keyword) AP_CHECK_HIP(hipMemcpyAsync(keyword, ix->kw, n * (R / 2) * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
     if (kw_count) AP_CHECK_HIP(hipMemcpyAsync(kw_count, ix->kw_count, n * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
     if (entry) AP_CHECK_HIP(hipMemcpyAsync(entry, ix->entry, (size_t)ix->params.n_entry * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
+    return AP_OK;
+}
+
+// Mark-deletion (Section 4.1, updates of the hybrid index): deleted documents stay in the graph and are searched
+// through; the searches leave them out of their answers.
+__global__ void k_mark_deleted(uint32_t *__restrict__ bits, int64_t n, const int32_t *__restrict__ ids, int64_t count, int restore,
+                               int32_t *__restrict__ bad) {
+    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < count; i += (int64_t)gridDim.x * blockDim.x) {
+        const int32_t v = ids[i];
+        if (v < 0 || v >= n) { atomicAdd(bad, 1); continue; }
+        if (restore) atomicAnd(&bits[v >> 5], ~(1u << (v & 31)));
+        else atomicOr(&bits[v >> 5], 1u << (v & 31));
+    }
+}
+
+extern "C" int ap_mark_deleted(ap_index *ix, const int32_t *ids, int64_t count, int restore, void *stream) {
+    AP_REQUIRE(ix, "index is NULL");
+    AP_REQUIRE(count >= 0 && (ids || count == 0), "ids is NULL");
+    if (count == 0) return AP_OK;
+    hipStream_t st = (hipStream_t)stream;
+    const size_t words = ((size_t)ix->corpus.n + 31) / 32;
+    if (!ix->deleted) {
+        if (restore) return AP_OK;   // nothing was ever deleted
+        AP_TRY(ap_dev_alloc(&ix->deleted, words));
+        AP_TRY(ap_dev_alloc(&ix->deleted_bad, 1));
+        AP_TRY(ap_fill_u32(ix->deleted, words, 0u, st));
+    }
+    AP_TRY(ap_fill_u32(ix->deleted_bad, 1, 0u, st));
+    const unsigned blocks = (unsigned)std::min<int64_t>((count + 255) / 256, 4096);
+    hipLaunchKernelGGL(k_mark_deleted, dim3(blocks), dim3(256), 0, st, ix->deleted, ix->corpus.n, ids, count, restore, ix->deleted_bad);
+    AP_CHECK_HIP(hipGetLastError());
+    int32_t bad = 0;
+    AP_CHECK_HIP(hipMemcpyAsync(&bad, ix->deleted_bad, sizeof(bad), hipMemcpyDeviceToHost, st));
+    AP_CHECK_HIP(hipStreamSynchronize(st));
+    AP_REQUIRE(bad == 0, "%d of the %lld ids are outside [0, n); the others were applied", bad, (long long)count);
     return AP_OK;
 }
 

@@ -73,6 +73,8 @@ struct ap_index {
     int32_t *kw_count = nullptr;
     int32_t *entry = nullptr;  // owned: n_entry
     bool has_graph = false;
+    uint32_t *deleted = nullptr;   // owned: one bit per document, set = mark-deleted (allocated on first use)
+    int32_t *deleted_bad = nullptr; // owned: 1 counter, ids out of range in the last ap_mark_deleted
     float w_default[3] = {1.f, 1.f, 1.f};
     // search workspace (grow only)
     uint32_t *visited = nullptr;

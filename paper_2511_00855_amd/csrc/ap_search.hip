@@ -31,6 +31,7 @@ struct ApSearchArgs {
     int32_t *counts;    // nq x 3: candidates scored, iterations, candidates whose dense row was skipped
     const uint2 *rec;   // packed (term, weight) records of the documents' two sparse parts
     const uint4 *meta;  // per document: first entry, counts, |d_dense|
+    const uint32_t *deleted;   // one bit per document, NULL = nothing is mark-deleted: left out of the answers only
     // keyword-constrained search only
     const int32_t *kw_edges;   // n x KR keyword edges, kw_count[u] of them valid
     const int32_t *kw_count;
@@ -302,9 +303,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
             __syncthreads();
             if (wave == 0) {
                 const int32_t m = s_xn;
+                if (g.deleted) {   // a mark-deleted document cannot be an answer: it does not take a place here
+                    for (int32_t j = lane; j < m; j += 64) {
+                        const int32_t v = ap_pool_id<KW>(xk[j]);
+                        if ((g.deleted[v >> 5] >> (v & 31)) & 1u) xk[j] = 0ull;
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                }
                 for (int32_t j = 0; j < m; j++) {
                     const uint64_t key = xk[j] & ~1ull;
-                    if (kc == g.k && key < kwc[kc - 1]) continue;
+                    if (key == 0ull || (kc == g.k && key < kwc[kc - 1])) continue;
                     int32_t pos = 0;
                     for (int32_t base = 0; base < kc; base += 64) {
                         const int32_t i = base + lane;
@@ -379,7 +388,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
             int32_t o = 0;
             for (int32_t base = 0; base < len && o < g.k; base += 64) {
                 const int32_t i = base + lane;
-                const bool sat = i < len && (cur[i] & 2ull);
+                bool sat = i < len && (cur[i] & 2ull);
+                if (sat && g.deleted) { const int32_t v = ap_pool_id<KW>(cur[i]); sat = !((g.deleted[v >> 5] >> (v & 31)) & 1u); }
                 const uint64_t mask = __ballot(sat);
                 const int32_t at = o + __popcll(mask & ((1ull << lane) - 1ull));
                 if (sat && at < g.k) {
@@ -394,6 +404,26 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
                 g.out_ids[q * g.k + i] = have ? ap_pool_id<KW>(kwc[i - o]) : -1;
                 g.out_scores[q * g.k + i] = have ? ap_key_score(kwc[i - o]) : -INFINITY;
             }
+        }
+        return;
+    }
+    if (g.deleted) {
+        // mark-deletion: the best k pool entries that are not deleted
+        if (wave == 0) {
+            int32_t o = 0;
+            for (int32_t base = 0; base < len && o < g.k; base += 64) {
+                const int32_t i = base + lane;
+                bool live = i < len;
+                if (live) { const int32_t v = ap_pool_id<KW>(cur[i]); live = !((g.deleted[v >> 5] >> (v & 31)) & 1u); }
+                const uint64_t mask = __ballot(live);
+                const int32_t at = o + __popcll(mask & ((1ull << lane) - 1ull));
+                if (live && at < g.k) {
+                    g.out_ids[q * g.k + at] = ap_pool_id<KW>(cur[i]);
+                    g.out_scores[q * g.k + at] = ap_key_score(cur[i]);
+                }
+                o += __popcll(mask);
+            }
+            for (int32_t i = (o < g.k ? o : g.k) + lane; i < g.k; i += 64) { g.out_ids[q * g.k + i] = -1; g.out_scores[q * g.k + i] = -INFINITY; }
         }
         return;
     }
@@ -455,6 +485,7 @@ static int ap_search_impl(ap_index *ix, const ap_queries *q, const float *per_qu
     g.counts = ix->search_counts;
     g.rec = ix->rec;
     g.meta = ix->meta;
+    g.deleted = ix->deleted;
     ix->last_nq = q->nq;
     AP_TRY(ap_fill_u32(ix->visited, need, 0u, st));
     const size_t smem = (size_t)(g.L + 3 * g.cmax + (kw ? g.cmax + g.k : 0)) * 8 + (size_t)g.cmax * (16 + 4) +

@@ -135,3 +135,39 @@ def test_keyword_argument_checks(tiny):
         ix.search_batch_keywords(qs, 10, 32, np.full((qs.n, 17), -1, np.int32))
     with pytest.raises(RuntimeError):
         ix.search_batch_keywords(qs, 64, 32, np.full((qs.n, 2), -1, np.int32))
+
+
+def test_mark_deletion(tiny):
+    """Mark-deleted documents are searched through and left out of the answers of both searches; restoring them
+    brings the old answers back."""
+    w, docs, qs, ix, D, Q, sem, ke, kc, ent, wq, table = tiny
+    _say("mark-deletion")
+    N = docs.n
+    k, L = 10, 32
+    base_ids, base_sc = [t.cpu().numpy() for t in ix.search_batch(qs, k, L, wq)]
+    base_counts = ix.search_stats(qs.n)[0].cpu().numpy()
+    rng = np.random.default_rng(6)
+    dele = np.unique(np.concatenate([rng.choice(N, N // 5, replace=False), base_ids[:, 0], base_ids[:, 4]])).astype(np.int32)
+    kw = make_keywords(w.queries, seed=4, max_terms=2, stride=2, p_none=0.1)
+    try:
+        ix.mark_deleted(dele)
+        ids, sc = [t.cpu().numpy() for t in ix.search_batch(qs, k, L, wq)]
+        counts = ix.search_stats(qs.n)[0].cpu().numpy()
+        assert np.array_equal(counts[:, :2], base_counts[:, :2])          # the search itself did not change
+        assert not np.isin(ids[ids >= 0], dele).any()
+        kids, ksc = [t.cpu().numpy() for t in ix.search_batch_keywords(qs, k, L, kw, wq)]
+        kids2, ksc2 = [t.cpu().numpy() for t in ix.search_batch_keywords(qs, 8, 8, kw, wq, True, True, 0, 2)]
+        for qi in range(qs.n):
+            oi, os_, _ = O.search(D, sem, ent, Q, qi, wq[qi], k, L, score_table=table[qi], deleted=dele)
+            assert np.array_equal(ids[qi], oi) and np.array_equal(sc[qi], os_), qi
+            oi, os_, _ = O.search_kw(D, sem, ke, kc, ent, Q, qi, wq[qi], k, L, _kw_list(kw[qi]), score_table=table[qi], deleted=dele)
+            assert np.array_equal(kids[qi], oi) and np.array_equal(ksc[qi], os_), qi
+            oi, os_, _ = O.search_kw(D, sem, ke, kc, ent, Q, qi, wq[qi], 8, 8, _kw_list(kw[qi]), True, True, 0, 2,
+                                     score_table=table[qi], deleted=dele)
+            assert np.array_equal(kids2[qi][:8], oi) and np.array_equal(ksc2[qi][:8], os_), qi
+        with pytest.raises(RuntimeError):
+            ix.mark_deleted(np.array([3, N, 5], np.int32))
+    finally:
+        ix.mark_deleted(np.concatenate([dele, [3, 5]]).astype(np.int32), restore=True)
+    ids, sc = [t.cpu().numpy() for t in ix.search_batch(qs, k, L, wq)]
+    assert np.array_equal(ids, base_ids) and np.array_equal(sc, base_sc)

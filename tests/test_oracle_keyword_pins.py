@@ -173,3 +173,63 @@ def test_python_set_restatement(small, kw_all):
                 assert all(sat[int(x)] for x in ids if x >= 0)
                 found += len(res)
     assert found > 0
+
+
+# ------------------------------------------------------------- mark-deletion (Section 4.1, updates of the index)
+def test_mark_deletion_filters_only_the_answer(small):
+    """Deleted documents are searched through and left out of the answer: the visit log does not change, and the
+    answer is the undeleted part of the pool.  With a pool as large as the corpus on a graph that reaches
+    everything, the answer is the exact top-k of the undeleted documents."""
+    w, D, Q, b, wq, table = small
+    N = D.n
+    rng = np.random.default_rng(12)
+    for qi in range(Q.n):
+        base_ids, _, base_log = O.search(D, b.graph, b.entry, Q, qi, wq, 12, 12, log=True)
+        dele = [int(base_ids[0]), int(base_ids[3]), int(rng.integers(0, N))]
+        ids, sc, log = O.search(D, b.graph, b.entry, Q, qi, wq, 5, 12, log=True, deleted=dele)
+        assert np.array_equal(log, base_log)
+        want = [int(v) for v in base_ids if v >= 0 and v not in dele][:5]
+        assert [int(v) for v in ids if v >= 0] == want
+        assert np.allclose(sc[:len(want)], table[qi][want], rtol=1e-6)
+        # nothing deleted = the plain search
+        a = O.search(D, b.graph, b.entry, Q, qi, wq, 5, 12, deleted=[])
+        c = O.search(D, b.graph, b.entry, Q, qi, wq, 5, 12)
+        assert np.array_equal(a[0], c[0]) and np.array_equal(a[1], c[1])
+    ring = np.stack([(np.arange(N) + s) % N for s in (1, 5)], axis=1).astype(np.int32)
+    dele = rng.choice(N, N // 3, replace=False)
+    for qi in range(4):
+        ids, _, nv = O.search(D, ring, np.array([0], np.int32), Q, qi, wq, 7, N, deleted=dele)
+        alive = [v for v in np.argsort(-table[qi].astype(np.float64), kind="stable") if v not in set(dele.tolist())]
+        alive.sort(key=lambda v: (-float(table[qi][v]), v))
+        assert nv == N and list(ids) == alive[:7]
+
+
+def test_mark_deletion_with_keywords():
+    """The six documents of the hand-traced case with document 2 deleted: 2 still satisfies the keyword, so its
+    keyword edge to 5 is still followed, but 2 itself is neither kept in the secondary pool nor returned."""
+    D, Q, graph, ke, kc = _six_documents()
+    w = (1.0, 0.0, 0.0)
+    entry = np.array([0], np.int32)
+    ids, sc, log = O.search_kw(D, graph, ke, kc, entry, Q, 0, w, 2, 2, [7], log=True, deleted=[2])
+    assert list(log) == [0, 1, 2, 5] and list(ids) == [5, -1]
+    ids, _, _ = O.search_kw(D, graph, ke, kc, entry, Q, 0, w, 2, 2, [7], deleted=[5])
+    assert list(ids) == [2, -1]
+    ids, _, _ = O.search_kw(D, graph, ke, kc, entry, Q, 0, w, 2, 2, [7], deleted=[0, 1])
+    assert list(ids) == [5, 2]
+
+
+def test_mark_deletion_keyword_restatement(small):
+    w, D, Q, b, wq, table = small
+    N = D.n
+    rng = np.random.default_rng(3)
+    dele = set(rng.choice(N, N // 4, replace=False).tolist())
+    for qi in range(Q.n):
+        kw = _query_keywords(w, qi, 2)
+        sat = [_satisfies(w, v, kw, False) for v in range(N)]
+        for (k, L, width) in ((5, 12, 1), (4, 8, 2)):
+            ids, sc, log = O.search_kw(D, b.graph, b.ke, b.ke_count, b.entry, Q, qi, wq, k, L, kw, width=width, log=True,
+                                       deleted=sorted(dele))
+            # the restatement with an unbounded secondary pool returns all satisfying documents it met, in order
+            res, order = _py_search_kw(table[qi], sat, b.graph, b.ke, b.ke_count, b.entry, N, L, width, 0)
+            assert list(log) == order
+            assert [int(x) for x in ids if x >= 0] == [v for v in res if v not in dele][:k]
