@@ -350,3 +350,92 @@ def search_kw(D: VS, graph, kw_edges, kw_count, entry, Q: VS, qi, w, k, L, kw, k
     if log:
         return ids, sc, vl[:n].copy()
     return ids, sc, int(n)
+
+
+# ---------------------------------------------------------------- updates: insertion
+def rows_of(D: VS, lo: int, hi: int) -> VS:
+    """Documents lo..hi-1 of an encoded vector set as a vector set of their own (values unchanged)."""
+    ns = SimpleNamespace(n=hi - lo, dim=D.dim, dense=D.dense[lo:hi],
+                         sp_indptr=D.sp_indptr[lo:hi + 1] - D.sp_indptr[lo],
+                         sp_idx=D.sp_idx[D.sp_indptr[lo]:D.sp_indptr[hi]], sp_val=D.sp_val[D.sp_indptr[lo]:D.sp_indptr[hi]],
+                         tx_indptr=D.tx_indptr[lo:hi + 1] - D.tx_indptr[lo],
+                         tx_idx=D.tx_idx[D.tx_indptr[lo]:D.tx_indptr[hi]], tx_val=D.tx_val[D.tx_indptr[lo]:D.tx_indptr[hi]])
+    return VS(ns)
+
+
+def merge_ranked(ids_a, sc_a, ids_b, sc_b, K):
+    """Best K of two ranked lists over disjoint ids, by (score descending, id ascending); -1 / -inf padded."""
+    both = [(float(s), int(i)) for i, s in zip(ids_a, sc_a) if i >= 0] + [(float(s), int(i)) for i, s in zip(ids_b, sc_b) if i >= 0]
+    both.sort(key=lambda t: (-t[0], t[1]))
+    both = both[:K]
+    ids = np.full(K, -1, np.int32); sc = np.full(K, -np.inf, np.float32)
+    ids[:len(both)] = [t[1] for t in both]; sc[:len(both)] = [t[0] for t in both]
+    return ids, sc
+
+
+def insert_index(old, docs, beam=None):
+    """Insertion of new documents (Section 4.1, updates of the hybrid index).  `docs` is the enlarged corpus: its
+    first N0 documents are those of the index `old` (a build_index or insert_index result), the rest are new.
+      0. S0 over the enlarged corpus (corpus statistics, hence all lexical weights, are those of the new corpus).
+      1. Candidate set one: the K best old documents for each new one, found by the search of Algorithm 2 on the
+         old semantic edges from the old entry points, with the new document as the query, the construction
+         weights and a pool of `beam` (default 2K).
+      2. Candidate set two: K-lists among the new documents alone (seed + the usual refinement rounds).
+      3. The K-list of a new document = the best K of both sets; it is scored once more without 2-hop exploration
+         so that its per-path lists = the best P per path among set two's per-path lists and the list's members.
+      4. S4/S5 for the new documents only; S6 over all documents (old documents gain reverse neighbours among the
+         new ones); entry points from all self-similarities.
+    Returns a namespace like build_index's, plus the intermediates of steps 1-3 for the new documents."""
+    params = old.params
+    D = encode_docs(docs, params.bm25_k1, params.bm25_b)
+    N0, N1 = old.graph.shape[0], D.n
+    M = N1 - N0
+    assert M >= 1
+    R, K, P = params.degree, params.knn_k, params.sp_len
+    w = np.asarray(params.build_w, np.float32)
+    L = int(beam) if beam else 2 * K
+    self_s = self_sim(D, np.arange(N1, dtype=np.int64), w)
+    # 1: the old graph, padded with edge-less rows for the new documents (they are never reached)
+    g_old = np.vstack([old.graph, np.full((M, R), -1, np.int32)])
+    c1_ids = np.empty((M, K), np.int32); c1_sc = np.empty((M, K), np.float32)
+    for j in range(M):
+        c1_ids[j], c1_sc[j], _ = search(D, g_old, old.entry, D, N0 + j, w, K, max(L, K))
+    # 2: the new documents among themselves
+    Dn = rows_of(D, N0, N1)
+    c2_ids, c2_sc = seed_knn(Dn, np.arange(M, dtype=np.int64), K)
+    spi2, sps2 = empty_sp(M, P)
+    for _ in range(params.nd_rounds):
+        c2_ids, c2_sc, spi2, sps2 = refine_round(Dn, w, K, params.nd_sample, P, c2_ids, spi2, sps2)
+    if params.nd_rounds == 0:
+        c2_sc = hybrid_block(Dn, np.arange(M), Dn, c2_ids, w)[:, :, 3].copy()
+    shift = lambda a: np.where(a >= 0, a + N0, -1).astype(np.int32)
+    c2_ids, spi2 = shift(c2_ids), shift(spi2)
+    # 3: merge, then per-path lists
+    knn = np.full((N1, K), -1, np.int32); knn_sc = np.full((N1, K), -np.inf, np.float32)
+    for j in range(M):
+        knn[N0 + j], knn_sc[N0 + j] = merge_ranked(c1_ids[j], c1_sc[j], c2_ids[j], c2_sc[j], K)
+    merged_ids = knn[N0:].copy(); merged_sc = knn_sc[N0:].copy()
+    spi = np.full((3, N1, P), -1, np.int32); sps = np.full((3, N1, P), -np.inf, np.float32)
+    spi[:, :N0], sps[:, :N0] = old.sp_ids, old.sp_scores
+    spi[:, N0:], sps[:, N0:] = spi2, sps2
+    newv = np.arange(N0, N1, dtype=np.int64)
+    f_ids, f_sc, f_spi, f_sps = refine_round(D, w, K, 0, P, knn, spi, sps, node_ids=newv)
+    knn[N0:], knn_sc[N0:] = f_ids, f_sc
+    spi[:, N0:], sps[:, N0:] = f_spi, f_sps
+    # 4
+    se = np.vstack([old.se, np.full((M, R), -1, np.int32)])
+    ke = np.vstack([old.ke, np.full((M, old.ke.shape[1]), -1, np.int32)])
+    ke_cnt = np.concatenate([old.ke_count, np.zeros(M, np.int32)])
+    sorted_ids = np.vstack([old.sorted_ids, np.full((M, K), -1, np.int32)])
+    for u in range(N0, N1):
+        r = prune_node(D, u, w, R, params.ke_cap, knn[u], knn_sc[u], self_all=self_s, mode=params.prune_mode)
+        se[u, :len(r.se)] = r.se
+        ke[u, :len(r.ke)] = r.ke
+        ke_cnt[u] = len(r.ke)
+        sorted_ids[u] = r.sorted
+    graph = assemble(N1, R, K, P, se, sorted_ids, spi)
+    entry = entry_points(self_s, params.n_entry)
+    return SimpleNamespace(D=D, self_sim=self_s, knn_ids=knn, knn_scores=knn_sc, sp_ids=spi, sp_scores=sps, se=se, ke=ke,
+                           ke_count=ke_cnt, sorted_ids=sorted_ids, graph=graph, entry=entry, params=params,
+                           cand1_ids=c1_ids, cand1_scores=c1_sc, cand2_ids=c2_ids, cand2_scores=c2_sc,
+                           cand2_sp_ids=spi2, cand2_sp_scores=sps2, merged_ids=merged_ids, merged_scores=merged_sc, n_old=N0)
