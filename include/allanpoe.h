@@ -152,6 +152,40 @@ int ap_search_batch_keywords(ap_index *index, const ap_queries *queries, const f
  * skipped and reported as AP_EINVAL after the others were applied. */
 int ap_mark_deleted(ap_index *index, const int32_t *ids, int64_t count, int restore, void *stream);
 
+/* Insertion of new documents (Section 4.1, updates of the hybrid index).
+ * `enlarged` is the corpus after the insertion: its first n0 documents are
+ * those of `old`, unchanged and in the same order, the rest are new; same
+ * dimension, dense type and vocabularies.  Produces a new index over the
+ * enlarged corpus (which it borrows like ap_build_index does); `old` stays
+ * valid and is not modified.  Steps: S0 over the enlarged corpus (lexical
+ * weights follow the new corpus statistics); candidate set one = the K best
+ * old documents for each new one, found by the search of Algorithm 2 on the
+ * old semantic edges with the new document as the query, the construction
+ * weights and a pool of `beam` (0 = 2K); candidate set two = K-lists among the
+ * new documents alone (seed + the refinement rounds of the parameters); the
+ * K-list of a new document = the best K of both sets; pruning and keyword
+ * recycling for the new documents only; edge-list assembly over all documents
+ * (old documents gain reverse neighbours among the new ones); entry points
+ * from all self-similarities.  Needs an index produced by ap_build_index or
+ * ap_insert_documents (AP_ESTATE for an imported graph).  Synchronises
+ * `stream`.  trace (may be NULL): optional device buffers that receive the
+ * intermediates for the m = n1 - n0 new documents, any of them NULL. */
+typedef struct {
+    int32_t *cand1_ids; float *cand1_sc;       /* m x K: candidate set one */
+    int32_t *cand2_ids; float *cand2_sc;       /* m x K: candidate set two (global ids) */
+    int32_t *cand2_sp_ids; float *cand2_sp_sc; /* 3 x m x P: per-path lists that came with set two */
+    int32_t *merged_ids; float *merged_sc;     /* m x K: best K of both sets */
+    int32_t *knn_ids; float *knn_sc;           /* m x K: the list handed to pruning */
+} ap_insert_trace;
+int ap_insert_documents(const ap_index *old, const ap_corpus *enlarged, int32_t beam, const ap_insert_trace *trace,
+                        void *stream, ap_index **out);
+
+/* What the construction keeps for later insertions (any pointer may be NULL):
+ * pruned lists n x degree, detour-sorted lists n x knn_k, per-path lists
+ * 3 x n x sp_len and their scores. */
+int ap_export_build_state(const ap_index *index, int32_t *se, int32_t *sorted_ids, int32_t *sp_ids, float *sp_sc,
+                          void *stream);
+
 void ap_free_index(ap_index *index);
 const char *ap_last_error(void); /* host string, thread-local */
 

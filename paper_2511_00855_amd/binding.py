@@ -41,6 +41,11 @@ class _Queries(C.Structure):
                 ("sp_val", C.c_void_p), ("tx_indptr", C.c_void_p), ("tx_idx", C.c_void_p), ("tx_cnt", C.c_void_p)]
 
 
+class _InsertTrace(C.Structure):
+    _fields_ = [(f, C.c_void_p) for f in ("cand1_ids", "cand1_sc", "cand2_ids", "cand2_sc", "cand2_sp_ids", "cand2_sp_sc",
+                                          "merged_ids", "merged_sc", "knn_ids", "knn_sc")]
+
+
 class _SearchParams(C.Structure):
     _fields_ = [("k", C.c_int32), ("beam", C.c_int32), ("max_iters", C.c_int32), ("search_width", C.c_int32)]
 
@@ -206,6 +211,44 @@ class Index:
             rc = lib().ap_search_batch(self._h, C.byref(qs), _ptr(w), C.byref(sp), _ptr(ids), _ptr(sc), _stream())
         _check(rc, "ap_search_batch")
         return ids, sc
+
+    def insert(self, enlarged: DeviceVecs, beam: int = 0, trace: bool = False):
+        """A new index over `enlarged` (this index's documents first, unchanged, then the new ones); see
+        ap_insert_documents.  With trace=True also returns the intermediates of the new documents."""
+        n0, n1 = self.docs.n, enlarged.n
+        m, K, P = n1 - n0, self.params.knn_k, self.params.sp_len or -(-self.params.degree // 6)
+        dev = self.device
+        tr = None
+        bufs = {}
+        if trace:
+            def mk(shape, dt):
+                return torch.empty(shape, dtype=dt, device=dev)
+            bufs = dict(cand1_ids=mk((m, K), torch.int32), cand1_sc=mk((m, K), torch.float32),
+                        cand2_ids=mk((m, K), torch.int32), cand2_sc=mk((m, K), torch.float32),
+                        cand2_sp_ids=mk((3, m, P), torch.int32), cand2_sp_sc=mk((3, m, P), torch.float32),
+                        merged_ids=mk((m, K), torch.int32), merged_sc=mk((m, K), torch.float32),
+                        knn_ids=mk((m, K), torch.int32), knn_sc=mk((m, K), torch.float32))
+            tr = _InsertTrace(*[_ptr(bufs[f]) for f, _ in _InsertTrace._fields_])
+        h = C.c_void_p()
+        cs = enlarged.corpus_struct()
+        with torch.cuda.device(dev):
+            rc = lib().ap_insert_documents(self._h, C.byref(cs), C.c_int32(beam), C.byref(tr) if tr is not None else None,
+                                           _stream(), C.byref(h))
+        _check(rc, "ap_insert_documents")
+        ix = Index(h, enlarged, self.params)
+        return (ix, bufs) if trace else ix
+
+    def export_build_state(self):
+        n, R, K = self.docs.n, self.params.degree, self.params.knn_k
+        P = self.params.sp_len or -(-R // 6)
+        dev = self.device
+        se = torch.empty((n, R), dtype=torch.int32, device=dev)
+        srt = torch.empty((n, K), dtype=torch.int32, device=dev)
+        spi = torch.empty((3, n, P), dtype=torch.int32, device=dev)
+        sps = torch.empty((3, n, P), dtype=torch.float32, device=dev)
+        with torch.cuda.device(dev):
+            _check(lib().ap_export_build_state(self._h, _ptr(se), _ptr(srt), _ptr(spi), _ptr(sps), _stream()), "ap_export_build_state")
+        return se, srt, spi, sps
 
     def mark_deleted(self, ids, restore: bool = False):
         """Marks documents deleted (or restores them): searched through, left out of the answers."""

@@ -146,7 +146,7 @@ static hipError_t seed_exact_rows(const ap_index *ix, const int32_t *node_ids, i
 // per-row candidate buffer, from which the exact top-K is selected.  A row
 // whose buffer overflows (not observed; the buffer holds twice the expected
 // number of candidates) is redone by the exact path.
-static int seed_knn_impl(const ap_index *ix, const int32_t *node_ids, int64_t nn, int32_t K, int32_t *out_ids,
+int ap_seed_knn_impl(const ap_index *ix, const int32_t *node_ids, int64_t nn, int32_t K, int32_t *out_ids,
                          float *out_sc, hipStream_t st) {
     const int64_t n = ix->docs.n;
     int64_t cs = std::max<int64_t>(16384, (n + 63) / 64);
@@ -226,7 +226,7 @@ extern "C" int ap_stage_seed_knn(const ap_index *ix, const int32_t *node_ids, in
     if (!node_ids) nn = ix->docs.n;
     AP_REQUIRE(nn >= 0, "nn is negative");
     if (nn == 0) return AP_OK;
-    return seed_knn_impl(ix, node_ids, nn, K, out_ids, out_scores, (hipStream_t)stream);
+    return ap_seed_knn_impl(ix, node_ids, nn, K, out_ids, out_scores, (hipStream_t)stream);
 }
 
 extern "C" int ap_stage_entry_points(const ap_index *ix, int32_t E, int32_t *out_entry, void *stream) {
@@ -372,7 +372,7 @@ extern "C" int ap_stage_refine(const ap_index *ix, int32_t K, int32_t S, int32_t
                                const int32_t *sp_ids, const float *sp_sc, const int32_t *node_ids, int64_t nn,
                                int32_t *out_ids, float *out_sc, int32_t *out_sp_ids, float *out_sp_sc, void *stream) {
     AP_REQUIRE(ix && knn_ids && sp_ids && sp_sc && out_ids && out_sc && out_sp_ids && out_sp_sc, "NULL argument");
-    AP_REQUIRE(K >= 1 && K <= 256 && S >= 1 && S <= 32 && P >= 1 && P <= 32, "need 1<=K<=256, 1<=S<=32, 1<=P<=32");
+    AP_REQUIRE(K >= 1 && K <= 256 && S >= 0 && S <= 32 && P >= 1 && P <= 32, "need 1<=K<=256, 0<=S<=32, 1<=P<=32");
     if (!node_ids) nn = ix->docs.n;
     if (nn <= 0) return AP_OK;
     const float *w = ix->params.build_w;
@@ -722,7 +722,7 @@ __global__ __launch_bounds__(256) void k_detour_prune(ApVecs D, const float *__r
     for (int32_t i = lane; i < K; i += 64) if (o_flag) o_flag[xo * K + i] = flag[i];
 }
 
-static int prune_impl(const ap_index *ix, int32_t K, int32_t R, const int32_t *knn_ids, const float *knn_sc,
+int ap_prune_impl(const ap_index *ix, int32_t K, int32_t R, const int32_t *knn_ids, const float *knn_sc,
                       const int32_t *node_ids, int64_t nn, float *pm_out, int32_t *count, int32_t *sorted_ids,
                       int32_t *se, int32_t *ke, int32_t *ke_count, int32_t *flag, hipStream_t st) {
     const int64_t per = (int64_t)K * K;
@@ -769,7 +769,7 @@ extern "C" int ap_stage_prune(const ap_index *ix, int32_t K, int32_t R, const in
     AP_REQUIRE(K >= 1 && K <= 256 && R >= 2 && R <= 128, "need 1<=K<=256, 2<=R<=128");
     if (!node_ids) nn = ix->docs.n;
     if (nn <= 0) return AP_OK;
-    return prune_impl(ix, K, R, knn_ids, knn_sc, node_ids, nn, pm, count, sorted_ids, se, ke, ke_count, flag, (hipStream_t)stream);
+    return ap_prune_impl(ix, K, R, knn_ids, knn_sc, node_ids, nn, pm, count, sorted_ids, se, ke, ke_count, flag, (hipStream_t)stream);
 }
 
 // =================================================================== S6: assembly
@@ -849,7 +849,7 @@ __global__ __launch_bounds__(256) void k_assemble(int64_t n, int32_t R, int32_t 
     for (int32_t i = lane; i < R; i += 64) out[u * R + i] = i < len ? row[i] : -1;
 }
 
-static int assemble_impl(const ap_index *ix, int32_t R, int32_t K, int32_t P, const int32_t *se, const int32_t *sorted_ids,
+int ap_assemble_impl(const ap_index *ix, int32_t R, int32_t K, int32_t P, const int32_t *se, const int32_t *sorted_ids,
                          const int32_t *sp_ids, int32_t *out_graph, hipStream_t st) {
     const int64_t n = ix->docs.n;
     const int32_t q = R / 4;
@@ -880,7 +880,7 @@ extern "C" int ap_stage_assemble(const ap_index *ix, int32_t R, int32_t K, int32
                                  const int32_t *sorted_ids, const int32_t *sp_ids, int32_t *out_graph, void *stream) {
     AP_REQUIRE(ix && se && sorted_ids && sp_ids && out_graph, "NULL argument");
     AP_REQUIRE(R >= 4 && R % 4 == 0 && R <= 128 && K >= 1 && K <= 256 && P >= 1 && P <= 32, "need R%%4==0, 4<=R<=128, 1<=K<=256, 1<=P<=32");
-    return assemble_impl(ix, R, K, P, se, sorted_ids, sp_ids, out_graph, (hipStream_t)stream);
+    return ap_assemble_impl(ix, R, K, P, se, sorted_ids, sp_ids, out_graph, (hipStream_t)stream);
 }
 
 // =================================================================== the whole build
@@ -902,6 +902,17 @@ __global__ __launch_bounds__(256) void k_rescore_lists(ApVecs D, float wd, float
         if (v >= 0) { float sd, ss, sf; ap_hybrid_wave<DT, NV>(D, qa, a, v, sd, ss, sf); s = ap_fuse(wd, ws, wf, sd, ss, sf); }
         if (lane == 0) sc[u * K + i] = s;
     }
+}
+
+// Fused scores (construction weights) of the first nn rows of existing lists.
+int ap_rescore_lists(const ap_index *ix, int64_t nn, int32_t K, const int32_t *knn, float *sc, hipStream_t st) {
+    if (nn <= 0) return AP_OK;
+    const float *w = ix->params.build_w;
+    AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim,
+                      hipLaunchKernelGGL((k_rescore_lists<DT, NV>), dim3((unsigned)nn), dim3(256), 0, st, ix->docs, w[0], w[1], w[2],
+                                         K, knn, sc));
+    AP_CHECK_HIP(hipGetLastError());
+    return AP_OK;
 }
 
 struct BuildBufs {
@@ -935,7 +946,7 @@ static int build_impl(ap_index *ix, hipStream_t st, BuildBufs &b) {
     AP_TRY(ap_dev_alloc(&b.se, (size_t)n * R));
     AP_TRY(ap_dev_alloc(&b.sorted, (size_t)n * K));
     AP_TRY(ap_alloc_graph(ix));
-    AP_TRY(seed_knn_impl(ix, nullptr, n, K, b.knn[0], b.knn_sc[0], st));
+    AP_TRY(ap_seed_knn_impl(ix, nullptr, n, K, b.knn[0], b.knn_sc[0], st));
     AP_CHECK_HIP(mark(2));
     AP_TRY(ap_fill_u32(b.spi[0], (size_t)3 * n * P, 0xffffffffu, st));          // id -1
     AP_TRY(ap_fill_u32(b.sps[0], (size_t)3 * n * P, 0xff800000u, st));          // -inf
@@ -945,17 +956,12 @@ static int build_impl(ap_index *ix, hipStream_t st, BuildBufs &b) {
                                b.knn_sc[1 - cur], b.spi[1 - cur], b.sps[1 - cur], st));
         cur = 1 - cur;
     }
-    if (p.nd_rounds == 0) {
-        AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim,
-                          hipLaunchKernelGGL((k_rescore_lists<DT, NV>), dim3((unsigned)n), dim3(256), 0, st, ix->docs,
-                                             p.build_w[0], p.build_w[1], p.build_w[2], K, b.knn[cur], b.knn_sc[cur]));
-        AP_CHECK_HIP(hipGetLastError());
-    }
+    if (p.nd_rounds == 0) AP_TRY(ap_rescore_lists(ix, n, K, b.knn[cur], b.knn_sc[cur], st));
     AP_CHECK_HIP(mark(3));
-    AP_TRY(prune_impl(ix, K, R, b.knn[cur], b.knn_sc[cur], nullptr, n, nullptr, nullptr, b.sorted, b.se, ix->kw, ix->kw_count,
+    AP_TRY(ap_prune_impl(ix, K, R, b.knn[cur], b.knn_sc[cur], nullptr, n, nullptr, nullptr, b.sorted, b.se, ix->kw, ix->kw_count,
                       nullptr, st));
     AP_CHECK_HIP(mark(4));
-    AP_TRY(assemble_impl(ix, R, K, P, b.se, b.sorted, b.spi[cur], ix->graph, st));
+    AP_TRY(ap_assemble_impl(ix, R, K, P, b.se, b.sorted, b.spi[cur], ix->graph, st));
     AP_TRY(ap_stage_entry_points(ix, p.n_entry, ix->entry, st));
     AP_CHECK_HIP(mark(5));
     AP_CHECK_HIP(hipStreamSynchronize(st));
@@ -969,6 +975,9 @@ static int build_impl(ap_index *ix, hipStream_t st, BuildBufs &b) {
     ix->timings[5] = total;
     for (auto &e : ev) (void)hipEventDestroy(e);
     ix->has_graph = true;
+    // kept for later insertions
+    ix->st_se = b.se; ix->st_sorted = b.sorted; ix->st_spi = b.spi[cur]; ix->st_sps = b.sps[cur];
+    b.se = nullptr; b.sorted = nullptr; b.spi[cur] = nullptr; b.sps[cur] = nullptr;
     return AP_OK;
 }
 

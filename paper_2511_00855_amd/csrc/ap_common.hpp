@@ -85,6 +85,10 @@ struct ap_index {
     int32_t last_nq = 0;
     hipEvent_t ev_search[2] = {nullptr, nullptr};
     float timings[6] = {0, 0, 0, 0, 0, 0};
+    // owned: what the construction leaves behind for later insertions (NULL for imported graphs):
+    // pruned lists n x degree, detour-sorted lists n x knn_k, per-path lists 3 x n x sp_len with their scores
+    int32_t *st_se = nullptr, *st_sorted = nullptr, *st_spi = nullptr;
+    float *st_sps = nullptr;
 };
 
 template <typename T>
@@ -102,6 +106,20 @@ static inline int ap_dev_alloc(T **p, size_t count) {
 int ap_validate_corpus(const ap_corpus *c);
 int ap_validate_params(const ap_build_params *p);
 int ap_ingest_impl(ap_index *ix, hipStream_t st);
+int ap_alloc_graph(ap_index *ix);
+int ap_fill_u32(void *p, size_t n, uint32_t v, hipStream_t st);
+// stage bodies shared by the whole build and by insertion (ap_build.hip)
+int ap_seed_knn_impl(const ap_index *ix, const int32_t *node_ids, int64_t nn, int32_t K, int32_t *out_ids, float *out_sc,
+                     hipStream_t st);
+int ap_prune_impl(const ap_index *ix, int32_t K, int32_t R, const int32_t *knn_ids, const float *knn_sc, const int32_t *node_ids,
+                  int64_t nn, float *pm_out, int32_t *count, int32_t *sorted_ids, int32_t *se, int32_t *ke, int32_t *ke_count,
+                  int32_t *flag, hipStream_t st);
+int ap_assemble_impl(const ap_index *ix, int32_t R, int32_t K, int32_t P, const int32_t *se, const int32_t *sorted_ids,
+                     const int32_t *sp_ids, int32_t *out_graph, hipStream_t st);
+int ap_rescore_lists(const ap_index *ix, int64_t nn, int32_t K, const int32_t *knn, float *sc, hipStream_t st);
+// the plain search with an arbitrary query view and device weights (ap_search.hip)
+int ap_search_core(ap_index *ix, const ApVecs &Q, const float *w_dev, int32_t w_stride, int32_t k, int32_t beam, int32_t max_iters,
+                   int32_t width, int32_t *out_ids, float *out_scores, hipStream_t st);
 
 // ---------------------------------------------------------------- device code
 #ifdef __HIPCC__

@@ -14,7 +14,6 @@
 #include "ap_common.hpp"
 
 
-int ap_fill_u32(void *p, size_t n, uint32_t v, hipStream_t st);
 int ap_validate_queries(const ap_queries *q);
 
 struct ApSearchArgs {
@@ -433,47 +432,47 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
     }
 }
 
-// kw_terms == NULL: the plain search; otherwise the keyword-constrained one.
-static int ap_search_impl(ap_index *ix, const ap_queries *q, const float *per_query_w, const ap_search_params *p,
-                          const int32_t *kw_terms, int32_t kw_stride, uint32_t kw_flags, int32_t *out_ids, float *out_scores,
-                          void *stream) {
+// The launch itself.  Q: the queries (any view with f32 dense rows); w_dev / w_stride: device weights, one triple
+// per query (stride 3) or one for all (stride 0).  kw_terms == NULL: the plain search; otherwise the
+// keyword-constrained one.
+static int ap_search_launch(ap_index *ix, const ApVecs &Q, const float *w_dev, int32_t w_stride, int32_t k, int32_t beam,
+                            int32_t max_iters, int32_t width, const int32_t *kw_terms, int32_t kw_stride, uint32_t kw_flags,
+                            int32_t *out_ids, float *out_scores, hipStream_t st) {
     const bool kw = kw_terms != nullptr;
-    AP_REQUIRE(ix && p, "NULL argument");
+    const int32_t nq = (int32_t)Q.n;
     if (!ix->has_graph) { ap_set_error("index has no graph: build or import one first"); return AP_ESTATE; }
-    AP_TRY(ap_validate_queries(q));
-    AP_REQUIRE(q->nq == 0 || (out_ids && out_scores), "NULL output");
-    AP_REQUIRE(p->beam >= 1 && p->beam <= 4096, "beam = %d must be in [1, 4096]", p->beam);
-    AP_REQUIRE(p->k >= 1 && p->k <= p->beam, "k = %d must be in [1, beam]", p->k);
-    AP_REQUIRE(p->search_width >= 1 && p->search_width <= 8, "search_width = %d must be in [1, 8]", p->search_width);
-    AP_REQUIRE(p->max_iters >= 0, "max_iters must be >= 0");
-    if (q->nq == 0) return AP_OK;
-    hipStream_t st = (hipStream_t)stream;
+    AP_REQUIRE(nq == 0 || (out_ids && out_scores), "NULL output");
+    AP_REQUIRE(beam >= 1 && beam <= 4096, "beam = %d must be in [1, 4096]", beam);
+    AP_REQUIRE(k >= 1 && k <= beam, "k = %d must be in [1, beam]", k);
+    AP_REQUIRE(width >= 1 && width <= 8, "search_width = %d must be in [1, 8]", width);
+    AP_REQUIRE(max_iters >= 0, "max_iters must be >= 0");
+    if (nq == 0) return AP_OK;
     ApSearchArgs g;
     g.D = ix->docs;
-    g.Q = ApVecs{q->nq, ix->docs.dim, q->dense, q->sp_indptr, q->sp_idx, q->sp_val, q->tx_indptr, q->tx_idx, q->tx_cnt};
+    g.Q = Q;
     g.graph = ix->graph;
     g.entry = ix->entry;
-    g.w = per_query_w ? per_query_w : ix->w_dev;
-    g.w_stride = per_query_w ? 3 : 0;
+    g.w = w_dev;
+    g.w_stride = w_stride;
     g.R = ix->params.degree;
     g.E = ix->params.n_entry;
-    g.k = p->k; g.L = p->beam; g.max_iters = p->max_iters; g.width = p->search_width;
+    g.k = k; g.L = beam; g.max_iters = max_iters; g.width = width;
     g.KR = kw ? ix->params.degree / 2 : 0;
     g.kw_edges = ix->kw; g.kw_count = ix->kw_count; g.kw_terms = kw_terms; g.kw_stride = kw_stride;
     g.kw_all = (kw_flags & AP_KW_ALL) ? 1 : 0;
     g.kw_use_edges = (kw_flags & AP_KW_NO_EDGES) ? 0 : 1;
     g.cmax = g.E > g.width * (g.R + g.KR) ? g.E : g.width * (g.R + g.KR);
     g.words = ((size_t)ix->docs.n + 31) / 32;
-    const size_t need = g.words * (size_t)q->nq;
+    const size_t need = g.words * (size_t)nq;
     if (need > ix->visited_words) {
         if (ix->visited) { AP_CHECK_HIP(hipStreamSynchronize(st)); (void)hipFree(ix->visited); ix->visited = nullptr; ix->visited_words = 0; }
         AP_TRY(ap_dev_alloc(&ix->visited, need));
         ix->visited_words = need;
     }
-    if ((size_t)q->nq * 3 > ix->search_counts_cap) {
+    if ((size_t)nq * 3 > ix->search_counts_cap) {
         if (ix->search_counts) { AP_CHECK_HIP(hipStreamSynchronize(st)); (void)hipFree(ix->search_counts); ix->search_counts = nullptr; ix->search_counts_cap = 0; }
-        AP_TRY(ap_dev_alloc(&ix->search_counts, (size_t)q->nq * 3));
-        ix->search_counts_cap = (size_t)q->nq * 3;
+        AP_TRY(ap_dev_alloc(&ix->search_counts, (size_t)nq * 3));
+        ix->search_counts_cap = (size_t)nq * 3;
     }
     if (!ix->ev_search[0]) {
         AP_CHECK_HIP(hipEventCreate(&ix->ev_search[0]));
@@ -486,7 +485,7 @@ static int ap_search_impl(ap_index *ix, const ap_queries *q, const float *per_qu
     g.rec = ix->rec;
     g.meta = ix->meta;
     g.deleted = ix->deleted;
-    ix->last_nq = q->nq;
+    ix->last_nq = nq;
     AP_TRY(ap_fill_u32(ix->visited, need, 0u, st));
     const size_t smem = (size_t)(g.L + 3 * g.cmax + (kw ? g.cmax + g.k : 0)) * 8 + (size_t)g.cmax * (16 + 4) +
                         ((1 << AP_QSP_BITS) + (1 << AP_QTX_BITS)) * 8 + 8;
@@ -498,20 +497,35 @@ static int ap_search_impl(ap_index *ix, const ap_queries *q, const float *per_qu
             if (smem > 48 * 1024)
                 le = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_search<DT, NV, true>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-            if (le == hipSuccess) hipLaunchKernelGGL((k_search<DT, NV, true>), dim3((unsigned)q->nq), dim3(256), smem, st, g);
+            if (le == hipSuccess) hipLaunchKernelGGL((k_search<DT, NV, true>), dim3((unsigned)nq), dim3(256), smem, st, g);
         });
     } else {
         AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim, {
             if (smem > 48 * 1024)
                 le = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_search<DT, NV, false>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-            if (le == hipSuccess) hipLaunchKernelGGL((k_search<DT, NV, false>), dim3((unsigned)q->nq), dim3(256), smem, st, g);
+            if (le == hipSuccess) hipLaunchKernelGGL((k_search<DT, NV, false>), dim3((unsigned)nq), dim3(256), smem, st, g);
         });
     }
     AP_CHECK_HIP(le);
     AP_CHECK_HIP(hipGetLastError());
     AP_CHECK_HIP(hipEventRecord(ix->ev_search[1], st));
     return AP_OK;
+}
+
+int ap_search_core(ap_index *ix, const ApVecs &Q, const float *w_dev, int32_t w_stride, int32_t k, int32_t beam, int32_t max_iters,
+                   int32_t width, int32_t *out_ids, float *out_scores, hipStream_t st) {
+    return ap_search_launch(ix, Q, w_dev, w_stride, k, beam, max_iters, width, nullptr, 0, 0u, out_ids, out_scores, st);
+}
+
+static int ap_search_impl(ap_index *ix, const ap_queries *q, const float *per_query_w, const ap_search_params *p,
+                          const int32_t *kw_terms, int32_t kw_stride, uint32_t kw_flags, int32_t *out_ids, float *out_scores,
+                          void *stream) {
+    AP_REQUIRE(ix && p, "NULL argument");
+    AP_TRY(ap_validate_queries(q));
+    const ApVecs Q{q->nq, ix->docs.dim, q->dense, q->sp_indptr, q->sp_idx, q->sp_val, q->tx_indptr, q->tx_idx, q->tx_cnt};
+    return ap_search_launch(ix, Q, per_query_w ? per_query_w : ix->w_dev, per_query_w ? 3 : 0, p->k, p->beam, p->max_iters,
+                            p->search_width, kw_terms, kw_stride, kw_flags, out_ids, out_scores, (hipStream_t)stream);
 }
 
 extern "C" int ap_search_batch(ap_index *ix, const ap_queries *q, const float *per_query_w,

@@ -1,0 +1,181 @@
+"""GPU parity of the insertion of new documents (Section 4.1, updates of the hybrid index): every step of
+ap_insert_documents against the oracle fed the GPU's previous step, the way the construction stages are tested."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from paper_2511_00855_amd import binding as B
+from paper_2511_00855_amd.synth import make_workload, subset_vecset
+from parity import RTOL_F32, row_norms
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _np(*ts):
+    return [t.cpu().numpy() for t in ts]
+
+
+@pytest.fixture(scope="module", params=["f32", "bf16"])
+def grown(request):
+    bf16 = request.param == "bf16"
+    w = make_workload("tiny", seed=23, n=1200, nq=40, dim=96, bf16=bf16)
+    n0 = 1000
+    old_docs = B.DeviceVecs(subset_vecset(w.docs, np.arange(n0)), bf16=bf16)
+    all_docs = B.DeviceVecs(w.docs, bf16=bf16)
+    bp = B.build_params(16, knn_k=32, nd_rounds=2, nd_sample=8, n_entry=16)
+    old = B.Index.build(old_docs, bp)
+    _say(f"insert {request.param}: {w.docs.n - n0} documents into {n0}")
+    new, tr = old.insert(all_docs, trace=True)
+    tr = {k: v.cpu().numpy() for k, v in tr.items()}
+    D = O.encode_docs(w.docs)
+    yield w, n0, bp, old, new, tr, D, all_docs
+    new.close(); old.close()
+
+
+def test_insert_candidate_set_one_is_a_search_of_the_old_graph(grown):
+    w, n0, bp, old, new, tr, D, all_docs = grown
+    n1, K, R = w.docs.n, bp.knn_k, bp.degree
+    wv = np.array([1, 1, 1], np.float32)
+    sem_old, _, _, ent_old = _np(*old.export_graph())
+    g_pad = np.vstack([sem_old, np.full((n1 - n0, R), -1, np.int32)])
+    # S0 of the enlarged corpus: the new index's lexical weights are the oracle's
+    tx_w = new.export_ingest()[0].cpu().numpy()
+    np.testing.assert_allclose(tx_w, D.tx_val, rtol=1e-5)
+    sample = np.arange(n0, n1, 7)
+    allc = np.tile(np.arange(n1, dtype=np.int32), (len(sample), 1))
+    table = new.hybrid_scores_docs(sample.astype(np.int32), allc, wv).cpu().numpy()[:, :, 3]
+    for x, u in enumerate(sample):
+        oi, os_, _ = O.search(D, g_pad, ent_old, D, int(u), wv, K, 2 * K, score_table=table[x])
+        assert np.array_equal(tr["cand1_ids"][u - n0], oi), u
+        assert np.array_equal(tr["cand1_sc"][u - n0], os_), u
+    assert (tr["cand1_ids"] < n0).all()
+
+
+def test_insert_candidate_set_two_and_merge(grown):
+    w, n0, bp, old, new, tr, D, all_docs = grown
+    n1, K, P = w.docs.n, bp.knn_k, -(-bp.degree // 6)
+    M = n1 - n0
+    wv = np.array([1, 1, 1], np.float32)
+    Dn = O.rows_of(D, n0, n1)
+    ids, sc = O.seed_knn(Dn, np.arange(M), K)
+    spi, sps = O.empty_sp(M, P)
+    for _ in range(bp.nd_rounds):
+        ids, sc, spi, sps = O.refine_round(Dn, wv, K, bp.nd_sample, P, ids, spi, sps)
+    ids = np.where(ids >= 0, ids + n0, -1)
+    same = (tr["cand2_ids"] == ids).mean()
+    assert same > 0.99, same                      # near-ties aside, the same lists
+    assert ((tr["cand2_ids"] >= n0) | (tr["cand2_ids"] < 0)).all()
+    m = tr["cand2_ids"] == ids
+    assert np.allclose(tr["cand2_sc"][m], sc[m], rtol=1e-4, atol=1e-5)
+    spi_g = np.where(spi >= 0, spi + n0, -1)
+    assert (tr["cand2_sp_ids"] == spi_g).mean() > 0.99
+    # the merge is exact
+    for j in range(M):
+        mi, ms = O.merge_ranked(tr["cand1_ids"][j], tr["cand1_sc"][j], tr["cand2_ids"][j], tr["cand2_sc"][j], K)
+        assert np.array_equal(tr["merged_ids"][j], mi) and np.array_equal(tr["merged_sc"][j], ms), j
+    # both kinds of neighbour occur
+    assert (tr["merged_ids"] < n0).any() and (tr["merged_ids"] >= n0).any()
+
+
+def test_insert_lists_prune_and_assembly(grown):
+    w, n0, bp, old, new, tr, D, all_docs = grown
+    n1, K, R, P = w.docs.n, bp.knn_k, bp.degree, -(-bp.degree // 6)
+    M = n1 - n0
+    wv = np.array([1, 1, 1], np.float32)
+    dn = row_norms(w.docs)
+    se_o, srt_o, spi_o, sps_o = _np(*old.export_build_state())
+    se, srt, spi, sps = _np(*new.export_build_state())
+    # old documents keep their state
+    assert np.array_equal(se[:n0], se_o) and np.array_equal(srt[:n0], srt_o)
+    assert np.array_equal(spi[:, :n0], spi_o) and np.array_equal(sps[:, :n0], sps_o)
+    _, ke_o, kc_o, _ = _np(*old.export_graph())
+    sem, ke, kc, ent = _np(*new.export_graph())
+    assert np.array_equal(ke[:n0], ke_o) and np.array_equal(kc[:n0], kc_o)
+    # the list handed to pruning: the merged list scored again (same members, ranked), and the per-path lists =
+    # one oracle pass without 2-hop exploration over the GPU's merged lists and set two's per-path lists
+    knn_full = np.full((n1, K), -1, np.int32); knn_full[n0:] = tr["merged_ids"]
+    spi_in = np.full((3, n1, P), -1, np.int32); sps_in = np.full((3, n1, P), -np.inf, np.float32)
+    spi_in[:, n0:], sps_in[:, n0:] = tr["cand2_sp_ids"], tr["cand2_sp_sc"]
+    newv = np.arange(n0, n1)
+    o_ids, o_sc, o_spi, o_sps = O.refine_round(D, wv, K, 0, P, knn_full, spi_in, sps_in, node_ids=newv)
+    assert (tr["knn_ids"] == o_ids).mean() > 0.99
+    for j in range(M):
+        assert set(tr["knn_ids"][j].tolist()) == set(tr["merged_ids"][j].tolist())
+        assert (np.diff(tr["knn_sc"][j][tr["knn_ids"][j] >= 0]) <= 0).all()
+    m = tr["knn_ids"] == o_ids
+    tol = RTOL_F32 * (dn[newv][:, None] * dn.max() + np.abs(o_sc))
+    assert (np.abs(tr["knn_sc"] - o_sc)[m] <= tol[m]).all()
+    assert (spi[:, n0:] == o_spi).mean() > 0.99
+    # pruning of the new documents: the stage on the same lists gives the stored state, and the oracle replays it
+    knn_sc_full = np.full((n1, K), -np.inf, np.float32); knn_sc_full[n0:] = tr["knn_sc"]
+    knn_full[n0:] = tr["knn_ids"]
+    g = new.stage_prune(K, R, knn_full, knn_sc_full, newv.astype(np.int32))
+    pm, g_srt, g_se, g_ke, g_kc = _np(g["pm"], g["sorted_ids"], g["se"], g["ke"], g["ke_count"])
+    assert np.array_equal(g_se, se[n0:]) and np.array_equal(g_srt, srt[n0:])
+    assert np.array_equal(g_ke, ke[n0:]) and np.array_equal(g_kc, kc[n0:])
+    self_gpu = new.export_ingest()[3].cpu().numpy()
+    for j in range(0, M, 5):
+        u = n0 + j
+        r = O.prune_node(D, u, wv, R, R // 2, tr["knn_ids"][j], tr["knn_sc"][j], self_all=self_gpu, Pm=pm[j])
+        assert np.array_equal(se[u][:len(r.se)], r.se) and (se[u][len(r.se):] == -1).all(), u
+        assert np.array_equal(srt[u], r.sorted) and kc[u] == len(r.ke) and np.array_equal(ke[u][:len(r.ke)], r.ke), u
+    # assembly over all documents and the entry points: exact
+    assert np.array_equal(sem, O.assemble(n1, R, K, P, se, srt, spi))
+    assert np.array_equal(ent, O.entry_points(self_gpu, bp.n_entry))
+    gained = sum(int((sem[x] >= n0).any()) for x in range(n0))
+    assert gained > n0 // 10            # old documents point at new ones
+
+
+def test_inserted_index_searches_and_grows_again(grown):
+    w, n0, bp, old, new, tr, D, all_docs = grown
+    n1, k, L = w.docs.n, 10, 64
+    qs = B.DeviceVecs(w.queries)
+    Q = O.VS(w.queries)
+    wq = np.tile(np.float32(w.weights), (qs.n, 1))
+    sem, _, _, ent = _np(*new.export_graph())
+    ids, sc = _np(*new.search_batch(qs, k, L, wq))
+    table = new.hybrid_scores(qs, np.tile(np.arange(n1, dtype=np.int32), (qs.n, 1)), wq).cpu().numpy()[:, :, 3]
+    for qi in range(qs.n):
+        oi, os_, _ = O.search(D, sem, ent, Q, qi, wq[qi], k, L, score_table=table[qi])
+        assert np.array_equal(ids[qi], oi) and np.array_equal(sc[qi], os_), qi
+    gt = new.bruteforce_topk(qs, k, wq)[0].cpu().numpy()
+    rebuilt = B.Index.build(all_docs, bp)
+    ids_r = rebuilt.search_batch(qs, k, L, wq)[0].cpu().numpy()
+    rec = lambda a: float(np.mean([len(set(x) & set(y)) / k for x, y in zip(a, gt)]))
+    _say(f"  recall@10 beam {L}: inserted {rec(ids):.3f}, rebuilt {rec(ids_r):.3f}; "
+         f"new documents among the answers: {(ids >= n0).mean():.3f} (share of the corpus {1 - n0 / n1:.3f})")
+    assert rec(ids) > rec(ids_r) - 0.08
+    rebuilt.close()
+    # a second insertion on top of the first: 1200 documents = the first 1100 of the new index's corpus + 100
+    first = B.Index.build(B.DeviceVecs(subset_vecset(w.docs, np.arange(900)), bf16=all_docs.dtype != 0), bp)
+    second = first.insert(B.DeviceVecs(subset_vecset(w.docs, np.arange(1050)), bf16=all_docs.dtype != 0))
+    third = second.insert(all_docs)
+    se3, srt3, spi3, _ = _np(*third.export_build_state())
+    sem3 = third.export_graph()[0].cpu().numpy()
+    assert np.array_equal(sem3, O.assemble(n1, bp.degree, bp.knn_k, -(-bp.degree // 6), se3, srt3, spi3))
+    for u in range(0, n1, 13):
+        row = sem3[u][sem3[u] >= 0]
+        assert u not in row and len(set(row.tolist())) == len(row) and (row < n1).all()
+    ids3 = third.search_batch(qs, k, L, wq)[0].cpu().numpy()
+    _say(f"  after two insertions (900 + 150 + 150): recall@10 {rec(ids3):.3f}")
+    assert rec(ids3) > rec(ids_r) - 0.12
+    for x in (first, second, third):
+        x.close()
+
+
+def test_insert_argument_checks(grown):
+    w, n0, bp, old, new, tr, D, all_docs = grown
+    sem, ke, kc, ent = old.export_graph()
+    imported = B.Index.import_graph(old.docs, bp, sem, ent, ke, kc)
+    with pytest.raises(RuntimeError, match="construction state"):
+        imported.insert(all_docs)
+    imported.close()
+    with pytest.raises(RuntimeError, match="nothing to insert"):
+        new.insert(old.docs)
+    with pytest.raises(RuntimeError):
+        old.insert(all_docs, beam=5000)
