@@ -83,6 +83,45 @@ def keyword_leg(args, w, ix, qs, wq, k, chosen):
     return dict(required_terms="1-2 of each query's own text tokens, any-match", sampled_queries=len(sample), sweep=out)
 
 
+def insert_leg(args, w, bp, docs, qs, wq, k, gt, sweep, build_s, bf16):
+    """Insertion (Section 4.1, updates): an index over the first (1-f) of the corpus receives the last f; the
+    updated index is searched at the beams of the main sweep, against the same ground truth as the rebuild."""
+    import numpy as np
+    import torch
+    from paper_2511_00855_amd import binding as B
+    from paper_2511_00855_amd.synth import subset_vecset
+    n = w.docs.n
+    out = []
+    for f in sorted({args.insert, args.insert / 2, args.insert / 4}):
+        n0 = n - int(round(n * f))
+        old_docs = B.DeviceVecs(subset_vecset(w.docs, np.arange(n0)), "cuda:0", bf16=bf16)
+        old = B.Index.build(old_docs, bp)
+        torch.cuda.synchronize()
+        t0 = time.time()
+        new = old.insert(docs)
+        torch.cuda.synchronize()
+        dt = time.time() - t0
+        st = dict(zip(("ingest", "candidate_sets", "merge_and_rescore", "prune", "assemble", "total"), new.build_timings().values()))
+        rows = []
+        for sw in sweep:
+            beam = sw["beam"]
+            new.search_batch(qs, k, beam, wq)
+            torch.cuda.synchronize()
+            t1 = time.time()
+            ids, _ = new.search_batch(qs, k, beam, wq)
+            torch.cuda.synchronize()
+            qps = qs.n / (time.time() - t1)
+            rows.append(dict(beam=beam, recall=round(recall_at_k(ids.cpu().numpy(), gt), 4), qps=round(qps, 1),
+                             rebuilt_recall=sw["recall"], rebuilt_qps=sw["qps"]))
+        out.append(dict(fraction=f, inserted=n - n0, seconds=round(dt, 3), rebuild_seconds=round(build_s, 3),
+                        share_of_rebuild=round(dt / build_s, 3), stages_s={a: round(b, 3) for a, b in st.items()}, search=rows))
+        log(f"[bench] insert {100 * f:.0f}% ({n - n0} docs): {dt:.3f}s = {100 * dt / build_s:.1f}% of the rebuild ({build_s:.2f}s); "
+            + "; ".join(f"beam {r['beam']}: recall {r['recall']:.4f} (rebuilt {r['rebuilt_recall']:.4f})" for r in rows[:1] + rows[-1:]))
+        new.close(); old.close()
+        del old_docs
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -100,6 +139,9 @@ def main():
                          "counters and for the streaming rate of this box) always runs three times")
     ap.add_argument("--prune-mode", type=int, default=0,
                     help="0 = joint RNG-IP pruning (the method), 1 = RNG only, 2 = IP only (the paper's pruning ablation)")
+    ap.add_argument("--insert", type=float, default=0.0,
+                    help="also measure insertion: build on the first (1-f) of the corpus, insert the last f "
+                         "(e.g. 0.2), report seconds next to the rebuild and recall/QPS of the updated index")
     ap.add_argument("--keywords", action="store_true",
                     help="also measure the keyword-constrained search (1-2 required terms per query, with and "
                          "without keyword edges) and add a keyword_search object to the line")
@@ -240,6 +282,7 @@ def main():
                     traffic_GBps=None if traffic is None else round(traffic / (k_ms * 1e-3) / 1e9, 1))
 
     kw_report = keyword_leg(args, w, ix, qs, wq, k, chosen) if args.keywords else None
+    ins_report = insert_leg(args, w, bp, docs, qs, wq, k, gt, sweep, build_s, bf16) if args.insert > 0 else None
 
     # ---- CPU baseline: the oracle as it stands, one thread, bounded sample of the same searches
     cpu = None
@@ -278,6 +321,8 @@ def main():
     }
     if kw_report is not None:
         line["keyword_search"] = kw_report
+    if ins_report is not None:
+        line["insertion"] = ins_report
     print(json.dumps(line), flush=True)
     ix.close()
 

@@ -3,6 +3,7 @@
 #include <stdarg.h>
 #include <string.h>
 #include <new>
+#include <algorithm>
 #include "ap_common.hpp"
 
 static thread_local char g_err[512] = "";
@@ -266,6 +267,39 @@ int ap_alloc_graph(ap_index *ix) {
     return AP_OK;
 }
 
+// An imported graph comes from outside: every id must be -1 (padding) or a document, every keyword count within
+// its row.  The searches rely on it.
+__global__ void k_count_bad_ids(const int32_t *__restrict__ ids, size_t count, int64_t n, int32_t lo, int32_t *__restrict__ bad) {
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x)
+        if (ids[i] < lo || ids[i] >= n) atomicAdd(bad, 1);
+}
+
+static int ap_check_imported(ap_index *ix, hipStream_t st) {
+    const size_t n = (size_t)ix->corpus.n, R = (size_t)ix->params.degree;
+    int32_t *bad = nullptr;
+    AP_TRY(ap_dev_alloc(&bad, 1));
+    int rc = ap_fill_u32(bad, 1, 0u, st);
+    auto count = [&](const int32_t *p, size_t cnt, int64_t hi, int32_t lo) {
+        const unsigned blocks = (unsigned)std::min<size_t>((cnt + 255) / 256, 8192);
+        hipLaunchKernelGGL(k_count_bad_ids, dim3(blocks ? blocks : 1), dim3(256), 0, st, p, cnt, hi, lo, bad);
+    };
+    if (rc == AP_OK) {
+        count(ix->graph, n * R, (int64_t)n, -1);
+        count(ix->kw, n * (R / 2), (int64_t)n, -1);
+        count(ix->kw_count, n, (int64_t)(R / 2) + 1, 0);
+        count(ix->entry, (size_t)ix->params.n_entry, (int64_t)n, -1);
+    }
+    int32_t h = 0;
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipMemcpyAsync(&h, bad, sizeof(h), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    (void)hipFree(bad);
+    if (rc != AP_OK) return rc;
+    AP_CHECK_HIP(e);
+    AP_REQUIRE(h == 0, "the imported graph holds %d ids or counts out of range", h);
+    return AP_OK;
+}
+
 extern "C" int ap_import_graph(const ap_corpus *corpus, const ap_build_params *params, const int32_t *semantic,
                                const int32_t *keyword, const int32_t *kw_count, const int32_t *entry, void *stream,
                                ap_index **out) {
@@ -281,9 +315,13 @@ extern "C" int ap_import_graph(const ap_corpus *corpus, const ap_build_params *p
     hipError_t e = hipMemcpyAsync(ix->graph, semantic, n * R * sizeof(int32_t), hipMemcpyDeviceToDevice, st);
     if (e == hipSuccess && keyword) e = hipMemcpyAsync(ix->kw, keyword, n * (R / 2) * sizeof(int32_t), hipMemcpyDeviceToDevice, st);
     if (e == hipSuccess && kw_count) e = hipMemcpyAsync(ix->kw_count, kw_count, n * sizeof(int32_t), hipMemcpyDeviceToDevice, st);
-    if (e == hipSuccess && !kw_count) { rc = ap_fill_u32(ix->kw_count, n, 0, st); }
+    if (e == hipSuccess && !kw_count) {
+        rc = ap_fill_u32(ix->kw_count, n, 0, st);
+        if (rc == AP_OK) rc = ap_fill_u32(ix->kw, n * (R / 2), 0xffffffffu, st);
+    }
     if (e == hipSuccess) e = hipMemcpyAsync(ix->entry, entry, (size_t)params->n_entry * sizeof(int32_t), hipMemcpyDeviceToDevice, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e == hipSuccess && rc == AP_OK) rc = ap_check_imported(ix, st);
     if (e != hipSuccess || rc != AP_OK) {
         if (e != hipSuccess) { ap_set_error("graph import copy failed: %s", hipGetErrorString(e)); rc = AP_EHIP; }
         ap_free_index(ix); *out = nullptr; return rc;

@@ -117,9 +117,10 @@ int ap_prune_impl(const ap_index *ix, int32_t K, int32_t R, const int32_t *knn_i
 int ap_assemble_impl(const ap_index *ix, int32_t R, int32_t K, int32_t P, const int32_t *se, const int32_t *sorted_ids,
                      const int32_t *sp_ids, int32_t *out_graph, hipStream_t st);
 int ap_rescore_lists(const ap_index *ix, int64_t nn, int32_t K, const int32_t *knn, float *sc, hipStream_t st);
-// the plain search with an arbitrary query view and device weights (ap_search.hip)
+// the plain search with an arbitrary query view and device weights (ap_search.hip); big_tables: the queries are as long
+// as documents, give them larger look-up tables
 int ap_search_core(ap_index *ix, const ApVecs &Q, const float *w_dev, int32_t w_stride, int32_t k, int32_t beam, int32_t max_iters,
-                   int32_t width, int32_t *out_ids, float *out_scores, hipStream_t st);
+                   int32_t width, bool big_tables, int32_t *out_ids, float *out_scores, hipStream_t st);
 
 // ---------------------------------------------------------------- device code
 #ifdef __HIPCC__

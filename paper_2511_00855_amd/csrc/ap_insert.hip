@@ -120,7 +120,7 @@ static int insert_impl(const ap_index *old, ap_index *nx, int32_t beam, const ap
             const ApVecs Q{qn, nx->docs.dim, static_cast<const char *>(qd) + (size_t)q0 * nx->docs.dim * 4,
                            nx->docs.sp_indptr + n0 + q0, nx->docs.sp_idx, nx->docs.sp_val,
                            nx->docs.tx_indptr + n0 + q0, nx->docs.tx_idx, nx->docs.tx_val};
-            AP_TRY(ap_search_core(nx, Q, w_dev, 0, K, L, 0, 1, c1_ids + q0 * K, c1_sc + q0 * K, st));
+            AP_TRY(ap_search_core(nx, Q, w_dev, 0, K, L, 0, 1, true, c1_ids + q0 * K, c1_sc + q0 * K, st));
         }
     }
     nx->has_graph = false;

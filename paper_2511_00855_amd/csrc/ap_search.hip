@@ -73,14 +73,19 @@ __device__ __forceinline__ int32_t ap_rank_in(const uint64_t *keys, int32_t n, u
 #ifndef AP_SEARCH_G
 #define AP_SEARCH_G 1
 #endif
-#define AP_QSP_BITS 8    // query sparse table: 256 slots, lists up to 64 entries
-#define AP_QTX_BITS 7    // query lexical table: 128 slots, lists up to 32 entries
+// Sizes of the query's two look-up tables (at most a quarter full).  Ordinary queries: 256 + 128 slots (lists up to
+// 64 / 32 entries).  Queries that are documents (insertion): 1024 + 512 slots (lists up to 256 / 128 entries).
+template <bool BIG> struct ApQTab {
+    static constexpr int SPB = BIG ? 10 : 8;
+    static constexpr int TXB = BIG ? 9 : 7;
+    static constexpr int SLOTS = (1 << SPB) + (1 << TXB);
+};
 
 // KW: each candidate's lexical terms are also compared with the query's required
 // terms (s_kw[0..n_kw)); the key of a candidate that satisfies the constraint
 // carries the "satisfies" flag, and its dense row may only be skipped when the
 // bound also rules out the secondary pool (full, and its last score above the bound).
-template <int DT, int NV, bool TAB, bool KW>
+template <int DT, int NV, bool TAB, bool KW, bool BIG>
 __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const uint2 *rec, const float *qa, const uint64_t *qtab,
                                                        const ApLists &a, float wd, float ws, float wf, float qnorm, bool pool_full,
                                                        float worst_score, const int32_t *cand, const uint4 *s_meta, int32_t c,
@@ -115,9 +120,9 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const ui
             const int32_t v = __builtin_amdgcn_readfirstlane(cand[i]);
             float ss, sf;
             if (TAB)
-                ap_rec_reduce_tab<2, 1, AP_QSP_BITS, AP_QTX_BITS>(r[gi], (const AP_LDS uint64_t *)qtab,
-                                                                  (const AP_LDS uint64_t *)(qtab + (1 << AP_QSP_BITS)), spn[gi], txn[gi],
-                                                                  si[gi], sv[gi], ti[gi], tv[gi], ss, sf);
+                ap_rec_reduce_tab<2, 1, ApQTab<BIG>::SPB, ApQTab<BIG>::TXB>(r[gi], (const AP_LDS uint64_t *)qtab,
+                                                                            (const AP_LDS uint64_t *)(qtab + (1 << ApQTab<BIG>::SPB)),
+                                                                            spn[gi], txn[gi], si[gi], sv[gi], ti[gi], tv[gi], ss, sf);
             else
                 ap_rec_reduce_lists<2, 1>(r[gi], a, spn[gi], txn[gi], si[gi], sv[gi], ti[gi], tv[gi], ss, sf);
             // upper bound of the fused score, with slack far above fp32 rounding
@@ -152,9 +157,9 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const ui
 #ifndef AP_SEARCH_WAVES_PER_SIMD
 #define AP_SEARCH_WAVES_PER_SIMD 7
 #endif
-template <int DT, int NV, bool KW>
+template <int DT, int NV, bool KW, bool BIG>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_WAVES_PER_SIMD, 8))) void k_search(ApSearchArgs g) {
-    extern __shared__ uint64_t smem64[];
+    extern __shared__ __attribute__((aligned(16))) uint64_t smem64[];   // 16-byte aligned: the descriptors are read as uint4
     uint64_t *cur = smem64;                  // the pool: L keys, best first
     uint64_t *newk = cur + g.L;              // keys of this iteration's candidates, unordered
     uint64_t *newS = newk + g.cmax;          // the same, sorted
@@ -163,7 +168,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
     uint64_t *kwc = xk + (KW ? g.cmax : 0);  // KW: the secondary pool, k keys, best first
     uint64_t *qtab = kwc + (KW ? g.k : 0);   // the query's two look-up tables
     // descriptors of this iteration's candidates (16-byte aligned: an odd number of words before them shifts them by one)
-    uint4 *s_meta = reinterpret_cast<uint4 *>(qtab + (1 << AP_QSP_BITS) + (1 << AP_QTX_BITS) +
+    constexpr int SPB = ApQTab<BIG>::SPB, TXB = ApQTab<BIG>::TXB;
+    uint4 *s_meta = reinterpret_cast<uint4 *>(qtab + ApQTab<BIG>::SLOTS +
                                               ((g.L + 3 * g.cmax + (KW ? g.cmax + g.k : 0)) & 1));
     int32_t *cand = reinterpret_cast<int32_t *>(s_meta + g.cmax);
     __shared__ int32_t s_cnt, s_np, s_skip, s_xn, s_kc;
@@ -179,14 +185,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
         a.sp_n = (int32_t)(g.Q.sp_indptr[q + 1] - sb); a.tx_n = (int32_t)(g.Q.tx_indptr[q + 1] - tb);
         a.sp_idx = g.Q.sp_idx + sb; a.sp_val = g.Q.sp_val + sb; a.tx_idx = g.Q.tx_idx + tb; a.tx_val = g.Q.tx_val + tb;
     }
-    const bool use_tab = a.sp_n <= (1 << AP_QSP_BITS) / 4 && a.tx_n <= (1 << AP_QTX_BITS) / 4;   // uniform
+    const bool use_tab = a.sp_n <= (1 << SPB) / 4 && a.tx_n <= (1 << TXB) / 4;   // uniform
     if (use_tab) {
-        for (int i = threadIdx.x; i < (1 << AP_QSP_BITS) + (1 << AP_QTX_BITS); i += blockDim.x) qtab[i] = 0xffffffffull;
+        for (int i = threadIdx.x; i < ApQTab<BIG>::SLOTS; i += blockDim.x) qtab[i] = 0xffffffffull;
         __syncthreads();
-        const int t = threadIdx.x;
-        if (t < a.sp_n) ap_table_put(qtab, 1 << AP_QSP_BITS, AP_QSP_BITS, a.sp_idx[t], __float_as_int(a.sp_val[t]));
-        else if (t < a.sp_n + a.tx_n)
-            ap_table_put(qtab + (1 << AP_QSP_BITS), 1 << AP_QTX_BITS, AP_QTX_BITS, a.tx_idx[t - a.sp_n], __float_as_int(a.tx_val[t - a.sp_n]));
+        if (BIG) {
+            for (int t = threadIdx.x; t < a.sp_n + a.tx_n; t += blockDim.x) {
+                if (t < a.sp_n) ap_table_put(qtab, 1 << SPB, SPB, a.sp_idx[t], __float_as_int(a.sp_val[t]));
+                else ap_table_put(qtab + (1 << SPB), 1 << TXB, TXB, a.tx_idx[t - a.sp_n], __float_as_int(a.tx_val[t - a.sp_n]));
+            }
+        } else {   // at most 64 + 32 entries: one pass
+            const int t = threadIdx.x;
+            if (t < a.sp_n) ap_table_put(qtab, 1 << SPB, SPB, a.sp_idx[t], __float_as_int(a.sp_val[t]));
+            else if (t < a.sp_n + a.tx_n)
+                ap_table_put(qtab + (1 << SPB), 1 << TXB, TXB, a.tx_idx[t - a.sp_n], __float_as_int(a.tx_val[t - a.sp_n]));
+        }
     }
     float qa[NV * ApDense<DT>::EPC];
     ap_load_aside<DT, NV, AP_F32>(g.Q.dense, q, g.D.dim, qa);
@@ -215,7 +228,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
     // S7: entry points
     for (int32_t i = threadIdx.x; i < g.E; i += blockDim.x) {
         const int32_t v = g.entry[i];
-        if (v >= 0 && v < (int32_t)g.D.n) {
+        if (v >= 0) {
             const uint32_t bit = 1u << (v & 31);
             const uint32_t old = atomicOr(&vis[v >> 5], bit);
             if (!(old & bit)) cand[atomicAdd(&s_cnt, 1)] = v;
@@ -235,10 +248,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
         const bool second_full = kw_on && s_kc == g.k;   // s_kc and kwc were last written before the previous barriers
         const float second_worst = second_full ? ap_key_score(kwc[g.k - 1]) : 0.f;
         if (use_tab)
-            nskipped += ap_score_candidates<DT, NV, true, KW>(g.D, g.rec, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score, cand,
+            nskipped += ap_score_candidates<DT, NV, true, KW, BIG>(g.D, g.rec, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score, cand,
                                                               s_meta, c, newk, s_kw, n_kw, g.kw_all != 0, second_full, second_worst);
         else
-            nskipped += ap_score_candidates<DT, NV, false, KW>(g.D, g.rec, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score, cand,
+            nskipped += ap_score_candidates<DT, NV, false, KW, BIG>(g.D, g.rec, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score, cand,
                                                                s_meta, c, newk, s_kw, n_kw, g.kw_all != 0, second_full, second_worst);
         __syncthreads();
         // sort the new keys by ranking them among themselves; only those that
@@ -363,11 +376,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
         // constraint also brings its keyword edges
         const int32_t per = g.R + (KW ? g.KR : 0);
         for (int32_t i = threadIdx.x; i < np * per; i += blockDim.x) {
-            const int32_t pi = i / per, sl = i % per, u = s_par[pi];
-            int32_t v = -1;
-            if (sl < g.R) v = g.graph[(int64_t)u * g.R + sl];
-            else if (KW && g.kw_use_edges && s_psat[pi] && sl - g.R < g.kw_count[u]) v = g.kw_edges[(int64_t)u * g.KR + (sl - g.R)];
-            if (v >= 0 && v < (int32_t)g.D.n) {   // an imported graph is not trusted to hold valid ids
+            int32_t v;
+            if (KW) {
+                const int32_t pi = i / per, sl = i % per, u = s_par[pi];
+                v = -1;
+                if (sl < g.R) v = g.graph[(int64_t)u * g.R + sl];
+                else if (g.kw_use_edges && s_psat[pi] && sl - g.R < g.kw_count[u]) v = g.kw_edges[(int64_t)u * g.KR + (sl - g.R)];
+            } else {
+                v = g.graph[(int64_t)s_par[i / g.R] * g.R + (i % g.R)];
+            }
+            if (v >= 0) {
                 const uint32_t bit = 1u << (v & 31);
                 const uint32_t old = atomicOr(&vis[v >> 5], bit);
                 if (!(old & bit)) cand[atomicAdd(&s_cnt, 1)] = v;
@@ -406,8 +424,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
         }
         return;
     }
-    if (g.deleted) {
-        // mark-deletion: the best k pool entries that are not deleted
+    if (KW && g.deleted) {
+        // mark-deletion (searches on an index with deletions always run this instantiation): the best k live pool entries
         if (wave == 0) {
             int32_t o = 0;
             for (int32_t base = 0; base < len && o < g.k; base += 64) {
@@ -437,8 +455,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
 // keyword-constrained one.
 static int ap_search_launch(ap_index *ix, const ApVecs &Q, const float *w_dev, int32_t w_stride, int32_t k, int32_t beam,
                             int32_t max_iters, int32_t width, const int32_t *kw_terms, int32_t kw_stride, uint32_t kw_flags,
-                            int32_t *out_ids, float *out_scores, hipStream_t st) {
-    const bool kw = kw_terms != nullptr;
+                            bool big_tables, int32_t *out_ids, float *out_scores, hipStream_t st) {
+    // The keyword instantiation also serves plain searches on an index with mark-deleted documents (it carries the
+    // answer filter; without required terms it searches exactly like the plain one), so that the plain
+    // instantiation stays free of both.
+    const bool kw = kw_terms != nullptr || ix->deleted != nullptr;
     const int32_t nq = (int32_t)Q.n;
     if (!ix->has_graph) { ap_set_error("index has no graph: build or import one first"); return AP_ESTATE; }
     AP_REQUIRE(nq == 0 || (out_ids && out_scores), "NULL output");
@@ -446,7 +467,9 @@ static int ap_search_launch(ap_index *ix, const ApVecs &Q, const float *w_dev, i
     AP_REQUIRE(k >= 1 && k <= beam, "k = %d must be in [1, beam]", k);
     AP_REQUIRE(width >= 1 && width <= 8, "search_width = %d must be in [1, 8]", width);
     AP_REQUIRE(max_iters >= 0, "max_iters must be >= 0");
+    AP_REQUIRE(!kw || ix->docs.n < (1ll << 29), "keyword search and searches on an index with deletions need n < 2^29");
     if (nq == 0) return AP_OK;
+    if (!kw_terms) kw_stride = 0;
     ApSearchArgs g;
     g.D = ix->docs;
     g.Q = Q;
@@ -457,7 +480,7 @@ static int ap_search_launch(ap_index *ix, const ApVecs &Q, const float *w_dev, i
     g.R = ix->params.degree;
     g.E = ix->params.n_entry;
     g.k = k; g.L = beam; g.max_iters = max_iters; g.width = width;
-    g.KR = kw ? ix->params.degree / 2 : 0;
+    g.KR = kw_terms ? ix->params.degree / 2 : 0;
     g.kw_edges = ix->kw; g.kw_count = ix->kw_count; g.kw_terms = kw_terms; g.kw_stride = kw_stride;
     g.kw_all = (kw_flags & AP_KW_ALL) ? 1 : 0;
     g.kw_use_edges = (kw_flags & AP_KW_NO_EDGES) ? 0 : 1;
@@ -488,25 +511,21 @@ static int ap_search_launch(ap_index *ix, const ApVecs &Q, const float *w_dev, i
     ix->last_nq = nq;
     AP_TRY(ap_fill_u32(ix->visited, need, 0u, st));
     const size_t smem = (size_t)(g.L + 3 * g.cmax + (kw ? g.cmax + g.k : 0)) * 8 + (size_t)g.cmax * (16 + 4) +
-                        ((1 << AP_QSP_BITS) + (1 << AP_QTX_BITS)) * 8 + 8;
+                        (size_t)(big_tables ? ApQTab<true>::SLOTS : ApQTab<false>::SLOTS) * 8 + 8;
     AP_CHECK_HIP(hipEventRecord(ix->ev_search[0], st));
     AP_REQUIRE(smem <= 160 * 1024, "beam and search_width need %zu bytes of LDS (limit 160 KiB)", smem);
     hipError_t le = hipSuccess;
-    if (kw) {
-        AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim, {
-            if (smem > 48 * 1024)
-                le = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_search<DT, NV, true>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-            if (le == hipSuccess) hipLaunchKernelGGL((k_search<DT, NV, true>), dim3((unsigned)nq), dim3(256), smem, st, g);
-        });
-    } else {
-        AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim, {
-            if (smem > 48 * 1024)
-                le = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_search<DT, NV, false>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-            if (le == hipSuccess) hipLaunchKernelGGL((k_search<DT, NV, false>), dim3((unsigned)nq), dim3(256), smem, st, g);
-        });
-    }
+#define AP_LAUNCH_SEARCH(KWF, BIGF)                                                                                          \
+    AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim, {                                                                              \
+        if (smem > 48 * 1024)                                                                                                 \
+            le = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_search<DT, NV, KWF, BIGF>),                            \
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);                                  \
+        if (le == hipSuccess) hipLaunchKernelGGL((k_search<DT, NV, KWF, BIGF>), dim3((unsigned)nq), dim3(256), smem, st, g); \
+    })
+    if (kw) AP_LAUNCH_SEARCH(true, false);
+    else if (big_tables) AP_LAUNCH_SEARCH(false, true);
+    else AP_LAUNCH_SEARCH(false, false);
+#undef AP_LAUNCH_SEARCH
     AP_CHECK_HIP(le);
     AP_CHECK_HIP(hipGetLastError());
     AP_CHECK_HIP(hipEventRecord(ix->ev_search[1], st));
@@ -514,8 +533,8 @@ static int ap_search_launch(ap_index *ix, const ApVecs &Q, const float *w_dev, i
 }
 
 int ap_search_core(ap_index *ix, const ApVecs &Q, const float *w_dev, int32_t w_stride, int32_t k, int32_t beam, int32_t max_iters,
-                   int32_t width, int32_t *out_ids, float *out_scores, hipStream_t st) {
-    return ap_search_launch(ix, Q, w_dev, w_stride, k, beam, max_iters, width, nullptr, 0, 0u, out_ids, out_scores, st);
+                   int32_t width, bool big_tables, int32_t *out_ids, float *out_scores, hipStream_t st) {
+    return ap_search_launch(ix, Q, w_dev, w_stride, k, beam, max_iters, width, nullptr, 0, 0u, big_tables, out_ids, out_scores, st);
 }
 
 static int ap_search_impl(ap_index *ix, const ap_queries *q, const float *per_query_w, const ap_search_params *p,
@@ -525,7 +544,7 @@ static int ap_search_impl(ap_index *ix, const ap_queries *q, const float *per_qu
     AP_TRY(ap_validate_queries(q));
     const ApVecs Q{q->nq, ix->docs.dim, q->dense, q->sp_indptr, q->sp_idx, q->sp_val, q->tx_indptr, q->tx_idx, q->tx_cnt};
     return ap_search_launch(ix, Q, per_query_w ? per_query_w : ix->w_dev, per_query_w ? 3 : 0, p->k, p->beam, p->max_iters,
-                            p->search_width, kw_terms, kw_stride, kw_flags, out_ids, out_scores, (hipStream_t)stream);
+                            p->search_width, kw_terms, kw_stride, kw_flags, false, out_ids, out_scores, (hipStream_t)stream);
 }
 
 extern "C" int ap_search_batch(ap_index *ix, const ap_queries *q, const float *per_query_w,

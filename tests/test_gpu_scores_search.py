@@ -179,3 +179,17 @@ def test_search_sparse_graph_missing_results():
         assert np.array_equal(ids[qi], oi) and np.array_equal(sc[qi], os_)
         assert set(ids[qi][:4]) == {0, 1, 2, 3} and (ids[qi][4:] == -1).all() and np.isneginf(sc[qi][4:]).all()
     ix.close()
+    # an imported graph is checked once: ids beyond the corpus, ids below -1, keyword counts beyond the row
+    bp = B.build_params(R, knn_k=8, n_entry=4)
+    for bad in ("edge", "negative", "entry", "kw_count", "kw_edge"):
+        g2, e2 = graph.copy(), entry.copy()
+        kw = np.full((N, R // 2), -1, np.int32); kc = np.zeros(N, np.int32)
+        if bad == "edge": g2[5, 1] = N
+        if bad == "negative": g2[7, 0] = -2
+        if bad == "entry": e2[1] = N + 3
+        if bad == "kw_count": kc[9] = R // 2 + 1
+        if bad == "kw_edge": kw[3, 0] = N; kc[3] = 1
+        with pytest.raises(RuntimeError, match="out of range"):
+            B.Index.import_graph(docs, bp, g2, e2, kw, kc)
+    with pytest.raises(RuntimeError, match="come together"):
+        B.Index.import_graph(docs, bp, graph, entry, np.full((N, R // 2), -1, np.int32), None)
