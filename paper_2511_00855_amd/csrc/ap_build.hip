@@ -408,189 +408,100 @@ __global__ __launch_bounds__(256) void k_gram_dense(const void *dense, int32_t d
     });
 }
 
-// Sparse and lexical parts, and the fusion.  The 32 column documents' lists
-// of a block sit in LDS; the row document's lists are turned into two small
-// open-addressing tables (term -> weight), so that looking a column entry up
-// costs about one LDS probe instead of a binary search.  The matrix is
-// symmetric: P[i][j] is computed once, for i >= j, and mirrored.  A lane's
-// partial sum is w_s*ps + w_f*pf, so one wave reduction per pair suffices.
-#define AP_CB 32
-#define AP_CB_ENTRIES 5632
-#define AP_SP_SLOTS 1024    // sparse table slots (row lists up to 256 entries: at most a quarter full)
-#define AP_SP_BITS 10
-#define AP_TX_SLOTS 512     // lexical table slots (row lists up to 128 entries)
-#define AP_TX_BITS 9
+// Sparse and lexical parts of the neighbourhood similarities, and the fusion with the dense part: sorted lists are
+// merged, one lane per pair.
+// A 256-thread block takes a 16 x 16 tile of one neighbourhood's matrix (tiles on or below the diagonal; the matrix is
+// symmetric and mirrored on output).  The packed records of the tile's 16 row and 16 column documents (sparse
+// entries then lexical entries, ascending term ids) are copied to LDS, and thread (r, c) walks the two sorted lists
+// of its pair with two cursors: about |a| + |b| steps, one 8-byte LDS read per step, products added in ascending
+// term order.  Every lane works on a pair of its own, so an instruction serves 64 pairs; a wave-per-pair look-up
+// scheme spends most of its instructions on terms the other list does not hold.
+#define AP_GT 16                 // tile edge
+#define AP_GT_ENTRIES 6144       // LDS budget of a tile: 32 records of ~165 entries; a tile that needs more reads global memory
 
-#define AP_GRAM_THREADS 512
-#define AP_GRAM_WAVES 8
-#define AP_GC 4     // columns per wave per row: AP_GRAM_WAVES * AP_GC == AP_CB
+// Straight-line body: every lane of the wave runs the same instructions until the last lane's lists are used up; a
+// lane that is done keeps re-reading its last entries and adds nothing.
+template <typename P>
+__device__ __forceinline__ float ap_merge_dot(P a, int32_t na, P b, int32_t nb) {
+    float acc = 0.f;
+    bool live = na > 0 && nb > 0;
+    int32_t pa = 0, pb = 0;
+    uint64_t ea = live ? a[0] : 0ull, eb = live ? b[0] : 1ull;
+    while (__any(live)) {
+        const uint32_t ta = (uint32_t)ea, tb = (uint32_t)eb;
+        const float prod = __uint_as_float((uint32_t)(ea >> 32)) * __uint_as_float((uint32_t)(eb >> 32));
+        acc = (live && ta == tb) ? acc + prod : acc;
+        pa += (live && ta <= tb) ? 1 : 0;
+        pb += (live && tb <= ta) ? 1 : 0;
+        live = live && pa < na && pb < nb;
+        if (live) { ea = a[pa]; eb = b[pb]; }
+    }
+    return acc;
+}
 
-// One 512-thread block per (neighbourhood, block of 32 columns).  Rows i >= j0
-// are taken one after the other by the whole block: the row document's two
-// tables are shared (double buffered: while row i is being used, the entries
-// of row i+1 are already on their way from global memory), and wave w handles
-// columns j0+4w .. j0+4w+3 of the row, all twelve list slots in flight at once.
-template <int DT>
-__global__ __launch_bounds__(AP_GRAM_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_gram_sparse(ApVecs D, float wd, float ws, float wf, int32_t K,
-                                                                const int32_t *__restrict__ knn,
-                                                                const int32_t *__restrict__ node_ids, int64_t x0,
-                                                                float *__restrict__ pm) {
-    __shared__ int32_t b_idx[AP_CB_ENTRIES];
-    __shared__ float b_val[AP_CB_ENTRIES];
-    __shared__ int32_t b_off[2][AP_CB];           // offsets into b_idx/b_val, or -1 when the list stayed in global memory
-    __shared__ int32_t b_len[2][AP_CB];
-    __shared__ int32_t b_id[AP_CB];
-    __shared__ uint64_t t_sp[2][AP_SP_SLOTS];
-    __shared__ uint64_t t_tx[2][AP_TX_SLOTS];
-    __shared__ int32_t r_id[256], r_spn[256], r_txn[256];
-    __shared__ int64_t r_spb[256], r_txb[256];
+__global__ __launch_bounds__(256) void k_gram_merge(const uint2 *__restrict__ rec, const uint4 *__restrict__ meta, float wd, float ws,
+                                                    float wf, int32_t K, const int32_t *__restrict__ knn,
+                                                    const int32_t *__restrict__ node_ids, int64_t x0, float *__restrict__ pm) {
+    __shared__ uint64_t ent[AP_GT_ENTRIES];
+    __shared__ int32_t d_id[2 * AP_GT], d_off[2 * AP_GT], d_sn[2 * AP_GT], d_tn[2 * AP_GT];
+    __shared__ uint32_t d_first[2 * AP_GT];
+    __shared__ int32_t s_total;
     const int64_t x = blockIdx.y;
     const int64_t u = node_ids ? (int64_t)node_ids[x0 + x] : x0 + x;
-    const int32_t j0 = blockIdx.x * AP_CB;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    // layout of the column lists: lane 2c+part of wave 0 owns list `part` of column c
-    if (wave == 0) {
-        const int c = lane >> 1, part = lane & 1;
-        const int32_t v = j0 + c < K ? knn[u * K + j0 + c] : -1;
-        int32_t len = 0;
-        if (v >= 0) len = (int32_t)(part == 0 ? D.sp_indptr[v + 1] - D.sp_indptr[v] : D.tx_indptr[v + 1] - D.tx_indptr[v]);
-        int32_t incl = len;
+    // tile number -> (row block I, column block J), J <= I
+    int32_t I = 0, rem = (int32_t)blockIdx.x;
+    while (rem > I) { rem -= I + 1; I++; }
+    const int32_t J = rem;
+    const int tid = threadIdx.x, lane = tid & 63;
+    if (tid < 64) {   // slots 0..15: row documents, 16..31: column documents
+        int32_t id = -1, sn = 0, tn = 0;
+        uint32_t first = 0;
+        if (lane < 2 * AP_GT) {
+            const int32_t pos = (lane < AP_GT ? I * AP_GT + lane : J * AP_GT + lane - AP_GT);
+            if (pos < K) id = knn[u * K + pos];
+            if (id >= 0) { const uint4 m = meta[id]; first = m.x; sn = (int32_t)(m.y & 0xffffu); tn = (int32_t)(m.y >> 16); }
+        }
+        int32_t incl = sn + tn;
         for (int o = 1; o < 64; o <<= 1) {
             const int32_t up = __shfl_up(incl, o, 64);
             if (lane >= o) incl += up;
         }
-        if (part == 0) b_id[c] = v;
-        b_len[part][c] = len;
-        b_off[part][c] = incl <= AP_CB_ENTRIES ? incl - len : -1;
-    }
-    // where the row documents' lists are (rows j0 .. K-1)
-    for (int32_t i = j0 + tid; i < K; i += AP_GRAM_THREADS) {
-        const int32_t a = knn[u * K + i];
-        r_id[i] = a;
-        if (a >= 0) {
-            const int64_t sb = D.sp_indptr[a], tb = D.tx_indptr[a];
-            r_spb[i] = sb; r_spn[i] = (int32_t)(D.sp_indptr[a + 1] - sb);
-            r_txb[i] = tb; r_txn[i] = (int32_t)(D.tx_indptr[a + 1] - tb);
-        } else { r_spb[i] = 0; r_spn[i] = 0; r_txb[i] = 0; r_txn[i] = 0; }
+        if (lane < 2 * AP_GT) { d_id[lane] = id; d_off[lane] = incl - (sn + tn); d_sn[lane] = sn; d_tn[lane] = tn; d_first[lane] = first; }
+        if (lane == 2 * AP_GT - 1) s_total = incl;
     }
     __syncthreads();
-    for (int c = 0; c < AP_CB; c++) {
-        const int32_t v = b_id[c];
-        if (v < 0) continue;
-        for (int part = 0; part < 2; part++) {
-            const int32_t off = b_off[part][c], len = b_len[part][c];
-            if (off < 0) continue;
-            const int64_t g0 = part == 0 ? D.sp_indptr[v] : D.tx_indptr[v];
-            const int32_t *gi = part == 0 ? D.sp_idx : D.tx_idx;
-            const float *gv = part == 0 ? D.sp_val : D.tx_val;
-            for (int32_t e = tid; e < len; e += AP_GRAM_THREADS) { b_idx[off + e] = gi[g0 + e]; b_val[off + e] = gv[g0 + e]; }
+    const bool in_lds = s_total <= AP_GT_ENTRIES;   // uniform
+    const uint64_t *grec = reinterpret_cast<const uint64_t *>(rec);
+    if (in_lds) {
+        for (int d = 0; d < 2 * AP_GT; d++) {
+            const int32_t len = d_sn[d] + d_tn[d], off = d_off[d];
+            const uint64_t *src = grec + d_first[d];
+            for (int32_t e = tid; e < len; e += 256) ent[off + e] = src[e];
         }
+        __syncthreads();
     }
-    // a row whose lists fit the tables is "tabled": thread t holds entry t of the row (sparse entries first)
-    auto row_tabled = [&](int32_t i) { return r_id[i] >= 0 && r_spn[i] <= AP_SP_SLOTS / 4 && r_txn[i] <= AP_TX_SLOTS / 4; };
-    auto fetch = [&](int32_t i, int32_t &t, int32_t &vb, int &which) {
-        which = -1;
-        if (i >= K || !row_tabled(i)) return;
-        const int32_t sn = r_spn[i], tn = r_txn[i];
-        if (tid < sn) { t = D.sp_idx[r_spb[i] + tid]; vb = __float_as_int(D.sp_val[r_spb[i] + tid]); which = 0; }
-        else if (tid < sn + tn) { t = D.tx_idx[r_txb[i] + tid - sn]; vb = __float_as_int(D.tx_val[r_txb[i] + tid - sn]); which = 1; }
-    };
-    auto clear = [&](int buf) {
-        for (int s2 = tid; s2 < AP_SP_SLOTS; s2 += AP_GRAM_THREADS) t_sp[buf][s2] = 0xffffffffull;
-        for (int s2 = tid; s2 < AP_TX_SLOTS; s2 += AP_GRAM_THREADS) t_tx[buf][s2] = 0xffffffffull;
-    };
-    int32_t pf_t = 0, pf_v = 0; int pf_which;
-    clear(0);
-    fetch(j0, pf_t, pf_v, pf_which);
-    __syncthreads();
-    if (pf_which == 0) ap_table_put(t_sp[0], AP_SP_SLOTS, AP_SP_BITS, pf_t, pf_v);
-    else if (pf_which == 1) ap_table_put(t_tx[0], AP_TX_SLOTS, AP_TX_BITS, pf_t, pf_v);
-    __syncthreads();
+    const int r = tid / AP_GT, c = tid % AP_GT;
+    const int32_t i = I * AP_GT + r, j = J * AP_GT + c;
+    if (i >= K || j >= K || j > i) return;
     float *out = pm + x * (int64_t)K * K;
-    const AP_LDS int32_t *lb_idx = (const AP_LDS int32_t *)b_idx;
-    const AP_LDS float *lb_val = (const AP_LDS float *)b_val;
-    for (int32_t i = j0; i < K; i++) {
-        const int cur = (i - j0) & 1, nxt = cur ^ 1;
-        fetch(i + 1, pf_t, pf_v, pf_which);          // next row's entries: in flight during this row's work
-        clear(nxt);
-        const int32_t a = r_id[i];
-        const bool tabled = row_tabled(i);
-        const int32_t clast = (i - j0 < AP_CB - 1 ? i - j0 : AP_CB - 1) < K - 1 - j0 ? (i - j0 < AP_CB - 1 ? i - j0 : AP_CB - 1) : K - 1 - j0;
-        const int c0 = wave * AP_GC;
-        if (c0 <= clast) {
-            const float g_mine = (lane < AP_GC && c0 + lane <= clast) ? out[(int64_t)i * K + j0 + c0 + lane] : 0.f;
-            bool fast = tabled;
-#pragma unroll
-            for (int gq = 0; gq < AP_GC; gq++)
-                if (c0 + gq <= clast) fast = fast && b_id[c0 + gq] >= 0 && b_off[0][c0 + gq] >= 0 && b_off[1][c0 + gq] >= 0;
-            float pr[AP_GC];
-            if (fast) {
-                const AP_LDS uint64_t *tsp = (const AP_LDS uint64_t *)t_sp[cur];
-                const AP_LDS uint64_t *ttx = (const AP_LDS uint64_t *)t_tx[cur];
-                int32_t term[3 * AP_GC];
-                float bval[3 * AP_GC], aval[3 * AP_GC];
-#pragma unroll
-                for (int gq = 0; gq < AP_GC; gq++) {
-                    const int c = c0 + gq <= clast ? c0 + gq : clast;
-                    const int32_t so = b_off[0][c], sn = c0 + gq <= clast ? b_len[0][c] : 0;
-                    const int32_t to = b_off[1][c], tn = c0 + gq <= clast ? b_len[1][c] : 0;
-                    // look-ups 0..2GC-1 use the sparse table, 2GC..3GC-1 the lexical one
-                    term[2 * gq] = lane < sn ? lb_idx[so + lane] : -1;             bval[2 * gq] = lane < sn ? lb_val[so + lane] : 0.f;
-                    term[2 * gq + 1] = lane + 64 < sn ? lb_idx[so + 64 + lane] : -1; bval[2 * gq + 1] = lane + 64 < sn ? lb_val[so + 64 + lane] : 0.f;
-                    term[2 * AP_GC + gq] = lane < tn ? lb_idx[to + lane] : -1;      bval[2 * AP_GC + gq] = lane < tn ? lb_val[to + lane] : 0.f;
-                }
-                ap_table_get_many<3 * AP_GC, 2 * AP_GC, AP_SP_BITS, AP_TX_BITS>(tsp, ttx, term, aval);
-#pragma unroll
-                for (int gq = 0; gq < AP_GC; gq++) {
-                    const int c = c0 + gq <= clast ? c0 + gq : clast;
-                    const int32_t so = b_off[0][c], sn = c0 + gq <= clast ? b_len[0][c] : 0;
-                    const int32_t to = b_off[1][c], tn = c0 + gq <= clast ? b_len[1][c] : 0;
-                    float qs = fmaf(aval[2 * gq + 1], bval[2 * gq + 1], aval[2 * gq] * bval[2 * gq]);
-                    for (int32_t e = 128 + lane; e < sn; e += 64) qs = fmaf(ap_table_get(tsp, AP_SP_SLOTS, AP_SP_BITS, lb_idx[so + e]), lb_val[so + e], qs);
-                    float qt = aval[2 * AP_GC + gq] * bval[2 * AP_GC + gq];
-                    for (int32_t e = 64 + lane; e < tn; e += 64) qt = fmaf(ap_table_get(ttx, AP_TX_SLOTS, AP_TX_BITS, lb_idx[to + e]), lb_val[to + e], qt);
-                    pr[gq] = fmaf(wf, qt, ws * qs);
-                }
-            } else {
-                // a list that did not fit (column list not in LDS, or row list too long for the tables): plain search
-#pragma unroll
-                for (int gq = 0; gq < AP_GC; gq++) {
-                    pr[gq] = 0.f;
-                    const int c = c0 + gq;
-                    if (c > clast || a < 0 || b_id[c] < 0) continue;
-                    const int32_t b = b_id[c];
-                    float q2[2];
-                    for (int part = 0; part < 2; part++) {
-                        const int32_t off = b_off[part][c], len = b_len[part][c];
-                        const int32_t *bi; const float *bv; int64_t beg;
-                        if (off >= 0) { bi = b_idx; bv = b_val; beg = off; }
-                        else { bi = part == 0 ? D.sp_idx : D.tx_idx; bv = part == 0 ? D.sp_val : D.tx_val; beg = part == 0 ? D.sp_indptr[b] : D.tx_indptr[b]; }
-                        q2[part] = ap_sparse_partial(part == 0 ? D.sp_idx + r_spb[i] : D.tx_idx + r_txb[i],
-                                                     part == 0 ? D.sp_val + r_spb[i] : D.tx_val + r_txb[i],
-                                                     part == 0 ? r_spn[i] : r_txn[i], bi, bv, beg, beg + len, lane);
-                    }
-                    pr[gq] = fmaf(wf, q2[1], ws * q2[0]);
-                }
-            }
-            float my_val = 0.f;
-#pragma unroll
-            for (int gq = 0; gq < AP_GC; gq++) {
-                const int c = c0 + gq;
-                if (c > clast) continue;
-                float val = -INFINITY;
-                if (a >= 0 && b_id[c] >= 0) val = fmaf(wd, __shfl(g_mine, gq, 64), ap_wave_sum(pr[gq]));
-                if (lane == gq) my_val = val;
-            }
-            if (lane < AP_GC && c0 + lane <= clast) {
-                out[(int64_t)i * K + j0 + c0 + lane] = my_val;
-                out[(int64_t)(j0 + c0 + lane) * K + i] = my_val;
-            }
+    const int32_t a = d_id[r], b = d_id[AP_GT + c];
+    float val = -INFINITY;
+    if (a >= 0 && b >= 0) {
+        float qs, qt;
+        if (in_lds) {
+            const AP_LDS uint64_t *la = (const AP_LDS uint64_t *)ent + d_off[r];
+            const AP_LDS uint64_t *lb = (const AP_LDS uint64_t *)ent + d_off[AP_GT + c];
+            qs = ap_merge_dot(la, d_sn[r], lb, d_sn[AP_GT + c]);
+            qt = ap_merge_dot(la + d_sn[r], d_tn[r], lb + d_sn[AP_GT + c], d_tn[AP_GT + c]);
+        } else {
+            const uint64_t *ga = grec + d_first[r], *gb = grec + d_first[AP_GT + c];
+            qs = ap_merge_dot(ga, d_sn[r], gb, d_sn[AP_GT + c]);
+            qt = ap_merge_dot(ga + d_sn[r], d_tn[r], gb + d_sn[AP_GT + c], d_tn[AP_GT + c]);
         }
-        __syncthreads();     // table `nxt` is clear and nobody reads table `cur` any more
-        if (pf_which == 0) ap_table_put(t_sp[nxt], AP_SP_SLOTS, AP_SP_BITS, pf_t, pf_v);
-        else if (pf_which == 1) ap_table_put(t_tx[nxt], AP_TX_SLOTS, AP_TX_BITS, pf_t, pf_v);
-        __syncthreads();     // table `nxt` holds row i+1
+        val = fmaf(wd, out[(int64_t)i * K + j], fmaf(wf, qt, ws * qs));
     }
+    out[(int64_t)i * K + j] = val;
+    out[(int64_t)j * K + i] = val;
 }
 
 // =================================================================== S4 + S5: detour sort, IP prune, keyword flags
@@ -744,11 +655,9 @@ int ap_prune_impl(const ap_index *ix, int32_t K, int32_t R, const int32_t *knn_i
                 hipLaunchKernelGGL(k_gram_dense<AP_BF16>, g1, dim3(256), 0, st, ix->docs.dense, ix->docs.dim, K, knn_ids, node_ids, x0 + y0, pm + y0 * per);
             e = hipGetLastError();
             if (e != hipSuccess) break;
-            dim3 g2((unsigned)((K + AP_CB - 1) / AP_CB), (unsigned)yn);
-            if (ix->dtype == AP_F32)
-                hipLaunchKernelGGL(k_gram_sparse<AP_F32>, g2, dim3(AP_GRAM_THREADS), 0, st, ix->docs, w[0], w[1], w[2], K, knn_ids, node_ids, x0 + y0, pm + y0 * per);
-            else
-                hipLaunchKernelGGL(k_gram_sparse<AP_BF16>, g2, dim3(AP_GRAM_THREADS), 0, st, ix->docs, w[0], w[1], w[2], K, knn_ids, node_ids, x0 + y0, pm + y0 * per);
+            const int32_t tb = (K + AP_GT - 1) / AP_GT;
+            dim3 g2((unsigned)(tb * (tb + 1) / 2), (unsigned)yn);
+            hipLaunchKernelGGL(k_gram_merge, g2, dim3(256), 0, st, ix->rec, ix->meta, w[0], w[1], w[2], K, knn_ids, node_ids, x0 + y0, pm + y0 * per);
             e = hipGetLastError();
         }
         if (e != hipSuccess) break;

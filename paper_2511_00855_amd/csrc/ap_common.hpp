@@ -303,13 +303,6 @@ __device__ __forceinline__ void ap_table_put(uint64_t *tab, int slots, int bits,
     }
 }
 
-// 32-bit indexed global load: base + zero-extended 32-bit byte offset (the
-// index must stay below 2^30 elements of 4 bytes).
-template <typename T>
-__device__ __forceinline__ T ap_ld32(const T *base, uint32_t index) {
-    return *reinterpret_cast<const T *>(reinterpret_cast<const char *>(base) + (uint32_t)(index * (uint32_t)sizeof(T)));
-}
-
 // Partial inner product of an ascending list held by the a side with the
 // b side's list [beg, end) in global memory: lane l takes entries
 // beg+l, beg+l+64, ... of b and searches a (Section 4.1, Step 1; on the search
@@ -375,61 +368,6 @@ __device__ __forceinline__ void ap_lists_load(const ApVecs &B, int64_t spb, int3
         ti[k] = e < txn ? B.tx_idx[txb + e] : -1;
         tv[k] = e < txn ? B.tx_val[txb + e] : 0.f;
     }
-}
-
-// The same loads with 32-bit element offsets (lists stored below 2^30 entries).
-template <int SS, int TS>
-__device__ __forceinline__ void ap_lists_load32(const ApVecs &B, uint32_t spb, int32_t spn, uint32_t txb, int32_t txn,
-                                                int32_t *si, float *sv, int32_t *ti, float *tv) {
-    const int lane = threadIdx.x & 63;
-#pragma unroll
-    for (int k = 0; k < SS; k++) {
-        const int32_t e = k * 64 + lane;
-        si[k] = e < spn ? ap_ld32(B.sp_idx, spb + (uint32_t)e) : -1;
-        sv[k] = e < spn ? ap_ld32(B.sp_val, spb + (uint32_t)e) : 0.f;
-    }
-#pragma unroll
-    for (int k = 0; k < TS; k++) {
-        const int32_t e = k * 64 + lane;
-        ti[k] = e < txn ? ap_ld32(B.tx_idx, txb + (uint32_t)e) : -1;
-        tv[k] = e < txn ? ap_ld32(B.tx_val, txb + (uint32_t)e) : 0.f;
-    }
-}
-
-// Sparse and lexical sums with the a side's lists held as look-up tables
-// (2^SPB and 2^TXB slots).  Same per-lane accumulation order as
-// ap_lists_reduce: an absent term adds exactly 0.
-template <int SS, int TS, int SPB, int TXB>
-__device__ __forceinline__ void ap_lists_reduce_tab(const ApVecs &B, const AP_LDS uint64_t *tsp, const AP_LDS uint64_t *ttx,
-                                                    uint32_t spb, int32_t spn, uint32_t txb, int32_t txn, const int32_t *si,
-                                                    const float *sv, const int32_t *ti, const float *tv, float &ss, float &sf) {
-    const int lane = threadIdx.x & 63;
-    int32_t term[SS + TS];
-    float av[SS + TS];
-#pragma unroll
-    for (int k = 0; k < SS; k++) term[k] = si[k];
-#pragma unroll
-    for (int k = 0; k < TS; k++) term[SS + k] = ti[k];
-    ap_table_get_many<SS + TS, SS, SPB, TXB>(tsp, ttx, term, av);
-    float ps = 0.f, pf = 0.f;
-#pragma unroll
-    for (int k = 0; k < SS; k++) ps = fmaf(av[k], sv[k], ps);
-    for (int32_t e0 = SS * 64; e0 < spn; e0 += 64) {
-        const int32_t e = e0 + lane;
-        const int32_t t = e < spn ? ap_ld32(B.sp_idx, spb + (uint32_t)e) : -1;
-        const float x = e < spn ? ap_ld32(B.sp_val, spb + (uint32_t)e) : 0.f;
-        ps = fmaf(t >= 0 ? ap_table_get(tsp, 1 << SPB, SPB, t) : 0.f, x, ps);
-    }
-#pragma unroll
-    for (int k = 0; k < TS; k++) pf = fmaf(av[SS + k], tv[k], pf);
-    for (int32_t e0 = TS * 64; e0 < txn; e0 += 64) {
-        const int32_t e = e0 + lane;
-        const int32_t t = e < txn ? ap_ld32(B.tx_idx, txb + (uint32_t)e) : -1;
-        const float x = e < txn ? ap_ld32(B.tx_val, txb + (uint32_t)e) : 0.f;
-        pf = fmaf(t >= 0 ? ap_table_get(ttx, 1 << TXB, TXB, t) : 0.f, x, pf);
-    }
-    ss = ap_wave_sum(ps);
-    sf = ap_wave_sum(pf);
 }
 
 // ---- packed document records (search side) -------------------------------
