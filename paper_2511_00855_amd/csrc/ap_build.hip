@@ -281,8 +281,11 @@ __device__ __forceinline__ uint64_t ap_block_max(uint64_t v, uint64_t *red /* 8 
     return b;
 }
 
+#define AP_RT_SPB 10   // look-up tables of the node's own lists: 1024 + 512 slots, at most a quarter full
+#define AP_RT_TXB 9
 template <int DT, int NV>
-__global__ __launch_bounds__(512) void k_refine(ApVecs D, float wd, float ws, float wf, int32_t K, int32_t S, int32_t P,
+__global__ __launch_bounds__(512) void k_refine(ApVecs D, const uint2 *__restrict__ rec, const uint4 *__restrict__ meta, float wd,
+                                                float ws, float wf, int32_t K, int32_t S, int32_t P,
                                                 const int32_t *__restrict__ knn, const int32_t *__restrict__ sp_ids,
                                                 const float *__restrict__ sp_sc, const int32_t *__restrict__ node_ids,
                                                 int64_t nn, int32_t *__restrict__ out_ids, float *__restrict__ out_sc,
@@ -295,6 +298,7 @@ __global__ __launch_bounds__(512) void k_refine(ApVecs D, float wd, float ws, fl
     __shared__ float l_sp_val[AP_A_CAP], l_tx_val[AP_A_CAP];
     __shared__ uint64_t oldk[32];
     __shared__ uint64_t red[8];
+    __shared__ uint64_t qtab[(1 << AP_RT_SPB) + (1 << AP_RT_TXB)];
     __shared__ int32_t s_cnt, s_nold;
     const int64_t x = blockIdx.x;
     const int64_t u = node_ids ? (int64_t)node_ids[x] : x;
@@ -303,8 +307,17 @@ __global__ __launch_bounds__(512) void k_refine(ApVecs D, float wd, float ws, fl
     float qa[NV * ApDense<DT>::EPC];
     ap_load_aside<DT, NV, DT>(D.dense, u, D.dim, qa);
     for (int i = threadIdx.x; i < AP_HT; i += blockDim.x) ht[i] = -1;
+    // the node's own lists as look-up tables (the usual case); longer lists are searched where they lie
+    const bool use_tab = a.sp_n <= (1 << AP_RT_SPB) / 4 && a.tx_n <= (1 << AP_RT_TXB) / 4;   // uniform
+    if (use_tab) for (int i = threadIdx.x; i < (1 << AP_RT_SPB) + (1 << AP_RT_TXB); i += blockDim.x) qtab[i] = 0xffffffffull;
     if (threadIdx.x == 0) s_cnt = 0;
     __syncthreads();
+    if (use_tab) {
+        for (int t = threadIdx.x; t < a.sp_n + a.tx_n; t += blockDim.x) {
+            if (t < a.sp_n) ap_table_put(qtab, 1 << AP_RT_SPB, AP_RT_SPB, a.sp_idx[t], __float_as_int(a.sp_val[t]));
+            else ap_table_put(qtab + (1 << AP_RT_SPB), 1 << AP_RT_TXB, AP_RT_TXB, a.tx_idx[t - a.sp_n], __float_as_int(a.tx_val[t - a.sp_n]));
+        }
+    }
     // candidates: own list, and the first S neighbours of the first S neighbours
     const int32_t sl = S < K ? S : K;
     const int32_t slots = K + sl * sl;
@@ -323,7 +336,20 @@ __global__ __launch_bounds__(512) void k_refine(ApVecs D, float wd, float ws, fl
     for (int32_t i = wave; i < cnt; i += (int32_t)(blockDim.x >> 6)) {
         const int32_t v = cand[i];
         float sd, ss, sf;
-        ap_hybrid_wave<DT, NV>(D, qa, a, v, sd, ss, sf);
+        if (use_tab) {
+            const uint4 m = meta[v];
+            const uint2 *r = rec + __builtin_amdgcn_readfirstlane(m.x);
+            const int32_t spn = __builtin_amdgcn_readfirstlane((int32_t)(m.y & 0xffffu));
+            const int32_t txn = __builtin_amdgcn_readfirstlane((int32_t)(m.y >> 16));
+            int32_t si[2], ti[1];
+            float sv[2], tv[1];
+            ap_rec_load<2, 1>(r, spn, txn, si, sv, ti, tv);
+            sd = ap_dense_dot<DT, NV>(D, qa, v);
+            ap_rec_reduce_tab<2, 1, AP_RT_SPB, AP_RT_TXB>(r, (const AP_LDS uint64_t *)qtab, (const AP_LDS uint64_t *)(qtab + (1 << AP_RT_SPB)),
+                                                          spn, txn, si, sv, ti, tv, ss, sf);
+        } else {
+            ap_hybrid_wave<DT, NV>(D, qa, a, v, sd, ss, sf);
+        }
         if (lane == 0) {
             keys[i] = ap_make_key(ap_fuse(wd, ws, wf, sd, ss, sf), v, 1u);
             comp[0][i] = sd; comp[1][i] = ss; comp[2][i] = sf;
@@ -378,7 +404,7 @@ extern "C" int ap_stage_refine(const ap_index *ix, int32_t K, int32_t S, int32_t
     const float *w = ix->params.build_w;
     AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim,
                       hipLaunchKernelGGL((k_refine<DT, NV>), dim3((unsigned)nn), dim3(512), 0, (hipStream_t)stream, ix->docs,
-                                         w[0], w[1], w[2], K, S, P, knn_ids, sp_ids, sp_sc, node_ids, nn, out_ids, out_sc,
+                                         ix->rec, ix->meta, w[0], w[1], w[2], K, S, P, knn_ids, sp_ids, sp_sc, node_ids, nn, out_ids, out_sc,
                                          out_sp_ids, out_sp_sc));
     AP_CHECK_HIP(hipGetLastError());
     return AP_OK;
