@@ -15,13 +15,32 @@ int ap_alloc_graph(ap_index *ix);
 
 // =================================================================== S2: seed
 // scores[r][j] = <dense[node r], dense[j]> for a slab of rows and all columns.
+// Tile order of the seed products.  Workgroups are handed to the 8 XCDs round-robin by their linear id, and every XCD
+// has an L2 of its own: workgroup b runs on XCD b % 8 and is the (b / 8)-th of that XCD.  Each XCD gets a contiguous
+// band of row tiles and walks it column tile by column tile, so the band's rows stay in that XCD's L2 and a column
+// tile is fetched once per XCD instead of once per row tile.  Returns false for the padding workgroups of a band that
+// is shorter than the others.
+#define AP_XCDS 8
+__device__ __forceinline__ bool ap_seed_tile(int64_t row_tiles, int64_t &rt, int64_t &ct) {
+    const int64_t band = (row_tiles + AP_XCDS - 1) / AP_XCDS;
+    const int64_t xcd = blockIdx.x % AP_XCDS, idx = blockIdx.x / AP_XCDS;
+    rt = xcd * band + idx % band;
+    ct = idx / band;
+    return rt < row_tiles;
+}
+static inline unsigned ap_seed_grid(int64_t row_tiles, int64_t col_tiles) {
+    return (unsigned)(AP_XCDS * ((row_tiles + AP_XCDS - 1) / AP_XCDS) * col_tiles);
+}
+
 template <int DT>
 __global__ __launch_bounds__(256) void k_seed_scores(const void *dense, int32_t dim, int64_t n, const int32_t *node_ids,
                                                      int64_t row0, int64_t nrows, int64_t col0, int64_t ncols,
                                                      float *__restrict__ scores /* nrows x ncols */) {
     __shared__ __attribute__((aligned(16))) unsigned char lds[AP_TILE_LDS_BYTES];
     __shared__ int32_t a_rows[AP_TILE], b_rows[AP_TILE];
-    const int64_t i0 = (int64_t)blockIdx.y * AP_TILE, j0 = (int64_t)blockIdx.x * AP_TILE;
+    int64_t rt, ct;
+    if (!ap_seed_tile((nrows + AP_TILE - 1) / AP_TILE, rt, ct)) return;
+    const int64_t i0 = rt * AP_TILE, j0 = ct * AP_TILE;
     if (threadIdx.x < AP_TILE) {
         const int64_t r = i0 + threadIdx.x;
         a_rows[threadIdx.x] = r < nrows ? (node_ids ? node_ids[row0 + r] : (int32_t)(row0 + r)) : -1;
@@ -47,7 +66,9 @@ __global__ __launch_bounds__(256) void k_seed_thresh(const void *dense, int32_t 
     __shared__ __attribute__((aligned(16))) unsigned char lds[AP_TILE_LDS_BYTES];
     __shared__ int32_t a_rows[AP_TILE], b_rows[AP_TILE];
     __shared__ float s_tau[AP_TILE];
-    const int64_t i0 = (int64_t)blockIdx.y * AP_TILE, j0 = (int64_t)blockIdx.x * AP_TILE;
+    int64_t rt, ct;
+    if (!ap_seed_tile((nrows + AP_TILE - 1) / AP_TILE, rt, ct)) return;
+    const int64_t i0 = rt * AP_TILE, j0 = ct * AP_TILE;
     if (threadIdx.x < AP_TILE) {
         const int64_t r = i0 + threadIdx.x;
         a_rows[threadIdx.x] = r < nrows ? (node_ids ? node_ids[row0 + r] : (int32_t)(row0 + r)) : -1;
@@ -126,7 +147,7 @@ static hipError_t seed_exact_rows(const ap_index *ix, const int32_t *node_ids, i
     hipError_t e = hipSuccess;
     for (int64_t r0 = row0; r0 < row0 + nrows && e == hipSuccess; r0 += scratch_rows) {
         const int64_t nr = std::min(scratch_rows, row0 + nrows - r0);
-        dim3 grid((unsigned)((n + AP_TILE - 1) / AP_TILE), (unsigned)((nr + AP_TILE - 1) / AP_TILE));
+        dim3 grid(ap_seed_grid((nr + AP_TILE - 1) / AP_TILE, (n + AP_TILE - 1) / AP_TILE));
         if (ix->dtype == AP_F32)
             hipLaunchKernelGGL(k_seed_scores<AP_F32>, grid, dim3(256), 0, st, ix->docs.dense, ix->docs.dim, n, node_ids, r0, nr, (int64_t)0, n, scratch);
         else
@@ -182,8 +203,8 @@ int ap_seed_knn_impl(const ap_index *ix, const int32_t *node_ids, int64_t nn, in
     if (rc == AP_OK) rc = ap_dev_alloc(&ovf, (size_t)RS + 1);
     for (int64_t row0 = 0; rc == AP_OK && row0 < nn && e == hipSuccess; row0 += RS) {
         const int64_t nrows = std::min(RS, nn - row0);
-        const unsigned ytiles = (unsigned)((nrows + AP_TILE - 1) / AP_TILE);
-        dim3 gs((unsigned)(cs / AP_TILE), ytiles), gf((unsigned)((n + AP_TILE - 1) / AP_TILE), ytiles);
+        const int64_t ytiles = (nrows + AP_TILE - 1) / AP_TILE;
+        dim3 gs(ap_seed_grid(ytiles, cs / AP_TILE)), gf(ap_seed_grid(ytiles, (n + AP_TILE - 1) / AP_TILE));
         if (ix->dtype == AP_F32)
             hipLaunchKernelGGL(k_seed_scores<AP_F32>, gs, dim3(256), 0, st, ix->docs.dense, ix->docs.dim, n, node_ids, row0, nrows, (int64_t)0, cs, scratch);
         else
