@@ -301,8 +301,27 @@ def main():
         agree = recall_at_k(out[0].cpu().numpy()[:sample], oi)
         cpu = dict(value=round(sample / dt, 2), unit="queries/s", cores=1, kind="oracle",
                    sample=f"first {sample} of {nq} queries, beam {chosen}, same GPU-built graph; "
-                          f"{int(nv.sum())} hybrid similarities in {dt:.1f}s; top-{k} overlap with GPU {agree:.3f}")
+                          f"{int(nv.sum())} hybrid similarities in {dt:.1f}s; top-{k} overlap with GPU {agree:.3f}",
+                   hybrid_dists_per_s=round(float(nv.sum()) / dt, 1))
         log(f"[bench] oracle: {sample} queries in {dt:.1f}s = {sample / dt:.1f} qps on 1 core ({os.cpu_count()} visible)")
+        # construction: the oracle's refinement round and prune stage on a few nodes, extrapolated to the corpus
+        nodes = np.linspace(0, w.docs.n - 1, 6).astype(np.int64)
+        K, P = bp.knn_k, bp.sp_len or -(-w.degree // 6)
+        knn_gpu, knn_sc_gpu = [t.cpu().numpy() for t in ix.stage_seed_knn(K)]
+        e_i, e_s = O.empty_sp(w.docs.n, P)
+        wv = np.float32([1, 1, 1])
+        t2 = time.time()
+        r_ids, r_sc, _, _ = O.refine_round(D, wv, K, bp.nd_sample, P, knn_gpu, e_i, e_s, node_ids=nodes)
+        t_ref = (time.time() - t2) / len(nodes)
+        t2 = time.time()
+        for x, u in enumerate(nodes):
+            O.prune_node(D, int(u), wv, w.degree, w.degree // 2, r_ids[x], r_sc[x])
+        t_pr = (time.time() - t2) / len(nodes)
+        est = w.docs.n * (args.rounds * t_ref + t_pr)
+        cpu["build_extrapolated_s"] = round(est, 1)
+        cpu["build_sample"] = (f"{len(nodes)} nodes: one refinement round {t_ref:.3f}s/node, neighbourhood similarities + prune "
+                               f"{t_pr:.3f}s/node; x {w.docs.n} nodes, {args.rounds} rounds, seed stage not counted (extrapolation)")
+        log(f"[bench] oracle build, extrapolated from {len(nodes)} nodes: {est:,.0f}s on 1 core (GPU {build_s:.2f}s)")
 
     line = {
         "metric": "hybrid-search QPS at recall@10=0.95", "value": round(qps, 1), "unit": "queries/s",
