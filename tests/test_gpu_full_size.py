@@ -226,3 +226,60 @@ def test_dynamic_fusion_sweep(full, wset):
     assert torch.equal(graph_before, ix.export_graph()[0])          # no rebuild happened
     assert res[1][1] >= res[0][1] - 1e-9 and res[1][1] > 0.3
     ix.set_weights(w.weights)
+
+
+def test_full_size_insertion_sampled(full):
+    """Insertion at the size bench.py --insert measures (the last 20 % of config 2 into an index over the first
+    80 %): sampled new documents are checked step by step against the oracle fed the GPU's previous step."""
+    w, docs, qs, bp, ix, D, Q = full
+    from paper_2511_00855_amd.synth import subset_vecset
+    n1 = docs.n
+    n0 = n1 - n1 // 5
+    _say(f"full size: insertion of {n1 - n0} documents into {n0}")
+    old_docs = B.DeviceVecs(subset_vecset(w.docs, np.arange(n0)))
+    old = B.Index.build(old_docs, bp)
+    t0 = time.time()
+    new, tr = old.insert(docs, trace=True)
+    torch.cuda.synchronize()
+    _say(f"  inserted in {time.time() - t0:.2f}s {new.build_timings()}")
+    tr = {k: v.cpu().numpy() for k, v in tr.items()}
+    K, R, P = bp.knn_k, bp.degree, (bp.degree + 5) // 6
+    wv = np.array([1, 1, 1], np.float32)
+    sem_old, _, _, ent_old = [t.cpu().numpy() for t in old.export_graph()]
+    g_pad = np.vstack([sem_old, np.full((n1 - n0, R), -1, np.int32)])
+    sample = np.sort(np.random.default_rng(9).choice(np.arange(n0, n1), 12, replace=False))
+    # the enlarged corpus is the whole of config 2, so the oracle's S0 of the fixture applies
+    allc = np.tile(np.arange(n1, dtype=np.int32), (len(sample), 1))
+    table = new.hybrid_scores_docs(sample.astype(np.int32), allc, wv).cpu().numpy()[:, :, 3]
+    for x, u in enumerate(sample):
+        j = u - n0
+        oi, os_, _ = O.search(D, g_pad, ent_old, D, int(u), wv, K, 2 * K, score_table=table[x])
+        assert np.array_equal(tr["cand1_ids"][j], oi) and np.array_equal(tr["cand1_sc"][j], os_), u
+        mi, ms = O.merge_ranked(tr["cand1_ids"][j], tr["cand1_sc"][j], tr["cand2_ids"][j], tr["cand2_sc"][j], K)
+        assert np.array_equal(tr["merged_ids"][j], mi) and np.array_equal(tr["merged_sc"][j], ms), u
+        assert set(tr["knn_ids"][j].tolist()) == set(mi.tolist())
+        # set two lies among the new documents and its scores are the oracle's
+        c2 = tr["cand2_ids"][j]
+        assert ((c2 >= n0) | (c2 < 0)).all()
+        ref = O.hybrid_block(D, [int(u)], D, [np.maximum(c2, 0)], wv)[0, :, 3]
+        ok = c2 >= 0
+        assert np.allclose(tr["cand2_sc"][j][ok], ref[ok], rtol=1e-4, atol=1e-5), u
+    # pruning of the sampled new documents replayed on the GPU's own neighbourhood similarities; assembly exact
+    se, srt, spi, _ = [t.cpu().numpy() for t in new.export_build_state()]
+    sem, ke, kc, ent = [t.cpu().numpy() for t in new.export_graph()]
+    knn_full = torch.full((n1, K), -1, dtype=torch.int32, device=docs.device)
+    knn_sc_full = torch.full((n1, K), -np.inf, dtype=torch.float32, device=docs.device)
+    knn_full[n0:] = torch.from_numpy(tr["knn_ids"]).to(docs.device)
+    knn_sc_full[n0:] = torch.from_numpy(tr["knn_sc"]).to(docs.device)
+    g = new.stage_prune(K, R, knn_full, knn_sc_full, sample.astype(np.int32))
+    pm = g["pm"].cpu().numpy()
+    self_gpu = new.export_ingest()[3].cpu().numpy()
+    for x, u in enumerate(sample):
+        j = u - n0
+        r = O.prune_node(D, int(u), wv, R, R // 2, tr["knn_ids"][j], tr["knn_sc"][j], self_all=self_gpu, Pm=pm[x])
+        assert np.array_equal(se[u][:len(r.se)], r.se) and np.array_equal(srt[u], r.sorted), u
+        assert kc[u] == len(r.ke) and np.array_equal(ke[u][:len(r.ke)], r.ke), u
+    rows = np.concatenate([sample, np.arange(0, n0, n0 // 40)])
+    assert np.array_equal(sem[rows], O.assemble(n1, R, K, P, se, srt, spi, node_ids=rows))
+    assert np.array_equal(ent, O.entry_points(self_gpu, bp.n_entry))
+    new.close(); old.close()
