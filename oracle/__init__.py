@@ -44,6 +44,7 @@ def lib():
         _lib.orc_sparse_ip.restype = C.c_double
         _lib.orc_search.restype = C.c_int64
         _lib.orc_search_kw.restype = C.c_int64
+        _lib.orc_search_kg.restype = C.c_int64
         _lib.orc_bm25_encode.restype = C.c_int
     return _lib
 
@@ -439,3 +440,63 @@ def insert_index(old, docs, beam=None):
                            ke_count=ke_cnt, sorted_ids=sorted_ids, graph=graph, entry=entry, params=params,
                            cand1_ids=c1_ids, cand1_scores=c1_sc, cand2_ids=c2_ids, cand2_scores=c2_sc,
                            cand2_sp_ids=spi2, cand2_sp_scores=sps2, merged_ids=merged_ids, merged_scores=merged_sc, n_old=N0)
+
+
+# ---------------------------------------------------------------- logical edges (knowledge-graph augmentation)
+def entity_nodes(n_ent, doc_ent_indptr, doc_ent):
+    """The entity-to-document mapping (Section 3.4): CSR of the documents that mention each entity, ascending."""
+    rows = [[] for _ in range(n_ent)]
+    for x in range(len(doc_ent_indptr) - 1):
+        for e in doc_ent[doc_ent_indptr[x]:doc_ent_indptr[x + 1]]:
+            rows[int(e)].append(x)
+    indptr = np.concatenate([[0], np.cumsum([len(r) for r in rows])]).astype(np.int64)
+    idx = np.array([x for r in rows for x in r], np.int32)
+    return indptr, idx
+
+
+def logical_edges(kgs, n, cap):
+    """Logical edges of every document (Section 3.4; Algorithm 1's last step): triples (s, y, t) with s an entity
+    of x, (s, t) a relation, t not an entity of x, y != x a document that mentions t; in ascending (s, t, y)
+    order, the first `cap` of them.  Returns le [n, cap, 3] (-1 padded), le_count [n] and the entity-to-document CSR."""
+    en_ip, en = entity_nodes(kgs.n_ent, kgs.doc_ent_indptr, kgs.doc_ent)
+    le = np.full((n, cap, 3), -1, np.int32); cnt = np.zeros(n, np.int32)
+    for x in range(n):
+        mine = [int(e) for e in kgs.doc_ent[kgs.doc_ent_indptr[x]:kgs.doc_ent_indptr[x + 1]]]
+        out = []
+        for s in mine:
+            for t in kgs.kg_idx[kgs.kg_indptr[s]:kgs.kg_indptr[s + 1]]:
+                t = int(t)
+                if t in mine:
+                    continue
+                for y in en[en_ip[t]:en_ip[t + 1]]:
+                    if int(y) != x:
+                        out.append((s, int(y), t))
+        out = out[:cap]                      # generated in ascending (s, t, y)
+        cnt[x] = len(out)
+        if out:
+            le[x, :len(out)] = out
+    return le, cnt, en_ip, en
+
+
+def search_kg(D: VS, graph, entry, Q: VS, qi, w, k, L, kgs, le, le_count, en_ip, en, q_ent, w_k, max_hops=2, max_iters=0,
+              score_table=None, log=False):
+    """Search with knowledge-graph augmentation for one query (Section 4.2.3); q_ent: the query's entities."""
+    graph = _c(graph, np.int32); entry = _c(entry, np.int32)
+    w = _c(w, np.float32)
+    de_ip = _c(kgs.doc_ent_indptr, np.int64); de = _c(kgs.doc_ent, np.int32)
+    kg_ip = _c(kgs.kg_indptr, np.int64); kg = _c(kgs.kg_idx, np.int32)
+    en_ip = _c(en_ip, np.int64); en = _c(en, np.int32)
+    le = _c(le, np.int32); le_count = _c(le_count, np.int32)
+    qe = _c(np.asarray(q_ent, np.int32).reshape(-1), np.int32)
+    ids = np.empty(k, np.int32); sc = np.empty(k, np.float32)
+    st = None if score_table is None else _c(score_table, np.float32)
+    cap = D.n if log else 0
+    vl = np.empty(max(cap, 1), np.int32); al = np.empty((max(cap, 1), 2), np.int32)
+    n = lib().orc_search_kg(D.ref, _p(graph), C.c_int32(graph.shape[1]), _p(entry), C.c_int32(len(entry)), Q.ref,
+                            C.c_int64(qi), _p(w), C.c_int32(k), C.c_int32(L), C.c_int32(max_iters), _p(de_ip), _p(de),
+                            _p(kg_ip), _p(kg), _p(en_ip), _p(en), _p(le), C.c_int32(le.shape[1]), _p(le_count), _p(qe),
+                            C.c_int32(len(qe)), C.c_float(w_k), C.c_int32(max_hops), _p(st), _p(ids), _p(sc),
+                            _p(vl) if log else None, _p(al) if log else None, C.c_int64(cap))
+    if log:
+        return ids, sc, vl[:n].copy(), al[:n].copy()
+    return ids, sc, int(n)

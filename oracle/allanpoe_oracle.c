@@ -677,3 +677,119 @@ int64_t orc_search_kw(const orc_vecset *D, const int32_t *graph, int32_t R, cons
     free(visited); free(pool); free(expanded); free(sat); free(second); free(all); free(parents); free(psat);
     return nscored;
 }
+
+/* ------------------------------------------------------------------ */
+/* Search with knowledge-graph augmentation (Section 4.2.3 and the entity
+ * branches of Algorithm 2), one parent per iteration.
+ *   V(x)   = entities of document x          (doc_ent_indptr / doc_ent, ascending)
+ *   KG     = undirected relations of entities (kg_indptr / kg_idx, ascending)
+ *   nodes(e) = documents that mention e       (en_indptr / en_idx, ascending)
+ *   logical edges of x: le_count[x] triples (s, y, t) in le[x*le_cap*3 ..]: s in V(x), (s,t) in KG, t not in V(x),
+ *   y mentions t.
+ * Every pool entry carries (ent, hop): the entity through which it is tied to the query's entities and the
+ * number of relations in between; ent = -1 when there is no such tie.
+ *  - With query entities, the search starts from the documents that mention them (in the order of the query's
+ *    entities, then ascending document id, at most E of them), each with hop 0 and that entity; otherwise from
+ *    the usual entry points with no entity.
+ *  - Expanding u: its semantic edges, then -- if u has an entity and u.hop < max_hops -- the targets of its
+ *    logical edges whose source is u.ent.
+ *  - A newly seen o gets ent = the smallest entity of V(o) related to u.ent (none if u has no entity or V(o) holds
+ *    no such entity); with an entity, hop = u.hop + 1 and the score is raised by w_k / hop.
+ * ann_log (optional, capacity log_cap x 2): (ent, hop) of every scored document in scoring order.               */
+static int32_t related_entity(const int64_t *de_ip, const int32_t *de, const int64_t *kg_ip, const int32_t *kg,
+                              int64_t o, int32_t eu) {
+    int64_t p, r;
+    for (p = de_ip[o]; p < de_ip[o + 1]; p++)
+        for (r = kg_ip[eu]; r < kg_ip[eu + 1]; r++)
+            if (kg[r] == de[p]) return de[p];          /* V(o) is ascending: the first hit is the smallest */
+    return -1;
+}
+
+int64_t orc_search_kg(const orc_vecset *D, const int32_t *graph, int32_t R, const int32_t *entry, int32_t E,
+                      const orc_vecset *Q, int64_t qi, const float w[3], int32_t k, int32_t L, int32_t max_iters,
+                      const int64_t *de_ip, const int32_t *de, const int64_t *kg_ip, const int32_t *kg,
+                      const int64_t *en_ip, const int32_t *en, const int32_t *le, int32_t le_cap,
+                      const int32_t *le_count, const int32_t *q_ent, int32_t n_qe, float w_k, int32_t max_hops,
+                      const float *score_table, int32_t *out_ids, float *out_scores, int32_t *visit_log,
+                      int32_t *ann_log, int64_t log_cap) {
+    int64_t N = D->n, nscored = 0;
+    unsigned char *visited = (unsigned char *)calloc((size_t)(N > 0 ? N : 1), 1);
+    scored *pool = (scored *)malloc(sizeof(scored) * (size_t)(L + 1));
+    unsigned char *expanded = (unsigned char *)malloc((size_t)(L + 1));
+    int32_t *p_ent = (int32_t *)malloc(sizeof(int32_t) * (size_t)(L + 1));
+    int32_t *p_hop = (int32_t *)malloc(sizeof(int32_t) * (size_t)(L + 1));
+    int32_t len = 0, it = 0, i, e, started = 0;
+
+    /* one newly seen document o reached from a parent with (eu, hu); eu = -2: an initial document that carries
+     * (ent0, 0) itself */
+#define KG_VISIT(o, eu, hu, ent0)                                                                      \
+    do {                                                                                               \
+        int32_t ent_ = -1, hop_ = 0, p_;                                                               \
+        float s_ = score_table ? score_table[(o)] : hybrid_fused(Q, qi, D, (o), w);                    \
+        if ((eu) == -2) { ent_ = (ent0); hop_ = 0; }                                                   \
+        else if ((eu) >= 0) {                                                                          \
+            ent_ = related_entity(de_ip, de, kg_ip, kg, (o), (eu));                                    \
+            if (ent_ >= 0) { hop_ = (hu) + 1; s_ = s_ + w_k / (float)hop_; }                           \
+        }                                                                                              \
+        if (visit_log && nscored < log_cap) visit_log[nscored] = (o);                                  \
+        if (ann_log && nscored < log_cap) { ann_log[2 * nscored] = ent_; ann_log[2 * nscored + 1] = hop_; } \
+        nscored++;                                                                                     \
+        if (len == L && !ranks_before(s_, (o), pool[len - 1].s, pool[len - 1].id)) break;               \
+        if (len == L) len--;                                                                           \
+        p_ = len;                                                                                      \
+        while (p_ > 0 && ranks_before(s_, (o), pool[p_ - 1].s, pool[p_ - 1].id)) {                     \
+            pool[p_] = pool[p_ - 1]; expanded[p_] = expanded[p_ - 1];                                  \
+            p_ent[p_] = p_ent[p_ - 1]; p_hop[p_] = p_hop[p_ - 1]; p_--;                                \
+        }                                                                                              \
+        pool[p_].s = s_; pool[p_].id = (o); expanded[p_] = 0; p_ent[p_] = ent_; p_hop[p_] = hop_; len++; \
+    } while (0)
+
+    for (e = 0; e < n_qe && started < E; e++) {
+        int64_t p;
+        int32_t ent = q_ent[e];
+        if (ent < 0) continue;
+        for (p = en_ip[ent]; p < en_ip[ent + 1] && started < E; p++) {
+            int32_t v = en[p];
+            if (visited[v]) continue;
+            visited[v] = 1; started++;
+            KG_VISIT(v, -2, 0, ent);
+        }
+    }
+    if (started == 0) {
+        for (e = 0; e < E; e++) {
+            int32_t v = entry[e];
+            if (v < 0 || visited[v]) continue;
+            visited[v] = 1;
+            KG_VISIT(v, -1, 0, -1);
+        }
+    }
+    while (max_iters <= 0 || it < max_iters) {
+        int32_t u = -1, eu = -1, hu = 0;
+        for (i = 0; i < len; i++)
+            if (!expanded[i]) { expanded[i] = 1; u = pool[i].id; eu = p_ent[i]; hu = p_hop[i]; break; }
+        if (u < 0) break;
+        for (e = 0; e < R; e++) {
+            int32_t v = graph[(int64_t)u * R + e];
+            if (v < 0 || visited[v]) continue;
+            visited[v] = 1;
+            KG_VISIT(v, eu, hu, -1);
+        }
+        if (eu >= 0 && hu < max_hops) {
+            const int32_t *t3 = le + (int64_t)u * le_cap * 3;
+            for (e = 0; e < le_count[u] && e < le_cap; e++) {
+                int32_t v = t3[3 * e + 1];
+                if (t3[3 * e] != eu || v < 0 || visited[v]) continue;
+                visited[v] = 1;
+                KG_VISIT(v, eu, hu, -1);
+            }
+        }
+        it++;
+    }
+#undef KG_VISIT
+    for (i = 0; i < k; i++) {
+        out_ids[i] = i < len ? pool[i].id : -1;
+        out_scores[i] = i < len ? pool[i].s : -INFINITY;
+    }
+    free(visited); free(pool); free(expanded); free(p_ent); free(p_hop);
+    return nscored;
+}

@@ -272,3 +272,33 @@ def subset_vecset(v: VecSet, rows) -> VecSet:
         parts[pre + "_val"] = getattr(v, pre + "_val")[take]
     bf = None if v.dense_bf16 is None else v.dense_bf16[rows]
     return dataclasses.replace(v, n=len(rows), dense=v.dense[rows], dense_bf16=bf, **parts)
+
+
+def make_entity_graph(n_docs: int, nq: int, seed: int = 0, n_ent: Optional[int] = None, ents_per_doc=(1, 3),
+                      kg_degree: int = 4, max_query_ents: int = 2, stride: int = 4):
+    """A synthetic stand-in for a knowledge graph extracted from a corpus: every document mentions a few entities
+    (distinct ids, ascending), entities are joined by undirected relations (about kg_degree per entity, no
+    self-relations), and every query names 1..max_query_ents entities of one randomly chosen document.  Returns a
+    namespace of CSR arrays: doc_ent_indptr / doc_ent, kg_indptr / kg_idx (symmetric), and q_ent (nq x stride, -1
+    padded)."""
+    from types import SimpleNamespace
+    rng = np.random.default_rng(seed)
+    n_ent = int(n_ent or max(8, n_docs // 8))
+    counts = rng.integers(ents_per_doc[0], ents_per_doc[1] + 1, n_docs)
+    indptr = np.concatenate([[0], np.cumsum(counts)]).astype(np.int64)
+    ids = np.empty(indptr[-1], np.int32)
+    for i in range(n_docs):
+        ids[indptr[i]:indptr[i + 1]] = np.sort(rng.choice(n_ent, counts[i], replace=False))
+    a = rng.integers(0, n_ent, n_ent * kg_degree // 2)
+    b = rng.integers(0, n_ent, n_ent * kg_degree // 2)
+    keep = a != b
+    pairs = np.unique(np.concatenate([np.stack([a[keep], b[keep]], 1), np.stack([b[keep], a[keep]], 1)]), axis=0)
+    kg_indptr = np.concatenate([[0], np.cumsum(np.bincount(pairs[:, 0], minlength=n_ent))]).astype(np.int64)
+    kg_idx = pairs[:, 1].astype(np.int32)          # np.unique sorted the pairs: ascending targets per source
+    q_ent = np.full((nq, stride), -1, np.int32)
+    for q in range(nq):
+        d = int(rng.integers(0, n_docs))
+        mine = ids[indptr[d]:indptr[d + 1]]
+        m = min(int(rng.integers(1, max_query_ents + 1)), len(mine), stride)
+        q_ent[q, :m] = rng.choice(mine, m, replace=False)
+    return SimpleNamespace(n_ent=n_ent, doc_ent_indptr=indptr, doc_ent=ids, kg_indptr=kg_indptr, kg_idx=kg_idx, q_ent=q_ent)
