@@ -186,6 +186,42 @@ int ap_insert_documents(const ap_index *old, const ap_corpus *enlarged, int32_t 
 int ap_export_build_state(const ap_index *index, int32_t *se, int32_t *sorted_ids, int32_t *sp_ids, float *sp_sc,
                           void *stream);
 
+/* Knowledge-graph augmentation (Section 3.4; the last step of Algorithm 1).
+ * doc_ent_indptr (n+1) / doc_ent: the entities each document mentions, ids in
+ * [0, n_ent), ascending per document.  kg_indptr (n_ent+1) / kg_idx: the
+ * relations, as a symmetric adjacency of entities, ascending per row, no
+ * self-relation.  All four are device arrays the index borrows until it is
+ * freed or the call is repeated.  Derives the entity-to-document mapping and
+ * the logical edges of every document x: triples (s, y, t) with s an entity
+ * of x, (s, t) a relation, t not an entity of x and y != x a document that
+ * mentions t, in ascending (s, t, y) order, the first le_cap (<= 128) of them.
+ * Synchronises `stream`; malformed ids give AP_EINVAL. */
+int ap_set_knowledge_graph(ap_index *index, int32_t n_ent, const int64_t *doc_ent_indptr, const int32_t *doc_ent,
+                           const int64_t *kg_indptr, const int32_t *kg_idx, int32_t le_cap, void *stream);
+
+/* Copies out what ap_set_knowledge_graph derived (any pointer may be NULL):
+ * le n x le_cap x 3 (-1 padded), le_count n, en_indptr n_ent+1 and en_idx
+ * (documents per entity, ascending). */
+int ap_export_logical_edges(const ap_index *index, int32_t *le, int32_t *le_count, int64_t *en_indptr, int32_t *en_idx,
+                            void *stream);
+
+/* Search with knowledge-graph augmentation (Section 4.2.3; the entity
+ * branches of Algorithm 2).  q_ent (device): nq x ent_stride entity ids the
+ * query names, -1 = unused slot, ent_stride in [1, 16].  Every pool entry
+ * carries the entity that ties it to the query's entities and the number of
+ * relations in between (hop).  With query entities the search starts from the
+ * documents that mention them (order of the query's entities, then ascending
+ * id, at most n_entry; hop 0), otherwise from the usual entry points.
+ * Expanding u: its semantic edges, then -- if u has an entity and
+ * hop(u) < max_hops -- the targets of its logical edges whose source is that
+ * entity.  A newly seen document o gets the smallest of its entities related
+ * to u's entity (none if u has none); with an entity, hop(o) = hop(u) + 1 and
+ * the score is raised by w_k / hop(o).  One parent per iteration
+ * (params->search_width must be 1).  Other arguments as ap_search_batch. */
+int ap_search_batch_entities(ap_index *index, const ap_queries *queries, const float *per_query_w,
+                             const ap_search_params *params, const int32_t *q_ent, int32_t ent_stride, float w_k,
+                             int32_t max_hops, int32_t *out_ids, float *out_scores, void *stream);
+
 void ap_free_index(ap_index *index);
 const char *ap_last_error(void); /* host string, thread-local */
 

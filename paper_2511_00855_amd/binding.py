@@ -250,6 +250,44 @@ class Index:
             _check(lib().ap_export_build_state(self._h, _ptr(se), _ptr(srt), _ptr(spi), _ptr(sps), _stream()), "ap_export_build_state")
         return se, srt, spi, sps
 
+    def set_knowledge_graph(self, kgs, le_cap: int = 32):
+        """kgs: namespace with n_ent, doc_ent_indptr, doc_ent, kg_indptr, kg_idx (see ap_set_knowledge_graph)."""
+        dev = self.device
+        self._kg = (_dev(kgs.doc_ent_indptr, torch.int64, dev), _dev(kgs.doc_ent, torch.int32, dev),
+                    _dev(kgs.kg_indptr, torch.int64, dev), _dev(kgs.kg_idx, torch.int32, dev))   # kept alive: the index borrows them
+        self._kg_dims = (int(kgs.n_ent), int(le_cap), int(len(kgs.doc_ent)))
+        with torch.cuda.device(dev):
+            _check(lib().ap_set_knowledge_graph(self._h, C.c_int32(int(kgs.n_ent)), *[_ptr(t) for t in self._kg],
+                                                C.c_int32(le_cap), _stream()), "ap_set_knowledge_graph")
+
+    def export_logical_edges(self):
+        n_ent, cap, total = self._kg_dims
+        dev = self.device
+        le = torch.empty((self.docs.n, cap, 3), dtype=torch.int32, device=dev)
+        cnt = torch.empty(self.docs.n, dtype=torch.int32, device=dev)
+        en_ip = torch.empty(n_ent + 1, dtype=torch.int64, device=dev)
+        en = torch.empty(max(total, 1), dtype=torch.int32, device=dev)
+        with torch.cuda.device(dev):
+            _check(lib().ap_export_logical_edges(self._h, _ptr(le), _ptr(cnt), _ptr(en_ip), _ptr(en), _stream()),
+                   "ap_export_logical_edges")
+        return le, cnt, en_ip, en[:total]
+
+    def search_batch_entities(self, queries: DeviceVecs, k: int, beam: int, q_ent, w_k: float, max_hops: int = 2,
+                              per_query_w=None, max_iters: int = 0):
+        nq = queries.n
+        qe = _dev(q_ent, torch.int32, self.device)
+        assert qe.dim() == 2 and qe.shape[0] == nq
+        ids = torch.empty((nq, k), dtype=torch.int32, device=self.device)
+        sc = torch.empty((nq, k), dtype=torch.float32, device=self.device)
+        w = None if per_query_w is None else _dev(per_query_w, torch.float32, self.device)
+        qs = queries.queries_struct()
+        sp = _SearchParams(k, beam, max_iters, 1)
+        with torch.cuda.device(self.device):
+            rc = lib().ap_search_batch_entities(self._h, C.byref(qs), _ptr(w), C.byref(sp), _ptr(qe), C.c_int32(qe.shape[1]),
+                                                C.c_float(w_k), C.c_int32(max_hops), _ptr(ids), _ptr(sc), _stream())
+        _check(rc, "ap_search_batch_entities")
+        return ids, sc
+
     def mark_deleted(self, ids, restore: bool = False):
         """Marks documents deleted (or restores them): searched through, left out of the answers."""
         t = _dev(ids, torch.int32, self.device).reshape(-1)

@@ -232,7 +232,7 @@ extern "C" int ap_ingest(const ap_corpus *corpus, const ap_build_params *params,
 
 extern "C" void ap_free_index(ap_index *ix) {
     if (!ix) return;
-    void *ptrs[] = {ix->st_se, ix->st_sorted, ix->st_spi, ix->st_sps, ix->deleted, ix->deleted_bad, ix->tx_w, ix->df, ix->stats, ix->self_sim, ix->graph, ix->kw, ix->kw_count, ix->entry, ix->visited, ix->w_dev,
+    void *ptrs[] = {ix->kg_en_ip, ix->kg_en, ix->kg_le, ix->kg_le_count, ix->st_se, ix->st_sorted, ix->st_spi, ix->st_sps, ix->deleted, ix->deleted_bad, ix->tx_w, ix->df, ix->stats, ix->self_sim, ix->graph, ix->kw, ix->kw_count, ix->entry, ix->visited, ix->w_dev,
                     ix->search_counts, ix->dense_norm, ix->rec, ix->meta};
     for (void *p : ptrs) if (p) (void)hipFree(p);
     for (hipEvent_t e : ix->ev_search) if (e) (void)hipEventDestroy(e);

@@ -89,6 +89,14 @@ struct ap_index {
     // pruned lists n x degree, detour-sorted lists n x knn_k, per-path lists 3 x n x sp_len with their scores
     int32_t *st_se = nullptr, *st_sorted = nullptr, *st_spi = nullptr;
     float *st_sps = nullptr;
+    // knowledge-graph augmentation (ap_set_knowledge_graph): the caller's entity lists and relations (borrowed),
+    // the entity-to-document mapping and the logical edges (owned)
+    const int64_t *kg_de_ip = nullptr, *kg_ip = nullptr;
+    const int32_t *kg_de = nullptr, *kg_idx = nullptr;
+    int64_t *kg_en_ip = nullptr;
+    int32_t *kg_en = nullptr, *kg_le = nullptr, *kg_le_count = nullptr;
+    int32_t kg_n_ent = 0, kg_le_cap = 0;
+    int64_t kg_total = 0;
 };
 
 template <typename T>

@@ -1,0 +1,93 @@
+"""GPU parity of the knowledge-graph augmentation: logical edges against the oracle's (exact), and the search with
+entity branches (Section 4.2.3, Algorithm 2) replayed by the oracle on the GPU's own scores (ids, scores and the
+number of scored documents bit for bit)."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from paper_2511_00855_amd import binding as B
+from paper_2511_00855_amd.synth import make_entity_graph, make_workload
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+@pytest.fixture(scope="module")
+def shard():
+    w = make_workload("tiny", seed=27, n=3000, nq=40)
+    docs = B.DeviceVecs(w.docs); qs = B.DeviceVecs(w.queries)
+    ix = B.Index.build(docs, B.build_params(w.degree))
+    kgs = make_entity_graph(3000, 40, seed=5, n_ent=400)
+    kgs.q_ent[::7] = -1                                   # some queries name no entity
+    kgs.q_ent[3, 0], kgs.q_ent[3, 1] = -1, kgs.q_ent[3, 0]   # an unused slot before a used one
+    D = O.encode_docs(w.docs); Q = O.VS(w.queries)
+    sem, _, _, ent = [t.cpu().numpy() for t in ix.export_graph()]
+    wq = np.random.default_rng(2).uniform(0.1, 1.0, (qs.n, 3)).astype(np.float32)
+    table = ix.hybrid_scores(qs, np.tile(np.arange(docs.n, dtype=np.int32), (qs.n, 1)), wq).cpu().numpy()[:, :, 3]
+    yield w, docs, qs, ix, kgs, D, Q, sem, ent, wq, table
+    ix.close()
+
+
+def test_logical_edges_match_the_oracle(shard):
+    w, docs, qs, ix, kgs, D, Q, sem, ent, wq, table = shard
+    with pytest.raises(RuntimeError, match="no knowledge graph"):
+        ix.search_batch_entities(qs, 5, 16, kgs.q_ent, 0.5)
+    for cap in (4, 16):
+        _say(f"logical edges, at most {cap} per document")
+        ix.set_knowledge_graph(kgs, le_cap=cap)
+        le, cnt, en_ip, en = [t.cpu().numpy() for t in ix.export_logical_edges()]
+        ole, ocnt, oen_ip, oen = O.logical_edges(kgs, docs.n, cap)
+        assert np.array_equal(en_ip, oen_ip) and np.array_equal(en, oen)
+        assert np.array_equal(cnt, ocnt) and np.array_equal(le, ole)
+        assert (cnt == cap).any() and (cnt < cap).any()
+    bad = make_entity_graph(3000, 4, seed=5, n_ent=400)
+    bad.doc_ent = bad.doc_ent.copy(); bad.doc_ent[5] = 400
+    with pytest.raises(RuntimeError, match="entity ids"):
+        ix.set_knowledge_graph(bad)
+    ix.set_knowledge_graph(kgs, le_cap=16)
+
+
+def test_entity_search_replay(shard):
+    w, docs, qs, ix, kgs, D, Q, sem, ent, wq, table = shard
+    ix.set_knowledge_graph(kgs, le_cap=16)
+    le, cnt, en_ip, en = [t.cpu().numpy() for t in ix.export_logical_edges()]
+    tied = 0
+    for (k, L, w_k, hops, iters) in ((10, 64, 0.5, 2, 0), (5, 16, 2.0, 3, 0), (8, 8, 0.5, 1, 5), (10, 128, 0.0, 0, 0), (1, 1, 1.0, 2, 0)):
+        _say(f"entity search replay: k={k} beam={L} w_k={w_k} max_hops={hops} iters={iters}")
+        ids, sc = [t.cpu().numpy() for t in ix.search_batch_entities(qs, k, L, kgs.q_ent, w_k, hops, wq, iters)]
+        counts = ix.search_stats(qs.n)[0].cpu().numpy()
+        for qi in range(qs.n):
+            oi, os_, log, ann = O.search_kg(D, sem, ent, Q, qi, wq[qi], k, L, kgs, le, cnt, en_ip, en, kgs.q_ent[qi], w_k,
+                                            max_hops=hops, max_iters=iters, score_table=table[qi], log=True)
+            assert np.array_equal(ids[qi], oi), (qi, k, L, ids[qi], oi)
+            assert np.array_equal(sc[qi], os_), (qi, k, L)
+            assert counts[qi, 0] == len(log), (qi, counts[qi], len(log))
+            tied += int((ann[:, 1] > 0).sum())
+    assert tied > 100
+    # queries that name no entity are plain searches
+    none = (kgs.q_ent < 0).all(axis=1)
+    assert none.any()
+    ids, sc = [t.cpu().numpy() for t in ix.search_batch_entities(qs, 10, 64, kgs.q_ent, 0.5, 2, wq)]
+    pids, psc = [t.cpu().numpy() for t in ix.search_batch(qs, 10, 64, wq)]
+    assert np.array_equal(ids[none], pids[none]) and np.array_equal(sc[none], psc[none])
+    assert not np.array_equal(ids[~none], pids[~none])
+
+
+def test_entity_search_cost(shard):
+    """Measured, as in the paper's comparison with and without the knowledge graph: what the augmentation costs."""
+    w, docs, qs, ix, kgs, D, Q, sem, ent, wq, table = shard
+    ix.set_knowledge_graph(kgs, le_cap=16)
+    big = B.DeviceVecs(make_workload("tiny", seed=28, n=10, nq=2000).queries)
+    wb = np.tile(np.float32(w.weights), (big.n, 1))
+    qe = make_entity_graph(3000, big.n, seed=5, n_ent=400).q_ent
+    for name, fn in (("plain", lambda: ix.search_batch(big, 10, 64, wb)),
+                     ("entities", lambda: ix.search_batch_entities(big, 10, 64, qe, 0.5, 2, wb))):
+        fn(); torch.cuda.synchronize()
+        t0 = time.time(); fn(); torch.cuda.synchronize()
+        _say(f"  {name}: {big.n / (time.time() - t0):,.0f} queries/s, kernel {ix.search_kernel_ms():.2f} ms")
