@@ -36,7 +36,7 @@ template <int DT>
 __global__ __launch_bounds__(256) void k_seed_scores(const void *dense, int32_t dim, int64_t n, const int32_t *node_ids,
                                                      int64_t row0, int64_t nrows, int64_t col0, int64_t ncols,
                                                      float *__restrict__ scores /* nrows x ncols */) {
-    __shared__ __attribute__((aligned(16))) unsigned char lds[AP_TILE_LDS_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char lds[ApTileLds<DT>::BYTES];
     __shared__ int32_t a_rows[AP_TILE], b_rows[AP_TILE];
     int64_t rt, ct;
     if (!ap_seed_tile((nrows + AP_TILE - 1) / AP_TILE, rt, ct)) return;
@@ -63,7 +63,7 @@ __global__ __launch_bounds__(256) void k_seed_thresh(const void *dense, int32_t 
                                                      int64_t row0, int64_t nrows, const float *__restrict__ tau,
                                                      unsigned long long *__restrict__ buf, int32_t cap,
                                                      int32_t *__restrict__ cnt) {
-    __shared__ __attribute__((aligned(16))) unsigned char lds[AP_TILE_LDS_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char lds[ApTileLds<DT>::BYTES];
     __shared__ int32_t a_rows[AP_TILE], b_rows[AP_TILE];
     __shared__ float s_tau[AP_TILE];
     int64_t rt, ct;
@@ -437,7 +437,7 @@ template <int DT>
 __global__ __launch_bounds__(256) void k_gram_dense(const void *dense, int32_t dim, int32_t K, const int32_t *__restrict__ knn,
                                                     const int32_t *__restrict__ node_ids, int64_t x0,
                                                     float *__restrict__ pm /* chunk x K x K */) {
-    __shared__ __attribute__((aligned(16))) unsigned char lds[AP_TILE_LDS_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char lds[ApTileLds<DT>::BYTES];
     __shared__ int32_t a_rows[AP_TILE], b_rows[AP_TILE];
     const int64_t x = blockIdx.y;
     const int64_t u = node_ids ? (int64_t)node_ids[x0 + x] : x0 + x;

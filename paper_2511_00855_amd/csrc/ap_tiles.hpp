@@ -11,29 +11,36 @@ typedef float ap_f32x16 __attribute__((ext_vector_type(16)));
 #define AP_BK 32
 #define AP_LDS_STRIDE (AP_BK + 1)   // odd stride: the 32 rows read by one MFMA operand fall in distinct banks
 
-// Loads columns [k0, k0+32) of the 128 rows `rows[]` (row id -1 = zeros) into
-// lds[128][33] as f32.
+// Columns [k0, k0+32) of the 128 rows `rows[]` (row id -1 = zeros) as f32: thread t holds 4 consecutive columns of
+// rows t/8 + 32*pass.  Loading (global memory -> registers) and storing (registers -> lds[128][33]) are separate
+// steps so that the loads of the next chunk can be in flight while the current one is multiplied.
 template <int DT>
-__device__ __forceinline__ void ap_tile_stage(const void *dense, int32_t dim, const int32_t *rows, int32_t k0, float *lds) {
+__device__ __forceinline__ void ap_tile_load(const void *dense, int32_t dim, const int32_t *rows, int32_t k0, float4 v[4]) {
     const int t = threadIdx.x;
 #pragma unroll
     for (int pass = 0; pass < 4; pass++) {
         const int r = (t >> 3) + 32 * pass;
         const int c = (t & 7) * 4;
         const int32_t row = rows[r];
-        float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
+        v[pass] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (row >= 0 && k0 + c < dim) {
             if (DT == AP_F32) {
-                const float4 x = *reinterpret_cast<const float4 *>(static_cast<const float *>(dense) + (int64_t)row * dim + k0 + c);
-                v0 = x.x; v1 = x.y; v2 = x.z; v3 = x.w;
+                v[pass] = *reinterpret_cast<const float4 *>(static_cast<const float *>(dense) + (int64_t)row * dim + k0 + c);
             } else {
                 const uint2 x = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(dense) + (int64_t)row * dim + k0 + c);
-                v0 = __uint_as_float(x.x << 16); v1 = __uint_as_float(x.x & 0xffff0000u);
-                v2 = __uint_as_float(x.y << 16); v3 = __uint_as_float(x.y & 0xffff0000u);
+                v[pass] = make_float4(__uint_as_float(x.x << 16), __uint_as_float(x.x & 0xffff0000u),
+                                      __uint_as_float(x.y << 16), __uint_as_float(x.y & 0xffff0000u));
             }
         }
-        float *d = lds + r * AP_LDS_STRIDE + c;
-        d[0] = v0; d[1] = v1; d[2] = v2; d[3] = v3;
+    }
+}
+
+__device__ __forceinline__ void ap_tile_store(const float4 v[4], float *lds) {
+    const int t = threadIdx.x;
+#pragma unroll
+    for (int pass = 0; pass < 4; pass++) {
+        float *d = lds + ((t >> 3) + 32 * pass) * AP_LDS_STRIDE + (t & 7) * 4;
+        d[0] = v[pass].x; d[1] = v[pass].y; d[2] = v[pass].z; d[3] = v[pass].w;
     }
 }
 
@@ -54,11 +61,19 @@ __device__ __forceinline__ void ap_tile_gemm(const void *dense, int32_t dim, con
         for (int b = 0; b < 2; b++)
 #pragma unroll
             for (int r = 0; r < 16; r++) acc[a][b][r] = 0.f;
+    float4 va[4], vb[4];
+    __syncthreads();                // the row lists were just written by the caller's threads
+    ap_tile_load<DT>(dense, dim, a_rows, 0, va);
+    ap_tile_load<DT>(dense, dim, b_rows, 0, vb);
     for (int32_t k0 = 0; k0 < dim; k0 += AP_BK) {
+        __syncthreads();            // everyone is done with the previous chunk in LDS
+        ap_tile_store(va, lA);
+        ap_tile_store(vb, lB);
         __syncthreads();
-        ap_tile_stage<DT>(dense, dim, a_rows, k0, lA);
-        ap_tile_stage<DT>(dense, dim, b_rows, k0, lB);
-        __syncthreads();
+        if (k0 + AP_BK < dim) {     // the next chunk travels while this one is multiplied
+            ap_tile_load<DT>(dense, dim, a_rows, k0 + AP_BK, va);
+            ap_tile_load<DT>(dense, dim, b_rows, k0 + AP_BK, vb);
+        }
         const float *pa0 = lA + (wm * 64 + li) * AP_LDS_STRIDE + lk;
         const float *pa1 = pa0 + 32 * AP_LDS_STRIDE;
         const float *pb0 = lB + (wn * 64 + li) * AP_LDS_STRIDE + lk;
@@ -82,18 +97,28 @@ typedef __bf16 ap_bf16x8 __attribute__((ext_vector_type(8)));
 #define AP_BK16 64
 #define AP_LDS_STRIDE16 (AP_BK16 + 8)   // in bf16 elements: 144-byte rows keep the 16-byte operand reads spread over the banks
 
-__device__ __forceinline__ void ap_tile_stage_bf16(const void *dense, int32_t dim, const int32_t *rows, int32_t k0, uint16_t *lds) {
+// thread t holds 8 consecutive columns (16 bytes) of rows t / AP_TPR16 + AP_RPP16 * pass
+#define AP_TPR16 (AP_BK16 / 8)            // threads per row of a chunk
+#define AP_RPP16 (256 / AP_TPR16)         // rows per pass
+#define AP_NP16 (AP_TILE / AP_RPP16)      // passes
+__device__ __forceinline__ void ap_tile_load_bf16(const void *dense, int32_t dim, const int32_t *rows, int32_t k0, uint4 v[AP_NP16]) {
     const int t = threadIdx.x;
 #pragma unroll
-    for (int pass = 0; pass < 4; pass++) {
-        const int r = (t >> 3) + 32 * pass;
-        const int c = (t & 7) * 8;
+    for (int pass = 0; pass < AP_NP16; pass++) {
+        const int r = t / AP_TPR16 + AP_RPP16 * pass;
+        const int c = (t % AP_TPR16) * 8;
         const int32_t row = rows[r];
-        uint4 v = make_uint4(0, 0, 0, 0);
+        v[pass] = make_uint4(0, 0, 0, 0);
         if (row >= 0 && k0 + c < dim)   // dim is a multiple of 8: a 16-byte group is all inside or all outside
-            v = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(dense) + (int64_t)row * dim + k0 + c);
-        *reinterpret_cast<uint4 *>(lds + r * AP_LDS_STRIDE16 + c) = v;
+            v[pass] = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(dense) + (int64_t)row * dim + k0 + c);
     }
+}
+
+__device__ __forceinline__ void ap_tile_store_bf16(const uint4 v[AP_NP16], uint16_t *lds) {
+    const int t = threadIdx.x;
+#pragma unroll
+    for (int pass = 0; pass < AP_NP16; pass++)
+        *reinterpret_cast<uint4 *>(lds + (t / AP_TPR16 + AP_RPP16 * pass) * AP_LDS_STRIDE16 + (t % AP_TPR16) * 8) = v[pass];
 }
 
 __device__ __forceinline__ void ap_tile_gemm_bf16(const void *dense, int32_t dim, const int32_t *a_rows, const int32_t *b_rows,
@@ -107,11 +132,19 @@ __device__ __forceinline__ void ap_tile_gemm_bf16(const void *dense, int32_t dim
         for (int b = 0; b < 2; b++)
 #pragma unroll
             for (int r = 0; r < 16; r++) acc[a][b][r] = 0.f;
+    uint4 va[AP_NP16], vb[AP_NP16];
+    __syncthreads();                // the row lists were just written by the caller's threads
+    ap_tile_load_bf16(dense, dim, a_rows, 0, va);
+    ap_tile_load_bf16(dense, dim, b_rows, 0, vb);
     for (int32_t k0 = 0; k0 < dim; k0 += AP_BK16) {
+        __syncthreads();            // everyone is done with the previous chunk in LDS
+        ap_tile_store_bf16(va, lA);
+        ap_tile_store_bf16(vb, lB);
         __syncthreads();
-        ap_tile_stage_bf16(dense, dim, a_rows, k0, lA);
-        ap_tile_stage_bf16(dense, dim, b_rows, k0, lB);
-        __syncthreads();
+        if (k0 + AP_BK16 < dim) {   // the next chunk travels while this one is multiplied
+            ap_tile_load_bf16(dense, dim, a_rows, k0 + AP_BK16, va);
+            ap_tile_load_bf16(dense, dim, b_rows, k0 + AP_BK16, vb);
+        }
         const uint16_t *pa0 = lA + (wm * 64 + li) * AP_LDS_STRIDE16 + lk;
         const uint16_t *pa1 = pa0 + 32 * AP_LDS_STRIDE16;
         const uint16_t *pb0 = lB + (wn * 64 + li) * AP_LDS_STRIDE16 + lk;
@@ -130,10 +163,12 @@ __device__ __forceinline__ void ap_tile_gemm_bf16(const void *dense, int32_t dim
     }
 }
 
-// LDS bytes the tile product needs (both operands), for either storage type.
-#define AP_TILE_LDS_BYTES (2 * AP_TILE * AP_LDS_STRIDE * 4 > 2 * AP_TILE * AP_LDS_STRIDE16 * 2 ? 2 * AP_TILE * AP_LDS_STRIDE * 4 : 2 * AP_TILE * AP_LDS_STRIDE16 * 2)
+// LDS bytes the tile product needs (both operands) for a storage type.
+template <int DT> struct ApTileLds {
+    static constexpr int BYTES = DT == AP_BF16 ? 2 * AP_TILE * AP_LDS_STRIDE16 * 2 : 2 * AP_TILE * AP_LDS_STRIDE * 4;
+};
 
-// Tile product for storage type DT out of one raw LDS area of AP_TILE_LDS_BYTES bytes.
+// Tile product for storage type DT out of one raw LDS area of ApTileLds<DT>::BYTES bytes.
 template <int DT>
 __device__ __forceinline__ void ap_tile_product(const void *dense, int32_t dim, const int32_t *a_rows, const int32_t *b_rows,
                                                 void *lds, ap_f32x16 acc[2][2]) {
