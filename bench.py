@@ -131,7 +131,7 @@ def main():
     ap.add_argument("--n", type=int, default=None, help="override the number of documents (smaller rehearsal)")
     ap.add_argument("--nq", type=int, default=None)
     ap.add_argument("--rounds", type=int, default=3)
-    ap.add_argument("--beams", default="128,256,512,1024,1536,2048,2304,2560,3072,4096")
+    ap.add_argument("--beams", default="128,256,512,1024,1536,2048,2112,2144,2176,2240,2304,2560,3072,4096")
     ap.add_argument("--beam", type=int, default=0, help="fix the beam (skips the sweep; for profiling runs)")
     ap.add_argument("--target-recall", type=float, default=0.95)
     ap.add_argument("--calibrate-copy", action="store_true",

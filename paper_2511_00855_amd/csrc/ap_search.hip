@@ -23,6 +23,7 @@ struct ApSearchArgs {
     const float *w;     // per query (stride 3) or the index default (stride 0)
     int32_t w_stride;
     int32_t R, E, k, L, max_iters, width, cmax;
+    int32_t nxtw;       // words of the scratch that parks positions when more than 256 keys enter at once (0 when cmax <= 256)
     uint32_t *visited;
     size_t words;       // visited words per query
     int32_t *out_ids;
@@ -163,14 +164,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
     uint64_t *cur = smem64;                  // the pool: L keys, best first
     uint64_t *newk = cur + g.L;              // keys of this iteration's candidates, unordered
     uint64_t *newS = newk + g.cmax;          // the same, sorted
-    uint64_t *nxt = newS + g.cmax;           // scratch of cmax words
-    uint64_t *xk = nxt + g.cmax;             // KW: satisfying keys the pool did not keep in this iteration (cmax words)
+    uint64_t *nxt = newS + g.cmax;           // scratch of nxtw words (only wide searches need it)
+    uint64_t *xk = nxt + g.nxtw;             // KW: satisfying keys the pool did not keep in this iteration (cmax words)
     uint64_t *kwc = xk + (KW ? g.cmax : 0);  // KW: the secondary pool, k keys, best first
     uint64_t *qtab = kwc + (KW ? g.k : 0);   // the query's two look-up tables
     // descriptors of this iteration's candidates (16-byte aligned: an odd number of words before them shifts them by one)
     constexpr int SPB = ApQTab<BIG>::SPB, TXB = ApQTab<BIG>::TXB;
     uint4 *s_meta = reinterpret_cast<uint4 *>(qtab + ApQTab<BIG>::SLOTS +
-                                              ((g.L + 3 * g.cmax + (KW ? g.cmax + g.k : 0)) & 1));
+                                              ((g.L + 2 * g.cmax + g.nxtw + (KW ? g.cmax + g.k : 0)) & 1));
     int32_t *cand = reinterpret_cast<int32_t *>(s_meta + g.cmax);
     __shared__ int32_t s_cnt, s_np, s_skip, s_xn, s_kc;
     __shared__ int32_t s_par[8], s_psat[8];
@@ -510,7 +511,8 @@ static int ap_search_launch(ap_index *ix, const ApVecs &Q, const float *w_dev, i
     g.deleted = ix->deleted;
     ix->last_nq = nq;
     AP_TRY(ap_fill_u32(ix->visited, need, 0u, st));
-    const size_t smem = (size_t)(g.L + 3 * g.cmax + (kw ? g.cmax + g.k : 0)) * 8 + (size_t)g.cmax * (16 + 4) +
+    g.nxtw = g.cmax > 256 ? g.cmax : 0;
+    const size_t smem = (size_t)(g.L + 2 * g.cmax + g.nxtw + (kw ? g.cmax + g.k : 0)) * 8 + (size_t)g.cmax * (16 + 4) +
                         (size_t)(big_tables ? ApQTab<true>::SLOTS : ApQTab<false>::SLOTS) * 8 + 8;
     AP_CHECK_HIP(hipEventRecord(ix->ev_search[0], st));
     AP_REQUIRE(smem <= 160 * 1024, "beam and search_width need %zu bytes of LDS (limit 160 KiB)", smem);

@@ -73,7 +73,7 @@ def test_full_size_scores_sampled(full):
     assert_scores_close(got[rows], ref, score_tol(ref, wq[rows][:, None, :], qn, dn, RTOL_F32), "full-size scores")
 
 
-@pytest.mark.parametrize("beam", [128, 2304])
+@pytest.mark.parametrize("beam", [128, 2144])
 def test_full_size_search_replay(full, beam):
     """All 10,000 queries are searched exactly as bench.py does; for a sample the
     oracle's search, replayed on the GPU's own scores, must return the same ids
