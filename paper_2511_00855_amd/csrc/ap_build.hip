@@ -887,8 +887,9 @@ static int build_impl(ap_index *ix, hipStream_t st, BuildBufs &b) {
     const ap_build_params &p = ix->params;
     const int64_t n = ix->corpus.n;   // ix->docs is only filled in by the ingest step below
     const int32_t K = p.knn_k, R = p.degree, P = p.sp_len;
-    hipEvent_t ev[6];
-    for (auto &e : ev) AP_CHECK_HIP(hipEventCreate(&e));
+    ApStageEvents marks;
+    AP_CHECK_HIP(marks.create());
+    hipEvent_t *ev = marks.ev;
     auto mark = [&](int i) { return hipEventRecord(ev[i], st); };
     AP_CHECK_HIP(mark(0));
     AP_TRY(ap_ingest_impl(ix, st));
@@ -929,7 +930,6 @@ static int build_impl(ap_index *ix, hipStream_t st, BuildBufs &b) {
         total += ms * 1e-3f;
     }
     ix->timings[5] = total;
-    for (auto &e : ev) (void)hipEventDestroy(e);
     ix->has_graph = true;
     // kept for later insertions
     ix->st_se = b.se; ix->st_sorted = b.sorted; ix->st_spi = b.spi[cur]; ix->st_sps = b.sps[cur];

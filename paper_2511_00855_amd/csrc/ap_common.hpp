@@ -111,6 +111,16 @@ static inline int ap_dev_alloc(T **p, size_t count) {
     return AP_OK;
 }
 
+// The six stage marks of a construction or an insertion; destroyed on every way out.
+struct ApStageEvents {
+    hipEvent_t ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    hipError_t create() {
+        for (auto &e : ev) { const hipError_t r = hipEventCreate(&e); if (r != hipSuccess) return r; }
+        return hipSuccess;
+    }
+    ~ApStageEvents() { for (auto &e : ev) if (e) (void)hipEventDestroy(e); }
+};
+
 int ap_validate_corpus(const ap_corpus *c);
 int ap_validate_params(const ap_build_params *p);
 int ap_ingest_impl(ap_index *ix, hipStream_t st);

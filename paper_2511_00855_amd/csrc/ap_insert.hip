@@ -81,8 +81,9 @@ static int insert_impl(const ap_index *old, ap_index *nx, int32_t beam, const ap
     const int64_t n0 = old->corpus.n, n1 = nx->corpus.n, m = n1 - n0;
     const int32_t K = p.knn_k, R = p.degree, P = p.sp_len, KR = R / 2;
     const size_t esize = nx->dtype == AP_F32 ? 4 : 2;
-    hipEvent_t ev[6];
-    for (auto &e : ev) AP_CHECK_HIP(hipEventCreate(&e));
+    ApStageEvents marks;
+    AP_CHECK_HIP(marks.create());
+    hipEvent_t *ev = marks.ev;
     auto mark = [&](int i) { return hipEventRecord(ev[i], st); };
     InsertBufs B;
     AP_CHECK_HIP(mark(0));
@@ -235,7 +236,6 @@ static int insert_impl(const ap_index *old, ap_index *nx, int32_t beam, const ap
         total += ms * 1e-3f;
     }
     nx->timings[5] = total;
-    for (auto &e : ev) (void)hipEventDestroy(e);
     nx->has_graph = true;
     nx->st_se = se; nx->st_sorted = sorted; nx->st_spi = spi; nx->st_sps = sps;
     B.keep(se); B.keep(sorted); B.keep(spi); B.keep(sps);
