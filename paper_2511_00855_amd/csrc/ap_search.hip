@@ -232,7 +232,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
         if (v >= 0) {
             const uint32_t bit = 1u << (v & 31);
             const uint32_t old = atomicOr(&vis[v >> 5], bit);
-            if (!(old & bit)) cand[atomicAdd(&s_cnt, 1)] = v;
+            const uint4 m = g.meta[v];
+            if (!(old & bit)) { const int32_t at = atomicAdd(&s_cnt, 1); cand[at] = v; s_meta[at] = m; }
         }
     }
     __syncthreads();
@@ -240,9 +241,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
     for (;;) {
         const int32_t c = s_cnt;
         nscored += c;
-        // each candidate's descriptor (where its record is, how long, its dense norm): one round of 16-byte loads
-        for (int32_t i = threadIdx.x; i < c; i += blockDim.x) s_meta[i] = g.meta[cand[i]];
-        __syncthreads();
         const bool pool_full = len == g.L;
         const uint64_t worst = pool_full ? cur[g.L - 1] : 0ull;
         const float worst_score = ap_key_score(worst);
@@ -388,8 +386,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
             }
             if (v >= 0) {
                 const uint32_t bit = 1u << (v & 31);
+                // the descriptor (where the record is, how long, the dense norm) is fetched along with the visited
+                // test, not after it: one memory round trip less per iteration for 16 bytes per neighbour already seen
                 const uint32_t old = atomicOr(&vis[v >> 5], bit);
-                if (!(old & bit)) cand[atomicAdd(&s_cnt, 1)] = v;
+                const uint4 m = g.meta[v];
+                if (!(old & bit)) { const int32_t at = atomicAdd(&s_cnt, 1); cand[at] = v; s_meta[at] = m; }
             }
         }
         __syncthreads();
