@@ -146,9 +146,10 @@ int ap_search_batch_keywords(ap_index *index, const ap_queries *queries, const f
 /* Mark-deletion (Section 4.1, updates of the hybrid index): the count listed
  * documents (device ids) are marked deleted, or restored when restore != 0.
  * Deleted documents stay in the graph and are searched through like any
- * other; ap_search_batch and ap_search_batch_keywords leave them out of their
- * answers (and out of the secondary pool), so an answer holds the best k live
- * documents the search met.  Synchronises `stream`; ids outside [0, n) are
+ * other; ap_search_batch, ap_search_batch_keywords and
+ * ap_search_batch_entities leave them out of their answers (and out of the
+ * secondary pool), so an answer holds the best k live documents the search
+ * met.  The marks carry over to the index ap_insert_documents returns.  Synchronises `stream`; ids outside [0, n) are
  * skipped and reported as AP_EINVAL after the others were applied. */
 int ap_mark_deleted(ap_index *index, const int32_t *ids, int64_t count, int restore, void *stream);
 
@@ -166,7 +167,9 @@ int ap_mark_deleted(ap_index *index, const int32_t *ids, int64_t count, int rest
  * K-list of a new document = the best K of both sets; pruning and keyword
  * recycling for the new documents only; edge-list assembly over all documents
  * (old documents gain reverse neighbours among the new ones); entry points
- * from all self-similarities.  Needs an index produced by ap_build_index or
+ * from all self-similarities.  Mark-deleted documents of `old` stay deleted
+ * (and, being part of the graph, stay eligible as neighbours of new
+ * documents).  Needs an index produced by ap_build_index or
  * ap_insert_documents (AP_ESTATE for an imported graph).  Synchronises
  * `stream`.  trace (may be NULL): optional device buffers that receive the
  * intermediates for the m = n1 - n0 new documents, any of them NULL. */
@@ -195,7 +198,8 @@ int ap_export_build_state(const ap_index *index, int32_t *se, int32_t *sorted_id
  * the logical edges of every document x: triples (s, y, t) with s an entity
  * of x, (s, t) a relation, t not an entity of x and y != x a document that
  * mentions t, in ascending (s, t, y) order, the first le_cap (<= 128) of them.
- * Synchronises `stream`; malformed ids give AP_EINVAL. */
+ * Synchronises `stream`; row offsets that do not ascend from 0 to the total
+ * (< 2^31 each) or malformed ids give AP_EINVAL. */
 int ap_set_knowledge_graph(ap_index *index, int32_t n_ent, const int64_t *doc_ent_indptr, const int32_t *doc_ent,
                            const int64_t *kg_indptr, const int32_t *kg_idx, int32_t le_cap, void *stream);
 
@@ -207,9 +211,9 @@ int ap_export_logical_edges(const ap_index *index, int32_t *le, int32_t *le_coun
 
 /* Search with knowledge-graph augmentation (Section 4.2.3; the entity
  * branches of Algorithm 2).  q_ent (device): nq x ent_stride entity ids the
- * query names, -1 = unused slot, ent_stride in [1, 16].  Every pool entry
- * carries the entity that ties it to the query's entities and the number of
- * relations in between (hop).  With query entities the search starts from the
+ * query names, ent_stride in [1, 16]; a negative id or one >= n_ent is an
+ * unused slot.  Every pool entry carries the entity that ties it to the
+ * query's entities and the number of relations in between (hop).  With query entities the search starts from the
  * documents that mention them (order of the query's entities, then ascending
  * id, at most n_entry; hop 0), otherwise from the usual entry points.
  * Expanding u: its semantic edges, then -- if u has an entity and

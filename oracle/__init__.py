@@ -479,8 +479,9 @@ def logical_edges(kgs, n, cap):
 
 
 def search_kg(D: VS, graph, entry, Q: VS, qi, w, k, L, kgs, le, le_count, en_ip, en, q_ent, w_k, max_hops=2, max_iters=0,
-              score_table=None, log=False):
-    """Search with knowledge-graph augmentation for one query (Section 4.2.3); q_ent: the query's entities."""
+              score_table=None, log=False, deleted=None):
+    """Search with knowledge-graph augmentation for one query (Section 4.2.3); q_ent: the query's entities.
+    deleted: ids of mark-deleted documents (Section 4.1, updates), left out of the answer."""
     graph = _c(graph, np.int32); entry = _c(entry, np.int32)
     w = _c(w, np.float32)
     de_ip = _c(kgs.doc_ent_indptr, np.int64); de = _c(kgs.doc_ent, np.int32)
@@ -492,10 +493,11 @@ def search_kg(D: VS, graph, entry, Q: VS, qi, w, k, L, kgs, le, le_count, en_ip,
     st = None if score_table is None else _c(score_table, np.float32)
     cap = D.n if log else 0
     vl = np.empty(max(cap, 1), np.int32); al = np.empty((max(cap, 1), 2), np.int32)
+    dl = _deleted_bytes(deleted, D.n)
     n = lib().orc_search_kg(D.ref, _p(graph), C.c_int32(graph.shape[1]), _p(entry), C.c_int32(len(entry)), Q.ref,
                             C.c_int64(qi), _p(w), C.c_int32(k), C.c_int32(L), C.c_int32(max_iters), _p(de_ip), _p(de),
                             _p(kg_ip), _p(kg), _p(en_ip), _p(en), _p(le), C.c_int32(le.shape[1]), _p(le_count), _p(qe),
-                            C.c_int32(len(qe)), C.c_float(w_k), C.c_int32(max_hops), _p(st), _p(ids), _p(sc),
+                            C.c_int32(len(qe)), C.c_float(w_k), C.c_int32(max_hops), _p(st), _p(dl), _p(ids), _p(sc),
                             _p(vl) if log else None, _p(al) if log else None, C.c_int64(cap))
     if log:
         return ids, sc, vl[:n].copy(), al[:n].copy()

@@ -710,8 +710,8 @@ int64_t orc_search_kg(const orc_vecset *D, const int32_t *graph, int32_t R, cons
                       const int64_t *de_ip, const int32_t *de, const int64_t *kg_ip, const int32_t *kg,
                       const int64_t *en_ip, const int32_t *en, const int32_t *le, int32_t le_cap,
                       const int32_t *le_count, const int32_t *q_ent, int32_t n_qe, float w_k, int32_t max_hops,
-                      const float *score_table, int32_t *out_ids, float *out_scores, int32_t *visit_log,
-                      int32_t *ann_log, int64_t log_cap) {
+                      const float *score_table, const unsigned char *deleted, int32_t *out_ids, float *out_scores,
+                      int32_t *visit_log, int32_t *ann_log, int64_t log_cap) {
     int64_t N = D->n, nscored = 0;
     unsigned char *visited = (unsigned char *)calloc((size_t)(N > 0 ? N : 1), 1);
     scored *pool = (scored *)malloc(sizeof(scored) * (size_t)(L + 1));
@@ -786,9 +786,15 @@ int64_t orc_search_kg(const orc_vecset *D, const int32_t *graph, int32_t R, cons
         it++;
     }
 #undef KG_VISIT
-    for (i = 0; i < k; i++) {
-        out_ids[i] = i < len ? pool[i].id : -1;
-        out_scores[i] = i < len ? pool[i].s : -INFINITY;
+    /* mark-deletion (Section 4.1, updates): as in the plain search, deleted documents were searched through
+     * like any other and are only left out of the answer */
+    {
+        int32_t o = 0;
+        for (i = 0; i < len && o < k; i++) {
+            if (deleted && deleted[pool[i].id]) continue;
+            out_ids[o] = pool[i].id; out_scores[o] = pool[i].s; o++;
+        }
+        for (; o < k; o++) { out_ids[o] = -1; out_scores[o] = -INFINITY; }
     }
     free(visited); free(pool); free(expanded); free(p_ent); free(p_hop);
     return nscored;

@@ -227,6 +227,13 @@ static int insert_impl(const ap_index *old, ap_index *nx, int32_t beam, const ap
     AP_TRY(ap_assemble_impl(nx, R, K, P, se, sorted, spi, nx->graph, st));
     AP_TRY(ap_stage_entry_points(nx, p.n_entry, nx->entry, st));
     AP_CHECK_HIP(mark(5));
+    if (old->deleted) {   // marks of deletion carry over (bits past n0 in the old last word were never set)
+        const size_t w0 = ((size_t)n0 + 31) / 32, w1 = ((size_t)n1 + 31) / 32;
+        AP_TRY(ap_dev_alloc(&nx->deleted, w1));
+        AP_TRY(ap_dev_alloc(&nx->deleted_bad, 1));
+        AP_TRY(ap_fill_u32(nx->deleted, w1, 0u, st));
+        AP_COPY(nx->deleted, old->deleted, w0, uint32_t);
+    }
     AP_CHECK_HIP(hipStreamSynchronize(st));
     float total = 0.f;
     for (int i = 0; i < 5; i++) {

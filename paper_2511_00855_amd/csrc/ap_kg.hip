@@ -20,23 +20,34 @@
 int ap_validate_queries(const ap_queries *q);
 
 // ------------------------------------------------------------------ construction
-__global__ void k_ent_count(const int64_t *__restrict__ de_ip, const int32_t *__restrict__ de, int64_t n, int32_t n_ent,
+// row offsets must start at 0, never decrease and end at `total`; a row that fails is not read
+__device__ __forceinline__ bool ap_row_ok(const int64_t *ip, int64_t x, int64_t total) {
+    const int64_t b = ip[x], e = ip[x + 1];
+    return b >= 0 && e >= b && e <= total && (x > 0 || b == 0);
+}
+
+__global__ void k_ent_count(const int64_t *__restrict__ de_ip, const int32_t *__restrict__ de, int64_t n, int32_t n_ent, int64_t total,
                             unsigned long long *__restrict__ cnt, int32_t *__restrict__ bad) {
-    for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < n; x += (int64_t)gridDim.x * blockDim.x)
+    for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < n; x += (int64_t)gridDim.x * blockDim.x) {
+        if (!ap_row_ok(de_ip, x, total)) { atomicAdd(bad, 1); continue; }
         for (int64_t p = de_ip[x]; p < de_ip[x + 1]; p++) {
             const int32_t e = de[p];
             if (e < 0 || e >= n_ent || (p > de_ip[x] && de[p - 1] >= e)) { atomicAdd(bad, 1); continue; }
             atomicAdd(&cnt[e], 1ull);
         }
+    }
 }
 
 // relations must name entities, ascending per row, no self-relation
-__global__ void k_kg_check(const int64_t *__restrict__ kg_ip, const int32_t *__restrict__ kg, int32_t n_ent, int32_t *__restrict__ bad) {
-    for (int64_t s = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; s < n_ent; s += (int64_t)gridDim.x * blockDim.x)
+__global__ void k_kg_check(const int64_t *__restrict__ kg_ip, const int32_t *__restrict__ kg, int32_t n_ent, int64_t total,
+                           int32_t *__restrict__ bad) {
+    for (int64_t s = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; s < n_ent; s += (int64_t)gridDim.x * blockDim.x) {
+        if (!ap_row_ok(kg_ip, s, total)) { atomicAdd(bad, 1); continue; }
         for (int64_t p = kg_ip[s]; p < kg_ip[s + 1]; p++) {
             const int32_t t = kg[p];
             if (t < 0 || t >= n_ent || t == s || (p > kg_ip[s] && kg[p - 1] >= t)) atomicAdd(bad, 1);
         }
+    }
 }
 
 // Exclusive prefix sum of cnt[0..m) into out[0..m] by one workgroup: each thread sums a contiguous chunk, the
@@ -123,10 +134,12 @@ extern "C" int ap_set_knowledge_graph(ap_index *ix, int32_t n_ent, const int64_t
     hipStream_t st = (hipStream_t)stream;
     const int64_t n = ix->corpus.n;
     kg_release(ix);
-    int64_t total = 0;
+    int64_t total = 0, kg_total = 0;
     AP_CHECK_HIP(hipMemcpyAsync(&total, doc_ent_indptr + n, sizeof(int64_t), hipMemcpyDeviceToHost, st));
+    AP_CHECK_HIP(hipMemcpyAsync(&kg_total, kg_indptr + n_ent, sizeof(int64_t), hipMemcpyDeviceToHost, st));
     AP_CHECK_HIP(hipStreamSynchronize(st));
     AP_REQUIRE(total >= 0 && total < ((int64_t)1 << 31), "doc_ent_indptr[n] = %lld is out of range", (long long)total);
+    AP_REQUIRE(kg_total >= 0 && kg_total < ((int64_t)1 << 31), "kg_indptr[n_ent] = %lld is out of range", (long long)kg_total);
     unsigned long long *cnt = nullptr;
     int32_t *tmp = nullptr, *bad = nullptr;
     int rc = ap_dev_alloc(&cnt, (size_t)n_ent);
@@ -142,8 +155,8 @@ extern "C" int ap_set_knowledge_graph(ap_index *ix, int32_t n_ent, const int64_t
     int32_t h_bad = 0;
     if (rc == AP_OK) {
         const unsigned gd = (unsigned)std::min<int64_t>((n + 255) / 256, 4096), ge = (unsigned)std::min<int64_t>(((int64_t)n_ent + 255) / 256, 4096);
-        hipLaunchKernelGGL(k_ent_count, dim3(gd), dim3(256), 0, st, doc_ent_indptr, doc_ent, n, n_ent, cnt, bad);
-        hipLaunchKernelGGL(k_kg_check, dim3(ge), dim3(256), 0, st, kg_indptr, kg_idx, n_ent, bad);
+        hipLaunchKernelGGL(k_ent_count, dim3(gd), dim3(256), 0, st, doc_ent_indptr, doc_ent, n, n_ent, total, cnt, bad);
+        hipLaunchKernelGGL(k_kg_check, dim3(ge), dim3(256), 0, st, kg_indptr, kg_idx, n_ent, kg_total, bad);
         e = hipGetLastError();
         if (e == hipSuccess) e = hipMemcpyAsync(&h_bad, bad, sizeof(h_bad), hipMemcpyDeviceToHost, st);
         if (e == hipSuccess) e = hipStreamSynchronize(st);
@@ -165,7 +178,8 @@ extern "C" int ap_set_knowledge_graph(ap_index *ix, int32_t n_ent, const int64_t
     for (void *x : p) if (x) (void)hipFree(x);
     if (rc == AP_OK && e != hipSuccess) { ap_set_error("knowledge-graph set-up failed: %s", hipGetErrorString(e)); rc = AP_EHIP; }
     if (rc == AP_OK && h_bad != 0) {
-        ap_set_error("%d entity ids are out of range, not ascending within their row, or relate an entity to itself", h_bad);
+        ap_set_error("%d rows or entity ids are malformed (row offsets not ascending from 0 to the total, ids out of range or not "
+                     "ascending within their row, or an entity related to itself)", h_bad);
         rc = AP_EINVAL;
     }
     if (rc != AP_OK) { kg_release(ix); return rc; }
@@ -203,8 +217,9 @@ struct ApKgArgs {
     const int32_t *le, *le_count;
     int32_t le_cap;
     const int32_t *q_ent;
-    int32_t ent_stride, max_hops;
+    int32_t ent_stride, max_hops, n_ent;
     float w_k;
+    const uint32_t *deleted;   // one bit per document, NULL when nothing was ever deleted
 };
 
 // annotation of a pool entry: (entity + 1) << 8 | hop; 0 = no entity
@@ -259,7 +274,7 @@ __global__ __launch_bounds__(256) void k_search_kg(ApKgArgs g) {
         int32_t c = 0;
         for (int32_t j = 0; j < g.ent_stride && c < g.E; j++) {
             const int32_t e = g.q_ent[q * g.ent_stride + j];
-            if (e < 0) continue;
+            if (e < 0 || e >= g.n_ent) continue;
             for (int64_t p = g.en_ip[e]; p < g.en_ip[e + 1] && c < g.E; p++) {
                 const int32_t v = g.en[p];
                 const uint32_t bit = 1u << (v & 31);
@@ -381,11 +396,24 @@ __global__ __launch_bounds__(256) void k_search_kg(ApKgArgs g) {
         it++;
     }
     if (threadIdx.x == 0) { g.counts[q * 3] = nscored; g.counts[q * 3 + 1] = it; g.counts[q * 3 + 2] = 0; }
-    if (wave == 0)
-        for (int32_t i = lane; i < g.k; i += 64) {
-            g.out_ids[q * g.k + i] = i < len ? ap_key_id(cur[i]) : -1;
-            g.out_scores[q * g.k + i] = i < len ? ap_key_score(cur[i]) : -INFINITY;
+    // the best k pool entries; mark-deleted documents were searched through like any other and are left out here
+    if (wave == 0) {
+        int32_t o = 0;
+        for (int32_t base = 0; base < len && o < g.k; base += 64) {
+            const int32_t i = base + lane;
+            bool live = i < len;
+            if (live && g.deleted) { const int32_t v = ap_key_id(cur[i]); live = !((g.deleted[v >> 5] >> (v & 31)) & 1u); }
+            const uint64_t mask = __ballot(live);
+            const int32_t at = o + __popcll(mask & ((1ull << lane) - 1ull));
+            if (live && at < g.k) {
+                g.out_ids[q * g.k + at] = ap_key_id(cur[i]);
+                g.out_scores[q * g.k + at] = ap_key_score(cur[i]);
+            }
+            o += __popcll(mask);
         }
+        o = o < g.k ? o : g.k;
+        for (int32_t i = o + lane; i < g.k; i += 64) { g.out_ids[q * g.k + i] = -1; g.out_scores[q * g.k + i] = -INFINITY; }
+    }
 }
 
 extern "C" int ap_search_batch_entities(ap_index *ix, const ap_queries *q, const float *per_query_w, const ap_search_params *p,
@@ -436,6 +464,7 @@ extern "C" int ap_search_batch_entities(ap_index *ix, const ap_queries *q, const
     g.de_ip = ix->kg_de_ip; g.de = ix->kg_de; g.kg_ip = ix->kg_ip; g.kg = ix->kg_idx; g.en_ip = ix->kg_en_ip; g.en = ix->kg_en;
     g.le = ix->kg_le; g.le_count = ix->kg_le_count; g.le_cap = ix->kg_le_cap;
     g.q_ent = q_ent; g.ent_stride = ent_stride; g.max_hops = max_hops; g.w_k = w_k;
+    g.n_ent = ix->kg_n_ent; g.deleted = ix->deleted;
     ix->last_nq = nq;
     AP_TRY(ap_fill_u32(ix->visited, need, 0u, st));
     const size_t smem = (size_t)(g.L + g.cmax) * 8 + ((1 << AP_KG_SPB) + (1 << AP_KG_TXB)) * 8 + 8 + (size_t)g.cmax * 16 +

@@ -168,6 +168,39 @@ def test_inserted_index_searches_and_grows_again(grown):
         x.close()
 
 
+def test_marks_of_deletion_carry_over(grown):
+    w, n0, bp, old, new, tr, D, all_docs = grown
+    qs = B.DeviceVecs(w.queries)
+    wq = np.tile(np.float32(w.weights), (qs.n, 1))
+    k, L = 10, 48
+    ids0 = new.search_batch(qs, k, L, wq)[0].cpu().numpy()
+    dele = np.unique(ids0[:, :2][ids0[:, :2] < n0]).astype(np.int32)      # old documents that are top answers
+    assert len(dele) > 5
+    old.mark_deleted(dele)
+    try:
+        again = old.insert(all_docs)
+    finally:
+        old.mark_deleted(dele, restore=True)
+    # the graph is the one built without the marks (deleted documents stay eligible as neighbours) ...
+    for a, b in zip(again.export_graph(), new.export_graph()):
+        assert torch.equal(a, b)
+    # ... and its answers leave the deleted documents out: the oracle's search on the same graph with the same marks
+    ids, sc = _np(*again.search_batch(qs, k, L, wq))
+    assert not np.isin(ids, dele).any()
+    sem, _, _, ent = _np(*again.export_graph())
+    Q = O.VS(w.queries)
+    table = again.hybrid_scores(qs, np.tile(np.arange(w.docs.n, dtype=np.int32), (qs.n, 1)), wq).cpu().numpy()[:, :, 3]
+    for qi in range(qs.n):
+        oi, os_, _ = O.search(D, sem, ent, Q, qi, wq[qi], k, L, score_table=table[qi], deleted=dele)
+        assert np.array_equal(ids[qi], oi) and np.array_equal(sc[qi], os_), qi
+    # a new document can be deleted in the new index as well
+    newest = np.unique(ids[ids >= n0])[:3].astype(np.int32)
+    assert len(newest) > 0
+    again.mark_deleted(newest)
+    assert not np.isin(again.search_batch(qs, k, L, wq)[0].cpu().numpy(), np.concatenate([dele, newest])).any()
+    again.close()
+
+
 def test_insert_argument_checks(grown):
     w, n0, bp, old, new, tr, D, all_docs = grown
     sem, ke, kc, ent = old.export_graph()

@@ -50,7 +50,45 @@ def test_logical_edges_match_the_oracle(shard):
     bad.doc_ent = bad.doc_ent.copy(); bad.doc_ent[5] = 400
     with pytest.raises(RuntimeError, match="entity ids"):
         ix.set_knowledge_graph(bad)
+    # row offsets that run backwards or past the end are refused before any row is read
+    for arr, at in (("doc_ent_indptr", 7), ("kg_indptr", 3)):
+        bad = make_entity_graph(3000, 4, seed=5, n_ent=400)
+        ip = getattr(bad, arr).copy(); ip[at] = ip[-1] + 5
+        setattr(bad, arr, ip)
+        with pytest.raises(RuntimeError, match="row offsets"):
+            ix.set_knowledge_graph(bad)
     ix.set_knowledge_graph(kgs, le_cap=16)
+
+
+def test_entity_search_skips_mark_deleted_documents(shard):
+    w, docs, qs, ix, kgs, D, Q, sem, ent, wq, table = shard
+    ix.set_knowledge_graph(kgs, le_cap=16)
+    le, cnt, en_ip, en = [t.cpu().numpy() for t in ix.export_logical_edges()]
+    k, L, w_k, hops = 10, 48, 0.5, 2
+    base_ids, base_sc = [t.cpu().numpy() for t in ix.search_batch_entities(qs, k, L, kgs.q_ent, w_k, hops, wq)]
+    base_counts = ix.search_stats(qs.n)[0].cpu().numpy()
+    rng = np.random.default_rng(8)
+    dele = np.unique(np.concatenate([rng.choice(docs.n, docs.n // 4, replace=False), base_ids[:, 0], base_ids[:, 5]])).astype(np.int32)
+    dele = dele[dele >= 0]
+    _say(f"entity search with {len(dele)} mark-deleted documents")
+    try:
+        ix.mark_deleted(dele)
+        ids, sc = [t.cpu().numpy() for t in ix.search_batch_entities(qs, k, L, kgs.q_ent, w_k, hops, wq)]
+        counts = ix.search_stats(qs.n)[0].cpu().numpy()
+        assert np.array_equal(counts[:, :2], base_counts[:, :2])          # the traversal did not change
+        assert not np.isin(ids[ids >= 0], dele).any()
+        for qi in range(qs.n):
+            oi, os_, _ = O.search_kg(D, sem, ent, Q, qi, wq[qi], k, L, kgs, le, cnt, en_ip, en, kgs.q_ent[qi], w_k,
+                                     max_hops=hops, score_table=table[qi], deleted=dele)
+            assert np.array_equal(ids[qi], oi) and np.array_equal(sc[qi], os_), qi
+    finally:
+        ix.mark_deleted(dele, restore=True)
+    ids, sc = [t.cpu().numpy() for t in ix.search_batch_entities(qs, k, L, kgs.q_ent, w_k, hops, wq)]
+    assert np.array_equal(ids, base_ids) and np.array_equal(sc, base_sc)
+    # an entity id past the last entity is an unused slot, like a negative one
+    qe = kgs.q_ent.copy(); qe[qe < 0] = 400 + 17
+    ids2, sc2 = [t.cpu().numpy() for t in ix.search_batch_entities(qs, k, L, qe, w_k, hops, wq)]
+    assert np.array_equal(ids2, base_ids) and np.array_equal(sc2, base_sc)
 
 
 def test_entity_search_replay(shard):

@@ -176,3 +176,25 @@ def test_python_restatement(small):
             rewarded += sum(1 for a in pann if a[1] > 0)
             via_logical += len(order)
     assert rewarded > 50
+
+
+def test_mark_deleted_documents_are_searched_through_and_left_out(small):
+    """Section 4.1 (updates): with deletions the traversal is the one without them (same documents scored, in the same
+    order), and the answer is the undeleted pool's order with the deleted documents struck out."""
+    w, D, Q, b, kgs, le, lc, en_ip, en, wq, table = small
+    struck = 0
+    for qi in range(Q.n):
+        k, L = 5, 16
+        full, fsc, flog, _ = O.search_kg(D, b.graph, b.entry, Q, qi, wq, L, L, kgs, le, lc, en_ip, en, kgs.q_ent[qi], 0.5,
+                                         score_table=table[qi], log=True)
+        dele = [int(full[0]), int(full[3])] + list(range(0, D.n, 9))
+        ids, sc, log, _ = O.search_kg(D, b.graph, b.entry, Q, qi, wq, k, L, kgs, le, lc, en_ip, en, kgs.q_ent[qi], 0.5,
+                                      score_table=table[qi], log=True, deleted=dele)
+        assert list(log) == list(flog)
+        keep = [(int(i), s) for i, s in zip(full, fsc) if i >= 0 and int(i) not in set(dele)][:k]
+        want = [i for i, _ in keep] + [-1] * (k - len(keep))
+        assert [int(x) for x in ids] == want, qi
+        assert np.array_equal(sc[:len(keep)], np.float32([s for _, s in keep]))
+        assert np.isneginf(sc[len(keep):]).all()
+        struck += sum(1 for i in full[:k] if int(i) in set(dele))
+    assert struck >= 2 * Q.n
