@@ -26,9 +26,11 @@
  *  - Scores are similarities: larger is better (the paper's dis is -score).
  *    Every ranking is by (score descending, id ascending).  A missing result
  *    has id -1 and score -inf.
- *  - CSR rows must hold strictly ascending term ids in [0, vocab).  ids of
- *    documents must fit 30 bits (n < 2^30); the two CSR parts together hold
- *    fewer than 2^32 entries and no list more than 65,535 (else AP_EINVAL).
+ *  - CSR rows must hold strictly ascending term ids in [0, vocab) and finite
+ *    values, with row offsets ascending from 0.  ids of documents must fit 30
+ *    bits (n < 2^30); the two CSR parts together hold fewer than 2^32 entries
+ *    and no list more than 65,535.  A corpus is checked for all of this when
+ *    an index is made from it (AP_EINVAL); query batches are not checked.
  *  - Calls on one index from several host threads at once are not supported
  *    (the search workspace is per index).
  */
@@ -114,7 +116,8 @@ int ap_build_index(const ap_corpus *corpus, const ap_build_params *params, void 
 
 /* Default fusion weights [w_d, w_s, w_f] (host pointer) used by searches that
  * pass no per-query weights.  O(1): the index is never rebuilt for a change of
- * weights (Theorem 1; Section 4.2.1). */
+ * weights (Theorem 1; Section 4.2.1).  A blocking 12-byte copy: call it when
+ * no search that relies on the default weights is still in flight. */
 int ap_set_weights(ap_index *index, const float w[3]);
 
 /* Algorithm 2 on the semantic edges for nq queries at once.  per_query_w is
@@ -240,13 +243,14 @@ int ap_ingest(const ap_corpus *corpus, const ap_build_params *params, void *stre
 int ap_export_ingest(const ap_index *index, float *tx_w, int32_t *df, float *avgdl, float *self_sim, void *stream);
 
 /* Definition 1 for explicit pairs: for query x and its c candidates
- * cand_ids[x*c + y] (document ids, -1 = hole) writes
+ * cand_ids[x*c + y] (document ids; anything outside [0, n) is a hole) writes
  * out4[(x*c + y)*4 + {0,1,2,3}] = sim_d, sim_s, sim_f, M_w (holes: -inf). */
 int ap_hybrid_scores(const ap_index *index, const ap_queries *queries, const int32_t *cand_ids, int32_t c,
                      const float *per_query_w, float *out4, void *stream);
 
 /* Same with documents on the query side (construction's document-document
- * similarities): a_ids[na] document ids, w3 three host floats. */
+ * similarities): a_ids[na] document ids (one outside [0, n) gives a line of
+ * holes), w3 three host floats. */
 int ap_hybrid_scores_docs(const ap_index *index, const int32_t *a_ids, int32_t na, const int32_t *cand_ids,
                           int32_t c, const float w3[3], float *out4, void *stream);
 

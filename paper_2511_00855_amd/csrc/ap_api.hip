@@ -133,6 +133,23 @@ __global__ void k_max_list_len(const int64_t *__restrict__ sp_indptr, const int6
     atomicMax(out, m);
 }
 
+// One CSR part of the corpus as the kernels rely on it: offsets ascending from 0 to the total, term ids strictly
+// ascending within a row and inside the vocabulary, values finite (and, for term counts, not negative).
+__global__ void k_check_csr(const int64_t *__restrict__ ip, const int32_t *__restrict__ idx, const float *__restrict__ val, int64_t n,
+                            int64_t total, int32_t vocab, int counts, int32_t *__restrict__ bad) {
+    for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < n; x += (int64_t)gridDim.x * blockDim.x) {
+        if (!ap_row_ok(ip, x, total)) { atomicAdd(bad, 1); continue; }
+        int32_t wrong = 0;
+        const int64_t b = ip[x], e = ip[x + 1];
+        for (int64_t p = b; p < e; p++) {
+            const int32_t t = idx[p];
+            const float v = val[p];
+            wrong += (t < 0 || t >= vocab || (p > b && idx[p - 1] >= t) || !(v - v == 0.f) || (counts && v < 0.f)) ? 1 : 0;
+        }
+        if (wrong) atomicAdd(bad, wrong);
+    }
+}
+
 __global__ void k_fill_u32(uint32_t *p, size_t n, uint32_t v) {
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
 }
@@ -157,9 +174,22 @@ int ap_ingest_impl(ap_index *ix, hipStream_t st) {
     AP_REQUIRE(last >= 0 && sp_last >= 0, "indptr[n] is negative");
     AP_REQUIRE(last + sp_last < (1ll << 32), "the two CSR parts together must hold fewer than 2^32 entries");
     ix->tx_nnz = last;
+    AP_TRY(ap_dev_alloc(&ix->stats, 4));
+    {
+        int32_t *bad = reinterpret_cast<int32_t *>(ix->stats);
+        AP_TRY(ap_fill_u32(bad, 1, 0, st));
+        const int blocks = (int)std::min<int64_t>((c.n + 255) / 256, 8192);
+        hipLaunchKernelGGL(k_check_csr, dim3(blocks), dim3(256), 0, st, c.sp_indptr, c.sp_idx, c.sp_val, c.n, sp_last, c.sp_vocab, 0, bad);
+        hipLaunchKernelGGL(k_check_csr, dim3(blocks), dim3(256), 0, st, c.tx_indptr, c.tx_idx, c.tx_tf, c.n, last, c.tx_vocab, 1, bad);
+        AP_CHECK_HIP(hipGetLastError());
+        int32_t h = 0;
+        AP_CHECK_HIP(hipMemcpyAsync(&h, bad, sizeof(h), hipMemcpyDeviceToHost, st));
+        AP_CHECK_HIP(hipStreamSynchronize(st));
+        AP_REQUIRE(h == 0, "the corpus CSR is malformed in %d places (row offsets must ascend from 0 to the total; term ids strictly "
+                   "ascending within a row and inside the vocabulary; values finite, term counts not negative)", h);
+    }
     AP_TRY(ap_dev_alloc(&ix->tx_w, (size_t)last));
     AP_TRY(ap_dev_alloc(&ix->df, (size_t)c.tx_vocab));
-    AP_TRY(ap_dev_alloc(&ix->stats, 4));
     AP_TRY(ap_dev_alloc(&ix->self_sim, (size_t)c.n));
     AP_TRY(ap_dev_alloc(&ix->dense_norm, (size_t)c.n));
     AP_TRY(ap_dev_alloc(&ix->w_dev, 4));

@@ -111,6 +111,12 @@ static inline int ap_dev_alloc(T **p, size_t count) {
     return AP_OK;
 }
 
+// CSR row offsets must start at 0, never decrease and end at `total`; a row that fails is not read.
+__device__ __forceinline__ bool ap_row_ok(const int64_t *ip, int64_t x, int64_t total) {
+    const int64_t b = ip[x], e = ip[x + 1];
+    return b >= 0 && e >= b && e <= total && (x > 0 || b == 0);
+}
+
 // The six stage marks of a construction or an insertion; destroyed on every way out.
 struct ApStageEvents {
     hipEvent_t ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};

@@ -17,18 +17,23 @@ __global__ __launch_bounds__(256) void k_hybrid_pairs(ApVecs A, ApVecs B, const 
     __shared__ float l_tx_val[AP_LIST_CAP];
     const int64_t x = blockIdx.x;
     const int64_t row = a_ids ? (int64_t)a_ids[x] : x;
+    const int32_t y0 = blockIdx.y * chunk;
+    const int32_t y1 = y0 + chunk < c ? y0 + chunk : c;
+    if (row < 0 || row >= A.n) {   // not a row of A: the whole line of results is holes (uniform over the workgroup)
+        for (int32_t y = y0 + (int32_t)threadIdx.x; y < y1; y += blockDim.x)
+            *reinterpret_cast<float4 *>(out4 + (x * c + y) * 4) = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+        return;
+    }
     const ApLists a = ap_stage_lists(A, row, l_sp_idx, l_sp_val, l_tx_idx, l_tx_val, AP_LIST_CAP);
     float qa[NV * ApDense<DT>::EPC];
     ap_load_aside<DT, NV, SRC>(A.dense, row, A.dim, qa);
     __syncthreads();
     const float wd = w[x * w_stride + 0], ws = w[x * w_stride + 1], wf = w[x * w_stride + 2];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int32_t y0 = blockIdx.y * chunk;
-    const int32_t y1 = y0 + chunk < c ? y0 + chunk : c;
     for (int32_t y = y0 + wave; y < y1; y += 4) {
         const int32_t j = cand[x * c + y];
         float sd, ss, sf, fu;
-        if (j >= 0) {
+        if (j >= 0 && j < B.n) {
             ap_hybrid_wave<DT, NV>(B, qa, a, j, sd, ss, sf);
             fu = ap_fuse(wd, ws, wf, sd, ss, sf);
         } else {

@@ -20,12 +20,6 @@
 int ap_validate_queries(const ap_queries *q);
 
 // ------------------------------------------------------------------ construction
-// row offsets must start at 0, never decrease and end at `total`; a row that fails is not read
-__device__ __forceinline__ bool ap_row_ok(const int64_t *ip, int64_t x, int64_t total) {
-    const int64_t b = ip[x], e = ip[x + 1];
-    return b >= 0 && e >= b && e <= total && (x > 0 || b == 0);
-}
-
 __global__ void k_ent_count(const int64_t *__restrict__ de_ip, const int32_t *__restrict__ de, int64_t n, int32_t n_ent, int64_t total,
                             unsigned long long *__restrict__ cnt, int32_t *__restrict__ bad) {
     for (int64_t x = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; x < n; x += (int64_t)gridDim.x * blockDim.x) {

@@ -131,3 +131,49 @@ def test_tiny_corpora_and_single_query():
         reached = (ids[0] >= 0).sum()
         assert np.array_equal(ids[0][:reached], gt[0][:reached]) or reached < min(n, 8)
         ix.close()
+
+
+def test_malformed_corpus_is_refused():
+    """A corpus is checked once, when an index is made from it: every kernel relies on ascending ids inside the
+    vocabulary, ascending row offsets and finite values."""
+    _say("edge case: malformed corpora")
+    base = make_workload("tiny", seed=61, n=200, nq=2, dim=16)
+    bp = B.build_params(8, knn_k=16, nd_rounds=1, nd_sample=4, n_entry=4)
+
+    def broken(change):
+        w = make_workload("tiny", seed=61, n=200, nq=2, dim=16)
+        change(w.docs)
+        return B.DeviceVecs(w.docs)
+
+    def swap(v):          # two neighbouring ids of one row out of order
+        r = int(np.argmax(np.diff(v.sp_indptr) >= 2)); p = v.sp_indptr[r]
+        v.sp_idx[p], v.sp_idx[p + 1] = v.sp_idx[p + 1], v.sp_idx[p]
+
+    def repeat(v):        # a repeated term
+        r = int(np.argmax(np.diff(v.tx_indptr) >= 2)); p = v.tx_indptr[r]
+        v.tx_idx[p + 1] = v.tx_idx[p]
+
+    def past_vocab(v): v.tx_idx[v.tx_indptr[3 + 1] - 1] = v.tx_vocab
+    def negative_id(v): v.sp_idx[v.sp_indptr[7]] = -2
+    def nan_value(v): v.sp_val[5] = np.nan
+    def negative_count(v): v.tx_val[9] = -1.0
+    def offsets_back(v): v.sp_indptr[10] = v.sp_indptr[9] - 1
+    def offsets_past(v): v.tx_indptr[20] = v.tx_indptr[-1] + 3
+    def offsets_start(v): v.tx_indptr[0] = 1
+
+    for change in (swap, repeat, past_vocab, negative_id, nan_value, negative_count, offsets_back, offsets_past, offsets_start):
+        with pytest.raises(RuntimeError, match="malformed"):
+            B.Index.build(broken(change), bp)
+        with pytest.raises(RuntimeError, match="malformed"):
+            B.Index.ingest(broken(change), bp)
+    # the untouched corpus builds, and ids outside the corpus are holes for the explicit-pair scorer
+    docs = B.DeviceVecs(base.docs); qs = B.DeviceVecs(base.queries)
+    ix = B.Index.build(docs, bp)
+    cand = np.array([[0, 200, -1, 199, 1 << 30], [-5, 3, 200, 4, 5]], np.int32)
+    got = ix.hybrid_scores(qs, cand, np.ones((2, 3), np.float32)).cpu().numpy()
+    hole = (cand < 0) | (cand >= 200)
+    assert np.isneginf(got[hole]).all() and np.isfinite(got[~hole]).all()
+    gd = ix.hybrid_scores_docs(np.array([5, 200, -1], np.int32), np.tile(np.arange(4, dtype=np.int32), (3, 1)),
+                               np.ones(3, np.float32)).cpu().numpy()
+    assert np.isfinite(gd[0]).all() and np.isneginf(gd[1:]).all()
+    ix.close()
