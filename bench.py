@@ -83,6 +83,41 @@ def keyword_leg(args, w, ix, qs, wq, k, chosen):
     return dict(required_terms="1-2 of each query's own text tokens, any-match", sampled_queries=len(sample), sweep=out)
 
 
+WEIGHT_SETTINGS = ((1.0, 0.0, 0.0), (0.0, 1.0, 0.0), (0.0, 0.0, 1.0), (0.5, 0.5, 0.0), (0.34, 0.33, 0.33))
+
+
+def weights_leg(args, ix, qs, k):
+    """Dynamic fusion (Theorem 1; Section 4.2.1): the same index, never rebuilt, searched under five other weight
+    settings; per setting the exact top-k under those weights, then beams upward until the recall target."""
+    import numpy as np
+    import torch
+    nq = qs.n
+    out = []
+    for wv in WEIGHT_SETTINGS:
+        wq = torch.from_numpy(np.tile(np.float32(wv), (nq, 1))).to("cuda:0")
+        gt = ix.bruteforce_topk(qs, k, wq)[0].cpu().numpy()
+        rows, hit = [], None
+        for beam in sorted(int(b) for b in args.weight_beams.split(",")):
+            ix.search_batch(qs, k, beam, wq)
+            torch.cuda.synchronize()
+            t1 = time.time()
+            ids, _ = ix.search_batch(qs, k, beam, wq)
+            torch.cuda.synchronize()
+            dt = time.time() - t1
+            rec = recall_at_k(ids.cpu().numpy(), gt)
+            counts, kms = ix.search_stats(nq)
+            rows.append(dict(beam=beam, recall=round(rec, 4), qps=round(nq / dt, 1), kernel_ms=round(kms, 3),
+                             dists_per_query=round(int(counts[:, 0].sum().item()) / nq, 1)))
+            if rec >= args.target_recall:
+                hit = rows[-1]
+                break
+        out.append(dict(weights=wv, at_target=hit, sweep=rows))
+        last = rows[-1]
+        log(f"[bench] weights {wv}: " + (f"recall {hit['recall']:.4f} at beam {hit['beam']}, {hit['qps']:,.0f} qps" if hit else
+                                         f"target not reached; beam {last['beam']}: recall {last['recall']:.4f}, {last['qps']:,.0f} qps"))
+    return out
+
+
 def insert_leg(args, w, bp, docs, qs, wq, k, gt, sweep, build_s, bf16):
     """Insertion (Section 4.1, updates): an index over the first (1-f) of the corpus receives the last f; the
     updated index is searched at the beams of the main sweep, against the same ground truth as the rebuild."""
@@ -131,7 +166,10 @@ def main():
     ap.add_argument("--n", type=int, default=None, help="override the number of documents (smaller rehearsal)")
     ap.add_argument("--nq", type=int, default=None)
     ap.add_argument("--rounds", type=int, default=3)
-    ap.add_argument("--beams", default="128,256,512,1024,1536,2048,2112,2144,2176,2240,2304,2560,3072,4096")
+    ap.add_argument("--beams", default="128,256,512,1024,1536,2048,2112,2144,2176,2240,2304,2560,3072,4096,6144,8192,12288,16384")
+    ap.add_argument("--weight-sweep", action="store_true",
+                    help="also search the same index under five other weight settings (dynamic fusion, no rebuild)")
+    ap.add_argument("--weight-beams", default="128,512,1024,1536,2048,2304,2560,2816,3072,3584,4096,4608,5120,5632,6144,8192,12288,16384")
     ap.add_argument("--beam", type=int, default=0, help="fix the beam (skips the sweep; for profiling runs)")
     ap.add_argument("--target-recall", type=float, default=0.95)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -283,6 +321,7 @@ def main():
 
     kw_report = keyword_leg(args, w, ix, qs, wq, k, chosen) if args.keywords else None
     ins_report = insert_leg(args, w, bp, docs, qs, wq, k, gt, sweep, build_s, bf16) if args.insert > 0 else None
+    ws_report = weights_leg(args, ix, qs, k) if args.weight_sweep else None
 
     # ---- CPU baseline: the oracle as it stands, one thread, bounded sample of the same searches
     cpu = None
@@ -342,6 +381,8 @@ def main():
         line["keyword_search"] = kw_report
     if ins_report is not None:
         line["insertion"] = ins_report
+    if ws_report is not None:
+        line["dynamic_fusion"] = ws_report
     print(json.dumps(line), flush=True)
     ix.close()
 

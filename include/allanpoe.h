@@ -100,9 +100,11 @@ typedef struct {
     const int64_t *tx_indptr; const int32_t *tx_idx; const float *tx_cnt;
 } ap_queries;
 
+#define AP_MAX_BEAM 16384
 typedef struct {
     int32_t k;            /* results per query; k <= beam */
-    int32_t beam;         /* L: candidate pool capacity; <= 4096 */
+    int32_t beam;         /* L: candidate pool capacity; <= AP_MAX_BEAM, as far as the pool (8 bytes per entry) and the
+                             call's other per-query arrays fit a workgroup's 160 KB of LDS (else AP_EINVAL) */
     int32_t max_iters;    /* 0 = until the pool is fully expanded */
     int32_t search_width; /* p: pool entries expanded per iteration; 1..8 */
 } ap_search_params;

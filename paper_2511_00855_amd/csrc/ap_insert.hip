@@ -113,7 +113,7 @@ static int insert_impl(const ap_index *old, ap_index *nx, int32_t beam, const ap
         qd = qdense;
     }
     {
-        const int32_t L = std::min<int32_t>(4096, std::max<int32_t>(beam > 0 ? beam : 2 * K, K));
+        const int32_t L = std::min<int32_t>(AP_MAX_BEAM, std::max<int32_t>(beam > 0 ? beam : 2 * K, K));
         const size_t words = ((size_t)n1 + 31) / 32;
         const int64_t step = std::max<int64_t>(1, (int64_t)(((size_t)1 << 28) / words));   // at most 1 GiB of visited bits per launch
         for (int64_t q0 = 0; q0 < m; q0 += step) {
@@ -264,7 +264,7 @@ extern "C" int ap_insert_documents(const ap_index *old, const ap_corpus *enlarge
     AP_REQUIRE(enlarged->dim == old->corpus.dim && enlarged->dense_dtype == old->corpus.dense_dtype &&
                enlarged->sp_vocab == old->corpus.sp_vocab && enlarged->tx_vocab == old->corpus.tx_vocab,
                "the enlarged corpus must keep dimension, dense type and vocabularies");
-    AP_REQUIRE(beam >= 0 && beam <= 4096, "beam = %d must be in [0, 4096] (0 = twice the list length)", beam);
+    AP_REQUIRE(beam >= 0 && beam <= AP_MAX_BEAM, "beam = %d must be in [0, %d] (0 = twice the list length)", beam, AP_MAX_BEAM);
     ap_index *nx = new (std::nothrow) ap_index();
     if (!nx) { ap_set_error("out of host memory"); return AP_ENOMEM; }
     nx->corpus = *enlarged;

@@ -419,7 +419,7 @@ extern "C" int ap_search_batch_entities(ap_index *ix, const ap_queries *q, const
     if (!ix->kg_le) { ap_set_error("no knowledge graph was set on this index (ap_set_knowledge_graph)"); return AP_ESTATE; }
     AP_REQUIRE(q->nq == 0 || (q_ent && out_ids && out_scores), "NULL argument");
     AP_REQUIRE(ent_stride >= 1 && ent_stride <= 16, "ent_stride = %d must be in [1, 16]", ent_stride);
-    AP_REQUIRE(p->beam >= 1 && p->beam <= 4096, "beam = %d must be in [1, 4096]", p->beam);
+    AP_REQUIRE(p->beam >= 1 && p->beam <= AP_MAX_BEAM, "beam = %d must be in [1, %d]", p->beam, AP_MAX_BEAM);
     AP_REQUIRE(p->k >= 1 && p->k <= p->beam, "k = %d must be in [1, beam]", p->k);
     AP_REQUIRE(p->search_width == 1, "the knowledge-graph search expands one parent per iteration (search_width = 1)");
     AP_REQUIRE(p->max_iters >= 0, "max_iters must be >= 0");

@@ -465,7 +465,7 @@ static int ap_search_launch(ap_index *ix, const ApVecs &Q, const float *w_dev, i
     const int32_t nq = (int32_t)Q.n;
     if (!ix->has_graph) { ap_set_error("index has no graph: build or import one first"); return AP_ESTATE; }
     AP_REQUIRE(nq == 0 || (out_ids && out_scores), "NULL output");
-    AP_REQUIRE(beam >= 1 && beam <= 4096, "beam = %d must be in [1, 4096]", beam);
+    AP_REQUIRE(beam >= 1 && beam <= AP_MAX_BEAM, "beam = %d must be in [1, %d]", beam, AP_MAX_BEAM);
     AP_REQUIRE(k >= 1 && k <= beam, "k = %d must be in [1, beam]", k);
     AP_REQUIRE(width >= 1 && width <= 8, "search_width = %d must be in [1, 8]", width);
     AP_REQUIRE(max_iters >= 0, "max_iters must be >= 0");
@@ -515,8 +515,8 @@ static int ap_search_launch(ap_index *ix, const ApVecs &Q, const float *w_dev, i
     g.nxtw = g.cmax > 256 ? g.cmax : 0;
     const size_t smem = (size_t)(g.L + 2 * g.cmax + g.nxtw + (kw ? g.cmax + g.k : 0)) * 8 + (size_t)g.cmax * (16 + 4) +
                         (size_t)(big_tables ? ApQTab<true>::SLOTS : ApQTab<false>::SLOTS) * 8 + 8;
-    AP_CHECK_HIP(hipEventRecord(ix->ev_search[0], st));
     AP_REQUIRE(smem <= 160 * 1024, "beam and search_width need %zu bytes of LDS (limit 160 KiB)", smem);
+    AP_CHECK_HIP(hipEventRecord(ix->ev_search[0], st));
     hipError_t le = hipSuccess;
 #define AP_LAUNCH_SEARCH(KWF, BIGF)                                                                                          \
     AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim, {                                                                              \

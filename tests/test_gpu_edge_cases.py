@@ -177,3 +177,23 @@ def test_malformed_corpus_is_refused():
                                np.ones(3, np.float32)).cpu().numpy()
     assert np.isfinite(gd[0]).all() and np.isneginf(gd[1:]).all()
     ix.close()
+
+
+def test_pools_beyond_64_kb_of_lds():
+    """Beams of 8192 and 16384 (pools of 64 and 128 KB, one workgroup per CU) replayed by the oracle, on a corpus
+    larger than the pool."""
+    _say("edge case: beams 8192 and 16384")
+    w = make_workload("tiny", seed=71, n=24000, nq=4, dim=32)
+    docs = B.DeviceVecs(w.docs); qs = B.DeviceVecs(w.queries)
+    ix = B.Index.build(docs, B.build_params(16, knn_k=32, nd_rounds=1, nd_sample=8, n_entry=16))
+    D = O.encode_docs(w.docs); Q = O.VS(w.queries)
+    sem, _, _, ent = [t.cpu().numpy() for t in ix.export_graph()]
+    wq = np.tile(np.float32(w.weights), (qs.n, 1))
+    for (k, L, width) in ((10, 8192, 1), (100, 16384, 1), (10, 12000, 4)):
+        _say(f"  beam {L}, width {width}")
+        _replay_search(ix, docs, qs, w, D, Q, sem, ent, wq, k, L, 0, width)
+    counts = ix.search_stats(qs.n)[0].cpu().numpy()
+    assert (counts[:, 0] > 12000).all()          # the pool did fill
+    with pytest.raises(RuntimeError, match="beam"):
+        ix.search_batch(qs, 10, 16385, wq)
+    ix.close()

@@ -211,4 +211,4 @@ def test_insert_argument_checks(grown):
     with pytest.raises(RuntimeError, match="nothing to insert"):
         new.insert(old.docs)
     with pytest.raises(RuntimeError):
-        old.insert(all_docs, beam=5000)
+        old.insert(all_docs, beam=20000)
