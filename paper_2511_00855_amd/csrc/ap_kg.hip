@@ -293,6 +293,7 @@ __global__ __launch_bounds__(256) void k_search_kg(ApKgArgs g) {
         __syncthreads();
     }
     int32_t len = 0, it = 0, nscored = 0;   // len is kept by wave 0, the only one that touches the pool
+    int32_t fu = 0;                          // (wave 0) every pool entry before this position has been expanded
     for (;;) {
         const int32_t c = s_cnt;
         nscored += c;
@@ -345,15 +346,17 @@ __global__ __launch_bounds__(256) void k_search_kg(ApKgArgs g) {
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
                 len = len < g.L ? len + 1 : g.L;
+                fu = fu < pos ? fu : pos;
             }
             // the best entry not yet expanded becomes the parent
             int32_t found = -1;
             if (!(g.max_iters > 0 && it >= g.max_iters)) {
-                for (int32_t base = 0; base < len && found < 0; base += 64) {
+                for (int32_t base = fu & ~63; base < len && found < 0; base += 64) {
                     const int32_t i = base + lane;
                     const uint64_t mask = __ballot(i < len && (cur[i] & 1ull));
                     if (mask) found = base + (int32_t)__builtin_ctzll(mask);
                 }
+                fu = found >= 0 ? found + 1 : len;
             }
             if (lane == 0) {
                 if (found >= 0) { s_par = ap_key_id(cur[found]); s_pann = (int32_t)cura[found]; cur[found] &= ~1ull; }

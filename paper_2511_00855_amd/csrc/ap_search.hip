@@ -23,7 +23,7 @@ struct ApSearchArgs {
     const float *w;     // per query (stride 3) or the index default (stride 0)
     int32_t w_stride;
     int32_t R, E, k, L, max_iters, width, cmax;
-    int32_t nxtw;       // words of the scratch that parks positions when more than 256 keys enter at once (0 when cmax <= 256)
+    int32_t nxtw;       // words of the scratch that parks positions when more keys enter at once than the workgroup has threads (else 0)
     uint32_t *visited;
     size_t words;       // visited words per query
     int32_t *out_ids;
@@ -62,7 +62,7 @@ __device__ __forceinline__ int32_t ap_rank_in(const uint64_t *keys, int32_t n, u
     return lo;
 }
 
-// Scores the c candidates of this iteration; wave w takes candidates w, w+4, ...
+// Scores the c candidates of this iteration; wave w of the workgroup's NW takes candidates w, w+NW, ...
 // The sparse and lexical parts (the short segments) are evaluated first.  When
 // the pool is full and even the largest dense part the norms allow,
 // |w_d| |q_d| |d_d|, could not lift the candidate past the pool's last entry,
@@ -86,7 +86,7 @@ template <bool BIG> struct ApQTab {
 // terms (s_kw[0..n_kw)); the key of a candidate that satisfies the constraint
 // carries the "satisfies" flag, and its dense row may only be skipped when the
 // bound also rules out the secondary pool (full, and its last score above the bound).
-template <int DT, int NV, bool TAB, bool KW, bool BIG>
+template <int DT, int NV, bool TAB, bool KW, bool BIG, int NW>
 __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const uint2 *rec, const float *qa, const uint64_t *qtab,
                                                        const ApLists &a, float wd, float ws, float wf, float qnorm, bool pool_full,
                                                        float worst_score, const int32_t *cand, const uint4 *s_meta, int32_t c,
@@ -95,7 +95,7 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const ui
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int32_t skipped = 0;
     constexpr int G = AP_SEARCH_G;   // candidates whose list segments are in flight together
-    for (int32_t i0 = wave; i0 < c; i0 += 4 * G) {
+    for (int32_t i0 = wave; i0 < c; i0 += NW * G) {
         int32_t si[G][2], ti[G][1];
         float sv[G][2], tv[G][1];
         const uint2 *r[G];
@@ -103,7 +103,7 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const ui
         float dn[G];
 #pragma unroll
         for (int gi = 0; gi < G; gi++) {
-            const int32_t i = i0 + 4 * gi;
+            const int32_t i = i0 + NW * gi;
             if (i < c) {
                 const uint4 m = s_meta[i];
                 // the descriptor is the same in every lane: keep the record's address in scalar registers
@@ -116,7 +116,7 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const ui
         }
 #pragma unroll
         for (int gi = 0; gi < G; gi++) {
-            const int32_t i = i0 + 4 * gi;
+            const int32_t i = i0 + NW * gi;
             if (i >= c) continue;
             const int32_t v = __builtin_amdgcn_readfirstlane(cand[i]);
             float ss, sf;
@@ -155,11 +155,26 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const ui
     return skipped;
 }
 
+// NT threads per workgroup.  256 (four waves) is the usual size: seven workgroups share a CU while the pool is small
+// enough, and the register budget is the 72 VGPRs of seven waves per SIMD.  When the pool is so large that the LDS
+// holds four workgroups or fewer, 512 or 1024 threads keep the CU's SIMDs occupied with one query's candidates.
 #ifndef AP_SEARCH_WAVES_PER_SIMD
 #define AP_SEARCH_WAVES_PER_SIMD 7
 #endif
-template <int DT, int NV, bool KW, bool BIG>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_WAVES_PER_SIMD, 8))) void k_search(ApSearchArgs g) {
+#ifndef AP_SEARCH_NT512_AT
+#define AP_SEARCH_NT512_AT 4    // workgroups of 256 threads a CU's LDS holds at or below which 512 threads are used
+#endif
+#ifndef AP_SEARCH_NT1024_AT
+#define AP_SEARCH_NT1024_AT 1   // ... and 1024 threads
+#endif
+// Wide bf16 rows (more than 1024 columns: 24 or 32 query values per lane) do not fit seven waves' registers without
+// spilling; they run at five waves per SIMD.
+template <int DT, int NV, int NT> struct ApSearchWaves {
+    static constexpr int MIN = (DT == AP_BF16 && NV >= 3) ? (NT == 1024 ? 4 : 5) : NT == 256 ? AP_SEARCH_WAVES_PER_SIMD : NT == 512 ? 6 : 4;
+};
+template <int DT, int NV, bool KW, bool BIG, int NT>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(ApSearchWaves<DT, NV, NT>::MIN, 8)))
+void k_search(ApSearchArgs g) {
     extern __shared__ __attribute__((aligned(16))) uint64_t smem64[];   // 16-byte aligned: the descriptors are read as uint4
     uint64_t *cur = smem64;                  // the pool: L keys, best first
     uint64_t *newk = cur + g.L;              // keys of this iteration's candidates, unordered
@@ -238,6 +253,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
     }
     __syncthreads();
     int32_t len = 0, it = 0, nscored = 0, nskipped = 0;
+    int32_t fu = 0;   // every pool entry before this position has been expanded
     for (;;) {
         const int32_t c = s_cnt;
         nscored += c;
@@ -247,10 +263,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
         const bool second_full = kw_on && s_kc == g.k;   // s_kc and kwc were last written before the previous barriers
         const float second_worst = second_full ? ap_key_score(kwc[g.k - 1]) : 0.f;
         if (use_tab)
-            nskipped += ap_score_candidates<DT, NV, true, KW, BIG>(g.D, g.rec, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score, cand,
+            nskipped += ap_score_candidates<DT, NV, true, KW, BIG, NT / 64>(g.D, g.rec, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score, cand,
                                                               s_meta, c, newk, s_kw, n_kw, g.kw_all != 0, second_full, second_worst);
         else
-            nskipped += ap_score_candidates<DT, NV, false, KW, BIG>(g.D, g.rec, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score, cand,
+            nskipped += ap_score_candidates<DT, NV, false, KW, BIG, NT / 64>(g.D, g.rec, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score, cand,
                                                                s_meta, c, newk, s_kw, n_kw, g.kw_all != 0, second_full, second_worst);
         __syncthreads();
         // sort the new keys by ranking them among themselves; only those that
@@ -273,21 +289,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
         if (cin > 0) {
             // In-place rank merge.  A pool entry at position t moves up by the number of entering keys that rank
             // before it, so only entries from the first insertion point on move, and they only move towards the
-            // end: chunks of 512 entries are read, then written, from the back of the pool to the front.
+            // end: chunks of 2 NT entries are read, then (one barrier later) written, from the back of the pool to the
+            // front.  A chunk's writes never reach below its own start, so they need not be fenced from the reads of
+            // the chunk before it; the barrier of that chunk orders them before its writes.
             const int32_t rmin = ap_rank_in(cur, len, newS[0]);
+            fu = fu < rmin ? fu : rmin;   // the best entering key lands at rmin, unexpanded; entries before it stay put
             uint64_t nkey = 0; int32_t npos = g.L;
             if ((int32_t)threadIdx.x < cin) { nkey = newS[threadIdx.x]; npos = (int32_t)threadIdx.x + ap_rank_in(cur, len, nkey); }
-            for (int32_t t = (int32_t)threadIdx.x + 256; t < cin; t += 256) {   // more than 256 entering keys (wide searches)
+            for (int32_t t = (int32_t)threadIdx.x + NT; t < cin; t += NT) {   // more entering keys than threads (wide searches)
                 const uint64_t key = newS[t];
                 nxt[t] = (uint64_t)(uint32_t)(t + ap_rank_in(cur, len, key));   // park the positions in the scratch array
             }
             __syncthreads();
-            for (int32_t hi = len; hi > rmin; hi -= 512) {
-                const int32_t lo = hi - 512 > rmin ? hi - 512 : rmin;
+            for (int32_t hi = len; hi > rmin; hi -= 2 * NT) {
+                const int32_t lo = hi - 2 * NT > rmin ? hi - 2 * NT : rmin;
                 uint64_t held[2]; int32_t dest[2];
 #pragma unroll
                 for (int m = 0; m < 2; m++) {
-                    const int32_t t = lo + (int32_t)threadIdx.x + 256 * m;
+                    const int32_t t = lo + (int32_t)threadIdx.x + NT * m;
                     dest[m] = g.L;
                     if (t < hi) { held[m] = cur[t]; dest[m] = t + ap_rank_in(newS, cin, held[m]); }
                 }
@@ -295,13 +314,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
 #pragma unroll
                 for (int m = 0; m < 2; m++) {
                     if (dest[m] < g.L) cur[dest[m]] = held[m];
-                    else if (kw_on && lo + (int32_t)threadIdx.x + 256 * m < hi && (held[m] & 2ull)) xk[atomicAdd(&s_xn, 1)] = held[m];   // evicted
+                    else if (kw_on && lo + (int32_t)threadIdx.x + NT * m < hi && (held[m] & 2ull)) xk[atomicAdd(&s_xn, 1)] = held[m];   // evicted
                 }
-                __syncthreads();
+                // no barrier here: these writes land at or after `lo`, the next chunk's reads come before it
             }
             if (npos < g.L) cur[npos] = nkey;
             else if (kw_on && (int32_t)threadIdx.x < cin && (nkey & 2ull)) xk[atomicAdd(&s_xn, 1)] = nkey;
-            for (int32_t t = (int32_t)threadIdx.x + 256; t < cin; t += 256) {
+            for (int32_t t = (int32_t)threadIdx.x + NT; t < cin; t += NT) {
                 const int32_t r = (int32_t)(uint32_t)nxt[t];
                 if (r < g.L) cur[r] = newS[t];
                 else if (kw_on && (newS[t] & 2ull)) xk[atomicAdd(&s_xn, 1)] = newS[t];
@@ -353,19 +372,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(AP_SEARCH_W
         if (g.max_iters > 0 && it >= g.max_iters) break;
         // S8: pick the best `width` unexpanded entries (wave 0), mark them expanded
         if (wave == 0) {
-            int32_t found = 0;
-            for (int32_t base = 0; base < len && found < g.width; base += 64) {
+            int32_t found = 0, last = -1;
+            for (int32_t base = fu & ~63; base < len && found < g.width; base += 64) {   // the scan starts where it can first succeed
                 const int32_t i = base + lane;
                 const bool un = i < len && (cur[i] & 1ull);
                 const uint64_t mask = __ballot(un);
                 const int32_t rank = __popcll(mask & ((1ull << lane) - 1ull));
-                if (un && found + rank < g.width) {
+                const bool take = un && found + rank < g.width;
+                if (take) {
                     s_par[found + rank] = ap_pool_id<KW>(cur[i]);
                     if (KW) s_psat[found + rank] = (int32_t)((cur[i] >> 1) & 1ull);
                     cur[i] &= ~1ull;
                 }
+                const uint64_t tmask = __ballot(take);
+                if (tmask) last = base + 63 - (int32_t)__builtin_clzll(tmask);
                 found += __popcll(mask);
             }
+            fu = last >= 0 ? last + 1 : len;   // everything up to the last entry taken is expanded now
             if (lane == 0) { s_np = found < g.width ? found : g.width; s_cnt = 0; }
         }
         __syncthreads();
@@ -512,22 +535,36 @@ static int ap_search_launch(ap_index *ix, const ApVecs &Q, const float *w_dev, i
     g.deleted = ix->deleted;
     ix->last_nq = nq;
     AP_TRY(ap_fill_u32(ix->visited, need, 0u, st));
-    g.nxtw = g.cmax > 256 ? g.cmax : 0;
-    const size_t smem = (size_t)(g.L + 2 * g.cmax + g.nxtw + (kw ? g.cmax + g.k : 0)) * 8 + (size_t)g.cmax * (16 + 4) +
-                        (size_t)(big_tables ? ApQTab<true>::SLOTS : ApQTab<false>::SLOTS) * 8 + 8;
+    auto lds_bytes = [&](int32_t nt) {
+        const int32_t nxtw = g.cmax > nt ? g.cmax : 0;
+        return (size_t)(g.L + 2 * g.cmax + nxtw + (kw ? g.cmax + g.k : 0)) * 8 + (size_t)g.cmax * (16 + 4) +
+               (size_t)(big_tables ? ApQTab<true>::SLOTS : ApQTab<false>::SLOTS) * 8 + 8;
+    };
+    // Workgroup size (plain search): four waves as long as the LDS holds at least five workgroups per CU; a pool
+    // that leaves room for two to four gets eight waves, one that fills the CU alone sixteen (measured: each is the
+    // fastest in its range).
+    int32_t nt = 256;
+    if (!kw && !big_tables) {
+        const size_t per_cu = (size_t)160 * 1024 / lds_bytes(256);
+        nt = per_cu > AP_SEARCH_NT512_AT ? 256 : per_cu > AP_SEARCH_NT1024_AT ? 512 : 1024;
+    }
+    g.nxtw = g.cmax > nt ? g.cmax : 0;
+    const size_t smem = lds_bytes(nt);
     AP_REQUIRE(smem <= 160 * 1024, "beam and search_width need %zu bytes of LDS (limit 160 KiB)", smem);
     AP_CHECK_HIP(hipEventRecord(ix->ev_search[0], st));
     hipError_t le = hipSuccess;
-#define AP_LAUNCH_SEARCH(KWF, BIGF)                                                                                          \
-    AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim, {                                                                              \
-        if (smem > 48 * 1024)                                                                                                 \
-            le = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_search<DT, NV, KWF, BIGF>),                            \
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);                                  \
-        if (le == hipSuccess) hipLaunchKernelGGL((k_search<DT, NV, KWF, BIGF>), dim3((unsigned)nq), dim3(256), smem, st, g); \
+#define AP_LAUNCH_SEARCH(KWF, BIGF, NTF)                                                                                         \
+    AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim, {                                                                                  \
+        if (smem > 48 * 1024)                                                                                                     \
+            le = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_search<DT, NV, KWF, BIGF, NTF>),                           \
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);                                      \
+        if (le == hipSuccess) hipLaunchKernelGGL((k_search<DT, NV, KWF, BIGF, NTF>), dim3((unsigned)nq), dim3(NTF), smem, st, g); \
     })
-    if (kw) AP_LAUNCH_SEARCH(true, false);
-    else if (big_tables) AP_LAUNCH_SEARCH(false, true);
-    else AP_LAUNCH_SEARCH(false, false);
+    if (kw) AP_LAUNCH_SEARCH(true, false, 256);
+    else if (big_tables) AP_LAUNCH_SEARCH(false, true, 256);
+    else if (nt == 256) AP_LAUNCH_SEARCH(false, false, 256);
+    else if (nt == 512) AP_LAUNCH_SEARCH(false, false, 512);
+    else AP_LAUNCH_SEARCH(false, false, 1024);
 #undef AP_LAUNCH_SEARCH
     AP_CHECK_HIP(le);
     AP_CHECK_HIP(hipGetLastError());

@@ -197,3 +197,39 @@ def test_pools_beyond_64_kb_of_lds():
     with pytest.raises(RuntimeError, match="beam"):
         ix.search_batch(qs, 10, 16385, wq)
     ix.close()
+
+
+@pytest.mark.parametrize("dim,bf16", [(1536, True), (2048, True), (1024, False), (8, True)])
+def test_widest_and_narrowest_dense_rows(dim, bf16):
+    """The widest rows each storage type allows (24 or 32 query values per lane), and the narrowest bf16 row: scores
+    against the oracle, the build's stages chained, and the search replayed."""
+    _say(f"edge case: dim {dim} bf16={bf16}")
+    w = make_workload("tiny", seed=81, n=500, nq=8, dim=dim, bf16=bf16)
+    docs = B.DeviceVecs(w.docs, bf16=bf16); qs = B.DeviceVecs(w.queries)
+    bp = B.build_params(8, knn_k=16, nd_rounds=1, nd_sample=4, n_entry=8)
+    ix = B.Index.build(docs, bp)
+    D = O.encode_docs(w.docs); Q = O.VS(w.queries)
+    N, nq = docs.n, qs.n
+    wq = np.random.default_rng(3).uniform(0.1, 1.0, (nq, 3)).astype(np.float32)
+    allc = np.tile(np.arange(N, dtype=np.int32), (nq, 1))
+    got = ix.hybrid_scores(qs, allc, wq).cpu().numpy()
+    ref = O.hybrid_block(Q, np.arange(nq), D, allc, wq)
+    tol = score_tol(ref, wq[:, None, :], row_norms(w.queries)[:, None], row_norms(w.docs)[None, :], RTOL_F32)
+    assert_scores_close(got, ref, tol, f"dim {dim}")
+    sem, _, _, ent = [t.cpu().numpy() for t in ix.export_graph()]
+    for (k, L, iters, width) in ((5, 16, 0, 1), (8, 64, 0, 2), (10, 300, 0, 1)):
+        _replay_search(ix, docs, qs, w, D, Q, sem, ent, wq, k, L, iters, width)
+    # keyword search runs another instantiation of the same kernel
+    from paper_2511_00855_amd.synth import make_keywords
+    kw = make_keywords(w.queries, seed=4, max_terms=2, stride=2, p_none=0.2)
+    table = ix.hybrid_scores(qs, allc, wq).cpu().numpy()[:, :, 3]
+    _, ke, kc, _ = [t.cpu().numpy() for t in ix.export_graph()]
+    kids, ksc = [t.cpu().numpy() for t in ix.search_batch_keywords(qs, 5, 32, kw, wq)]
+    for qi in range(nq):
+        terms = [int(t) for t in kw[qi] if t >= 0]
+        oi, os_, _ = O.search_kw(D, sem, ke, kc, ent, Q, qi, wq[qi], 5, 32, terms, score_table=table[qi])
+        assert np.array_equal(kids[qi], oi) and np.array_equal(ksc[qi], os_), qi
+    gt = ix.bruteforce_topk(qs, 5, wq)[0].cpu().numpy()
+    oi = np.stack([O.bruteforce_topk(Q, [qi], D, wq[qi], 5)[0][0] for qi in range(nq)])
+    assert (gt == oi).mean() > 0.97
+    ix.close()

@@ -152,7 +152,7 @@ def test_search_edge_cases(tiny):
     with pytest.raises(B.ApError):
         ix.search_batch(qs, 10, 5)          # k > beam
     with pytest.raises(B.ApError):
-        ix.search_batch(qs, 10, 8192)
+        ix.search_batch(qs, 10, 16385)
     with pytest.raises(B.ApError):
         ix.search_batch(qs, 10, 64, search_width=9)
     ing = B.Index.ingest(docs, B.build_params(w.degree))
