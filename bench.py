@@ -162,7 +162,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="cfg2", help="cfg2 (default), tiny, cfg3")
+    ap.add_argument("--workload", default="cfg2", help="cfg2 (default), tiny, cfg3, cfg5")
     ap.add_argument("--n", type=int, default=None, help="override the number of documents (smaller rehearsal)")
     ap.add_argument("--nq", type=int, default=None)
     ap.add_argument("--rounds", type=int, default=3)
@@ -196,11 +196,12 @@ def main():
     from paper_2511_00855_amd import binding as B
     from paper_2511_00855_amd.synth import make_workload
 
+    os.environ.setdefault("ALLANPOE_PROGRESS", "1")   # a build of millions of documents reports on stderr as it goes
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     B.lib()   # fail loudly if the HIP library is not built
 
     t0 = time.time()
-    w = make_workload(args.workload, seed=0, n=args.n, nq=args.nq)
+    w = make_workload(args.workload, seed=0, n=args.n, nq=args.nq, progress=lambda m: log(f"[bench] generating: {m}"))
     cfg = w.extra["config"]
     bf16 = bool(cfg["bf16"])
     log(f"[bench] workload {args.workload}: n={w.docs.n} nq={w.queries.n} dim={w.docs.dim} bf16={bf16} "

@@ -31,6 +31,8 @@
  *    bits (n < 2^30); the two CSR parts together hold fewer than 2^32 entries
  *    and no list more than 65,535.  A corpus is checked for all of this when
  *    an index is made from it (AP_EINVAL); query batches are not checked.
+ *  - With ALLANPOE_PROGRESS set in the environment, ap_build_index reports on
+ *    stderr how far its seed stage has come (minutes on millions of documents).
  *  - Calls on one index from several host threads at once are not supported
  *    (the search workspace is per index).
  */

@@ -1,6 +1,8 @@
 // Index lifetime, argument validation, S0 (lexical encoding) and the graph
 // import/export calls of the C ABI.
 #include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 #include <new>
 #include <algorithm>
@@ -16,6 +18,20 @@ void ap_set_error(const char *fmt, ...) {
 }
 
 extern "C" const char *ap_last_error(void) { return g_err; }
+
+// Long steps of a construction report where they are on stderr when ALLANPOE_PROGRESS is set in the environment
+// (a corpus of millions of documents spends minutes in the seed stage).
+void ap_progress(const char *fmt, ...) {
+    static const bool on = getenv("ALLANPOE_PROGRESS") != nullptr;
+    if (!on) return;
+    va_list ap;
+    va_start(ap, fmt);
+    fputs("[allanpoe] ", stderr);
+    vfprintf(stderr, fmt, ap);
+    fputc('\n', stderr);
+    fflush(stderr);
+    va_end(ap);
+}
 
 int ap_validate_corpus(const ap_corpus *c) {
     AP_REQUIRE(c != nullptr, "corpus is NULL");

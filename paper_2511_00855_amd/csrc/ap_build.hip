@@ -226,6 +226,7 @@ int ap_seed_knn_impl(const ap_index *ix, const int32_t *node_ids, int64_t nn, in
         e = hipMemcpyAsync(&n_ovf, ovf, sizeof(int32_t), hipMemcpyDeviceToHost, st);
         if (e == hipSuccess) e = hipStreamSynchronize(st);
         if (e != hipSuccess) break;
+        if ((row0 / RS) % 64 == 63) ap_progress("seed lists: %lld of %lld rows", (long long)(row0 + nrows), (long long)nn);
         if (n_ovf > 0) {   // redo the slab by the exact path
             if (!ex_scratch) rc = ap_dev_alloc(&ex_scratch, (size_t)ex_rows * (size_t)n);
             if (rc != AP_OK) break;
@@ -309,7 +310,7 @@ __global__ __launch_bounds__(512) void k_refine(ApVecs D, const uint2 *__restric
                                                 float ws, float wf, int32_t K, int32_t S, int32_t P,
                                                 const int32_t *__restrict__ knn, const int32_t *__restrict__ sp_ids,
                                                 const float *__restrict__ sp_sc, const int32_t *__restrict__ node_ids,
-                                                int64_t nn, int32_t *__restrict__ out_ids, float *__restrict__ out_sc,
+                                                int64_t nn, int64_t x0, int32_t *__restrict__ out_ids, float *__restrict__ out_sc,
                                                 int32_t *__restrict__ out_sp_ids, float *__restrict__ out_sp_sc) {
     __shared__ int32_t ht[AP_HT];
     __shared__ int32_t cand[AP_MAXC];
@@ -321,7 +322,7 @@ __global__ __launch_bounds__(512) void k_refine(ApVecs D, const uint2 *__restric
     __shared__ uint64_t red[8];
     __shared__ uint64_t qtab[(1 << AP_RT_SPB) + (1 << AP_RT_TXB)];
     __shared__ int32_t s_cnt, s_nold;
-    const int64_t x = blockIdx.x;
+    const int64_t x = x0 + blockIdx.x;   // the launch covers nodes x0 .. x0 + gridDim.x of the nn
     const int64_t u = node_ids ? (int64_t)node_ids[x] : x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const ApLists a = ap_stage_lists(D, u, l_sp_idx, l_sp_val, l_tx_idx, l_tx_val, AP_A_CAP);
@@ -423,11 +424,14 @@ extern "C" int ap_stage_refine(const ap_index *ix, int32_t K, int32_t S, int32_t
     if (!node_ids) nn = ix->docs.n;
     if (nn <= 0) return AP_OK;
     const float *w = ix->params.build_w;
-    AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim,
-                      hipLaunchKernelGGL((k_refine<DT, NV>), dim3((unsigned)nn), dim3(512), 0, (hipStream_t)stream, ix->docs,
-                                         ix->rec, ix->meta, w[0], w[1], w[2], K, S, P, knn_ids, sp_ids, sp_sc, node_ids, nn, out_ids, out_sc,
-                                         out_sp_ids, out_sp_sc));
-    AP_CHECK_HIP(hipGetLastError());
+    for (int64_t x0 = 0; x0 < nn; x0 += AP_MAX_LAUNCH_THREADS / 512) {   // a launch holds fewer than 2^32 threads
+        const int64_t cn = std::min<int64_t>(AP_MAX_LAUNCH_THREADS / 512, nn - x0);
+        AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim,
+                          hipLaunchKernelGGL((k_refine<DT, NV>), dim3((unsigned)cn), dim3(512), 0, (hipStream_t)stream, ix->docs,
+                                             ix->rec, ix->meta, w[0], w[1], w[2], K, S, P, knn_ids, sp_ids, sp_sc, node_ids, nn, x0, out_ids,
+                                             out_sc, out_sp_ids, out_sp_sc));
+        AP_CHECK_HIP(hipGetLastError());
+    }
     return AP_OK;
 }
 
@@ -760,10 +764,10 @@ __global__ void k_rev_round(const int32_t *__restrict__ se, int64_t n, int32_t R
 // padding from the rest of SE and from the detour-sorted list.
 __global__ __launch_bounds__(256) void k_assemble(int64_t n, int32_t R, int32_t K, int32_t P, const int32_t *__restrict__ se,
                                                   const int32_t *__restrict__ sorted_ids, const int32_t *__restrict__ sp_ids,
-                                                  const unsigned long long *__restrict__ rev, int32_t *__restrict__ out) {
+                                                  const unsigned long long *__restrict__ rev, int64_t u0, int32_t *__restrict__ out) {
     __shared__ int32_t rows[4][128];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t u = blockIdx.x * 4 + wave;
+    const int64_t u = u0 + (int64_t)blockIdx.x * 4 + wave;
     if (u >= n) return;
     int32_t *row = rows[wave];
     int32_t len = 0;
@@ -821,8 +825,11 @@ int ap_assemble_impl(const ap_index *ix, int32_t R, int32_t K, int32_t P, const 
             e = hipGetLastError();
         }
         if (e == hipSuccess) {
-            hipLaunchKernelGGL(k_assemble, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st, n, R, K, P, se, sorted_ids, sp_ids, rev, out_graph);
-            e = hipGetLastError();
+            for (int64_t u0 = 0; u0 < n && e == hipSuccess; u0 += AP_MAX_LAUNCH_THREADS / 64) {   // four nodes per 256 threads
+                const int64_t cn = std::min<int64_t>(AP_MAX_LAUNCH_THREADS / 64, n - u0);
+                hipLaunchKernelGGL(k_assemble, dim3((unsigned)((cn + 3) / 4)), dim3(256), 0, st, n, R, K, P, se, sorted_ids, sp_ids, rev, u0, out_graph);
+                e = hipGetLastError();
+            }
         }
         if (e == hipSuccess) e = hipStreamSynchronize(st);
     }
@@ -842,11 +849,11 @@ extern "C" int ap_stage_assemble(const ap_index *ix, int32_t R, int32_t K, int32
 // =================================================================== the whole build
 // Fused scores of existing lists (used when no refinement round runs).
 template <int DT, int NV>
-__global__ __launch_bounds__(256) void k_rescore_lists(ApVecs D, float wd, float ws, float wf, int32_t K,
+__global__ __launch_bounds__(256) void k_rescore_lists(ApVecs D, float wd, float ws, float wf, int32_t K, int64_t u0,
                                                        const int32_t *__restrict__ knn, float *__restrict__ sc) {
     __shared__ int32_t l_sp_idx[AP_A_CAP], l_tx_idx[AP_A_CAP];
     __shared__ float l_sp_val[AP_A_CAP], l_tx_val[AP_A_CAP];
-    const int64_t u = blockIdx.x;
+    const int64_t u = u0 + blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const ApLists a = ap_stage_lists(D, u, l_sp_idx, l_sp_val, l_tx_idx, l_tx_val, AP_A_CAP);
     float qa[NV * ApDense<DT>::EPC];
@@ -864,10 +871,13 @@ __global__ __launch_bounds__(256) void k_rescore_lists(ApVecs D, float wd, float
 int ap_rescore_lists(const ap_index *ix, int64_t nn, int32_t K, const int32_t *knn, float *sc, hipStream_t st) {
     if (nn <= 0) return AP_OK;
     const float *w = ix->params.build_w;
-    AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim,
-                      hipLaunchKernelGGL((k_rescore_lists<DT, NV>), dim3((unsigned)nn), dim3(256), 0, st, ix->docs, w[0], w[1], w[2],
-                                         K, knn, sc));
-    AP_CHECK_HIP(hipGetLastError());
+    for (int64_t u0 = 0; u0 < nn; u0 += AP_MAX_LAUNCH_THREADS / 256) {
+        const int64_t cn = std::min<int64_t>(AP_MAX_LAUNCH_THREADS / 256, nn - u0);
+        AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim,
+                          hipLaunchKernelGGL((k_rescore_lists<DT, NV>), dim3((unsigned)cn), dim3(256), 0, st, ix->docs, w[0], w[1], w[2],
+                                             K, u0, knn, sc));
+        AP_CHECK_HIP(hipGetLastError());
+    }
     return AP_OK;
 }
 
@@ -903,7 +913,9 @@ static int build_impl(ap_index *ix, hipStream_t st, BuildBufs &b) {
     AP_TRY(ap_dev_alloc(&b.se, (size_t)n * R));
     AP_TRY(ap_dev_alloc(&b.sorted, (size_t)n * K));
     AP_TRY(ap_alloc_graph(ix));
+    ap_progress("ingest done; seed lists of %lld documents", (long long)n);
     AP_TRY(ap_seed_knn_impl(ix, nullptr, n, K, b.knn[0], b.knn_sc[0], st));
+    ap_progress("seed lists done; %d refinement rounds, pruning, assembly", p.nd_rounds);
     AP_CHECK_HIP(mark(2));
     AP_TRY(ap_fill_u32(b.spi[0], (size_t)3 * n * P, 0xffffffffu, st));          // id -1
     AP_TRY(ap_fill_u32(b.sps[0], (size_t)3 * n * P, 0xff800000u, st));          // -inf

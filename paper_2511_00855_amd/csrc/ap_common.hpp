@@ -12,6 +12,7 @@
 
 // ---------------------------------------------------------------- errors
 void ap_set_error(const char *fmt, ...);
+void ap_progress(const char *fmt, ...) __attribute__((format(printf, 1, 2)));   // to stderr, only when ALLANPOE_PROGRESS is set
 
 #define AP_CHECK_HIP(expr)                                                                   \
     do {                                                                                     \
@@ -110,6 +111,12 @@ static inline int ap_dev_alloc(T **p, size_t count) {
     }
     return AP_OK;
 }
+
+// A kernel launch holds fewer than 2^32 threads: launches whose grid grows with the corpus are cut into slices of at
+// most this many threads (grids beyond the limit were seen to wrap around silently).
+#ifndef AP_MAX_LAUNCH_THREADS
+#define AP_MAX_LAUNCH_THREADS ((int64_t)1 << 31)
+#endif
 
 // CSR row offsets must start at 0, never decrease and end at `total`; a row that fails is not read.
 __device__ __forceinline__ bool ap_row_ok(const int64_t *ip, int64_t x, int64_t total) {

@@ -40,9 +40,9 @@ __global__ void k_bf16_to_f32(const uint16_t *__restrict__ in, float *__restrict
 // holds entry t of the first list or entry t-K of the second and counts the keys that rank before its own.
 __global__ __launch_bounds__(512) void k_merge_ranked(int32_t K, const int32_t *__restrict__ a_ids, const float *__restrict__ a_sc,
                                                       const int32_t *__restrict__ b_ids, const float *__restrict__ b_sc,
-                                                      int32_t *__restrict__ out_ids, float *__restrict__ out_sc) {
+                                                      int64_t x0, int32_t *__restrict__ out_ids, float *__restrict__ out_sc) {
     __shared__ uint64_t keys[512];
-    const int64_t x = blockIdx.x;
+    const int64_t x = x0 + blockIdx.x;
     const int32_t t = threadIdx.x;
     uint64_t key = 0;
     if (t < 2 * K) {
@@ -181,9 +181,11 @@ static int insert_impl(const ap_index *old, ap_index *nx, int32_t beam, const ap
     AP_TRY(B.get(&new_ids, (size_t)m));
     AP_TRY(ap_fill_u32(knn, (size_t)n0 * K, 0xffffffffu, st));          // rows of old documents are never read
     AP_TRY(ap_fill_u32(knn_sc, (size_t)n0 * K, 0xff800000u, st));
-    hipLaunchKernelGGL(k_merge_ranked, dim3((unsigned)m), dim3(512), 0, st, K, c1_ids, c1_sc, r_ids[cur], r_sc[cur],
-                       knn + (size_t)n0 * K, knn_sc + (size_t)n0 * K);
-    AP_CHECK_HIP(hipGetLastError());
+    for (int64_t x0 = 0; x0 < m; x0 += AP_MAX_LAUNCH_THREADS / 512) {
+        hipLaunchKernelGGL(k_merge_ranked, dim3((unsigned)std::min<int64_t>(AP_MAX_LAUNCH_THREADS / 512, m - x0)), dim3(512), 0, st, K,
+                           c1_ids, c1_sc, r_ids[cur], r_sc[cur], x0, knn + (size_t)n0 * K, knn_sc + (size_t)n0 * K);
+        AP_CHECK_HIP(hipGetLastError());
+    }
     hipLaunchKernelGGL(k_iota, dim3(grid_for((size_t)m)), dim3(256), 0, st, new_ids, m, (int32_t)n0);
     AP_CHECK_HIP(hipGetLastError());
     if (tr) {

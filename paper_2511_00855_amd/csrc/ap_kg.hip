@@ -429,6 +429,7 @@ extern "C" int ap_search_batch_entities(ap_index *ix, const ap_queries *q, const
     AP_REQUIRE(max_hops >= 0 && max_hops <= 255, "max_hops = %d must be in [0, 255]", max_hops);
     AP_REQUIRE(w_k == w_k && w_k - w_k == 0.f, "w_k must be finite");
     if (q->nq == 0) return AP_OK;
+    AP_REQUIRE((int64_t)q->nq * 1024 < ((int64_t)1 << 32), "at most %d queries per call", (1 << 22) - 1);   // a launch holds < 2^32 threads
     hipStream_t st = (hipStream_t)stream;
     const int32_t nq = q->nq;
     ApKgArgs g;

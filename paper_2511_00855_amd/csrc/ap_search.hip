@@ -494,6 +494,7 @@ static int ap_search_launch(ap_index *ix, const ApVecs &Q, const float *w_dev, i
     AP_REQUIRE(max_iters >= 0, "max_iters must be >= 0");
     AP_REQUIRE(!kw || ix->docs.n < (1ll << 29), "keyword search and searches on an index with deletions need n < 2^29");
     if (nq == 0) return AP_OK;
+    AP_REQUIRE((int64_t)nq * 1024 < ((int64_t)1 << 32), "at most %d queries per call", (1 << 22) - 1);   // a launch holds < 2^32 threads
     if (!kw_terms) kw_stride = 0;
     ApSearchArgs g;
     g.D = ix->docs;

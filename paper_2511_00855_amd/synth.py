@@ -68,21 +68,33 @@ def _draw_terms(rng: np.random.Generator, cdf: np.ndarray, perm: np.ndarray, n: 
     return perm[r]
 
 
-def _bags(rng, cdf, perm, counts: np.ndarray) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
-    """Token bags WITH repetition -> CSR of (term id ascending, count)."""
+def _say(progress, msg: str) -> None:
+    if progress is not None:
+        progress(msg)
+
+
+_ROW_BLOCK = 1 << 19   # rows per step of the generators below (a step of a large corpus takes seconds, not minutes)
+
+
+def _bags(rng, cdf, perm, counts: np.ndarray, progress=None) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Token bags WITH repetition -> CSR of (term id ascending, count).  Rows are handled in blocks; the tokens of
+    all rows come from one stream of draws, so the result does not depend on the block size."""
     n = len(counts)
-    total = int(counts.sum())
-    rows = np.repeat(np.arange(n, dtype=np.int64), counts)
-    toks = _draw_terms(rng, cdf, perm, total).astype(np.int64)
     vocab = len(cdf)
-    key = rows * vocab + toks
-    uk, cnt = np.unique(key, return_counts=True)
-    r = uk // vocab
-    t = (uk % vocab).astype(np.int32)
     indptr = np.zeros(n + 1, dtype=np.int64)
-    np.add.at(indptr, r + 1, 1)
+    terms, tfs = [], []
+    for b0 in range(0, n, _ROW_BLOCK):
+        b1 = min(n, b0 + _ROW_BLOCK)
+        c = counts[b0:b1]
+        rows = np.repeat(np.arange(b0, b1, dtype=np.int64), c)
+        toks = _draw_terms(rng, cdf, perm, int(c.sum())).astype(np.int64)
+        uk, cnt = np.unique(rows * vocab + toks, return_counts=True)
+        indptr[b0 + 1:b1 + 1] = np.bincount(uk // vocab - b0, minlength=b1 - b0)
+        terms.append((uk % vocab).astype(np.int32)); tfs.append(cnt.astype(np.float32))
+        if n > _ROW_BLOCK:
+            _say(progress, f"text of rows {b0}..{b1} of {n}")
     np.cumsum(indptr, out=indptr)
-    return indptr, t, cnt.astype(np.float32)
+    return indptr, np.concatenate(terms) if terms else np.zeros(0, np.int32), np.concatenate(tfs) if tfs else np.zeros(0, np.float32)
 
 
 def _first_distinct(draws: np.ndarray, need: np.ndarray) -> np.ndarray:
@@ -97,7 +109,7 @@ def _first_distinct(draws: np.ndarray, need: np.ndarray) -> np.ndarray:
     return first & (np.cumsum(first, axis=1) <= need[:, None])
 
 
-def _distinct_sets(rng, cdf, perm, counts: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+def _distinct_sets(rng, cdf, perm, counts: np.ndarray, progress=None) -> Tuple[np.ndarray, np.ndarray]:
     """Per row, `counts[i]` DISTINCT Zipf term ids (keep drawing until distinct), sorted.
 
     Rows are handled in blocks: every row of a block draws the same number of
@@ -114,6 +126,8 @@ def _distinct_sets(rng, cdf, perm, counts: np.ndarray) -> Tuple[np.ndarray, np.n
         b1 = min(n, b0 + block)
         need = counts[b0:b1]
         rows = np.nonzero(need > 0)[0]
+        if b0 and b0 % _ROW_BLOCK == 0:
+            _say(progress, f"sparse lists of rows ..{b0} of {n}")
         if not len(rows):
             continue
         m = int(need.max()) * 2 + 8
@@ -158,23 +172,32 @@ def bf16_to_f32(b: np.ndarray) -> np.ndarray:
     return (b.astype(np.uint32) << 16).view(np.float32)
 
 
-def _dense(rng, n: int, dim: int, bf16: bool):
-    x = rng.standard_normal((n, dim), dtype=np.float32)
-    x /= np.linalg.norm(x, axis=1, keepdims=True).astype(np.float32)
-    if bf16:
-        b = f32_to_bf16_rne(x)
-        return bf16_to_f32(b).reshape(n, dim), b.reshape(n, dim)
-    return x, None
+def _dense(rng, n: int, dim: int, bf16: bool, progress=None):
+    """Unit-norm Gaussian rows, generated in row blocks out of one stream of draws (the result does not depend on
+    the block size).  bf16: the rows are rounded to bf16 and `dense` holds those values widened back."""
+    x = np.empty((n, dim), dtype=np.float32)
+    b = np.empty((n, dim), dtype=np.uint16) if bf16 else None
+    for r0 in range(0, n, _ROW_BLOCK):
+        r1 = min(n, r0 + _ROW_BLOCK)
+        blk = rng.standard_normal((r1 - r0, dim), dtype=np.float32)
+        blk /= np.linalg.norm(blk, axis=1, keepdims=True).astype(np.float32)
+        if bf16:
+            b[r0:r1] = f32_to_bf16_rne(blk)
+            blk = bf16_to_f32(b[r0:r1])
+        x[r0:r1] = blk
+        if n > _ROW_BLOCK:
+            _say(progress, f"dense rows {r0}..{r1} of {n}")
+    return x, b
 
 
 def make_vecset(rng, n: int, dim: int, *, bf16: bool, sp_vocab: int, sp_counts: np.ndarray,
-                tx_vocab: int, tx_counts: np.ndarray, sp_cdf, sp_perm, tx_cdf, tx_perm) -> VecSet:
-    dense, dense_b = _dense(rng, n, dim, bf16)
-    sp_indptr, sp_idx = _distinct_sets(rng, sp_cdf, sp_perm, sp_counts)
+                tx_vocab: int, tx_counts: np.ndarray, sp_cdf, sp_perm, tx_cdf, tx_perm, progress=None) -> VecSet:
+    dense, dense_b = _dense(rng, n, dim, bf16, progress)
+    sp_indptr, sp_idx = _distinct_sets(rng, sp_cdf, sp_perm, sp_counts, progress)
     sp_val = np.abs(rng.standard_normal(len(sp_idx))).astype(np.float32)
     # a weight that rounds to 0 would make "nnz" a lie; nudge (probability ~0)
     sp_val[sp_val == 0] = np.float32(1e-3)
-    tx_indptr, tx_idx, tx_val = _bags(rng, tx_cdf, tx_perm, tx_counts)
+    tx_indptr, tx_idx, tx_val = _bags(rng, tx_cdf, tx_perm, tx_counts, progress)
     return VecSet(n=n, dim=dim, dense=dense, sp_indptr=sp_indptr, sp_idx=sp_idx, sp_val=sp_val,
                   tx_indptr=tx_indptr, tx_idx=tx_idx, tx_val=tx_val, sp_vocab=sp_vocab,
                   tx_vocab=tx_vocab, dense_bf16=dense_b)
@@ -219,10 +242,11 @@ def _counts(rng, spec, n):
 
 
 def make_workload(name: str = "tiny", seed: int = 0, *, n: Optional[int] = None, nq: Optional[int] = None,
-                  **override) -> Workload:
+                  progress=None, **override) -> Workload:
     """Build one of the named workloads.  `n`, `nq` and any config key can be
     overridden to get a smaller case with the same distributions (used by tests
-    that need several tiles and a ragged tail but not the full size)."""
+    that need several tiles and a ragged tail but not the full size).
+    progress: called with a short message after every block of a large corpus."""
     c = dict(CONFIGS[name])
     c.update(override)
     if n is not None:
@@ -236,7 +260,7 @@ def make_workload(name: str = "tiny", seed: int = 0, *, n: Optional[int] = None,
     tx_perm = rng.permutation(vocab).astype(np.int64)
     common = dict(sp_vocab=vocab, tx_vocab=vocab, sp_cdf=cdf, sp_perm=sp_perm, tx_cdf=cdf, tx_perm=tx_perm)
     docs = make_vecset(rng, c["n"], c["dim"], bf16=c["bf16"], sp_counts=_counts(rng, c["sp"], c["n"]),
-                       tx_counts=_counts(rng, c["tx"], c["n"]), **common)
+                       tx_counts=_counts(rng, c["tx"], c["n"]), progress=progress, **common)
     qs = make_vecset(rng, c["nq"], c["dim"], bf16=False, sp_counts=_counts(rng, c["qsp"], c["nq"]),
                      tx_counts=np.maximum(_counts(rng, c["qtx"], c["nq"]), 1), **common)
     return Workload(name=name, docs=docs, queries=qs, weights=tuple(c["weights"]), degree=c["degree"],
