@@ -424,8 +424,9 @@ extern "C" int ap_stage_refine(const ap_index *ix, int32_t K, int32_t S, int32_t
     if (!node_ids) nn = ix->docs.n;
     if (nn <= 0) return AP_OK;
     const float *w = ix->params.build_w;
-    for (int64_t x0 = 0; x0 < nn; x0 += AP_MAX_LAUNCH_THREADS / 512) {   // a launch holds fewer than 2^32 threads
-        const int64_t cn = std::min<int64_t>(AP_MAX_LAUNCH_THREADS / 512, nn - x0);
+    const int64_t slice = AP_MAX_LAUNCH_THREADS / 512;   // a launch holds fewer than 2^32 threads
+    for (int64_t x0 = 0; x0 < nn; x0 += slice) {
+        const int64_t cn = std::min<int64_t>(slice, nn - x0);
         AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim,
                           hipLaunchKernelGGL((k_refine<DT, NV>), dim3((unsigned)cn), dim3(512), 0, (hipStream_t)stream, ix->docs,
                                              ix->rec, ix->meta, w[0], w[1], w[2], K, S, P, knn_ids, sp_ids, sp_sc, node_ids, nn, x0, out_ids,
@@ -825,8 +826,9 @@ int ap_assemble_impl(const ap_index *ix, int32_t R, int32_t K, int32_t P, const 
             e = hipGetLastError();
         }
         if (e == hipSuccess) {
-            for (int64_t u0 = 0; u0 < n && e == hipSuccess; u0 += AP_MAX_LAUNCH_THREADS / 64) {   // four nodes per 256 threads
-                const int64_t cn = std::min<int64_t>(AP_MAX_LAUNCH_THREADS / 64, n - u0);
+            const int64_t slice = AP_MAX_LAUNCH_THREADS / 64;   // four nodes per 256 threads
+            for (int64_t u0 = 0; u0 < n && e == hipSuccess; u0 += slice) {
+                const int64_t cn = std::min<int64_t>(slice, n - u0);
                 hipLaunchKernelGGL(k_assemble, dim3((unsigned)((cn + 3) / 4)), dim3(256), 0, st, n, R, K, P, se, sorted_ids, sp_ids, rev, u0, out_graph);
                 e = hipGetLastError();
             }
@@ -871,8 +873,9 @@ __global__ __launch_bounds__(256) void k_rescore_lists(ApVecs D, float wd, float
 int ap_rescore_lists(const ap_index *ix, int64_t nn, int32_t K, const int32_t *knn, float *sc, hipStream_t st) {
     if (nn <= 0) return AP_OK;
     const float *w = ix->params.build_w;
-    for (int64_t u0 = 0; u0 < nn; u0 += AP_MAX_LAUNCH_THREADS / 256) {
-        const int64_t cn = std::min<int64_t>(AP_MAX_LAUNCH_THREADS / 256, nn - u0);
+    const int64_t slice = AP_MAX_LAUNCH_THREADS / 256;
+    for (int64_t u0 = 0; u0 < nn; u0 += slice) {
+        const int64_t cn = std::min<int64_t>(slice, nn - u0);
         AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim,
                           hipLaunchKernelGGL((k_rescore_lists<DT, NV>), dim3((unsigned)cn), dim3(256), 0, st, ix->docs, w[0], w[1], w[2],
                                              K, u0, knn, sc));

@@ -3,6 +3,7 @@
 // kernel (pair scoring, construction, search) calls, so that a pair of vectors
 // gets bit-identical component sums wherever it is evaluated.
 #pragma once
+#include <stdlib.h>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdio.h>
@@ -113,10 +114,14 @@ static inline int ap_dev_alloc(T **p, size_t count) {
 }
 
 // A kernel launch holds fewer than 2^32 threads: launches whose grid grows with the corpus are cut into slices of at
-// most this many threads (grids beyond the limit were seen to wrap around silently).
-#ifndef AP_MAX_LAUNCH_THREADS
-#define AP_MAX_LAUNCH_THREADS ((int64_t)1 << 31)
-#endif
+// most this many threads (grids beyond the limit were seen to wrap around silently).  AP_MAX_LAUNCH_THREADS in the
+// environment (a multiple of 1024) is a test knob that makes small corpora run in several slices.
+static inline int64_t ap_max_launch_threads() {
+    const char *env = getenv("AP_MAX_LAUNCH_THREADS");
+    const int64_t v = env ? atoll(env) : 0;
+    return v >= 1024 && v % 1024 == 0 ? v : (int64_t)1 << 31;
+}
+#define AP_MAX_LAUNCH_THREADS ap_max_launch_threads()
 
 // CSR row offsets must start at 0, never decrease and end at `total`; a row that fails is not read.
 __device__ __forceinline__ bool ap_row_ok(const int64_t *ip, int64_t x, int64_t total) {

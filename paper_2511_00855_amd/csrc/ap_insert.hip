@@ -181,8 +181,9 @@ static int insert_impl(const ap_index *old, ap_index *nx, int32_t beam, const ap
     AP_TRY(B.get(&new_ids, (size_t)m));
     AP_TRY(ap_fill_u32(knn, (size_t)n0 * K, 0xffffffffu, st));          // rows of old documents are never read
     AP_TRY(ap_fill_u32(knn_sc, (size_t)n0 * K, 0xff800000u, st));
-    for (int64_t x0 = 0; x0 < m; x0 += AP_MAX_LAUNCH_THREADS / 512) {
-        hipLaunchKernelGGL(k_merge_ranked, dim3((unsigned)std::min<int64_t>(AP_MAX_LAUNCH_THREADS / 512, m - x0)), dim3(512), 0, st, K,
+    const int64_t slice = AP_MAX_LAUNCH_THREADS / 512;
+    for (int64_t x0 = 0; x0 < m; x0 += slice) {
+        hipLaunchKernelGGL(k_merge_ranked, dim3((unsigned)std::min<int64_t>(slice, m - x0)), dim3(512), 0, st, K,
                            c1_ids, c1_sc, r_ids[cur], r_sc[cur], x0, knn + (size_t)n0 * K, knn_sc + (size_t)n0 * K);
         AP_CHECK_HIP(hipGetLastError());
     }

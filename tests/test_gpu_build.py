@@ -8,7 +8,7 @@ import torch
 
 import oracle as O
 from paper_2511_00855_amd import binding as B
-from paper_2511_00855_amd.synth import make_workload
+from paper_2511_00855_amd.synth import make_workload, subset_vecset
 from parity import RTOL_F32, assert_ranked_equiv, row_norms
 
 pytestmark = pytest.mark.gpu
@@ -253,7 +253,7 @@ def test_s6_assemble_and_entry(case):
     assert np.array_equal(ent, O.entry_points(self_gpu, 16))
 
 
-def test_whole_build_equals_stage_chain_and_searches(case):
+def test_whole_build_equals_stage_chain_and_searches(case, monkeypatch):
     name, w, docs, ix, D, wv, dn, (R, K, S, P) = case
     _say(f"whole build {name}")
     N = docs.n
@@ -282,6 +282,22 @@ def test_whole_build_equals_stage_chain_and_searches(case):
     sem2, kw2, kc2, ent2 = _np(*again.export_graph())
     assert np.array_equal(sem, sem2) and np.array_equal(kw, kw2) and np.array_equal(ent, ent2)
     again.close()
+    # a launch holds fewer than 2^32 threads, so kernels with one workgroup per document run in slices on corpora of
+    # millions; with the limit turned down to 64k threads (slices of 128 to 1024 documents) the bits are the same
+    monkeypatch.setenv("AP_MAX_LAUNCH_THREADS", "65536")
+    sliced = B.Index.build(docs, bp)
+    sem3, kw3, kc3, ent3 = _np(*sliced.export_graph())
+    assert np.array_equal(sem, sem3) and np.array_equal(kw, kw3) and np.array_equal(kc, kc3) and np.array_equal(ent, ent3)
+    if N > 300:
+        grown = B.Index.build(B.DeviceVecs(subset_vecset(w.docs, np.arange(N - 200)), bf16=docs.dtype != 0), bp)
+        a = grown.insert(docs)
+        monkeypatch.delenv("AP_MAX_LAUNCH_THREADS")
+        b = grown.insert(docs)
+        for x, y in zip(a.export_graph(), b.export_graph()):
+            assert torch.equal(x, y)
+        a.close(); b.close(); grown.close()
+    monkeypatch.delenv("AP_MAX_LAUNCH_THREADS", raising=False)
+    sliced.close()
     # the graph is searchable: recall against the exhaustive scorer
     qs = B.DeviceVecs(w.queries)
     wq = np.tile(np.float32(w.weights), (qs.n, 1))
