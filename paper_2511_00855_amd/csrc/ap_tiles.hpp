@@ -11,36 +11,40 @@ typedef float ap_f32x16 __attribute__((ext_vector_type(16)));
 #define AP_BK 32
 #define AP_LDS_STRIDE (AP_BK + 1)   // odd stride: the 32 rows read by one MFMA operand fall in distinct banks
 
-// Columns [k0, k0+32) of the 128 rows `rows[]` (row id -1 = zeros) as f32: thread t holds 4 consecutive columns of
-// rows t/8 + 32*pass.  Loading (global memory -> registers) and storing (registers -> lds[128][33]) are separate
-// steps so that the loads of the next chunk can be in flight while the current one is multiplied.
+// Columns [k0, k0+32) of 128 rows (row id -1 = zeros) as f32: thread t holds 4 consecutive columns of rows
+// t/8 + 32*pass, whose ids it keeps in row[] for the whole product.  Loading (global memory -> registers) and
+// storing (registers -> lds[128][33]) are separate steps so that the loads of the next chunk can be in flight while
+// the current one is multiplied.  The loads are unconditional (a hole reads row 0, a column past the end re-reads
+// the row's last group) so that four loads issue back to back; what they brought is zeroed when it is stored.
 template <int DT>
-__device__ __forceinline__ void ap_tile_load(const void *dense, int32_t dim, const int32_t *rows, int32_t k0, float4 v[4]) {
-    const int t = threadIdx.x;
+__device__ __forceinline__ void ap_tile_load(const void *dense, int32_t dim, const int32_t row[4], int32_t k0, float4 v[4]) {
+    const int c = (threadIdx.x & 7) * 4;
+    const bool inside = k0 + c < dim;              // dim is a multiple of 4: a group of 4 is all inside or all outside
+    const int32_t col = inside ? k0 + c : dim - 4;
 #pragma unroll
     for (int pass = 0; pass < 4; pass++) {
-        const int r = (t >> 3) + 32 * pass;
-        const int c = (t & 7) * 4;
-        const int32_t row = rows[r];
-        v[pass] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (row >= 0 && k0 + c < dim) {
-            if (DT == AP_F32) {
-                v[pass] = *reinterpret_cast<const float4 *>(static_cast<const float *>(dense) + (int64_t)row * dim + k0 + c);
-            } else {
-                const uint2 x = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(dense) + (int64_t)row * dim + k0 + c);
-                v[pass] = make_float4(__uint_as_float(x.x << 16), __uint_as_float(x.x & 0xffff0000u),
-                                      __uint_as_float(x.y << 16), __uint_as_float(x.y & 0xffff0000u));
-            }
+        const int64_t at = (int64_t)(row[pass] < 0 ? 0 : row[pass]) * dim + col;
+        float4 x;
+        if (DT == AP_F32) {
+            x = *reinterpret_cast<const float4 *>(static_cast<const float *>(dense) + at);
+        } else {
+            const uint2 y = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(dense) + at);
+            x = make_float4(__uint_as_float(y.x << 16), __uint_as_float(y.x & 0xffff0000u), __uint_as_float(y.y << 16),
+                            __uint_as_float(y.y & 0xffff0000u));
         }
+        v[pass] = x;
     }
 }
 
-__device__ __forceinline__ void ap_tile_store(const float4 v[4], float *lds) {
+// k0: the chunk v[] was loaded for.
+__device__ __forceinline__ void ap_tile_store(const float4 v[4], const int32_t row[4], int32_t dim, int32_t k0, float *lds) {
     const int t = threadIdx.x;
+    const bool inside = k0 + (t & 7) * 4 < dim;
 #pragma unroll
     for (int pass = 0; pass < 4; pass++) {
         float *d = lds + ((t >> 3) + 32 * pass) * AP_LDS_STRIDE + (t & 7) * 4;
-        d[0] = v[pass].x; d[1] = v[pass].y; d[2] = v[pass].z; d[3] = v[pass].w;
+        const bool keep = row[pass] >= 0 && inside;
+        d[0] = keep ? v[pass].x : 0.f; d[1] = keep ? v[pass].y : 0.f; d[2] = keep ? v[pass].z : 0.f; d[3] = keep ? v[pass].w : 0.f;
     }
 }
 
@@ -62,17 +66,23 @@ __device__ __forceinline__ void ap_tile_gemm(const void *dense, int32_t dim, con
 #pragma unroll
             for (int r = 0; r < 16; r++) acc[a][b][r] = 0.f;
     float4 va[4], vb[4];
+    int32_t ra[4], rb[4];
     __syncthreads();                // the row lists were just written by the caller's threads
-    ap_tile_load<DT>(dense, dim, a_rows, 0, va);
-    ap_tile_load<DT>(dense, dim, b_rows, 0, vb);
+#pragma unroll
+    for (int pass = 0; pass < 4; pass++) {
+        ra[pass] = a_rows[(threadIdx.x >> 3) + 32 * pass];
+        rb[pass] = b_rows[(threadIdx.x >> 3) + 32 * pass];
+    }
+    ap_tile_load<DT>(dense, dim, ra, 0, va);
+    ap_tile_load<DT>(dense, dim, rb, 0, vb);
     for (int32_t k0 = 0; k0 < dim; k0 += AP_BK) {
         __syncthreads();            // everyone is done with the previous chunk in LDS
-        ap_tile_store(va, lA);
-        ap_tile_store(vb, lB);
+        ap_tile_store(va, ra, dim, k0, lA);
+        ap_tile_store(vb, rb, dim, k0, lB);
         __syncthreads();
         if (k0 + AP_BK < dim) {     // the next chunk travels while this one is multiplied
-            ap_tile_load<DT>(dense, dim, a_rows, k0 + AP_BK, va);
-            ap_tile_load<DT>(dense, dim, b_rows, k0 + AP_BK, vb);
+            ap_tile_load<DT>(dense, dim, ra, k0 + AP_BK, va);
+            ap_tile_load<DT>(dense, dim, rb, k0 + AP_BK, vb);
         }
         const float *pa0 = lA + (wm * 64 + li) * AP_LDS_STRIDE + lk;
         const float *pa1 = pa0 + 32 * AP_LDS_STRIDE;
@@ -101,24 +111,23 @@ typedef __bf16 ap_bf16x8 __attribute__((ext_vector_type(8)));
 #define AP_TPR16 (AP_BK16 / 8)            // threads per row of a chunk
 #define AP_RPP16 (256 / AP_TPR16)         // rows per pass
 #define AP_NP16 (AP_TILE / AP_RPP16)      // passes
-__device__ __forceinline__ void ap_tile_load_bf16(const void *dense, int32_t dim, const int32_t *rows, int32_t k0, uint4 v[AP_NP16]) {
-    const int t = threadIdx.x;
-#pragma unroll
-    for (int pass = 0; pass < AP_NP16; pass++) {
-        const int r = t / AP_TPR16 + AP_RPP16 * pass;
-        const int c = (t % AP_TPR16) * 8;
-        const int32_t row = rows[r];
-        v[pass] = make_uint4(0, 0, 0, 0);
-        if (row >= 0 && k0 + c < dim)   // dim is a multiple of 8: a 16-byte group is all inside or all outside
-            v[pass] = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(dense) + (int64_t)row * dim + k0 + c);
-    }
-}
-
-__device__ __forceinline__ void ap_tile_store_bf16(const uint4 v[AP_NP16], uint16_t *lds) {
-    const int t = threadIdx.x;
+// row[]: the ids of this thread's rows, kept in registers for the whole product; unconditional loads, zeroed when
+// stored, as above.
+__device__ __forceinline__ void ap_tile_load_bf16(const void *dense, int32_t dim, const int32_t row[AP_NP16], int32_t k0, uint4 v[AP_NP16]) {
+    const int c = (threadIdx.x % AP_TPR16) * 8;
+    const int32_t col = k0 + c < dim ? k0 + c : dim - 8;   // dim is a multiple of 8: a 16-byte group is all inside or all outside
 #pragma unroll
     for (int pass = 0; pass < AP_NP16; pass++)
-        *reinterpret_cast<uint4 *>(lds + (t / AP_TPR16 + AP_RPP16 * pass) * AP_LDS_STRIDE16 + (t % AP_TPR16) * 8) = v[pass];
+        v[pass] = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(dense) + (int64_t)(row[pass] < 0 ? 0 : row[pass]) * dim + col);
+}
+
+__device__ __forceinline__ void ap_tile_store_bf16(const uint4 v[AP_NP16], const int32_t row[AP_NP16], int32_t dim, int32_t k0, uint16_t *lds) {
+    const int t = threadIdx.x;
+    const bool inside = k0 + (t % AP_TPR16) * 8 < dim;
+#pragma unroll
+    for (int pass = 0; pass < AP_NP16; pass++)
+        *reinterpret_cast<uint4 *>(lds + (t / AP_TPR16 + AP_RPP16 * pass) * AP_LDS_STRIDE16 + (t % AP_TPR16) * 8) =
+            (row[pass] >= 0 && inside) ? v[pass] : make_uint4(0, 0, 0, 0);
 }
 
 __device__ __forceinline__ void ap_tile_gemm_bf16(const void *dense, int32_t dim, const int32_t *a_rows, const int32_t *b_rows,
@@ -133,17 +142,23 @@ __device__ __forceinline__ void ap_tile_gemm_bf16(const void *dense, int32_t dim
 #pragma unroll
             for (int r = 0; r < 16; r++) acc[a][b][r] = 0.f;
     uint4 va[AP_NP16], vb[AP_NP16];
+    int32_t ra[AP_NP16], rb[AP_NP16];
     __syncthreads();                // the row lists were just written by the caller's threads
-    ap_tile_load_bf16(dense, dim, a_rows, 0, va);
-    ap_tile_load_bf16(dense, dim, b_rows, 0, vb);
+#pragma unroll
+    for (int pass = 0; pass < AP_NP16; pass++) {
+        ra[pass] = a_rows[threadIdx.x / AP_TPR16 + AP_RPP16 * pass];
+        rb[pass] = b_rows[threadIdx.x / AP_TPR16 + AP_RPP16 * pass];
+    }
+    ap_tile_load_bf16(dense, dim, ra, 0, va);
+    ap_tile_load_bf16(dense, dim, rb, 0, vb);
     for (int32_t k0 = 0; k0 < dim; k0 += AP_BK16) {
         __syncthreads();            // everyone is done with the previous chunk in LDS
-        ap_tile_store_bf16(va, lA);
-        ap_tile_store_bf16(vb, lB);
+        ap_tile_store_bf16(va, ra, dim, k0, lA);
+        ap_tile_store_bf16(vb, rb, dim, k0, lB);
         __syncthreads();
         if (k0 + AP_BK16 < dim) {   // the next chunk travels while this one is multiplied
-            ap_tile_load_bf16(dense, dim, a_rows, k0 + AP_BK16, va);
-            ap_tile_load_bf16(dense, dim, b_rows, k0 + AP_BK16, vb);
+            ap_tile_load_bf16(dense, dim, ra, k0 + AP_BK16, va);
+            ap_tile_load_bf16(dense, dim, rb, k0 + AP_BK16, vb);
         }
         const uint16_t *pa0 = lA + (wm * 64 + li) * AP_LDS_STRIDE16 + lk;
         const uint16_t *pa1 = pa0 + 32 * AP_LDS_STRIDE16;
