@@ -86,6 +86,41 @@ __global__ __launch_bounds__(256) void k_seed_thresh(const void *dense, int32_t 
     });
 }
 
+// The thresholded sweep for bf16 rows on 256x256 tiles (the product above): the same appends as k_seed_thresh.
+// 4 x 4 waves of 64 x 64 each: measured faster than 2 x 4 waves of 128 x 64 or 2 x 2 of 128 x 128 (fewer LDS reads per
+// MFMA, but fewer waves to overlap them with), and 12 % faster than the 128 x 128 tiles of k_seed_thresh.
+#ifndef AP_BIG_WM
+#define AP_BIG_WM 4
+#define AP_BIG_WN 4
+#endif
+template <int WM, int WN>
+__global__ __launch_bounds__(WM * WN * 64) void k_seed_thresh_big(const void *dense, int32_t dim, int64_t n, const int32_t *node_ids,
+                                                                  int64_t row0, int64_t nrows, const float *__restrict__ tau,
+                                                                  unsigned long long *__restrict__ buf, int32_t cap,
+                                                                  int32_t *__restrict__ cnt) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char big_lds[];
+    __shared__ int32_t a_rows[AP_BIG], b_rows[AP_BIG];
+    __shared__ float s_tau[AP_BIG];
+    int64_t rt, ct;
+    if (!ap_seed_tile((nrows + AP_BIG - 1) / AP_BIG, rt, ct)) return;
+    const int64_t i0 = rt * AP_BIG, j0 = ct * AP_BIG;
+    for (int32_t x = threadIdx.x; x < AP_BIG; x += blockDim.x) {
+        const int64_t r = i0 + x;
+        a_rows[x] = r < nrows ? (node_ids ? node_ids[row0 + r] : (int32_t)(row0 + r)) : -1;
+        s_tau[x] = r < nrows ? tau[r] : INFINITY;
+        const int64_t j = j0 + x;
+        b_rows[x] = j < n ? (int32_t)j : -1;
+    }
+    ap_f32x16 acc[ApBig<WM, WN>::FA][ApBig<WM, WN>::FB];
+    ap_big_gemm_bf16<WM, WN>(dense, dim, a_rows, b_rows, reinterpret_cast<uint16_t *>(big_lds), acc);
+    ap_big_foreach<WM, WN>(acc, [&](int i, int j, float v) {
+        if (i0 + i < nrows && j0 + j < n && v >= s_tau[i] && a_rows[i] != (int32_t)(j0 + j)) {
+            const int32_t pos = atomicAdd(&cnt[i0 + i], 1);
+            if (pos < cap) buf[(i0 + i) * (int64_t)cap + pos] = ap_make_key(v, (int32_t)(j0 + j), 1u);
+        }
+    });
+}
+
 // One block per row: exact top-K of the row (excluding the node itself), sorted.
 // Row r of `scores` has ncols entries; its result goes to row out_row0 + r.
 __global__ __launch_bounds__(256) void k_select_rows(const float *__restrict__ scores, int64_t ncols, int32_t K,
@@ -217,8 +252,13 @@ int ap_seed_knn_impl(const ap_index *ix, const int32_t *node_ids, int64_t nn, in
         if (rc != AP_OK) break;
         if (ix->dtype == AP_F32)
             hipLaunchKernelGGL(k_seed_thresh<AP_F32>, gf, dim3(256), 0, st, ix->docs.dense, ix->docs.dim, n, node_ids, row0, nrows, tau, buf, (int32_t)cap, cnt);
-        else
-            hipLaunchKernelGGL(k_seed_thresh<AP_BF16>, gf, dim3(256), 0, st, ix->docs.dense, ix->docs.dim, n, node_ids, row0, nrows, tau, buf, (int32_t)cap, cnt);
+        else {
+            const dim3 gb(ap_seed_grid((nrows + AP_BIG - 1) / AP_BIG, (n + AP_BIG - 1) / AP_BIG));
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN>), hipFuncAttributeMaxDynamicSharedMemorySize, AP_BIG_LDS_BYTES);
+            if (e != hipSuccess) break;
+            hipLaunchKernelGGL((k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN>), gb, dim3(AP_BIG_WM * AP_BIG_WN * 64), AP_BIG_LDS_BYTES, st, ix->docs.dense, ix->docs.dim, n,
+                               node_ids, row0, nrows, tau, buf, (int32_t)cap, cnt);
+        }
         hipLaunchKernelGGL(k_select_buf, dim3((unsigned)nrows), dim3(256), 0, st, buf, (int32_t)cap, cnt, K, row0, out_ids, out_sc, ovf, ovf + 1);
         e = hipGetLastError();
         if (e != hipSuccess) break;

@@ -178,6 +178,115 @@ __device__ __forceinline__ void ap_tile_gemm_bf16(const void *dense, int32_t dim
     }
 }
 
+// The large bf16 product: a 256x256 tile by WM x WN waves, each a (256/WM) x (256/WN) block of 32x32 MFMA tiles,
+// twice the multiply-adds per byte fetched of the 128x128 tile, and fewer LDS reads per MFMA the larger a wave's
+// block is.  Chunks of 64 columns alternate between two LDS stages, so a chunk costs one barrier: while chunk k is
+// multiplied out of one stage, chunk k+1 (already in registers) is written to the other and chunk k+2 is on its way
+// from memory.  Same instruction, operand layout and chunk order as the 128x128 product: every element gets the
+// same bits.
+#define AP_BIG 256
+#define AP_BIG_STAGE (2 * AP_BIG * AP_LDS_STRIDE16)               // bf16 elements of one stage (A then B)
+#define AP_BIG_LDS_BYTES (2 * AP_BIG_STAGE * 2)
+template <int WM, int WN> struct ApBig {
+    static constexpr int THREADS = WM * WN * 64;
+    static constexpr int NP = AP_BIG * AP_TPR16 / THREADS;        // 16-byte groups per thread, operand and chunk
+    static constexpr int RPP = THREADS / AP_TPR16;                // rows per pass of the staging
+    static constexpr int FA = AP_BIG / WM / 32, FB = AP_BIG / WN / 32;   // 32x32 tiles of a wave's block
+};
+template <int NP>
+__device__ __forceinline__ void ap_big_load(const void *dense, int32_t dim, const int32_t row[NP], int32_t k0, uint4 v[NP]) {
+    const int c = (threadIdx.x % AP_TPR16) * 8;
+    const int32_t col = k0 + c < dim ? k0 + c : dim - 8;
+#pragma unroll
+    for (int pass = 0; pass < NP; pass++)
+        v[pass] = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(dense) + (int64_t)(row[pass] < 0 ? 0 : row[pass]) * dim + col);
+}
+template <int NP, int RPP>
+__device__ __forceinline__ void ap_big_store(const uint4 v[NP], const int32_t row[NP], int32_t dim, int32_t k0, uint16_t *lds) {
+    const int t = threadIdx.x;
+    const bool inside = k0 + (t % AP_TPR16) * 8 < dim;
+#pragma unroll
+    for (int pass = 0; pass < NP; pass++)
+        *reinterpret_cast<uint4 *>(lds + (t / AP_TPR16 + RPP * pass) * AP_LDS_STRIDE16 + (t % AP_TPR16) * 8) =
+            (row[pass] >= 0 && inside) ? v[pass] : make_uint4(0, 0, 0, 0);
+}
+template <int WM, int WN>
+__device__ __forceinline__ void ap_big_gemm_bf16(const void *dense, int32_t dim, const int32_t *a_rows, const int32_t *b_rows,
+                                                 uint16_t *lds, ap_f32x16 acc[ApBig<WM, WN>::FA][ApBig<WM, WN>::FB]) {
+    using B = ApBig<WM, WN>;
+    constexpr int NP = B::NP, RPP = B::RPP, FA = B::FA, FB = B::FB;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int li = lane & 31, lk = (lane >> 5) * 8;
+#pragma unroll
+    for (int a = 0; a < FA; a++)
+#pragma unroll
+        for (int b = 0; b < FB; b++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) acc[a][b][r] = 0.f;
+    uint4 va[NP], vb[NP];
+    int32_t ra[NP], rb[NP];
+    __syncthreads();                // the row lists were just written by the caller's threads
+#pragma unroll
+    for (int pass = 0; pass < NP; pass++) {
+        ra[pass] = a_rows[threadIdx.x / AP_TPR16 + RPP * pass];
+        rb[pass] = b_rows[threadIdx.x / AP_TPR16 + RPP * pass];
+    }
+    const int32_t nch = (dim + AP_BK16 - 1) / AP_BK16;
+    ap_big_load<NP>(dense, dim, ra, 0, va);
+    ap_big_load<NP>(dense, dim, rb, 0, vb);
+    ap_big_store<NP, RPP>(va, ra, dim, 0, lds);
+    ap_big_store<NP, RPP>(vb, rb, dim, 0, lds + AP_BIG * AP_LDS_STRIDE16);
+    if (nch > 1) {
+        ap_big_load<NP>(dense, dim, ra, AP_BK16, va);
+        ap_big_load<NP>(dense, dim, rb, AP_BK16, vb);
+    }
+    __syncthreads();
+    for (int32_t k = 0; k < nch; k++) {
+        uint16_t *cur = lds + (k & 1) * AP_BIG_STAGE, *nxt = lds + ((k + 1) & 1) * AP_BIG_STAGE;
+        if (k + 1 < nch) {          // the other stage was last read before the barrier that ended the previous round
+            ap_big_store<NP, RPP>(va, ra, dim, (k + 1) * AP_BK16, nxt);
+            ap_big_store<NP, RPP>(vb, rb, dim, (k + 1) * AP_BK16, nxt + AP_BIG * AP_LDS_STRIDE16);
+        }
+        if (k + 2 < nch) {          // travels while this chunk and the next are multiplied
+            ap_big_load<NP>(dense, dim, ra, (k + 2) * AP_BK16, va);
+            ap_big_load<NP>(dense, dim, rb, (k + 2) * AP_BK16, vb);
+        }
+        const uint16_t *pa = cur + (wm * (AP_BIG / WM) + li) * AP_LDS_STRIDE16 + lk;
+        const uint16_t *pb = cur + AP_BIG * AP_LDS_STRIDE16 + (wn * (AP_BIG / WN) + li) * AP_LDS_STRIDE16 + lk;
+#pragma unroll
+        for (int kk = 0; kk < AP_BK16; kk += 16) {
+            ap_bf16x8 fa[FA], fb[FB];
+#pragma unroll
+            for (int a = 0; a < FA; a++) fa[a] = __builtin_bit_cast(ap_bf16x8, *reinterpret_cast<const uint4 *>(pa + a * 32 * AP_LDS_STRIDE16 + kk));
+#pragma unroll
+            for (int b = 0; b < FB; b++) fb[b] = __builtin_bit_cast(ap_bf16x8, *reinterpret_cast<const uint4 *>(pb + b * 32 * AP_LDS_STRIDE16 + kk));
+#pragma unroll
+            for (int a = 0; a < FA; a++)
+#pragma unroll
+                for (int b = 0; b < FB; b++) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+}
+
+// Calls f(i, j, value) for every element this lane holds of the 256x256 tile.
+template <int WM, int WN, typename F>
+__device__ __forceinline__ void ap_big_foreach(const ap_f32x16 acc[ApBig<WM, WN>::FA][ApBig<WM, WN>::FB], F f) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+#pragma unroll
+    for (int a = 0; a < ApBig<WM, WN>::FA; a++)
+#pragma unroll
+        for (int b = 0; b < ApBig<WM, WN>::FB; b++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) {
+                const int i = wm * (AP_BIG / WM) + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                const int j = wn * (AP_BIG / WN) + b * 32 + (lane & 31);
+                f(i, j, acc[a][b][r]);
+            }
+}
+
 // LDS bytes the tile product needs (both operands) for a storage type.
 template <int DT> struct ApTileLds {
     static constexpr int BYTES = DT == AP_BF16 ? 2 * AP_TILE * AP_LDS_STRIDE16 * 2 : 2 * AP_TILE * AP_LDS_STRIDE * 4;
