@@ -233,3 +233,29 @@ def test_widest_and_narrowest_dense_rows(dim, bf16):
     oi = np.stack([O.bruteforce_topk(Q, [qi], D, wq[qi], 5)[0][0] for qi in range(nq)])
     assert (gt == oi).mean() > 0.97
     ix.close()
+
+
+@pytest.mark.parametrize("dim", [8, 72, 200, 1024])
+def test_bf16_threshold_sweep_on_ragged_shapes(dim, monkeypatch):
+    """The thresholded seed sweep of bf16 rows (256x256 tiles, two LDS stages) against the score-row path (128x128
+    tiles, itself checked against the oracle elsewhere): same ids and the same score bits, with a ragged last row
+    tile, a ragged last column tile and a last chunk of fewer than 64 columns; also with overflowing buffers."""
+    _say(f"edge case: bf16 threshold sweep, dim {dim}")
+    w = make_workload("tiny", seed=91, n=777, nq=2, dim=dim, bf16=True, sp=("fixed", 4), tx=("fixed", 4))
+    docs = B.DeviceVecs(w.docs, bf16=True)
+    ix = B.Index.ingest(docs, B.build_params(8, knn_k=24, nd_rounds=1, nd_sample=4, n_entry=4))
+    K = 24
+    exact = [t.cpu().numpy() for t in ix.stage_seed_knn(K)]
+    oi, os_ = O.seed_knn(O.encode_docs(w.docs), np.arange(docs.n), K)
+    assert (exact[0] == oi).mean() > 0.99
+    nodes = np.arange(5, 700, 3, dtype=np.int32)
+    exact_sub = [t.cpu().numpy() for t in ix.stage_seed_knn(K, nodes)]
+    monkeypatch.setenv("AP_SEED_SAMPLE_COLS", "128")
+    for cap in (None, "32"):
+        if cap:
+            monkeypatch.setenv("AP_SEED_BUFFER_CAP", cap)
+        thr = [t.cpu().numpy() for t in ix.stage_seed_knn(K)]
+        assert np.array_equal(thr[0], exact[0]) and np.array_equal(thr[1], exact[1])
+        thr_sub = [t.cpu().numpy() for t in ix.stage_seed_knn(K, nodes)]
+        assert np.array_equal(thr_sub[0], exact_sub[0]) and np.array_equal(thr_sub[1], exact_sub[1])
+    ix.close()
