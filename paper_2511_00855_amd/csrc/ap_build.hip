@@ -93,17 +93,20 @@ __global__ __launch_bounds__(256) void k_seed_thresh(const void *dense, int32_t 
 #define AP_BIG_WM 4
 #define AP_BIG_WN 4
 #endif
-template <int WM, int WN>
+// RUN: every tile of the launch is two runs of 256 consecutive documents inside the corpus (no node list, no ragged
+// edge, dim a multiple of 64); the host launches the edges of a sweep with RUN = false.  The launch covers row tiles
+// rt0 .. rt0 + nrt and column tiles from ct0 on.
+template <int WM, int WN, bool RUN>
 __global__ __launch_bounds__(WM * WN * 64) void k_seed_thresh_big(const void *dense, int32_t dim, int64_t n, const int32_t *node_ids,
                                                                   int64_t row0, int64_t nrows, const float *__restrict__ tau,
                                                                   unsigned long long *__restrict__ buf, int32_t cap,
-                                                                  int32_t *__restrict__ cnt) {
+                                                                  int32_t *__restrict__ cnt, int64_t rt0, int64_t nrt, int64_t ct0) {
     extern __shared__ __attribute__((aligned(16))) unsigned char big_lds[];
     __shared__ int32_t a_rows[AP_BIG], b_rows[AP_BIG];
-    __shared__ float s_tau[AP_BIG];
+    __shared__ __attribute__((aligned(16))) float s_tau[AP_BIG];
     int64_t rt, ct;
-    if (!ap_seed_tile((nrows + AP_BIG - 1) / AP_BIG, rt, ct)) return;
-    const int64_t i0 = rt * AP_BIG, j0 = ct * AP_BIG;
+    if (!ap_seed_tile(nrt, rt, ct)) return;
+    const int64_t i0 = (rt0 + rt) * AP_BIG, j0 = (ct0 + ct) * AP_BIG;
     for (int32_t x = threadIdx.x; x < AP_BIG; x += blockDim.x) {
         const int64_t r = i0 + x;
         a_rows[x] = r < nrows ? (node_ids ? node_ids[row0 + r] : (int32_t)(row0 + r)) : -1;
@@ -112,13 +115,45 @@ __global__ __launch_bounds__(WM * WN * 64) void k_seed_thresh_big(const void *de
         b_rows[x] = j < n ? (int32_t)j : -1;
     }
     ap_f32x16 acc[ApBig<WM, WN>::FA][ApBig<WM, WN>::FB];
-    ap_big_gemm_bf16<WM, WN>(dense, dim, a_rows, b_rows, reinterpret_cast<uint16_t *>(big_lds), acc);
-    ap_big_foreach<WM, WN>(acc, [&](int i, int j, float v) {
-        if (i0 + i < nrows && j0 + j < n && v >= s_tau[i] && a_rows[i] != (int32_t)(j0 + j)) {
-            const int32_t pos = atomicAdd(&cnt[i0 + i], 1);
-            if (pos < cap) buf[(i0 + i) * (int64_t)cap + pos] = ap_make_key(v, (int32_t)(j0 + j), 1u);
-        }
-    });
+    if (RUN) {
+        const int32_t a_first = (int32_t)(row0 + i0), b_first = (int32_t)j0;
+        ap_big_gemm_bf16<WM, WN, true>(dense, dim, a_rows, b_rows, a_first, b_first, reinterpret_cast<uint16_t *>(big_lds), acc);
+        // A lane holds 4 consecutive rows x (FB x 32 columns apart) per 8-row group: the rows' thresholds come as one
+        // 16-byte LDS read, and an element costs a compare and a (rarely taken) branch.  Only a tile whose row and
+        // column runs overlap can pair a document with itself.
+        const bool diagonal = a_first < b_first + AP_BIG && b_first < a_first + AP_BIG;
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        const int wm = wave / WN, wn = wave % WN;
+#pragma unroll
+        for (int a = 0; a < ApBig<WM, WN>::FA; a++)
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+                const int ib = wm * (AP_BIG / WM) + a * 32 + 8 * q + 4 * (lane >> 5);
+                const float4 t4 = *reinterpret_cast<const float4 *>(&s_tau[ib]);
+                const float tt[4] = {t4.x, t4.y, t4.z, t4.w};
+#pragma unroll
+                for (int b = 0; b < ApBig<WM, WN>::FB; b++)
+#pragma unroll
+                    for (int rr = 0; rr < 4; rr++) {
+                        const float v = acc[a][b][4 * q + rr];
+                        if (v >= tt[rr]) {
+                            const int i = ib + rr, j = wn * (AP_BIG / WN) + b * 32 + (lane & 31);
+                            if (!(diagonal && a_first + i == b_first + j)) {
+                                const int32_t pos = atomicAdd(&cnt[i0 + i], 1);
+                                if (pos < cap) buf[(i0 + i) * (int64_t)cap + pos] = ap_make_key(v, b_first + j, 1u);
+                            }
+                        }
+                    }
+            }
+    } else {
+        ap_big_gemm_bf16<WM, WN, false>(dense, dim, a_rows, b_rows, 0, 0, reinterpret_cast<uint16_t *>(big_lds), acc);
+        ap_big_foreach<WM, WN>(acc, [&](int i, int j, float v) {
+            if (i0 + i < nrows && j0 + j < n && v >= s_tau[i] && a_rows[i] != (int32_t)(j0 + j)) {
+                const int32_t pos = atomicAdd(&cnt[i0 + i], 1);
+                if (pos < cap) buf[(i0 + i) * (int64_t)cap + pos] = ap_make_key(v, (int32_t)(j0 + j), 1u);
+            }
+        });
+    }
 }
 
 // One block per row: exact top-K of the row (excluding the node itself), sorted.
@@ -253,11 +288,34 @@ int ap_seed_knn_impl(const ap_index *ix, const int32_t *node_ids, int64_t nn, in
         if (ix->dtype == AP_F32)
             hipLaunchKernelGGL(k_seed_thresh<AP_F32>, gf, dim3(256), 0, st, ix->docs.dense, ix->docs.dim, n, node_ids, row0, nrows, tau, buf, (int32_t)cap, cnt);
         else {
-            const dim3 gb(ap_seed_grid((nrows + AP_BIG - 1) / AP_BIG, (n + AP_BIG - 1) / AP_BIG));
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN>), hipFuncAttributeMaxDynamicSharedMemorySize, AP_BIG_LDS_BYTES);
+            // the inner tiles (runs of consecutive documents, all inside the corpus) take the lean instantiation, the ragged
+            // last row tile and last column tile the general one
+            const int64_t row_tiles = (nrows + AP_BIG - 1) / AP_BIG, col_tiles = (n + AP_BIG - 1) / AP_BIG;
+            const bool runs = node_ids == nullptr && ix->docs.dim % AP_BK16 == 0;
+            const int64_t full_rt = runs ? nrows / AP_BIG : 0, full_ct = runs ? n / AP_BIG : 0;
+            auto sweep = [&](bool lean, int64_t rt0, int64_t nrt, int64_t ct0, int64_t nct) {
+                if (nrt <= 0 || nct <= 0 || e != hipSuccess) return;
+                const dim3 gb(ap_seed_grid(nrt, nct));
+                const dim3 tb(AP_BIG_WM * AP_BIG_WN * 64);
+                if (lean) {
+                    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN, true>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, AP_BIG_LDS_BYTES);
+                    if (e == hipSuccess)
+                        hipLaunchKernelGGL((k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN, true>), gb, tb, AP_BIG_LDS_BYTES, st, ix->docs.dense, ix->docs.dim, n,
+                                           node_ids, row0, nrows, tau, buf, (int32_t)cap, cnt, rt0, nrt, ct0);
+                } else {
+                    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN, false>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, AP_BIG_LDS_BYTES);
+                    if (e == hipSuccess)
+                        hipLaunchKernelGGL((k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN, false>), gb, tb, AP_BIG_LDS_BYTES, st, ix->docs.dense, ix->docs.dim, n,
+                                           node_ids, row0, nrows, tau, buf, (int32_t)cap, cnt, rt0, nrt, ct0);
+                }
+                if (e == hipSuccess) e = hipGetLastError();
+            };
+            sweep(true, 0, full_rt, 0, full_ct);
+            sweep(false, 0, full_rt, full_ct, col_tiles - full_ct);          // ragged last column tile
+            sweep(false, full_rt, row_tiles - full_rt, 0, col_tiles);        // ragged last row tile (or everything)
             if (e != hipSuccess) break;
-            hipLaunchKernelGGL((k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN>), gb, dim3(AP_BIG_WM * AP_BIG_WN * 64), AP_BIG_LDS_BYTES, st, ix->docs.dense, ix->docs.dim, n,
-                               node_ids, row0, nrows, tau, buf, (int32_t)cap, cnt);
         }
         hipLaunchKernelGGL(k_select_buf, dim3((unsigned)nrows), dim3(256), 0, st, buf, (int32_t)cap, cnt, K, row0, out_ids, out_sc, ovf, ovf + 1);
         e = hipGetLastError();

@@ -187,6 +187,7 @@ __device__ __forceinline__ void ap_tile_gemm_bf16(const void *dense, int32_t dim
 #define AP_BIG 256
 #define AP_BIG_STAGE (2 * AP_BIG * AP_LDS_STRIDE16)               // bf16 elements of one stage (A then B)
 #define AP_BIG_LDS_BYTES (2 * AP_BIG_STAGE * 2)
+typedef uint32_t ap_u32x4 __attribute__((ext_vector_type(4)));   // a 16-byte group as a plain vector value
 template <int WM, int WN> struct ApBig {
     static constexpr int THREADS = WM * WN * 64;
     static constexpr int NP = AP_BIG * AP_TPR16 / THREADS;        // 16-byte groups per thread, operand and chunk
@@ -194,80 +195,124 @@ template <int WM, int WN> struct ApBig {
     static constexpr int FA = AP_BIG / WM / 32, FB = AP_BIG / WN / 32;   // 32x32 tiles of a wave's block
 };
 template <int NP>
-__device__ __forceinline__ void ap_big_load(const void *dense, int32_t dim, const int32_t row[NP], int32_t k0, uint4 v[NP]) {
+__device__ __forceinline__ void ap_big_load(const void *dense, int32_t dim, const int32_t row[NP], int32_t k0, ap_u32x4 v[NP]) {
     const int c = (threadIdx.x % AP_TPR16) * 8;
     const int32_t col = k0 + c < dim ? k0 + c : dim - 8;
 #pragma unroll
     for (int pass = 0; pass < NP; pass++)
-        v[pass] = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(dense) + (int64_t)(row[pass] < 0 ? 0 : row[pass]) * dim + col);
+        v[pass] = *reinterpret_cast<const ap_u32x4 *>(static_cast<const uint16_t *>(dense) + (int64_t)(row[pass] < 0 ? 0 : row[pass]) * dim + col);
 }
 template <int NP, int RPP>
-__device__ __forceinline__ void ap_big_store(const uint4 v[NP], const int32_t row[NP], int32_t dim, int32_t k0, uint16_t *lds) {
+__device__ __forceinline__ void ap_big_store(const ap_u32x4 v[NP], const int32_t row[NP], int32_t dim, int32_t k0, uint16_t *lds) {
     const int t = threadIdx.x;
     const bool inside = k0 + (t % AP_TPR16) * 8 < dim;
 #pragma unroll
     for (int pass = 0; pass < NP; pass++)
-        *reinterpret_cast<uint4 *>(lds + (t / AP_TPR16 + RPP * pass) * AP_LDS_STRIDE16 + (t % AP_TPR16) * 8) =
-            (row[pass] >= 0 && inside) ? v[pass] : make_uint4(0, 0, 0, 0);
+        *reinterpret_cast<ap_u32x4 *>(lds + (t / AP_TPR16 + RPP * pass) * AP_LDS_STRIDE16 + (t % AP_TPR16) * 8) =
+            (row[pass] >= 0 && inside) ? v[pass] : ap_u32x4{0u, 0u, 0u, 0u};
 }
-template <int WM, int WN>
+template <int NP, int RPP>
+__device__ __forceinline__ void ap_big_load_run(const char *run, uint32_t off0, uint32_t pass_stride, int32_t k0, ap_u32x4 (&v)[NP]) {
+#pragma unroll
+    for (int pass = 0; pass < NP; pass++) v[pass] = *reinterpret_cast<const ap_u32x4 *>(run + (off0 + pass * pass_stride + (uint32_t)k0 * 2u));
+}
+template <int NP, int RPP>
+__device__ __forceinline__ void ap_big_store_run(const ap_u32x4 (&v)[NP], uint16_t *lds) {
+#pragma unroll
+    for (int pass = 0; pass < NP; pass++)
+        *reinterpret_cast<ap_u32x4 *>(lds + (threadIdx.x / AP_TPR16 + RPP * pass) * AP_LDS_STRIDE16 + (threadIdx.x % AP_TPR16) * 8) = v[pass];
+}
+#define AP_BIG_LOAD(run, row, k0, v)                                  \
+    do {                                                              \
+        if constexpr (RUN) ap_big_load_run<NP, RPP>(run, run_off, run_stride, k0, v); \
+        else ap_big_load<NP>(dense, dim, row, k0, v);                 \
+    } while (0)
+#define AP_BIG_STORE(v, row, k0, to)                                  \
+    do {                                                              \
+        if constexpr (RUN) ap_big_store_run<NP, RPP>(v, to);          \
+        else ap_big_store<NP, RPP>(v, row, dim, k0, to);              \
+    } while (0)
+// RUN: both operands are runs of 256 consecutive documents (first ids a_first / b_first; a_rows / b_rows unused), all
+// inside the corpus, and dim is a multiple of 64 -- the case of every tile of a sweep but those on its edges.  Then an
+// address is a uniform base plus a 32-bit offset that is fixed for the whole product, nothing needs zeroing, and a
+// chunk costs no vector instruction besides its loads, stores and MFMAs.
+template <int WM, int WN, bool RUN>
 __device__ __forceinline__ void ap_big_gemm_bf16(const void *dense, int32_t dim, const int32_t *a_rows, const int32_t *b_rows,
-                                                 uint16_t *lds, ap_f32x16 acc[ApBig<WM, WN>::FA][ApBig<WM, WN>::FB]) {
+                                                 int32_t a_first, int32_t b_first, uint16_t *lds,
+                                                 ap_f32x16 acc[ApBig<WM, WN>::FA][ApBig<WM, WN>::FB]) {
     using B = ApBig<WM, WN>;
     constexpr int NP = B::NP, RPP = B::RPP, FA = B::FA, FB = B::FB;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int li = lane & 31, lk = (lane >> 5) * 8;
+    const char *run_a = static_cast<const char *>(dense) + (int64_t)a_first * dim * 2;   // uniform
+    const char *run_b = static_cast<const char *>(dense) + (int64_t)b_first * dim * 2;
+    const uint32_t run_off = (uint32_t)(threadIdx.x / AP_TPR16) * (uint32_t)dim * 2u + (threadIdx.x % AP_TPR16) * 16u;
+    const uint32_t run_stride = (uint32_t)RPP * (uint32_t)dim * 2u;   // from one of a thread's rows to the next (uniform)
 #pragma unroll
     for (int a = 0; a < FA; a++)
 #pragma unroll
         for (int b = 0; b < FB; b++)
 #pragma unroll
             for (int r = 0; r < 16; r++) acc[a][b][r] = 0.f;
-    uint4 va[NP], vb[NP];
+    ap_u32x4 va0[NP], vb0[NP], va1[NP], vb1[NP];   // two chunks on their way from memory
     int32_t ra[NP], rb[NP];
     __syncthreads();                // the row lists were just written by the caller's threads
 #pragma unroll
     for (int pass = 0; pass < NP; pass++) {
-        ra[pass] = a_rows[threadIdx.x / AP_TPR16 + RPP * pass];
-        rb[pass] = b_rows[threadIdx.x / AP_TPR16 + RPP * pass];
+        ra[pass] = RUN ? 0 : a_rows[threadIdx.x / AP_TPR16 + RPP * pass];
+        rb[pass] = RUN ? 0 : b_rows[threadIdx.x / AP_TPR16 + RPP * pass];
     }
     const int32_t nch = (dim + AP_BK16 - 1) / AP_BK16;
-    ap_big_load<NP>(dense, dim, ra, 0, va);
-    ap_big_load<NP>(dense, dim, rb, 0, vb);
-    ap_big_store<NP, RPP>(va, ra, dim, 0, lds);
-    ap_big_store<NP, RPP>(vb, rb, dim, 0, lds + AP_BIG * AP_LDS_STRIDE16);
+    AP_BIG_LOAD(run_a, ra, 0, va0);
+    AP_BIG_LOAD(run_b, rb, 0, vb0);
+    AP_BIG_STORE(va0, ra, 0, lds);
+    AP_BIG_STORE(vb0, rb, 0, lds + AP_BIG * AP_LDS_STRIDE16);
     if (nch > 1) {
-        ap_big_load<NP>(dense, dim, ra, AP_BK16, va);
-        ap_big_load<NP>(dense, dim, rb, AP_BK16, vb);
+        AP_BIG_LOAD(run_a, ra, AP_BK16, va0);
+        AP_BIG_LOAD(run_b, rb, AP_BK16, vb0);
+    }
+    if (nch > 2) {
+        AP_BIG_LOAD(run_a, ra, 2 * AP_BK16, va1);
+        AP_BIG_LOAD(run_b, rb, 2 * AP_BK16, vb1);
     }
     __syncthreads();
-    for (int32_t k = 0; k < nch; k++) {
-        uint16_t *cur = lds + (k & 1) * AP_BIG_STAGE, *nxt = lds + ((k + 1) & 1) * AP_BIG_STAGE;
-        if (k + 1 < nch) {          // the other stage was last read before the barrier that ended the previous round
-            ap_big_store<NP, RPP>(va, ra, dim, (k + 1) * AP_BK16, nxt);
-            ap_big_store<NP, RPP>(vb, rb, dim, (k + 1) * AP_BK16, nxt + AP_BIG * AP_LDS_STRIDE16);
-        }
-        if (k + 2 < nch) {          // travels while this chunk and the next are multiplied
-            ap_big_load<NP>(dense, dim, ra, (k + 2) * AP_BK16, va);
-            ap_big_load<NP>(dense, dim, rb, (k + 2) * AP_BK16, vb);
-        }
-        const uint16_t *pa = cur + (wm * (AP_BIG / WM) + li) * AP_LDS_STRIDE16 + lk;
-        const uint16_t *pb = cur + AP_BIG * AP_LDS_STRIDE16 + (wn * (AP_BIG / WN) + li) * AP_LDS_STRIDE16 + lk;
-#pragma unroll
-        for (int kk = 0; kk < AP_BK16; kk += 16) {
-            ap_bf16x8 fa[FA], fb[FB];
-#pragma unroll
-            for (int a = 0; a < FA; a++) fa[a] = __builtin_bit_cast(ap_bf16x8, *reinterpret_cast<const uint4 *>(pa + a * 32 * AP_LDS_STRIDE16 + kk));
-#pragma unroll
-            for (int b = 0; b < FB; b++) fb[b] = __builtin_bit_cast(ap_bf16x8, *reinterpret_cast<const uint4 *>(pb + b * 32 * AP_LDS_STRIDE16 + kk));
-#pragma unroll
-            for (int a = 0; a < FA; a++)
-#pragma unroll
-                for (int b = 0; b < FB; b++) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
-        }
-        __syncthreads();
+    // Round k multiplies chunk k out of stage k & 1.  Register set k & 1 holds chunk k+1: it goes to the other stage
+    // (last read before the barrier that ended round k-1) and is then filled with chunk k+3, so two chunks travel
+    // while two are multiplied.
+#define AP_BIG_ROUND(k, sa, sb)                                                                                                                       \
+    do {                                                                                                                                              \
+        uint16_t *cur = lds + ((k) & 1) * AP_BIG_STAGE, *nxt = lds + (((k) + 1) & 1) * AP_BIG_STAGE;                                                  \
+        if ((k) + 1 < nch) {                                                                                                                          \
+            AP_BIG_STORE(sa, ra, ((k) + 1) * AP_BK16, nxt);                                                                                           \
+            AP_BIG_STORE(sb, rb, ((k) + 1) * AP_BK16, nxt + AP_BIG * AP_LDS_STRIDE16);                                                                \
+        }                                                                                                                                             \
+        if ((k) + 3 < nch) {                                                                                                                          \
+            AP_BIG_LOAD(run_a, ra, ((k) + 3) * AP_BK16, sa);                                                                                          \
+            AP_BIG_LOAD(run_b, rb, ((k) + 3) * AP_BK16, sb);                                                                                          \
+        }                                                                                                                                             \
+        const uint16_t *pa = cur + (wm * (AP_BIG / WM) + li) * AP_LDS_STRIDE16 + lk;                                                                  \
+        const uint16_t *pb = cur + AP_BIG * AP_LDS_STRIDE16 + (wn * (AP_BIG / WN) + li) * AP_LDS_STRIDE16 + lk;                                       \
+_Pragma("unroll")                                                                                                                                     \
+        for (int kk = 0; kk < AP_BK16; kk += 16) {                                                                                                    \
+            ap_bf16x8 fa[FA], fb[FB];                                                                                                                 \
+_Pragma("unroll")                                                                                                                                     \
+            for (int a = 0; a < FA; a++) fa[a] = __builtin_bit_cast(ap_bf16x8, *reinterpret_cast<const ap_u32x4 *>(pa + a * 32 * AP_LDS_STRIDE16 + kk)); \
+_Pragma("unroll")                                                                                                                                     \
+            for (int b = 0; b < FB; b++) fb[b] = __builtin_bit_cast(ap_bf16x8, *reinterpret_cast<const ap_u32x4 *>(pb + b * 32 * AP_LDS_STRIDE16 + kk)); \
+_Pragma("unroll")                                                                                                                                     \
+            for (int a = 0; a < FA; a++)                                                                                                              \
+_Pragma("unroll")                                                                                                                                     \
+                for (int b = 0; b < FB; b++) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);                   \
+        }                                                                                                                                             \
+        __syncthreads();                                                                                                                              \
+    } while (0)
+
+    for (int32_t k = 0; k < nch; k += 2) {
+        AP_BIG_ROUND(k, va0, vb0);
+        if (k + 1 < nch) AP_BIG_ROUND(k + 1, va1, vb1);
     }
+#undef AP_BIG_ROUND
 }
 
 // Calls f(i, j, value) for every element this lane holds of the 256x256 tile.
