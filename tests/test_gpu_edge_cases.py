@@ -235,7 +235,7 @@ def test_widest_and_narrowest_dense_rows(dim, bf16):
     ix.close()
 
 
-@pytest.mark.parametrize("dim", [8, 72, 200, 1024])
+@pytest.mark.parametrize("dim", [8, 64, 72, 128, 192, 200, 1024])
 def test_bf16_threshold_sweep_on_ragged_shapes(dim, monkeypatch):
     """The thresholded seed sweep of bf16 rows (256x256 tiles, two LDS stages) against the score-row path (128x128
     tiles, itself checked against the oracle elsewhere): same ids and the same score bits, with a ragged last row
