@@ -181,9 +181,9 @@ __device__ __forceinline__ void ap_tile_gemm_bf16(const void *dense, int32_t dim
 // The large bf16 product: a 256x256 tile by WM x WN waves, each a (256/WM) x (256/WN) block of 32x32 MFMA tiles,
 // twice the multiply-adds per byte fetched of the 128x128 tile, and fewer LDS reads per MFMA the larger a wave's
 // block is.  Chunks of 64 columns alternate between two LDS stages, so a chunk costs one barrier: while chunk k is
-// multiplied out of one stage, chunk k+1 (already in registers) is written to the other and chunk k+2 is on its way
-// from memory.  Same instruction, operand layout and chunk order as the 128x128 product: every element gets the
-// same bits.
+// multiplied out of one stage, chunk k+1 (already in registers) is written to the other and chunks k+2 and k+3 are
+// on their way from memory.  Same instruction, operand layout and chunk order as the 128x128 product: every element
+// gets the same bits.
 #define AP_BIG 256
 #define AP_BIG_STAGE (2 * AP_BIG * AP_LDS_STRIDE16)               // bf16 elements of one stage (A then B)
 #define AP_BIG_LDS_BYTES (2 * AP_BIG_STAGE * 2)
@@ -314,6 +314,8 @@ _Pragma("unroll")                                                               
     }
 #undef AP_BIG_ROUND
 }
+#undef AP_BIG_LOAD
+#undef AP_BIG_STORE
 
 // Calls f(i, j, value) for every element this lane holds of the 256x256 tile.
 template <int WM, int WN, typename F>
