@@ -2,7 +2,8 @@
 documents, d = 768, 10,000 queries) in the launch configuration bench.py
 times, on sampled outputs the oracle can compute one by one; plus the
 dynamic-fusion sweep of config 4 (five weight settings on the same index, no
-rebuild)."""
+rebuild), and 150,000 documents of config 3's shape (bf16 rows) through the
+seed sweep a million-document build uses."""
 import time
 import types
 
@@ -285,3 +286,41 @@ def test_full_size_insertion_sampled(full):
     assert np.array_equal(sem[rows], O.assemble(n1, R, K, P, se, srt, spi, node_ids=rows))
     assert np.array_equal(ent, O.entry_points(self_gpu, bp.n_entry))
     new.close(); old.close()
+
+
+def test_bf16_corpus_at_scale_sampled():
+    """150,000 documents of config 3's shape (d = 1024 stored bf16): the exact seed lists come from the thresholded
+    sweep over all columns in the configuration a million-document build runs it in (19 slabs of 8,192 rows,
+    256x256 tiles, inner and edge instantiations).  Sampled rows against the oracle's exhaustive top-K, the same
+    rows bit for bit against the sweep over a node list (the general instantiation), and a search replay."""
+    t0 = time.time()
+    w = make_workload("cfg3", seed=4, n=150_000, nq=16)
+    _say(f"150k bf16 documents generated in {time.time() - t0:.1f}s")
+    docs = B.DeviceVecs(w.docs, bf16=True)
+    qs = B.DeviceVecs(w.queries)
+    bp = B.build_params(w.degree)
+    K = bp.knn_k
+    ix = B.Index.build(docs, bp)
+    torch.cuda.synchronize()
+    _say(f"built {ix.build_timings()}")
+    all_ids, all_sc = [t.cpu().numpy() for t in ix.stage_seed_knn(K)]
+    nodes = np.sort(np.random.default_rng(6).choice(docs.n, 48, replace=False)).astype(np.int32)
+    nodes[0], nodes[-1] = 0, docs.n - 1                       # first row of the first slab, last row of the ragged last one
+    sub_ids, sub_sc = [t.cpu().numpy() for t in ix.stage_seed_knn(K, nodes)]
+    assert np.array_equal(sub_ids, all_ids[nodes]) and np.array_equal(sub_sc, all_sc[nodes])
+    D = O.encode_docs(w.docs)
+    dn = row_norms(w.docs)
+    _say("oracle: exhaustive dense top-K of the sampled rows")
+    oid, osc = O.seed_knn(D, nodes, K)
+    assert_ranked_equiv(sub_ids, sub_sc, oid, osc, lambda r, s: RTOL_F32 * dn[nodes[r]] * dn.max(),
+                        lambda r, j: float(np.dot(D.dense[nodes[r]].astype(np.float64), D.dense[j].astype(np.float64))), "bf16 seed")
+    # the built index searches like the oracle on the same graph
+    Q = O.VS(w.queries)
+    wq = np.tile(np.float32(w.weights), (qs.n, 1))
+    sem, _, _, ent = [t.cpu().numpy() for t in ix.export_graph()]
+    ids, sc = [t.cpu().numpy() for t in ix.search_batch(qs, 10, 256, wq)]
+    table = ix.hybrid_scores(qs, np.tile(np.arange(docs.n, dtype=np.int32), (qs.n, 1)), wq).cpu().numpy()[:, :, 3]
+    for qi in range(qs.n):
+        oi, os_, _ = O.search(D, sem, ent, Q, qi, wq[qi], 10, 256, score_table=table[qi])
+        assert np.array_equal(ids[qi], oi) and np.array_equal(sc[qi], os_), qi
+    ix.close()
