@@ -178,7 +178,9 @@ int ap_mark_deleted(ap_index *index, const int32_t *ids, int64_t count, int rest
  * (old documents gain reverse neighbours among the new ones); entry points
  * from all self-similarities.  Mark-deleted documents of `old` stay deleted
  * (and, being part of the graph, stay eligible as neighbours of new
- * documents).  Needs an index produced by ap_build_index or
+ * documents); a knowledge graph set on `old` is not carried over (its
+ * arrays describe the old corpus: call ap_set_knowledge_graph on the new
+ * index).  Needs an index produced by ap_build_index or
  * ap_insert_documents (AP_ESTATE for an imported graph).  Synchronises
  * `stream`.  trace (may be NULL): optional device buffers that receive the
  * intermediates for the m = n1 - n0 new documents, any of them NULL. */
