@@ -323,6 +323,16 @@ int ap_calibration_copy(void *dst, const void *src, size_t bytes, void *stream);
  * [0] ingest, [1] seed, [2] refinement, [3] prune, [4] assemble+entry, [5] total. */
 int ap_build_timings(const ap_index *index, float out6[6]);
 
+/* Debug settings, for tests: they drive small inputs through the code paths of large ones and never change a
+ * result.  One process-wide value per name (host string), 0 = the library's own choice:
+ *   "seed_sample_cols"        columns sampled for the seed threshold (forces the thresholded sweep on small corpora)
+ *   "seed_buffer_cap"         capacity of a row's candidate buffer in that sweep (forces the overflow fallback)
+ *   "seed_tau_ulps"           raises every row's threshold by this many ulps (forces the short-row fallback)
+ *   "max_launch_threads"      a multiple of 1024: launches that grow with the corpus run in slices of this many threads
+ *   "search_workspace_bytes"  cap of the searches' visited-set workspace (forces searches in several slabs of queries)
+ * Unknown names and negative values give AP_EINVAL.  Not thread-safe against running calls. */
+int ap_debug_set(const char *name, int64_t value);
+
 #ifdef __cplusplus
 }
 #endif

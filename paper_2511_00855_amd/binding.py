@@ -99,6 +99,19 @@ def calibration_copy(dst: torch.Tensor, src: torch.Tensor):
         _check(lib().ap_calibration_copy(_ptr(dst), _ptr(src), C.c_size_t(nbytes), _stream()), "ap_calibration_copy")
 
 
+def debug_set(name: str, value: int):
+    """A debug setting of the library (see ap_debug_set); 0 restores the library's own choice."""
+    _check(lib().ap_debug_set(name.encode(), C.c_int64(int(value))), "ap_debug_set")
+
+
+DEBUG_NAMES = ("seed_sample_cols", "seed_buffer_cap", "seed_tau_ulps", "max_launch_threads", "search_workspace_bytes")
+
+
+def debug_reset():
+    for name in DEBUG_NAMES:
+        debug_set(name, 0)
+
+
 class DeviceVecs:
     """Device copies of a vector set (documents or queries)."""
 

@@ -19,6 +19,22 @@ void ap_set_error(const char *fmt, ...) {
 
 extern "C" const char *ap_last_error(void) { return g_err; }
 
+ApDebug g_ap_debug;
+
+extern "C" int ap_debug_set(const char *name, int64_t value) {
+    AP_REQUIRE(name != nullptr, "name is NULL");
+    AP_REQUIRE(value >= 0, "value must be >= 0 (0 = the library's own choice)");
+    struct { const char *name; int64_t *field; } table[] = {
+        {"seed_sample_cols", &g_ap_debug.seed_sample_cols},       {"seed_buffer_cap", &g_ap_debug.seed_buffer_cap},
+        {"seed_tau_ulps", &g_ap_debug.seed_tau_ulps},             {"max_launch_threads", &g_ap_debug.max_launch_threads},
+        {"search_workspace_bytes", &g_ap_debug.search_workspace_bytes},
+    };
+    for (auto &t : table)
+        if (strcmp(name, t.name) == 0) { *t.field = value; return AP_OK; }
+    ap_set_error("unknown debug setting '%s'", name);
+    return AP_EINVAL;
+}
+
 // Long steps of a construction report where they are on stderr when ALLANPOE_PROGRESS is set in the environment
 // (a corpus of millions of documents spends minutes in the seed stage).
 void ap_progress(const char *fmt, ...) {

@@ -178,15 +178,21 @@ __global__ __launch_bounds__(256) void k_select_rows(const float *__restrict__ s
 }
 
 // tau[r] = K-th best score of row r of a [nrows x K] sorted score table.
-__global__ void k_take_tau(const float *__restrict__ sc, int64_t nrows, int32_t K, float *__restrict__ tau) {
+// ulps (a debug setting, normally 0) raises the threshold by that many representable values.
+__global__ void k_take_tau(const float *__restrict__ sc, int64_t nrows, int32_t K, uint32_t ulps, float *__restrict__ tau) {
     const int64_t r = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
-    if (r < nrows) tau[r] = sc[r * K + K - 1];
+    if (r < nrows) {
+        const float t = sc[r * K + K - 1];
+        tau[r] = (ulps && t - t == 0.f) ? ap_ord2f(ap_f2ord(t) + ulps) : t;
+    }
 }
 
 // One block per row: exact top-K among the row's buffered candidate keys.
-// Rows whose buffer overflowed are reported (flags[r] = 1) and left to the caller.
+// Rows whose buffer overflowed are reported in overflow_rows and left to the caller, and so are rows that hold fewer
+// than `need` = min(K, n - 1) keys: the threshold came from another kernel's product of the same rows, and a score
+// that kernel rounded one ulp higher would silently shorten the list.
 __global__ __launch_bounds__(256) void k_select_buf(const unsigned long long *__restrict__ buf, int32_t cap,
-                                                    const int32_t *__restrict__ cnt, int32_t K, int64_t out_row0,
+                                                    const int32_t *__restrict__ cnt, int32_t K, int32_t need, int64_t out_row0,
                                                     int32_t *__restrict__ out_ids, float *__restrict__ out_sc,
                                                     int32_t *__restrict__ n_overflow, int32_t *__restrict__ overflow_rows) {
     __shared__ uint32_t hist[256];
@@ -195,7 +201,7 @@ __global__ __launch_bounds__(256) void k_select_buf(const unsigned long long *__
     __shared__ uint64_t pre;
     const int64_t r = blockIdx.x;
     const int32_t c = cnt[r];
-    if (c > cap) {   // uniform for the block
+    if (c > cap || c < need) {   // uniform for the block
         if (threadIdx.x == 0) overflow_rows[atomicAdd(n_overflow, 1)] = (int32_t)r;
         return;
     }
@@ -241,7 +247,7 @@ int ap_seed_knn_impl(const ap_index *ix, const int32_t *node_ids, int64_t nn, in
                          float *out_sc, hipStream_t st) {
     const int64_t n = ix->docs.n;
     int64_t cs = std::max<int64_t>(16384, (n + 63) / 64);
-    if (const char *env = getenv("AP_SEED_SAMPLE_COLS")) cs = std::max<int64_t>(K + 1, atoll(env));
+    if (g_ap_debug.seed_sample_cols > 0) cs = std::max<int64_t>(K + 1, g_ap_debug.seed_sample_cols);
     cs = (cs + AP_TILE - 1) / AP_TILE * AP_TILE;
     // rows per launch of the exact path: a score slab of ~1 GiB
     int64_t ex_rows = std::max<int64_t>(AP_TILE, (((int64_t)1 << 28) / n) / AP_TILE * AP_TILE);
@@ -261,7 +267,7 @@ int ap_seed_knn_impl(const ap_index *ix, const int32_t *node_ids, int64_t nn, in
     // expected candidates per row = K * n / cs (tau is the K-th best of cs sampled columns)
     int64_t cap = 1024;
     while (cap < 2 * ((int64_t)K * n / cs + K)) cap <<= 1;
-    if (const char *env = getenv("AP_SEED_BUFFER_CAP")) cap = std::max<int64_t>(1, atoll(env));   // test knob: forces overflows
+    if (g_ap_debug.seed_buffer_cap > 0) cap = g_ap_debug.seed_buffer_cap;   // forces overflows
     float *scratch = nullptr, *tau = nullptr, *tmp_sc = nullptr, *ex_scratch = nullptr;
     unsigned long long *buf = nullptr;
     int32_t *cnt = nullptr, *ovf = nullptr;   // ovf[0] = number of overflowed rows, ovf[1..] = their indices
@@ -281,7 +287,8 @@ int ap_seed_knn_impl(const ap_index *ix, const int32_t *node_ids, int64_t nn, in
             hipLaunchKernelGGL(k_seed_scores<AP_BF16>, gs, dim3(256), 0, st, ix->docs.dense, ix->docs.dim, n, node_ids, row0, nrows, (int64_t)0, cs, scratch);
         hipLaunchKernelGGL(k_select_rows, dim3((unsigned)nrows), dim3(256), 0, st, scratch, cs, K, node_ids, row0, 1, (int64_t)0,
                            (int32_t *)nullptr, tmp_sc);
-        hipLaunchKernelGGL(k_take_tau, dim3((unsigned)((nrows + 255) / 256)), dim3(256), 0, st, tmp_sc, nrows, K, tau);
+        hipLaunchKernelGGL(k_take_tau, dim3((unsigned)((nrows + 255) / 256)), dim3(256), 0, st, tmp_sc, nrows, K,
+                           (uint32_t)g_ap_debug.seed_tau_ulps, tau);
         rc = ap_fill_u32(cnt, (size_t)nrows, 0u, st);
         if (rc == AP_OK) rc = ap_fill_u32(ovf, 1, 0u, st);
         if (rc != AP_OK) break;
@@ -317,7 +324,8 @@ int ap_seed_knn_impl(const ap_index *ix, const int32_t *node_ids, int64_t nn, in
             sweep(false, full_rt, row_tiles - full_rt, 0, col_tiles);        // ragged last row tile (or everything)
             if (e != hipSuccess) break;
         }
-        hipLaunchKernelGGL(k_select_buf, dim3((unsigned)nrows), dim3(256), 0, st, buf, (int32_t)cap, cnt, K, row0, out_ids, out_sc, ovf, ovf + 1);
+        hipLaunchKernelGGL(k_select_buf, dim3((unsigned)nrows), dim3(256), 0, st, buf, (int32_t)cap, cnt, K,
+                           (int32_t)std::min<int64_t>(K, n - 1), row0, out_ids, out_sc, ovf, ovf + 1);
         e = hipGetLastError();
         if (e != hipSuccess) break;
         int32_t n_ovf = 0;
@@ -458,7 +466,7 @@ __global__ __launch_bounds__(512) void k_refine(ApVecs D, const uint2 *__restric
         float sd, ss, sf;
         if (use_tab) {
             const uint4 m = meta[v];
-            const uint2 *r = rec + __builtin_amdgcn_readfirstlane(m.x);
+            const uint2 *r = rec + ap_uniform_u32(m.x);
             const int32_t spn = __builtin_amdgcn_readfirstlane((int32_t)(m.y & 0xffffu));
             const int32_t txn = __builtin_amdgcn_readfirstlane((int32_t)(m.y >> 16));
             int32_t si[2], ti[1];
@@ -728,7 +736,7 @@ __global__ __launch_bounds__(256) void k_detour_prune(ApVecs D, const float *__r
     for (int32_t r = 0; r < K; r++) {
         const int32_t pv = order[r], v = ids[pv];
         if (v < 0) break;   // holes are sorted last
-        if (nse == 0) { if (lane == 0) se_pos[0] = pv; nse = 1; __builtin_amdgcn_wave_barrier(); continue; }
+        if (nse == 0) { if (lane == 0) se_pos[0] = pv; nse = 1; ap_wave_sync(); continue; }
         // T = K(A) n K(v)
         const int64_t vb = D.tx_indptr[v], ve = D.tx_indptr[v + 1];
         int32_t nt_all = 0;
@@ -740,7 +748,7 @@ __global__ __launch_bounds__(256) void k_detour_prune(ApVecs D, const float *__r
             if (in) { const int32_t pos = nt_all + __popcll(m & ((1ull << lane) - 1ull)); if (pos < AP_T_CAP) T[pos] = term; }
             nt_all += __popcll(m);
         }
-        __builtin_amdgcn_wave_barrier();
+        ap_wave_sync();
         const int32_t nt = nt_all < AP_T_CAP ? nt_all : AP_T_CAP;
         int32_t fl = 0;
         if (nt_all > 0) {
@@ -774,9 +782,9 @@ __global__ __launch_bounds__(256) void k_detour_prune(ApVecs D, const float *__r
         }
         if (ok) nse++;
         else if (fl && nke < ke_cap) nke++;
-        __builtin_amdgcn_wave_barrier();
+        ap_wave_sync();
     }
-    __builtin_amdgcn_wave_barrier();
+    ap_wave_sync();
     for (int32_t i = lane; i < R; i += 64) if (o_se) o_se[xo * R + i] = i < nse ? ids[se_pos[i]] : -1;
     for (int32_t i = nke + lane; i < ke_cap; i += 64) if (o_ke) o_ke[xo * ke_cap + i] = -1;
     if (lane == 0 && o_ke_count) o_ke_count[xo] = nke;
@@ -880,7 +888,7 @@ __global__ __launch_bounds__(256) void k_assemble(int64_t n, int32_t R, int32_t 
         if (v < 0 || v == (int32_t)u || present(v)) return false;
         if (lane == 0) row[len] = v;
         len++;
-        __builtin_amdgcn_wave_barrier();
+        ap_wave_sync();
         return true;
     };
     for (int32_t i = 0; i < q; i++) push(se[u * R + i]);
@@ -904,7 +912,7 @@ __global__ __launch_bounds__(256) void k_assemble(int64_t n, int32_t R, int32_t 
     }
     for (int32_t i = q; i < R && len < R; i++) push(se[u * R + i]);
     for (int32_t i = 0; i < K && len < R; i++) push(sorted_ids[u * K + i]);
-    __builtin_amdgcn_wave_barrier();
+    ap_wave_sync();
     for (int32_t i = lane; i < R; i += 64) out[u * R + i] = i < len ? row[i] : -1;
 }
 

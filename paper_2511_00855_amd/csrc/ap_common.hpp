@@ -113,12 +113,21 @@ static inline int ap_dev_alloc(T **p, size_t count) {
     return AP_OK;
 }
 
+// Debug settings (ap_debug_set): 0 = the library's own choice.  They exist so that tests can drive small inputs
+// through the code paths of large ones; nothing here changes a result.
+struct ApDebug {
+    int64_t seed_sample_cols = 0;        // columns sampled for the seed threshold (forces the thresholded sweep on small corpora)
+    int64_t seed_buffer_cap = 0;         // capacity of a row's candidate buffer in that sweep (forces the overflow fallback)
+    int64_t seed_tau_ulps = 0;           // raises every row's threshold by this many ulps (forces the short-row fallback)
+    int64_t max_launch_threads = 0;      // a multiple of 1024: launches that grow with the corpus are cut into slices of this many threads
+    int64_t search_workspace_bytes = 0;  // cap of the search's visited-set workspace (forces searches in several slabs of queries)
+};
+extern ApDebug g_ap_debug;
+
 // A kernel launch holds fewer than 2^32 threads: launches whose grid grows with the corpus are cut into slices of at
-// most this many threads (grids beyond the limit were seen to wrap around silently).  AP_MAX_LAUNCH_THREADS in the
-// environment (a multiple of 1024) is a test knob that makes small corpora run in several slices.
+// most this many threads (grids beyond the limit were seen to wrap around silently).
 static inline int64_t ap_max_launch_threads() {
-    const char *env = getenv("AP_MAX_LAUNCH_THREADS");
-    const int64_t v = env ? atoll(env) : 0;
+    const int64_t v = g_ap_debug.max_launch_threads;
     return v >= 1024 && v % 1024 == 0 ? v : (int64_t)1 << 31;
 }
 #define AP_MAX_LAUNCH_THREADS ap_max_launch_threads()
@@ -248,6 +257,14 @@ __device__ __forceinline__ float ap_wave_sum(float v) {
 }
 
 #define AP_LDS __attribute__((address_space(3)))
+
+// Orders one wave's LDS traffic: what any lane wrote before this point is what every lane of the wave reads after it.
+// The barrier alone only pins the instruction schedule; the fence is what keeps the compiler from moving or caching
+// the accesses across it (the hardware runs a wave's LDS instructions in order).
+__device__ __forceinline__ void ap_wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
 
 // Largest power of two <= n (0 for n <= 0): first stride of the halving search below.
 __device__ __forceinline__ int32_t ap_pow2_floor(int32_t n) { return n > 0 ? (1 << (31 - __clz(n))) : 0; }
@@ -405,6 +422,10 @@ __device__ __forceinline__ void ap_lists_load(const ApVecs &B, int64_t spb, int3
         tv[k] = e < txn ? B.tx_val[txb + e] : 0.f;
     }
 }
+
+// A wave-uniform 32-bit value moved to scalar registers.  The builtin returns a signed int: an offset of 2^31 or more
+// must come back as unsigned before it is added to a pointer.
+__device__ __forceinline__ uint32_t ap_uniform_u32(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
 
 // ---- packed document records (search side) -------------------------------
 // One document's sparse entries followed by its lexical entries, 8 bytes each

@@ -301,7 +301,7 @@ __global__ __launch_bounds__(256) void k_search_kg(ApKgArgs g) {
         __syncthreads();
         for (int32_t i = wave; i < c; i += 4) {
             const uint4 m = s_meta[i];
-            const uint2 *r = g.rec + __builtin_amdgcn_readfirstlane(m.x);
+            const uint2 *r = g.rec + ap_uniform_u32(m.x);
             const int32_t spn = __builtin_amdgcn_readfirstlane((int32_t)(m.y & 0xffffu));
             const int32_t txn = __builtin_amdgcn_readfirstlane((int32_t)(m.y >> 16));
             const int32_t v = __builtin_amdgcn_readfirstlane(cand[i]);

@@ -107,10 +107,10 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const ui
             if (i < c) {
                 const uint4 m = s_meta[i];
                 // the descriptor is the same in every lane: keep the record's address in scalar registers
-                r[gi] = rec + __builtin_amdgcn_readfirstlane(m.x);
+                r[gi] = rec + ap_uniform_u32(m.x);
                 spn[gi] = __builtin_amdgcn_readfirstlane((int32_t)(m.y & 0xffffu));
                 txn[gi] = __builtin_amdgcn_readfirstlane((int32_t)(m.y >> 16));
-                dn[gi] = __uint_as_float(__builtin_amdgcn_readfirstlane(m.z));
+                dn[gi] = __uint_as_float(ap_uniform_u32(m.z));
                 ap_rec_load<2, 1>(r[gi], spn[gi], txn[gi], si[gi], sv[gi], ti[gi], tv[gi]);
             }
         }

@@ -54,3 +54,13 @@ def test_host_side_argument_checks():
     assert not h.value
     assert lib.ap_set_weights(None, (C.c_float * 3)(1, 1, 1)) == -1
     lib.ap_free_index(None)                                           # no-op
+
+
+def test_debug_settings_are_named_and_bounded():
+    lib = B.lib()
+    for name in B.DEBUG_NAMES:
+        B.debug_set(name, 0)
+    assert lib.ap_debug_set(b"no_such_setting", C.c_int64(1)) == -1
+    assert b"no_such_setting" in lib.ap_last_error()
+    assert lib.ap_debug_set(b"seed_buffer_cap", C.c_int64(-5)) == -1
+    assert lib.ap_debug_set(None, C.c_int64(0)) == -1

@@ -70,7 +70,7 @@ def test_s2_seed_knn(case):
         assert u not in ids[r]
 
 
-def test_s2_seed_knn_threshold_path(case, monkeypatch):
+def test_s2_seed_knn_threshold_path(case, debug_knobs):
     """Large corpora never store the N x N scores: a column sample bounds each
     row's K-th best, one sweep buffers the scores above the bound.  Forced here
     on small corpora by shrinking the sample; also with a buffer so small that
@@ -81,11 +81,18 @@ def test_s2_seed_knn_threshold_path(case, monkeypatch):
     _say(f"S2 seed threshold path {name}")
     sub, nodes = _nodes(docs.n, name)
     exact = _np(*ix.stage_seed_knn(K, sub))
-    monkeypatch.setenv("AP_SEED_SAMPLE_COLS", "256")
+    debug_knobs("seed_sample_cols", 256)
     thr = _np(*ix.stage_seed_knn(K, sub))
-    monkeypatch.setenv("AP_SEED_BUFFER_CAP", "64")
+    debug_knobs("seed_buffer_cap", 64)
     ovf = _np(*ix.stage_seed_knn(K, sub))
-    for got in (thr, ovf):
+    # a threshold above the row's K-th best (here doubled: 2^23 ulps) leaves a row short of K candidates; such rows
+    # are redone by the exact path like overflowing ones
+    debug_knobs("seed_buffer_cap", 0)
+    debug_knobs("seed_tau_ulps", 1 << 23)
+    short = _np(*ix.stage_seed_knn(K, sub))
+    debug_knobs("seed_tau_ulps", 1)
+    ulp = _np(*ix.stage_seed_knn(K, sub))
+    for got in (thr, ovf, short, ulp):
         assert np.array_equal(got[0], exact[0]) and np.array_equal(got[1], exact[1])
 
 
@@ -253,7 +260,7 @@ def test_s6_assemble_and_entry(case):
     assert np.array_equal(ent, O.entry_points(self_gpu, 16))
 
 
-def test_whole_build_equals_stage_chain_and_searches(case, monkeypatch):
+def test_whole_build_equals_stage_chain_and_searches(case, debug_knobs):
     name, w, docs, ix, D, wv, dn, (R, K, S, P) = case
     _say(f"whole build {name}")
     N = docs.n
@@ -284,19 +291,19 @@ def test_whole_build_equals_stage_chain_and_searches(case, monkeypatch):
     again.close()
     # a launch holds fewer than 2^32 threads, so kernels with one workgroup per document run in slices on corpora of
     # millions; with the limit turned down to 64k threads (slices of 128 to 1024 documents) the bits are the same
-    monkeypatch.setenv("AP_MAX_LAUNCH_THREADS", "65536")
+    debug_knobs("max_launch_threads", 65536)
     sliced = B.Index.build(docs, bp)
     sem3, kw3, kc3, ent3 = _np(*sliced.export_graph())
     assert np.array_equal(sem, sem3) and np.array_equal(kw, kw3) and np.array_equal(kc, kc3) and np.array_equal(ent, ent3)
     if N > 300:
         grown = B.Index.build(B.DeviceVecs(subset_vecset(w.docs, np.arange(N - 200)), bf16=docs.dtype != 0), bp)
         a = grown.insert(docs)
-        monkeypatch.delenv("AP_MAX_LAUNCH_THREADS")
+        debug_knobs("max_launch_threads", 0)
         b = grown.insert(docs)
         for x, y in zip(a.export_graph(), b.export_graph()):
             assert torch.equal(x, y)
         a.close(); b.close(); grown.close()
-    monkeypatch.delenv("AP_MAX_LAUNCH_THREADS", raising=False)
+    debug_knobs("max_launch_threads", 0)
     sliced.close()
     # the graph is searchable: recall against the exhaustive scorer
     qs = B.DeviceVecs(w.queries)

@@ -260,6 +260,43 @@ def test_refine_round_bruteforce(small):
 
 
 # --------------------------------------------------------------- S4
+def test_pairwise_is_the_fused_gram_of_the_listed_documents(small):
+    """Neighbourhood similarities (Section 4.1 Step 2 needs sim(X, Y) for all members of a list): entry (i, j) is the
+    hybrid similarity of Definition 1 between the i-th and j-th listed documents, pinned here to the dot product of
+    the densely expanded concatenated vectors (Theorem 1) under weights that are not all equal; an empty slot gives
+    a row and a column of -inf; the diagonal holds self-similarities; the matrix is symmetric."""
+    w, D, _ = small
+    wv = np.array([0.6, 1.7, 0.45], np.float32)
+    comps, F = _fused_matrix(w, D, wv.astype(np.float64))
+    rng = np.random.default_rng(12)
+    for trial in range(6):
+        K = (5, 9, 16, 24, 1, 2)[trial]
+        ids = rng.choice(D.n, K, replace=False).astype(np.int32)
+        holes = rng.choice(K, K // 4, replace=False) if K >= 4 else np.array([], np.int64)
+        ids[holes] = -1
+        Pm = O.pairwise(D, wv, ids)
+        assert Pm.shape == (K, K) and Pm.dtype == np.float32
+        live = ids >= 0
+        # holes: whole rows and columns, and nothing else
+        assert np.isneginf(Pm[~live, :]).all() and np.isneginf(Pm[:, ~live]).all()
+        assert np.isfinite(Pm[np.ix_(live, live)]).all()
+        ref = F[np.ix_(ids[live], ids[live])]
+        np.testing.assert_allclose(Pm[np.ix_(live, live)], ref, rtol=2e-6, atol=1e-6)
+        # each component carries its own weight: drop one and the matrix changes by exactly that component
+        for p in range(3):
+            w0 = wv.copy(); w0[p] = 0.0
+            diff = Pm[np.ix_(live, live)].astype(np.float64) - O.pairwise(D, w0, ids)[np.ix_(live, live)]
+            np.testing.assert_allclose(diff, wv[p] * comps[p][np.ix_(ids[live], ids[live])], rtol=1e-4, atol=2e-5)
+        assert np.array_equal(Pm, Pm.T)
+    # the order of the list is the order of the matrix (a transposed or permuted index would show here)
+    ids = np.array([40, 7, 199], np.int32)
+    Pm = O.pairwise(D, wv, ids)
+    for i in range(3):
+        for j in range(3):
+            assert abs(Pm[i, j] - F[ids[i], ids[j]]) <= 2e-6 * abs(F[ids[i], ids[j]]) + 1e-6
+    assert abs(Pm[0, 0] - F[40, 40]) < 1e-4 and Pm[0, 0] != Pm[1, 1]
+
+
 def test_detour_recount_from_definition():
     """Section 3.3: A->X->Y detours A->Y iff max(dis(A,X), dis(X,Y)) < dis(A,Y),
     dis = -sim.  Recount with distances, no shared code."""
