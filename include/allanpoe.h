@@ -124,11 +124,11 @@ int ap_build_index(const ap_corpus *corpus, const ap_build_params *params, void 
  * no search that relies on the default weights is still in flight. */
 int ap_set_weights(ap_index *index, const float w[3]);
 
-/* Algorithm 2 on the semantic edges for nq queries at once (nq < 2^22 per
- * call).  per_query_w is nq x 3 (device) or NULL for the index default.
- * out_ids / out_scores are nq x k.  The call sizes a per-index workspace
- * (one visited bit per document and query) and may allocate on first use or
- * when nq grows. */
+/* Algorithm 2 on the semantic edges for nq queries at once.  per_query_w is
+ * nq x 3 (device) or NULL for the index default.  out_ids / out_scores are
+ * nq x k.  The call sizes a per-index workspace (one visited bit per document
+ * for every query in flight, at most 2 GiB: larger batches run in slabs of
+ * queries, one launch each) and may allocate on first use or when nq grows. */
 int ap_search_batch(ap_index *index, const ap_queries *queries, const float *per_query_w,
                     const ap_search_params *params, int32_t *out_ids, float *out_scores, void *stream);
 

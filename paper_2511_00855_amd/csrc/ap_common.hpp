@@ -162,6 +162,16 @@ int ap_prune_impl(const ap_index *ix, int32_t K, int32_t R, const int32_t *knn_i
 int ap_assemble_impl(const ap_index *ix, int32_t R, int32_t K, int32_t P, const int32_t *se, const int32_t *sorted_ids,
                      const int32_t *sp_ids, int32_t *out_graph, hipStream_t st);
 int ap_rescore_lists(const ap_index *ix, int64_t nn, int32_t K, const int32_t *knn, float *sc, hipStream_t st);
+// The visited-set workspace of a search call: `slab` queries are in flight at a time, each with a bitset of one bit
+// per document.  `counts` (nq x 3) and the two events belong to the index's measurement surface and may be absent.
+struct ApSearchWs {
+    uint32_t *visited = nullptr;
+    int32_t slab = 0;
+    int32_t *counts = nullptr;
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+};
+// sizes the workspace an index owns (grow only, capped) for a call of nq queries (ap_search.hip)
+int ap_search_reserve(ap_index *ix, int32_t nq, hipStream_t st, ApSearchWs *ws);
 // the plain search with an arbitrary query view and device weights (ap_search.hip); big_tables: the queries are as long
 // as documents, give them larger look-up tables
 int ap_search_core(ap_index *ix, const ApVecs &Q, const float *w_dev, int32_t w_stride, int32_t k, int32_t beam, int32_t max_iters,

@@ -114,15 +114,9 @@ static int insert_impl(const ap_index *old, ap_index *nx, int32_t beam, const ap
     }
     {
         const int32_t L = std::min<int32_t>(AP_MAX_BEAM, std::max<int32_t>(beam > 0 ? beam : 2 * K, K));
-        const size_t words = ((size_t)n1 + 31) / 32;
-        const int64_t step = std::max<int64_t>(1, (int64_t)(((size_t)1 << 28) / words));   // at most 1 GiB of visited bits per launch
-        for (int64_t q0 = 0; q0 < m; q0 += step) {
-            const int64_t qn = std::min(step, m - q0);
-            const ApVecs Q{qn, nx->docs.dim, static_cast<const char *>(qd) + (size_t)q0 * nx->docs.dim * 4,
-                           nx->docs.sp_indptr + n0 + q0, nx->docs.sp_idx, nx->docs.sp_val,
-                           nx->docs.tx_indptr + n0 + q0, nx->docs.tx_idx, nx->docs.tx_val};
-            AP_TRY(ap_search_core(nx, Q, w_dev, 0, K, L, 0, 1, true, c1_ids + q0 * K, c1_sc + q0 * K, st));
-        }
+        const ApVecs Q{m, nx->docs.dim, qd, nx->docs.sp_indptr + n0, nx->docs.sp_idx, nx->docs.sp_val,
+                       nx->docs.tx_indptr + n0, nx->docs.tx_idx, nx->docs.tx_val};
+        AP_TRY(ap_search_core(nx, Q, w_dev, 0, K, L, 0, 1, true, c1_ids, c1_sc, st));   // runs in slabs of queries by itself
     }
     nx->has_graph = false;
 

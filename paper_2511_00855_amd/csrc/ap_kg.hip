@@ -200,7 +200,8 @@ struct ApKgArgs {
     const int32_t *graph, *entry;
     const float *w;
     int32_t w_stride, R, E, k, L, max_iters, cmax;
-    uint32_t *visited;
+    int32_t q0;         // the launch covers queries q0 .. q0 + gridDim.x
+    uint32_t *visited;  // one bitset per query of the launch
     size_t words;
     int32_t *out_ids;
     float *out_scores;
@@ -242,7 +243,7 @@ __global__ __launch_bounds__(256) void k_search_kg(ApKgArgs g) {
     uint32_t *canda = cura + g.L;                                      // annotations of the candidates
     int32_t *cand = reinterpret_cast<int32_t *>(canda + g.cmax);
     __shared__ int32_t s_cnt, s_par, s_pann;
-    const int64_t q = blockIdx.x;
+    const int64_t q = (int64_t)g.q0 + blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     ApLists a;
     {
@@ -262,7 +263,7 @@ __global__ __launch_bounds__(256) void k_search_kg(ApKgArgs g) {
     float qa[NV * ApDense<DT>::EPC];
     ap_load_aside<DT, NV, AP_F32>(g.Q.dense, q, g.D.dim, qa);
     const float wd = g.w[q * g.w_stride + 0], ws = g.w[q * g.w_stride + 1], wf = g.w[q * g.w_stride + 2];
-    uint32_t *vis = g.visited + (size_t)q * g.words;
+    uint32_t *vis = g.visited + (size_t)blockIdx.x * g.words;
     if (threadIdx.x == 0) {
         // the documents that mention the query's entities, in the order of the entities then ascending id, at most E
         int32_t c = 0;
@@ -429,7 +430,6 @@ extern "C" int ap_search_batch_entities(ap_index *ix, const ap_queries *q, const
     AP_REQUIRE(max_hops >= 0 && max_hops <= 255, "max_hops = %d must be in [0, 255]", max_hops);
     AP_REQUIRE(w_k == w_k && w_k - w_k == 0.f, "w_k must be finite");
     if (q->nq == 0) return AP_OK;
-    AP_REQUIRE((int64_t)q->nq * 1024 < ((int64_t)1 << 32), "at most %d queries per call", (1 << 22) - 1);   // a launch holds < 2^32 threads
     hipStream_t st = (hipStream_t)stream;
     const int32_t nq = q->nq;
     ApKgArgs g;
@@ -442,41 +442,31 @@ extern "C" int ap_search_batch_entities(ap_index *ix, const ap_queries *q, const
     g.k = p->k; g.L = p->beam; g.max_iters = p->max_iters;
     g.cmax = std::max(g.E, g.R + ix->kg_le_cap);
     g.words = ((size_t)ix->docs.n + 31) / 32;
-    const size_t need = g.words * (size_t)nq;
-    if (need > ix->visited_words) {
-        if (ix->visited) { AP_CHECK_HIP(hipStreamSynchronize(st)); (void)hipFree(ix->visited); ix->visited = nullptr; ix->visited_words = 0; }
-        AP_TRY(ap_dev_alloc(&ix->visited, need));
-        ix->visited_words = need;
-    }
-    if ((size_t)nq * 3 > ix->search_counts_cap) {
-        if (ix->search_counts) { AP_CHECK_HIP(hipStreamSynchronize(st)); (void)hipFree(ix->search_counts); ix->search_counts = nullptr; ix->search_counts_cap = 0; }
-        AP_TRY(ap_dev_alloc(&ix->search_counts, (size_t)nq * 3));
-        ix->search_counts_cap = (size_t)nq * 3;
-    }
-    if (!ix->ev_search[0]) {
-        AP_CHECK_HIP(hipEventCreate(&ix->ev_search[0]));
-        AP_CHECK_HIP(hipEventCreate(&ix->ev_search[1]));
-    }
-    g.visited = ix->visited; g.out_ids = out_ids; g.out_scores = out_scores; g.counts = ix->search_counts;
+    ApSearchWs ws;
+    AP_TRY(ap_search_reserve(ix, nq, st, &ws));
+    g.visited = ws.visited; g.out_ids = out_ids; g.out_scores = out_scores; g.counts = ws.counts;
     g.rec = ix->rec; g.meta = ix->meta;
     g.de_ip = ix->kg_de_ip; g.de = ix->kg_de; g.kg_ip = ix->kg_ip; g.kg = ix->kg_idx; g.en_ip = ix->kg_en_ip; g.en = ix->kg_en;
     g.le = ix->kg_le; g.le_count = ix->kg_le_count; g.le_cap = ix->kg_le_cap;
     g.q_ent = q_ent; g.ent_stride = ent_stride; g.max_hops = max_hops; g.w_k = w_k;
     g.n_ent = ix->kg_n_ent; g.deleted = ix->deleted;
-    ix->last_nq = nq;
-    AP_TRY(ap_fill_u32(ix->visited, need, 0u, st));
     const size_t smem = (size_t)(g.L + g.cmax) * 8 + ((1 << AP_KG_SPB) + (1 << AP_KG_TXB)) * 8 + 8 + (size_t)g.cmax * 16 +
                         (size_t)(g.L + 2 * g.cmax) * 4;
     AP_REQUIRE(smem <= 160 * 1024, "beam needs %zu bytes of LDS (limit 160 KiB)", smem);
-    AP_CHECK_HIP(hipEventRecord(ix->ev_search[0], st));
-    hipError_t le = hipSuccess;
-    AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim, {
-        if (smem > 48 * 1024)
-            le = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_search_kg<DT, NV>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (le == hipSuccess) hipLaunchKernelGGL((k_search_kg<DT, NV>), dim3((unsigned)nq), dim3(256), smem, st, g);
-    });
-    AP_CHECK_HIP(le);
-    AP_CHECK_HIP(hipGetLastError());
+    for (int32_t q0 = 0; q0 < nq; q0 += ws.slab) {   // slabs of queries share the workspace
+        const int32_t qn = std::min(ws.slab, nq - q0);
+        g.q0 = q0;
+        AP_TRY(ap_fill_u32(ws.visited, g.words * (size_t)qn, 0u, st));
+        if (q0 == 0) AP_CHECK_HIP(hipEventRecord(ws.ev0, st));
+        hipError_t le = hipSuccess;
+        AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim, {
+            if (smem > 48 * 1024)
+                le = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_search_kg<DT, NV>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+            if (le == hipSuccess) hipLaunchKernelGGL((k_search_kg<DT, NV>), dim3((unsigned)qn), dim3(256), smem, st, g);
+        });
+        AP_CHECK_HIP(le);
+        AP_CHECK_HIP(hipGetLastError());
+    }
     AP_CHECK_HIP(hipEventRecord(ix->ev_search[1], st));
     return AP_OK;
 }

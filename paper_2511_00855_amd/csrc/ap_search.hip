@@ -11,6 +11,7 @@
 // visited set is an exact bitset (one bit per document) in a per-index global
 // workspace.
 #include <stdlib.h>
+#include <algorithm>
 #include "ap_common.hpp"
 
 
@@ -24,11 +25,12 @@ struct ApSearchArgs {
     int32_t w_stride;
     int32_t R, E, k, L, max_iters, width, cmax;
     int32_t nxtw;       // words of the scratch that parks positions when more keys enter at once than the workgroup has threads (else 0)
-    uint32_t *visited;
+    int32_t q0;         // the launch covers queries q0 .. q0 + gridDim.x (a slab of the batch)
+    uint32_t *visited;  // one bitset per query of the slab
     size_t words;       // visited words per query
     int32_t *out_ids;
     float *out_scores;
-    int32_t *counts;    // nq x 3: candidates scored, iterations, candidates whose dense row was skipped
+    int32_t *counts;    // nq x 3: candidates scored, iterations, candidates whose dense row was skipped (NULL: not wanted)
     const uint2 *rec;   // packed (term, weight) records of the documents' two sparse parts
     const uint4 *meta;  // per document: first entry, counts, |d_dense|
     const uint32_t *deleted;   // one bit per document, NULL = nothing is mark-deleted: left out of the answers only
@@ -192,7 +194,7 @@ void k_search(ApSearchArgs g) {
     __shared__ int32_t s_par[8], s_psat[8];
     __shared__ int32_t s_kw[AP_KW_MAX_TERMS];
 
-    const int64_t q = blockIdx.x;
+    const int64_t q = (int64_t)g.q0 + blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     // the query's lists: look-up tables in LDS when they are short (the usual case), else left in global memory
     ApLists a;
@@ -227,7 +229,7 @@ void k_search(ApSearchArgs g) {
         qnorm = sqrtf(ap_wave_sum(p));
     }
     const float wd = g.w[q * g.w_stride + 0], ws = g.w[q * g.w_stride + 1], wf = g.w[q * g.w_stride + 2];
-    uint32_t *vis = g.visited + (size_t)q * g.words;
+    uint32_t *vis = g.visited + (size_t)blockIdx.x * g.words;
     if (threadIdx.x == 0) { s_cnt = 0; s_skip = 0; s_xn = 0; s_kc = 0; }
     // the query's required terms, unused slots squeezed out (uniform)
     int32_t n_kw = 0;
@@ -421,7 +423,7 @@ void k_search(ApSearchArgs g) {
     }
     if (lane == 0) atomicAdd(&s_skip, nskipped);
     __syncthreads();
-    if (threadIdx.x == 0) { g.counts[q * 3] = nscored; g.counts[q * 3 + 1] = it; g.counts[q * 3 + 2] = s_skip; }
+    if (threadIdx.x == 0 && g.counts) { g.counts[q * 3] = nscored; g.counts[q * 3 + 1] = it; g.counts[q * 3 + 2] = s_skip; }
     // S9
     if (kw_on) {
         // Everything in the secondary pool ranked after the pool's last entry when it was handed over, and that
@@ -475,26 +477,57 @@ void k_search(ApSearchArgs g) {
     }
 }
 
+// Default cap of the index-owned workspace: 2 GiB of visited bits (16,384 queries of a million documents at a time).
+#define AP_SEARCH_WS_BYTES ((size_t)2 << 30)
+
+// Queries per slab when `cap_words` words are available: as many as fit, then evened out over the slabs.
+static int32_t ap_slab_size(int32_t nq, size_t words, size_t cap_words) {
+    size_t fit = std::max<size_t>(1, cap_words / std::max<size_t>(words, 1));
+    fit = std::min<size_t>(fit, (size_t)1 << 21);   // a launch of workgroups of up to 1024 threads holds fewer than 2^32 threads
+    if (fit >= (size_t)nq) return nq;
+    const size_t slabs = ((size_t)nq + fit - 1) / fit;
+    return (int32_t)(((size_t)nq + slabs - 1) / slabs);
+}
+
+// Sizes the workspace an index owns (grow only) for a call of nq queries.
+int ap_search_reserve(ap_index *ix, int32_t nq, hipStream_t st, ApSearchWs *ws) {
+    const size_t words = ((size_t)ix->docs.n + 31) / 32;
+    const size_t cap_bytes = g_ap_debug.search_workspace_bytes > 0 ? (size_t)g_ap_debug.search_workspace_bytes : AP_SEARCH_WS_BYTES;
+    ws->slab = ap_slab_size(nq, words, cap_bytes / 4);
+    const size_t need = words * (size_t)ws->slab;
+    if (need > ix->visited_words) {
+        if (ix->visited) { AP_CHECK_HIP(hipStreamSynchronize(st)); (void)hipFree(ix->visited); ix->visited = nullptr; ix->visited_words = 0; }
+        AP_TRY(ap_dev_alloc(&ix->visited, need));
+        ix->visited_words = need;
+    }
+    if ((size_t)nq * 3 > ix->search_counts_cap) {
+        if (ix->search_counts) { AP_CHECK_HIP(hipStreamSynchronize(st)); (void)hipFree(ix->search_counts); ix->search_counts = nullptr; ix->search_counts_cap = 0; }
+        AP_TRY(ap_dev_alloc(&ix->search_counts, (size_t)nq * 3));
+        ix->search_counts_cap = (size_t)nq * 3;
+    }
+    if (!ix->ev_search[0]) {
+        AP_CHECK_HIP(hipEventCreate(&ix->ev_search[0]));
+        AP_CHECK_HIP(hipEventCreate(&ix->ev_search[1]));
+    }
+    ws->visited = ix->visited;
+    ws->counts = ix->search_counts;
+    ws->ev0 = ix->ev_search[0]; ws->ev1 = ix->ev_search[1];
+    ix->last_nq = nq;
+    return AP_OK;
+}
+
 // The launch itself.  Q: the queries (any view with f32 dense rows); w_dev / w_stride: device weights, one triple
 // per query (stride 3) or one for all (stride 0).  kw_terms == NULL: the plain search; otherwise the
-// keyword-constrained one.
-static int ap_search_launch(ap_index *ix, const ApVecs &Q, const float *w_dev, int32_t w_stride, int32_t k, int32_t beam,
-                            int32_t max_iters, int32_t width, const int32_t *kw_terms, int32_t kw_stride, uint32_t kw_flags,
-                            bool big_tables, int32_t *out_ids, float *out_scores, hipStream_t st) {
+// keyword-constrained one.  The queries run in slabs of ws.slab, one launch each, that share the workspace.
+// Nothing here allocates: the workspace comes from the caller.
+static int ap_search_launch(const ap_index *ix, const ApSearchWs &ws, const ApVecs &Q, const float *w_dev, int32_t w_stride, int32_t k,
+                            int32_t beam, int32_t max_iters, int32_t width, const int32_t *kw_terms, int32_t kw_stride,
+                            uint32_t kw_flags, bool big_tables, int32_t *out_ids, float *out_scores, hipStream_t st) {
     // The keyword instantiation also serves plain searches on an index with mark-deleted documents (it carries the
     // answer filter; without required terms it searches exactly like the plain one), so that the plain
     // instantiation stays free of both.
     const bool kw = kw_terms != nullptr || ix->deleted != nullptr;
     const int32_t nq = (int32_t)Q.n;
-    if (!ix->has_graph) { ap_set_error("index has no graph: build or import one first"); return AP_ESTATE; }
-    AP_REQUIRE(nq == 0 || (out_ids && out_scores), "NULL output");
-    AP_REQUIRE(beam >= 1 && beam <= AP_MAX_BEAM, "beam = %d must be in [1, %d]", beam, AP_MAX_BEAM);
-    AP_REQUIRE(k >= 1 && k <= beam, "k = %d must be in [1, beam]", k);
-    AP_REQUIRE(width >= 1 && width <= 8, "search_width = %d must be in [1, 8]", width);
-    AP_REQUIRE(max_iters >= 0, "max_iters must be >= 0");
-    AP_REQUIRE(!kw || ix->docs.n < (1ll << 29), "keyword search and searches on an index with deletions need n < 2^29");
-    if (nq == 0) return AP_OK;
-    AP_REQUIRE((int64_t)nq * 1024 < ((int64_t)1 << 32), "at most %d queries per call", (1 << 22) - 1);   // a launch holds < 2^32 threads
     if (!kw_terms) kw_stride = 0;
     ApSearchArgs g;
     g.D = ix->docs;
@@ -512,30 +545,13 @@ static int ap_search_launch(ap_index *ix, const ApVecs &Q, const float *w_dev, i
     g.kw_use_edges = (kw_flags & AP_KW_NO_EDGES) ? 0 : 1;
     g.cmax = g.E > g.width * (g.R + g.KR) ? g.E : g.width * (g.R + g.KR);
     g.words = ((size_t)ix->docs.n + 31) / 32;
-    const size_t need = g.words * (size_t)nq;
-    if (need > ix->visited_words) {
-        if (ix->visited) { AP_CHECK_HIP(hipStreamSynchronize(st)); (void)hipFree(ix->visited); ix->visited = nullptr; ix->visited_words = 0; }
-        AP_TRY(ap_dev_alloc(&ix->visited, need));
-        ix->visited_words = need;
-    }
-    if ((size_t)nq * 3 > ix->search_counts_cap) {
-        if (ix->search_counts) { AP_CHECK_HIP(hipStreamSynchronize(st)); (void)hipFree(ix->search_counts); ix->search_counts = nullptr; ix->search_counts_cap = 0; }
-        AP_TRY(ap_dev_alloc(&ix->search_counts, (size_t)nq * 3));
-        ix->search_counts_cap = (size_t)nq * 3;
-    }
-    if (!ix->ev_search[0]) {
-        AP_CHECK_HIP(hipEventCreate(&ix->ev_search[0]));
-        AP_CHECK_HIP(hipEventCreate(&ix->ev_search[1]));
-    }
-    g.visited = ix->visited;
+    g.visited = ws.visited;
     g.out_ids = out_ids;
     g.out_scores = out_scores;
-    g.counts = ix->search_counts;
+    g.counts = ws.counts;
     g.rec = ix->rec;
     g.meta = ix->meta;
     g.deleted = ix->deleted;
-    ix->last_nq = nq;
-    AP_TRY(ap_fill_u32(ix->visited, need, 0u, st));
     auto lds_bytes = [&](int32_t nt) {
         const int32_t nxtw = g.cmax > nt ? g.cmax : 0;
         return (size_t)(g.L + 2 * g.cmax + nxtw + (kw ? g.cmax + g.k : 0)) * 8 + (size_t)g.cmax * (16 + 4) +
@@ -552,30 +568,53 @@ static int ap_search_launch(ap_index *ix, const ApVecs &Q, const float *w_dev, i
     g.nxtw = g.cmax > nt ? g.cmax : 0;
     const size_t smem = lds_bytes(nt);
     AP_REQUIRE(smem <= 160 * 1024, "beam and search_width need %zu bytes of LDS (limit 160 KiB)", smem);
-    AP_CHECK_HIP(hipEventRecord(ix->ev_search[0], st));
     hipError_t le = hipSuccess;
 #define AP_LAUNCH_SEARCH(KWF, BIGF, NTF)                                                                                         \
     AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim, {                                                                                  \
         if (smem > 48 * 1024)                                                                                                     \
             le = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_search<DT, NV, KWF, BIGF, NTF>),                           \
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);                                      \
-        if (le == hipSuccess) hipLaunchKernelGGL((k_search<DT, NV, KWF, BIGF, NTF>), dim3((unsigned)nq), dim3(NTF), smem, st, g); \
+        if (le == hipSuccess) hipLaunchKernelGGL((k_search<DT, NV, KWF, BIGF, NTF>), dim3((unsigned)qn), dim3(NTF), smem, st, g); \
     })
-    if (kw) AP_LAUNCH_SEARCH(true, false, 256);
-    else if (big_tables) AP_LAUNCH_SEARCH(false, true, 256);
-    else if (nt == 256) AP_LAUNCH_SEARCH(false, false, 256);
-    else if (nt == 512) AP_LAUNCH_SEARCH(false, false, 512);
-    else AP_LAUNCH_SEARCH(false, false, 1024);
+    for (int32_t q0 = 0; q0 < nq; q0 += ws.slab) {
+        const int32_t qn = std::min(ws.slab, nq - q0);
+        g.q0 = q0;
+        // every slab starts from empty visited sets (a fill kernel, not a memset: callers may capture the stream)
+        AP_TRY(ap_fill_u32(ws.visited, g.words * (size_t)qn, 0u, st));
+        if (q0 == 0 && ws.ev0) AP_CHECK_HIP(hipEventRecord(ws.ev0, st));
+        if (kw) AP_LAUNCH_SEARCH(true, false, 256);
+        else if (big_tables) AP_LAUNCH_SEARCH(false, true, 256);
+        else if (nt == 256) AP_LAUNCH_SEARCH(false, false, 256);
+        else if (nt == 512) AP_LAUNCH_SEARCH(false, false, 512);
+        else AP_LAUNCH_SEARCH(false, false, 1024);
+        AP_CHECK_HIP(le);
+        AP_CHECK_HIP(hipGetLastError());
+    }
 #undef AP_LAUNCH_SEARCH
-    AP_CHECK_HIP(le);
-    AP_CHECK_HIP(hipGetLastError());
-    AP_CHECK_HIP(hipEventRecord(ix->ev_search[1], st));
+    if (ws.ev1) AP_CHECK_HIP(hipEventRecord(ws.ev1, st));
+    return AP_OK;
+}
+
+// Argument checks shared by every entry into the search.
+static int ap_search_check(const ap_index *ix, int32_t nq, int32_t k, int32_t beam, int32_t max_iters, int32_t width, bool kw,
+                           const int32_t *out_ids, const float *out_scores) {
+    if (!ix->has_graph) { ap_set_error("index has no graph: build or import one first"); return AP_ESTATE; }
+    AP_REQUIRE(nq == 0 || (out_ids && out_scores), "NULL output");
+    AP_REQUIRE(beam >= 1 && beam <= AP_MAX_BEAM, "beam = %d must be in [1, %d]", beam, AP_MAX_BEAM);
+    AP_REQUIRE(k >= 1 && k <= beam, "k = %d must be in [1, beam]", k);
+    AP_REQUIRE(width >= 1 && width <= 8, "search_width = %d must be in [1, 8]", width);
+    AP_REQUIRE(max_iters >= 0, "max_iters must be >= 0");
+    AP_REQUIRE(!(kw || ix->deleted) || ix->docs.n < (1ll << 29), "keyword search and searches on an index with deletions need n < 2^29");
     return AP_OK;
 }
 
 int ap_search_core(ap_index *ix, const ApVecs &Q, const float *w_dev, int32_t w_stride, int32_t k, int32_t beam, int32_t max_iters,
                    int32_t width, bool big_tables, int32_t *out_ids, float *out_scores, hipStream_t st) {
-    return ap_search_launch(ix, Q, w_dev, w_stride, k, beam, max_iters, width, nullptr, 0, 0u, big_tables, out_ids, out_scores, st);
+    AP_TRY(ap_search_check(ix, (int32_t)Q.n, k, beam, max_iters, width, false, out_ids, out_scores));
+    if (Q.n == 0) return AP_OK;
+    ApSearchWs ws;
+    AP_TRY(ap_search_reserve(ix, (int32_t)Q.n, st, &ws));
+    return ap_search_launch(ix, ws, Q, w_dev, w_stride, k, beam, max_iters, width, nullptr, 0, 0u, big_tables, out_ids, out_scores, st);
 }
 
 static int ap_search_impl(ap_index *ix, const ap_queries *q, const float *per_query_w, const ap_search_params *p,
@@ -583,8 +622,12 @@ static int ap_search_impl(ap_index *ix, const ap_queries *q, const float *per_qu
                           void *stream) {
     AP_REQUIRE(ix && p, "NULL argument");
     AP_TRY(ap_validate_queries(q));
+    AP_TRY(ap_search_check(ix, q->nq, p->k, p->beam, p->max_iters, p->search_width, kw_terms != nullptr, out_ids, out_scores));
+    if (q->nq == 0) return AP_OK;
     const ApVecs Q{q->nq, ix->docs.dim, q->dense, q->sp_indptr, q->sp_idx, q->sp_val, q->tx_indptr, q->tx_idx, q->tx_cnt};
-    return ap_search_launch(ix, Q, per_query_w ? per_query_w : ix->w_dev, per_query_w ? 3 : 0, p->k, p->beam, p->max_iters,
+    ApSearchWs ws;
+    AP_TRY(ap_search_reserve(ix, q->nq, (hipStream_t)stream, &ws));
+    return ap_search_launch(ix, ws, Q, per_query_w ? per_query_w : ix->w_dev, per_query_w ? 3 : 0, p->k, p->beam, p->max_iters,
                             p->search_width, kw_terms, kw_stride, kw_flags, false, out_ids, out_scores, (hipStream_t)stream);
 }
 

@@ -129,3 +129,31 @@ def test_entity_search_cost(shard):
         fn(); torch.cuda.synchronize()
         t0 = time.time(); fn(); torch.cuda.synchronize()
         _say(f"  {name}: {big.n / (time.time() - t0):,.0f} queries/s, kernel {ix.search_kernel_ms():.2f} ms")
+
+
+def test_searches_in_slabs_of_queries_give_the_same_bits(shard, debug_knobs):
+    """A batch whose visited sets exceed the workspace cap runs in slabs of queries, one launch each: with the cap
+    turned down to seven queries' worth, the plain, the keyword-constrained and the entity search return the bits
+    and the per-query counters of the single launch."""
+    from paper_2511_00855_amd.synth import make_keywords
+    w, docs, qs, ix, kgs, D, Q, sem, ent, wq, table = shard
+    ix.set_knowledge_graph(kgs, le_cap=16)
+    kw = make_keywords(w.queries, seed=3, max_terms=2, stride=2, p_none=0.2)
+    runs = (("plain", lambda: ix.search_batch(qs, 10, 96, wq, search_width=2)),
+            ("keywords", lambda: ix.search_batch_keywords(qs, 10, 64, kw, wq)),
+            ("entities", lambda: ix.search_batch_entities(qs, 10, 64, kgs.q_ent, 0.5, 2, wq)))
+    whole = {}
+    for name, fn in runs:
+        ids, sc = [t.cpu().numpy() for t in fn()]
+        whole[name] = (ids, sc, ix.search_stats(qs.n)[0].cpu().numpy())
+    words = (docs.n + 31) // 32
+    debug_knobs("search_workspace_bytes", 7 * words * 4)         # 40 queries -> 6 slabs of 7, 7, 7, 7, 7, 5
+    for name, fn in runs:
+        _say(f"search in slabs: {name}")
+        ids, sc = [t.cpu().numpy() for t in fn()]
+        counts = ix.search_stats(qs.n)[0].cpu().numpy()
+        assert np.array_equal(ids, whole[name][0]) and np.array_equal(sc, whole[name][1]), name
+        assert np.array_equal(counts, whole[name][2]), name
+    debug_knobs("search_workspace_bytes", 1)                     # less than one query's set: one query per launch
+    ids, sc = [t.cpu().numpy() for t in ix.search_batch(qs, 10, 96, wq, search_width=2)]
+    assert np.array_equal(ids, whole["plain"][0]) and np.array_equal(sc, whole["plain"][1])
