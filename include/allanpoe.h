@@ -38,6 +38,7 @@
  */
 #ifndef ALLANPOE_H
 #define ALLANPOE_H
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -131,6 +132,19 @@ int ap_set_weights(ap_index *index, const float w[3]);
  * queries, one launch each) and may allocate on first use or when nq grows. */
 int ap_search_batch(ap_index *index, const ap_queries *queries, const float *per_query_w,
                     const ap_search_params *params, int32_t *out_ids, float *out_scores, void *stream);
+
+/* ap_search_batch for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same results bit for bit; the visited
+ * sets live in a static device array of AP_NOALLOC_WORKSPACE_BYTES (64 MiB, held by every GPU the library runs
+ * on until the process ends) instead of the index's workspace, and batches beyond it run in slabs of queries.
+ * The call allocates nothing, records no events and writes nothing into the index: ap_search_stats does not
+ * report on it.  A corpus of more than 8 * AP_NOALLOC_WORKSPACE_BYTES documents (one query's visited bits
+ * would not fit) is refused with AP_EINVAL.  All such calls on one GPU share the array: calls that overlap
+ * (different streams, different host threads, different indexes) race; calls on one stream are ordered.  Not for
+ * indexes with mark-deleted documents when n >= 2^29 (as ap_search_batch). */
+#define AP_NOALLOC_WORKSPACE_BYTES ((size_t)64 << 20)
+int ap_search_batch_noalloc(const ap_index *index, const ap_queries *queries, const float *per_query_w,
+                            const ap_search_params *params, int32_t *out_ids, float *out_scores, void *stream);
 
 /* Keyword-constrained search (Section 4.2.2; the keyword branches of
  * Algorithm 2).  kw_terms (device): nq x kw_stride term ids of the lexical

@@ -225,6 +225,17 @@ class Index:
         _check(rc, "ap_search_batch")
         return ids, sc
 
+    def search_batch_noalloc(self, queries: DeviceVecs, k: int, beam: int, per_query_w, out, max_iters: int = 0,
+                             search_width: int = 1):
+        """ap_search_batch_noalloc: the caller brings every buffer (per_query_w may be None); nothing is allocated here."""
+        ids, sc = out
+        qs = queries.queries_struct()
+        sp = _SearchParams(k, beam, max_iters, search_width)
+        with torch.cuda.device(self.device):
+            rc = lib().ap_search_batch_noalloc(self._h, C.byref(qs), _ptr(per_query_w), C.byref(sp), _ptr(ids), _ptr(sc), _stream())
+        _check(rc, "ap_search_batch_noalloc")
+        return ids, sc
+
     def insert(self, enlarged: DeviceVecs, beam: int = 0, trace: bool = False):
         """A new index over `enlarged` (this index's documents first, unchanged, then the new ones); see
         ap_insert_documents.  With trace=True also returns the intermediates of the new documents."""

@@ -267,6 +267,9 @@ int ap_ingest_impl(ap_index *ix, hipStream_t st) {
     }
     AP_CHECK_HIP(hipMemcpyAsync(ix->w_dev, ix->w_default, 3 * sizeof(float), hipMemcpyHostToDevice, st));
     AP_CHECK_HIP(hipStreamSynchronize(st));
+    // set-up of this device for searches that must not allocate: the address of their static workspace
+    void *ws = nullptr;
+    AP_TRY(ap_static_scratch(&ws));
     return AP_OK;
 }
 

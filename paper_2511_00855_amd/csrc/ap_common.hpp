@@ -172,6 +172,8 @@ struct ApSearchWs {
 };
 // sizes the workspace an index owns (grow only, capped) for a call of nq queries (ap_search.hip)
 int ap_search_reserve(ap_index *ix, int32_t nq, hipStream_t st, ApSearchWs *ws);
+// address, on the current device, of the static workspace of ap_search_batch_noalloc (looked up once per device)
+int ap_static_scratch(void **out);
 // the plain search with an arbitrary query view and device weights (ap_search.hip); big_tables: the queries are as long
 // as documents, give them larger look-up tables
 int ap_search_core(ap_index *ix, const ApVecs &Q, const float *w_dev, int32_t w_stride, int32_t k, int32_t beam, int32_t max_iters,

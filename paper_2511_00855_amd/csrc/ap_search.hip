@@ -12,6 +12,7 @@
 // workspace.
 #include <stdlib.h>
 #include <algorithm>
+#include <mutex>
 #include "ap_common.hpp"
 
 
@@ -634,6 +635,56 @@ static int ap_search_impl(ap_index *ix, const ap_queries *q, const float *per_qu
 extern "C" int ap_search_batch(ap_index *ix, const ap_queries *q, const float *per_query_w,
                                const ap_search_params *p, int32_t *out_ids, float *out_scores, void *stream) {
     return ap_search_impl(ix, q, per_query_w, p, nullptr, 0, 0u, out_ids, out_scores, stream);
+}
+
+// ---- the search for callers that cannot allocate ---------------------------------------------------------------
+// The visited sets live in a file-scope device array instead of an index-owned allocation.  Each GPU holds its own
+// copy of the array at its own address; host code uses the address hipGetSymbolAddress returns for the current
+// device, never the array's name (which is only a host-side stand-in).
+static __device__ __align__(256) unsigned char scratch[AP_NOALLOC_WORKSPACE_BYTES];
+
+#define AP_MAX_DEVICES 64
+static std::mutex g_scratch_lock;
+static void *g_scratch_ptr[AP_MAX_DEVICES];   // per device, filled on first use
+
+// The address of `scratch` on the current device (looked up once per device).
+int ap_static_scratch(void **out) {
+    int dev = -1;
+    AP_CHECK_HIP(hipGetDevice(&dev));
+    AP_REQUIRE(dev >= 0 && dev < AP_MAX_DEVICES, "device %d is beyond the %d devices this library keeps a workspace for", dev, AP_MAX_DEVICES);
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        AP_CHECK_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        AP_REQUIRE(p != nullptr, "the static search workspace has no address on device %d", dev);
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return AP_OK;
+}
+
+extern "C" int ap_search_batch_noalloc(const ap_index *ix, const ap_queries *q, const float *per_query_w,
+                                       const ap_search_params *p, int32_t *out_ids, float *out_scores, void *stream) {
+    AP_REQUIRE(ix && p, "NULL argument");
+    AP_TRY(ap_validate_queries(q));
+    AP_TRY(ap_search_check(ix, q->nq, p->k, p->beam, p->max_iters, p->search_width, false, out_ids, out_scores));
+    const size_t words = ((size_t)ix->docs.n + 31) / 32;
+    // the debug setting that caps the index-owned workspace caps this one too (never beyond the array)
+    const size_t cap = g_ap_debug.search_workspace_bytes > 0 ? std::min<size_t>((size_t)g_ap_debug.search_workspace_bytes, AP_NOALLOC_WORKSPACE_BYTES)
+                                                             : AP_NOALLOC_WORKSPACE_BYTES;
+    AP_REQUIRE(words * 4 <= cap,
+               "the corpus has %lld documents: one visited bit per document does not fit the static workspace of %zu bytes "
+               "(at most %zu documents); use ap_search_batch",
+               (long long)ix->docs.n, cap, cap * 8);
+    if (q->nq == 0) return AP_OK;
+    void *base = nullptr;
+    AP_TRY(ap_static_scratch(&base));
+    ApSearchWs ws;                       // no counters, no events: nothing of the index is written
+    ws.visited = static_cast<uint32_t *>(base);
+    ws.slab = ap_slab_size(q->nq, words, cap / 4);
+    const ApVecs Q{q->nq, ix->docs.dim, q->dense, q->sp_indptr, q->sp_idx, q->sp_val, q->tx_indptr, q->tx_idx, q->tx_cnt};
+    return ap_search_launch(ix, ws, Q, per_query_w ? per_query_w : ix->w_dev, per_query_w ? 3 : 0, p->k, p->beam, p->max_iters,
+                            p->search_width, nullptr, 0, 0u, false, out_ids, out_scores, (hipStream_t)stream);
 }
 
 extern "C" int ap_search_batch_keywords(ap_index *ix, const ap_queries *q, const float *per_query_w,
