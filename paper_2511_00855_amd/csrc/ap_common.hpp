@@ -268,6 +268,24 @@ __device__ __forceinline__ float ap_wave_sum(float v) {
     return v;
 }
 
+// Two sums at once: the wave sums of a and of b, each with the additions of ap_wave_sum (the same tree, so the same
+// bits), for the price of little more than one.  In the first exchange every lane keeps one of its two values and
+// hands the other to its neighbour; from then on half of the lanes reduce a and the other half b.  Which half a lane
+// is in, (lane ^ lane >> 2) & 1, is flipped by the first exchange and kept by all the later ones.
+__device__ __forceinline__ void ap_wave_sum2(float a, float b, float &sa, float &sb) {
+    const int lane = threadIdx.x & 63;
+    const bool second = ((lane ^ (lane >> 2)) & 1) != 0;
+    float v = second ? b : a;
+    v += ap_dpp<0xB1>(second ? a : b);   // the neighbour (lane ^ 1) keeps the other kind and sends this lane's kind
+    v += ap_dpp<0x4E>(v);
+    v += ap_dpp<0x141>(v);
+    v += ap_dpp<0x140>(v);
+    v += __shfl_xor(v, 16, 64);
+    v += __shfl_xor(v, 32, 64);
+    sa = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    sb = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 1));
+}
+
 #define AP_LDS __attribute__((address_space(3)))
 
 // Orders one wave's LDS traffic: what any lane wrote before this point is what every lane of the wave reads after it.
@@ -307,6 +325,49 @@ __device__ __forceinline__ float ap_match_fma(IP a_idx, VP a_val, int32_t a_n, i
 // full, so every probe sequence ends at an empty slot.
 __device__ __forceinline__ uint32_t ap_term_hash(int32_t t, int bits) {
     return (__umul24((uint32_t)t & 0xffffffu, 0x9E3779u) ^ ((uint32_t)t >> 24)) >> (32 - bits) ;
+}
+
+// ---- bucketed tables: one read per look-up ---------------------------------
+// A table of 2^bits slots seen as 2^(bits-1) buckets of two slots (16 bytes, read at once).  A term belongs to the
+// bucket its hash names, and the hash's multiplier is chosen per table so that no bucket has to hold three terms: a
+// query's few dozen terms nearly always allow that under one of the first multipliers tried (seed 0 is
+// ap_term_hash's).  A look-up is then one 16-byte read and two compares, with no probe sequence.
+__device__ __forceinline__ uint32_t ap_seed_mult(int32_t seed) { return ((0x9E3779u + 0x3C6EF4u * (uint32_t)seed) | 1u) & 0xffffffu; }
+__device__ __forceinline__ uint32_t ap_term_hash_m(int32_t t, uint32_t mult, int bits) {
+    return (__umul24((uint32_t)t & 0xffffffu, mult) ^ ((uint32_t)t >> 24)) >> (32 - bits);
+}
+// Weight of term t, 0 if absent.  An empty slot holds term -1 and weight bits 0, so t = -1 (a lane past the end of
+// a list) reads 0 as well.  tab: 16-byte aligned.
+template <typename TP>
+__device__ __forceinline__ float ap_bucket_get(TP tab, uint32_t mult, int bits, int32_t t) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const uint32_t h = ap_term_hash_m(t, mult, bits - 1);
+    const u32x4 b = *reinterpret_cast<const AP_LDS u32x4 *>(tab + 2 * h);
+    return __uint_as_float(b.x == (uint32_t)t ? b.y : (b.z == (uint32_t)t ? b.w : 0u));
+}
+#define AP_SEED_TRIES 32
+// One wave builds the table of the n <= 64 entries (idx, val): it tries multipliers until no bucket gets a third
+// term, clears the table and stores the entries.  Every lane returns the seed, -1 if none of the first
+// AP_SEED_TRIES does it (the table then holds nothing usable).
+__device__ __forceinline__ int32_t ap_bucket_build(const int32_t *idx, const float *val, int32_t n, uint64_t *tab, int bits) {
+    const int lane = threadIdx.x & 63;
+    const int32_t nb = 1 << (bits - 1);
+    const int32_t term = lane < n ? idx[lane] : -1;
+    int32_t *cnt = reinterpret_cast<int32_t *>(tab);   // bucket counters while searching (the table has 2^(bits+1) words)
+    for (int32_t s = 0; s < AP_SEED_TRIES; s++) {
+        for (int32_t i = lane; i < nb; i += 64) cnt[i] = 0;
+        ap_wave_sync();
+        const uint32_t h = ap_term_hash_m(term, ap_seed_mult(s), bits - 1);
+        const int32_t place = lane < n ? atomicAdd(&cnt[h], 1) : 0;
+        ap_wave_sync();
+        if (__ballot(place >= 2) == 0ull) {
+            for (int32_t i = lane; i < 2 * nb; i += 64) tab[i] = 0xffffffffull;
+            ap_wave_sync();
+            if (lane < n) tab[2 * h + place] = ((uint64_t)__float_as_uint(val[lane]) << 32) | (uint32_t)term;
+            return s;
+        }
+    }
+    return -1;
 }
 
 // Weight of term t in the table, 0 if absent (t = -1 is never present).
@@ -411,6 +472,46 @@ __device__ __forceinline__ float ap_dense_dot(const ApVecs &B, const float *qa, 
     return ap_wave_sum(pd);
 }
 
+// The same product in two steps, so that the rows of several candidates can be on their way before the first is
+// used: the raw 16-byte groups first, the multiply-adds (same order, same bits as ap_dense_dot) later.
+template <int DT, int NV>
+__device__ __forceinline__ void ap_dense_load_raw(const ApVecs &B, int64_t row, uint4 *raw) {
+    constexpr int EPC = ApDense<DT>::EPC;
+    const int lane = threadIdx.x & 63;
+    const char *base = static_cast<const char *>(B.dense) + row * (int64_t)B.dim * (16 / EPC);
+#pragma unroll
+    for (int i = 0; i < NV; i++) {
+        const int col = (i * 64 + lane) * EPC;
+        raw[i] = make_uint4(0u, 0u, 0u, 0u);
+        if (col < B.dim) raw[i] = *reinterpret_cast<const uint4 *>(base + (int64_t)col * (16 / EPC));
+    }
+}
+template <int DT, int NV>
+__device__ __forceinline__ float ap_dense_dot_raw(const ApVecs &B, const float *qa, const uint4 *raw) {
+    constexpr int EPC = ApDense<DT>::EPC;
+    const int lane = threadIdx.x & 63;
+    float pd = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; i++) {
+        const int col = (i * 64 + lane) * EPC;
+        if (col < B.dim) {
+            float d[EPC];
+            const uint4 v = raw[i];
+            if constexpr (DT == AP_F32) {
+                d[0] = __uint_as_float(v.x); d[1] = __uint_as_float(v.y); d[2] = __uint_as_float(v.z); d[3] = __uint_as_float(v.w);
+            } else {
+                d[0] = __uint_as_float(v.x << 16); d[1] = __uint_as_float(v.x & 0xffff0000u);
+                d[2] = __uint_as_float(v.y << 16); d[3] = __uint_as_float(v.y & 0xffff0000u);
+                d[4] = __uint_as_float(v.z << 16); d[5] = __uint_as_float(v.z & 0xffff0000u);
+                d[6] = __uint_as_float(v.w << 16); d[7] = __uint_as_float(v.w & 0xffff0000u);
+            }
+#pragma unroll
+            for (int e = 0; e < EPC; e++) pd = fmaf(qa[i * EPC + e], d[e], pd);
+        }
+    }
+    return ap_wave_sum(pd);
+}
+
 // Sparse and lexical parts of Definition 1 for one row of B whose lists are at
 // [spb, spb+spn) and [txb, txb+txn).  The first SS / TS 64-entry slots of the
 // two lists are loaded before any look-up starts (all loads in flight
@@ -496,6 +597,38 @@ __device__ __forceinline__ void ap_rec_reduce_tab(const uint2 *r, const AP_LDS u
     }
     ss = ap_wave_sum(ps);
     sf = ap_wave_sum(pf);
+}
+
+// The same sums against bucketed tables (multipliers msp, mtx): one read per look-up, no probing, and the two
+// wave sums share their exchanges.  Same per-lane accumulation order, same reduction tree: the same bits.
+template <int SS, int TS, int SPB, int TXB>
+__device__ __forceinline__ void ap_rec_reduce_bucket(const uint2 *r, const AP_LDS uint64_t *tsp, const AP_LDS uint64_t *ttx, uint32_t msp,
+                                                     uint32_t mtx, int32_t spn, int32_t txn, const int32_t *si, const float *sv,
+                                                     const int32_t *ti, const float *tv, float &ss, float &sf) {
+    const int lane = threadIdx.x & 63;
+    float av[SS + TS];
+#pragma unroll
+    for (int k = 0; k < SS; k++) av[k] = ap_bucket_get(tsp, msp, SPB, si[k]);
+#pragma unroll
+    for (int k = 0; k < TS; k++) av[SS + k] = ap_bucket_get(ttx, mtx, TXB, ti[k]);
+    float ps = 0.f, pf = 0.f;
+#pragma unroll
+    for (int k = 0; k < SS; k++) ps = fmaf(av[k], sv[k], ps);
+    for (int32_t e0 = SS * 64; e0 < spn; e0 += 64) {
+        const int32_t e = e0 + lane;
+        uint2 x = make_uint2(0xffffffffu, 0u);
+        if (e < spn) x = r[e];
+        ps = fmaf(ap_bucket_get(tsp, msp, SPB, (int32_t)x.x), __uint_as_float(x.y), ps);
+    }
+#pragma unroll
+    for (int k = 0; k < TS; k++) pf = fmaf(av[SS + k], tv[k], pf);
+    for (int32_t e0 = TS * 64; e0 < txn; e0 += 64) {
+        const int32_t e = e0 + lane;
+        uint2 x = make_uint2(0xffffffffu, 0u);
+        if (e < txn) x = r[spn + e];
+        pf = fmaf(ap_bucket_get(ttx, mtx, TXB, (int32_t)x.x), __uint_as_float(x.y), pf);
+    }
+    ap_wave_sum2(ps, pf, ss, sf);
 }
 
 // The same sums with the a side's lists searched where they lie (lists too long for the tables).

@@ -18,6 +18,20 @@
 
 int ap_validate_queries(const ap_queries *q);
 
+// Marks bit `bit` of a visited word and returns the word as it was.  Only the workgroup that searches the query
+// ever touches its visited set (zeroed by an earlier kernel), so the atomic needs workgroup scope only: it is carried
+// out in the L2 of the workgroup's own XCD instead of travelling to the memory side as a device-scope atomic does.
+#ifndef AP_VIS_DEVICE_SCOPE
+#define AP_VIS_DEVICE_SCOPE 0
+#endif
+__device__ __forceinline__ uint32_t ap_visit(uint32_t *word, uint32_t bit) {
+#if AP_VIS_DEVICE_SCOPE
+    return atomicOr(word, bit);
+#else
+    return __hip_atomic_fetch_or(word, bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+#endif
+}
+
 struct ApSearchArgs {
     ApVecs D, Q;
     const int32_t *graph;
@@ -74,9 +88,6 @@ __device__ __forceinline__ int32_t ap_rank_in(const uint64_t *keys, int32_t n, u
 // TAB: the query's lists are look-up tables in LDS (the usual case); otherwise
 // they are searched where they lie in global memory.
 // Returns the number of candidates whose dense row was skipped (wave-uniform).
-#ifndef AP_SEARCH_G
-#define AP_SEARCH_G 1
-#endif
 // Sizes of the query's two look-up tables (at most a quarter full).  Ordinary queries: 256 + 128 slots (lists up to
 // 64 / 32 entries).  Queries that are documents (insertion): 1024 + 512 slots (lists up to 256 / 128 entries).
 template <bool BIG> struct ApQTab {
@@ -89,15 +100,18 @@ template <bool BIG> struct ApQTab {
 // terms (s_kw[0..n_kw)); the key of a candidate that satisfies the constraint
 // carries the "satisfies" flag, and its dense row may only be skipped when the
 // bound also rules out the secondary pool (full, and its last score above the bound).
-template <int DT, int NV, bool TAB, bool KW, bool BIG, int NW>
+// G: candidates a wave keeps on their way at once.  Their records are loaded together, then reduced one by one;
+// then the dense rows of those that still need one are loaded together and multiplied one by one.  G = 1 is the
+// plain order (record, sums, dense row); larger G trades registers for memory requests in flight, which pays where
+// a large pool leaves a CU with few waves.  The order of the additions inside a candidate does not depend on G.
+template <int DT, int NV, bool TAB, bool KW, bool BIG, int NW, int G>
 __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const uint2 *rec, const float *qa, const uint64_t *qtab,
                                                        const ApLists &a, float wd, float ws, float wf, float qnorm, bool pool_full,
                                                        float worst_score, const int32_t *cand, const uint4 *s_meta, int32_t c,
                                                        uint64_t *newk, const int32_t *s_kw, int32_t n_kw, bool kw_all,
-                                                       bool second_full, float second_worst) {
+                                                       bool second_full, float second_worst, uint32_t msp, uint32_t mtx) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int32_t skipped = 0;
-    constexpr int G = AP_SEARCH_G;   // candidates whose list segments are in flight together
     for (int32_t i0 = wave; i0 < c; i0 += NW * G) {
         int32_t si[G][2], ti[G][1];
         float sv[G][2], tv[G][1];
@@ -117,23 +131,29 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const ui
                 ap_rec_load<2, 1>(r[gi], spn[gi], txn[gi], si[gi], sv[gi], ti[gi], tv[gi]);
             }
         }
+        float ss[G], sf[G];
+        uint32_t flags[G];
+        bool need[G];      // uniform: the candidate's dense row has to be read
 #pragma unroll
         for (int gi = 0; gi < G; gi++) {
             const int32_t i = i0 + NW * gi;
+            need[gi] = false;
             if (i >= c) continue;
-            const int32_t v = __builtin_amdgcn_readfirstlane(cand[i]);
-            float ss, sf;
-            if (TAB)
+            if (TAB && !BIG)   // ordinary queries: bucketed tables, one read per look-up
+                ap_rec_reduce_bucket<2, 1, ApQTab<BIG>::SPB, ApQTab<BIG>::TXB>(r[gi], (const AP_LDS uint64_t *)qtab,
+                                                                               (const AP_LDS uint64_t *)(qtab + (1 << ApQTab<BIG>::SPB)),
+                                                                               msp, mtx, spn[gi], txn[gi], si[gi], sv[gi], ti[gi], tv[gi], ss[gi], sf[gi]);
+            else if (TAB)      // queries that are documents (insertion): open-addressing tables
                 ap_rec_reduce_tab<2, 1, ApQTab<BIG>::SPB, ApQTab<BIG>::TXB>(r[gi], (const AP_LDS uint64_t *)qtab,
                                                                             (const AP_LDS uint64_t *)(qtab + (1 << ApQTab<BIG>::SPB)),
-                                                                            spn[gi], txn[gi], si[gi], sv[gi], ti[gi], tv[gi], ss, sf);
+                                                                            spn[gi], txn[gi], si[gi], sv[gi], ti[gi], tv[gi], ss[gi], sf[gi]);
             else
-                ap_rec_reduce_lists<2, 1>(r[gi], a, spn[gi], txn[gi], si[gi], sv[gi], ti[gi], tv[gi], ss, sf);
+                ap_rec_reduce_lists<2, 1>(r[gi], a, spn[gi], txn[gi], si[gi], sv[gi], ti[gi], tv[gi], ss[gi], sf[gi]);
             // upper bound of the fused score, with slack far above fp32 rounding
             const float dmax = fabsf(wd) * qnorm * dn[gi] * 1.0001f;
-            const float part = fmaf(wf, sf, ws * ss);
-            const float ub = part + dmax + 1e-5f * (fabsf(ws * ss) + fabsf(wf * sf) + dmax);
-            uint32_t flags = 1u;
+            const float part = fmaf(wf, sf[gi], ws * ss[gi]);
+            const float ub = part + dmax + 1e-5f * (fabsf(ws * ss[gi]) + fabsf(wf * sf[gi]) + dmax);
+            flags[gi] = 1u;
             if (KW && n_kw > 0) {
                 uint32_t hit = 0;   // bit j: required term j occurs in the candidate's text
                 for (int32_t e0 = 0; e0 < txn[gi]; e0 += 64) {
@@ -142,21 +162,70 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const ui
                     for (int32_t j = 0; j < n_kw; j++) hit |= __ballot(term == s_kw[j]) != 0ull ? 1u << j : 0u;
                 }
                 const bool sat = kw_all ? hit == (1u << n_kw) - 1u : hit != 0u;
-                flags |= sat ? 2u : 0u;
+                flags[gi] |= sat ? 2u : 0u;
             }
-            uint64_t key;
-            if (pool_full && ub < worst_score && (!(flags & 2u) || (second_full && ub < second_worst))) {
-                key = (uint64_t)(uint32_t)(i + 1);   // ranks after every real key (score bits 0), distinct per candidate
+            if (pool_full && ub < worst_score && (!(flags[gi] & 2u) || (second_full && ub < second_worst))) {
+                if (lane == 0) newk[i] = (uint64_t)(uint32_t)(i + 1);   // ranks after every real key (score bits 0), distinct per candidate
                 skipped++;
             } else {
-                const float sd = ap_dense_dot<DT, NV>(D, qa, v);
-                key = ap_pool_key<KW>(ap_fuse(wd, ws, wf, sd, ss, sf), v, flags);
+                need[gi] = true;
             }
-            if (lane == 0) newk[i] = key;
+        }
+        uint4 raw[G][NV];
+        int32_t v[G];
+#pragma unroll
+        for (int gi = 0; gi < G; gi++) {
+            if (need[gi]) {
+                v[gi] = __builtin_amdgcn_readfirstlane(cand[i0 + NW * gi]);
+                ap_dense_load_raw<DT, NV>(D, v[gi], raw[gi]);
+            }
+        }
+#pragma unroll
+        for (int gi = 0; gi < G; gi++) {
+            if (need[gi]) {
+                const float sd = ap_dense_dot_raw<DT, NV>(D, qa, raw[gi]);
+                if (lane == 0) newk[i0 + NW * gi] = ap_pool_key<KW>(ap_fuse(wd, ws, wf, sd, ss[gi], sf[gi]), v[gi], flags[gi]);
+            }
         }
     }
     return skipped;
 }
+
+// Candidates a wave keeps in flight (ap_score_candidates' G), by workgroup size.  Measured on a million-document
+// shape at every pool size: one is fastest everywhere.  A second candidate costs some 35 registers, and the kernel is
+// bound by instruction issue, not by the latency of a wave's own loads, even with sixteen waves alone on a CU.
+#ifndef AP_SEARCH_G_256
+#define AP_SEARCH_G_256 1
+#endif
+#ifndef AP_SEARCH_G_512
+#define AP_SEARCH_G_512 1
+#endif
+#ifndef AP_SEARCH_G_1024
+#define AP_SEARCH_G_1024 1
+#endif
+#ifndef AP_SEARCH_WAVES_512
+#define AP_SEARCH_WAVES_512 6
+#endif
+template <int NT> struct ApSearchG { static constexpr int G = NT == 1024 ? AP_SEARCH_G_1024 : NT == 512 ? AP_SEARCH_G_512 : AP_SEARCH_G_256; };
+
+// Profiling aid of debug builds (-DAP_SEARCH_PROFILE): thread 0 of every workgroup adds the time it spent in each
+// phase of the loop (100 MHz ticks) to a device array that ap_debug_search_profile reads and clears.
+#ifdef AP_SEARCH_PROFILE
+__device__ unsigned long long g_search_prof[8];
+#define AP_PROF_DECL unsigned long long prof_t = wall_clock64(), prof_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0}
+#define AP_PROF(i) do { const unsigned long long now_ = wall_clock64(); prof_acc[i] += now_ - prof_t; prof_t = now_; } while (0)
+#define AP_PROF_FLUSH do { if (threadIdx.x == 0) for (int i_ = 0; i_ < 8; i_++) atomicAdd(&g_search_prof[i_], prof_acc[i_]); } while (0)
+extern "C" int ap_debug_search_profile(unsigned long long out8[8]) {
+    AP_CHECK_HIP(hipMemcpyFromSymbol(out8, HIP_SYMBOL(g_search_prof), sizeof(g_search_prof)));
+    unsigned long long z[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    AP_CHECK_HIP(hipMemcpyToSymbol(HIP_SYMBOL(g_search_prof), z, sizeof(z)));
+    return AP_OK;
+}
+#else
+#define AP_PROF_DECL
+#define AP_PROF(i)
+#define AP_PROF_FLUSH
+#endif
 
 // NT threads per workgroup.  256 (four waves) is the usual size: seven workgroups share a CU while the pool is small
 // enough, and the register budget is the 72 VGPRs of seven waves per SIMD.  When the pool is so large that the LDS
@@ -173,7 +242,7 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const ui
 // Wide bf16 rows (more than 1024 columns: 24 or 32 query values per lane) do not fit seven waves' registers without
 // spilling; they run at five waves per SIMD.
 template <int DT, int NV, int NT> struct ApSearchWaves {
-    static constexpr int MIN = (DT == AP_BF16 && NV >= 3) ? (NT == 1024 ? 4 : 5) : NT == 256 ? AP_SEARCH_WAVES_PER_SIMD : NT == 512 ? 6 : 4;
+    static constexpr int MIN = (DT == AP_BF16 && NV >= 3) ? (NT == 1024 ? 4 : 5) : NT == 256 ? AP_SEARCH_WAVES_PER_SIMD : NT == 512 ? AP_SEARCH_WAVES_512 : 4;
 };
 template <int DT, int NV, bool KW, bool BIG, int NT>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(ApSearchWaves<DT, NV, NT>::MIN, 8)))
@@ -183,17 +252,23 @@ void k_search(ApSearchArgs g) {
     uint64_t *newk = cur + g.L;              // keys of this iteration's candidates, unordered
     uint64_t *newS = newk + g.cmax;          // the same, sorted
     uint64_t *nxt = newS + g.cmax;           // scratch of nxtw words (only wide searches need it)
-    uint64_t *xk = nxt + g.nxtw;             // KW: satisfying keys the pool did not keep in this iteration (cmax words)
-    uint64_t *kwc = xk + (KW ? g.cmax : 0);  // KW: the secondary pool, k keys, best first
-    uint64_t *qtab = kwc + (KW ? g.k : 0);   // the query's two look-up tables
-    // descriptors of this iteration's candidates (16-byte aligned: an odd number of words before them shifts them by one)
+    // Large pools (workgroups of 512 or 1024 threads): the keys that cannot enter are dropped before sorting, and
+    // parents are picked from a bitmap of the unexpanded entries.
+    constexpr bool PIPE = !KW && !BIG && NT >= 512;
+    uint64_t *xk = nxt + g.nxtw;             // cmax words.  KW: satisfying keys the pool did not keep in this iteration; PIPE: entering keys, unordered
+    uint64_t *kwc = xk + (KW || PIPE ? g.cmax : 0);  // KW: the secondary pool, k keys, best first
+    // the query's two look-up tables, 16-byte aligned (buckets and descriptors are read 16 bytes at a time): an odd
+    // number of words before them shifts them by one
+    uint64_t *qtab = kwc + (KW ? g.k : 0) + ((g.L + 2 * g.cmax + g.nxtw + (KW || PIPE ? g.cmax : 0) + (KW ? g.k : 0)) & 1);
+    // descriptors of this iteration's candidates
     constexpr int SPB = ApQTab<BIG>::SPB, TXB = ApQTab<BIG>::TXB;
-    uint4 *s_meta = reinterpret_cast<uint4 *>(qtab + ApQTab<BIG>::SLOTS +
-                                              ((g.L + 2 * g.cmax + g.nxtw + (KW ? g.cmax + g.k : 0)) & 1));
+    uint4 *s_meta = reinterpret_cast<uint4 *>(qtab + ApQTab<BIG>::SLOTS);
     int32_t *cand = reinterpret_cast<int32_t *>(s_meta + g.cmax);
-    __shared__ int32_t s_cnt, s_np, s_skip, s_xn, s_kc;
+    uint64_t *umask = reinterpret_cast<uint64_t *>(cand + g.cmax + (g.cmax & 1));   // PIPE: one bit per pool entry
+    __shared__ int32_t s_cnt, s_np, s_skip, s_xn, s_kc, s_nin, s_fu, s_rmin;
     __shared__ int32_t s_par[8], s_psat[8];
     __shared__ int32_t s_kw[AP_KW_MAX_TERMS];
+    __shared__ int32_t s_seed[2];
 
     const int64_t q = (int64_t)g.q0 + blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -204,20 +279,26 @@ void k_search(ApSearchArgs g) {
         a.sp_n = (int32_t)(g.Q.sp_indptr[q + 1] - sb); a.tx_n = (int32_t)(g.Q.tx_indptr[q + 1] - tb);
         a.sp_idx = g.Q.sp_idx + sb; a.sp_val = g.Q.sp_val + sb; a.tx_idx = g.Q.tx_idx + tb; a.tx_val = g.Q.tx_val + tb;
     }
-    const bool use_tab = a.sp_n <= (1 << SPB) / 4 && a.tx_n <= (1 << TXB) / 4;   // uniform
-    if (use_tab) {
+    // Ordinary queries (lists of at most 64 / 32 entries): wave 0 builds the two bucketed tables; if no multiplier
+    // fits a list (or a list is longer), the lists are searched where they lie.  Queries that are documents get
+    // open-addressing tables four times their length.
+    bool use_tab = a.sp_n <= (1 << SPB) / 4 && a.tx_n <= (1 << TXB) / 4;   // uniform
+    uint32_t msp = 0, mtx = 0;
+    if (!BIG) {
+        if (use_tab && wave == 0) {
+            const int32_t s0 = ap_bucket_build(a.sp_idx, a.sp_val, a.sp_n, qtab, SPB);
+            const int32_t s1 = ap_bucket_build(a.tx_idx, a.tx_val, a.tx_n, qtab + (1 << SPB), TXB);
+            if (lane == 0) { s_seed[0] = s0; s_seed[1] = s1; }
+        }
+        __syncthreads();
+        use_tab = use_tab && s_seed[0] >= 0 && s_seed[1] >= 0;
+        if (use_tab) { msp = ap_seed_mult(s_seed[0]); mtx = ap_seed_mult(s_seed[1]); }
+    } else if (use_tab) {
         for (int i = threadIdx.x; i < ApQTab<BIG>::SLOTS; i += blockDim.x) qtab[i] = 0xffffffffull;
         __syncthreads();
-        if (BIG) {
-            for (int t = threadIdx.x; t < a.sp_n + a.tx_n; t += blockDim.x) {
-                if (t < a.sp_n) ap_table_put(qtab, 1 << SPB, SPB, a.sp_idx[t], __float_as_int(a.sp_val[t]));
-                else ap_table_put(qtab + (1 << SPB), 1 << TXB, TXB, a.tx_idx[t - a.sp_n], __float_as_int(a.tx_val[t - a.sp_n]));
-            }
-        } else {   // at most 64 + 32 entries: one pass
-            const int t = threadIdx.x;
+        for (int t = threadIdx.x; t < a.sp_n + a.tx_n; t += blockDim.x) {
             if (t < a.sp_n) ap_table_put(qtab, 1 << SPB, SPB, a.sp_idx[t], __float_as_int(a.sp_val[t]));
-            else if (t < a.sp_n + a.tx_n)
-                ap_table_put(qtab + (1 << SPB), 1 << TXB, TXB, a.tx_idx[t - a.sp_n], __float_as_int(a.tx_val[t - a.sp_n]));
+            else ap_table_put(qtab + (1 << SPB), 1 << TXB, TXB, a.tx_idx[t - a.sp_n], __float_as_int(a.tx_val[t - a.sp_n]));
         }
     }
     float qa[NV * ApDense<DT>::EPC];
@@ -231,7 +312,7 @@ void k_search(ApSearchArgs g) {
     }
     const float wd = g.w[q * g.w_stride + 0], ws = g.w[q * g.w_stride + 1], wf = g.w[q * g.w_stride + 2];
     uint32_t *vis = g.visited + (size_t)blockIdx.x * g.words;
-    if (threadIdx.x == 0) { s_cnt = 0; s_skip = 0; s_xn = 0; s_kc = 0; }
+    if (threadIdx.x == 0) { s_cnt = 0; s_skip = 0; s_xn = 0; s_kc = 0; s_nin = 0; s_fu = 0; }
     // the query's required terms, unused slots squeezed out (uniform)
     int32_t n_kw = 0;
     if (KW) {
@@ -249,7 +330,7 @@ void k_search(ApSearchArgs g) {
         const int32_t v = g.entry[i];
         if (v >= 0) {
             const uint32_t bit = 1u << (v & 31);
-            const uint32_t old = atomicOr(&vis[v >> 5], bit);
+            const uint32_t old = ap_visit(&vis[v >> 5], bit);
             const uint4 m = g.meta[v];
             if (!(old & bit)) { const int32_t at = atomicAdd(&s_cnt, 1); cand[at] = v; s_meta[at] = m; }
         }
@@ -257,7 +338,9 @@ void k_search(ApSearchArgs g) {
     __syncthreads();
     int32_t len = 0, it = 0, nscored = 0, nskipped = 0;
     int32_t fu = 0;   // every pool entry before this position has been expanded
+    AP_PROF_DECL;
     for (;;) {
+        AP_PROF(0);
         const int32_t c = s_cnt;
         nscored += c;
         const bool pool_full = len == g.L;
@@ -265,23 +348,48 @@ void k_search(ApSearchArgs g) {
         const float worst_score = ap_key_score(worst);
         const bool second_full = kw_on && s_kc == g.k;   // s_kc and kwc were last written before the previous barriers
         const float second_worst = second_full ? ap_key_score(kwc[g.k - 1]) : 0.f;
+        constexpr int G = ApSearchG<NT>::G;
         if (use_tab)
-            nskipped += ap_score_candidates<DT, NV, true, KW, BIG, NT / 64>(g.D, g.rec, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score, cand,
-                                                              s_meta, c, newk, s_kw, n_kw, g.kw_all != 0, second_full, second_worst);
+            nskipped += ap_score_candidates<DT, NV, true, KW, BIG, NT / 64, G>(g.D, g.rec, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score, cand,
+                                                                 s_meta, c, newk, s_kw, n_kw, g.kw_all != 0, second_full, second_worst, msp, mtx);
         else
-            nskipped += ap_score_candidates<DT, NV, false, KW, BIG, NT / 64>(g.D, g.rec, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score, cand,
-                                                               s_meta, c, newk, s_kw, n_kw, g.kw_all != 0, second_full, second_worst);
+            nskipped += ap_score_candidates<DT, NV, false, KW, BIG, NT / 64, G>(g.D, g.rec, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score, cand,
+                                                                  s_meta, c, newk, s_kw, n_kw, g.kw_all != 0, second_full, second_worst, 0u, 0u);
+        AP_PROF(1);
         __syncthreads();
-        // sort the new keys by ranking them among themselves; only those that
-        // rank before the pool's last entry (when the pool is full) can enter
-        for (int32_t t = threadIdx.x; t < c; t += blockDim.x) {
-            const uint64_t key = newk[t];
-            int32_t r = 0;
-            for (int32_t j = 0; j < c; j++) r += newk[j] > key;
-            newS[r] = key;
+        AP_PROF(2);
+        int32_t cin;
+        if (PIPE) {
+            // Only keys that rank before the pool's last entry can enter (any key while the pool has room): late in a
+            // search they are a small part of the iteration's candidates, so they are picked out first (unordered, in
+            // xk) and ranked among themselves afterwards.
+            for (int32_t t = threadIdx.x; t < c; t += blockDim.x) {
+                const uint64_t key = newk[t];
+                if ((key >> 32) != 0ull && key > worst) xk[atomicAdd(&s_nin, 1)] = key;
+            }
+            __syncthreads();
+            cin = s_nin;
+            for (int32_t t = threadIdx.x; t < cin; t += blockDim.x) {
+                const uint64_t key = xk[t];
+                int32_t r = 0;
+                for (int32_t j = 0; j < cin; j++) r += xk[j] > key;
+                newS[r] = key;
+            }
+            __syncthreads();
+            if (threadIdx.x == 0) s_nin = 0;   // next touched after the barriers of the merge or the pick
+        } else {
+            // sort the new keys by ranking them among themselves; only those that
+            // rank before the pool's last entry (when the pool is full) can enter
+            for (int32_t t = threadIdx.x; t < c; t += blockDim.x) {
+                const uint64_t key = newk[t];
+                int32_t r = 0;
+                for (int32_t j = 0; j < c; j++) r += newk[j] > key;
+                newS[r] = key;
+            }
+            __syncthreads();
+            cin = ap_rank_in(newS, c, worst);   // new keys that rank before `worst` (all of them while the pool has room)
         }
-        __syncthreads();
-        const int32_t cin = ap_rank_in(newS, c, worst);   // new keys that rank before `worst` (all of them while the pool has room)
+        AP_PROF(3);
         if (kw_on) {
             // scored, satisfying, but ranked after the full pool's last entry: to the secondary pool
             for (int32_t t = cin + (int32_t)threadIdx.x; t < c; t += blockDim.x) {
@@ -295,15 +403,16 @@ void k_search(ApSearchArgs g) {
             // end: chunks of 2 NT entries are read, then (one barrier later) written, from the back of the pool to the
             // front.  A chunk's writes never reach below its own start, so they need not be fenced from the reads of
             // the chunk before it; the barrier of that chunk orders them before its writes.
-            const int32_t rmin = ap_rank_in(cur, len, newS[0]);
-            fu = fu < rmin ? fu : rmin;   // the best entering key lands at rmin, unexpanded; entries before it stay put
             uint64_t nkey = 0; int32_t npos = g.L;
             if ((int32_t)threadIdx.x < cin) { nkey = newS[threadIdx.x]; npos = (int32_t)threadIdx.x + ap_rank_in(cur, len, nkey); }
+            if (threadIdx.x == 0) s_rmin = npos;   // where the best entering key lands
             for (int32_t t = (int32_t)threadIdx.x + NT; t < cin; t += NT) {   // more entering keys than threads (wide searches)
                 const uint64_t key = newS[t];
                 nxt[t] = (uint64_t)(uint32_t)(t + ap_rank_in(cur, len, key));   // park the positions in the scratch array
             }
             __syncthreads();
+            const int32_t rmin = s_rmin;
+            fu = fu < rmin ? fu : rmin;   // the best entering key lands at rmin, unexpanded; entries before it stay put
             for (int32_t hi = len; hi > rmin; hi -= 2 * NT) {
                 const int32_t lo = hi - 2 * NT > rmin ? hi - 2 * NT : rmin;
                 uint64_t held[2]; int32_t dest[2];
@@ -372,9 +481,47 @@ void k_search(ApSearchArgs g) {
                 if (lane == 0) { s_xn = 0; s_kc = kc; }
             }
         }
+        AP_PROF(4);
         if (g.max_iters > 0 && it >= g.max_iters) break;
         // S8: pick the best `width` unexpanded entries (wave 0), mark them expanded
-        if (wave == 0) {
+        if (PIPE) {
+            // Late in a search the unexpanded entries are few and far apart, and a scan by one wave would walk most of
+            // the pool: every wave reduces its share of the pool from the cursor on to one bit per entry, and wave 0
+            // picks from the bits.
+            const int32_t b0 = fu >> 6, nb = (len + 63) >> 6;
+            for (int32_t b = b0 + wave; b < nb; b += NT / 64) {
+                const int32_t i = b * 64 + lane;
+                const uint64_t m = __ballot(i < len && (cur[i] & 1ull));
+                if (lane == 0) umask[b] = m;
+            }
+            __syncthreads();
+            if (wave == 0) {
+                // the first `width` set bits, found with uniform (scalar) steps; lane j then takes the j-th of them
+                int32_t found = 0, last = -1, mine = -1;
+                for (int32_t base = b0; base < nb && found < g.width; base += 64) {
+                    const int32_t b = base + lane;
+                    const uint64_t m = b < nb ? umask[b] : 0ull;
+                    uint64_t nz = __ballot(m != 0ull);
+                    while (nz != 0ull && found < g.width) {
+                        const int32_t src = (int32_t)__builtin_ctzll(nz);
+                        nz &= nz - 1ull;
+                        uint64_t word = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int32_t)(m >> 32), src) << 32) |
+                                        (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int32_t)(uint32_t)m, src);
+                        while (word != 0ull && found < g.width) {
+                            last = (base + src) * 64 + (int32_t)__builtin_ctzll(word);
+                            word &= word - 1ull;
+                            if (lane == found) mine = last;
+                            found++;
+                        }
+                    }
+                }
+                if (mine >= 0) {
+                    s_par[lane] = ap_pool_id<KW>(cur[mine]);
+                    cur[mine] &= ~1ull;
+                }
+                if (lane == 0) { s_np = found; s_cnt = 0; s_fu = last >= 0 ? last + 1 : len; }
+            }
+        } else if (wave == 0) {
             int32_t found = 0, last = -1;
             for (int32_t base = fu & ~63; base < len && found < g.width; base += 64) {   // the scan starts where it can first succeed
                 const int32_t i = base + lane;
@@ -395,7 +542,9 @@ void k_search(ApSearchArgs g) {
             if (lane == 0) { s_np = found < g.width ? found : g.width; s_cnt = 0; }
         }
         __syncthreads();
+        AP_PROF(5);
         const int32_t np = s_np;
+        if (PIPE) fu = s_fu;   // every wave needs the cursor (the bitmap starts there)
         if (np == 0) break;
         // neighbours of the parents that were never seen before; a parent that satisfies the keyword
         // constraint also brings its keyword edges
@@ -414,14 +563,16 @@ void k_search(ApSearchArgs g) {
                 const uint32_t bit = 1u << (v & 31);
                 // the descriptor (where the record is, how long, the dense norm) is fetched along with the visited
                 // test, not after it: one memory round trip less per iteration for 16 bytes per neighbour already seen
-                const uint32_t old = atomicOr(&vis[v >> 5], bit);
+                const uint32_t old = ap_visit(&vis[v >> 5], bit);
                 const uint4 m = g.meta[v];
                 if (!(old & bit)) { const int32_t at = atomicAdd(&s_cnt, 1); cand[at] = v; s_meta[at] = m; }
             }
         }
         __syncthreads();
+        AP_PROF(6);
         it++;
     }
+    AP_PROF_FLUSH;
     if (lane == 0) atomicAdd(&s_skip, nskipped);
     __syncthreads();
     if (threadIdx.x == 0 && g.counts) { g.counts[q * 3] = nscored; g.counts[q * 3 + 1] = it; g.counts[q * 3 + 2] = s_skip; }
@@ -555,8 +706,10 @@ static int ap_search_launch(const ap_index *ix, const ApSearchWs &ws, const ApVe
     g.deleted = ix->deleted;
     auto lds_bytes = [&](int32_t nt) {
         const int32_t nxtw = g.cmax > nt ? g.cmax : 0;
-        return (size_t)(g.L + 2 * g.cmax + nxtw + (kw ? g.cmax + g.k : 0)) * 8 + (size_t)g.cmax * (16 + 4) +
-               (size_t)(big_tables ? ApQTab<true>::SLOTS : ApQTab<false>::SLOTS) * 8 + 8;
+        const bool pipe = !kw && !big_tables && nt >= 512;   // the large-pool path's entering keys and bitmap of the pool
+        return (size_t)(g.L + 2 * g.cmax + nxtw + (kw || pipe ? g.cmax : 0) + (kw ? g.k : 0)) * 8 + (size_t)g.cmax * (16 + 4) +
+               (size_t)(big_tables ? ApQTab<true>::SLOTS : ApQTab<false>::SLOTS) * 8 + 8 +
+               (pipe ? (size_t)(g.cmax & 1) * 4 + (size_t)((g.L + 63) / 64) * 8 : 0);
     };
     // Workgroup size (plain search): four waves as long as the LDS holds at least five workgroups per CU; a pool
     // that leaves room for two to four gets eight waves, one that fills the CU alone sixteen (measured: each is the
