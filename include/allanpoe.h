@@ -337,6 +337,11 @@ int ap_calibration_copy(void *dst, const void *src, size_t bytes, void *stream);
  * [0] ingest, [1] seed, [2] refinement, [3] prune, [4] assemble+entry, [5] total. */
 int ap_build_timings(const ap_index *index, float out6[6]);
 
+/* Work counters of the construction stages run on this index so far (host array; synchronises `stream`):
+ * [0] hybrid similarities evaluated by refinement rounds (whole builds, insertions and ap_stage_refine calls),
+ * [1] reserved (0). */
+int ap_build_counters(const ap_index *index, uint64_t out2[2], void *stream);
+
 /* Debug settings, for tests: they drive small inputs through the code paths of large ones and never change a
  * result.  One process-wide value per name (host string), 0 = the library's own choice:
  *   "seed_sample_cols"        columns sampled for the seed threshold (forces the thresholded sweep on small corpora)

@@ -471,6 +471,12 @@ class Index:
         _check(lib().ap_search_stats(self._h, None, C.c_int32(0), C.byref(ms), None), "ap_search_stats")
         return float(ms.value)
 
+    def build_counters(self):
+        out = (C.c_uint64 * 2)()
+        with torch.cuda.device(self.device):
+            _check(lib().ap_build_counters(self._h, out, _stream()), "ap_build_counters")
+        return dict(refine_similarities=int(out[0]))
+
     def build_timings(self):
         out = (C.c_float * 6)()
         _check(lib().ap_build_timings(self._h, out), "ap_build_timings")

@@ -225,6 +225,8 @@ int ap_ingest_impl(ap_index *ix, hipStream_t st) {
     AP_TRY(ap_dev_alloc(&ix->self_sim, (size_t)c.n));
     AP_TRY(ap_dev_alloc(&ix->dense_norm, (size_t)c.n));
     AP_TRY(ap_dev_alloc(&ix->w_dev, 4));
+    AP_TRY(ap_dev_alloc(&ix->counters, 2));
+    AP_TRY(ap_fill_u32(ix->counters, 4, 0u, st));
     AP_TRY(ap_fill_u32(ix->df, (size_t)c.tx_vocab, 0, st));
     AP_TRY(ap_fill_u32(ix->stats, 4, 0, st));
     unsigned long long *total = reinterpret_cast<unsigned long long *>(ix->stats + 2);
@@ -251,7 +253,7 @@ int ap_ingest_impl(ap_index *ix, hipStream_t st) {
         AP_CHECK_HIP(hipGetLastError());
     }
     {
-        AP_TRY(ap_dev_alloc(&ix->rec, (size_t)(last + sp_last)));
+        AP_TRY(ap_dev_alloc(&ix->rec, (size_t)(last + sp_last) + 1));   // one spare entry: the scorers read a record's first entry unconditionally
         AP_TRY(ap_dev_alloc(&ix->meta, (size_t)c.n));
         int32_t *mx = reinterpret_cast<int32_t *>(ix->stats + 1);
         int blocks = (int)((c.n + 255) / 256 < 4096 ? (c.n + 255) / 256 : 4096);
@@ -297,7 +299,7 @@ extern "C" int ap_ingest(const ap_corpus *corpus, const ap_build_params *params,
 
 extern "C" void ap_free_index(ap_index *ix) {
     if (!ix) return;
-    void *ptrs[] = {ix->kg_en_ip, ix->kg_en, ix->kg_le, ix->kg_le_count, ix->st_se, ix->st_sorted, ix->st_spi, ix->st_sps, ix->deleted, ix->deleted_bad, ix->tx_w, ix->df, ix->stats, ix->self_sim, ix->graph, ix->kw, ix->kw_count, ix->entry, ix->visited, ix->w_dev,
+    void *ptrs[] = {ix->kg_en_ip, ix->kg_en, ix->kg_le, ix->kg_le_count, ix->st_se, ix->st_sorted, ix->st_spi, ix->st_sps, ix->deleted, ix->deleted_bad, ix->counters, ix->tx_w, ix->df, ix->stats, ix->self_sim, ix->graph, ix->kw, ix->kw_count, ix->entry, ix->visited, ix->w_dev,
                     ix->search_counts, ix->dense_norm, ix->rec, ix->meta};
     for (void *p : ptrs) if (p) (void)hipFree(p);
     for (hipEvent_t e : ix->ev_search) if (e) (void)hipEventDestroy(e);
@@ -453,6 +455,15 @@ extern "C" int ap_calibration_copy(void *dst, const void *src, size_t bytes, voi
     if (bytes == 0) return AP_OK;
     hipLaunchKernelGGL(k_copy_u128, dim3(8192), dim3(256), 0, (hipStream_t)stream, (const uint4 *)src, (uint4 *)dst, bytes / 16);
     AP_CHECK_HIP(hipGetLastError());
+    return AP_OK;
+}
+
+extern "C" int ap_build_counters(const ap_index *ix, uint64_t out2[2], void *stream) {
+    AP_REQUIRE(ix && out2, "NULL argument");
+    unsigned long long h[2] = {0, 0};
+    AP_CHECK_HIP(hipMemcpyAsync(h, ix->counters, sizeof(h), hipMemcpyDeviceToHost, (hipStream_t)stream));
+    AP_CHECK_HIP(hipStreamSynchronize((hipStream_t)stream));
+    out2[0] = h[0]; out2[1] = h[1];
     return AP_OK;
 }
 

@@ -417,7 +417,8 @@ __global__ __launch_bounds__(512) void k_refine(ApVecs D, const uint2 *__restric
                                                 const int32_t *__restrict__ knn, const int32_t *__restrict__ sp_ids,
                                                 const float *__restrict__ sp_sc, const int32_t *__restrict__ node_ids,
                                                 int64_t nn, int64_t x0, int32_t *__restrict__ out_ids, float *__restrict__ out_sc,
-                                                int32_t *__restrict__ out_sp_ids, float *__restrict__ out_sp_sc) {
+                                                int32_t *__restrict__ out_sp_ids, float *__restrict__ out_sp_sc,
+                                                unsigned long long *__restrict__ n_sims) {
     __shared__ int32_t ht[AP_HT];
     __shared__ int32_t cand[AP_MAXC];
     __shared__ uint64_t keys[AP_MAXC];
@@ -461,6 +462,7 @@ __global__ __launch_bounds__(512) void k_refine(ApVecs D, const uint2 *__restric
     }
     __syncthreads();
     const int32_t cnt = s_cnt;
+    if (threadIdx.x == 0 && n_sims) atomicAdd(n_sims, (unsigned long long)cnt);   // measurement: similarities of this node and round
     for (int32_t i = wave; i < cnt; i += (int32_t)(blockDim.x >> 6)) {
         const int32_t v = cand[i];
         float sd, ss, sf;
@@ -536,7 +538,7 @@ extern "C" int ap_stage_refine(const ap_index *ix, int32_t K, int32_t S, int32_t
         AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim,
                           hipLaunchKernelGGL((k_refine<DT, NV>), dim3((unsigned)cn), dim3(512), 0, (hipStream_t)stream, ix->docs,
                                              ix->rec, ix->meta, w[0], w[1], w[2], K, S, P, knn_ids, sp_ids, sp_sc, node_ids, nn, x0, out_ids,
-                                             out_sc, out_sp_ids, out_sp_sc));
+                                             out_sc, out_sp_ids, out_sp_sc, ix->counters));
         AP_CHECK_HIP(hipGetLastError());
     }
     return AP_OK;

@@ -62,6 +62,7 @@ struct ap_index {
     int64_t tx_nnz;
     float *tx_w = nullptr;     // owned: BM25 weight per lexical entry
     int32_t *df = nullptr;     // owned: document frequency per term
+    unsigned long long *counters = nullptr;   // owned: [0] hybrid similarities evaluated by refinement rounds on this index
     float *stats = nullptr;    // owned: [0] avgdl
     float *self_sim = nullptr; // owned: fused self-similarity under build_w
     float *dense_norm = nullptr; // owned: |d_dense| per document (upper bound of the dense part in the search)
@@ -480,10 +481,9 @@ __device__ __forceinline__ void ap_dense_load_raw(const ApVecs &B, int64_t row, 
     const int lane = threadIdx.x & 63;
     const char *base = static_cast<const char *>(B.dense) + row * (int64_t)B.dim * (16 / EPC);
 #pragma unroll
-    for (int i = 0; i < NV; i++) {
+    for (int i = 0; i < NV; i++) {   // a lane past the end of the row re-reads the row's first group (never used: see ap_dense_dot_raw)
         const int col = (i * 64 + lane) * EPC;
-        raw[i] = make_uint4(0u, 0u, 0u, 0u);
-        if (col < B.dim) raw[i] = *reinterpret_cast<const uint4 *>(base + (int64_t)col * (16 / EPC));
+        raw[i] = *reinterpret_cast<const uint4 *>(base + (int64_t)(col < B.dim ? col : 0) * (16 / EPC));
     }
 }
 template <int DT, int NV>
@@ -545,23 +545,38 @@ __device__ __forceinline__ uint32_t ap_uniform_u32(uint32_t v) { return (uint32_
 // (term id, weight bits), so that a candidate costs one contiguous segment
 // and one 16-byte descriptor instead of four segments and five scattered words.
 // `r` points at the document's first entry (wave-uniform).
+// Straight-line code: a lane past the end of a list reads the record's first entry instead (a line the wave fetches
+// anyway) and discards it, so the loads issue back to back with no branch around any of them.  The record array
+// ends with one spare entry, so that the first entry of an empty record is readable too.
 template <int SS, int TS>
-__device__ __forceinline__ void ap_rec_load(const uint2 *r, int32_t spn, int32_t txn, int32_t *si, float *sv, int32_t *ti, float *tv) {
+__device__ __forceinline__ void ap_rec_load_raw(const uint2 *r, int32_t spn, int32_t txn, uint2 *xs, uint2 *xt) {
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int k = 0; k < SS; k++) { const int32_t e = k * 64 + lane; xs[k] = r[e < spn ? e : 0]; }
+#pragma unroll
+    for (int k = 0; k < TS; k++) { const int32_t e = k * 64 + lane; xt[k] = r[e < txn ? spn + e : 0]; }
+}
+// What the loads brought, as (term, weight) per slot; a lane past the end of a list gets term -1 and weight 0.
+template <int SS, int TS>
+__device__ __forceinline__ void ap_rec_decode(const uint2 *xs, const uint2 *xt, int32_t spn, int32_t txn, int32_t *si, float *sv,
+                                              int32_t *ti, float *tv) {
     const int lane = threadIdx.x & 63;
 #pragma unroll
     for (int k = 0; k < SS; k++) {
-        const int32_t e = k * 64 + lane;
-        uint2 x = make_uint2(0xffffffffu, 0u);
-        if (e < spn) x = r[e];
-        si[k] = (int32_t)x.x; sv[k] = __uint_as_float(x.y);
+        const bool ok = k * 64 + lane < spn;
+        si[k] = ok ? (int32_t)xs[k].x : -1; sv[k] = ok ? __uint_as_float(xs[k].y) : 0.f;
     }
 #pragma unroll
     for (int k = 0; k < TS; k++) {
-        const int32_t e = k * 64 + lane;
-        uint2 x = make_uint2(0xffffffffu, 0u);
-        if (e < txn) x = r[spn + e];
-        ti[k] = (int32_t)x.x; tv[k] = __uint_as_float(x.y);
+        const bool ok = k * 64 + lane < txn;
+        ti[k] = ok ? (int32_t)xt[k].x : -1; tv[k] = ok ? __uint_as_float(xt[k].y) : 0.f;
     }
+}
+template <int SS, int TS>
+__device__ __forceinline__ void ap_rec_load(const uint2 *r, int32_t spn, int32_t txn, int32_t *si, float *sv, int32_t *ti, float *tv) {
+    uint2 xs[SS], xt[TS];
+    ap_rec_load_raw<SS, TS>(r, spn, txn, xs, xt);
+    ap_rec_decode<SS, TS>(xs, xt, spn, txn, si, sv, ti, tv);
 }
 
 // Sparse and lexical sums of a packed record against the a side's look-up

@@ -113,8 +113,7 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const ui
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int32_t skipped = 0;
     for (int32_t i0 = wave; i0 < c; i0 += NW * G) {
-        int32_t si[G][2], ti[G][1];
-        float sv[G][2], tv[G][1];
+        uint2 xs[G][2], xt[G][1];
         const uint2 *r[G];
         int32_t spn[G], txn[G];
         float dn[G];
@@ -128,7 +127,7 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const ui
                 spn[gi] = __builtin_amdgcn_readfirstlane((int32_t)(m.y & 0xffffu));
                 txn[gi] = __builtin_amdgcn_readfirstlane((int32_t)(m.y >> 16));
                 dn[gi] = __uint_as_float(ap_uniform_u32(m.z));
-                ap_rec_load<2, 1>(r[gi], spn[gi], txn[gi], si[gi], sv[gi], ti[gi], tv[gi]);
+                ap_rec_load_raw<2, 1>(r[gi], spn[gi], txn[gi], xs[gi], xt[gi]);
             }
         }
         float ss[G], sf[G];
@@ -139,16 +138,19 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const ui
             const int32_t i = i0 + NW * gi;
             need[gi] = false;
             if (i >= c) continue;
+            int32_t si[2], ti[1];
+            float sv[2], tv[1];
+            ap_rec_decode<2, 1>(xs[gi], xt[gi], spn[gi], txn[gi], si, sv, ti, tv);
             if (TAB && !BIG)   // ordinary queries: bucketed tables, one read per look-up
                 ap_rec_reduce_bucket<2, 1, ApQTab<BIG>::SPB, ApQTab<BIG>::TXB>(r[gi], (const AP_LDS uint64_t *)qtab,
                                                                                (const AP_LDS uint64_t *)(qtab + (1 << ApQTab<BIG>::SPB)),
-                                                                               msp, mtx, spn[gi], txn[gi], si[gi], sv[gi], ti[gi], tv[gi], ss[gi], sf[gi]);
+                                                                               msp, mtx, spn[gi], txn[gi], si, sv, ti, tv, ss[gi], sf[gi]);
             else if (TAB)      // queries that are documents (insertion): open-addressing tables
                 ap_rec_reduce_tab<2, 1, ApQTab<BIG>::SPB, ApQTab<BIG>::TXB>(r[gi], (const AP_LDS uint64_t *)qtab,
                                                                             (const AP_LDS uint64_t *)(qtab + (1 << ApQTab<BIG>::SPB)),
-                                                                            spn[gi], txn[gi], si[gi], sv[gi], ti[gi], tv[gi], ss[gi], sf[gi]);
+                                                                            spn[gi], txn[gi], si, sv, ti, tv, ss[gi], sf[gi]);
             else
-                ap_rec_reduce_lists<2, 1>(r[gi], a, spn[gi], txn[gi], si[gi], sv[gi], ti[gi], tv[gi], ss[gi], sf[gi]);
+                ap_rec_reduce_lists<2, 1>(r[gi], a, spn[gi], txn[gi], si, sv, ti, tv, ss[gi], sf[gi]);
             // upper bound of the fused score, with slack far above fp32 rounding
             const float dmax = fabsf(wd) * qnorm * dn[gi] * 1.0001f;
             const float part = fmaf(wf, sf[gi], ws * ss[gi]);
@@ -157,7 +159,7 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const ui
             if (KW && n_kw > 0) {
                 uint32_t hit = 0;   // bit j: required term j occurs in the candidate's text
                 for (int32_t e0 = 0; e0 < txn[gi]; e0 += 64) {
-                    int32_t term = ti[gi][0];
+                    int32_t term = ti[0];
                     if (e0 > 0) term = e0 + lane < txn[gi] ? (int32_t)r[gi][spn[gi] + e0 + lane].x : -1;
                     for (int32_t j = 0; j < n_kw; j++) hit |= __ballot(term == s_kw[j]) != 0ull ? 1u << j : 0u;
                 }
@@ -191,9 +193,10 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const ui
     return skipped;
 }
 
-// Candidates a wave keeps in flight (ap_score_candidates' G), by workgroup size.  Measured on a million-document
-// shape at every pool size: one is fastest everywhere.  A second candidate costs some 35 registers, and the kernel is
-// bound by instruction issue, not by the latency of a wave's own loads, even with sixteen waves alone on a CU.
+// Candidates a wave keeps in flight (ap_score_candidates' G), by workgroup size, as measured on a million-document
+// shape: a second candidate costs some 35 registers, which the four- and eight-wave workgroups that share a CU cannot
+// spare (one is fastest there: other waves hide the latency); sixteen waves alone on a CU gain 6 % from a second one
+// and nothing from a third.
 #ifndef AP_SEARCH_G_256
 #define AP_SEARCH_G_256 1
 #endif
@@ -201,7 +204,7 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const ui
 #define AP_SEARCH_G_512 1
 #endif
 #ifndef AP_SEARCH_G_1024
-#define AP_SEARCH_G_1024 1
+#define AP_SEARCH_G_1024 2
 #endif
 #ifndef AP_SEARCH_WAVES_512
 #define AP_SEARCH_WAVES_512 6
@@ -265,7 +268,7 @@ void k_search(ApSearchArgs g) {
     uint4 *s_meta = reinterpret_cast<uint4 *>(qtab + ApQTab<BIG>::SLOTS);
     int32_t *cand = reinterpret_cast<int32_t *>(s_meta + g.cmax);
     uint64_t *umask = reinterpret_cast<uint64_t *>(cand + g.cmax + (g.cmax & 1));   // PIPE: one bit per pool entry
-    __shared__ int32_t s_cnt, s_np, s_skip, s_xn, s_kc, s_nin, s_fu, s_rmin;
+    __shared__ int32_t s_cnt, s_np, s_skip, s_xn, s_kc, s_nin, s_rmin;
     __shared__ int32_t s_par[8], s_psat[8];
     __shared__ int32_t s_kw[AP_KW_MAX_TERMS];
     __shared__ int32_t s_seed[2];
@@ -312,7 +315,7 @@ void k_search(ApSearchArgs g) {
     }
     const float wd = g.w[q * g.w_stride + 0], ws = g.w[q * g.w_stride + 1], wf = g.w[q * g.w_stride + 2];
     uint32_t *vis = g.visited + (size_t)blockIdx.x * g.words;
-    if (threadIdx.x == 0) { s_cnt = 0; s_skip = 0; s_xn = 0; s_kc = 0; s_nin = 0; s_fu = 0; }
+    if (threadIdx.x == 0) { s_cnt = 0; s_skip = 0; s_xn = 0; s_kc = 0; s_nin = 0; }
     // the query's required terms, unused slots squeezed out (uniform)
     int32_t n_kw = 0;
     if (KW) {
@@ -358,6 +361,7 @@ void k_search(ApSearchArgs g) {
         AP_PROF(1);
         __syncthreads();
         AP_PROF(2);
+        if (threadIdx.x == 0) s_cnt = 0;   // every thread has read this iteration's count; the gather counts anew after further barriers
         int32_t cin;
         if (PIPE) {
             // Only keys that rank before the pool's last entry can enter (any key while the pool has room): late in a
@@ -369,11 +373,24 @@ void k_search(ApSearchArgs g) {
             }
             __syncthreads();
             cin = s_nin;
-            for (int32_t t = threadIdx.x; t < cin; t += blockDim.x) {
-                const uint64_t key = xk[t];
-                int32_t r = 0;
-                for (int32_t j = 0; j < cin; j++) r += xk[j] > key;
-                newS[r] = key;
+            // One wave per entering key finds both of its ranks: among the entering keys (64 compares a step) and among
+            // the pool (64 probes a step: three steps for 16384 entries instead of fourteen halvings).  The first gives
+            // the key its place in newS, the second goes to rr (in newk's space, which is free now).
+            int32_t *rr = reinterpret_cast<int32_t *>(newk);
+            for (int32_t j = wave; j < cin; j += NT / 64) {
+                const uint64_t key = xk[j];
+                int32_t e = 0;
+                for (int32_t i0 = 0; i0 < cin; i0 += 64) e += (int32_t)__popcll(__ballot(i0 + lane < cin && xk[i0 + lane] > key));
+                int32_t lo = 0, hi = len;   // the rank (number of pool entries that rank before the key) lies in [lo, hi]
+                while (hi > lo) {
+                    const int32_t step = (hi - lo + 63) >> 6;
+                    const int32_t at = lo + (lane + 1) * step - 1;
+                    const int32_t n_before = (int32_t)__popcll(__ballot(at < hi && cur[at] > key));
+                    const int32_t nlo = lo + n_before * step, nhi = lo + (n_before + 1) * step - 1;
+                    lo = nlo;
+                    hi = nhi < hi ? nhi : hi;
+                }
+                if (lane == 0) { newS[e] = key; rr[e] = lo; }
             }
             __syncthreads();
             if (threadIdx.x == 0) s_nin = 0;   // next touched after the barriers of the merge or the pick
@@ -397,7 +414,54 @@ void k_search(ApSearchArgs g) {
                 if ((key >> 32) != 0ull && (key & 2ull)) xk[atomicAdd(&s_xn, 1)] = key;
             }
         }
-        if (cin > 0) {
+        if (PIPE && cin > 0) {
+            // In-place rank merge of a large pool.  The entering keys are few against the pool, so what costs is
+            // latency and barriers: the number of entering keys that land before each 64-entry block of the pool is
+            // tabulated, after which a pool entry finds how far it moves with two reads; entries from the first
+            // insertion point on are read in chunks of 4 NT from the back of the pool to the front and written one
+            // barrier later (a chunk's writes never reach below its own start).
+            const int32_t *rr = reinterpret_cast<const int32_t *>(newk);   // rank of every entering key among the pool, ascending
+            int32_t *bshift = reinterpret_cast<int32_t *>(umask);          // entering keys that land before block b
+            const int32_t rmin = rr[0];
+            fu = fu < rmin ? fu : rmin;   // the best entering key lands at rmin, unexpanded; entries before it stay put
+            const int32_t nb = (len + 63) >> 6;
+            for (int32_t b = threadIdx.x; b <= nb; b += NT) {   // number of ranks below 64 b
+                int32_t lo = 0, hi = cin;
+                while (lo < hi) {
+                    const int32_t mid = (lo + hi) >> 1;
+                    if (rr[mid] < 64 * b) lo = mid + 1; else hi = mid;
+                }
+                bshift[b] = lo;
+            }
+            __syncthreads();
+            constexpr int CH = 4;
+            for (int32_t hi = len; hi > rmin; hi -= CH * NT) {
+                const int32_t lo = hi - CH * NT > rmin ? hi - CH * NT : rmin;
+                uint64_t held[CH]; int32_t dest[CH];
+#pragma unroll
+                for (int m = 0; m < CH; m++) {
+                    const int32_t t = lo + (int32_t)threadIdx.x + NT * m;
+                    dest[m] = g.L;
+                    if (t < hi) {
+                        held[m] = cur[t];
+                        int32_t k = bshift[t >> 6];
+                        while (k < cin && rr[k] <= t) k++;   // insertion points inside the entry's own block: rarely any
+                        dest[m] = t + k;
+                    }
+                }
+                __syncthreads();
+#pragma unroll
+                for (int m = 0; m < CH; m++)
+                    if (dest[m] < g.L) cur[dest[m]] = held[m];
+                // no barrier here: these writes land at or after `lo`, the next chunk's reads come before it
+            }
+            for (int32_t t = threadIdx.x; t < cin; t += NT) {
+                const int32_t r = rr[t] + t;
+                if (r < g.L) cur[r] = newS[t];
+            }
+            len = len + cin < g.L ? len + cin : g.L;
+            __syncthreads();
+        } else if (cin > 0) {
             // In-place rank merge.  A pool entry at position t moves up by the number of entering keys that rank
             // before it, so only entries from the first insertion point on move, and they only move towards the
             // end: chunks of 2 NT entries are read, then (one barrier later) written, from the back of the pool to the
@@ -484,6 +548,7 @@ void k_search(ApSearchArgs g) {
         AP_PROF(4);
         if (g.max_iters > 0 && it >= g.max_iters) break;
         // S8: pick the best `width` unexpanded entries (wave 0), mark them expanded
+        int32_t pipe_np = 0;
         if (PIPE) {
             // Late in a search the unexpanded entries are few and far apart, and a scan by one wave would walk most of
             // the pool: every wave reduces its share of the pool from the cursor on to one bit per entry, and wave 0
@@ -495,32 +560,35 @@ void k_search(ApSearchArgs g) {
                 if (lane == 0) umask[b] = m;
             }
             __syncthreads();
-            if (wave == 0) {
-                // the first `width` set bits, found with uniform (scalar) steps; lane j then takes the j-th of them
-                int32_t found = 0, last = -1, mine = -1;
-                for (int32_t base = b0; base < nb && found < g.width; base += 64) {
-                    const int32_t b = base + lane;
-                    const uint64_t m = b < nb ? umask[b] : 0ull;
-                    uint64_t nz = __ballot(m != 0ull);
-                    while (nz != 0ull && found < g.width) {
-                        const int32_t src = (int32_t)__builtin_ctzll(nz);
-                        nz &= nz - 1ull;
-                        uint64_t word = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int32_t)(m >> 32), src) << 32) |
-                                        (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int32_t)(uint32_t)m, src);
-                        while (word != 0ull && found < g.width) {
-                            last = (base + src) * 64 + (int32_t)__builtin_ctzll(word);
-                            word &= word - 1ull;
-                            if (lane == found) mine = last;
-                            found++;
-                        }
+            // Every wave picks for itself (the same scalar steps over the same bits, so the same parents): the first
+            // `width` set bits are found with uniform steps and lane j takes the j-th.  No barrier is needed between
+            // the pick and the gather of the parents' neighbours; wave 0 marks the parents expanded.
+            int32_t found = 0, last = -1, mine = -1;
+            for (int32_t base = b0; base < nb && found < g.width; base += 64) {
+                const int32_t b = base + lane;
+                const uint64_t m = b < nb ? umask[b] : 0ull;
+                uint64_t nz = __ballot(m != 0ull);
+                while (nz != 0ull && found < g.width) {
+                    const int32_t src = (int32_t)__builtin_ctzll(nz);
+                    nz &= nz - 1ull;
+                    uint64_t word = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int32_t)(m >> 32), src) << 32) |
+                                    (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int32_t)(uint32_t)m, src);
+                    while (word != 0ull && found < g.width) {
+                        last = (base + src) * 64 + (int32_t)__builtin_ctzll(word);
+                        word &= word - 1ull;
+                        if (lane == found) mine = last;
+                        found++;
                     }
                 }
-                if (mine >= 0) {
-                    s_par[lane] = ap_pool_id<KW>(cur[mine]);
-                    cur[mine] &= ~1ull;
-                }
-                if (lane == 0) { s_np = found; s_cnt = 0; s_fu = last >= 0 ? last + 1 : len; }
             }
+            if (mine >= 0) {
+                const uint64_t key = cur[mine];
+                s_par[lane] = ap_pool_id<KW>(key);     // every wave stores the same ids
+                if (wave == 0) cur[mine] = key & ~1ull;   // only the flag changes: a wave that reads the entry meanwhile gets the same id
+            }
+            ap_wave_sync();
+            pipe_np = found;
+            fu = last >= 0 ? last + 1 : len;   // everything up to the last entry taken is expanded now
         } else if (wave == 0) {
             int32_t found = 0, last = -1;
             for (int32_t base = fu & ~63; base < len && found < g.width; base += 64) {   // the scan starts where it can first succeed
@@ -539,12 +607,11 @@ void k_search(ApSearchArgs g) {
                 found += __popcll(mask);
             }
             fu = last >= 0 ? last + 1 : len;   // everything up to the last entry taken is expanded now
-            if (lane == 0) { s_np = found < g.width ? found : g.width; s_cnt = 0; }
+            if (lane == 0) s_np = found < g.width ? found : g.width;
         }
-        __syncthreads();
+        if (!PIPE) __syncthreads();
         AP_PROF(5);
-        const int32_t np = s_np;
-        if (PIPE) fu = s_fu;   // every wave needs the cursor (the bitmap starts there)
+        const int32_t np = PIPE ? pipe_np : s_np;
         if (np == 0) break;
         // neighbours of the parents that were never seen before; a parent that satisfies the keyword
         // constraint also brings its keyword edges
