@@ -104,7 +104,8 @@ def debug_set(name: str, value: int):
     _check(lib().ap_debug_set(name.encode(), C.c_int64(int(value))), "ap_debug_set")
 
 
-DEBUG_NAMES = ("seed_sample_cols", "seed_buffer_cap", "seed_tau_ulps", "max_launch_threads", "search_workspace_bytes")
+DEBUG_NAMES = ("seed_sample_cols", "seed_buffer_cap", "seed_tau_ulps", "max_launch_threads", "search_workspace_bytes",
+               "search_visited_global")
 
 
 def debug_reset():

@@ -18,19 +18,21 @@
 
 int ap_validate_queries(const ap_queries *q);
 
-// Marks bit `bit` of a visited word and returns the word as it was.  Only the workgroup that searches the query
-// ever touches its visited set (zeroed by an earlier kernel), so the atomic needs workgroup scope only: it is carried
-// out in the L2 of the workgroup's own XCD instead of travelling to the memory side as a device-scope atomic does.
-#ifndef AP_VIS_DEVICE_SCOPE
-#define AP_VIS_DEVICE_SCOPE 0
-#endif
-__device__ __forceinline__ uint32_t ap_visit(uint32_t *word, uint32_t bit) {
-#if AP_VIS_DEVICE_SCOPE
-    return atomicOr(word, bit);
-#else
-    return __hip_atomic_fetch_or(word, bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-#endif
-}
+// The visited set of a query: one bit per document, in LDS when the corpus is small enough for that not to cost a
+// workgroup its place on the CU (ap_search_launch decides), else in a per-call global workspace.  Marks document v and
+// tells whether it had been marked before.  Only the workgroup that searches the query ever touches its set, so the
+// global atomic needs workgroup scope only.
+struct ApVisited {
+    uint32_t *g;             // global bitset of this query
+    AP_LDS uint32_t *l;      // LDS bitset, or null
+    __device__ __forceinline__ bool test_and_set(int32_t v) const {
+        const uint32_t bit = 1u << (v & 31);
+        uint32_t old;
+        if (l) old = __hip_atomic_fetch_or(l + (v >> 5), bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);   // uniform branch
+        else old = __hip_atomic_fetch_or(g + (v >> 5), bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        return (old & bit) != 0u;
+    }
+};
 
 struct ApSearchArgs {
     ApVecs D, Q;
@@ -39,6 +41,7 @@ struct ApSearchArgs {
     const float *w;     // per query (stride 3) or the index default (stride 0)
     int32_t w_stride;
     int32_t R, E, k, L, max_iters, width, cmax;
+    int32_t vis_lds;    // the visited sets live in LDS (words words after the kernel's other arrays), not in `visited`
     int32_t nxtw;       // words of the scratch that parks positions when more keys enter at once than the workgroup has threads (else 0)
     int32_t q0;         // the launch covers queries q0 .. q0 + gridDim.x (a slab of the batch)
     uint32_t *visited;  // one bitset per query of the slab
@@ -314,7 +317,11 @@ void k_search(ApSearchArgs g) {
         qnorm = sqrtf(ap_wave_sum(p));
     }
     const float wd = g.w[q * g.w_stride + 0], ws = g.w[q * g.w_stride + 1], wf = g.w[q * g.w_stride + 2];
-    uint32_t *vis = g.visited + (size_t)blockIdx.x * g.words;
+    ApVisited vis{g.visited + (size_t)blockIdx.x * g.words, nullptr};
+    if (g.vis_lds) {   // uniform
+        vis.l = (AP_LDS uint32_t *)reinterpret_cast<uint32_t *>(umask + (PIPE ? (g.L + 63) / 64 : 0));
+        for (size_t i = threadIdx.x; i < g.words; i += blockDim.x) vis.l[i] = 0u;
+    }
     if (threadIdx.x == 0) { s_cnt = 0; s_skip = 0; s_xn = 0; s_kc = 0; s_nin = 0; }
     // the query's required terms, unused slots squeezed out (uniform)
     int32_t n_kw = 0;
@@ -332,10 +339,9 @@ void k_search(ApSearchArgs g) {
     for (int32_t i = threadIdx.x; i < g.E; i += blockDim.x) {
         const int32_t v = g.entry[i];
         if (v >= 0) {
-            const uint32_t bit = 1u << (v & 31);
-            const uint32_t old = ap_visit(&vis[v >> 5], bit);
+            const bool seen = vis.test_and_set(v);
             const uint4 m = g.meta[v];
-            if (!(old & bit)) { const int32_t at = atomicAdd(&s_cnt, 1); cand[at] = v; s_meta[at] = m; }
+            if (!seen) { const int32_t at = atomicAdd(&s_cnt, 1); cand[at] = v; s_meta[at] = m; }
         }
     }
     __syncthreads();
@@ -627,12 +633,11 @@ void k_search(ApSearchArgs g) {
                 v = g.graph[(int64_t)s_par[i / g.R] * g.R + (i % g.R)];
             }
             if (v >= 0) {
-                const uint32_t bit = 1u << (v & 31);
                 // the descriptor (where the record is, how long, the dense norm) is fetched along with the visited
                 // test, not after it: one memory round trip less per iteration for 16 bytes per neighbour already seen
-                const uint32_t old = ap_visit(&vis[v >> 5], bit);
+                const bool seen = vis.test_and_set(v);
                 const uint4 m = g.meta[v];
-                if (!(old & bit)) { const int32_t at = atomicAdd(&s_cnt, 1); cand[at] = v; s_meta[at] = m; }
+                if (!seen) { const int32_t at = atomicAdd(&s_cnt, 1); cand[at] = v; s_meta[at] = m; }
             }
         }
         __syncthreads();
@@ -787,7 +792,17 @@ static int ap_search_launch(const ap_index *ix, const ApSearchWs &ws, const ApVe
         nt = per_cu > AP_SEARCH_NT512_AT ? 256 : per_cu > AP_SEARCH_NT1024_AT ? 512 : 1024;
     }
     g.nxtw = g.cmax > nt ? g.cmax : 0;
-    const size_t smem = lds_bytes(nt);
+    size_t smem = lds_bytes(nt);
+    // Visited sets in LDS (four-wave workgroups only): when the bitset fits beside the kernel's other arrays without
+    // taking a workgroup's place on the CU (seven of them run on one while the pool is small).  Measured on 100,000
+    // documents (12.5 KB a set): 4 to 5 % faster up to beam 512, 29 % slower at beam 2144 where it costs two of the
+    // seven workgroups, which is why the rule is about occupancy.  Same results either way.
+    g.vis_lds = 0;
+    if (nt == 256 && g_ap_debug.search_visited_global == 0) {
+        const size_t with = smem + g.words * 4 + 8, lds = (size_t)160 * 1024;
+        const size_t now = std::min<size_t>(7, lds / smem), then = with <= lds ? std::min<size_t>(7, lds / with) : 0;
+        if (then >= now && then > 0) { g.vis_lds = 1; smem = with; }
+    }
     AP_REQUIRE(smem <= 160 * 1024, "beam and search_width need %zu bytes of LDS (limit 160 KiB)", smem);
     hipError_t le = hipSuccess;
 #define AP_LAUNCH_SEARCH(KWF, BIGF, NTF)                                                                                         \
@@ -801,7 +816,7 @@ static int ap_search_launch(const ap_index *ix, const ApSearchWs &ws, const ApVe
         const int32_t qn = std::min(ws.slab, nq - q0);
         g.q0 = q0;
         // every slab starts from empty visited sets (a fill kernel, not a memset: callers may capture the stream)
-        AP_TRY(ap_fill_u32(ws.visited, g.words * (size_t)qn, 0u, st));
+        if (!g.vis_lds) AP_TRY(ap_fill_u32(ws.visited, g.words * (size_t)qn, 0u, st));
         if (q0 == 0 && ws.ev0) AP_CHECK_HIP(hipEventRecord(ws.ev0, st));
         if (kw) AP_LAUNCH_SEARCH(true, false, 256);
         else if (big_tables) AP_LAUNCH_SEARCH(false, true, 256);

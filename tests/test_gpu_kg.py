@@ -154,6 +154,16 @@ def test_searches_in_slabs_of_queries_give_the_same_bits(shard, debug_knobs):
         counts = ix.search_stats(qs.n)[0].cpu().numpy()
         assert np.array_equal(ids, whole[name][0]) and np.array_equal(sc, whole[name][1]), name
         assert np.array_equal(counts, whole[name][2]), name
+    # a corpus this small keeps its visited sets in LDS; kept in the global workspace instead, the same bits come out
+    debug_knobs("search_workspace_bytes", 0)
+    debug_knobs("search_visited_global", 1)
+    for name, fn in runs:
+        ids, sc = [t.cpu().numpy() for t in fn()]
+        counts = ix.search_stats(qs.n)[0].cpu().numpy()
+        assert np.array_equal(ids, whole[name][0]) and np.array_equal(sc, whole[name][1]) and np.array_equal(counts, whole[name][2]), name
+    debug_knobs("search_workspace_bytes", 7 * words * 4)
+    ids, sc = [t.cpu().numpy() for t in ix.search_batch(qs, 10, 96, wq, search_width=2)]
+    assert np.array_equal(ids, whole["plain"][0]) and np.array_equal(sc, whole["plain"][1])
     debug_knobs("search_workspace_bytes", 1)                     # less than one query's set: one query per launch
     ids, sc = [t.cpu().numpy() for t in ix.search_batch(qs, 10, 96, wq, search_width=2)]
     assert np.array_equal(ids, whole["plain"][0]) and np.array_equal(sc, whole["plain"][1])

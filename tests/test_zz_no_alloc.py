@@ -40,6 +40,9 @@ def test_noalloc_search_equals_search_batch(debug_knobs):
     bufs = {name: _out(n, kk, dev) for name, (n, kk) in dict(first=(40, k), second=(13, k), default_w=(40, k), slabs=(40, k),
                                                              other=(9, 5), again=(40, k)).items()}
     wq13 = wq[:13].contiguous()
+    # corpora this small would keep their visited sets in LDS: hold them in the workspace, which is what this entry
+    # point is about (the references above ran with the sets in LDS: same bits either way)
+    debug_knobs("search_visited_global", 1)
     torch.cuda.synchronize()
     free0 = torch.cuda.mem_get_info()[0]
 
@@ -54,7 +57,9 @@ def test_noalloc_search_equals_search_batch(debug_knobs):
     debug_knobs("search_workspace_bytes", 7 * ((docs.n + 31) // 32) * 4)
     ix.search_batch_noalloc(qs, k, 96, wq, bufs["slabs"], search_width=2)
     debug_knobs("search_workspace_bytes", 0)
+    debug_knobs("search_visited_global", 0)     # and once with the library's own choice (LDS here)
     ix.search_batch_noalloc(qs, k, 96, wq, bufs["again"], search_width=2)
+    debug_knobs("search_visited_global", 1)
     torch.cuda.synchronize()
     assert torch.cuda.mem_get_info()[0] == free0, "device memory changed across calls that must not allocate"
 
