@@ -22,6 +22,9 @@ int ap_validate_queries(const ap_queries *q);
 // workgroup its place on the CU (ap_search_launch decides), else in a per-call global workspace.  Marks document v and
 // tells whether it had been marked before.  Only the workgroup that searches the query ever touches its set, so the
 // global atomic needs workgroup scope only.
+#ifndef AP_VIS_SCOPE
+#define AP_VIS_SCOPE __HIP_MEMORY_SCOPE_WORKGROUP
+#endif
 struct ApVisited {
     uint32_t *g;             // global bitset of this query
     AP_LDS uint32_t *l;      // LDS bitset, or null
@@ -29,7 +32,7 @@ struct ApVisited {
         const uint32_t bit = 1u << (v & 31);
         uint32_t old;
         if (l) old = __hip_atomic_fetch_or(l + (v >> 5), bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);   // uniform branch
-        else old = __hip_atomic_fetch_or(g + (v >> 5), bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        else old = __hip_atomic_fetch_or(g + (v >> 5), bit, __ATOMIC_RELAXED, AP_VIS_SCOPE);
         return (old & bit) != 0u;
     }
 };
