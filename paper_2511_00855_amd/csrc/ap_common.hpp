@@ -557,7 +557,8 @@ __device__ __forceinline__ void ap_rec_load_raw(const uint2 *r, int32_t spn, int
 #pragma unroll
     for (int k = 0; k < TS; k++) { const int32_t e = k * 64 + lane; xt[k] = r[e < txn ? spn + e : 0]; }
 }
-// What the loads brought, as (term, weight) per slot; a lane past the end of a list gets term -1 and weight 0.
+// What the loads brought, as (term, weight) per slot.  A lane past the end of a list gets term -1, which no look-up
+// finds, so that its weight (the first entry's, a finite number) is multiplied by exactly 0.
 template <int SS, int TS>
 __device__ __forceinline__ void ap_rec_decode(const uint2 *xs, const uint2 *xt, int32_t spn, int32_t txn, int32_t *si, float *sv,
                                               int32_t *ti, float *tv) {
@@ -565,12 +566,12 @@ __device__ __forceinline__ void ap_rec_decode(const uint2 *xs, const uint2 *xt, 
 #pragma unroll
     for (int k = 0; k < SS; k++) {
         const bool ok = k * 64 + lane < spn;
-        si[k] = ok ? (int32_t)xs[k].x : -1; sv[k] = ok ? __uint_as_float(xs[k].y) : 0.f;
+        si[k] = ok ? (int32_t)xs[k].x : -1; sv[k] = __uint_as_float(xs[k].y);
     }
 #pragma unroll
     for (int k = 0; k < TS; k++) {
         const bool ok = k * 64 + lane < txn;
-        ti[k] = ok ? (int32_t)xt[k].x : -1; tv[k] = ok ? __uint_as_float(xt[k].y) : 0.f;
+        ti[k] = ok ? (int32_t)xt[k].x : -1; tv[k] = __uint_as_float(xt[k].y);
     }
 }
 template <int SS, int TS>

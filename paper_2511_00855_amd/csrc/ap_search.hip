@@ -257,23 +257,22 @@ template <int DT, int NV, bool KW, bool BIG, int NT>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(ApSearchWaves<DT, NV, NT>::MIN, 8)))
 void k_search(ApSearchArgs g) {
     extern __shared__ __attribute__((aligned(16))) uint64_t smem64[];   // 16-byte aligned: the descriptors are read as uint4
-    uint64_t *cur = smem64;                  // the pool: L keys, best first
-    uint64_t *newk = cur + g.L;              // keys of this iteration's candidates, unordered
-    uint64_t *newS = newk + g.cmax;          // the same, sorted
-    uint64_t *nxt = newS + g.cmax;           // scratch of nxtw words (only wide searches need it)
     // Large pools (workgroups of 512 or 1024 threads): the keys that cannot enter are dropped before sorting, and
     // parents are picked from a bitmap of the unexpanded entries.
     constexpr bool PIPE = !KW && !BIG && NT >= 512;
-    uint64_t *xk = nxt + g.nxtw;             // cmax words.  KW: satisfying keys the pool did not keep in this iteration; PIPE: entering keys, unordered
-    uint64_t *kwc = xk + (KW || PIPE ? g.cmax : 0);  // KW: the secondary pool, k keys, best first
-    // the query's two look-up tables, 16-byte aligned (buckets and descriptors are read 16 bytes at a time): an odd
-    // number of words before them shifts them by one
-    uint64_t *qtab = kwc + (KW ? g.k : 0) + ((g.L + 2 * g.cmax + g.nxtw + (KW || PIPE ? g.cmax : 0) + (KW ? g.k : 0)) & 1);
-    // descriptors of this iteration's candidates
     constexpr int SPB = ApQTab<BIG>::SPB, TXB = ApQTab<BIG>::TXB;
+    // The query's two look-up tables come first: at a fixed LDS address, so that a look-up's address is the hash alone.
+    // Then the descriptors and ids of this iteration's candidates (16-byte reads), then the 64-bit arrays.
+    uint64_t *qtab = smem64;
     uint4 *s_meta = reinterpret_cast<uint4 *>(qtab + ApQTab<BIG>::SLOTS);
     int32_t *cand = reinterpret_cast<int32_t *>(s_meta + g.cmax);
-    uint64_t *umask = reinterpret_cast<uint64_t *>(cand + g.cmax + (g.cmax & 1));   // PIPE: one bit per pool entry
+    uint64_t *cur = reinterpret_cast<uint64_t *>(cand + g.cmax + (g.cmax & 1));   // the pool: L keys, best first
+    uint64_t *newk = cur + g.L;              // keys of this iteration's candidates, unordered
+    uint64_t *newS = newk + g.cmax;          // the same, sorted
+    uint64_t *nxt = newS + g.cmax;           // scratch of nxtw words (only wide searches need it)
+    uint64_t *xk = nxt + g.nxtw;             // cmax words.  KW: satisfying keys the pool did not keep in this iteration; PIPE: entering keys, unordered
+    uint64_t *kwc = xk + (KW || PIPE ? g.cmax : 0);  // KW: the secondary pool, k keys, best first
+    uint64_t *umask = kwc + (KW ? g.k : 0);   // PIPE: one bit per pool entry; after it the visited set when it lives in LDS
     __shared__ int32_t s_cnt, s_np, s_skip, s_xn, s_kc, s_nin, s_rmin;
     __shared__ int32_t s_par[8], s_psat[8];
     __shared__ int32_t s_kw[AP_KW_MAX_TERMS];
