@@ -109,7 +109,7 @@ typedef struct {
     int32_t beam;         /* L: candidate pool capacity; <= AP_MAX_BEAM, as far as the pool (8 bytes per entry) and the
                              call's other per-query arrays fit a workgroup's 160 KB of LDS (else AP_EINVAL) */
     int32_t max_iters;    /* 0 = until the pool is fully expanded */
-    int32_t search_width; /* p: pool entries expanded per iteration; 1..8 */
+    int32_t search_width; /* p: pool entries expanded per iteration; 1..16 */
 } ap_search_params;
 
 /* ---- the three calls of the problem statement -------------------------- */

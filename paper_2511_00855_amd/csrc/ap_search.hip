@@ -113,7 +113,7 @@ template <bool BIG> struct ApQTab {
 template <int DT, int NV, bool TAB, bool KW, bool BIG, int NW, int G>
 __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const uint2 *rec, const float *qa, const uint64_t *qtab,
                                                        const ApLists &a, float wd, float ws, float wf, float qnorm, bool pool_full,
-                                                       float worst_score, const int32_t *cand, const uint4 *s_meta, int32_t c,
+                                                       float worst_score, const uint4 *s_meta, int32_t c,
                                                        uint64_t *newk, const int32_t *s_kw, int32_t n_kw, bool kw_all,
                                                        bool second_full, float second_worst, uint32_t msp, uint32_t mtx) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -121,7 +121,7 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const ui
     for (int32_t i0 = wave; i0 < c; i0 += NW * G) {
         uint2 xs[G][2], xt[G][1];
         const uint2 *r[G];
-        int32_t spn[G], txn[G];
+        int32_t spn[G], txn[G], v[G];
         float dn[G];
 #pragma unroll
         for (int gi = 0; gi < G; gi++) {
@@ -133,6 +133,7 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const ui
                 spn[gi] = __builtin_amdgcn_readfirstlane((int32_t)(m.y & 0xffffu));
                 txn[gi] = __builtin_amdgcn_readfirstlane((int32_t)(m.y >> 16));
                 dn[gi] = __uint_as_float(ap_uniform_u32(m.z));
+                v[gi] = (int32_t)ap_uniform_u32(m.w);
                 ap_rec_load_raw<2, 1>(r[gi], spn[gi], txn[gi], xs[gi], xt[gi]);
             }
         }
@@ -180,14 +181,9 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const ui
             }
         }
         uint4 raw[G][NV];
-        int32_t v[G];
 #pragma unroll
-        for (int gi = 0; gi < G; gi++) {
-            if (need[gi]) {
-                v[gi] = __builtin_amdgcn_readfirstlane(cand[i0 + NW * gi]);
-                ap_dense_load_raw<DT, NV>(D, v[gi], raw[gi]);
-            }
-        }
+        for (int gi = 0; gi < G; gi++)
+            if (need[gi]) ap_dense_load_raw<DT, NV>(D, v[gi], raw[gi]);
 #pragma unroll
         for (int gi = 0; gi < G; gi++) {
             if (need[gi]) {
@@ -262,19 +258,20 @@ void k_search(ApSearchArgs g) {
     constexpr bool PIPE = !KW && !BIG && NT >= 512;
     constexpr int SPB = ApQTab<BIG>::SPB, TXB = ApQTab<BIG>::TXB;
     // The query's two look-up tables come first: at a fixed LDS address, so that a look-up's address is the hash alone.
-    // Then the descriptors and ids of this iteration's candidates (16-byte reads), then the 64-bit arrays.
+    // Then this iteration's candidates: 16 bytes each, the document's descriptor with its id in the fourth word.
+    // PIPE: once the candidates are scored their space is free until the next gather, and holds the entering keys,
+    // unordered (xk) and sorted (newS): what lets the largest pool (16384 entries) take sixteen parents' neighbours.
     uint64_t *qtab = smem64;
     uint4 *s_meta = reinterpret_cast<uint4 *>(qtab + ApQTab<BIG>::SLOTS);
-    int32_t *cand = reinterpret_cast<int32_t *>(s_meta + g.cmax);
-    uint64_t *cur = reinterpret_cast<uint64_t *>(cand + g.cmax + (g.cmax & 1));   // the pool: L keys, best first
+    uint64_t *cur = reinterpret_cast<uint64_t *>(s_meta + g.cmax);   // the pool: L keys, best first
     uint64_t *newk = cur + g.L;              // keys of this iteration's candidates, unordered
-    uint64_t *newS = newk + g.cmax;          // the same, sorted
-    uint64_t *nxt = newS + g.cmax;           // scratch of nxtw words (only wide searches need it)
-    uint64_t *xk = nxt + g.nxtw;             // cmax words.  KW: satisfying keys the pool did not keep in this iteration; PIPE: entering keys, unordered
-    uint64_t *kwc = xk + (KW || PIPE ? g.cmax : 0);  // KW: the secondary pool, k keys, best first
+    uint64_t *newS = PIPE ? reinterpret_cast<uint64_t *>(s_meta) + g.cmax : newk + g.cmax;   // the same, sorted
+    uint64_t *nxt = newk + (PIPE ? 1 : 2) * g.cmax;   // scratch of nxtw words (only wide searches of small pools need it)
+    uint64_t *xk = PIPE ? reinterpret_cast<uint64_t *>(s_meta) : nxt + g.nxtw;   // cmax words.  KW: satisfying keys the pool did not keep in this iteration; PIPE: entering keys, unordered
+    uint64_t *kwc = nxt + g.nxtw + (KW ? g.cmax : 0);   // KW: the secondary pool, k keys, best first
     uint64_t *umask = kwc + (KW ? g.k : 0);   // PIPE: one bit per pool entry; after it the visited set when it lives in LDS
     __shared__ int32_t s_cnt, s_np, s_skip, s_xn, s_kc, s_nin, s_rmin;
-    __shared__ int32_t s_par[8], s_psat[8];
+    __shared__ int32_t s_par[16], s_psat[16];
     __shared__ int32_t s_kw[AP_KW_MAX_TERMS];
     __shared__ int32_t s_seed[2];
 
@@ -343,7 +340,7 @@ void k_search(ApSearchArgs g) {
         if (v >= 0) {
             const bool seen = vis.test_and_set(v);
             const uint4 m = g.meta[v];
-            if (!seen) { const int32_t at = atomicAdd(&s_cnt, 1); cand[at] = v; s_meta[at] = m; }
+            if (!seen) s_meta[atomicAdd(&s_cnt, 1)] = make_uint4(m.x, m.y, m.z, (uint32_t)v);
         }
     }
     __syncthreads();
@@ -361,10 +358,10 @@ void k_search(ApSearchArgs g) {
         const float second_worst = second_full ? ap_key_score(kwc[g.k - 1]) : 0.f;
         constexpr int G = ApSearchG<NT>::G;
         if (use_tab)
-            nskipped += ap_score_candidates<DT, NV, true, KW, BIG, NT / 64, G>(g.D, g.rec, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score, cand,
+            nskipped += ap_score_candidates<DT, NV, true, KW, BIG, NT / 64, G>(g.D, g.rec, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score,
                                                                  s_meta, c, newk, s_kw, n_kw, g.kw_all != 0, second_full, second_worst, msp, mtx);
         else
-            nskipped += ap_score_candidates<DT, NV, false, KW, BIG, NT / 64, G>(g.D, g.rec, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score, cand,
+            nskipped += ap_score_candidates<DT, NV, false, KW, BIG, NT / 64, G>(g.D, g.rec, qa, qtab, a, wd, ws, wf, qnorm, pool_full, worst_score,
                                                                   s_meta, c, newk, s_kw, n_kw, g.kw_all != 0, second_full, second_worst, 0u, 0u);
         AP_PROF(1);
         __syncthreads();
@@ -639,7 +636,7 @@ void k_search(ApSearchArgs g) {
                 // test, not after it: one memory round trip less per iteration for 16 bytes per neighbour already seen
                 const bool seen = vis.test_and_set(v);
                 const uint4 m = g.meta[v];
-                if (!seen) { const int32_t at = atomicAdd(&s_cnt, 1); cand[at] = v; s_meta[at] = m; }
+                if (!seen) s_meta[atomicAdd(&s_cnt, 1)] = make_uint4(m.x, m.y, m.z, (uint32_t)v);
             }
         }
         __syncthreads();
@@ -779,11 +776,10 @@ static int ap_search_launch(const ap_index *ix, const ApSearchWs &ws, const ApVe
     g.meta = ix->meta;
     g.deleted = ix->deleted;
     auto lds_bytes = [&](int32_t nt) {
-        const int32_t nxtw = g.cmax > nt ? g.cmax : 0;
-        const bool pipe = !kw && !big_tables && nt >= 512;   // the large-pool path's entering keys and bitmap of the pool
-        return (size_t)(g.L + 2 * g.cmax + nxtw + (kw || pipe ? g.cmax : 0) + (kw ? g.k : 0)) * 8 + (size_t)g.cmax * (16 + 4) +
-               (size_t)(big_tables ? ApQTab<true>::SLOTS : ApQTab<false>::SLOTS) * 8 + 8 +
-               (pipe ? (size_t)(g.cmax & 1) * 4 + (size_t)((g.L + 63) / 64) * 8 : 0);
+        const bool pipe = !kw && !big_tables && nt >= 512;   // the large-pool path: entering keys in the candidates' space, a bitmap of the pool
+        const int32_t nxtw = !pipe && g.cmax > nt ? g.cmax : 0;
+        return (size_t)(g.L + (pipe ? 1 : 2) * g.cmax + nxtw + (kw ? g.cmax + g.k : 0)) * 8 + (size_t)g.cmax * 16 +
+               (size_t)(big_tables ? ApQTab<true>::SLOTS : ApQTab<false>::SLOTS) * 8 + (pipe ? (size_t)((g.L + 63) / 64) * 8 : 0);
     };
     // Workgroup size (plain search): four waves as long as the LDS holds at least five workgroups per CU; a pool
     // that leaves room for two to four gets eight waves, one that fills the CU alone sixteen (measured: each is the
@@ -793,7 +789,7 @@ static int ap_search_launch(const ap_index *ix, const ApSearchWs &ws, const ApVe
         const size_t per_cu = (size_t)160 * 1024 / lds_bytes(256);
         nt = per_cu > AP_SEARCH_NT512_AT ? 256 : per_cu > AP_SEARCH_NT1024_AT ? 512 : 1024;
     }
-    g.nxtw = g.cmax > nt ? g.cmax : 0;
+    g.nxtw = nt == 256 && g.cmax > nt ? g.cmax : 0;
     size_t smem = lds_bytes(nt);
     // Visited sets in LDS (four-wave workgroups only): when the bitset fits beside the kernel's other arrays without
     // taking a workgroup's place on the CU (seven of them run on one while the pool is small).  Measured on 100,000
@@ -840,7 +836,7 @@ static int ap_search_check(const ap_index *ix, int32_t nq, int32_t k, int32_t be
     AP_REQUIRE(nq == 0 || (out_ids && out_scores), "NULL output");
     AP_REQUIRE(beam >= 1 && beam <= AP_MAX_BEAM, "beam = %d must be in [1, %d]", beam, AP_MAX_BEAM);
     AP_REQUIRE(k >= 1 && k <= beam, "k = %d must be in [1, beam]", k);
-    AP_REQUIRE(width >= 1 && width <= 8, "search_width = %d must be in [1, 8]", width);
+    AP_REQUIRE(width >= 1 && width <= 16, "search_width = %d must be in [1, 16]", width);
     AP_REQUIRE(max_iters >= 0, "max_iters must be >= 0");
     AP_REQUIRE(!(kw || ix->deleted) || ix->docs.n < (1ll << 29), "keyword search and searches on an index with deletions need n < 2^29");
     return AP_OK;

@@ -194,7 +194,7 @@ def test_pools_beyond_64_kb_of_lds():
     D = O.encode_docs(w.docs); Q = O.VS(w.queries)
     sem, _, _, ent = [t.cpu().numpy() for t in ix.export_graph()]
     wq = np.tile(np.float32(w.weights), (qs.n, 1))
-    for (k, L, width) in ((10, 8192, 1), (100, 16384, 1), (10, 12000, 4)):
+    for (k, L, width) in ((10, 8192, 1), (100, 16384, 1), (10, 12000, 4), (10, 16384, 16)):
         _say(f"  beam {L}, width {width}")
         _replay_search(ix, docs, qs, w, D, Q, sem, ent, wq, k, L, 0, width)
     counts = ix.search_stats(qs.n)[0].cpu().numpy()

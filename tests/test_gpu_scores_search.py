@@ -123,7 +123,7 @@ def test_search_matches_oracle_replay(tiny):
     ref4 = O.hybrid_block(Q, np.arange(nq), D, allc, wq)
     qn = row_norms(w.queries)[:, None]; dn = row_norms(w.docs)[None, :]
     assert_scores_close(table, ref4[:, :, 3], score_tol(ref4, wq[:, None, :], qn, dn, RTOL_F32)[:, :, 3], "table")
-    for (k, L, iters, width) in ((10, 64, 0, 1), (10, 32, 0, 2), (5, 16, 4, 1), (10, 128, 0, 4), (1, 1, 0, 1)):
+    for (k, L, iters, width) in ((10, 64, 0, 1), (10, 32, 0, 2), (5, 16, 4, 1), (10, 128, 0, 4), (10, 128, 0, 16), (1, 1, 0, 1)):
         _say(f"search tiny k={k} L={L} iters={iters} width={width}")
         ids, sc = [t.cpu().numpy() for t in ix.search_batch(qs, k, L, wq, iters, width)]
         for qi in range(nq):
@@ -154,7 +154,7 @@ def test_search_edge_cases(tiny):
     with pytest.raises(B.ApError):
         ix.search_batch(qs, 10, 16385)
     with pytest.raises(B.ApError):
-        ix.search_batch(qs, 10, 64, search_width=9)
+        ix.search_batch(qs, 10, 64, search_width=17)
     ing = B.Index.ingest(docs, B.build_params(w.degree))
     with pytest.raises(B.ApError):
         ing.search_batch(qs, 10, 64)        # no graph
