@@ -540,6 +540,12 @@ __device__ __forceinline__ void ap_lists_load(const ApVecs &B, int64_t spb, int3
 // A wave-uniform 32-bit value moved to scalar registers.  The builtin returns a signed int: an offset of 2^31 or more
 // must come back as unsigned before it is added to a pointer.
 __device__ __forceinline__ uint32_t ap_uniform_u32(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+__device__ __forceinline__ int32_t ap_uniform_i32(int32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ uint64_t ap_uniform_u64(uint64_t v) {
+    return ((uint64_t)ap_uniform_u32((uint32_t)(v >> 32)) << 32) | (uint64_t)ap_uniform_u32((uint32_t)v);
+}
+// The wave's number inside its workgroup, as a scalar: loops that stride over it then run on scalar branches.
+__device__ __forceinline__ int ap_wave_id() { return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
 
 // ---- packed document records (search side) -------------------------------
 // One document's sparse entries followed by its lexical entries, 8 bytes each

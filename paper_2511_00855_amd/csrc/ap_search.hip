@@ -116,7 +116,7 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const ui
                                                        float worst_score, const uint4 *s_meta, int32_t c,
                                                        uint64_t *newk, const int32_t *s_kw, int32_t n_kw, bool kw_all,
                                                        bool second_full, float second_worst, uint32_t msp, uint32_t mtx) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = ap_wave_id();
     int32_t skipped = 0;
     for (int32_t i0 = wave; i0 < c; i0 += NW * G) {
         uint2 xs[G][2], xt[G][1];
@@ -257,12 +257,13 @@ void k_search(ApSearchArgs g) {
     // parents are picked from a bitmap of the unexpanded entries.
     constexpr bool PIPE = !KW && !BIG && NT >= 512;
     constexpr int SPB = ApQTab<BIG>::SPB, TXB = ApQTab<BIG>::TXB;
-    // The query's two look-up tables come first: at a fixed LDS address, so that a look-up's address is the hash alone.
-    // Then this iteration's candidates: 16 bytes each, the document's descriptor with its id in the fourth word.
+    // The query's two look-up tables are a static array: at an address the compiler knows, so that a look-up's address
+    // is the hash alone.  The dynamic part starts with this iteration's candidates: 16 bytes each, the document's
+    // descriptor with its id in the fourth word.
     // PIPE: once the candidates are scored their space is free until the next gather, and holds the entering keys,
     // unordered (xk) and sorted (newS): what lets the largest pool (16384 entries) take sixteen parents' neighbours.
-    uint64_t *qtab = smem64;
-    uint4 *s_meta = reinterpret_cast<uint4 *>(qtab + ApQTab<BIG>::SLOTS);
+    __shared__ __attribute__((aligned(16))) uint64_t qtab[ApQTab<BIG>::SLOTS];
+    uint4 *s_meta = reinterpret_cast<uint4 *>(smem64);
     uint64_t *cur = reinterpret_cast<uint64_t *>(s_meta + g.cmax);   // the pool: L keys, best first
     uint64_t *newk = cur + g.L;              // keys of this iteration's candidates, unordered
     uint64_t *newS = PIPE ? reinterpret_cast<uint64_t *>(s_meta) + g.cmax : newk + g.cmax;   // the same, sorted
@@ -276,7 +277,7 @@ void k_search(ApSearchArgs g) {
     __shared__ int32_t s_seed[2];
 
     const int64_t q = (int64_t)g.q0 + blockIdx.x;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = ap_wave_id();
     // the query's lists: look-up tables in LDS when they are short (the usual case), else left in global memory
     ApLists a;
     {
@@ -296,8 +297,9 @@ void k_search(ApSearchArgs g) {
             if (lane == 0) { s_seed[0] = s0; s_seed[1] = s1; }
         }
         __syncthreads();
-        use_tab = use_tab && s_seed[0] >= 0 && s_seed[1] >= 0;
-        if (use_tab) { msp = ap_seed_mult(s_seed[0]); mtx = ap_seed_mult(s_seed[1]); }
+        const int32_t seed0 = ap_uniform_i32(s_seed[0]), seed1 = ap_uniform_i32(s_seed[1]);
+        use_tab = use_tab && seed0 >= 0 && seed1 >= 0;
+        if (use_tab) { msp = ap_seed_mult(seed0); mtx = ap_seed_mult(seed1); }
     } else if (use_tab) {
         for (int i = threadIdx.x; i < ApQTab<BIG>::SLOTS; i += blockDim.x) qtab[i] = 0xffffffffull;
         __syncthreads();
@@ -349,10 +351,10 @@ void k_search(ApSearchArgs g) {
     AP_PROF_DECL;
     for (;;) {
         AP_PROF(0);
-        const int32_t c = s_cnt;
+        const int32_t c = ap_uniform_i32(s_cnt);   // counts and keys that every thread reads alike are kept in scalar registers
         nscored += c;
         const bool pool_full = len == g.L;
-        const uint64_t worst = pool_full ? cur[g.L - 1] : 0ull;
+        const uint64_t worst = pool_full ? ap_uniform_u64(cur[g.L - 1]) : 0ull;
         const float worst_score = ap_key_score(worst);
         const bool second_full = kw_on && s_kc == g.k;   // s_kc and kwc were last written before the previous barriers
         const float second_worst = second_full ? ap_key_score(kwc[g.k - 1]) : 0.f;
@@ -377,7 +379,7 @@ void k_search(ApSearchArgs g) {
                 if ((key >> 32) != 0ull && key > worst) xk[atomicAdd(&s_nin, 1)] = key;
             }
             __syncthreads();
-            cin = s_nin;
+            cin = ap_uniform_i32(s_nin);
             // One wave per entering key finds both of its ranks: among the entering keys (64 compares a step) and among
             // the pool (64 probes a step: three steps for 16384 entries instead of fourteen halvings).  The first gives
             // the key its place in newS, the second goes to rr (in newk's space, which is free now).
@@ -409,7 +411,7 @@ void k_search(ApSearchArgs g) {
                 newS[r] = key;
             }
             __syncthreads();
-            cin = ap_rank_in(newS, c, worst);   // new keys that rank before `worst` (all of them while the pool has room)
+            cin = ap_uniform_i32(ap_rank_in(newS, c, worst));   // new keys that rank before `worst` (all of them while the pool has room)
         }
         AP_PROF(3);
         if (kw_on) {
@@ -427,7 +429,7 @@ void k_search(ApSearchArgs g) {
             // barrier later (a chunk's writes never reach below its own start).
             const int32_t *rr = reinterpret_cast<const int32_t *>(newk);   // rank of every entering key among the pool, ascending
             int32_t *bshift = reinterpret_cast<int32_t *>(umask);          // entering keys that land before block b
-            const int32_t rmin = rr[0];
+            const int32_t rmin = ap_uniform_i32(rr[0]);
             fu = fu < rmin ? fu : rmin;   // the best entering key lands at rmin, unexpanded; entries before it stay put
             const int32_t nb = (len + 63) >> 6;
             for (int32_t b = threadIdx.x; b <= nb; b += NT) {   // number of ranks below 64 b
@@ -480,7 +482,7 @@ void k_search(ApSearchArgs g) {
                 nxt[t] = (uint64_t)(uint32_t)(t + ap_rank_in(cur, len, key));   // park the positions in the scratch array
             }
             __syncthreads();
-            const int32_t rmin = s_rmin;
+            const int32_t rmin = ap_uniform_i32(s_rmin);
             fu = fu < rmin ? fu : rmin;   // the best entering key lands at rmin, unexpanded; entries before it stay put
             for (int32_t hi = len; hi > rmin; hi -= 2 * NT) {
                 const int32_t lo = hi - 2 * NT > rmin ? hi - 2 * NT : rmin;
@@ -616,7 +618,7 @@ void k_search(ApSearchArgs g) {
         }
         if (!PIPE) __syncthreads();
         AP_PROF(5);
-        const int32_t np = PIPE ? pipe_np : s_np;
+        const int32_t np = PIPE ? pipe_np : ap_uniform_i32(s_np);
         if (np == 0) break;
         // neighbours of the parents that were never seen before; a parent that satisfies the keyword
         // constraint also brings its keyword edges
@@ -801,14 +803,16 @@ static int ap_search_launch(const ap_index *ix, const ApSearchWs &ws, const ApVe
         const size_t now = std::min<size_t>(7, lds / smem), then = with <= lds ? std::min<size_t>(7, lds / with) : 0;
         if (then >= now && then > 0) { g.vis_lds = 1; smem = with; }
     }
-    AP_REQUIRE(smem <= 160 * 1024, "beam and search_width need %zu bytes of LDS (limit 160 KiB)", smem);
+    // the kernel's static arrays (counters, parents, required terms) take a few hundred bytes more
+    AP_REQUIRE(smem + 512 <= 160 * 1024, "beam and search_width need %zu bytes of LDS (limit 160 KiB)", smem + 512);
+    const size_t dyn = smem - (size_t)(big_tables ? ApQTab<true>::SLOTS : ApQTab<false>::SLOTS) * 8;   // the tables are a static array
     hipError_t le = hipSuccess;
 #define AP_LAUNCH_SEARCH(KWF, BIGF, NTF)                                                                                         \
     AP_DISPATCH_DENSE(ix->dtype, ix->docs.dim, {                                                                                  \
         if (smem > 48 * 1024)                                                                                                     \
             le = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_search<DT, NV, KWF, BIGF, NTF>),                           \
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);                                      \
-        if (le == hipSuccess) hipLaunchKernelGGL((k_search<DT, NV, KWF, BIGF, NTF>), dim3((unsigned)qn), dim3(NTF), smem, st, g); \
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);                                       \
+        if (le == hipSuccess) hipLaunchKernelGGL((k_search<DT, NV, KWF, BIGF, NTF>), dim3((unsigned)qn), dim3(NTF), dyn, st, g);  \
     })
     for (int32_t q0 = 0; q0 < nq; q0 += ws.slab) {
         const int32_t qn = std::min(ws.slab, nq - q0);
