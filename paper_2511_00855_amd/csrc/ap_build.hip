@@ -122,7 +122,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_seed_thresh_big(const void *de
         // 16-byte LDS read, and an element costs a compare and a (rarely taken) branch.  Only a tile whose row and
         // column runs overlap can pair a document with itself.
         const bool diagonal = a_first < b_first + AP_BIG && b_first < a_first + AP_BIG;
-        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        const int lane = threadIdx.x & 63, wave = ap_wave_id();
         const int wm = wave / WN, wn = wave % WN;
 #pragma unroll
         for (int a = 0; a < ApBig<WM, WN>::FA; a++)
@@ -431,7 +431,7 @@ __global__ __launch_bounds__(512) void k_refine(ApVecs D, const uint2 *__restric
     __shared__ int32_t s_cnt, s_nold;
     const int64_t x = x0 + blockIdx.x;   // the launch covers nodes x0 .. x0 + gridDim.x of the nn
     const int64_t u = node_ids ? (int64_t)node_ids[x] : x;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = ap_wave_id();
     const ApLists a = ap_stage_lists(D, u, l_sp_idx, l_sp_val, l_tx_idx, l_tx_val, AP_A_CAP);
     float qa[NV * ApDense<DT>::EPC];
     ap_load_aside<DT, NV, DT>(D.dense, u, D.dim, qa);
@@ -461,10 +461,10 @@ __global__ __launch_bounds__(512) void k_refine(ApVecs D, const uint2 *__restric
         if (v >= 0 && v != (int32_t)u && ap_ht_insert(ht, v)) cand[atomicAdd(&s_cnt, 1)] = v;
     }
     __syncthreads();
-    const int32_t cnt = s_cnt;
+    const int32_t cnt = ap_uniform_i32(s_cnt);
     if (threadIdx.x == 0 && n_sims) atomicAdd(n_sims, (unsigned long long)cnt);   // measurement: similarities of this node and round
     for (int32_t i = wave; i < cnt; i += (int32_t)(blockDim.x >> 6)) {
-        const int32_t v = cand[i];
+        const int32_t v = ap_uniform_i32(cand[i]);
         float sd, ss, sf;
         if (use_tab) {
             const uint4 m = meta[v];
@@ -875,7 +875,7 @@ __global__ __launch_bounds__(256) void k_assemble(int64_t n, int32_t R, int32_t 
                                                   const int32_t *__restrict__ sorted_ids, const int32_t *__restrict__ sp_ids,
                                                   const unsigned long long *__restrict__ rev, int64_t u0, int32_t *__restrict__ out) {
     __shared__ int32_t rows[4][128];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = ap_wave_id();
     const int64_t u = u0 + (int64_t)blockIdx.x * 4 + wave;
     if (u >= n) return;
     int32_t *row = rows[wave];
@@ -964,7 +964,7 @@ __global__ __launch_bounds__(256) void k_rescore_lists(ApVecs D, float wd, float
     __shared__ int32_t l_sp_idx[AP_A_CAP], l_tx_idx[AP_A_CAP];
     __shared__ float l_sp_val[AP_A_CAP], l_tx_val[AP_A_CAP];
     const int64_t u = u0 + blockIdx.x;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = ap_wave_id();
     const ApLists a = ap_stage_lists(D, u, l_sp_idx, l_sp_val, l_tx_idx, l_tx_val, AP_A_CAP);
     float qa[NV * ApDense<DT>::EPC];
     ap_load_aside<DT, NV, DT>(D.dense, u, D.dim, qa);

@@ -29,7 +29,7 @@ __global__ __launch_bounds__(256) void k_hybrid_pairs(ApVecs A, ApVecs B, const 
     ap_load_aside<DT, NV, SRC>(A.dense, row, A.dim, qa);
     __syncthreads();
     const float wd = w[x * w_stride + 0], ws = w[x * w_stride + 1], wf = w[x * w_stride + 2];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = ap_wave_id();
     for (int32_t y = y0 + wave; y < y1; y += 4) {
         const int32_t j = cand[x * c + y];
         float sd, ss, sf, fu;
@@ -142,7 +142,7 @@ __global__ __launch_bounds__(256) void k_bf_scores(ApVecs Q, ApVecs D, int32_t q
     }
     __syncthreads();
     const int lane = threadIdx.x & 63;
-    const int64_t wave = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t wave = blockIdx.x * 4 + ap_wave_id();
     const int64_t nwaves = (int64_t)gridDim.x * 4;
     for (int64_t j = wave; j < D.n; j += nwaves) {
         float dr[NV * EPC];

@@ -244,7 +244,7 @@ __global__ __launch_bounds__(256) void k_search_kg(ApKgArgs g) {
     int32_t *cand = reinterpret_cast<int32_t *>(canda + g.cmax);
     __shared__ int32_t s_cnt, s_par, s_pann;
     const int64_t q = (int64_t)g.q0 + blockIdx.x;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = ap_wave_id();
     ApLists a;
     {
         const int64_t sb = g.Q.sp_indptr[q], tb = g.Q.tx_indptr[q];

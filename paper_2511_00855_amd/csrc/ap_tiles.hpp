@@ -56,7 +56,7 @@ __device__ __forceinline__ void ap_tile_store(const float4 v[4], const int32_t r
 template <int DT>
 __device__ __forceinline__ void ap_tile_gemm(const void *dense, int32_t dim, const int32_t *a_rows, const int32_t *b_rows,
                                              float *lA, float *lB, ap_f32x16 acc[2][2]) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = ap_wave_id();
     const int wm = wave >> 1, wn = wave & 1;
     const int li = lane & 31, lk = lane >> 5;
 #pragma unroll
@@ -132,7 +132,7 @@ __device__ __forceinline__ void ap_tile_store_bf16(const uint4 v[AP_NP16], const
 
 __device__ __forceinline__ void ap_tile_gemm_bf16(const void *dense, int32_t dim, const int32_t *a_rows, const int32_t *b_rows,
                                                   uint16_t *lA, uint16_t *lB, ap_f32x16 acc[2][2]) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = ap_wave_id();
     const int wm = wave >> 1, wn = wave & 1;
     const int li = lane & 31, lk = (lane >> 5) * 8;
 #pragma unroll
@@ -242,7 +242,7 @@ __device__ __forceinline__ void ap_big_gemm_bf16(const void *dense, int32_t dim,
                                                  ap_f32x16 acc[ApBig<WM, WN>::FA][ApBig<WM, WN>::FB]) {
     using B = ApBig<WM, WN>;
     constexpr int NP = B::NP, RPP = B::RPP, FA = B::FA, FB = B::FB;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = ap_wave_id();
     const int wm = wave / WN, wn = wave % WN;
     const int li = lane & 31, lk = (lane >> 5) * 8;
     const char *run_a = static_cast<const char *>(dense) + (int64_t)a_first * dim * 2;   // uniform
@@ -320,7 +320,7 @@ _Pragma("unroll")                                                               
 // Calls f(i, j, value) for every element this lane holds of the 256x256 tile.
 template <int WM, int WN, typename F>
 __device__ __forceinline__ void ap_big_foreach(const ap_f32x16 acc[ApBig<WM, WN>::FA][ApBig<WM, WN>::FB], F f) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = ap_wave_id();
     const int wm = wave / WN, wn = wave % WN;
 #pragma unroll
     for (int a = 0; a < ApBig<WM, WN>::FA; a++)
@@ -355,7 +355,7 @@ __device__ __forceinline__ void ap_tile_product(const void *dense, int32_t dim, 
 // Calls f(i, j, value) for every element this lane holds of the 128x128 tile.
 template <typename F>
 __device__ __forceinline__ void ap_tile_foreach(const ap_f32x16 acc[2][2], F f) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = ap_wave_id();
     const int wm = wave >> 1, wn = wave & 1;
 #pragma unroll
     for (int a = 0; a < 2; a++)
