@@ -208,6 +208,9 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const ui
 #ifndef AP_SEARCH_G_1024
 #define AP_SEARCH_G_1024 2
 #endif
+#ifndef AP_RANK_LANES
+#define AP_RANK_LANES 16        // lanes that rank one entering key of a large pool (16, 32 or 64)
+#endif
 #ifndef AP_SEARCH_WAVES_512
 #define AP_SEARCH_WAVES_512 6
 #endif
@@ -380,24 +383,35 @@ void k_search(ApSearchArgs g) {
             }
             __syncthreads();
             cin = ap_uniform_i32(s_nin);
-            // One wave per entering key finds both of its ranks: among the entering keys (64 compares a step) and among
-            // the pool (64 probes a step: three steps for 16384 entries instead of fourteen halvings).  The first gives
-            // the key its place in newS, the second goes to rr (in newk's space, which is free now).
+            // A group of AP_RANK_LANES lanes per entering key finds both of its ranks: among the entering keys (a compare
+            // per lane and step) and among the pool (as many probes a step as the group has lanes: four steps of 16
+            // for 16384 entries instead of fourteen halvings).  The first gives the key its place in newS, the second
+            // goes to rr (in newk's space, which is free now).  Late in a search few keys enter, and what costs is the
+            // chain of dependent LDS reads per key: four keys share a wave's steps.
+            constexpr int GL = AP_RANK_LANES, GSH = GL == 64 ? 6 : GL == 32 ? 5 : 4, GPW = 64 / GL;
+            static_assert(GL == 16 || GL == 32 || GL == 64, "lanes per key");
+            const int grp = lane >> GSH, gl = lane & (GL - 1);
+            auto group_count = [&](bool p) -> int32_t {   // lanes of this lane's group for which p holds
+                const uint64_t m = __ballot(p);
+                if (GL == 64) return (int32_t)__popcll(m);
+                return (int32_t)__popc((uint32_t)(m >> (grp * GL)) & (GL == 32 ? 0xffffffffu : 0xffffu));
+            };
             int32_t *rr = reinterpret_cast<int32_t *>(newk);
-            for (int32_t j = wave; j < cin; j += NT / 64) {
-                const uint64_t key = xk[j];
+            for (int32_t j0 = wave * GPW; j0 < cin; j0 += NT / 64 * GPW) {
+                const int32_t j = j0 + grp;
+                const bool on = j < cin;
+                const uint64_t key = on ? xk[j] : 0ull;
                 int32_t e = 0;
-                for (int32_t i0 = 0; i0 < cin; i0 += 64) e += (int32_t)__popcll(__ballot(i0 + lane < cin && xk[i0 + lane] > key));
-                int32_t lo = 0, hi = len;   // the rank (number of pool entries that rank before the key) lies in [lo, hi]
-                while (hi > lo) {
-                    const int32_t step = (hi - lo + 63) >> 6;
-                    const int32_t at = lo + (lane + 1) * step - 1;
-                    const int32_t n_before = (int32_t)__popcll(__ballot(at < hi && cur[at] > key));
+                for (int32_t i0 = 0; i0 < cin; i0 += GL) e += group_count(on && i0 + gl < cin && xk[i0 + gl] > key);
+                int32_t lo = 0, hi = on ? len : 0;   // the rank (number of pool entries that rank before the key) lies in [lo, hi]
+                while (__any(hi > lo)) {
+                    const int32_t step = (hi - lo + GL - 1) >> GSH;
+                    const int32_t at = lo + (gl + 1) * step - 1;
+                    const int32_t n_before = group_count(hi > lo && at < hi && cur[at] > key);
                     const int32_t nlo = lo + n_before * step, nhi = lo + (n_before + 1) * step - 1;
-                    lo = nlo;
-                    hi = nhi < hi ? nhi : hi;
+                    if (hi > lo) { lo = nlo; hi = nhi < hi ? nhi : hi; }
                 }
-                if (lane == 0) { newS[e] = key; rr[e] = lo; }
+                if (on && gl == 0) { newS[e] = key; rr[e] = lo; }
             }
             __syncthreads();
             if (threadIdx.x == 0) s_nin = 0;   // next touched after the barriers of the merge or the pick
