@@ -599,6 +599,27 @@ __device__ __forceinline__ float ap_merge_dot(P a, int32_t na, P b, int32_t nb) 
     return acc;
 }
 
+// The same walk over two lists in LDS that each end in a sentinel entry (term 0xffffffff, weight 0): the cursors are
+// clamped to the sentinels instead of every operation being masked, so a step is thirteen vector instructions.  A
+// finished lane sits on a sentinel, whose term matches nothing but the other sentinel, and then adds 0 x 0.  a_end and
+// b_end are the LDS byte addresses of the sentinels; same products in the same order as ap_merge_dot.
+__device__ __forceinline__ float ap_merge_dot_lds(uint32_t a, uint32_t a_end, uint32_t b, uint32_t b_end) {
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));   // a plain vector value: loads from LDS as it is
+    typedef const AP_LDS u32x2 *LP;
+    float acc = 0.f;
+    u32x2 ea = *(LP)(uintptr_t)a, eb = *(LP)(uintptr_t)b;
+    while (__any(a < a_end && b < b_end)) {
+        const float prod = fmaf(__uint_as_float(ea.y), __uint_as_float(eb.y), acc);
+        acc = ea.x == eb.x ? prod : acc;
+        const uint32_t na = a + (ea.x <= eb.x ? 8u : 0u), nb = b + (eb.x <= ea.x ? 8u : 0u);
+        a = na < a_end ? na : a_end;
+        b = nb < b_end ? nb : b_end;
+        ea = *(LP)(uintptr_t)a;
+        eb = *(LP)(uintptr_t)b;
+    }
+    return acc;
+}
+
 __global__ __launch_bounds__(256) void k_gram_merge(const uint2 *__restrict__ rec, const uint4 *__restrict__ meta, float wd, float ws,
                                                     float wf, int32_t K, const int32_t *__restrict__ knn,
                                                     const int32_t *__restrict__ node_ids, int64_t x0, float *__restrict__ pm) {
@@ -621,12 +642,13 @@ __global__ __launch_bounds__(256) void k_gram_merge(const uint2 *__restrict__ re
             if (pos < K) id = knn[u * K + pos];
             if (id >= 0) { const uint4 m = meta[id]; first = m.x; sn = (int32_t)(m.y & 0xffffu); tn = (int32_t)(m.y >> 16); }
         }
-        int32_t incl = sn + tn;
+        const int32_t room = lane < 2 * AP_GT ? sn + tn + 2 : 0;   // a record in LDS: sparse entries, sentinel, lexical entries, sentinel
+        int32_t incl = room;
         for (int o = 1; o < 64; o <<= 1) {
             const int32_t up = __shfl_up(incl, o, 64);
             if (lane >= o) incl += up;
         }
-        if (lane < 2 * AP_GT) { d_id[lane] = id; d_off[lane] = incl - (sn + tn); d_sn[lane] = sn; d_tn[lane] = tn; d_first[lane] = first; }
+        if (lane < 2 * AP_GT) { d_id[lane] = id; d_off[lane] = incl - room; d_sn[lane] = sn; d_tn[lane] = tn; d_first[lane] = first; }
         if (lane == 2 * AP_GT - 1) s_total = incl;
     }
     __syncthreads();
@@ -634,9 +656,10 @@ __global__ __launch_bounds__(256) void k_gram_merge(const uint2 *__restrict__ re
     const uint64_t *grec = reinterpret_cast<const uint64_t *>(rec);
     if (in_lds) {
         for (int d = 0; d < 2 * AP_GT; d++) {
-            const int32_t len = d_sn[d] + d_tn[d], off = d_off[d];
+            const int32_t sn = d_sn[d], len = sn + d_tn[d], off = d_off[d];
             const uint64_t *src = grec + d_first[d];
-            for (int32_t e = tid; e < len; e += 256) ent[off + e] = src[e];
+            for (int32_t e = tid; e < len; e += 256) ent[off + e + (e >= sn ? 1 : 0)] = src[e];
+            if (tid == 0) { ent[off + sn] = 0xffffffffull; ent[off + len + 1] = 0xffffffffull; }
         }
         __syncthreads();
     }
@@ -649,10 +672,11 @@ __global__ __launch_bounds__(256) void k_gram_merge(const uint2 *__restrict__ re
     if (a >= 0 && b >= 0) {
         float qs, qt;
         if (in_lds) {
-            const AP_LDS uint64_t *la = (const AP_LDS uint64_t *)ent + d_off[r];
-            const AP_LDS uint64_t *lb = (const AP_LDS uint64_t *)ent + d_off[AP_GT + c];
-            qs = ap_merge_dot(la, d_sn[r], lb, d_sn[AP_GT + c]);
-            qt = ap_merge_dot(la + d_sn[r], d_tn[r], lb + d_sn[AP_GT + c], d_tn[AP_GT + c]);
+            const uint32_t base = (uint32_t)(uintptr_t)(const AP_LDS uint64_t *)ent;
+            const uint32_t la = base + 8u * (uint32_t)d_off[r], lb = base + 8u * (uint32_t)d_off[AP_GT + c];
+            const uint32_t sa = 8u * (uint32_t)d_sn[r], sb = 8u * (uint32_t)d_sn[AP_GT + c];
+            qs = ap_merge_dot_lds(la, la + sa, lb, lb + sb);
+            qt = ap_merge_dot_lds(la + sa + 8u, la + sa + 8u + 8u * (uint32_t)d_tn[r], lb + sb + 8u, lb + sb + 8u + 8u * (uint32_t)d_tn[AP_GT + c]);
         } else {
             const uint64_t *ga = grec + d_first[r], *gb = grec + d_first[AP_GT + c];
             qs = ap_merge_dot(ga, d_sn[r], gb, d_sn[AP_GT + c]);
