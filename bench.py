@@ -52,27 +52,26 @@ def parse_sweep(text):
     return out
 
 
-def keyword_leg(args, w, ix, qs, wq, k, chosen):
-    """Keyword-constrained search (Section 4.2.2): every query requires 1-2 of its own text tokens.  Ground truth
-    = exact top-k among the documents holding a required term, on up to 1000 sampled queries (exhaustive scores
-    from ap_hybrid_scores, filter and top-k in torch: measurement only)."""
+def keyword_ground_truth(w, ix, wq, kw, sample, k):
+    """Exact top-k among the documents that hold at least one of a query's required terms, for the sampled queries:
+    exhaustive scores from ap_hybrid_scores; filter and top-k in torch (measurement only; ties by lower id as torch
+    returns them is not relied on: tests compare it with a brute force on the oracle's scores up to near-ties).
+    Returns (ids [len(sample), k] with -1 where fewer than k documents satisfy, scores)."""
     import numpy as np
     import scipy.sparse as sps
     import torch
     from paper_2511_00855_amd import binding as B
-    from paper_2511_00855_amd.synth import make_keywords, subset_vecset
-    nq, n = qs.n, w.docs.n
-    kw = make_keywords(w.queries, seed=1, max_terms=2, stride=2)
-    sample = np.arange(0, nq, max(1, nq // 1000))[:1000]
+    from paper_2511_00855_amd.synth import subset_vecset
+    n = w.docs.n
     inv = sps.csr_matrix((np.ones(len(w.docs.tx_idx), np.int8), w.docs.tx_idx, w.docs.tx_indptr),
                          shape=(n, w.docs.tx_vocab)).tocsc()
-    gt = []
+    gt, gs = [], []
     for c0 in range(0, len(sample), 250):
         rows = sample[c0:c0 + 250]
         sub = B.DeviceVecs(subset_vecset(w.queries, rows), "cuda:0")
         allc = torch.arange(n, dtype=torch.int32, device="cuda:0").repeat(len(rows), 1)
         sc = ix.hybrid_scores(sub, allc, wq[torch.from_numpy(rows).to("cuda:0")])[:, :, 3]
-        rr, cc = [], []
+        rr, cc = [np.zeros(0, np.int64)], [np.zeros(0, np.int64)]
         for x, qi in enumerate(rows):
             for t in kw[qi][kw[qi] >= 0]:
                 d = inv.indices[inv.indptr[t]:inv.indptr[t + 1]]
@@ -81,9 +80,21 @@ def keyword_leg(args, w, ix, qs, wq, k, chosen):
         mask[torch.from_numpy(np.concatenate(rr)).to("cuda:0"), torch.from_numpy(np.concatenate(cc)).to("cuda:0")] = True
         top = sc.masked_fill(~mask, float("-inf")).topk(k, dim=1)
         ids = torch.where(torch.isinf(top.values), torch.full_like(top.indices, -1), top.indices)
-        gt.append(ids.cpu().numpy())
+        gt.append(ids.cpu().numpy()); gs.append(top.values.cpu().numpy())
         del sc, mask, allc
-    gt = np.concatenate(gt)
+    return np.concatenate(gt), np.concatenate(gs)
+
+
+def keyword_leg(args, w, ix, qs, wq, k, chosen):
+    """Keyword-constrained search (Section 4.2.2): every query requires 1-2 of its own text tokens.  Ground truth
+    = exact top-k among the documents holding a required term, on up to 1000 sampled queries."""
+    import numpy as np
+    import torch
+    from paper_2511_00855_amd.synth import make_keywords
+    nq = qs.n
+    kw = make_keywords(w.queries, seed=1, max_terms=2, stride=2)
+    sample = np.arange(0, nq, max(1, nq // 1000))[:1000]
+    gt, _ = keyword_ground_truth(w, ix, wq, kw, sample, k)
     out = []
     for beam in sorted({w.beam, 512, chosen}):
         for edges in (True, False):

@@ -171,3 +171,31 @@ def test_mark_deletion(tiny):
         ix.mark_deleted(np.concatenate([dele, [3, 5]]).astype(np.int32), restore=True)
     ids, sc = [t.cpu().numpy() for t in ix.search_batch(qs, k, L, wq)]
     assert np.array_equal(ids, base_ids) and np.array_equal(sc, base_sc)
+
+
+def test_bench_keyword_ground_truth_is_the_constrained_top_k(tiny):
+    """bench.py's keyword leg measures recall against a ground truth it computes with torch (mask of the documents
+    that hold a required term over the GPU's exhaustive scores, then top-k).  Here the same function against a
+    brute force over the oracle's fp64 scores: the satisfying documents enumerated from the CSR rows one by one,
+    sorted by (score, id).  Differences are admitted only between near-ties."""
+    import bench
+    from parity import assert_ranked_equiv, score_tol
+    w, docs, qs, ix, D, Q, sem, ke, kc, ent, wq, table = tiny
+    k = 10
+    kw = make_keywords(w.queries, seed=9, max_terms=2, stride=2)
+    sample = np.arange(0, qs.n, 2)
+    gt, gs = bench.keyword_ground_truth(w, ix, torch.from_numpy(wq).cuda(), kw, sample, k)
+    allc = np.tile(np.arange(docs.n, dtype=np.int32), (len(sample), 1))
+    ref = O.hybrid_block(Q, sample, D, allc, wq[sample])
+    tol = score_tol(ref, wq[sample][:, None, :], row_norms(w.queries)[sample][:, None], row_norms(w.docs)[None, :], RTOL_F32)[:, :, 3]
+    fused = ref[:, :, 3]
+    oid = np.full((len(sample), k), -1, np.int64); osc = np.full((len(sample), k), -np.inf)
+    nfew = 0
+    for x, qi in enumerate(sample):
+        sat = [v for v in range(docs.n) if _has(w, v, _kw_list(kw[qi]), False)]
+        order = sorted(sat, key=lambda v: (-fused[x, v], v))[:k]
+        oid[x, :len(order)] = order; osc[x, :len(order)] = fused[x, order]
+        nfew += len(order) < k
+    assert (gt >= 0).sum() == (oid >= 0).sum()
+    assert_ranked_equiv(gt, gs, oid, osc, lambda r, s_: float(tol[r].max()), lambda r, j: float(fused[r, j]), "keyword ground truth")
+    _say(f"keyword ground truth: {len(sample)} queries, {nfew} with fewer than {k} satisfying documents")
