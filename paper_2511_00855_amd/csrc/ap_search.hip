@@ -6,10 +6,11 @@
 //
 // Per query, in LDS: the candidate pool (one sorted array of 64-bit keys that
 // plays both `cand` and `topk` of Algorithm 2; bit 0 of a key = "not yet
-// expanded"), the keys of the neighbours scored in this iteration, and the
-// query's two sparse lists.  The query's dense slice stays in registers.  The
-// visited set is an exact bitset (one bit per document) in a per-index global
-// workspace.
+// expanded"), the descriptors and keys of the neighbours scored in this
+// iteration, and the query's two sparse lists as look-up tables.  The query's
+// dense slice stays in registers.  The visited set is an exact bitset (one bit
+// per document): in LDS for small pools on small corpora, else in a global
+// workspace of bounded size (large batches run in slabs of queries).
 #include <stdlib.h>
 #include <algorithm>
 #include <mutex>
