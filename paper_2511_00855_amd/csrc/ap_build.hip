@@ -713,6 +713,16 @@ __device__ __forceinline__ bool ap_list_has(const int32_t *idx, int64_t beg, int
     return lo < end && idx[lo] == t;
 }
 
+// The same test on a list of n ascending ids in LDS.
+__device__ __forceinline__ bool ap_list_has_lds(const int32_t *idx, int32_t n, int32_t t) {
+    int32_t lo = 0, hi = n;
+    while (lo < hi) {
+        const int32_t mid = (lo + hi) >> 1;
+        if (idx[mid] < t) lo = mid + 1; else hi = mid;
+    }
+    return lo < n && idx[lo] == t;
+}
+
 __global__ __launch_bounds__(256) void k_detour_prune(ApVecs D, const float *__restrict__ self_sim, int32_t K, int32_t R,
                                                       int32_t ke_cap, const int32_t *__restrict__ knn,
                                                       const float *__restrict__ knn_sc, const int32_t *__restrict__ node_ids,
@@ -724,12 +734,16 @@ __global__ __launch_bounds__(256) void k_detour_prune(ApVecs D, const float *__r
     __shared__ int32_t ids[256], cnt[256], order[256], se_pos[128], flag[256];
     __shared__ float simA[256];
     __shared__ int32_t T[AP_T_CAP];
+    __shared__ int32_t a_tx[AP_T_CAP];   // the node's own keywords: every step of the walk searches them
     const int64_t x = blockIdx.x;               // index inside the chunk (pm)
     const int64_t xo = xout0 + x;               // index in the output arrays
     const int64_t u = node_ids ? (int64_t)node_ids[x0 + x] : x0 + x;
     const float *P = pm + x * (int64_t)K * K;
     const int t = threadIdx.x;
     if (t < K) { ids[t] = knn[u * K + t]; simA[t] = knn_sc[u * K + t]; flag[t] = 0; }
+    const int64_t a_beg = D.tx_indptr[u], a_end = D.tx_indptr[u + 1];
+    const bool a_in_lds = a_end - a_beg <= AP_T_CAP;   // uniform
+    if (a_in_lds) for (int32_t e = t; e < (int32_t)(a_end - a_beg); e += 256) a_tx[e] = D.tx_idx[a_beg + e];
     __syncthreads();
     if (t < K) {
         int32_t c = 0;
@@ -776,7 +790,7 @@ __global__ __launch_bounds__(256) void k_detour_prune(ApVecs D, const float *__r
         for (int64_t e0 = vb; e0 < ve; e0 += 64) {
             const int64_t e = e0 + lane;
             const int32_t term = e < ve ? D.tx_idx[e] : -1;
-            const bool in = term >= 0 && ap_list_has(D.tx_idx, ab, ae, term);
+            const bool in = term >= 0 && (a_in_lds ? ap_list_has_lds(a_tx, (int32_t)(ae - ab), term) : ap_list_has(D.tx_idx, ab, ae, term));
             const uint64_t m = __ballot(in);
             if (in) { const int32_t pos = nt_all + __popcll(m & ((1ull << lane) - 1ull)); if (pos < AP_T_CAP) T[pos] = term; }
             nt_all += __popcll(m);
