@@ -269,3 +269,39 @@ def test_bf16_threshold_sweep_on_ragged_shapes(dim, debug_knobs):
         thr_sub = [t.cpu().numpy() for t in ix.stage_seed_knn(K, nodes)]
         assert np.array_equal(thr_sub[0], exact_sub[0]) and np.array_equal(thr_sub[1], exact_sub[1])
     ix.close()
+
+
+def test_random_search_settings_replayed():
+    """Forty seeded draws of (k, beam, parents per iteration, iteration cap) across the three workgroup sizes of the
+    search (256, 512 and 1024 threads), on two graphs of different degree, each replayed by the oracle on the GPU's own
+    score table: ids, scores and the number of scored documents bit for bit.  The draws include pools that never fill,
+    more candidates per iteration than the workgroup has threads, and caps that stop the search mid-way."""
+    rng = np.random.default_rng(2024)
+    for degree, n in ((64, 20000), (24, 30000)):
+        w = make_workload("tiny", seed=90 + degree, n=n, nq=3, dim=32)
+        docs = B.DeviceVecs(w.docs); qs = B.DeviceVecs(w.queries)
+        ix = B.Index.build(docs, B.build_params(degree, knn_k=2 * degree, nd_rounds=1, nd_sample=8, n_entry=32))
+        D = O.encode_docs(w.docs); Q = O.VS(w.queries)
+        sem, _, _, ent = [t.cpu().numpy() for t in ix.export_graph()]
+        wq = rng.uniform(0.1, 1.0, (qs.n, 3)).astype(np.float32)
+        allc = np.tile(np.arange(docs.n, dtype=np.int32), (qs.n, 1))
+        table = ix.hybrid_scores(qs, allc, wq).cpu().numpy()[:, :, 3]
+        for case in range(20):
+            beam = int(rng.choice([rng.integers(1, 400), rng.integers(400, 5000), rng.integers(5000, 16385)]))
+            width = int(rng.integers(1, 17))
+            k = int(min(beam, rng.choice([1, 10, 100])))
+            iters = int(rng.choice([0, 0, rng.integers(1, 60)]))
+            try:
+                ids, sc = [t.cpu().numpy() for t in ix.search_batch(qs, k, beam, wq, iters, width)]
+            except B.ApError as e:   # the only admissible refusal: the setting does not fit the LDS
+                assert "LDS" in str(e), (degree, beam, width, str(e))
+                assert (beam + width * degree) * 8 + width * degree * 16 > 150 * 1024, (degree, beam, width)
+                continue
+            counts = ix.search_stats(qs.n)[0].cpu().numpy()
+            _say(f"  degree {degree}: k {k} beam {beam} parents {width} cap {iters}: {counts[:, 0].mean():.0f} scored, {counts[:, 1].mean():.0f} iterations")
+            for qi in range(qs.n):
+                oi, os_, nv = O.search(D, sem, ent, Q, qi, wq[qi], k, beam, iters, width, score_table=table[qi])
+                assert np.array_equal(ids[qi], oi), (degree, qi, k, beam, width, iters)
+                assert np.array_equal(sc[qi], os_), (degree, qi, k, beam, width, iters)
+                assert counts[qi, 0] == nv, (degree, qi, k, beam, width, iters, counts[qi], nv)
+        ix.close()
