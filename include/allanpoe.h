@@ -350,6 +350,7 @@ int ap_build_counters(const ap_index *index, uint64_t out2[2], void *stream);
  *   "max_launch_threads"      a multiple of 1024: launches that grow with the corpus run in slices of this many threads
  *   "search_workspace_bytes"  cap of the searches' visited-set workspace (forces searches in several slabs of queries)
  *   "search_visited_global"   1: visited sets stay in the global workspace even where the search would keep them in LDS
+ *   "search_query_lists"      1: the plain and keyword searches look query terms up in the query's lists, not in LDS tables
  * Unknown names and negative values give AP_EINVAL.  Not thread-safe against running calls. */
 int ap_debug_set(const char *name, int64_t value);
 

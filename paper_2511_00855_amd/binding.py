@@ -105,7 +105,7 @@ def debug_set(name: str, value: int):
 
 
 DEBUG_NAMES = ("seed_sample_cols", "seed_buffer_cap", "seed_tau_ulps", "max_launch_threads", "search_workspace_bytes",
-               "search_visited_global")
+               "search_visited_global", "search_query_lists")
 
 
 def debug_reset():

@@ -28,6 +28,7 @@ extern "C" int ap_debug_set(const char *name, int64_t value) {
         {"seed_sample_cols", &g_ap_debug.seed_sample_cols},       {"seed_buffer_cap", &g_ap_debug.seed_buffer_cap},
         {"seed_tau_ulps", &g_ap_debug.seed_tau_ulps},             {"max_launch_threads", &g_ap_debug.max_launch_threads},
         {"search_workspace_bytes", &g_ap_debug.search_workspace_bytes}, {"search_visited_global", &g_ap_debug.search_visited_global},
+        {"search_query_lists", &g_ap_debug.search_query_lists},
     };
     for (auto &t : table)
         if (strcmp(name, t.name) == 0) { *t.field = value; return AP_OK; }

@@ -122,6 +122,7 @@ struct ApDebug {
     int64_t seed_tau_ulps = 0;           // raises every row's threshold by this many ulps (forces the short-row fallback)
     int64_t max_launch_threads = 0;      // a multiple of 1024: launches that grow with the corpus are cut into slices of this many threads
     int64_t search_visited_global = 0;   // 1: the searches' visited sets stay in global memory even where they would fit LDS
+    int64_t search_query_lists = 0;      // 1: the searches look the query's terms up in its lists (the path of queries too long for the LDS tables)
     int64_t search_workspace_bytes = 0;  // cap of the search's visited-set workspace (forces searches in several slabs of queries)
 };
 extern ApDebug g_ap_debug;

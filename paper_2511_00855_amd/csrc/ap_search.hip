@@ -48,6 +48,7 @@ struct ApSearchArgs {
     int32_t vis_lds;    // the visited sets live in LDS (words words after the kernel's other arrays), not in `visited`
     int32_t nxtw;       // words of the scratch that parks positions when more keys enter at once than the workgroup has threads (else 0)
     int32_t q0;         // the launch covers queries q0 .. q0 + gridDim.x (a slab of the batch)
+    int32_t no_tables;  // debug: search the query's lists where they lie even when they fit the LDS tables
     uint32_t *visited;  // one bitset per query of the slab
     size_t words;       // visited words per query
     int32_t *out_ids;
@@ -292,7 +293,7 @@ void k_search(ApSearchArgs g) {
     // Ordinary queries (lists of at most 64 / 32 entries): wave 0 builds the two bucketed tables; if no multiplier
     // fits a list (or a list is longer), the lists are searched where they lie.  Queries that are documents get
     // open-addressing tables four times their length.
-    bool use_tab = a.sp_n <= (1 << SPB) / 4 && a.tx_n <= (1 << TXB) / 4;   // uniform
+    bool use_tab = !g.no_tables && a.sp_n <= (1 << SPB) / 4 && a.tx_n <= (1 << TXB) / 4;   // uniform
     uint32_t msp = 0, mtx = 0;
     if (!BIG) {
         if (use_tab && wave == 0) {
@@ -832,6 +833,7 @@ static int ap_search_launch(const ap_index *ix, const ApSearchWs &ws, const ApVe
     for (int32_t q0 = 0; q0 < nq; q0 += ws.slab) {
         const int32_t qn = std::min(ws.slab, nq - q0);
         g.q0 = q0;
+        g.no_tables = g_ap_debug.search_query_lists != 0;
         // every slab starts from empty visited sets (a fill kernel, not a memset: callers may capture the stream)
         if (!g.vis_lds) AP_TRY(ap_fill_u32(ws.visited, g.words * (size_t)qn, 0u, st));
         if (q0 == 0 && ws.ev0) AP_CHECK_HIP(hipEventRecord(ws.ev0, st));

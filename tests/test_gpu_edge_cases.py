@@ -305,3 +305,30 @@ def test_random_search_settings_replayed():
                 assert np.array_equal(sc[qi], os_), (degree, qi, k, beam, width, iters)
                 assert counts[qi, 0] == nv, (degree, qi, k, beam, width, iters, counts[qi], nv)
         ix.close()
+
+
+def test_query_tables_and_query_lists_give_the_same_bits(debug_knobs):
+    """The search looks a candidate's terms up in LDS tables built from the query's lists, and in the lists themselves
+    when a query is too long for the tables (or no hash multiplier fits it).  The debug setting forces the second way
+    on ordinary queries: answers, scores and counters must be the same bits, in all three workgroup sizes and in the
+    keyword search."""
+    from paper_2511_00855_amd.synth import make_keywords
+    w = make_workload("tiny", seed=77, n=14000, nq=6, dim=48)
+    docs = B.DeviceVecs(w.docs); qs = B.DeviceVecs(w.queries)
+    ix = B.Index.build(docs, B.build_params(32, knn_k=64, nd_rounds=1, nd_sample=8, n_entry=16))
+    wq = np.random.default_rng(3).uniform(0.1, 1.0, (qs.n, 3)).astype(np.float32)
+    kw = make_keywords(w.queries, seed=5, max_terms=2, stride=2)
+    got = {}
+    for lists in (0, 1):
+        debug_knobs("search_query_lists", lists)
+        for (k, L, width) in ((10, 64, 1), (10, 700, 3), (5, 5000, 4), (10, 12000, 16)):
+            ids, sc = [t.cpu().numpy() for t in ix.search_batch(qs, k, L, wq, 0, width)]
+            got[(lists, "plain", L)] = (ids, sc, ix.search_stats(qs.n)[0].cpu().numpy())
+        ids, sc = [t.cpu().numpy() for t in ix.search_batch_keywords(qs, 10, 300, kw, wq)]
+        got[(lists, "kw", 300)] = (ids, sc, ix.search_stats(qs.n)[0].cpu().numpy())
+    for (lists, kind, L), v in got.items():
+        if lists == 0:
+            o = got[(1, kind, L)]
+            for x, y in zip(v, o):
+                assert np.array_equal(x, y), (kind, L)
+    ix.close()
