@@ -115,6 +115,38 @@ def keyword_leg(args, w, ix, qs, wq, k, chosen):
     return dict(required_terms="1-2 of each query's own text tokens, any-match", sampled_queries=len(sample), sweep=out)
 
 
+def entities_leg(args, w, ix, qs, wq, k):
+    """Search with entities (Sections 3.4 and 4.2.3) on a synthetic entity graph over this corpus (every document
+    mentions 1-3 entities, about four relations per entity, every query names 1-2 entities of one document): what
+    the augmentation costs against the plain search of the same index at the same beam, and how often it changes the
+    answer.  The paper applies the knowledge graph to small shards; so should --n."""
+    import numpy as np
+    import torch
+    from paper_2511_00855_amd.synth import make_entity_graph
+    nq = qs.n
+    kgs = make_entity_graph(w.docs.n, nq, seed=5)
+    ix.set_knowledge_graph(kgs, le_cap=16)
+    out = []
+    for beam in (64, 128, 512):
+        row = dict(beam=beam)
+        ans = {}
+        for name, fn in (("plain", lambda: ix.search_batch(qs, k, beam, wq)),
+                         ("entities", lambda: ix.search_batch_entities(qs, k, beam, kgs.q_ent, 0.5, 2, wq))):
+            fn(); torch.cuda.synchronize()
+            t1 = time.time()
+            ids, _ = fn()
+            torch.cuda.synchronize()
+            row[name + "_qps"] = round(nq / (time.time() - t1), 1)
+            row[name + "_kernel_ms"] = round(ix.search_kernel_ms(), 3)
+            ans[name] = ids.cpu().numpy()
+        row["qps_ratio"] = round(row["entities_qps"] / row["plain_qps"], 3)
+        row["queries_whose_answer_changed"] = round(float((ans["plain"] != ans["entities"]).any(axis=1).mean()), 4)
+        out.append(row)
+        log(f"[bench] entities beam {beam}: plain {row['plain_qps']:,.0f} qps, with entities {row['entities_qps']:,.0f} qps "
+            f"({row['qps_ratio']:.2f}x), answers changed for {100 * row['queries_whose_answer_changed']:.1f}% of the queries")
+    return dict(entity_graph=f"{kgs.n_ent} entities, {len(kgs.doc_ent)} mentions, {len(kgs.kg_idx) // 2} relations; reward 0.5, 2 hops", sweep=out)
+
+
 WEIGHT_SETTINGS = ((1.0, 0.0, 0.0), (0.0, 1.0, 0.0), (0.0, 0.0, 1.0), (0.5, 0.5, 0.0), (0.34, 0.33, 0.33))
 
 
@@ -374,6 +406,8 @@ def run_workload(args, name, *, n, nq, steps, warmup, sweep_text, cpu_seconds, g
             res["insertion"] = insert_leg(args, w, bp, docs, qs, wq, k, gt, sweep, build_s, bf16)
         elif leg == "weights":
             res["dynamic_fusion"] = weights_leg(args, ix, qs, k)
+        elif leg == "entities":
+            res["entity_search"] = entities_leg(args, w, ix, qs, wq, k)
 
     # ---- CPU baseline: the oracle as it stands, one thread, bounded samples of the same work
     if cpu_seconds > 0:
@@ -455,6 +489,8 @@ def main():
     ap.add_argument("--keywords", action="store_true",
                     help="also measure the keyword-constrained search (1-2 required terms per query, with and "
                          "without keyword edges) and add a keyword_search object to the line")
+    ap.add_argument("--entities", action="store_true",
+                    help="also time the search with entities (Section 4.2.3) on a synthetic entity graph over the corpus")
     ap.add_argument("--no-cfg2", action="store_true", help="skip the brief config-2 leg that precedes a larger headline workload")
     ap.add_argument("--graph-nodes", type=int, default=500, help="nodes sampled for the graph-quality figures (0 = skip)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -487,7 +523,8 @@ def main():
     log(f"[bench] streaming copy of 1 GiB: {copy_gbs:,.0f} GB/s (read + write)")
     del a, b
 
-    legs = [x for x, on in (("keywords", args.keywords), ("insert", args.insert > 0), ("weights", args.weight_sweep)) if on]
+    legs = [x for x, on in (("keywords", args.keywords), ("insert", args.insert > 0), ("weights", args.weight_sweep),
+                                ("entities", args.entities)) if on]
     side = None
     if args.workload in ("cfg3", "cfg5") and not args.no_cfg2 and not args.beam:
         # config 2 first, briefly: its own sweep to the recall target and a short timed run
@@ -523,7 +560,7 @@ def main():
         "dtype": "bf16-storage/f32-accumulate" if main_res["bf16"] else "f32", "data": "synthetic",
     }
     line.update({x: y for x, y in m.items() if x not in ("value", "ms_per_step")})
-    for extra in ("keyword_search", "insertion", "dynamic_fusion"):
+    for extra in ("keyword_search", "insertion", "dynamic_fusion", "entity_search"):
         if extra in main_res:
             line[extra] = main_res[extra]
     if side is not None:

@@ -237,12 +237,12 @@ __global__ __launch_bounds__(256) void k_search_kg(ApKgArgs g) {
     extern __shared__ __attribute__((aligned(16))) uint64_t smem64[];
     uint64_t *cur = smem64;                                  // the pool, best first
     uint64_t *newk = cur + g.L;                              // keys of this iteration's candidates
-    uint64_t *qtab = newk + g.cmax;                          // the query's look-up tables
-    uint4 *s_meta = reinterpret_cast<uint4 *>(qtab + (1 << AP_KG_SPB) + (1 << AP_KG_TXB) + ((g.L + g.cmax) & 1));
+    uint64_t *qtab = newk + g.cmax + ((g.L + g.cmax) & 1);   // the query's look-up tables (16-byte aligned: read two slots at a time)
+    uint4 *s_meta = reinterpret_cast<uint4 *>(qtab + (1 << AP_KG_SPB) + (1 << AP_KG_TXB));
     uint32_t *cura = reinterpret_cast<uint32_t *>(s_meta + g.cmax);   // annotations of the pool entries
     uint32_t *canda = cura + g.L;                                      // annotations of the candidates
     int32_t *cand = reinterpret_cast<int32_t *>(canda + g.cmax);
-    __shared__ int32_t s_cnt, s_par, s_pann;
+    __shared__ int32_t s_cnt, s_par, s_pann, s_seed[2], s_len, s_skip;
     const int64_t q = (int64_t)g.q0 + blockIdx.x;
     const int lane = threadIdx.x & 63, wave = ap_wave_id();
     ApLists a;
@@ -251,19 +251,33 @@ __global__ __launch_bounds__(256) void k_search_kg(ApKgArgs g) {
         a.sp_n = (int32_t)(g.Q.sp_indptr[q + 1] - sb); a.tx_n = (int32_t)(g.Q.tx_indptr[q + 1] - tb);
         a.sp_idx = g.Q.sp_idx + sb; a.sp_val = g.Q.sp_val + sb; a.tx_idx = g.Q.tx_idx + tb; a.tx_val = g.Q.tx_val + tb;
     }
-    const bool use_tab = a.sp_n <= (1 << AP_KG_SPB) / 4 && a.tx_n <= (1 << AP_KG_TXB) / 4;   // uniform
+    // the query's lists as bucket tables with a hash multiplier of their own, as in the plain search; lists that are
+    // too long for them, or that no multiplier fits, are searched where they lie
+    bool use_tab = a.sp_n <= (1 << AP_KG_SPB) / 4 && a.tx_n <= (1 << AP_KG_TXB) / 4;   // uniform
+    uint32_t msp = 0, mtx = 0;
+    if (use_tab && wave == 0) {
+        const int32_t s0 = ap_bucket_build(a.sp_idx, a.sp_val, a.sp_n, qtab, AP_KG_SPB);
+        const int32_t s1 = ap_bucket_build(a.tx_idx, a.tx_val, a.tx_n, qtab + (1 << AP_KG_SPB), AP_KG_TXB);
+        if (lane == 0) { s_seed[0] = s0; s_seed[1] = s1; }
+    }
+    __syncthreads();
     if (use_tab) {
-        for (int i = threadIdx.x; i < (1 << AP_KG_SPB) + (1 << AP_KG_TXB); i += blockDim.x) qtab[i] = 0xffffffffull;
-        __syncthreads();
-        const int t = threadIdx.x;
-        if (t < a.sp_n) ap_table_put(qtab, 1 << AP_KG_SPB, AP_KG_SPB, a.sp_idx[t], __float_as_int(a.sp_val[t]));
-        else if (t < a.sp_n + a.tx_n)
-            ap_table_put(qtab + (1 << AP_KG_SPB), 1 << AP_KG_TXB, AP_KG_TXB, a.tx_idx[t - a.sp_n], __float_as_int(a.tx_val[t - a.sp_n]));
+        const int32_t seed0 = ap_uniform_i32(s_seed[0]), seed1 = ap_uniform_i32(s_seed[1]);
+        use_tab = seed0 >= 0 && seed1 >= 0;
+        if (use_tab) { msp = ap_seed_mult(seed0); mtx = ap_seed_mult(seed1); }
     }
     float qa[NV * ApDense<DT>::EPC];
     ap_load_aside<DT, NV, AP_F32>(g.Q.dense, q, g.D.dim, qa);
     const float wd = g.w[q * g.w_stride + 0], ws = g.w[q * g.w_stride + 1], wf = g.w[q * g.w_stride + 2];
+    float qnorm;
+    {
+        float p = 0.f;
+#pragma unroll
+        for (int i = 0; i < NV * ApDense<DT>::EPC; i++) p = fmaf(qa[i], qa[i], p);
+        qnorm = sqrtf(ap_wave_sum(p));
+    }
     uint32_t *vis = g.visited + (size_t)blockIdx.x * g.words;
+    if (threadIdx.x == 0) { s_len = 0; s_skip = 0; }
     if (threadIdx.x == 0) {
         // the documents that mention the query's entities, in the order of the entities then ascending id, at most E
         int32_t c = 0;
@@ -295,11 +309,16 @@ __global__ __launch_bounds__(256) void k_search_kg(ApKgArgs g) {
     }
     int32_t len = 0, it = 0, nscored = 0;   // len is kept by wave 0, the only one that touches the pool
     int32_t fu = 0;                          // (wave 0) every pool entry before this position has been expanded
+    int32_t nskipped = 0;
     for (;;) {
         const int32_t c = s_cnt;
         nscored += c;
         for (int32_t i = threadIdx.x; i < c; i += blockDim.x) s_meta[i] = g.meta[cand[i]];
         __syncthreads();
+        // as in the plain search: when the pool is full and even the largest dense part the norms allow (plus the
+        // candidate's reward) could not lift a candidate past the pool's last entry, its dense row is not read
+        const bool pool_full = s_len == g.L;
+        const float worst_score = pool_full ? ap_key_score(cur[g.L - 1]) : 0.f;
         for (int32_t i = wave; i < c; i += 4) {
             const uint4 m = s_meta[i];
             const uint2 *r = g.rec + ap_uniform_u32(m.x);
@@ -310,14 +329,25 @@ __global__ __launch_bounds__(256) void k_search_kg(ApKgArgs g) {
             float sv[2], tv[1], ss, sf;
             ap_rec_load<2, 1>(r, spn, txn, si, sv, ti, tv);
             if (use_tab)
-                ap_rec_reduce_tab<2, 1, AP_KG_SPB, AP_KG_TXB>(r, (const AP_LDS uint64_t *)qtab, (const AP_LDS uint64_t *)(qtab + (1 << AP_KG_SPB)),
-                                                              spn, txn, si, sv, ti, tv, ss, sf);
+                ap_rec_reduce_bucket<2, 1, AP_KG_SPB, AP_KG_TXB>(r, (const AP_LDS uint64_t *)qtab, (const AP_LDS uint64_t *)(qtab + (1 << AP_KG_SPB)),
+                                                                 msp, mtx, spn, txn, si, sv, ti, tv, ss, sf);
             else
                 ap_rec_reduce_lists<2, 1>(r, a, spn, txn, si, sv, ti, tv, ss, sf);
+            const uint32_t an = canda[i];
+            const float reward = (an != 0u && (an & 0xffu) != 0u) ? g.w_k / (float)(an & 0xffu) : 0.f;   // the reward of a tie: w_k / hop
+            {
+                const float dmax = fabsf(wd) * qnorm * __uint_as_float(ap_uniform_u32(m.z)) * 1.0001f;
+                const float part = fmaf(wf, sf, ws * ss);
+                const float ub = part + dmax + fabsf(reward) + 1e-5f * (fabsf(ws * ss) + fabsf(wf * sf) + dmax + fabsf(reward));
+                if (pool_full && ub < worst_score) {
+                    if (lane == 0) newk[i] = (uint64_t)(uint32_t)(i + 1);   // ranks after every real key (score bits 0)
+                    nskipped++;
+                    continue;
+                }
+            }
             const float sd = ap_dense_dot<DT, NV>(g.D, qa, v);
             float s = ap_fuse(wd, ws, wf, sd, ss, sf);
-            const uint32_t an = canda[i];
-            if (an != 0u && (an & 0xffu) != 0u) s = s + g.w_k / (float)(an & 0xffu);   // the reward of a tie: w_k / hop
+            if (an != 0u && (an & 0xffu) != 0u) s = s + reward;
             if (lane == 0) newk[i] = ap_make_key(s, v, 1u);
         }
         __syncthreads();
@@ -363,6 +393,7 @@ __global__ __launch_bounds__(256) void k_search_kg(ApKgArgs g) {
                 if (found >= 0) { s_par = ap_key_id(cur[found]); s_pann = (int32_t)cura[found]; cur[found] &= ~1ull; }
                 else s_par = -1;
                 s_cnt = 0;
+                s_len = len;
             }
         }
         __syncthreads();
@@ -393,7 +424,9 @@ __global__ __launch_bounds__(256) void k_search_kg(ApKgArgs g) {
         __syncthreads();
         it++;
     }
-    if (threadIdx.x == 0) { g.counts[q * 3] = nscored; g.counts[q * 3 + 1] = it; g.counts[q * 3 + 2] = 0; }
+    if (lane == 0) atomicAdd(&s_skip, nskipped);
+    __syncthreads();
+    if (threadIdx.x == 0) { g.counts[q * 3] = nscored; g.counts[q * 3 + 1] = it; g.counts[q * 3 + 2] = s_skip; }
     // the best k pool entries; mark-deleted documents were searched through like any other and are left out here
     if (wave == 0) {
         int32_t o = 0;
