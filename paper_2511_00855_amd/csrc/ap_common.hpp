@@ -349,24 +349,36 @@ __device__ __forceinline__ float ap_bucket_get(TP tab, uint32_t mult, int bits, 
     return __uint_as_float(b.x == (uint32_t)t ? b.y : (b.z == (uint32_t)t ? b.w : 0u));
 }
 #define AP_SEED_TRIES 32
-// One wave builds the table of the n <= 64 entries (idx, val): it tries multipliers until no bucket gets a third
-// term, clears the table and stores the entries.  Every lane returns the seed, -1 if none of the first
-// AP_SEED_TRIES does it (the table then holds nothing usable).
+// One wave builds the table of the n <= 64 CH entries (idx, val), lane l holding entries l, l + 64, ...: it tries
+// multipliers until no bucket gets a third term, clears the table and stores the entries.  Every lane returns the
+// seed, -1 if none of the first AP_SEED_TRIES does it (the table then holds nothing usable).
+template <int CH = 1>
 __device__ __forceinline__ int32_t ap_bucket_build(const int32_t *idx, const float *val, int32_t n, uint64_t *tab, int bits) {
     const int lane = threadIdx.x & 63;
     const int32_t nb = 1 << (bits - 1);
-    const int32_t term = lane < n ? idx[lane] : -1;
+    int32_t term[CH];
+#pragma unroll
+    for (int c = 0; c < CH; c++) term[c] = c * 64 + lane < n ? idx[c * 64 + lane] : -1;
     int32_t *cnt = reinterpret_cast<int32_t *>(tab);   // bucket counters while searching (the table has 2^(bits+1) words)
     for (int32_t s = 0; s < AP_SEED_TRIES; s++) {
         for (int32_t i = lane; i < nb; i += 64) cnt[i] = 0;
         ap_wave_sync();
-        const uint32_t h = ap_term_hash_m(term, ap_seed_mult(s), bits - 1);
-        const int32_t place = lane < n ? atomicAdd(&cnt[h], 1) : 0;
+        uint32_t h[CH];
+        int32_t place[CH];
+        bool bad = false;
+#pragma unroll
+        for (int c = 0; c < CH; c++) {
+            h[c] = ap_term_hash_m(term[c], ap_seed_mult(s), bits - 1);
+            place[c] = c * 64 + lane < n ? atomicAdd(&cnt[h[c]], 1) : 0;
+            bad = bad || place[c] >= 2;
+        }
         ap_wave_sync();
-        if (__ballot(place >= 2) == 0ull) {
+        if (__ballot(bad) == 0ull) {
             for (int32_t i = lane; i < 2 * nb; i += 64) tab[i] = 0xffffffffull;
             ap_wave_sync();
-            if (lane < n) tab[2 * h + place] = ((uint64_t)__float_as_uint(val[lane]) << 32) | (uint32_t)term;
+#pragma unroll
+            for (int c = 0; c < CH; c++)
+                if (c * 64 + lane < n) tab[2 * h[c] + place[c]] = ((uint64_t)__float_as_uint(val[c * 64 + lane]) << 32) | (uint32_t)term[c];
             return s;
         }
     }

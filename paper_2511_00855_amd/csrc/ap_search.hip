@@ -97,7 +97,8 @@ __device__ __forceinline__ int32_t ap_rank_in(const uint64_t *keys, int32_t n, u
 // they are searched where they lie in global memory.
 // Returns the number of candidates whose dense row was skipped (wave-uniform).
 // Sizes of the query's two look-up tables (at most a quarter full).  Ordinary queries: 256 + 128 slots (lists up to
-// 64 / 32 entries).  Queries that are documents (insertion): 1024 + 512 slots (lists up to 256 / 128 entries).
+// 64 / 32 entries).  Queries that are documents (insertion): 1024 + 512 slots (lists up to 256 / 128 entries).  Both are
+// bucketed: two slots a bucket, a hash multiplier per table under which no bucket needs a third.
 template <bool BIG> struct ApQTab {
     static constexpr int SPB = BIG ? 10 : 8;
     static constexpr int TXB = BIG ? 9 : 7;
@@ -150,14 +151,10 @@ __device__ __forceinline__ int32_t ap_score_candidates(const ApVecs &D, const ui
             int32_t si[2], ti[1];
             float sv[2], tv[1];
             ap_rec_decode<2, 1>(xs[gi], xt[gi], spn[gi], txn[gi], si, sv, ti, tv);
-            if (TAB && !BIG)   // ordinary queries: bucketed tables, one read per look-up
+            if (TAB)   // bucketed tables, one read per look-up
                 ap_rec_reduce_bucket<2, 1, ApQTab<BIG>::SPB, ApQTab<BIG>::TXB>(r[gi], (const AP_LDS uint64_t *)qtab,
                                                                                (const AP_LDS uint64_t *)(qtab + (1 << ApQTab<BIG>::SPB)),
                                                                                msp, mtx, spn[gi], txn[gi], si, sv, ti, tv, ss[gi], sf[gi]);
-            else if (TAB)      // queries that are documents (insertion): open-addressing tables
-                ap_rec_reduce_tab<2, 1, ApQTab<BIG>::SPB, ApQTab<BIG>::TXB>(r[gi], (const AP_LDS uint64_t *)qtab,
-                                                                            (const AP_LDS uint64_t *)(qtab + (1 << ApQTab<BIG>::SPB)),
-                                                                            spn[gi], txn[gi], si, sv, ti, tv, ss[gi], sf[gi]);
             else
                 ap_rec_reduce_lists<2, 1>(r[gi], a, spn[gi], txn[gi], si, sv, ti, tv, ss[gi], sf[gi]);
             // upper bound of the fused score, with slack far above fp32 rounding
@@ -290,28 +287,20 @@ void k_search(ApSearchArgs g) {
         a.sp_n = (int32_t)(g.Q.sp_indptr[q + 1] - sb); a.tx_n = (int32_t)(g.Q.tx_indptr[q + 1] - tb);
         a.sp_idx = g.Q.sp_idx + sb; a.sp_val = g.Q.sp_val + sb; a.tx_idx = g.Q.tx_idx + tb; a.tx_val = g.Q.tx_val + tb;
     }
-    // Ordinary queries (lists of at most 64 / 32 entries): wave 0 builds the two bucketed tables; if no multiplier
-    // fits a list (or a list is longer), the lists are searched where they lie.  Queries that are documents get
-    // open-addressing tables four times their length.
+    // Wave 0 builds the two bucketed tables (lists of at most 64 / 32 entries; 256 / 128 for queries that are documents);
+    // if no multiplier fits a list, or a list is longer, the lists are searched where they lie.
     bool use_tab = !g.no_tables && a.sp_n <= (1 << SPB) / 4 && a.tx_n <= (1 << TXB) / 4;   // uniform
     uint32_t msp = 0, mtx = 0;
-    if (!BIG) {
-        if (use_tab && wave == 0) {
-            const int32_t s0 = ap_bucket_build(a.sp_idx, a.sp_val, a.sp_n, qtab, SPB);
-            const int32_t s1 = ap_bucket_build(a.tx_idx, a.tx_val, a.tx_n, qtab + (1 << SPB), TXB);
-            if (lane == 0) { s_seed[0] = s0; s_seed[1] = s1; }
-        }
-        __syncthreads();
+    if (use_tab && wave == 0) {
+        const int32_t s0 = ap_bucket_build<BIG ? 4 : 1>(a.sp_idx, a.sp_val, a.sp_n, qtab, SPB);
+        const int32_t s1 = ap_bucket_build<BIG ? 2 : 1>(a.tx_idx, a.tx_val, a.tx_n, qtab + (1 << SPB), TXB);
+        if (lane == 0) { s_seed[0] = s0; s_seed[1] = s1; }
+    }
+    __syncthreads();
+    if (use_tab) {
         const int32_t seed0 = ap_uniform_i32(s_seed[0]), seed1 = ap_uniform_i32(s_seed[1]);
-        use_tab = use_tab && seed0 >= 0 && seed1 >= 0;
+        use_tab = seed0 >= 0 && seed1 >= 0;
         if (use_tab) { msp = ap_seed_mult(seed0); mtx = ap_seed_mult(seed1); }
-    } else if (use_tab) {
-        for (int i = threadIdx.x; i < ApQTab<BIG>::SLOTS; i += blockDim.x) qtab[i] = 0xffffffffull;
-        __syncthreads();
-        for (int t = threadIdx.x; t < a.sp_n + a.tx_n; t += blockDim.x) {
-            if (t < a.sp_n) ap_table_put(qtab, 1 << SPB, SPB, a.sp_idx[t], __float_as_int(a.sp_val[t]));
-            else ap_table_put(qtab + (1 << SPB), 1 << TXB, TXB, a.tx_idx[t - a.sp_n], __float_as_int(a.tx_val[t - a.sp_n]));
-        }
     }
     float qa[NV * ApDense<DT>::EPC];
     ap_load_aside<DT, NV, AP_F32>(g.Q.dense, q, g.D.dim, qa);
