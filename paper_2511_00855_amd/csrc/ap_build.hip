@@ -427,8 +427,8 @@ __global__ __launch_bounds__(512) void k_refine(ApVecs D, const uint2 *__restric
     __shared__ float l_sp_val[AP_A_CAP], l_tx_val[AP_A_CAP];
     __shared__ uint64_t oldk[32];
     __shared__ uint64_t red[8];
-    __shared__ uint64_t qtab[(1 << AP_RT_SPB) + (1 << AP_RT_TXB)];
-    __shared__ int32_t s_cnt, s_nold;
+    __shared__ __attribute__((aligned(16))) uint64_t qtab[(1 << AP_RT_SPB) + (1 << AP_RT_TXB)];
+    __shared__ int32_t s_cnt, s_nold, s_seed[2];
     const int64_t x = x0 + blockIdx.x;   // the launch covers nodes x0 .. x0 + gridDim.x of the nn
     const int64_t u = node_ids ? (int64_t)node_ids[x] : x;
     const int lane = threadIdx.x & 63, wave = ap_wave_id();
@@ -436,16 +436,22 @@ __global__ __launch_bounds__(512) void k_refine(ApVecs D, const uint2 *__restric
     float qa[NV * ApDense<DT>::EPC];
     ap_load_aside<DT, NV, DT>(D.dense, u, D.dim, qa);
     for (int i = threadIdx.x; i < AP_HT; i += blockDim.x) ht[i] = -1;
-    // the node's own lists as look-up tables (the usual case); longer lists are searched where they lie
-    const bool use_tab = a.sp_n <= (1 << AP_RT_SPB) / 4 && a.tx_n <= (1 << AP_RT_TXB) / 4;   // uniform
-    if (use_tab) for (int i = threadIdx.x; i < (1 << AP_RT_SPB) + (1 << AP_RT_TXB); i += blockDim.x) qtab[i] = 0xffffffffull;
+    // the node's own lists as bucket tables with a hash multiplier of their own (the usual case: one 16-byte read per
+    // look-up, as in the search); lists that are longer, or that no multiplier fits, are searched where they lie
+    bool use_tab = a.sp_n <= (1 << AP_RT_SPB) / 4 && a.tx_n <= (1 << AP_RT_TXB) / 4;   // uniform
+    uint32_t msp = 0, mtx = 0;
     if (threadIdx.x == 0) s_cnt = 0;
     __syncthreads();
+    if (use_tab && wave == 0) {
+        const int32_t s0 = ap_bucket_build<4>(a.sp_idx, a.sp_val, a.sp_n, qtab, AP_RT_SPB);
+        const int32_t s1 = ap_bucket_build<2>(a.tx_idx, a.tx_val, a.tx_n, qtab + (1 << AP_RT_SPB), AP_RT_TXB);
+        if (lane == 0) { s_seed[0] = s0; s_seed[1] = s1; }
+    }
+    __syncthreads();
     if (use_tab) {
-        for (int t = threadIdx.x; t < a.sp_n + a.tx_n; t += blockDim.x) {
-            if (t < a.sp_n) ap_table_put(qtab, 1 << AP_RT_SPB, AP_RT_SPB, a.sp_idx[t], __float_as_int(a.sp_val[t]));
-            else ap_table_put(qtab + (1 << AP_RT_SPB), 1 << AP_RT_TXB, AP_RT_TXB, a.tx_idx[t - a.sp_n], __float_as_int(a.tx_val[t - a.sp_n]));
-        }
+        const int32_t seed0 = ap_uniform_i32(s_seed[0]), seed1 = ap_uniform_i32(s_seed[1]);
+        use_tab = seed0 >= 0 && seed1 >= 0;
+        if (use_tab) { msp = ap_seed_mult(seed0); mtx = ap_seed_mult(seed1); }
     }
     // candidates: own list, and the first S neighbours of the first S neighbours
     const int32_t sl = S < K ? S : K;
@@ -475,8 +481,8 @@ __global__ __launch_bounds__(512) void k_refine(ApVecs D, const uint2 *__restric
             float sv[2], tv[1];
             ap_rec_load<2, 1>(r, spn, txn, si, sv, ti, tv);
             sd = ap_dense_dot<DT, NV>(D, qa, v);
-            ap_rec_reduce_tab<2, 1, AP_RT_SPB, AP_RT_TXB>(r, (const AP_LDS uint64_t *)qtab, (const AP_LDS uint64_t *)(qtab + (1 << AP_RT_SPB)),
-                                                          spn, txn, si, sv, ti, tv, ss, sf);
+            ap_rec_reduce_bucket<2, 1, AP_RT_SPB, AP_RT_TXB>(r, (const AP_LDS uint64_t *)qtab, (const AP_LDS uint64_t *)(qtab + (1 << AP_RT_SPB)),
+                                                             msp, mtx, spn, txn, si, sv, ti, tv, ss, sf);
         } else {
             ap_hybrid_wave<DT, NV>(D, qa, a, v, sd, ss, sf);
         }
