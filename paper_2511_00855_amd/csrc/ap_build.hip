@@ -469,18 +469,28 @@ __global__ __launch_bounds__(512) void k_refine(ApVecs D, const uint2 *__restric
     __syncthreads();
     const int32_t cnt = ap_uniform_i32(s_cnt);
     if (threadIdx.x == 0 && n_sims) atomicAdd(n_sims, (unsigned long long)cnt);   // measurement: similarities of this node and round
+    // where each candidate's record lies and how long it is: fetched for all candidates at once, and parked in the space
+    // the candidates' component scores take later, so that the scoring loop starts its loads without a round trip of its own
+    if (use_tab) {
+        for (int32_t t = threadIdx.x; t < cnt; t += blockDim.x) {
+            const uint4 m = meta[cand[t]];
+            comp[0][t] = __uint_as_float(m.x); comp[1][t] = __uint_as_float(m.y);
+        }
+        __syncthreads();
+    }
     for (int32_t i = wave; i < cnt; i += (int32_t)(blockDim.x >> 6)) {
         const int32_t v = ap_uniform_i32(cand[i]);
         float sd, ss, sf;
         if (use_tab) {
-            const uint4 m = meta[v];
-            const uint2 *r = rec + ap_uniform_u32(m.x);
-            const int32_t spn = __builtin_amdgcn_readfirstlane((int32_t)(m.y & 0xffffu));
-            const int32_t txn = __builtin_amdgcn_readfirstlane((int32_t)(m.y >> 16));
+            uint4 raw[NV];
+            ap_dense_load_raw<DT, NV>(D, v, raw);   // the dense row is always needed here: its loads go first
+            const uint32_t mx = ap_uniform_u32(__float_as_uint(comp[0][i])), my = ap_uniform_u32(__float_as_uint(comp[1][i]));
+            const uint2 *r = rec + mx;
+            const int32_t spn = (int32_t)(my & 0xffffu), txn = (int32_t)(my >> 16);
             int32_t si[2], ti[1];
             float sv[2], tv[1];
             ap_rec_load<2, 1>(r, spn, txn, si, sv, ti, tv);
-            sd = ap_dense_dot<DT, NV>(D, qa, v);
+            sd = ap_dense_dot_raw<DT, NV>(D, qa, raw);
             ap_rec_reduce_bucket<2, 1, AP_RT_SPB, AP_RT_TXB>(r, (const AP_LDS uint64_t *)qtab, (const AP_LDS uint64_t *)(qtab + (1 << AP_RT_SPB)),
                                                              msp, mtx, spn, txn, si, sv, ti, tv, ss, sf);
         } else {
