@@ -395,20 +395,6 @@ __device__ __forceinline__ bool ap_ht_has(const int32_t *ht, int32_t v) {
     }
 }
 
-// Block-wide maximum of a 64-bit key; every thread gets the result.
-__device__ __forceinline__ uint64_t ap_block_max(uint64_t v, uint64_t *red /* 8 */) {
-    for (int o = 32; o > 0; o >>= 1) {
-        const uint64_t other = __shfl_xor(v, o, 64);
-        v = other > v ? other : v;
-    }
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
-    __syncthreads();
-    uint64_t b = red[0];
-    for (int i = 1; i < (int)(blockDim.x >> 6); i++) b = red[i] > b ? red[i] : b;
-    return b;
-}
-
 #define AP_RT_SPB 10   // look-up tables of the node's own lists: 1024 + 512 slots, at most a quarter full
 #define AP_RT_TXB 9
 template <int DT, int NV>
@@ -425,10 +411,9 @@ __global__ __launch_bounds__(512) void k_refine(ApVecs D, const uint2 *__restric
     __shared__ float comp[3][AP_MAXC];
     __shared__ int32_t l_sp_idx[AP_A_CAP], l_tx_idx[AP_A_CAP];
     __shared__ float l_sp_val[AP_A_CAP], l_tx_val[AP_A_CAP];
-    __shared__ uint64_t oldk[32];
-    __shared__ uint64_t red[8];
+    __shared__ uint64_t oldk[3][32];
     __shared__ __attribute__((aligned(16))) uint64_t qtab[(1 << AP_RT_SPB) + (1 << AP_RT_TXB)];
-    __shared__ int32_t s_cnt, s_nold, s_seed[2];
+    __shared__ int32_t s_cnt, s_seed[2];
     const int64_t x = x0 + blockIdx.x;   // the launch covers nodes x0 .. x0 + gridDim.x of the nn
     const int64_t u = node_ids ? (int64_t)node_ids[x] : x;
     const int lane = threadIdx.x & 63, wave = ap_wave_id();
@@ -510,28 +495,39 @@ __global__ __launch_bounds__(512) void k_refine(ApVecs D, const uint2 *__restric
         if (r < K) { out_ids[x * K + r] = ap_key_id(key); out_sc[x * K + r] = ap_key_score(key); }
     }
     for (int32_t t = cnt + threadIdx.x; t < K; t += blockDim.x) { out_ids[x * K + t] = -1; out_sc[x * K + t] = -INFINITY; }
-    // per-path lists: the best P by each single similarity among this round's
-    // candidates and the previous list (entries scored again this round excepted)
-    for (int p = 0; p < 3; p++) {
-        __syncthreads();
-        if (threadIdx.x == 0) s_nold = 0;
-        __syncthreads();
-        if (threadIdx.x < P) {
-            const int32_t id = sp_ids[((int64_t)p * D.n + u) * P + threadIdx.x];
-            if (id >= 0 && !ap_ht_has(ht, id))
-                oldk[atomicAdd(&s_nold, 1)] = ap_make_key(sp_sc[((int64_t)p * D.n + u) * P + threadIdx.x], id, 1u);
+    // per-path lists: the best P by each single similarity among this round's candidates and the previous list (entries
+    // scored again this round excepted).  One wave per path, on its own: every lane keeps its share of the keys in
+    // registers and the P best are drawn one after the other by wave-wide maxima (no block-wide pass, no barrier).
+    if (wave < 3) {
+        const int p = wave;
+        uint64_t ok = 0;
+        bool have = false;
+        if (lane < P) {
+            const int32_t id = sp_ids[((int64_t)p * D.n + u) * P + lane];
+            if (id >= 0 && !ap_ht_has(ht, id)) { have = true; ok = ap_make_key(sp_sc[((int64_t)p * D.n + u) * P + lane], id, 1u); }
         }
-        __syncthreads();
-        const int32_t nold = s_nold;
+        const uint64_t hm = __ballot(have);
+        const int32_t nold = (int32_t)__popcll(hm);
+        if (have) oldk[p][__popcll(hm & ((1ull << lane) - 1ull))] = ok;
+        ap_wave_sync();
+        constexpr int PER = (AP_MAXC + 32 + 63) / 64;
+        uint64_t mine[PER];
+#pragma unroll
+        for (int j = 0; j < PER; j++) {
+            const int32_t t = j * 64 + lane;
+            mine[j] = t < cnt ? ap_make_key(comp[p][t], cand[t], 1u) : (t < cnt + nold ? oldk[p][t - cnt] : 0ull);
+        }
         uint64_t prev = ~0ull;
         for (int32_t r = 0; r < P; r++) {
             uint64_t best = 0;
-            for (int32_t t = threadIdx.x; t < cnt + nold; t += blockDim.x) {
-                const uint64_t key = t < cnt ? ap_make_key(comp[p][t], cand[t], 1u) : oldk[t - cnt];
-                if (key < prev && key > best) best = key;
+#pragma unroll
+            for (int j = 0; j < PER; j++)
+                if (mine[j] < prev && mine[j] > best) best = mine[j];
+            for (int o = 32; o > 0; o >>= 1) {
+                const uint64_t other = __shfl_xor(best, o, 64);
+                best = other > best ? other : best;
             }
-            best = ap_block_max(best, red);
-            if (threadIdx.x == 0) {
+            if (lane == 0) {
                 out_sp_ids[((int64_t)p * nn + x) * P + r] = best ? ap_key_id(best) : -1;
                 out_sp_sc[((int64_t)p * nn + x) * P + r] = best ? ap_key_score(best) : -INFINITY;
             }
