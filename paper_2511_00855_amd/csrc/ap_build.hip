@@ -725,14 +725,14 @@ __device__ __forceinline__ bool ap_list_has(const int32_t *idx, int64_t beg, int
     return lo < end && idx[lo] == t;
 }
 
-// The same test on a list of n ascending ids in LDS.
-__device__ __forceinline__ bool ap_list_has_lds(const int32_t *idx, int32_t n, int32_t t) {
+// Where t stands in a list of n ascending ids in LDS, -1 if it is not there.
+__device__ __forceinline__ int32_t ap_list_find_lds(const int32_t *idx, int32_t n, int32_t t) {
     int32_t lo = 0, hi = n;
     while (lo < hi) {
         const int32_t mid = (lo + hi) >> 1;
         if (idx[mid] < t) lo = mid + 1; else hi = mid;
     }
-    return lo < n && idx[lo] == t;
+    return lo < n && idx[lo] == t ? lo : -1;
 }
 
 __global__ __launch_bounds__(256) void k_detour_prune(ApVecs D, const float *__restrict__ self_sim, int32_t K, int32_t R,
@@ -747,6 +747,10 @@ __global__ __launch_bounds__(256) void k_detour_prune(ApVecs D, const float *__r
     __shared__ float simA[256];
     __shared__ int32_t T[AP_T_CAP];
     __shared__ int32_t a_tx[AP_T_CAP];   // the node's own keywords: every step of the walk searches them
+    // Per keyword of the node, the members of SE that hold it (bit i = the i-th member; |SE| <= R <= 128).  "Some member
+    // holds every shared keyword" is then an AND over the shared keywords' words instead of a search of every
+    // member's list for every shared keyword.
+    __shared__ unsigned long long kwm[AP_T_CAP][2];
     const int64_t x = blockIdx.x;               // index inside the chunk (pm)
     const int64_t xo = xout0 + x;               // index in the output arrays
     const int64_t u = node_ids ? (int64_t)node_ids[x0 + x] : x0 + x;
@@ -755,7 +759,7 @@ __global__ __launch_bounds__(256) void k_detour_prune(ApVecs D, const float *__r
     if (t < K) { ids[t] = knn[u * K + t]; simA[t] = knn_sc[u * K + t]; flag[t] = 0; }
     const int64_t a_beg = D.tx_indptr[u], a_end = D.tx_indptr[u + 1];
     const bool a_in_lds = a_end - a_beg <= AP_T_CAP;   // uniform
-    if (a_in_lds) for (int32_t e = t; e < (int32_t)(a_end - a_beg); e += 256) a_tx[e] = D.tx_idx[a_beg + e];
+    if (a_in_lds) for (int32_t e = t; e < (int32_t)(a_end - a_beg); e += 256) { a_tx[e] = D.tx_idx[a_beg + e]; kwm[e][0] = 0ull; kwm[e][1] = 0ull; }
     __syncthreads();
     if (t < K) {
         int32_t c = 0;
@@ -795,22 +799,37 @@ __global__ __launch_bounds__(256) void k_detour_prune(ApVecs D, const float *__r
     for (int32_t r = 0; r < K; r++) {
         const int32_t pv = order[r], v = ids[pv];
         if (v < 0) break;   // holes are sorted last
-        if (nse == 0) { if (lane == 0) se_pos[0] = pv; nse = 1; ap_wave_sync(); continue; }
-        // T = K(A) n K(v)
+        if (nse == 0 && !a_in_lds) { if (lane == 0) se_pos[0] = pv; nse = 1; ap_wave_sync(); continue; }
+        // T = K(A) n K(v): the shared keywords themselves, or (node's list in LDS) their places in the node's list
         const int64_t vb = D.tx_indptr[v], ve = D.tx_indptr[v + 1];
         int32_t nt_all = 0;
         for (int64_t e0 = vb; e0 < ve; e0 += 64) {
             const int64_t e = e0 + lane;
             const int32_t term = e < ve ? D.tx_idx[e] : -1;
-            const bool in = term >= 0 && (a_in_lds ? ap_list_has_lds(a_tx, (int32_t)(ae - ab), term) : ap_list_has(D.tx_idx, ab, ae, term));
+            int32_t at = -1;
+            if (term >= 0) at = a_in_lds ? ap_list_find_lds(a_tx, (int32_t)(ae - ab), term) : (ap_list_has(D.tx_idx, ab, ae, term) ? 0 : -1);
+            const bool in = at >= 0;
             const uint64_t m = __ballot(in);
-            if (in) { const int32_t pos = nt_all + __popcll(m & ((1ull << lane) - 1ull)); if (pos < AP_T_CAP) T[pos] = term; }
+            if (in) { const int32_t pos = nt_all + __popcll(m & ((1ull << lane) - 1ull)); if (pos < AP_T_CAP) T[pos] = a_in_lds ? at : term; }
             nt_all += __popcll(m);
         }
         ap_wave_sync();
         const int32_t nt = nt_all < AP_T_CAP ? nt_all : AP_T_CAP;
+        if (nse == 0) {   // the first member of SE: its keywords are noted, nothing is tested
+            if (lane == 0) se_pos[0] = pv;
+            for (int32_t k = lane; k < nt; k += 64) kwm[T[k]][0] |= 1ull;
+            nse = 1;
+            ap_wave_sync();
+            continue;
+        }
         int32_t fl = 0;
-        if (nt_all > 0) {
+        if (nt_all > 0 && a_in_lds) {
+            // a member holds every shared keyword iff its bit survives the AND of those keywords' words
+            unsigned long long w0 = ~0ull, w1 = ~0ull;
+            for (int32_t k = lane; k < nt; k += 64) { w0 &= kwm[T[k]][0]; w1 &= kwm[T[k]][1]; }
+            for (int32_t o = 32; o > 0; o >>= 1) { w0 &= __shfl_xor(w0, o); w1 &= __shfl_xor(w1, o); }
+            fl = (w0 | w1) ? 0 : 1;
+        } else if (nt_all > 0) {
             // does some member of SE hold every shared keyword?
             bool covered = false;
             for (int32_t i = lane; i < nse; i += 64) {
@@ -839,6 +858,7 @@ __global__ __launch_bounds__(256) void k_detour_prune(ApVecs D, const float *__r
             if (ok) se_pos[nse] = pv;
             else if (fl && nke < ke_cap && o_ke) o_ke[xo * ke_cap + nke] = v;
         }
+        if (ok && a_in_lds) for (int32_t k = lane; k < nt; k += 64) kwm[T[k]][nse >> 6] |= 1ull << (nse & 63);
         if (ok) nse++;
         else if (fl && nke < ke_cap) nke++;
         ap_wave_sync();
