@@ -104,10 +104,12 @@ __global__ __launch_bounds__(WM * WN * 64) void k_seed_thresh_big(const void *de
     extern __shared__ __attribute__((aligned(16))) unsigned char big_lds[];
     __shared__ int32_t a_rows[AP_BIG], b_rows[AP_BIG];
     __shared__ __attribute__((aligned(16))) float s_tau[AP_BIG];
+    __shared__ int32_t s_cnt[AP_BIG], s_base[AP_BIG];   // RUN: the tile's candidates per row, and where each row's go in buf
     int64_t rt, ct;
     if (!ap_seed_tile(nrt, rt, ct)) return;
     const int64_t i0 = (rt0 + rt) * AP_BIG, j0 = (ct0 + ct) * AP_BIG;
     for (int32_t x = threadIdx.x; x < AP_BIG; x += blockDim.x) {
+        s_cnt[x] = 0;
         const int64_t r = i0 + x;
         a_rows[x] = r < nrows ? (node_ids ? node_ids[row0 + r] : (int32_t)(row0 + r)) : -1;
         s_tau[x] = r < nrows ? tau[r] : INFINITY;
@@ -119,11 +121,26 @@ __global__ __launch_bounds__(WM * WN * 64) void k_seed_thresh_big(const void *de
         const int32_t a_first = (int32_t)(row0 + i0), b_first = (int32_t)j0;
         ap_big_gemm_bf16<WM, WN, true>(dense, dim, a_rows, b_rows, a_first, b_first, reinterpret_cast<uint16_t *>(big_lds), acc);
         // A lane holds 4 consecutive rows x (FB x 32 columns apart) per 8-row group: the rows' thresholds come as one
-        // 16-byte LDS read, and an element costs a compare and a (rarely taken) branch.  Only a tile whose row and
-        // column runs overlap can pair a document with itself.
+        // 16-byte LDS read, and an element costs a compare and a (rarely taken) branch.  A candidate is not appended to
+        // its row's buffer on the spot (an atomic on the row's counter whose answer the store has to wait for, some
+        // forty times per wave): the wave notes it in its own part of the LDS the product has left (place = a running
+        // count + the lane's rank among the lanes that passed, no atomic), and afterwards the candidates are counted per
+        // row in LDS, every row with candidates takes its places in buf with ONE atomic for the whole tile, and the
+        // candidates are written out.  Only a tile whose row and column runs overlap can pair a document with itself.
         const bool diagonal = a_first < b_first + AP_BIG && b_first < a_first + AP_BIG;
         const int lane = threadIdx.x & 63, wave = ap_wave_id();
         const int wm = wave / WN, wn = wave % WN;
+        constexpr int W_CAP = AP_BIG_LDS_BYTES / (WM * WN) / 8;   // entries of a wave's part
+        uint64_t *stage = reinterpret_cast<uint64_t *>(big_lds) + wave * W_CAP;
+        // an entry: score bits | column in the tile << 32 | row in the tile << 40 | (later) place among the row's << 48
+        const uint32_t lane_pack = (uint32_t)(((wm * (AP_BIG / WM) + 4 * (lane >> 5)) << 8) | (wn * (AP_BIG / WN) + (lane & 31)));
+        auto append = [&](int i, int j, float v) {   // the direct way, for what a wave's part cannot hold
+            if (!(diagonal && a_first + i == b_first + j)) {
+                const int32_t pos = atomicAdd(&cnt[i0 + i], 1);
+                if (pos < cap) buf[(i0 + i) * (int64_t)cap + pos] = ap_make_key(v, b_first + j, 1u);
+            }
+        };
+        int32_t nw = 0;   // uniform: candidates of this wave so far
 #pragma unroll
         for (int a = 0; a < ApBig<WM, WN>::FA; a++)
 #pragma unroll
@@ -136,15 +153,39 @@ __global__ __launch_bounds__(WM * WN * 64) void k_seed_thresh_big(const void *de
 #pragma unroll
                     for (int rr = 0; rr < 4; rr++) {
                         const float v = acc[a][b][4 * q + rr];
-                        if (v >= tt[rr]) {
-                            const int i = ib + rr, j = wn * (AP_BIG / WN) + b * 32 + (lane & 31);
-                            if (!(diagonal && a_first + i == b_first + j)) {
-                                const int32_t pos = atomicAdd(&cnt[i0 + i], 1);
-                                if (pos < cap) buf[(i0 + i) * (int64_t)cap + pos] = ap_make_key(v, b_first + j, 1u);
+                        const bool pass = v >= tt[rr];
+                        const uint64_t m = __ballot(pass);
+                        if (m) {
+                            if (pass) {
+                                const int32_t slot = nw + (int32_t)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+                                const uint32_t pack = lane_pack + (uint32_t)(((a * 32 + 8 * q + rr) << 8) | (b * 32));
+                                if (slot < W_CAP) stage[slot] = ((uint64_t)pack << 32) | __float_as_uint(v);
+                                else append(ib + rr, wn * (AP_BIG / WN) + b * 32 + (lane & 31), v);
                             }
+                            nw += __popcll(m);
                         }
                     }
             }
+        const int32_t ns = nw < W_CAP ? nw : W_CAP;
+        for (int32_t p = lane; p < ns; p += 64) {
+            const uint64_t e = stage[p];
+            const int32_t j = (int32_t)(e >> 32) & 255, i = (int32_t)(e >> 40) & 255;
+            if (diagonal && a_first + i == b_first + j) { stage[p] = e | (0xffffull << 48); continue; }   // the document itself: dropped
+            stage[p] = e | ((uint64_t)atomicAdd(&s_cnt[i], 1) << 48);
+        }
+        __syncthreads();
+        for (int32_t x = threadIdx.x; x < AP_BIG; x += blockDim.x) {
+            const int32_t c = s_cnt[x];
+            s_base[x] = c ? atomicAdd(&cnt[i0 + x], c) : 0;
+        }
+        __syncthreads();
+        for (int32_t p = lane; p < ns; p += 64) {
+            const uint64_t e = stage[p];
+            const int32_t j = (int32_t)(e >> 32) & 255, i = (int32_t)(e >> 40) & 255, place = (int32_t)(e >> 48);
+            if (place == 0xffff) continue;
+            const int32_t pos = s_base[i] + place;
+            if (pos < cap) buf[(i0 + i) * (int64_t)cap + pos] = ap_make_key(__uint_as_float((uint32_t)e), b_first + j, 1u);
+        }
     } else {
         ap_big_gemm_bf16<WM, WN, false>(dense, dim, a_rows, b_rows, 0, 0, reinterpret_cast<uint16_t *>(big_lds), acc);
         ap_big_foreach<WM, WN>(acc, [&](int i, int j, float v) {
