@@ -54,6 +54,54 @@ __global__ __launch_bounds__(256) void k_seed_scores(const void *dense, int32_t 
     });
 }
 
+// Appending a tile's candidates to their rows' buffers.  A candidate is not appended on the spot (an atomic on the
+// row's counter whose answer the store has to wait for, at some forty of a lane's sixty-four elements): the wave notes
+// it in its own part of the LDS the product has left (place = a running count + the lane's rank among the lanes that
+// passed: no atomic, no wait); afterwards the candidates are counted per row in LDS, every row that has some takes its
+// places in buf with ONE atomic for the whole tile, and the candidates are written out.
+// An entry: score bits | column in the tile << 32 | row in the tile << 40 | (later) place among the row's << 48.
+// direct(i, j, v): the append on the spot, for what the wave's part (wcap entries) cannot hold.
+template <typename DIRECT>
+__device__ __forceinline__ void ap_seed_stage(bool pass, int i, int j, float v, uint64_t *stage, int32_t wcap, int32_t &nw, DIRECT direct) {
+    const uint64_t m = __ballot(pass);
+    if (m) {
+        if (pass) {
+            const int32_t slot = nw + (int32_t)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+            if (slot < wcap) stage[slot] = ((uint64_t)(uint32_t)((i << 8) | j) << 32) | __float_as_uint(v);
+            else direct(i, j, v);
+        }
+        nw += __popcll(m);
+    }
+}
+// Called by every thread of the workgroup once its wave has staged nw candidates.  drop(i, j): a candidate that is not
+// one after all (the document itself, a row or column past the end).  s_cnt[rows] must be zero on entry.
+template <typename DROP>
+__device__ __forceinline__ void ap_seed_flush(uint64_t *stage, int32_t wcap, int32_t nw, int32_t rows, int32_t *s_cnt, int32_t *s_base,
+                                              int32_t *__restrict__ cnt, unsigned long long *__restrict__ buf, int32_t cap, int64_t i0,
+                                              int32_t col0, DROP drop) {
+    const int lane = threadIdx.x & 63;
+    const int32_t ns = nw < wcap ? nw : wcap;
+    for (int32_t p = lane; p < ns; p += 64) {
+        const uint64_t e = stage[p];
+        const int32_t j = (int32_t)(e >> 32) & 255, i = (int32_t)(e >> 40) & 255;
+        if (drop(i, j)) { stage[p] = e | (0xffffull << 48); continue; }
+        stage[p] = e | ((uint64_t)atomicAdd(&s_cnt[i], 1) << 48);
+    }
+    __syncthreads();
+    for (int32_t x = threadIdx.x; x < rows; x += blockDim.x) {
+        const int32_t c = s_cnt[x];
+        s_base[x] = c ? atomicAdd(&cnt[i0 + x], c) : 0;
+    }
+    __syncthreads();
+    for (int32_t p = lane; p < ns; p += 64) {
+        const uint64_t e = stage[p];
+        const int32_t j = (int32_t)(e >> 32) & 255, i = (int32_t)(e >> 40) & 255, place = (int32_t)(e >> 48);
+        if (place == 0xffff) continue;
+        const int32_t pos = s_base[i] + place;
+        if (pos < cap) buf[(i0 + i) * (int64_t)cap + pos] = ap_make_key(__uint_as_float((uint32_t)e), col0 + j, 1u);
+    }
+}
+
 // The same product over all columns, but instead of storing the scores, every
 // score that reaches its row's threshold tau (a lower bound of the row's K-th
 // best, found on a sample of the columns) is appended to the row's candidate
@@ -66,11 +114,13 @@ __global__ __launch_bounds__(256) void k_seed_thresh(const void *dense, int32_t 
     __shared__ __attribute__((aligned(16))) unsigned char lds[ApTileLds<DT>::BYTES];
     __shared__ int32_t a_rows[AP_TILE], b_rows[AP_TILE];
     __shared__ float s_tau[AP_TILE];
+    __shared__ int32_t s_cnt[AP_TILE], s_base[AP_TILE];
     int64_t rt, ct;
     if (!ap_seed_tile((nrows + AP_TILE - 1) / AP_TILE, rt, ct)) return;
     const int64_t i0 = rt * AP_TILE, j0 = ct * AP_TILE;
     if (threadIdx.x < AP_TILE) {
         const int64_t r = i0 + threadIdx.x;
+        s_cnt[threadIdx.x] = 0;
         a_rows[threadIdx.x] = r < nrows ? (node_ids ? node_ids[row0 + r] : (int32_t)(row0 + r)) : -1;
         s_tau[threadIdx.x] = r < nrows ? tau[r] : INFINITY;
         const int64_t j = j0 + threadIdx.x;
@@ -78,12 +128,19 @@ __global__ __launch_bounds__(256) void k_seed_thresh(const void *dense, int32_t 
     }
     ap_f32x16 acc[2][2];
     ap_tile_product<DT>(dense, dim, a_rows, b_rows, lds, acc);
-    ap_tile_foreach(acc, [&](int i, int j, float v) {
-        if (i0 + i < nrows && j0 + j < n && v >= s_tau[i] && a_rows[i] != (int32_t)(j0 + j)) {
+    __syncthreads();   // the product's LDS is free
+    constexpr int W_CAP = ApTileLds<DT>::BYTES / 4 / 8;
+    uint64_t *stage = reinterpret_cast<uint64_t *>(lds) + ap_wave_id() * W_CAP;
+    auto drop = [&](int i, int j) { return !(i0 + i < nrows && j0 + j < n && a_rows[i] != (int32_t)(j0 + j)); };
+    auto direct = [&](int i, int j, float v) {
+        if (!drop(i, j)) {
             const int32_t pos = atomicAdd(&cnt[i0 + i], 1);
             if (pos < cap) buf[(i0 + i) * (int64_t)cap + pos] = ap_make_key(v, (int32_t)(j0 + j), 1u);
         }
-    });
+    };
+    int32_t nw = 0;
+    ap_tile_foreach(acc, [&](int i, int j, float v) { ap_seed_stage(v >= s_tau[i], i, j, v, stage, W_CAP, nw, direct); });
+    ap_seed_flush(stage, W_CAP, nw, AP_TILE, s_cnt, s_base, cnt, buf, cap, i0, (int32_t)j0, drop);
 }
 
 // The thresholded sweep for bf16 rows on 256x256 tiles (the product above): the same appends as k_seed_thresh.
@@ -121,21 +178,16 @@ __global__ __launch_bounds__(WM * WN * 64) void k_seed_thresh_big(const void *de
         const int32_t a_first = (int32_t)(row0 + i0), b_first = (int32_t)j0;
         ap_big_gemm_bf16<WM, WN, true>(dense, dim, a_rows, b_rows, a_first, b_first, reinterpret_cast<uint16_t *>(big_lds), acc);
         // A lane holds 4 consecutive rows x (FB x 32 columns apart) per 8-row group: the rows' thresholds come as one
-        // 16-byte LDS read, and an element costs a compare and a (rarely taken) branch.  A candidate is not appended to
-        // its row's buffer on the spot (an atomic on the row's counter whose answer the store has to wait for, some
-        // forty times per wave): the wave notes it in its own part of the LDS the product has left (place = a running
-        // count + the lane's rank among the lanes that passed, no atomic), and afterwards the candidates are counted per
-        // row in LDS, every row with candidates takes its places in buf with ONE atomic for the whole tile, and the
-        // candidates are written out.  Only a tile whose row and column runs overlap can pair a document with itself.
+        // 16-byte LDS read, and an element costs a compare and a (rarely taken) branch.  Only a tile whose row and
+        // column runs overlap can pair a document with itself.
         const bool diagonal = a_first < b_first + AP_BIG && b_first < a_first + AP_BIG;
         const int lane = threadIdx.x & 63, wave = ap_wave_id();
         const int wm = wave / WN, wn = wave % WN;
-        constexpr int W_CAP = AP_BIG_LDS_BYTES / (WM * WN) / 8;   // entries of a wave's part
+        constexpr int W_CAP = AP_BIG_LDS_BYTES / (WM * WN) / 8;   // entries of a wave's part of the LDS
         uint64_t *stage = reinterpret_cast<uint64_t *>(big_lds) + wave * W_CAP;
-        // an entry: score bits | column in the tile << 32 | row in the tile << 40 | (later) place among the row's << 48
-        const uint32_t lane_pack = (uint32_t)(((wm * (AP_BIG / WM) + 4 * (lane >> 5)) << 8) | (wn * (AP_BIG / WN) + (lane & 31)));
-        auto append = [&](int i, int j, float v) {   // the direct way, for what a wave's part cannot hold
-            if (!(diagonal && a_first + i == b_first + j)) {
+        auto drop = [&](int i, int j) { return diagonal && a_first + i == b_first + j; };
+        auto direct = [&](int i, int j, float v) {
+            if (!drop(i, j)) {
                 const int32_t pos = atomicAdd(&cnt[i0 + i], 1);
                 if (pos < cap) buf[(i0 + i) * (int64_t)cap + pos] = ap_make_key(v, b_first + j, 1u);
             }
@@ -153,47 +205,24 @@ __global__ __launch_bounds__(WM * WN * 64) void k_seed_thresh_big(const void *de
 #pragma unroll
                     for (int rr = 0; rr < 4; rr++) {
                         const float v = acc[a][b][4 * q + rr];
-                        const bool pass = v >= tt[rr];
-                        const uint64_t m = __ballot(pass);
-                        if (m) {
-                            if (pass) {
-                                const int32_t slot = nw + (int32_t)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-                                const uint32_t pack = lane_pack + (uint32_t)(((a * 32 + 8 * q + rr) << 8) | (b * 32));
-                                if (slot < W_CAP) stage[slot] = ((uint64_t)pack << 32) | __float_as_uint(v);
-                                else append(ib + rr, wn * (AP_BIG / WN) + b * 32 + (lane & 31), v);
-                            }
-                            nw += __popcll(m);
-                        }
+                        ap_seed_stage(v >= tt[rr], ib + rr, wn * (AP_BIG / WN) + b * 32 + (lane & 31), v, stage, W_CAP, nw, direct);
                     }
             }
-        const int32_t ns = nw < W_CAP ? nw : W_CAP;
-        for (int32_t p = lane; p < ns; p += 64) {
-            const uint64_t e = stage[p];
-            const int32_t j = (int32_t)(e >> 32) & 255, i = (int32_t)(e >> 40) & 255;
-            if (diagonal && a_first + i == b_first + j) { stage[p] = e | (0xffffull << 48); continue; }   // the document itself: dropped
-            stage[p] = e | ((uint64_t)atomicAdd(&s_cnt[i], 1) << 48);
-        }
-        __syncthreads();
-        for (int32_t x = threadIdx.x; x < AP_BIG; x += blockDim.x) {
-            const int32_t c = s_cnt[x];
-            s_base[x] = c ? atomicAdd(&cnt[i0 + x], c) : 0;
-        }
-        __syncthreads();
-        for (int32_t p = lane; p < ns; p += 64) {
-            const uint64_t e = stage[p];
-            const int32_t j = (int32_t)(e >> 32) & 255, i = (int32_t)(e >> 40) & 255, place = (int32_t)(e >> 48);
-            if (place == 0xffff) continue;
-            const int32_t pos = s_base[i] + place;
-            if (pos < cap) buf[(i0 + i) * (int64_t)cap + pos] = ap_make_key(__uint_as_float((uint32_t)e), b_first + j, 1u);
-        }
+        ap_seed_flush(stage, W_CAP, nw, AP_BIG, s_cnt, s_base, cnt, buf, cap, i0, b_first, drop);
     } else {
         ap_big_gemm_bf16<WM, WN, false>(dense, dim, a_rows, b_rows, 0, 0, reinterpret_cast<uint16_t *>(big_lds), acc);
-        ap_big_foreach<WM, WN>(acc, [&](int i, int j, float v) {
-            if (i0 + i < nrows && j0 + j < n && v >= s_tau[i] && a_rows[i] != (int32_t)(j0 + j)) {
+        constexpr int W_CAP = AP_BIG_LDS_BYTES / (WM * WN) / 8;
+        uint64_t *stage = reinterpret_cast<uint64_t *>(big_lds) + ap_wave_id() * W_CAP;
+        auto drop = [&](int i, int j) { return !(i0 + i < nrows && j0 + j < n && a_rows[i] != (int32_t)(j0 + j)); };
+        auto direct = [&](int i, int j, float v) {
+            if (!drop(i, j)) {
                 const int32_t pos = atomicAdd(&cnt[i0 + i], 1);
                 if (pos < cap) buf[(i0 + i) * (int64_t)cap + pos] = ap_make_key(v, (int32_t)(j0 + j), 1u);
             }
-        });
+        };
+        int32_t nw = 0;
+        ap_big_foreach<WM, WN>(acc, [&](int i, int j, float v) { ap_seed_stage(v >= s_tau[i], i, j, v, stage, W_CAP, nw, direct); });
+        ap_seed_flush(stage, W_CAP, nw, AP_BIG, s_cnt, s_base, cnt, buf, cap, i0, (int32_t)j0, drop);
     }
 }
 
