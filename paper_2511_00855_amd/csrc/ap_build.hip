@@ -681,30 +681,36 @@ __device__ __forceinline__ float ap_merge_dot(P a, int32_t na, P b, int32_t nb) 
     return acc;
 }
 
-// The same walk over two lists in LDS that each end in a sentinel entry (term 0xffffffff, weight 0): the cursors are
-// clamped to the sentinels instead of every operation being masked, which halves the vector instructions of a step.  A
-// finished lane sits on a sentinel, whose term matches nothing but the other sentinel, and then adds 0 x 0.  a_end and
-// b_end are the LDS byte addresses of the sentinels; same products in the same order as ap_merge_dot.
+// The same walk over two lists in LDS that each end in a sentinel entry (weight 0) and one entry of padding: nothing is
+// masked and no cursor is clamped.  The a side's sentinel term is 0xffffffff and a's cursor moves on "a's term <= b's
+// term" compared UNSIGNED; the b side's is 0x7fffffff and b's cursor moves on "b's term <= a's term" compared SIGNED.
+// Real terms lie in [0, 0x7fffffff), where the two orders agree; a's sentinel is the largest value of the unsigned
+// order and b's the largest of the signed one, so a cursor that has reached its sentinel never moves again, whatever
+// the other side shows, and the two sentinels never match each other or a term.  The walk tests "is any lane's pair
+// still live" once per four steps: a lane whose pair is done idles on its sentinels.  a_end and b_end are the LDS byte
+// addresses of the sentinels; same products in the same order as ap_merge_dot.
+#define AP_GT_SENT 2
+#define AP_GT_SENT_A 0xffffffffull
+#define AP_GT_SENT_B 0x7fffffffull
 __device__ __forceinline__ float ap_merge_dot_lds(uint32_t a, uint32_t a_end, uint32_t b, uint32_t b_end) {
     typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));   // a plain vector value: loads from LDS as it is
     typedef const AP_LDS u32x2 *LP;
     auto at = [](uint32_t p) { return *(LP)(uintptr_t)p; };
-    auto next = [](uint32_t p, uint32_t end) { return p + 8u < end ? p + 8u : end; };
     float acc = 0.f;
     // Each list's current entry and the one after it are in registers; a step reads the entry that follows the new
     // "next" position, which the step after it may select: the LDS round trip has a step's instructions to hide behind.
-    uint32_t a1 = next(a, a_end), b1 = next(b, b_end);
-    u32x2 ea = at(a), eb = at(b), ea1 = at(a1), eb1 = at(b1);
+    u32x2 ea = at(a), eb = at(b), ea1 = at(a + 8u), eb1 = at(b + 8u);
     while (__any(a < a_end && b < b_end)) {
-        const float prod = fmaf(__uint_as_float(ea.y), __uint_as_float(eb.y), acc);
-        acc = ea.x == eb.x ? prod : acc;
-        const bool adva = ea.x <= eb.x, advb = eb.x <= ea.x;
-        a = adva ? a1 : a; b = advb ? b1 : b;
-        a1 = next(a, a_end); b1 = next(b, b_end);
-        const u32x2 la = at(a1), lb = at(b1);
-        ea.x = adva ? ea1.x : ea.x; ea.y = adva ? ea1.y : ea.y;
-        eb.x = advb ? eb1.x : eb.x; eb.y = advb ? eb1.y : eb.y;
-        ea1 = la; eb1 = lb;
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            acc = fmaf(ea.x == eb.x ? __uint_as_float(ea.y) : 0.f, __uint_as_float(eb.y), acc);   // adds exactly 0 when the terms differ
+            const bool adva = ea.x <= eb.x, advb = (int32_t)eb.x <= (int32_t)ea.x;
+            a = adva ? a + 8u : a; b = advb ? b + 8u : b;
+            const u32x2 la = at(a + 8u), lb = at(b + 8u);
+            ea.x = adva ? ea1.x : ea.x; ea.y = adva ? ea1.y : ea.y;
+            eb.x = advb ? eb1.x : eb.x; eb.y = advb ? eb1.y : eb.y;
+            ea1 = la; eb1 = lb;
+        }
     }
     return acc;
 }
@@ -731,7 +737,7 @@ __global__ __launch_bounds__(256) void k_gram_merge(const uint2 *__restrict__ re
             if (pos < K) id = knn[u * K + pos];
             if (id >= 0) { const uint4 m = meta[id]; first = m.x; sn = (int32_t)(m.y & 0xffffu); tn = (int32_t)(m.y >> 16); }
         }
-        const int32_t room = lane < 2 * AP_GT ? sn + tn + 2 : 0;   // a record in LDS: sparse entries, sentinel, lexical entries, sentinel
+        const int32_t room = lane < 2 * AP_GT ? sn + tn + 2 * AP_GT_SENT : 0;   // a record in LDS: sparse entries, sentinels, lexical entries, sentinels
         int32_t incl = room;
         for (int o = 1; o < 64; o <<= 1) {
             const int32_t up = __shfl_up(incl, o, 64);
@@ -747,8 +753,11 @@ __global__ __launch_bounds__(256) void k_gram_merge(const uint2 *__restrict__ re
         for (int d = 0; d < 2 * AP_GT; d++) {
             const int32_t sn = d_sn[d], len = sn + d_tn[d], off = d_off[d];
             const uint64_t *src = grec + d_first[d];
-            for (int32_t e = tid; e < len; e += 256) ent[off + e + (e >= sn ? 1 : 0)] = src[e];
-            if (tid == 0) { ent[off + sn] = 0xffffffffull; ent[off + len + 1] = 0xffffffffull; }
+            for (int32_t e = tid; e < len; e += 256) ent[off + e + (e >= sn ? AP_GT_SENT : 0)] = src[e];
+            if (tid < AP_GT_SENT) {   // slots 0..15 are a sides of the walks, 16..31 b sides
+                const uint64_t sent = d < AP_GT ? AP_GT_SENT_A : AP_GT_SENT_B;
+                ent[off + sn + tid] = sent; ent[off + len + AP_GT_SENT + tid] = sent;
+            }
         }
         __syncthreads();
     }
@@ -765,7 +774,8 @@ __global__ __launch_bounds__(256) void k_gram_merge(const uint2 *__restrict__ re
             const uint32_t la = base + 8u * (uint32_t)d_off[r], lb = base + 8u * (uint32_t)d_off[AP_GT + c];
             const uint32_t sa = 8u * (uint32_t)d_sn[r], sb = 8u * (uint32_t)d_sn[AP_GT + c];
             qs = ap_merge_dot_lds(la, la + sa, lb, lb + sb);
-            qt = ap_merge_dot_lds(la + sa + 8u, la + sa + 8u + 8u * (uint32_t)d_tn[r], lb + sb + 8u, lb + sb + 8u + 8u * (uint32_t)d_tn[AP_GT + c]);
+            const uint32_t ta = la + sa + 8u * AP_GT_SENT, tb = lb + sb + 8u * AP_GT_SENT;
+            qt = ap_merge_dot_lds(ta, ta + 8u * (uint32_t)d_tn[r], tb, tb + 8u * (uint32_t)d_tn[AP_GT + c]);
         } else {
             const uint64_t *ga = grec + d_first[r], *gb = grec + d_first[AP_GT + c];
             qs = ap_merge_dot(ga, d_sn[r], gb, d_sn[AP_GT + c]);
