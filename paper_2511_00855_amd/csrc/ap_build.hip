@@ -477,7 +477,7 @@ __global__ __launch_bounds__(512) void k_refine(ApVecs D, const uint2 *__restric
                                                 unsigned long long *__restrict__ n_sims) {
     __shared__ int32_t ht[AP_HT];
     __shared__ int32_t cand[AP_MAXC];
-    __shared__ uint64_t keys[AP_MAXC];
+    __shared__ uint64_t keys[2048];   // the candidates' fused keys, sorted in place afterwards (AP_MAXC padded to a power of two)
     __shared__ float comp[3][AP_MAXC];
     __shared__ int32_t l_sp_idx[AP_A_CAP], l_tx_idx[AP_A_CAP];
     __shared__ float l_sp_val[AP_A_CAP], l_tx_val[AP_A_CAP];
@@ -556,15 +556,17 @@ __global__ __launch_bounds__(512) void k_refine(ApVecs D, const uint2 *__restric
             comp[0][i] = sd; comp[1][i] = ss; comp[2][i] = sf;
         }
     }
-    __syncthreads();
-    // top-K under the fused score by ranking
-    for (int32_t t = threadIdx.x; t < cnt; t += blockDim.x) {
-        const uint64_t key = keys[t];
-        int32_t r = 0;
-        for (int32_t j = 0; j < cnt; j++) r += keys[j] > key;
-        if (r < K) { out_ids[x * K + r] = ap_key_id(key); out_sc[x * K + r] = ap_key_score(key); }
+    // top-K under the fused score: the keys (all different: a key carries its id) sorted in LDS.  Ranking every key
+    // against every other took a third of the kernel's vector instructions.
+    int32_t n2 = 64;
+    while (n2 < cnt) n2 <<= 1;   // uniform; cnt <= AP_MAXC <= 2048
+    for (int32_t t = cnt + threadIdx.x; t < n2; t += blockDim.x) keys[t] = 0ull;
+    ap_bitonic_desc(keys, n2);   // begins and ends with a barrier
+    for (int32_t t = threadIdx.x; t < K; t += blockDim.x) {
+        const uint64_t key = t < cnt ? keys[t] : 0ull;
+        out_ids[x * K + t] = t < cnt ? ap_key_id(key) : -1;
+        out_sc[x * K + t] = t < cnt ? ap_key_score(key) : -INFINITY;
     }
-    for (int32_t t = cnt + threadIdx.x; t < K; t += blockDim.x) { out_ids[x * K + t] = -1; out_sc[x * K + t] = -INFINITY; }
     // per-path lists: the best P by each single similarity among this round's candidates and the previous list (entries
     // scored again this round excepted).  One wave per path, on its own: every lane keeps its share of the keys in
     // registers and the P best are drawn one after the other by wave-wide maxima (no block-wide pass, no barrier).
