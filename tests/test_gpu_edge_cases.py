@@ -271,6 +271,29 @@ def test_bf16_threshold_sweep_on_ragged_shapes(dim, debug_knobs):
     ix.close()
 
 
+def test_threshold_sweep_with_more_candidates_than_a_wave_stages(debug_knobs):
+    """The sweeps note a tile's candidates in LDS, a wave in its own part, before they are appended to the rows' buffers;
+    what a part cannot hold is appended on the spot.  A threshold taken from very few sampled columns lets nearly half of
+    every tile pass, far more than the parts hold: the lean 256x256 kernel, its ragged edge tiles and (f32 rows) the
+    128x128 kernel must still give the exact lists, bit for bit."""
+    _say("edge case: threshold sweeps with overflowing staging parts")
+    K = 120
+    for bf16 in (True, False):
+        w = make_workload("tiny", seed=93, n=1100, nq=2, dim=64, bf16=bf16, sp=("fixed", 4), tx=("fixed", 4))
+        docs = B.DeviceVecs(w.docs, bf16=bf16)
+        ix = B.Index.ingest(docs, B.build_params(8, knn_k=K, nd_rounds=1, nd_sample=4, n_entry=4))
+        exact = [t.cpu().numpy() for t in ix.stage_seed_knn(K)]
+        nodes = np.arange(3, 1000, 2, dtype=np.int32)
+        exact_sub = [t.cpu().numpy() for t in ix.stage_seed_knn(K, nodes)]
+        debug_knobs("seed_sample_cols", 256)
+        thr = [t.cpu().numpy() for t in ix.stage_seed_knn(K)]
+        assert np.array_equal(thr[0], exact[0]) and np.array_equal(thr[1], exact[1]), bf16
+        thr_sub = [t.cpu().numpy() for t in ix.stage_seed_knn(K, nodes)]
+        assert np.array_equal(thr_sub[0], exact_sub[0]) and np.array_equal(thr_sub[1], exact_sub[1]), bf16
+        debug_knobs("seed_sample_cols", 0)
+        ix.close()
+
+
 def test_random_search_settings_replayed():
     """Forty seeded draws of (k, beam, parents per iteration, iteration cap) across the three workgroup sizes of the
     search (256, 512 and 1024 threads), on two graphs of different degree, each replayed by the oracle on the GPU's own
