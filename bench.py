@@ -29,7 +29,7 @@ MFMA_PEAK_TFLOPS = {True: 2500.0, False: 157.3}   # dense bf16 / fp32 matrix pea
 # (beam, width) settings tried in order until the recall target is met
 SWEEPS = {
     "tiny": "64,128,256,512",
-    "cfg2": "128,512,1024,1536,2048,2112,2144,2176,2240,2304,2560,3072,4096:4,6144:4,8192:16,12288:16,16384:16",
+    "cfg2": "128,512,1024,1536,2048:16,2080:16,2112:16,2144:16,2176:16,2240:16,2304:16,2560,3072,4096:4,6144:4,8192:16,12288:16,16384:16",
     "cfg3": "128,1024,4096:4,8192:16,12288:16,14336:16,15360:16,16384:16",
     "cfg5": "128,1024,4096:4,16384:16",
 }

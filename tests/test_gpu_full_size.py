@@ -74,23 +74,23 @@ def test_full_size_scores_sampled(full):
     assert_scores_close(got[rows], ref, score_tol(ref, wq[rows][:, None, :], qn, dn, RTOL_F32), "full-size scores")
 
 
-@pytest.mark.parametrize("beam", [128, 2144])
-def test_full_size_search_replay(full, beam):
-    """All 10,000 queries are searched exactly as bench.py does; for a sample the
-    oracle's search, replayed on the GPU's own scores, must return the same ids
-    and scores bit for bit."""
+@pytest.mark.parametrize("beam,width", [(128, 1), (2144, 1), (2112, 16)])
+def test_full_size_search_replay(full, beam, width):
+    """All 10,000 queries are searched exactly as bench.py does (2112 with sixteen parents per iteration is the setting
+    it times on this workload); for a sample the oracle's search, replayed on the GPU's own scores, must return the same
+    ids and scores bit for bit."""
     w, docs, qs, bp, ix, D, Q = full
-    _say(f"full size: search beam {beam}")
+    _say(f"full size: search beam {beam}, {width} parent(s) per iteration")
     nq, N, k = qs.n, docs.n, w.k
     wq = np.tile(np.float32(w.weights), (nq, 1))
-    ids, sc = [t.cpu().numpy() for t in ix.search_batch(qs, k, beam, wq)]
+    ids, sc = [t.cpu().numpy() for t in ix.search_batch(qs, k, beam, wq, 0, width)]
     counts, ms = ix.search_stats(nq)
     counts = counts.cpu().numpy()
     sem, _, _, ent = [t.cpu().numpy() for t in ix.export_graph()]
     sample = np.arange(0, nq, nq // 100)[:100]
     table = _score_table(w, ix, sample, wq)
     for x, qi in enumerate(sample):
-        oi, os_, nv = O.search(D, sem, ent, Q, int(qi), wq[qi], k, beam, score_table=table[x])
+        oi, os_, nv = O.search(D, sem, ent, Q, int(qi), wq[qi], k, beam, 0, width, score_table=table[x])
         assert np.array_equal(ids[qi], oi), (qi, beam)
         assert np.array_equal(sc[qi], os_), (qi, beam)
         assert counts[qi, 0] == nv, (qi, counts[qi], nv)     # the same documents were scored
