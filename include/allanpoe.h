@@ -339,7 +339,8 @@ int ap_build_timings(const ap_index *index, float out6[6]);
 
 /* Work counters of the construction stages run on this index so far (host array; synchronises `stream`):
  * [0] hybrid similarities evaluated by refinement rounds (whole builds, insertions and ap_stage_refine calls),
- * [1] reserved (0). */
+ * [1] FLOPs (2 per multiply-add; padded tiles included) of the dense products of the seed stages (the sampled columns,
+ *     the sweeps, the exact rows). */
 int ap_build_counters(const ap_index *index, uint64_t out2[2], void *stream);
 
 /* Debug settings, for tests: they drive small inputs through the code paths of large ones and never change a
@@ -347,6 +348,7 @@ int ap_build_counters(const ap_index *index, uint64_t out2[2], void *stream);
  *   "seed_sample_cols"        columns sampled for the seed threshold (forces the thresholded sweep on small corpora)
  *   "seed_buffer_cap"         capacity of a row's candidate buffer in that sweep (forces the overflow fallback)
  *   "seed_tau_ulps"           raises every row's threshold by this many ulps (forces the short-row fallback)
+ *   "seed_one_sided"          1: whole-corpus seed lists of bf16 rows by the one-sided sweep instead of the symmetric one
  *   "max_launch_threads"      a multiple of 1024: launches that grow with the corpus run in slices of this many threads
  *   "search_workspace_bytes"  cap of the searches' visited-set workspace (forces searches in several slabs of queries)
  *   "search_visited_global"   1: visited sets stay in the global workspace even where the search would keep them in LDS

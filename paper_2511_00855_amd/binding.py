@@ -105,7 +105,7 @@ def debug_set(name: str, value: int):
 
 
 DEBUG_NAMES = ("seed_sample_cols", "seed_buffer_cap", "seed_tau_ulps", "max_launch_threads", "search_workspace_bytes",
-               "search_visited_global", "search_query_lists")
+               "search_visited_global", "search_query_lists", "seed_one_sided")
 
 
 def debug_reset():
@@ -476,7 +476,7 @@ class Index:
         out = (C.c_uint64 * 2)()
         with torch.cuda.device(self.device):
             _check(lib().ap_build_counters(self._h, out, _stream()), "ap_build_counters")
-        return dict(refine_similarities=int(out[0]))
+        return dict(refine_similarities=int(out[0]), seed_flops=int(out[1]))
 
     def build_timings(self):
         out = (C.c_float * 6)()

@@ -28,7 +28,7 @@ extern "C" int ap_debug_set(const char *name, int64_t value) {
         {"seed_sample_cols", &g_ap_debug.seed_sample_cols},       {"seed_buffer_cap", &g_ap_debug.seed_buffer_cap},
         {"seed_tau_ulps", &g_ap_debug.seed_tau_ulps},             {"max_launch_threads", &g_ap_debug.max_launch_threads},
         {"search_workspace_bytes", &g_ap_debug.search_workspace_bytes}, {"search_visited_global", &g_ap_debug.search_visited_global},
-        {"search_query_lists", &g_ap_debug.search_query_lists},
+        {"search_query_lists", &g_ap_debug.search_query_lists},         {"seed_one_sided", &g_ap_debug.seed_one_sided},
     };
     for (auto &t : table)
         if (strcmp(name, t.name) == 0) { *t.field = value; return AP_OK; }
@@ -464,7 +464,7 @@ extern "C" int ap_build_counters(const ap_index *ix, uint64_t out2[2], void *str
     unsigned long long h[2] = {0, 0};
     AP_CHECK_HIP(hipMemcpyAsync(h, ix->counters, sizeof(h), hipMemcpyDeviceToHost, (hipStream_t)stream));
     AP_CHECK_HIP(hipStreamSynchronize((hipStream_t)stream));
-    out2[0] = h[0]; out2[1] = h[1];
+    out2[0] = h[0]; out2[1] = ix->seed_flops;
     return AP_OK;
 }
 

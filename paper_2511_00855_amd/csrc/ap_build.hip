@@ -59,46 +59,51 @@ __global__ __launch_bounds__(256) void k_seed_scores(const void *dense, int32_t 
 // it in its own part of the LDS the product has left (place = a running count + the lane's rank among the lanes that
 // passed: no atomic, no wait); afterwards the candidates are counted per row in LDS, every row that has some takes its
 // places in buf with ONE atomic for the whole tile, and the candidates are written out.
-// An entry: score bits | column in the tile << 32 | row in the tile << 40 | (later) place among the row's << 48.
-// direct(i, j, v): the append on the spot, for what the wave's part (wcap entries) cannot hold.
+// An entry: score bits | column in the tile << 32 | row in the tile << 40 | side << 48 | (later) place << 49.
+// side 0: the candidate goes to the buffer of its row's document (id = its column's document); side 1, used by the
+// symmetric sweep only: the score is also that of the mirrored pair, and the candidate goes to the buffer of its
+// column's document (id = its row's document).
+// direct(side, i, j, v): the append on the spot, for what the wave's part (wcap entries) cannot hold.
 template <typename DIRECT>
-__device__ __forceinline__ void ap_seed_stage(bool pass, int i, int j, float v, uint64_t *stage, int32_t wcap, int32_t &nw, DIRECT direct) {
+__device__ __forceinline__ void ap_seed_stage(bool pass, int side, int i, int j, float v, uint64_t *stage, int32_t wcap, int32_t &nw, DIRECT direct) {
     const uint64_t m = __ballot(pass);
     if (m) {
         if (pass) {
             const int32_t slot = nw + (int32_t)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-            if (slot < wcap) stage[slot] = ((uint64_t)(uint32_t)((i << 8) | j) << 32) | __float_as_uint(v);
-            else direct(i, j, v);
+            if (slot < wcap) stage[slot] = ((uint64_t)(uint32_t)((side << 16) | (i << 8) | j) << 32) | __float_as_uint(v);
+            else direct(side, i, j, v);
         }
         nw += __popcll(m);
     }
 }
-// Called by every thread of the workgroup once its wave has staged nw candidates.  drop(i, j): a candidate that is not
-// one after all (the document itself, a row or column past the end).  s_cnt[rows] must be zero on entry.
+// Called by every thread of the workgroup once its wave has staged nw candidates.  drop(side, i, j): a candidate that is
+// not one after all (the document itself, a row or column past the end).  s_cnt[2 * rows] must be zero on entry
+// ([rows] if no candidate has side 1).  Buffers and counters are indexed by row0 + (row in the tile) for side 0 and by
+// row1 + (column in the tile) for side 1; the ids stored are id0 + column and id1 + row.
 template <typename DROP>
-__device__ __forceinline__ void ap_seed_flush(uint64_t *stage, int32_t wcap, int32_t nw, int32_t rows, int32_t *s_cnt, int32_t *s_base,
-                                              int32_t *__restrict__ cnt, unsigned long long *__restrict__ buf, int32_t cap, int64_t i0,
-                                              int32_t col0, DROP drop) {
+__device__ __forceinline__ void ap_seed_flush(uint64_t *stage, int32_t wcap, int32_t nw, int32_t rows, bool both_sides, int32_t *s_cnt,
+                                              int32_t *s_base, int32_t *__restrict__ cnt, unsigned long long *__restrict__ buf, int32_t cap,
+                                              int64_t row0, int32_t id0, int64_t row1, int32_t id1, DROP drop) {
     const int lane = threadIdx.x & 63;
     const int32_t ns = nw < wcap ? nw : wcap;
     for (int32_t p = lane; p < ns; p += 64) {
         const uint64_t e = stage[p];
-        const int32_t j = (int32_t)(e >> 32) & 255, i = (int32_t)(e >> 40) & 255;
-        if (drop(i, j)) { stage[p] = e | (0xffffull << 48); continue; }
-        stage[p] = e | ((uint64_t)atomicAdd(&s_cnt[i], 1) << 48);
+        const int32_t j = (int32_t)(e >> 32) & 255, i = (int32_t)(e >> 40) & 255, side = (int32_t)(e >> 48) & 1;
+        if (drop(side, i, j)) { stage[p] = e | (0x7fffull << 49); continue; }
+        stage[p] = e | ((uint64_t)atomicAdd(&s_cnt[side ? rows + j : i], 1) << 49);
     }
     __syncthreads();
-    for (int32_t x = threadIdx.x; x < rows; x += blockDim.x) {
+    for (int32_t x = threadIdx.x; x < (both_sides ? 2 * rows : rows); x += blockDim.x) {
         const int32_t c = s_cnt[x];
-        s_base[x] = c ? atomicAdd(&cnt[i0 + x], c) : 0;
+        s_base[x] = c ? atomicAdd(&cnt[x < rows ? row0 + x : row1 + (x - rows)], c) : 0;
     }
     __syncthreads();
     for (int32_t p = lane; p < ns; p += 64) {
         const uint64_t e = stage[p];
-        const int32_t j = (int32_t)(e >> 32) & 255, i = (int32_t)(e >> 40) & 255, place = (int32_t)(e >> 48);
-        if (place == 0xffff) continue;
-        const int32_t pos = s_base[i] + place;
-        if (pos < cap) buf[(i0 + i) * (int64_t)cap + pos] = ap_make_key(__uint_as_float((uint32_t)e), col0 + j, 1u);
+        const int32_t j = (int32_t)(e >> 32) & 255, i = (int32_t)(e >> 40) & 255, side = (int32_t)(e >> 48) & 1, place = (int32_t)(e >> 49);
+        if (place == 0x7fff) continue;
+        const int32_t pos = s_base[side ? rows + j : i] + place;
+        if (pos < cap) buf[(side ? row1 + j : row0 + i) * (int64_t)cap + pos] = ap_make_key(__uint_as_float((uint32_t)e), side ? id1 + i : id0 + j, 1u);
     }
 }
 
@@ -131,16 +136,16 @@ __global__ __launch_bounds__(256) void k_seed_thresh(const void *dense, int32_t 
     __syncthreads();   // the product's LDS is free
     constexpr int W_CAP = ApTileLds<DT>::BYTES / 4 / 8;
     uint64_t *stage = reinterpret_cast<uint64_t *>(lds) + ap_wave_id() * W_CAP;
-    auto drop = [&](int i, int j) { return !(i0 + i < nrows && j0 + j < n && a_rows[i] != (int32_t)(j0 + j)); };
-    auto direct = [&](int i, int j, float v) {
-        if (!drop(i, j)) {
+    auto drop = [&](int, int i, int j) { return !(i0 + i < nrows && j0 + j < n && a_rows[i] != (int32_t)(j0 + j)); };
+    auto direct = [&](int, int i, int j, float v) {
+        if (!drop(0, i, j)) {
             const int32_t pos = atomicAdd(&cnt[i0 + i], 1);
             if (pos < cap) buf[(i0 + i) * (int64_t)cap + pos] = ap_make_key(v, (int32_t)(j0 + j), 1u);
         }
     };
     int32_t nw = 0;
-    ap_tile_foreach(acc, [&](int i, int j, float v) { ap_seed_stage(v >= s_tau[i], i, j, v, stage, W_CAP, nw, direct); });
-    ap_seed_flush(stage, W_CAP, nw, AP_TILE, s_cnt, s_base, cnt, buf, cap, i0, (int32_t)j0, drop);
+    ap_tile_foreach(acc, [&](int i, int j, float v) { ap_seed_stage(v >= s_tau[i], 0, i, j, v, stage, W_CAP, nw, direct); });
+    ap_seed_flush(stage, W_CAP, nw, AP_TILE, false, s_cnt, s_base, cnt, buf, cap, i0, (int32_t)j0, (int64_t)0, 0, drop);
 }
 
 // The thresholded sweep for bf16 rows on 256x256 tiles (the product above): the same appends as k_seed_thresh.
@@ -153,20 +158,28 @@ __global__ __launch_bounds__(256) void k_seed_thresh(const void *dense, int32_t 
 // RUN: every tile of the launch is two runs of 256 consecutive documents inside the corpus (no node list, no ragged
 // edge, dim a multiple of 64); the host launches the edges of a sweep with RUN = false.  The launch covers row tiles
 // rt0 .. rt0 + nrt and column tiles from ct0 on.
-template <int WM, int WN, bool RUN>
+// SYM (with RUN, rows = the whole corpus, row0 = 0): the product is symmetric, so only the tiles on and above the
+// diagonal are computed (a launch's tiles below it return at once), and a score of an off-diagonal tile is offered
+// twice: to its row's document against that document's threshold, and to its column's document against that one's.
+// The mirrored pair would have got the same bits: the same products summed over k in the same order.
+template <int WM, int WN, bool RUN, bool SYM>
 __global__ __launch_bounds__(WM * WN * 64) void k_seed_thresh_big(const void *dense, int32_t dim, int64_t n, const int32_t *node_ids,
                                                                   int64_t row0, int64_t nrows, const float *__restrict__ tau,
                                                                   unsigned long long *__restrict__ buf, int32_t cap,
                                                                   int32_t *__restrict__ cnt, int64_t rt0, int64_t nrt, int64_t ct0) {
+    static_assert(RUN || !SYM, "the symmetric sweep is for runs of consecutive documents");
     extern __shared__ __attribute__((aligned(16))) unsigned char big_lds[];
     __shared__ int32_t a_rows[AP_BIG], b_rows[AP_BIG];
     __shared__ __attribute__((aligned(16))) float s_tau[AP_BIG];
-    __shared__ int32_t s_cnt[AP_BIG], s_base[AP_BIG];   // RUN: the tile's candidates per row, and where each row's go in buf
+    __shared__ float s_tauc[SYM ? AP_BIG : 1];          // SYM: the thresholds of the tile's column documents
+    __shared__ int32_t s_cnt[(SYM ? 2 : 1) * AP_BIG], s_base[(SYM ? 2 : 1) * AP_BIG];   // the tile's candidates per buffer, and where each buffer's go
     int64_t rt, ct;
     if (!ap_seed_tile(nrt, rt, ct)) return;
     const int64_t i0 = (rt0 + rt) * AP_BIG, j0 = (ct0 + ct) * AP_BIG;
+    if (SYM && j0 < i0) return;   // below the diagonal: its mirror image does the work
     for (int32_t x = threadIdx.x; x < AP_BIG; x += blockDim.x) {
         s_cnt[x] = 0;
+        if (SYM) { s_cnt[AP_BIG + x] = 0; s_tauc[x] = tau[j0 + x]; }
         const int64_t r = i0 + x;
         a_rows[x] = r < nrows ? (node_ids ? node_ids[row0 + r] : (int32_t)(row0 + r)) : -1;
         s_tau[x] = r < nrows ? tau[r] : INFINITY;
@@ -181,17 +194,22 @@ __global__ __launch_bounds__(WM * WN * 64) void k_seed_thresh_big(const void *de
         // 16-byte LDS read, and an element costs a compare and a (rarely taken) branch.  Only a tile whose row and
         // column runs overlap can pair a document with itself.
         const bool diagonal = a_first < b_first + AP_BIG && b_first < a_first + AP_BIG;
+        const bool mirror = SYM && !diagonal;   // uniform: the scores also go to the column documents
         const int lane = threadIdx.x & 63, wave = ap_wave_id();
         const int wm = wave / WN, wn = wave % WN;
         constexpr int W_CAP = AP_BIG_LDS_BYTES / (WM * WN) / 8;   // entries of a wave's part of the LDS
         uint64_t *stage = reinterpret_cast<uint64_t *>(big_lds) + wave * W_CAP;
-        auto drop = [&](int i, int j) { return diagonal && a_first + i == b_first + j; };
-        auto direct = [&](int i, int j, float v) {
-            if (!drop(i, j)) {
-                const int32_t pos = atomicAdd(&cnt[i0 + i], 1);
-                if (pos < cap) buf[(i0 + i) * (int64_t)cap + pos] = ap_make_key(v, b_first + j, 1u);
+        auto drop = [&](int, int i, int j) { return diagonal && a_first + i == b_first + j; };
+        auto direct = [&](int side, int i, int j, float v) {
+            if (!drop(side, i, j)) {
+                const int64_t row = side ? j0 + j : i0 + i;
+                const int32_t pos = atomicAdd(&cnt[row], 1);
+                if (pos < cap) buf[row * (int64_t)cap + pos] = ap_make_key(v, side ? a_first + i : b_first + j, 1u);
             }
         };
+        float tc[ApBig<WM, WN>::FB];   // the thresholds of this lane's columns
+#pragma unroll
+        for (int b = 0; b < ApBig<WM, WN>::FB; b++) tc[b] = SYM ? s_tauc[wn * (AP_BIG / WN) + b * 32 + (lane & 31)] : INFINITY;
         int32_t nw = 0;   // uniform: candidates of this wave so far
 #pragma unroll
         for (int a = 0; a < ApBig<WM, WN>::FA; a++)
@@ -205,24 +223,26 @@ __global__ __launch_bounds__(WM * WN * 64) void k_seed_thresh_big(const void *de
 #pragma unroll
                     for (int rr = 0; rr < 4; rr++) {
                         const float v = acc[a][b][4 * q + rr];
-                        ap_seed_stage(v >= tt[rr], ib + rr, wn * (AP_BIG / WN) + b * 32 + (lane & 31), v, stage, W_CAP, nw, direct);
+                        const int j = wn * (AP_BIG / WN) + b * 32 + (lane & 31);
+                        ap_seed_stage(v >= tt[rr], 0, ib + rr, j, v, stage, W_CAP, nw, direct);
+                        if (SYM) ap_seed_stage(mirror && v >= tc[b], 1, ib + rr, j, v, stage, W_CAP, nw, direct);
                     }
             }
-        ap_seed_flush(stage, W_CAP, nw, AP_BIG, s_cnt, s_base, cnt, buf, cap, i0, b_first, drop);
+        ap_seed_flush(stage, W_CAP, nw, AP_BIG, SYM, s_cnt, s_base, cnt, buf, cap, i0, b_first, j0, a_first, drop);
     } else {
         ap_big_gemm_bf16<WM, WN, false>(dense, dim, a_rows, b_rows, 0, 0, reinterpret_cast<uint16_t *>(big_lds), acc);
         constexpr int W_CAP = AP_BIG_LDS_BYTES / (WM * WN) / 8;
         uint64_t *stage = reinterpret_cast<uint64_t *>(big_lds) + ap_wave_id() * W_CAP;
-        auto drop = [&](int i, int j) { return !(i0 + i < nrows && j0 + j < n && a_rows[i] != (int32_t)(j0 + j)); };
-        auto direct = [&](int i, int j, float v) {
-            if (!drop(i, j)) {
+        auto drop = [&](int, int i, int j) { return !(i0 + i < nrows && j0 + j < n && a_rows[i] != (int32_t)(j0 + j)); };
+        auto direct = [&](int, int i, int j, float v) {
+            if (!drop(0, i, j)) {
                 const int32_t pos = atomicAdd(&cnt[i0 + i], 1);
                 if (pos < cap) buf[(i0 + i) * (int64_t)cap + pos] = ap_make_key(v, (int32_t)(j0 + j), 1u);
             }
         };
         int32_t nw = 0;
-        ap_big_foreach<WM, WN>(acc, [&](int i, int j, float v) { ap_seed_stage(v >= s_tau[i], i, j, v, stage, W_CAP, nw, direct); });
-        ap_seed_flush(stage, W_CAP, nw, AP_BIG, s_cnt, s_base, cnt, buf, cap, i0, (int32_t)j0, drop);
+        ap_big_foreach<WM, WN>(acc, [&](int i, int j, float v) { ap_seed_stage(v >= s_tau[i], 0, i, j, v, stage, W_CAP, nw, direct); });
+        ap_seed_flush(stage, W_CAP, nw, AP_BIG, false, s_cnt, s_base, cnt, buf, cap, i0, (int32_t)j0, (int64_t)0, 0, drop);
     }
 }
 
@@ -294,6 +314,7 @@ static hipError_t seed_exact_rows(const ap_index *ix, const int32_t *node_ids, i
     for (int64_t r0 = row0; r0 < row0 + nrows && e == hipSuccess; r0 += scratch_rows) {
         const int64_t nr = std::min(scratch_rows, row0 + nrows - r0);
         dim3 grid(ap_seed_grid((nr + AP_TILE - 1) / AP_TILE, (n + AP_TILE - 1) / AP_TILE));
+        ix->seed_flops += (unsigned long long)(((nr + AP_TILE - 1) / AP_TILE) * ((n + AP_TILE - 1) / AP_TILE)) * 2ull * AP_TILE * AP_TILE * (unsigned long long)ix->docs.dim;
         if (ix->dtype == AP_F32)
             hipLaunchKernelGGL(k_seed_scores<AP_F32>, grid, dim3(256), 0, st, ix->docs.dense, ix->docs.dim, n, node_ids, r0, nr, (int64_t)0, n, scratch);
         else
@@ -304,6 +325,142 @@ static hipError_t seed_exact_rows(const ap_index *ix, const int32_t *node_ids, i
         e = hipGetLastError();
     }
     return e;
+}
+
+// rows list[r] of a [*, K] table take the values of row r of a compact one
+__global__ void k_scatter_rows(const int32_t *__restrict__ list, int64_t nlist, int32_t K, const int32_t *__restrict__ ids,
+                               const float *__restrict__ sc, int32_t *__restrict__ out_ids, float *__restrict__ out_sc) {
+    const int64_t t = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (t < nlist * K) {
+        const int64_t r = t / K, i = t % K;
+        out_ids[(int64_t)list[r] * K + i] = ids[t];
+        out_sc[(int64_t)list[r] * K + i] = sc[t];
+    }
+}
+
+// S2 for a whole corpus of bf16 rows: the sweep with half the products.  D D^T is symmetric, so only the tiles on and
+// above the diagonal are multiplied and every score is offered to both of its documents (k_seed_thresh_big<.., SYM>).
+// For that every document's candidate buffer has to exist at once, so the buffers are short (cap entries, by the
+// memory that is free) and the thresholds tight: tau = the m-th best of cs sampled columns with m < K, chosen so that
+// a row expects about 0.45 cap candidates.  Such a tau is not a guaranteed lower bound of the row's K-th best: a row
+// that ends up with fewer than K candidates (a few in ten thousand) or more than cap is redone by the exact path,
+// like an overflowing row of the one-sided sweep.  The lists are the exact ones either way.
+// *done = false (and AP_OK): not applicable here (shape, memory); the caller takes the one-sided sweep.
+static int ap_seed_knn_symmetric(const ap_index *ix, int32_t K, int32_t *out_ids, float *out_sc, hipStream_t st, bool *done) {
+    *done = false;
+    const int64_t n = ix->docs.n, T = n / AP_BIG;
+    if (ix->dtype != AP_BF16 || ix->docs.dim % AP_BK16 != 0 || T < 2 || n > ((int64_t)1 << 30)) return AP_OK;
+    size_t free_b = 0, total_b = 0;
+    if (hipMemGetInfo(&free_b, &total_b) != hipSuccess) return AP_OK;
+    int64_t cap = 4096;
+    while (cap > 512 && (double)n * (double)cap * 8.0 > 0.62 * (double)free_b) cap >>= 1;
+    if ((double)n * (double)cap * 8.0 > 0.62 * (double)free_b) return AP_OK;
+    const double mean = 0.45 * (double)cap;
+    int64_t m = std::min<int64_t>(K, 24);
+    int64_t cs = (int64_t)((double)m * (double)n / mean) + 1;
+    const int64_t cs_min = g_ap_debug.seed_sample_cols > 0 ? std::max<int64_t>(K + 1, g_ap_debug.seed_sample_cols) : 16384;
+    if (cs < cs_min || g_ap_debug.seed_sample_cols > 0) {   // a fixed sample: the rank that gives the same expectation
+        cs = cs_min;
+        m = std::min<int64_t>(K, std::max<int64_t>(m, (int64_t)(mean * (double)cs / (double)n) + 1));
+    }
+    cs = (cs + AP_TILE - 1) / AP_TILE * AP_TILE;
+    if (n < 2 * cs) return AP_OK;
+    if (g_ap_debug.seed_buffer_cap > 0) cap = g_ap_debug.seed_buffer_cap;   // forces overflows
+    const int64_t RS = 8192;
+    float *scratch = nullptr, *tau = nullptr, *tmp_sc = nullptr;
+    unsigned long long *buf = nullptr;
+    int32_t *cnt = nullptr, *ovf = nullptr;
+    int rc = ap_dev_alloc(&buf, (size_t)n * (size_t)cap);
+    if (rc != AP_OK) { (void)hipGetLastError(); ap_set_error("%s", ""); return AP_OK; }   // no room for the buffers after all: the one-sided sweep
+    rc = ap_dev_alloc(&scratch, (size_t)RS * (size_t)cs);
+    if (rc == AP_OK) rc = ap_dev_alloc(&tau, (size_t)n);
+    if (rc == AP_OK) rc = ap_dev_alloc(&tmp_sc, (size_t)RS * (size_t)m);
+    if (rc == AP_OK) rc = ap_dev_alloc(&cnt, (size_t)n);
+    if (rc == AP_OK) rc = ap_dev_alloc(&ovf, (size_t)n + 1);
+    hipError_t e = hipSuccess;
+    int32_t *re_ids = nullptr; float *re_sc = nullptr, *ex_scratch = nullptr;
+    if (rc == AP_OK) {
+        // thresholds of all rows
+        for (int64_t row0 = 0; row0 < n && e == hipSuccess; row0 += RS) {
+            const int64_t nrows = std::min(RS, n - row0);
+            dim3 gs(ap_seed_grid((nrows + AP_TILE - 1) / AP_TILE, cs / AP_TILE));
+            ix->seed_flops += (unsigned long long)(((nrows + AP_TILE - 1) / AP_TILE) * (cs / AP_TILE)) * 2ull * AP_TILE * AP_TILE * (unsigned long long)ix->docs.dim;
+            hipLaunchKernelGGL(k_seed_scores<AP_BF16>, gs, dim3(256), 0, st, ix->docs.dense, ix->docs.dim, n, (const int32_t *)nullptr, row0, nrows,
+                               (int64_t)0, cs, scratch);
+            hipLaunchKernelGGL(k_select_rows, dim3((unsigned)nrows), dim3(256), 0, st, scratch, cs, (int32_t)m, (const int32_t *)nullptr, row0, 1,
+                               (int64_t)0, (int32_t *)nullptr, tmp_sc);
+            hipLaunchKernelGGL(k_take_tau, dim3((unsigned)((nrows + 255) / 256)), dim3(256), 0, st, tmp_sc, nrows, (int32_t)m,
+                               (uint32_t)g_ap_debug.seed_tau_ulps, tau + row0);
+            e = hipGetLastError();
+        }
+        if (e == hipSuccess) rc = ap_fill_u32(cnt, (size_t)n, 0u, st);
+        if (rc == AP_OK) rc = ap_fill_u32(ovf, 1, 0u, st);
+    }
+    if (rc == AP_OK && e == hipSuccess) {
+        ap_progress("seed lists: thresholds of %lld rows (rank %lld of %lld sampled columns), buffers of %lld", (long long)n, (long long)m,
+                    (long long)cs, (long long)cap);
+        const dim3 tb(AP_BIG_WM * AP_BIG_WN * 64);
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN, true, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, AP_BIG_LDS_BYTES);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN, false, false>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, AP_BIG_LDS_BYTES);
+        // tiles multiplied: those on and above the diagonal, and the ragged last row and column of tiles
+        ix->seed_flops += (unsigned long long)(T * (T + 1) / 2 + (n % AP_BIG != 0 ? 2 * T + 1 : 0)) * 2ull * AP_BIG * AP_BIG * (unsigned long long)ix->docs.dim;
+        // the square of full tiles, a slab of 32 row tiles a launch: each XCD keeps four row tiles and walks the column
+        // tiles from the slab's own first column on
+        for (int64_t s0 = 0; s0 < T && e == hipSuccess; s0 += 32) {
+            const int64_t nrt = std::min<int64_t>(32, T - s0), nct = T - s0;
+            hipLaunchKernelGGL((k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN, true, true>), dim3(ap_seed_grid(nrt, nct)), tb, AP_BIG_LDS_BYTES, st,
+                               ix->docs.dense, ix->docs.dim, n, (const int32_t *)nullptr, (int64_t)0, n, tau, buf, (int32_t)cap, cnt, s0, nrt, s0);
+            e = hipGetLastError();
+            if ((s0 / 32) % 64 == 63) {
+                if (e == hipSuccess) e = hipStreamSynchronize(st);
+                ap_progress("seed lists: %lld of %lld row tiles", (long long)(s0 + nrt), (long long)T);
+            }
+        }
+        if (e == hipSuccess && n % AP_BIG != 0) {
+            // the ragged last column tile for the full row tiles, and the ragged last rows against every column: one-sided
+            hipLaunchKernelGGL((k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN, false, false>), dim3(ap_seed_grid(T, 1)), tb, AP_BIG_LDS_BYTES, st,
+                               ix->docs.dense, ix->docs.dim, n, (const int32_t *)nullptr, (int64_t)0, n, tau, buf, (int32_t)cap, cnt, (int64_t)0, T, T);
+            hipLaunchKernelGGL((k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN, false, false>), dim3(ap_seed_grid(1, T + 1)), tb, AP_BIG_LDS_BYTES, st,
+                               ix->docs.dense, ix->docs.dim, n, (const int32_t *)nullptr, (int64_t)0, n, tau, buf, (int32_t)cap, cnt, T, (int64_t)1, (int64_t)0);
+            e = hipGetLastError();
+        }
+        int32_t n_ovf = 0;
+        if (e == hipSuccess) {
+            hipLaunchKernelGGL(k_select_buf, dim3((unsigned)n), dim3(256), 0, st, buf, (int32_t)cap, cnt, K, (int32_t)std::min<int64_t>(K, n - 1),
+                               (int64_t)0, out_ids, out_sc, ovf, ovf + 1);
+            e = hipGetLastError();
+        }
+        if (e == hipSuccess) e = hipMemcpyAsync(&n_ovf, ovf, sizeof(int32_t), hipMemcpyDeviceToHost, st);
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+        if (e == hipSuccess && n_ovf > 0) {   // rows left short or overflowing: the exact path
+            ap_progress("seed lists: %d rows redone by the exact path", (int)n_ovf);
+            (void)hipFree(buf); buf = nullptr;
+            int64_t ex_rows = std::max<int64_t>(AP_TILE, (((int64_t)1 << 28) / n) / AP_TILE * AP_TILE);
+            ex_rows = std::min<int64_t>(ex_rows, ((int64_t)n_ovf + AP_TILE - 1) / AP_TILE * AP_TILE);
+            rc = ap_dev_alloc(&ex_scratch, (size_t)ex_rows * (size_t)n);
+            if (rc == AP_OK) rc = ap_dev_alloc(&re_ids, (size_t)n_ovf * (size_t)K);
+            if (rc == AP_OK) rc = ap_dev_alloc(&re_sc, (size_t)n_ovf * (size_t)K);
+            if (rc == AP_OK) {
+                e = seed_exact_rows(ix, ovf + 1, 0, n_ovf, K, ex_scratch, ex_rows, re_ids, re_sc, st);
+                if (e == hipSuccess) {
+                    const int64_t tot = (int64_t)n_ovf * K;
+                    hipLaunchKernelGGL(k_scatter_rows, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, ovf + 1, (int64_t)n_ovf, K, re_ids, re_sc,
+                                       out_ids, out_sc);
+                    e = hipGetLastError();
+                }
+                if (e == hipSuccess) e = hipStreamSynchronize(st);
+            }
+        }
+    }
+    void *ptrs[] = {scratch, tau, tmp_sc, buf, cnt, ovf, ex_scratch, re_ids, re_sc};
+    for (void *q : ptrs) if (q) (void)hipFree(q);
+    if (rc != AP_OK) return rc;
+    if (e != hipSuccess) { ap_set_error("seed k-NN failed: %s", hipGetErrorString(e)); return AP_EHIP; }
+    *done = true;
+    return AP_OK;
 }
 
 // S2.  Small corpora: every score row is materialised and the K best are
@@ -333,6 +490,11 @@ int ap_seed_knn_impl(const ap_index *ix, const int32_t *node_ids, int64_t nn, in
         if (e != hipSuccess) { ap_set_error("seed k-NN failed: %s", hipGetErrorString(e)); return AP_EHIP; }
         return AP_OK;
     }
+    if (!node_ids && !g_ap_debug.seed_one_sided) {   // the whole corpus: bf16 rows take the symmetric sweep where it applies
+        bool done = false;
+        rc = ap_seed_knn_symmetric(ix, K, out_ids, out_sc, st, &done);
+        if (rc != AP_OK || done) return rc;
+    }
     const int64_t RS = std::min<int64_t>(8192, (nn + AP_TILE - 1) / AP_TILE * AP_TILE);
     // expected candidates per row = K * n / cs (tau is the K-th best of cs sampled columns)
     int64_t cap = 1024;
@@ -351,6 +513,12 @@ int ap_seed_knn_impl(const ap_index *ix, const int32_t *node_ids, int64_t nn, in
         const int64_t nrows = std::min(RS, nn - row0);
         const int64_t ytiles = (nrows + AP_TILE - 1) / AP_TILE;
         dim3 gs(ap_seed_grid(ytiles, cs / AP_TILE)), gf(ap_seed_grid(ytiles, (n + AP_TILE - 1) / AP_TILE));
+        {   // FLOPs of the sample product and of the sweep (tiles of 128 for f32 rows, of 256 for bf16 rows)
+            const unsigned long long d2 = 2ull * (unsigned long long)ix->docs.dim;
+            ix->seed_flops += (unsigned long long)(ytiles * (cs / AP_TILE)) * AP_TILE * AP_TILE * d2;
+            if (ix->dtype == AP_F32) ix->seed_flops += (unsigned long long)(ytiles * ((n + AP_TILE - 1) / AP_TILE)) * AP_TILE * AP_TILE * d2;
+            else ix->seed_flops += (unsigned long long)(((nrows + AP_BIG - 1) / AP_BIG) * ((n + AP_BIG - 1) / AP_BIG)) * AP_BIG * AP_BIG * d2;
+        }
         if (ix->dtype == AP_F32)
             hipLaunchKernelGGL(k_seed_scores<AP_F32>, gs, dim3(256), 0, st, ix->docs.dense, ix->docs.dim, n, node_ids, row0, nrows, (int64_t)0, cs, scratch);
         else
@@ -375,16 +543,16 @@ int ap_seed_knn_impl(const ap_index *ix, const int32_t *node_ids, int64_t nn, in
                 const dim3 gb(ap_seed_grid(nrt, nct));
                 const dim3 tb(AP_BIG_WM * AP_BIG_WN * 64);
                 if (lean) {
-                    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN, true>),
+                    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN, true, false>),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, AP_BIG_LDS_BYTES);
                     if (e == hipSuccess)
-                        hipLaunchKernelGGL((k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN, true>), gb, tb, AP_BIG_LDS_BYTES, st, ix->docs.dense, ix->docs.dim, n,
+                        hipLaunchKernelGGL((k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN, true, false>), gb, tb, AP_BIG_LDS_BYTES, st, ix->docs.dense, ix->docs.dim, n,
                                            node_ids, row0, nrows, tau, buf, (int32_t)cap, cnt, rt0, nrt, ct0);
                 } else {
-                    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN, false>),
+                    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN, false, false>),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, AP_BIG_LDS_BYTES);
                     if (e == hipSuccess)
-                        hipLaunchKernelGGL((k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN, false>), gb, tb, AP_BIG_LDS_BYTES, st, ix->docs.dense, ix->docs.dim, n,
+                        hipLaunchKernelGGL((k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN, false, false>), gb, tb, AP_BIG_LDS_BYTES, st, ix->docs.dense, ix->docs.dim, n,
                                            node_ids, row0, nrows, tau, buf, (int32_t)cap, cnt, rt0, nrt, ct0);
                 }
                 if (e == hipSuccess) e = hipGetLastError();

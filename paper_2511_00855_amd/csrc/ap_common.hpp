@@ -63,6 +63,7 @@ struct ap_index {
     float *tx_w = nullptr;     // owned: BM25 weight per lexical entry
     int32_t *df = nullptr;     // owned: document frequency per term
     unsigned long long *counters = nullptr;   // owned: [0] hybrid similarities evaluated by refinement rounds on this index
+    mutable unsigned long long seed_flops = 0;   // FLOPs (2 per multiply-add, padded tiles included) of the seed stage's dense products so far
     float *stats = nullptr;    // owned: [0] avgdl
     float *self_sim = nullptr; // owned: fused self-similarity under build_w
     float *dense_norm = nullptr; // owned: |d_dense| per document (upper bound of the dense part in the search)
@@ -120,6 +121,7 @@ struct ApDebug {
     int64_t seed_sample_cols = 0;        // columns sampled for the seed threshold (forces the thresholded sweep on small corpora)
     int64_t seed_buffer_cap = 0;         // capacity of a row's candidate buffer in that sweep (forces the overflow fallback)
     int64_t seed_tau_ulps = 0;           // raises every row's threshold by this many ulps (forces the short-row fallback)
+    int64_t seed_one_sided = 0;          // 1: whole-corpus seed lists of bf16 rows by the one-sided sweep, not the symmetric one
     int64_t max_launch_threads = 0;      // a multiple of 1024: launches that grow with the corpus are cut into slices of this many threads
     int64_t search_visited_global = 0;   // 1: the searches' visited sets stay in global memory even where they would fit LDS
     int64_t search_query_lists = 0;      // 1: the searches look the query's terms up in its lists (the path of queries too long for the LDS tables)

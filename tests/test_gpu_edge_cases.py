@@ -294,6 +294,37 @@ def test_threshold_sweep_with_more_candidates_than_a_wave_stages(debug_knobs):
         ix.close()
 
 
+def test_symmetric_seed_sweep_against_one_sided_and_exact(debug_knobs):
+    """Whole-corpus seed lists of bf16 rows come from a sweep over the tiles on and above the diagonal of D D^T, every
+    score offered to both of its documents, with thresholds that are the m-th best (m < K) of a column sample.  Same
+    lists, bit for bit, as the one-sided sweep and as the exact score rows; also when rows overflow their buffers or fall
+    short of K candidates and are redone.  The symmetric sweep must have executed about half the one-sided FLOPs."""
+    _say("edge case: symmetric seed sweep")
+    K = 200
+    w = make_workload("tiny", seed=95, n=3000, nq=2, dim=64, bf16=True, sp=("fixed", 4), tx=("fixed", 4))
+    docs = B.DeviceVecs(w.docs, bf16=True)
+
+    def lists(**knobs):
+        for k, v in knobs.items():
+            debug_knobs(k, v)
+        ix = B.Index.ingest(docs, B.build_params(8, knn_k=K, nd_rounds=1, nd_sample=4, n_entry=4))
+        out = [t.cpu().numpy() for t in ix.stage_seed_knn(K)]
+        flops = ix.build_counters()["seed_flops"]
+        ix.close()
+        for k in knobs:
+            debug_knobs(k, 0)
+        return out, flops
+
+    exact, f_exact = lists()
+    sym, f_sym = lists(seed_sample_cols=256)
+    one, f_one = lists(seed_sample_cols=256, seed_one_sided=1)
+    ovf, _ = lists(seed_sample_cols=256, seed_buffer_cap=512)        # most rows overflow and are redone
+    short, _ = lists(seed_sample_cols=256, seed_tau_ulps=1 << 22)    # thresholds far too high: rows fall short
+    for name, got in (("symmetric", sym), ("one-sided", one), ("overflowing", ovf), ("short", short)):
+        assert np.array_equal(got[0], exact[0]) and np.array_equal(got[1], exact[1]), name
+    assert f_sym < 0.75 * f_one, (f_sym, f_one, f_exact)
+
+
 def test_random_search_settings_replayed():
     """Forty seeded draws of (k, beam, parents per iteration, iteration cap) across the three workgroup sizes of the
     search (256, 512 and 1024 threads), on two graphs of different degree, each replayed by the oracle on the GPU's own
