@@ -348,7 +348,7 @@ int ap_build_counters(const ap_index *index, uint64_t out2[2], void *stream);
  *   "seed_sample_cols"        columns sampled for the seed threshold (forces the thresholded sweep on small corpora)
  *   "seed_buffer_cap"         capacity of a row's candidate buffer in that sweep (forces the overflow fallback)
  *   "seed_tau_ulps"           raises every row's threshold by this many ulps (forces the short-row fallback)
- *   "seed_one_sided"          1: whole-corpus seed lists of bf16 rows by the one-sided sweep instead of the symmetric one
+ *   "seed_one_sided"          1: whole-corpus seed lists by the one-sided sweep instead of the symmetric one
  *   "max_launch_threads"      a multiple of 1024: launches that grow with the corpus run in slices of this many threads
  *   "search_workspace_bytes"  cap of the searches' visited-set workspace (forces searches in several slabs of queries)
  *   "search_visited_global"   1: visited sets stay in the global workspace even where the search would keep them in LDS

@@ -111,21 +111,28 @@ __device__ __forceinline__ void ap_seed_flush(uint64_t *stage, int32_t wcap, int
 // score that reaches its row's threshold tau (a lower bound of the row's K-th
 // best, found on a sample of the columns) is appended to the row's candidate
 // buffer as a ranking key.  cnt[r] counts the appends (also those beyond cap).
-template <int DT>
+// The launch covers column tiles from ct0 on.  SYM (rows = a slab of the whole corpus in order, every tile full and
+// inside the corpus): tau, buf and cnt point at the slab's first row inside arrays that cover the whole corpus; tiles
+// below the diagonal return at once, and a score of a tile above it is offered to its column's document as well (see
+// k_seed_thresh_big).
+template <int DT, bool SYM>
 __global__ __launch_bounds__(256) void k_seed_thresh(const void *dense, int32_t dim, int64_t n, const int32_t *node_ids,
                                                      int64_t row0, int64_t nrows, const float *__restrict__ tau,
                                                      unsigned long long *__restrict__ buf, int32_t cap,
-                                                     int32_t *__restrict__ cnt) {
+                                                     int32_t *__restrict__ cnt, int64_t ct0) {
     __shared__ __attribute__((aligned(16))) unsigned char lds[ApTileLds<DT>::BYTES];
     __shared__ int32_t a_rows[AP_TILE], b_rows[AP_TILE];
-    __shared__ float s_tau[AP_TILE];
-    __shared__ int32_t s_cnt[AP_TILE], s_base[AP_TILE];
+    __shared__ float s_tau[AP_TILE], s_tauc[SYM ? AP_TILE : 1];
+    __shared__ int32_t s_cnt[(SYM ? 2 : 1) * AP_TILE], s_base[(SYM ? 2 : 1) * AP_TILE];
     int64_t rt, ct;
     if (!ap_seed_tile((nrows + AP_TILE - 1) / AP_TILE, rt, ct)) return;
-    const int64_t i0 = rt * AP_TILE, j0 = ct * AP_TILE;
+    const int64_t i0 = rt * AP_TILE, j0 = (ct0 + ct) * AP_TILE;
+    if (SYM && j0 < row0 + i0) return;   // below the diagonal: its mirror image does the work
+    const bool mirror = SYM && j0 > row0 + i0;   // uniform
     if (threadIdx.x < AP_TILE) {
         const int64_t r = i0 + threadIdx.x;
         s_cnt[threadIdx.x] = 0;
+        if (SYM) { s_cnt[AP_TILE + threadIdx.x] = 0; s_tauc[threadIdx.x] = tau[j0 - row0 + threadIdx.x]; }
         a_rows[threadIdx.x] = r < nrows ? (node_ids ? node_ids[row0 + r] : (int32_t)(row0 + r)) : -1;
         s_tau[threadIdx.x] = r < nrows ? tau[r] : INFINITY;
         const int64_t j = j0 + threadIdx.x;
@@ -137,15 +144,19 @@ __global__ __launch_bounds__(256) void k_seed_thresh(const void *dense, int32_t 
     constexpr int W_CAP = ApTileLds<DT>::BYTES / 4 / 8;
     uint64_t *stage = reinterpret_cast<uint64_t *>(lds) + ap_wave_id() * W_CAP;
     auto drop = [&](int, int i, int j) { return !(i0 + i < nrows && j0 + j < n && a_rows[i] != (int32_t)(j0 + j)); };
-    auto direct = [&](int, int i, int j, float v) {
-        if (!drop(0, i, j)) {
-            const int32_t pos = atomicAdd(&cnt[i0 + i], 1);
-            if (pos < cap) buf[(i0 + i) * (int64_t)cap + pos] = ap_make_key(v, (int32_t)(j0 + j), 1u);
+    auto direct = [&](int side, int i, int j, float v) {
+        if (!drop(side, i, j)) {
+            const int64_t row = side ? j0 - row0 + j : i0 + i;
+            const int32_t pos = atomicAdd(&cnt[row], 1);
+            if (pos < cap) buf[row * (int64_t)cap + pos] = ap_make_key(v, side ? (int32_t)(row0 + i0 + i) : (int32_t)(j0 + j), 1u);
         }
     };
     int32_t nw = 0;
-    ap_tile_foreach(acc, [&](int i, int j, float v) { ap_seed_stage(v >= s_tau[i], 0, i, j, v, stage, W_CAP, nw, direct); });
-    ap_seed_flush(stage, W_CAP, nw, AP_TILE, false, s_cnt, s_base, cnt, buf, cap, i0, (int32_t)j0, (int64_t)0, 0, drop);
+    ap_tile_foreach(acc, [&](int i, int j, float v) {
+        ap_seed_stage(v >= s_tau[i], 0, i, j, v, stage, W_CAP, nw, direct);
+        if (SYM) ap_seed_stage(mirror && v >= s_tauc[j], 1, i, j, v, stage, W_CAP, nw, direct);
+    });
+    ap_seed_flush(stage, W_CAP, nw, AP_TILE, SYM, s_cnt, s_base, cnt, buf, cap, i0, (int32_t)j0, j0 - row0, (int32_t)(row0 + i0), drop);
 }
 
 // The thresholded sweep for bf16 rows on 256x256 tiles (the product above): the same appends as k_seed_thresh.
@@ -348,8 +359,10 @@ __global__ void k_scatter_rows(const int32_t *__restrict__ list, int64_t nlist, 
 // *done = false (and AP_OK): not applicable here (shape, memory); the caller takes the one-sided sweep.
 static int ap_seed_knn_symmetric(const ap_index *ix, int32_t K, int32_t *out_ids, float *out_sc, hipStream_t st, bool *done) {
     *done = false;
-    const int64_t n = ix->docs.n, T = n / AP_BIG;
-    if (ix->dtype != AP_BF16 || ix->docs.dim % AP_BK16 != 0 || T < 2 || n > ((int64_t)1 << 30)) return AP_OK;
+    const bool big = ix->dtype == AP_BF16;             // bf16 rows: 256x256 tiles; f32 rows: 128x128 tiles
+    const int64_t E = big ? AP_BIG : AP_TILE;
+    const int64_t n = ix->docs.n, T = n / E;
+    if ((big && ix->docs.dim % AP_BK16 != 0) || T < 2 || n > ((int64_t)1 << 30)) return AP_OK;
     size_t free_b = 0, total_b = 0;
     if (hipMemGetInfo(&free_b, &total_b) != hipSuccess) return AP_OK;
     int64_t cap = 4096;
@@ -385,8 +398,12 @@ static int ap_seed_knn_symmetric(const ap_index *ix, int32_t K, int32_t *out_ids
             const int64_t nrows = std::min(RS, n - row0);
             dim3 gs(ap_seed_grid((nrows + AP_TILE - 1) / AP_TILE, cs / AP_TILE));
             ix->seed_flops += (unsigned long long)(((nrows + AP_TILE - 1) / AP_TILE) * (cs / AP_TILE)) * 2ull * AP_TILE * AP_TILE * (unsigned long long)ix->docs.dim;
-            hipLaunchKernelGGL(k_seed_scores<AP_BF16>, gs, dim3(256), 0, st, ix->docs.dense, ix->docs.dim, n, (const int32_t *)nullptr, row0, nrows,
-                               (int64_t)0, cs, scratch);
+            if (big)
+                hipLaunchKernelGGL(k_seed_scores<AP_BF16>, gs, dim3(256), 0, st, ix->docs.dense, ix->docs.dim, n, (const int32_t *)nullptr, row0, nrows,
+                                   (int64_t)0, cs, scratch);
+            else
+                hipLaunchKernelGGL(k_seed_scores<AP_F32>, gs, dim3(256), 0, st, ix->docs.dense, ix->docs.dim, n, (const int32_t *)nullptr, row0, nrows,
+                                   (int64_t)0, cs, scratch);
             hipLaunchKernelGGL(k_select_rows, dim3((unsigned)nrows), dim3(256), 0, st, scratch, cs, (int32_t)m, (const int32_t *)nullptr, row0, 1,
                                (int64_t)0, (int32_t *)nullptr, tmp_sc);
             hipLaunchKernelGGL(k_take_tau, dim3((unsigned)((nrows + 255) / 256)), dim3(256), 0, st, tmp_sc, nrows, (int32_t)m,
@@ -399,33 +416,51 @@ static int ap_seed_knn_symmetric(const ap_index *ix, int32_t K, int32_t *out_ids
     if (rc == AP_OK && e == hipSuccess) {
         ap_progress("seed lists: thresholds of %lld rows (rank %lld of %lld sampled columns), buffers of %lld", (long long)n, (long long)m,
                     (long long)cs, (long long)cap);
-        const dim3 tb(AP_BIG_WM * AP_BIG_WN * 64);
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN, true, true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, AP_BIG_LDS_BYTES);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN, false, false>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, AP_BIG_LDS_BYTES);
         // tiles multiplied: those on and above the diagonal, and the ragged last row and column of tiles
-        ix->seed_flops += (unsigned long long)(T * (T + 1) / 2 + (n % AP_BIG != 0 ? 2 * T + 1 : 0)) * 2ull * AP_BIG * AP_BIG * (unsigned long long)ix->docs.dim;
-        // the square of full tiles, a slab of 32 row tiles a launch: each XCD keeps four row tiles and walks the column
-        // tiles from the slab's own first column on
-        for (int64_t s0 = 0; s0 < T && e == hipSuccess; s0 += 32) {
-            const int64_t nrt = std::min<int64_t>(32, T - s0), nct = T - s0;
-            hipLaunchKernelGGL((k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN, true, true>), dim3(ap_seed_grid(nrt, nct)), tb, AP_BIG_LDS_BYTES, st,
-                               ix->docs.dense, ix->docs.dim, n, (const int32_t *)nullptr, (int64_t)0, n, tau, buf, (int32_t)cap, cnt, s0, nrt, s0);
-            e = hipGetLastError();
-            if ((s0 / 32) % 64 == 63) {
-                if (e == hipSuccess) e = hipStreamSynchronize(st);
-                ap_progress("seed lists: %lld of %lld row tiles", (long long)(s0 + nrt), (long long)T);
+        ix->seed_flops += (unsigned long long)(T * (T + 1) / 2 + (n % E != 0 ? 2 * T + 1 : 0)) * 2ull * (unsigned long long)(E * E) * (unsigned long long)ix->docs.dim;
+        if (big) {
+            const dim3 tb(AP_BIG_WM * AP_BIG_WN * 64);
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN, true, true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, AP_BIG_LDS_BYTES);
+            if (e == hipSuccess)
+                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN, false, false>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, AP_BIG_LDS_BYTES);
+            // the square of full tiles, a slab of 32 row tiles a launch: each XCD keeps four row tiles and walks the column
+            // tiles from the slab's own first column on
+            for (int64_t s0 = 0; s0 < T && e == hipSuccess; s0 += 32) {
+                const int64_t nrt = std::min<int64_t>(32, T - s0), nct = T - s0;
+                hipLaunchKernelGGL((k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN, true, true>), dim3(ap_seed_grid(nrt, nct)), tb, AP_BIG_LDS_BYTES, st,
+                                   ix->docs.dense, ix->docs.dim, n, (const int32_t *)nullptr, (int64_t)0, n, tau, buf, (int32_t)cap, cnt, s0, nrt, s0);
+                e = hipGetLastError();
+                if ((s0 / 32) % 64 == 63) {
+                    if (e == hipSuccess) e = hipStreamSynchronize(st);
+                    ap_progress("seed lists: %lld of %lld row tiles", (long long)(s0 + nrt), (long long)T);
+                }
             }
-        }
-        if (e == hipSuccess && n % AP_BIG != 0) {
-            // the ragged last column tile for the full row tiles, and the ragged last rows against every column: one-sided
-            hipLaunchKernelGGL((k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN, false, false>), dim3(ap_seed_grid(T, 1)), tb, AP_BIG_LDS_BYTES, st,
-                               ix->docs.dense, ix->docs.dim, n, (const int32_t *)nullptr, (int64_t)0, n, tau, buf, (int32_t)cap, cnt, (int64_t)0, T, T);
-            hipLaunchKernelGGL((k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN, false, false>), dim3(ap_seed_grid(1, T + 1)), tb, AP_BIG_LDS_BYTES, st,
-                               ix->docs.dense, ix->docs.dim, n, (const int32_t *)nullptr, (int64_t)0, n, tau, buf, (int32_t)cap, cnt, T, (int64_t)1, (int64_t)0);
-            e = hipGetLastError();
+            if (e == hipSuccess && n % AP_BIG != 0) {
+                // the ragged last column tile for the full row tiles, and the ragged last rows against every column: one-sided
+                hipLaunchKernelGGL((k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN, false, false>), dim3(ap_seed_grid(T, 1)), tb, AP_BIG_LDS_BYTES, st,
+                                   ix->docs.dense, ix->docs.dim, n, (const int32_t *)nullptr, (int64_t)0, n, tau, buf, (int32_t)cap, cnt, (int64_t)0, T, T);
+                hipLaunchKernelGGL((k_seed_thresh_big<AP_BIG_WM, AP_BIG_WN, false, false>), dim3(ap_seed_grid(1, T + 1)), tb, AP_BIG_LDS_BYTES, st,
+                                   ix->docs.dense, ix->docs.dim, n, (const int32_t *)nullptr, (int64_t)0, n, tau, buf, (int32_t)cap, cnt, T, (int64_t)1, (int64_t)0);
+                e = hipGetLastError();
+            }
+        } else {
+            // f32 rows: the same on 128x128 tiles, a slab of 64 row tiles (eight per XCD) a launch
+            for (int64_t s0 = 0; s0 < T && e == hipSuccess; s0 += 64) {
+                const int64_t nrt = std::min<int64_t>(64, T - s0), nct = T - s0, r0 = s0 * AP_TILE;
+                hipLaunchKernelGGL((k_seed_thresh<AP_F32, true>), dim3(ap_seed_grid(nrt, nct)), dim3(256), 0, st, ix->docs.dense, ix->docs.dim, n,
+                                   (const int32_t *)nullptr, r0, nrt * AP_TILE, tau + r0, buf + r0 * cap, (int32_t)cap, cnt + r0, s0);
+                e = hipGetLastError();
+            }
+            if (e == hipSuccess && n % AP_TILE != 0) {
+                const int64_t r0 = T * AP_TILE;
+                hipLaunchKernelGGL((k_seed_thresh<AP_F32, false>), dim3(ap_seed_grid(T, 1)), dim3(256), 0, st, ix->docs.dense, ix->docs.dim, n,
+                                   (const int32_t *)nullptr, (int64_t)0, r0, tau, buf, (int32_t)cap, cnt, T);
+                hipLaunchKernelGGL((k_seed_thresh<AP_F32, false>), dim3(ap_seed_grid(1, T + 1)), dim3(256), 0, st, ix->docs.dense, ix->docs.dim, n,
+                                   (const int32_t *)nullptr, r0, n - r0, tau + r0, buf + r0 * cap, (int32_t)cap, cnt + r0, (int64_t)0);
+                e = hipGetLastError();
+            }
         }
         int32_t n_ovf = 0;
         if (e == hipSuccess) {
@@ -490,7 +525,7 @@ int ap_seed_knn_impl(const ap_index *ix, const int32_t *node_ids, int64_t nn, in
         if (e != hipSuccess) { ap_set_error("seed k-NN failed: %s", hipGetErrorString(e)); return AP_EHIP; }
         return AP_OK;
     }
-    if (!node_ids && !g_ap_debug.seed_one_sided) {   // the whole corpus: bf16 rows take the symmetric sweep where it applies
+    if (!node_ids && !g_ap_debug.seed_one_sided) {   // the whole corpus: the symmetric sweep where it applies
         bool done = false;
         rc = ap_seed_knn_symmetric(ix, K, out_ids, out_sc, st, &done);
         if (rc != AP_OK || done) return rc;
@@ -531,7 +566,7 @@ int ap_seed_knn_impl(const ap_index *ix, const int32_t *node_ids, int64_t nn, in
         if (rc == AP_OK) rc = ap_fill_u32(ovf, 1, 0u, st);
         if (rc != AP_OK) break;
         if (ix->dtype == AP_F32)
-            hipLaunchKernelGGL(k_seed_thresh<AP_F32>, gf, dim3(256), 0, st, ix->docs.dense, ix->docs.dim, n, node_ids, row0, nrows, tau, buf, (int32_t)cap, cnt);
+            hipLaunchKernelGGL((k_seed_thresh<AP_F32, false>), gf, dim3(256), 0, st, ix->docs.dense, ix->docs.dim, n, node_ids, row0, nrows, tau, buf, (int32_t)cap, cnt, (int64_t)0);
         else {
             // the inner tiles (runs of consecutive documents, all inside the corpus) take the lean instantiation, the ragged
             // last row tile and last column tile the general one

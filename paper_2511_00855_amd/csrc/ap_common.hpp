@@ -121,7 +121,7 @@ struct ApDebug {
     int64_t seed_sample_cols = 0;        // columns sampled for the seed threshold (forces the thresholded sweep on small corpora)
     int64_t seed_buffer_cap = 0;         // capacity of a row's candidate buffer in that sweep (forces the overflow fallback)
     int64_t seed_tau_ulps = 0;           // raises every row's threshold by this many ulps (forces the short-row fallback)
-    int64_t seed_one_sided = 0;          // 1: whole-corpus seed lists of bf16 rows by the one-sided sweep, not the symmetric one
+    int64_t seed_one_sided = 0;          // 1: whole-corpus seed lists by the one-sided sweep, not the symmetric one
     int64_t max_launch_threads = 0;      // a multiple of 1024: launches that grow with the corpus are cut into slices of this many threads
     int64_t search_visited_global = 0;   // 1: the searches' visited sets stay in global memory even where they would fit LDS
     int64_t search_query_lists = 0;      // 1: the searches look the query's terms up in its lists (the path of queries too long for the LDS tables)

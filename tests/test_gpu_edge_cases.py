@@ -294,15 +294,17 @@ def test_threshold_sweep_with_more_candidates_than_a_wave_stages(debug_knobs):
         ix.close()
 
 
-def test_symmetric_seed_sweep_against_one_sided_and_exact(debug_knobs):
-    """Whole-corpus seed lists of bf16 rows come from a sweep over the tiles on and above the diagonal of D D^T, every
-    score offered to both of its documents, with thresholds that are the m-th best (m < K) of a column sample.  Same
-    lists, bit for bit, as the one-sided sweep and as the exact score rows; also when rows overflow their buffers or fall
-    short of K candidates and are redone.  The symmetric sweep must have executed about half the one-sided FLOPs."""
-    _say("edge case: symmetric seed sweep")
+@pytest.mark.parametrize("bf16", [True, False])
+def test_symmetric_seed_sweep_against_one_sided_and_exact(bf16, debug_knobs):
+    """Whole-corpus seed lists come from a sweep over the tiles on and above the diagonal of D D^T (256x256 tiles for
+    bf16 rows, 128x128 for f32 rows), every score offered to both of its documents, with thresholds that are the m-th
+    best (m < K) of a column sample.  Same lists, bit for bit, as the one-sided sweep and as the exact score rows; also
+    when rows overflow their buffers or fall short of K candidates and are redone.  The symmetric sweep must have
+    executed well under the one-sided FLOPs."""
+    _say(f"edge case: symmetric seed sweep, bf16={bf16}")
     K = 200
-    w = make_workload("tiny", seed=95, n=3000, nq=2, dim=64, bf16=True, sp=("fixed", 4), tx=("fixed", 4))
-    docs = B.DeviceVecs(w.docs, bf16=True)
+    w = make_workload("tiny", seed=95, n=3000, nq=2, dim=64, bf16=bf16, sp=("fixed", 4), tx=("fixed", 4))
+    docs = B.DeviceVecs(w.docs, bf16=bf16)
 
     def lists(**knobs):
         for k, v in knobs.items():
