@@ -371,7 +371,7 @@ static int ap_seed_knn_symmetric(const ap_index *ix, int32_t K, int32_t *out_ids
     const double mean = 0.45 * (double)cap;
     int64_t m = std::min<int64_t>(K, 24);
     int64_t cs = (int64_t)((double)m * (double)n / mean) + 1;
-    const int64_t cs_min = g_ap_debug.seed_sample_cols > 0 ? std::max<int64_t>(K + 1, g_ap_debug.seed_sample_cols) : 16384;
+    const int64_t cs_min = g_ap_debug.seed_sample_cols > 0 ? std::max<int64_t>(K + 1, g_ap_debug.seed_sample_cols) : 4096;
     if (cs < cs_min || g_ap_debug.seed_sample_cols > 0) {   // a fixed sample: the rank that gives the same expectation
         cs = cs_min;
         m = std::min<int64_t>(K, std::max<int64_t>(m, (int64_t)(mean * (double)cs / (double)n) + 1));
